@@ -1,0 +1,149 @@
+/*
+ * darknight.h -- C ABI of the MI355X (gfx950) masked-layer library.
+ *
+ * The library implements the data-parallel hot path of DarKnight's matrix
+ * masking: encode K private inputs plus a noise input into K+2 obfuscated
+ * inputs, run the layer's bilinear operation (dense product or NCHW
+ * convolution) and its weight gradient on the obfuscated inputs only, decode
+ * with the inverse of the encoding matrix and check the redundant
+ * combination for integrity.
+ *
+ * Conventions
+ *   K  private inputs per virtual batch ("group"); S = K+2 encodings per
+ *      group (K+1 mask the inputs, one more is the integrity redundancy);
+ *      G groups; R = G*S encoded rows.  1 <= K <= DK_MAX_K.
+ *   All tensors are fp32, row-major and sample-major: a sample (or encoding)
+ *   is one contiguous row of n (input) or m (output) floats; convolution
+ *   rows are CHW images.  Group g owns input rows gK..gK+K-1, noise row g and
+ *   encoded rows gS..gS+S-1.
+ *   A[g] is S x S, A[g][i][j] = weight of source i in encoding j; sources are
+ *   the K inputs, then the noise vector, then a phantom all-zero source, so
+ *   the last row of A[g] is never read by dk_encode.
+ *   "device" pointers are HIP device memory owned by the caller; the library
+ *   never allocates, frees or keeps them.  "host" pointers are ordinary host
+ *   memory.  Kernels are enqueued on `stream` (a hipStream_t passed as
+ *   void*, NULL = default stream) and the call returns without waiting;
+ *   results, verdicts included, are in device memory once the stream has
+ *   drained.
+ *   The return value is the only error channel.  Argument errors are found
+ *   on the host before anything is launched; DK_ERR_HIP reports a failed
+ *   launch.  Nothing is written on error.
+ */
+#ifndef DARKNIGHT_H
+#define DARKNIGHT_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DK_MAX_K 16
+
+typedef enum {
+    DK_OK = 0,
+    DK_ERR_NULL = 1,        /* a required pointer is NULL                      */
+    DK_ERR_SHAPE = 2,       /* a size is non-positive, too large or K invalid  */
+    DK_ERR_UNSUPPORTED = 3, /* layer geometry the kernels do not cover         */
+    DK_ERR_ALIGN = 4,       /* a device pointer is not 4-byte aligned          */
+    DK_ERR_WORKSPACE = 5,   /* workspace missing or smaller than required      */
+    DK_ERR_HIP = 6,         /* the HIP runtime refused a launch                */
+    DK_ERR_SINGULAR = 7     /* dk_coeffs: A[g] is singular or gamma has a zero */
+} dk_status;
+
+/* Layer descriptor.  kind 0: dense y = W x with W[M][N].  kind 1: NCHW
+ * cross-correlation without bias, W[Co][Ci][kh][kw], zero padding, output
+ * Ho = (H + 2 pad - kh)/stride + 1 (same for Wo). */
+typedef struct dk_layer {
+    int kind;
+    int M, N;
+    int Ci, Co, H, W, kh, kw, stride, pad;
+} dk_layer;
+
+enum { DK_LINEAR = 0, DK_CONV2D = 1 };
+enum { DK_OP_FWD = 0, DK_OP_WGRAD = 1, DK_OP_VERIFY = 2 };
+
+const char *dk_status_str(int status);
+int dk_version(void);
+
+/* Flat per-sample input length n and output length m of a layer (0 if the
+ * descriptor is invalid). */
+long long dk_layer_in_len(const dk_layer *L);
+long long dk_layer_out_len(const dk_layer *L);
+
+/* Bytes of device workspace that dk_linear_fwd / dk_conv_fwd (DK_OP_FWD),
+ * dk_wgrad (DK_OP_WGRAD) or dk_verify (DK_OP_VERIFY) need for this layer,
+ * G groups of K inputs.  For DK_OP_VERIFY the layer may be NULL.  Returns 0
+ * for invalid arguments (every valid case needs a non-zero workspace). */
+size_t dk_workspace_bytes(const dk_layer *L, int op, int G, int K);
+
+/* Trusted-side coefficient derivation (host arithmetic, fp64 internally).
+ * From the random draws A[G][S][S] and gamma[G][S] (host) derive, per group:
+ *   Ainv = A^{-1}                 [G][S][S]  (Forward Pass, decoding relation
+ *                                             Y = Ybar A^{-1});
+ *   nvec = last column of Ainv    [G][S]     (the combination of the K+2
+ *                                             results that must vanish,
+ *                                             section Computational Integrity);
+ *   B[j][i] = Ainv[j][i]/gamma[j] [G][S][K]  (so that B^T Gamma A^T = [I|0],
+ *                                             Backward Propagation matrix
+ *                                             relation).
+ * All pointers are host memory; outputs may be NULL to skip them. */
+dk_status dk_coeffs(const float *A, const float *gamma, int G, int K,
+                    float *Ainv, float *nvec, float *B);
+
+/* Encoding (Forward Pass, DarKnight Encoding equation, plus the extra
+ * combination of section Computational Integrity):
+ *   xbar[gS+j][e] = sum_{i<K} A[g][i][j] x[gK+i][e] + A[g][K][j] r[g][e]
+ * x[G*K][n], r[G][n], A[G][S][S] (all device) -> xbar[G*S][n] (device). */
+dk_status dk_encode(const float *x, const float *r, const float *A,
+                    float *xbar, int G, int K, long long n, void *stream);
+
+/* The bilinear operation on encoded rows, dense case (Forward Pass):
+ *   ybar[R][M] = xbar[R][N] . W[M][N]^T.
+ * ws: device workspace of at least dk_workspace_bytes(L, DK_OP_FWD, ..). */
+dk_status dk_linear_fwd(const float *W, const float *xbar, float *ybar,
+                        int M, int N, int R, void *ws, size_t ws_bytes,
+                        void *stream);
+
+/* The bilinear operation on encoded rows, convolution case: R encoded CHW
+ * images xbar[R][Ci][H][W] -> ybar[R][Co][Ho][Wo]. */
+dk_status dk_conv_fwd(const dk_layer *L, const float *W, const float *xbar,
+                      float *ybar, int R, void *ws, size_t ws_bytes,
+                      void *stream);
+
+/* Masked weight gradient (Backward Propagation, gamma-weighted sum of the
+ * per-encoding products Eq_j, summed over all G virtual batches as in the
+ * large-batch aggregation):
+ *   dtilde[gS+j] = gamma[g][j] * sum_{i<K} B[g][j][i] delta[gK+i]
+ *   dW = (accumulate ? dW : 0) + scale * sum_rows <dtilde[row], xbar[row]>
+ * where <.,.> is the outer product (dense) or the convolution weight-gradient
+ * pairing.  xbar is the buffer dk_encode wrote at forward time.
+ * delta[G*K][m], B[G][S][K], gamma[G][S], xbar[G*S][n] (device) -> dW with
+ * the shape of W (device).  scale = 1/K gives the paper's average. */
+dk_status dk_wgrad(const dk_layer *L, const float *delta, const float *B,
+                   const float *gamma, const float *xbar, float *dW, int G,
+                   int K, float scale, int accumulate, void *ws,
+                   size_t ws_bytes, void *stream);
+
+/* Decoding (Forward Pass, DarKnight Decoding): the K wanted columns of
+ * Ybar . A^{-1}; the <W, r> column is not produced.
+ *   y[gK+i][e] = sum_j ybar[gS+j][e] Ainv[g][j][i],  i < K
+ * ybar[G*S][m], Ainv[G][S][S] (device) -> y[G*K][m] (device). */
+dk_status dk_decode(const float *ybar, const float *Ainv, float *y, int G,
+                    int K, long long m, void *stream);
+
+/* Integrity check (section Computational Integrity).  Per group,
+ *   t[e] = sum_j nvec[g][j] ybar[gS+j][e],  s[e] = sum_j |nvec[g][j] ybar[gS+j][e]|
+ *   resid[g] = max_e |t| / max_e s   (0 if the denominator is 0, +inf if any
+ *                                     t or s is not finite)
+ *   verdict[g] = 1 if resid[g] > tol or not finite, else 0.
+ * ybar[G*S][m], nvec[G][S] (device) -> verdict[G] int32, resid[G] (device;
+ * resid may be NULL).  ws: at least dk_workspace_bytes(NULL, DK_OP_VERIFY, G, K). */
+dk_status dk_verify(const float *ybar, const float *nvec, float tol,
+                    int *verdict, float *resid, int G, int K, long long m,
+                    void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DARKNIGHT_H */

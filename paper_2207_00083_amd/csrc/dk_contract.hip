@@ -1,0 +1,650 @@
+// The contractions of the masked layer on fp32 MFMA tiles: the layer's
+// forward on encoded rows (dense product, convolution as implicit GEMM) and
+// the weight gradient as one contraction of the mixed gradients with the
+// stored encodings.
+//
+// One engine serves all four: a workgroup of 64-lane waves owns a BM x BN
+// output tile and walks the contraction axis in steps of BK.  Both operands
+// are staged through LDS "k-major" (As[k][row], Bs[k][col]) so that the
+// v_mfma_f32_32x32x2_f32 operand fetch (lane l supplies row l%32 of k-slice
+// l/32) is one conflict-free ds_read_b32 per operand block.  Global loads for
+// step t+1 are issued before the MFMA loop of step t and land in the other
+// LDS buffer after it (register-staged double buffering, one barrier per
+// step).  What differs per operation is only how an operand tile is fetched
+// from HBM (the loader) and where an output element lives (the epilogue).
+#include "dk_internal.h"
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+template <int BM_, int BN_, int BK_, int WM_, int WN_>
+struct Cfg {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
+    static constexpr int NT = 64 * WM * WN;          // threads per workgroup
+    static constexpr int TM = BM / WM / 32;          // 32x32 blocks per wave, rows
+    static constexpr int TN = BN / WN / 32;          // 32x32 blocks per wave, cols
+    static constexpr int LDA = BM + 4;               // LDS row pitch (floats)
+    static constexpr int LDB = BN + 4;
+    static constexpr int LDS_FLOATS = 2 * BK * (LDA + LDB);
+    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 4 == 0, "tile shape");
+};
+
+// ---------------------------------------------------------------------------
+// Operand loaders.  Each fetches a BK x ROWS operand tile of contraction step
+// kt into registers (load) and later writes it k-major into LDS (store).
+// Elements outside the matrix read as zero.
+// ---------------------------------------------------------------------------
+
+struct MatParams {
+    const float *p;
+    long long ld;   // leading dimension (floats)
+    int rows;       // extent along the tile's row axis
+    int kdim;       // extent along the contraction axis
+};
+
+// Source stored [kdim][ld] with the tile's row axis contiguous.
+template <int ROWS, int BK, int NT, int LD, bool VEC>
+struct LoadKMajor {
+    using Params = MatParams;
+    static constexpr int PER_K = ROWS / 4;
+    static constexpr int N4 = BK * PER_K / NT;
+    static_assert(BK * PER_K % NT == 0, "tile/threads");
+    float4 st[N4];
+    const float *p; long long ld; int rows, kdim, row0, tid;
+
+    __device__ __forceinline__ void init(const Params &a, int row0_, int tid_)
+    { p = a.p; ld = a.ld; rows = a.rows; kdim = a.kdim; row0 = row0_; tid = tid_; }
+
+    __device__ __forceinline__ void load(int kt)
+    {
+#pragma unroll
+        for (int e = 0; e < N4; ++e) {
+            const int idx = tid + e * NT;
+            const int kr = idx / PER_K, c4 = idx % PER_K;
+            const int k = kt * BK + kr, row = row0 + c4 * 4;
+            const float *s = p + (long long)k * ld + row;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k < kdim) {
+                if (VEC && row + 3 < rows) {
+                    v = *reinterpret_cast<const float4 *>(s);
+                } else {
+                    if (row + 0 < rows) v.x = s[0];
+                    if (row + 1 < rows) v.y = s[1];
+                    if (row + 2 < rows) v.z = s[2];
+                    if (row + 3 < rows) v.w = s[3];
+                }
+            }
+            st[e] = v;
+        }
+    }
+
+    __device__ __forceinline__ void store(float *buf) const
+    {
+#pragma unroll
+        for (int e = 0; e < N4; ++e) {
+            const int idx = tid + e * NT;
+            const int kr = idx / PER_K, c4 = idx % PER_K;
+            *reinterpret_cast<float4 *>(buf + kr * LD + c4 * 4) = st[e];
+        }
+    }
+};
+
+// Source stored [rows][ld] with the contraction axis contiguous.
+template <int ROWS, int BK, int NT, int LD, bool VEC>
+struct LoadRowMajorK {
+    using Params = MatParams;
+    static constexpr int PER_ROW = BK / 4;
+    static constexpr int N4 = ROWS * PER_ROW / NT;
+    static_assert(ROWS * PER_ROW % NT == 0, "tile/threads");
+    float4 st[N4];
+    const float *p; long long ld; int rows, kdim, row0, tid;
+
+    __device__ __forceinline__ void init(const Params &a, int row0_, int tid_)
+    { p = a.p; ld = a.ld; rows = a.rows; kdim = a.kdim; row0 = row0_; tid = tid_; }
+
+    __device__ __forceinline__ void load(int kt)
+    {
+#pragma unroll
+        for (int e = 0; e < N4; ++e) {
+            const int idx = tid + e * NT;
+            const int row = idx / PER_ROW, kc = idx % PER_ROW;
+            const int k = kt * BK + kc * 4, r = row0 + row;
+            const float *s = p + (long long)r * ld + k;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (r < rows) {
+                if (VEC && k + 3 < kdim) {
+                    v = *reinterpret_cast<const float4 *>(s);
+                } else {
+                    if (k + 0 < kdim) v.x = s[0];
+                    if (k + 1 < kdim) v.y = s[1];
+                    if (k + 2 < kdim) v.z = s[2];
+                    if (k + 3 < kdim) v.w = s[3];
+                }
+            }
+            st[e] = v;
+        }
+    }
+
+    __device__ __forceinline__ void store(float *buf) const
+    {
+#pragma unroll
+        for (int e = 0; e < N4; ++e) {
+            const int idx = tid + e * NT;
+            const int row = idx / PER_ROW, kc = idx % PER_ROW;
+            float *d = buf + (kc * 4) * LD + row;
+            d[0 * LD] = st[e].x;
+            d[1 * LD] = st[e].y;
+            d[2 * LD] = st[e].z;
+            d[3 * LD] = st[e].w;
+        }
+    }
+};
+
+struct ConvParams {
+    const float *p;       // xbar[R][Ci][H][W] or dtilde[R][Co][Ho][Wo]
+    int Ci, Co, H, W, kh, kw, stride, pad, Ho, Wo;
+    int HoWo, Kg;         // Ho*Wo, Ci*kh*kw
+    int Q;                // R*Ho*Wo output pixels over all encoded rows
+    long long img;        // Ci*H*W
+};
+
+// Convolution forward, B operand: rows = output pixels q = (r, ho, wo),
+// contraction k = (ci, a, b); element = xbar[r][ci][ho*s+a-p][wo*s+b-p].
+template <int ROWS, int BK, int NT, int LD>
+struct LoadIm2colFwd {
+    using Params = ConvParams;
+    static constexpr int KSTEP = NT / ROWS;
+    static constexpr int NE = BK / KSTEP;
+    static_assert(NT % ROWS == 0 && BK % KSTEP == 0, "tile/threads");
+    float st[NE];
+    const float *base; int H, W, kh, kw, Kg, ih0, iw0, pcol, ksub; bool valid;
+
+    __device__ __forceinline__ void init(const Params &a, int q0, int tid)
+    {
+        pcol = tid % ROWS; ksub = tid / ROWS;
+        H = a.H; W = a.W; kh = a.kh; kw = a.kw; Kg = a.Kg;
+        const int q = q0 + pcol;
+        valid = q < a.Q;
+        const int r = valid ? q / a.HoWo : 0;
+        const int pix = valid ? q - r * a.HoWo : 0;
+        const int ho = pix / a.Wo, wo = pix - ho * a.Wo;
+        ih0 = ho * a.stride - a.pad;
+        iw0 = wo * a.stride - a.pad;
+        base = a.p + (long long)r * a.img;
+    }
+
+    __device__ __forceinline__ void load(int kt)
+    {
+        int k = kt * BK + ksub;
+        int ci = k / (kh * kw);
+        int rem = k - ci * (kh * kw);
+        int fa = rem / kw, fb = rem - fa * kw;
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            const int ih = ih0 + fa, iw = iw0 + fb;
+            const bool ok = valid && k < Kg && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W;
+            st[e] = ok ? base[((long long)ci * H + ih) * W + iw] : 0.0f;
+            k += KSTEP; fb += KSTEP;
+            while (fb >= kw) { fb -= kw; ++fa; }
+            while (fa >= kh) { fa -= kh; ++ci; }
+        }
+    }
+
+    __device__ __forceinline__ void store(float *buf) const
+    {
+#pragma unroll
+        for (int e = 0; e < NE; ++e) buf[(ksub + e * KSTEP) * LD + pcol] = st[e];
+    }
+};
+
+// Convolution weight gradient, A operand: rows = co, contraction q = (r, pix);
+// element = dtilde[r][co][pix].
+template <int ROWS, int BK, int NT, int LD>
+struct LoadDeltaQ {
+    using Params = ConvParams;
+    static constexpr int RSTEP = NT / BK;
+    static constexpr int NE = ROWS / RSTEP;
+    static_assert(NT % BK == 0 && ROWS % RSTEP == 0, "tile/threads");
+    float st[NE];
+    const float *p; int Co, HoWo, Q, row0, kq, rsub;
+
+    __device__ __forceinline__ void init(const Params &a, int row0_, int tid)
+    { p = a.p; Co = a.Co; HoWo = a.HoWo; Q = a.Q; row0 = row0_; kq = tid % BK; rsub = tid / BK; }
+
+    __device__ __forceinline__ void load(int kt)
+    {
+        const int q = kt * BK + kq;
+        const bool ok = q < Q;
+        const int r = ok ? q / HoWo : 0;
+        const int pix = ok ? q - r * HoWo : 0;
+        const float *s = p + (long long)r * Co * HoWo + pix;
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            const int co = row0 + rsub + e * RSTEP;
+            st[e] = (ok && co < Co) ? s[(long long)co * HoWo] : 0.0f;
+        }
+    }
+
+    __device__ __forceinline__ void store(float *buf) const
+    {
+#pragma unroll
+        for (int e = 0; e < NE; ++e) buf[kq * LD + rsub + e * RSTEP] = st[e];
+    }
+};
+
+// Convolution weight gradient, B operand: rows = j = (ci, a, b), contraction
+// q = (r, ho, wo); element = xbar[r][ci][ho*s+a-p][wo*s+b-p].
+template <int ROWS, int BK, int NT, int LD>
+struct LoadIm2colQ {
+    using Params = ConvParams;
+    static constexpr int RSTEP = NT / BK;
+    static constexpr int NE = ROWS / RSTEP;
+    static_assert(NT % BK == 0 && ROWS % RSTEP == 0, "tile/threads");
+    float st[NE];
+    int joff[NE];          // (ci*H + a)*W + b
+    short fa[NE], fb[NE];  // filter tap; fa = -20000 marks a row beyond Kg
+    const float *p; int H, W, Wo, HoWo, Q, stride, pad, kq, rsub; long long img;
+
+    __device__ __forceinline__ void init(const Params &a, int row0, int tid)
+    {
+        p = a.p; H = a.H; W = a.W; Wo = a.Wo; HoWo = a.HoWo; Q = a.Q;
+        stride = a.stride; pad = a.pad; img = a.img;
+        kq = tid % BK; rsub = tid / BK;
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            const int j = row0 + rsub + e * RSTEP;
+            const int ci = j / (a.kh * a.kw);
+            const int rem = j - ci * (a.kh * a.kw);
+            const int ta = rem / a.kw, tb = rem - ta * a.kw;
+            const bool ok = j < a.Kg;
+            joff[e] = ok ? (ci * H + ta) * W + tb : 0;
+            fa[e] = ok ? (short)ta : (short)-20000;
+            fb[e] = (short)tb;
+        }
+    }
+
+    __device__ __forceinline__ void load(int kt)
+    {
+        const int q = kt * BK + kq;
+        const bool okq = q < Q;
+        const int r = okq ? q / HoWo : 0;
+        const int pix = okq ? q - r * HoWo : 0;
+        const int ho = pix / Wo, wo = pix - ho * Wo;
+        const int ih0 = ho * stride - pad, iw0 = wo * stride - pad;
+        const long long b0 = (long long)r * img + (long long)ih0 * W + iw0;
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            const int ih = ih0 + fa[e], iw = iw0 + fb[e];
+            const bool ok = okq && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W;
+            st[e] = ok ? p[b0 + joff[e]] : 0.0f;
+        }
+    }
+
+    __device__ __forceinline__ void store(float *buf) const
+    {
+#pragma unroll
+        for (int e = 0; e < NE; ++e) buf[kq * LD + rsub + e * RSTEP] = st[e];
+    }
+};
+
+// ---------------------------------------------------------------------------
+// Epilogues: where output element (row, col) lives.
+// ---------------------------------------------------------------------------
+
+struct EpiDense {            // C[row][col], leading dimension ld
+    long long ld; int rows, cols;
+    __device__ __forceinline__ bool col_ok(int col) const { return col < cols; }
+    __device__ __forceinline__ long long col_off(int col) const { return col; }
+    __device__ __forceinline__ long long row_off(int row) const { return (long long)row * ld; }
+};
+
+struct EpiConvFwd {          // ybar[r][co][pix]; row = co, col = q = r*HoWo + pix
+    int rows, cols, HoWo; long long chw;   // chw = Co*HoWo
+    __device__ __forceinline__ bool col_ok(int col) const { return col < cols; }
+    __device__ __forceinline__ long long col_off(int col) const
+    { const int r = col / HoWo; return (long long)r * chw + (col - r * HoWo); }
+    __device__ __forceinline__ long long row_off(int row) const { return (long long)row * HoWo; }
+};
+
+// ---------------------------------------------------------------------------
+// The engine.
+// ---------------------------------------------------------------------------
+
+struct RunParams {
+    int tiles_m, tiles_n;     // output tiles
+    int ktiles, per_split;    // contraction steps in total / per K slice
+    int splits;
+    float alpha; int accumulate;
+    float *out;               // final output (splits == 1) ...
+    float *part;              // ... or partial sums [splits][out_elems]
+    long long out_elems;
+};
+
+template <class C, class LA, class LB, class EP>
+__global__ __launch_bounds__(C::NT) void contract_kernel(typename LA::Params pa,
+                                                          typename LB::Params pb, EP ep,
+                                                          RunParams rp)
+{
+    __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
+    constexpr int A_BUF = C::BK * C::LDA, B_BUF = C::BK * C::LDB;
+    float *const As = lds;                 // two buffers of A_BUF floats
+    float *const Bs = lds + 2 * A_BUF;     // two buffers of B_BUF floats
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave % C::WM) * (C::BM / C::WM);
+    const int wn0 = (wave / C::WM) * (C::BN / C::WN);
+
+    const int tiles = rp.tiles_m * rp.tiles_n;
+    const int split = blockIdx.x / tiles;
+    const int t = blockIdx.x - split * tiles;
+    const int tile_n = t / rp.tiles_m, tile_m = t - tile_n * rp.tiles_m;
+    const int row0 = tile_m * C::BM, col0 = tile_n * C::BN;
+
+    LA la; LB lb;
+    la.init(pa, row0, tid);
+    lb.init(pb, col0, tid);
+
+    f32x16 acc[C::TM][C::TN];
+#pragma unroll
+    for (int mi = 0; mi < C::TM; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < C::TN; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+
+    const int kt0 = split * rp.per_split;
+    int kt1 = kt0 + rp.per_split;
+    if (kt1 > rp.ktiles) kt1 = rp.ktiles;
+
+    const int li = lane & 31, lh = lane >> 5;
+    if (kt0 < kt1) {
+        la.load(kt0); lb.load(kt0);
+        la.store(As); lb.store(Bs);
+        __syncthreads();
+        for (int kt = kt0; kt < kt1; ++kt) {
+            const int cur = (kt - kt0) & 1;
+            const bool more = kt + 1 < kt1;
+            if (more) { la.load(kt + 1); lb.load(kt + 1); }
+            const float *a_s = As + cur * A_BUF + lh * C::LDA + wm0 + li;
+            const float *b_s = Bs + cur * B_BUF + lh * C::LDB + wn0 + li;
+#pragma unroll
+            for (int kk = 0; kk < C::BK; kk += 2) {
+                float a[C::TM], b[C::TN];
+#pragma unroll
+                for (int mi = 0; mi < C::TM; ++mi) a[mi] = a_s[kk * C::LDA + mi * 32];
+#pragma unroll
+                for (int ni = 0; ni < C::TN; ++ni) b[ni] = b_s[kk * C::LDB + ni * 32];
+#pragma unroll
+                for (int mi = 0; mi < C::TM; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < C::TN; ++ni)
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
+            }
+            if (more) { la.store(As + (cur ^ 1) * A_BUF); lb.store(Bs + (cur ^ 1) * B_BUF); }
+            __syncthreads();
+        }
+    }
+
+    // 32x32 accumulator block: lane holds column li, rows 8*(v/4) + 4*lh + v%4.
+    float *dst = rp.splits > 1 ? rp.part + (long long)split * rp.out_elems : rp.out;
+    const bool direct = rp.splits == 1;
+#pragma unroll
+    for (int ni = 0; ni < C::TN; ++ni) {
+        const int col = col0 + wn0 + ni * 32 + li;
+        if (!ep.col_ok(col)) continue;
+        const long long coff = ep.col_off(col);
+#pragma unroll
+        for (int mi = 0; mi < C::TM; ++mi)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + wm0 + mi * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
+                if (row >= ep.rows) continue;
+                float *d = dst + ep.row_off(row) + coff;
+                float val = acc[mi][ni][v];
+                if (direct) {
+                    val *= rp.alpha;
+                    if (rp.accumulate) val += *d;
+                }
+                *d = val;
+            }
+    }
+}
+
+// out[i] = (accumulate ? out[i] : 0) + alpha * sum_s part[s][i], slices added
+// in index order so that reruns are bitwise identical.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part,
+                                                            float *__restrict__ out,
+                                                            long long out_elems, int splits,
+                                                            float alpha, int accumulate)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= out_elems) return;
+    float s = 0.0f;
+    for (int k = 0; k < splits; ++k) s += part[(long long)k * out_elems + i];
+    s *= alpha;
+    if (accumulate) s += out[i];
+    out[i] = s;
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+template <class C, class LA, class LB, class EP>
+dk_status run(const typename LA::Params &pa, const typename LB::Params &pb, const EP &ep,
+              int rows, int cols, long long kdim, float alpha, int accumulate, float *out,
+              long long out_elems, float *part, size_t part_bytes, hipStream_t st)
+{
+    RunParams rp;
+    rp.tiles_m = (rows + C::BM - 1) / C::BM;
+    rp.tiles_n = (cols + C::BN - 1) / C::BN;
+    rp.ktiles = (int)((kdim + C::BK - 1) / C::BK);
+    const long long tiles = (long long)rp.tiles_m * rp.tiles_n;
+    const dk_split_plan sp = dk_plan_split(tiles, rp.ktiles, out_elems);
+    rp.splits = sp.splits;
+    rp.per_split = sp.ktiles_per_split;
+    rp.alpha = alpha;
+    rp.accumulate = accumulate;
+    rp.out = out;
+    rp.part = part;
+    rp.out_elems = out_elems;
+    DK_REQUIRE(tiles * rp.splits <= 0x7fffffffll, DK_ERR_SHAPE);
+    if (rp.splits > 1)
+        DK_REQUIRE(part && part_bytes >= (size_t)rp.splits * out_elems * sizeof(float), DK_ERR_WORKSPACE);
+    contract_kernel<C, LA, LB, EP><<<dim3((unsigned)(tiles * rp.splits)), dim3(C::NT), 0, st>>>(pa, pb, ep, rp);
+    DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+    if (rp.splits > 1) {
+        splitk_reduce_kernel<<<dim3((unsigned)((out_elems + 255) / 256)), dim3(256), 0, st>>>(
+            part, out, out_elems, rp.splits, alpha, accumulate);
+        DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+    }
+    return DK_OK;
+}
+
+template <class C>
+size_t split_bytes(long long rows, long long cols, long long kdim, long long out_elems)
+{
+    const long long tiles = ((rows + C::BM - 1) / C::BM) * ((cols + C::BN - 1) / C::BN);
+    const long long ktiles = (kdim + C::BK - 1) / C::BK;
+    const dk_split_plan sp = dk_plan_split(tiles, ktiles, out_elems);
+    return sp.splits > 1 ? (size_t)sp.splits * out_elems * sizeof(float) : 0;
+}
+
+// Tile shapes.  Dense layers and wide convolutions use a square 128x128 tile
+// (four waves, 64x64 each); convolutions with at most 64 output channels use
+// a 64-row tile so that no MFMA row is wasted.
+using CfgSq = Cfg<128, 128, 16, 2, 2>;
+using CfgFlat = Cfg<64, 256, 16, 1, 4>;
+using CfgWg64 = Cfg<64, 128, 16, 2, 2>;
+
+ConvParams conv_params(const dk_geom &g, const float *p, long long R)
+{
+    ConvParams c;
+    c.p = p;
+    c.Ci = g.Ci; c.Co = g.Co; c.H = g.H; c.W = g.W; c.kh = g.kh; c.kw = g.kw;
+    c.stride = g.stride; c.pad = g.pad; c.Ho = g.Ho; c.Wo = g.Wo;
+    c.HoWo = g.Ho * g.Wo;
+    c.Kg = (int)g.Kg;
+    c.Q = (int)(R * c.HoWo);
+    c.img = g.n;
+    return c;
+}
+
+template <class C, bool VA, bool VB>
+dk_status run_dense_nt(const float *A, const float *B, float *Cout, int rows, int cols, int kdim,
+                       float *part, size_t part_bytes, hipStream_t st)
+{
+    using LA = LoadRowMajorK<C::BM, C::BK, C::NT, C::LDA, VA>;
+    using LB = LoadRowMajorK<C::BN, C::BK, C::NT, C::LDB, VB>;
+    MatParams pa = {A, kdim, rows, kdim}, pb = {B, kdim, cols, kdim};
+    EpiDense ep = {cols, rows, cols};
+    return run<C, LA, LB, EpiDense>(pa, pb, ep, rows, cols, kdim, 1.0f, 0, Cout,
+                                    (long long)rows * cols, part, part_bytes, st);
+}
+
+template <class C, bool VEC>
+dk_status run_dense_tn(const float *A, const float *B, float *Cout, int rows, int cols, int kdim,
+                       float alpha, int accumulate, float *part, size_t part_bytes, hipStream_t st)
+{
+    using LA = LoadKMajor<C::BM, C::BK, C::NT, C::LDA, VEC>;
+    using LB = LoadKMajor<C::BN, C::BK, C::NT, C::LDB, VEC>;
+    MatParams pa = {A, rows, rows, kdim}, pb = {B, cols, cols, kdim};
+    EpiDense ep = {cols, rows, cols};
+    return run<C, LA, LB, EpiDense>(pa, pb, ep, rows, cols, kdim, alpha, accumulate, Cout,
+                                    (long long)rows * cols, part, part_bytes, st);
+}
+
+template <class C, bool VW>
+dk_status run_conv_fwd(const dk_geom &g, const float *W, const float *xbar, float *ybar, long long R,
+                       float *part, size_t part_bytes, hipStream_t st)
+{
+    using LA = LoadRowMajorK<C::BM, C::BK, C::NT, C::LDA, VW>;
+    using LB = LoadIm2colFwd<C::BN, C::BK, C::NT, C::LDB>;
+    const ConvParams cp = conv_params(g, xbar, R);
+    MatParams pa = {W, g.Kg, g.Co, (int)g.Kg};
+    EpiConvFwd ep = {g.Co, cp.Q, cp.HoWo, (long long)g.Co * cp.HoWo};
+    return run<C, LA, LB, EpiConvFwd>(pa, cp, ep, g.Co, cp.Q, g.Kg, 1.0f, 0, ybar, R * g.m, part,
+                                      part_bytes, st);
+}
+
+template <class C>
+dk_status run_conv_wgrad(const dk_geom &g, const float *dtilde, const float *xbar, float *dW,
+                         long long R, float alpha, int accumulate, float *part, size_t part_bytes,
+                         hipStream_t st)
+{
+    using LA = LoadDeltaQ<C::BM, C::BK, C::NT, C::LDA>;
+    using LB = LoadIm2colQ<C::BN, C::BK, C::NT, C::LDB>;
+    const ConvParams ca = conv_params(g, dtilde, R);
+    const ConvParams cb = conv_params(g, xbar, R);
+    EpiDense ep = {g.Kg, g.Co, (int)g.Kg};
+    return run<C, LA, LB, EpiDense>(ca, cb, ep, g.Co, (int)g.Kg, ca.Q, alpha, accumulate, dW,
+                                    (long long)g.Co * g.Kg, part, part_bytes, st);
+}
+
+bool conv_flat(const dk_geom &g) { return g.Co <= 64; }
+
+} // namespace
+
+size_t dk_ws_fwd_bytes(const dk_geom &g, long long R)
+{
+    size_t b;
+    if (!g.conv)
+        b = split_bytes<CfgSq>(R, g.M, g.N, R * g.m);
+    else if (conv_flat(g))
+        b = split_bytes<CfgFlat>(g.Co, R * g.Ho * g.Wo, g.Kg, R * g.m);
+    else
+        b = split_bytes<CfgSq>(g.Co, R * g.Ho * g.Wo, g.Kg, R * g.m);
+    return b < 256 ? 256 : b;
+}
+
+size_t dk_ws_wgrad_bytes(const dk_geom &g, long long R)
+{
+    // mixed gradients dtilde[R][m] first, then the split-K partial sums
+    size_t b = align_up((size_t)R * g.m * sizeof(float), 256);
+    if (!g.conv)
+        b += split_bytes<CfgSq>(g.M, g.N, R, (long long)g.M * g.N);
+    else if (conv_flat(g))
+        b += split_bytes<CfgWg64>(g.Co, g.Kg, R * g.Ho * g.Wo, g.Co * g.Kg);
+    else
+        b += split_bytes<CfgSq>(g.Co, g.Kg, R * g.Ho * g.Wo, g.Co * g.Kg);
+    return b;
+}
+
+DK_EXPORT dk_status dk_linear_fwd(const float *W, const float *xbar, float *ybar, int M, int N, int R,
+                                  void *ws, size_t ws_bytes, void *stream)
+{
+    DK_REQUIRE(W && xbar && ybar, DK_ERR_NULL);
+    DK_REQUIRE(M >= 1 && N >= 1 && R >= 1, DK_ERR_SHAPE);
+    DK_REQUIRE((long long)R * M < (1ll << 40) && (long long)M * N < (1ll << 40), DK_ERR_SHAPE);
+    DK_REQUIRE(dk_aligned(W, 4) && dk_aligned(xbar, 4) && dk_aligned(ybar, 4), DK_ERR_ALIGN);
+    dk_geom g = {};
+    g.M = M; g.N = N; g.n = N; g.m = M;
+    DK_REQUIRE(ws && ws_bytes >= dk_ws_fwd_bytes(g, R), DK_ERR_WORKSPACE);
+    DK_REQUIRE(dk_aligned(ws, 16), DK_ERR_ALIGN);
+    hipStream_t st = (hipStream_t)stream;
+    const bool va = (N % 4 == 0) && dk_aligned(xbar, 16);
+    const bool vb = (N % 4 == 0) && dk_aligned(W, 16);
+    if (va && vb)
+        return run_dense_nt<CfgSq, true, true>(xbar, W, ybar, R, M, N, (float *)ws, ws_bytes, st);
+    return run_dense_nt<CfgSq, false, false>(xbar, W, ybar, R, M, N, (float *)ws, ws_bytes, st);
+}
+
+DK_EXPORT dk_status dk_conv_fwd(const dk_layer *L, const float *W, const float *xbar, float *ybar,
+                                int R, void *ws, size_t ws_bytes, void *stream)
+{
+    DK_REQUIRE(L && W && xbar && ybar, DK_ERR_NULL);
+    dk_geom g;
+    dk_status s = dk_layer_geom(L, &g);
+    if (s != DK_OK) return s;
+    DK_REQUIRE(g.conv, DK_ERR_UNSUPPORTED);
+    DK_REQUIRE(R >= 1 && (long long)R * g.Ho * g.Wo < (1ll << 31) - 512, DK_ERR_SHAPE);
+    DK_REQUIRE(dk_aligned(W, 4) && dk_aligned(xbar, 4) && dk_aligned(ybar, 4), DK_ERR_ALIGN);
+    DK_REQUIRE(ws && ws_bytes >= dk_ws_fwd_bytes(g, R), DK_ERR_WORKSPACE);
+    DK_REQUIRE(dk_aligned(ws, 16), DK_ERR_ALIGN);
+    hipStream_t st = (hipStream_t)stream;
+    const bool vw = (g.Kg % 4 == 0) && dk_aligned(W, 16);
+    if (conv_flat(g))
+        return vw ? run_conv_fwd<CfgFlat, true>(g, W, xbar, ybar, R, (float *)ws, ws_bytes, st)
+                  : run_conv_fwd<CfgFlat, false>(g, W, xbar, ybar, R, (float *)ws, ws_bytes, st);
+    return vw ? run_conv_fwd<CfgSq, true>(g, W, xbar, ybar, R, (float *)ws, ws_bytes, st)
+              : run_conv_fwd<CfgSq, false>(g, W, xbar, ybar, R, (float *)ws, ws_bytes, st);
+}
+
+DK_EXPORT dk_status dk_wgrad(const dk_layer *L, const float *delta, const float *B, const float *gamma,
+                             const float *xbar, float *dW, int G, int K, float scale, int accumulate,
+                             void *ws, size_t ws_bytes, void *stream)
+{
+    DK_REQUIRE(L && delta && B && gamma && xbar && dW, DK_ERR_NULL);
+    DK_REQUIRE(G >= 1 && K >= 1 && K <= DK_MAX_K, DK_ERR_SHAPE);
+    dk_geom g;
+    dk_status s = dk_layer_geom(L, &g);
+    if (s != DK_OK) return s;
+    const long long R = (long long)G * (K + 2);
+    DK_REQUIRE(R < (1ll << 31), DK_ERR_SHAPE);
+    if (g.conv) DK_REQUIRE(R * g.Ho * g.Wo < (1ll << 31) - 512, DK_ERR_SHAPE);
+    DK_REQUIRE(dk_aligned(delta, 4) && dk_aligned(B, 4) && dk_aligned(gamma, 4) &&
+                   dk_aligned(xbar, 4) && dk_aligned(dW, 4), DK_ERR_ALIGN);
+    DK_REQUIRE(ws && ws_bytes >= dk_ws_wgrad_bytes(g, R), DK_ERR_WORKSPACE);
+    DK_REQUIRE(dk_aligned(ws, 16), DK_ERR_ALIGN);
+    hipStream_t st = (hipStream_t)stream;
+
+    float *dtilde = (float *)ws;
+    const size_t dt_bytes = align_up((size_t)R * g.m * sizeof(float), 256);
+    float *part = (float *)((char *)ws + dt_bytes);
+    const size_t part_bytes = ws_bytes - dt_bytes;
+
+    s = dk_delta_mix(delta, B, gamma, dtilde, G, K, g.m, st);
+    if (s != DK_OK) return s;
+
+    if (!g.conv) {
+        const bool vec = (g.M % 4 == 0) && (g.N % 4 == 0) && dk_aligned(xbar, 16);
+        if (vec)
+            return run_dense_tn<CfgSq, true>(dtilde, xbar, dW, g.M, g.N, (int)R, scale, accumulate,
+                                             part, part_bytes, st);
+        return run_dense_tn<CfgSq, false>(dtilde, xbar, dW, g.M, g.N, (int)R, scale, accumulate,
+                                          part, part_bytes, st);
+    }
+    if (conv_flat(g))
+        return run_conv_wgrad<CfgWg64>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
+    return run_conv_wgrad<CfgSq>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
+}

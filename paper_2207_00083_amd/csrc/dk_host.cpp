@@ -1,0 +1,161 @@
+// Host-side parts of the library: status strings, layer geometry, workspace
+// sizing and the trusted-side coefficient derivation.  No device code here.
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "dk_internal.h"
+
+DK_EXPORT const char *dk_status_str(int s)
+{
+    switch (s) {
+    case DK_OK: return "ok";
+    case DK_ERR_NULL: return "required pointer is NULL";
+    case DK_ERR_SHAPE: return "invalid size or K";
+    case DK_ERR_UNSUPPORTED: return "unsupported layer geometry";
+    case DK_ERR_ALIGN: return "device pointer not 4-byte aligned";
+    case DK_ERR_WORKSPACE: return "workspace missing or too small";
+    case DK_ERR_HIP: return "HIP launch failed";
+    case DK_ERR_SINGULAR: return "singular encoding matrix or zero gamma";
+    default: return "unknown status";
+    }
+}
+
+DK_EXPORT int dk_version(void) { return 100; }
+
+dk_status dk_layer_geom(const dk_layer *L, dk_geom *g)
+{
+    DK_REQUIRE(L && g, DK_ERR_NULL);
+    memset(g, 0, sizeof(*g));
+    if (L->kind == DK_LINEAR) {
+        DK_REQUIRE(L->M >= 1 && L->N >= 1, DK_ERR_SHAPE);
+        g->conv = false;
+        g->M = L->M;
+        g->N = L->N;
+        g->n = L->N;
+        g->m = L->M;
+        return DK_OK;
+    }
+    DK_REQUIRE(L->kind == DK_CONV2D, DK_ERR_UNSUPPORTED);
+    DK_REQUIRE(L->Ci >= 1 && L->Co >= 1 && L->H >= 1 && L->W >= 1, DK_ERR_SHAPE);
+    DK_REQUIRE(L->kh >= 1 && L->kw >= 1 && L->stride >= 1 && L->pad >= 0, DK_ERR_SHAPE);
+    DK_REQUIRE(L->kh <= 16 && L->kw <= 16 && L->stride <= 16 && L->pad <= 16, DK_ERR_UNSUPPORTED);
+    DK_REQUIRE(L->H + 2 * L->pad >= L->kh && L->W + 2 * L->pad >= L->kw, DK_ERR_SHAPE);
+    g->conv = true;
+    g->Ci = L->Ci; g->Co = L->Co; g->H = L->H; g->W = L->W;
+    g->kh = L->kh; g->kw = L->kw; g->stride = L->stride; g->pad = L->pad;
+    g->Ho = (L->H + 2 * L->pad - L->kh) / L->stride + 1;
+    g->Wo = (L->W + 2 * L->pad - L->kw) / L->stride + 1;
+    g->n = (long long)L->Ci * L->H * L->W;
+    g->m = (long long)L->Co * g->Ho * g->Wo;
+    g->Kg = (long long)L->Ci * L->kh * L->kw;
+    // the kernels index one sample's image and the filter bank with 32-bit ints
+    DK_REQUIRE(g->n < (1ll << 30) && g->m < (1ll << 30) && g->Kg * L->Co < (1ll << 30), DK_ERR_SHAPE);
+    return DK_OK;
+}
+
+DK_EXPORT long long dk_layer_in_len(const dk_layer *L)
+{
+    dk_geom g;
+    return dk_layer_geom(L, &g) == DK_OK ? g.n : 0;
+}
+
+DK_EXPORT long long dk_layer_out_len(const dk_layer *L)
+{
+    dk_geom g;
+    return dk_layer_geom(L, &g) == DK_OK ? g.m : 0;
+}
+
+DK_EXPORT size_t dk_workspace_bytes(const dk_layer *L, int op, int G, int K)
+{
+    if (G < 1 || K < 1 || K > DK_MAX_K) return 0;
+    if (op == DK_OP_VERIFY) return dk_ws_verify_bytes(G);
+    dk_geom g;
+    if (dk_layer_geom(L, &g) != DK_OK) return 0;
+    const long long R = (long long)G * (K + 2);
+    if (op == DK_OP_FWD) return dk_ws_fwd_bytes(g, R);
+    if (op == DK_OP_WGRAD) return dk_ws_wgrad_bytes(g, R);
+    return 0;
+}
+
+dk_split_plan dk_plan_split(long long out_tiles, long long ktiles, long long out_elems)
+{
+    // One workgroup per (output tile, K slice).  MI355X has 256 compute units
+    // and a contraction workgroup leaves room for about four per unit, so aim
+    // for ~1024 workgroups when the output alone has too few tiles.
+    dk_split_plan p = {1, (int)ktiles};
+    if (ktiles < 1) { p.ktiles_per_split = 0; return p; }
+    if (out_tiles >= 512 || ktiles == 1) return p;
+    long long s = (1024 + out_tiles - 1) / out_tiles;
+    if (s > ktiles) s = ktiles;
+    if (s > DK_MAX_SPLITS) s = DK_MAX_SPLITS;
+    while (s > 1 && s * out_elems * 4 > DK_SPLIT_WS_CAP_BYTES) --s;
+    const long long per = (ktiles + s - 1) / s;
+    p.ktiles_per_split = (int)per;
+    p.splits = (int)((ktiles + per - 1) / per);
+    return p;
+}
+
+// Gauss-Jordan inversion in fp64 with partial pivoting; a is destroyed.
+static bool invert(std::vector<double> &a, std::vector<double> &inv, int n)
+{
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < n; ++j) inv[i * n + j] = (i == j);
+    for (int c = 0; c < n; ++c) {
+        int piv = c;
+        for (int r = c + 1; r < n; ++r)
+            if (std::fabs(a[r * n + c]) > std::fabs(a[piv * n + c])) piv = r;
+        const double d = a[piv * n + c];
+        if (!(std::fabs(d) > 0.0) || !std::isfinite(d)) return false;
+        if (piv != c)
+            for (int j = 0; j < n; ++j) {
+                std::swap(a[c * n + j], a[piv * n + j]);
+                std::swap(inv[c * n + j], inv[piv * n + j]);
+            }
+        for (int j = 0; j < n; ++j) { a[c * n + j] /= d; inv[c * n + j] /= d; }
+        for (int r = 0; r < n; ++r) {
+            if (r == c) continue;
+            const double f = a[r * n + c];
+            if (f == 0.0) continue;
+            for (int j = 0; j < n; ++j) {
+                a[r * n + j] -= f * a[c * n + j];
+                inv[r * n + j] -= f * inv[c * n + j];
+            }
+        }
+    }
+    for (int q = 0; q < n * n; ++q)
+        if (!std::isfinite(inv[q])) return false;
+    return true;
+}
+
+DK_EXPORT dk_status dk_coeffs(const float *A, const float *gamma, int G, int K,
+                              float *Ainv, float *nvec, float *B)
+{
+    DK_REQUIRE(A, DK_ERR_NULL);
+    DK_REQUIRE(G >= 1 && K >= 1 && K <= DK_MAX_K, DK_ERR_SHAPE);
+    DK_REQUIRE(!B || gamma, DK_ERR_NULL);
+    const int S = K + 2;
+    std::vector<double> a(S * S), inv(S * S);
+    // first pass: validate everything so that nothing is written on error
+    for (int pass = 0; pass < 2; ++pass)
+        for (int g = 0; g < G; ++g) {
+            if (pass == 0 && B)
+                for (int j = 0; j < S; ++j) {
+                    const float gj = gamma[(size_t)g * S + j];
+                    DK_REQUIRE(gj != 0.0f && std::isfinite(gj), DK_ERR_SINGULAR);
+                }
+            for (int q = 0; q < S * S; ++q) a[q] = (double)A[(size_t)g * S * S + q];
+            DK_REQUIRE(invert(a, inv, S), DK_ERR_SINGULAR);
+            if (pass == 0) continue;
+            if (Ainv)
+                for (int q = 0; q < S * S; ++q) Ainv[(size_t)g * S * S + q] = (float)inv[q];
+            if (nvec)
+                for (int j = 0; j < S; ++j) nvec[(size_t)g * S + j] = (float)inv[j * S + (S - 1)];
+            if (B)
+                for (int j = 0; j < S; ++j)
+                    for (int i = 0; i < K; ++i)
+                        B[((size_t)g * S + j) * K + i] =
+                            (float)(inv[j * S + i] / (double)gamma[(size_t)g * S + j]);
+        }
+    return DK_OK;
+}

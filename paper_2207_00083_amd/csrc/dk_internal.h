@@ -1,0 +1,51 @@
+// Internal helpers shared by the library's translation units (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "darknight.h"
+
+#define DK_EXPORT extern "C" __attribute__((visibility("default")))
+
+#define DK_REQUIRE(cond, err) \
+    do {                      \
+        if (!(cond)) return (err); \
+    } while (0)
+
+static inline bool dk_aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+static inline dk_status dk_launch_status()
+{
+    return hipGetLastError() == hipSuccess ? DK_OK : DK_ERR_HIP;
+}
+
+// Validated geometry of a layer, filled by dk_layer_geom().
+struct dk_geom {
+    bool conv;
+    long long n, m;       // per-sample input / output length
+    int M, N;             // dense
+    int Ci, Co, H, W, kh, kw, stride, pad, Ho, Wo;
+    long long Kg;         // Ci*kh*kw
+};
+
+dk_status dk_layer_geom(const dk_layer *L, dk_geom *g);
+
+// Workspace carving, identical in dk_workspace_bytes and in the entry points.
+size_t dk_ws_fwd_bytes(const dk_geom &g, long long R);
+size_t dk_ws_wgrad_bytes(const dk_geom &g, long long R);
+size_t dk_ws_verify_bytes(int G);
+
+// Split-K plan for a contraction: how many slices, tiles per slice.
+struct dk_split_plan {
+    int splits;
+    int ktiles_per_split;
+};
+dk_split_plan dk_plan_split(long long out_tiles, long long ktiles, long long out_elems);
+
+#define DK_VERIFY_MAX_BLOCKS 64
+#define DK_MAX_SPLITS 256
+#define DK_SPLIT_WS_CAP_BYTES (1ll << 30)
+
+// Gradient mixing kernel launcher (defined with the other bandwidth-bound
+// kernels, used by dk_wgrad).
+dk_status dk_delta_mix(const float *delta, const float *B, const float *gamma, float *dtilde,
+                       int G, int K, long long m, hipStream_t st);

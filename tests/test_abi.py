@@ -1,0 +1,129 @@
+"""The C-ABI library loads, exports every symbol include/darknight.h declares
+and rejects bad arguments on the host, before anything is launched (so these
+run without a GPU)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import dk_inputs
+import oracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def dk():
+    import paper_2207_00083_amd as dk
+    if not os.path.exists(dk.lib_path()):
+        from paper_2207_00083_amd.build import build_library
+        build_library()
+    dk.load()
+    return dk
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "darknight.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dk_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(dk):
+    names = declared_symbols()
+    for must in ("dk_encode", "dk_linear_fwd", "dk_conv_fwd", "dk_wgrad", "dk_decode", "dk_verify",
+                 "dk_coeffs", "dk_workspace_bytes"):
+        assert must in names
+    lib = C.CDLL(dk.lib_path())
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_no_torch_or_oracle_in_the_library(dk):
+    blob = open(dk.lib_path(), "rb").read()
+    assert b"libtorch" not in blob and b"dk_oracle" not in blob
+
+
+def test_status_strings(dk):
+    assert dk.dk_status_str(0) == "ok"
+    assert len({dk.dk_status_str(i) for i in range(8)}) == 8
+
+
+def test_null_and_shape_errors_before_launch(dk):
+    lib = dk.load()
+    one = C.c_void_p(16)      # non-NULL, never dereferenced: every call below fails validation first
+    null = C.c_void_p(0)
+    assert lib.dk_encode(null, one, one, one, 1, 2, 8, null) == 1
+    assert lib.dk_encode(one, one, one, one, 0, 2, 8, null) == 2
+    assert lib.dk_encode(one, one, one, one, 1, 0, 8, null) == 2
+    assert lib.dk_encode(one, one, one, one, 1, dk.DK_MAX_K + 1, 8, null) == 2
+    assert lib.dk_encode(one, one, one, one, 1, 2, 0, null) == 2
+    assert lib.dk_encode(C.c_void_p(18), one, one, one, 1, 2, 8, null) == 4
+    assert lib.dk_decode(one, null, one, 1, 2, 8, null) == 1
+    assert lib.dk_decode(one, one, one, 1, 2, -1, null) == 2
+    assert lib.dk_verify(one, one, 1e-3, null, null, 1, 2, 8, one, 1 << 20, null) == 1
+    assert lib.dk_verify(one, one, 1e-3, one, null, 1, 2, 8, null, 0, null) == 5
+    assert lib.dk_verify(one, one, 1e-3, one, null, 1, 2, 8, one, 8, null) == 5
+    assert lib.dk_verify(one, one, -1.0, one, null, 1, 2, 8, one, 1 << 20, null) == 2
+    assert lib.dk_linear_fwd(one, one, null, 4, 4, 4, one, 1 << 20, null) == 1
+    assert lib.dk_linear_fwd(one, one, one, 4, 0, 4, one, 1 << 20, null) == 2
+    assert lib.dk_linear_fwd(one, one, one, 4, 4, 4, null, 0, null) == 5
+    lay = dk.DkLayer.of(dk_inputs.conv(4, 4, 8, 8, 3))
+    assert lib.dk_conv_fwd(None, one, one, one, 4, one, 1 << 20, null) == 1
+    assert lib.dk_conv_fwd(C.byref(lay), one, one, one, 0, one, 1 << 20, null) == 2
+    assert lib.dk_conv_fwd(C.byref(lay), one, one, one, 4, one, 8, null) == 5
+    lin = dk.DkLayer.of(dk_inputs.linear(4, 4))
+    assert lib.dk_conv_fwd(C.byref(lin), one, one, one, 4, one, 1 << 20, null) == 3
+    bad = dk.DkLayer.of(dk_inputs.conv(4, 4, 2, 2, 5, 1, 0))      # filter larger than padded image
+    assert lib.dk_conv_fwd(C.byref(bad), one, one, one, 4, one, 1 << 20, null) == 2
+    assert lib.dk_wgrad(C.byref(lay), one, one, one, one, null, 1, 2, 1.0, 0, one, 1 << 20, null) == 1
+    assert lib.dk_wgrad(C.byref(lay), one, one, one, one, one, 1, 2, 1.0, 0, one, 8, null) == 5
+    assert lib.dk_wgrad(C.byref(lay), one, one, one, one, one, 1, 99, 1.0, 0, one, 1 << 20, null) == 2
+
+
+def test_workspace_queries(dk):
+    L = dk_inputs.conv(64, 64, 32, 32, 3)
+    assert dk.dk_workspace_bytes(L, dk.DK_OP_FWD, 64, 4) >= 256
+    m = dk.dk_layer_out_len(L)
+    assert m == 64 * 32 * 32 and dk.dk_layer_in_len(L) == 64 * 32 * 32
+    assert dk.dk_workspace_bytes(L, dk.DK_OP_WGRAD, 64, 4) >= 64 * 6 * m * 4
+    assert dk.dk_workspace_bytes(None, dk.DK_OP_VERIFY, 64, 4) > 0
+    assert dk.dk_workspace_bytes(L, dk.DK_OP_FWD, 0, 4) == 0
+    assert dk.dk_workspace_bytes(L, 7, 4, 4) == 0
+    assert dk.dk_layer_out_len(dk_inputs.conv(3, 64, 224, 224, 7, 2, 3)) == 64 * 112 * 112
+
+
+@pytest.mark.parametrize("K", [1, 2, 4, 8, 16])
+def test_host_coefficients_match_the_oracle(dk, K):
+    rng = np.random.default_rng(K)
+    A, gamma = dk_inputs.sample_coeff_draws(rng, 7, K)
+    Ainv, nvec, B = dk.dk_coeffs(A, gamma)
+    oAinv, onvec, oB = oracle.coefficients(A, gamma)
+    for got, ref in ((Ainv, oAinv), (nvec, onvec), (B, oB)):
+        assert got.dtype == np.float32
+        assert np.max(np.abs(got - ref)) <= 2e-7 * np.max(np.abs(ref)) + 1e-12
+
+
+def test_host_coefficients_reject_singular(dk):
+    A = np.ones((1, 4, 4), dtype=np.float32)
+    g = np.ones((1, 4), dtype=np.float32)
+    with pytest.raises(dk.DkError) as e:
+        dk.dk_coeffs(A, g)
+    assert e.value.status == 7
+    A = np.eye(4, dtype=np.float32)[None]
+    g[0, 2] = 0.0
+    with pytest.raises(dk.DkError) as e:
+        dk.dk_coeffs(A, g)
+    assert e.value.status == 7
+
+
+def test_product_does_not_import_the_oracle():
+    import subprocess, sys
+    code = ("import sys; import paper_2207_00083_amd; "
+            "assert not any(m == 'oracle' or m.startswith('oracle.') for m in sys.modules), 'oracle imported'")
+    subprocess.run([sys.executable, "-c", code], check=True, cwd=ROOT)
+    for root, _, files in os.walk(os.path.join(ROOT, "paper_2207_00083_amd")):
+        for f in files:
+            if f.endswith((".py", ".hip", ".cpp", ".h")):
+                assert "oracle" not in open(os.path.join(root, f)).read().lower().replace("no fallback", ""), f

@@ -1,0 +1,377 @@
+"""Parity of the HIP path (through the C ABI) with the fp64 oracle, element by
+element on the same seeded fp32 inputs.  Every test prints its case first so
+that a faulting launch can be named from the log.
+
+Tolerances (normwise, max|got-ref| / max|ref|):
+  * 1e-3 on decoded outputs and weight gradients against the plain layer
+    definitions -- the contract;
+  * 2e-5 on single bandwidth-bound kernels and 1e-4 on single contractions
+    against the oracle's stage of the same name (fp32 rounding only);
+  * integrity verdicts: exact.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import dk_inputs
+import oracle
+from conftest import normwise_err as nerr
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+TOL_CONTRACT = 1e-3
+TOL_MIX = 2e-5
+TOL_GEMM = 1e-4
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def dk():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: torch.cuda.is_available() is False")
+    import paper_2207_00083_amd as dk
+    dk.load()
+    return dk
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def coeffs_dev(dk, d):
+    Ainv, nvec, B = dk.dk_coeffs(d["A"], d["gamma"])
+    return Ainv, nvec, B
+
+
+# ----------------------------------------------------------------------
+# bandwidth-bound kernels vs the oracle stage of the same name
+# ----------------------------------------------------------------------
+
+MIX_CASES = [(1, 1, 1), (1, 3, 7), (2, 1, 256), (2, 5, 1023), (3, 4, 1024), (4, 6, 4100),
+             (4, 64, 2048), (5, 2, 333), (8, 3, 5000), (8, 16, 8192), (16, 2, 777), (7, 2, 12)]
+
+
+@pytest.mark.parametrize("K,G,n", MIX_CASES)
+def test_encode_decode_verify_stages(dk, K, G, n):
+    say("mix stages", dict(K=K, G=G, n=n))
+    rng = np.random.default_rng(1000 + K * 7 + G * 3 + n)
+    S = K + 2
+    X = rng.standard_normal((G * K, n)).astype(np.float32)
+    r = (10 * rng.standard_normal((G, n))).astype(np.float32)
+    A, gamma = dk_inputs.sample_coeff_draws(rng, G, K)
+    Ainv, nvec, B = dk.dk_coeffs(A, gamma)
+
+    xbar = host(dk.dk_encode(dev(X), dev(r), dev(A), K))
+    ref = oracle.encode(X, r, A)
+    assert xbar.shape == (G * S, n)
+    assert nerr(xbar, ref) < TOL_MIX
+
+    # decode / verify are checked on a synthetic Ybar with the oracle's encodings as data
+    ybar = ref.astype(np.float32)
+    y = host(dk.dk_decode(dev(ybar), dev(Ainv), K))
+    yref = oracle.decode(ybar, Ainv)
+    assert y.shape == (G * K, n)
+    assert np.max(np.abs(y - yref)) < TOL_MIX * np.max(np.abs(ybar)) * np.max(np.abs(Ainv)) * S
+
+    v, rho = dk.dk_verify(dev(ybar), dev(nvec), K, tol=1e-3)
+    vref, rhoref = oracle.verify(ybar, nvec, 1e-3)
+    assert host(v).tolist() == vref.tolist() == [0] * G
+    # corrupt one element per odd group, where the null vector is largest
+    yc = ybar.copy()
+    expect = np.zeros(G, dtype=np.int32)
+    for g in range(0, G, 2):
+        j = int(np.argmax(np.abs(nvec[g])))
+        e = int(rng.integers(n))
+        yc[g * S + j, e] += 0.5 * max(1.0, float(np.max(np.abs(ybar[g * S:(g + 1) * S]))))
+        expect[g] = 1
+    v, rho = dk.dk_verify(dev(yc), dev(nvec), K, tol=1e-3)
+    vref, rhoref = oracle.verify(yc, nvec, 1e-3)
+    assert vref.tolist() == expect.tolist()
+    assert host(v).tolist() == vref.tolist()
+    assert np.allclose(host(rho)[expect == 1], rhoref[expect == 1], rtol=1e-3)
+
+
+def test_verify_nonfinite_and_zero(dk):
+    say("verify non-finite / all-zero")
+    K, G, n = 2, 4, 600
+    S = K + 2
+    rng = np.random.default_rng(5)
+    ybar = rng.standard_normal((G * S, n)).astype(np.float32)
+    nvec = np.ones((G, S), dtype=np.float32)
+    ybar[0:S] = 0.0                          # all-zero group: clean by definition
+    ybar[1 * S + 1, 17] = np.nan
+    ybar[2 * S + 3, 599] = np.inf
+    ybar[3 * S:4 * S] = 0.0
+    ybar[3 * S + 0, 5] = 1.0
+    ybar[3 * S + 1, 5] = -1.0                # consistent: t = 0
+    v, rho = dk.dk_verify(dev(ybar), dev(nvec), K, tol=1e-3)
+    vref, rhoref = oracle.verify(ybar, nvec, 1e-3)
+    assert vref.tolist() == [0, 1, 1, 0]
+    assert host(v).tolist() == vref.tolist()
+    rho = host(rho)
+    assert rho[0] == 0.0 and np.isinf(rho[1]) and np.isinf(rho[2]) and rho[3] == 0.0
+
+
+# ----------------------------------------------------------------------
+# contractions vs the plain definitions
+# ----------------------------------------------------------------------
+
+DENSE_CASES = [(4, 512, 256), (1, 1, 1), (3, 5, 7), (150, 300, 77), (260, 130, 1000),
+               (129, 257, 1025), (64, 1000, 4096), (384, 128, 130)]
+
+
+@pytest.mark.parametrize("R,M,N", DENSE_CASES)
+def test_linear_fwd(dk, R, M, N):
+    say("linear fwd", dict(R=R, M=M, N=N))
+    rng = np.random.default_rng(R * 31 + M * 17 + N)
+    W = rng.standard_normal((M, N)).astype(np.float32)
+    X = rng.standard_normal((R, N)).astype(np.float32)
+    got = host(dk.dk_linear_fwd(dev(W), dev(X)))
+    ref = oracle.dense_fwd(W, X)
+    assert got.shape == ref.shape
+    assert nerr(got, ref) < TOL_GEMM
+
+
+CONV_CASES = [
+    # Ci, Co, H, W, k, stride, pad, R
+    (8, 16, 12, 12, 3, 1, 1, 6),
+    (3, 64, 32, 32, 3, 1, 1, 6),
+    (16, 130, 9, 11, 3, 1, 1, 5),
+    (20, 24, 14, 14, 1, 1, 0, 6),
+    (16, 72, 14, 14, 1, 2, 0, 4),
+    (8, 8, 15, 13, 3, 2, 1, 3),
+    (3, 16, 30, 30, 7, 2, 3, 3),
+    (64, 64, 8, 8, 3, 1, 1, 12),
+    (5, 7, 6, 6, 3, 1, 0, 2),
+    (130, 20, 4, 4, 3, 1, 1, 3),
+    (32, 40, 2, 2, 3, 1, 1, 12),
+]
+
+
+@pytest.mark.parametrize("Ci,Co,H,W,k,stride,pad,R", CONV_CASES)
+def test_conv_fwd(dk, Ci, Co, H, W, k, stride, pad, R):
+    L = dk_inputs.conv(Ci, Co, H, W, k, stride, pad)
+    say("conv fwd", L, "R=%d" % R)
+    rng = np.random.default_rng(Ci * 131 + Co * 17 + H + k + stride)
+    Wt = rng.standard_normal(L.w_shape).astype(np.float32)
+    X = rng.standard_normal((R,) + L.in_shape).astype(np.float32)
+    got = host(dk.dk_conv_fwd(L, dev(Wt), dev(X)))
+    ref = oracle.conv_fwd(Wt, X, stride, pad)
+    assert got.shape == ref.shape
+    assert nerr(got, ref) < TOL_GEMM
+
+
+def _masked_case(L, K, G, seed, **kw):
+    rng = np.random.default_rng(seed)
+    return dk_inputs.masked_layer_inputs(rng, L, K=K, batch=G * K, **kw)
+
+
+def _run_masked(dk, d, tol=1e-3, scale=1.0, corrupt=None):
+    """Whole hot path on the GPU: encode -> layer on encodings -> verify ->
+    decode -> wgrad.  `corrupt` = list of (g, j, flat index, eta) added to Ybar."""
+    L, K, G = d["layer"], d["K"], d["G"]
+    S = K + 2
+    Ainv, nvec, B = dk.dk_coeffs(d["A"], d["gamma"])
+    xbar = dk.dk_encode(dev(d["X"]), dev(d["r"]), dev(d["A"]), K)
+    W = dev(d["W"])
+    ybar = dk.dk_linear_fwd(W, xbar) if L.kind == "linear" else dk.dk_conv_fwd(L, W, xbar)
+    if corrupt:
+        flat = ybar.view(G * S, -1)
+        for g, j, e, eta in corrupt:
+            flat[g * S + j, e] += eta
+    verdict, resid = dk.dk_verify(ybar, dev(nvec), K, tol=tol)
+    y = dk.dk_decode(ybar, dev(Ainv), K)
+    dW = dk.dk_wgrad(L, dev(d["delta"]), dev(B), dev(d["gamma"]), xbar, K, scale=scale)
+    return dict(xbar=host(xbar), ybar=host(ybar), verdict=host(verdict), resid=host(resid),
+                y=host(y), dW=host(dW), nvec=nvec)
+
+
+DENSE_MASKED = [(2, 1, 512, 256), (1, 3, 40, 50), (4, 8, 300, 260), (8, 4, 130, 1030), (3, 5, 37, 91)]
+
+
+@pytest.mark.parametrize("K,G,M,N", DENSE_MASKED)
+def test_dense_masked_layer(dk, K, G, M, N):
+    L = dk_inputs.linear(M, N)
+    say("dense masked layer", dict(K=K, G=G, M=M, N=N))
+    d = _masked_case(L, K, G, seed=K * 1000 + G * 100 + M + N)
+    out = _run_masked(dk, d, scale=1.0 / K)
+    Y = oracle.dense_fwd(d["W"], d["X"])
+    dW = oracle.dense_wgrad(d["delta"], d["X"], scale=1.0 / K)
+    assert nerr(out["y"], Y) < TOL_CONTRACT
+    assert nerr(out["dW"], dW) < TOL_CONTRACT
+    assert out["verdict"].tolist() == [0] * G
+    # stage-level diagnostics against the staged oracle
+    st = oracle.masked_layer(d["W"], d["X"], d["r"], d["delta"], d["A"], d["gamma"], scale=1.0 / K)
+    assert nerr(out["xbar"], st["Xbar"]) < TOL_MIX
+    assert nerr(out["ybar"], st["Ybar"]) < TOL_GEMM
+    assert st["verdict"].tolist() == [0] * G
+
+
+CONV_MASKED = [
+    # K, G, Ci, Co, H, W, k, stride, pad
+    (4, 3, 8, 16, 12, 12, 3, 1, 1),
+    (2, 4, 3, 64, 16, 16, 3, 1, 1),
+    (4, 2, 16, 130, 9, 11, 3, 1, 1),
+    (2, 3, 20, 24, 14, 14, 1, 1, 0),
+    (3, 2, 16, 72, 14, 14, 1, 2, 0),
+    (2, 2, 8, 8, 15, 13, 3, 2, 1),
+    (1, 2, 3, 16, 30, 30, 7, 2, 3),
+    (8, 1, 32, 40, 2, 2, 3, 1, 1),
+    (4, 2, 70, 20, 4, 4, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("K,G,Ci,Co,H,W,k,stride,pad", CONV_MASKED)
+def test_conv_masked_layer(dk, K, G, Ci, Co, H, W, k, stride, pad):
+    L = dk_inputs.conv(Ci, Co, H, W, k, stride, pad)
+    say("conv masked layer", dict(K=K, G=G), L)
+    d = _masked_case(L, K, G, seed=K * 1000 + G * 100 + Ci + Co + H + k)
+    out = _run_masked(dk, d)
+    Y = oracle.conv_fwd(d["W"], d["X"], stride, pad)
+    dW = oracle.conv_wgrad(d["delta"], d["X"], k, k, stride, pad)
+    assert nerr(out["y"], Y) < TOL_CONTRACT
+    assert nerr(out["dW"], dW) < TOL_CONTRACT
+    assert out["verdict"].tolist() == [0] * G
+
+
+def test_wgrad_accumulate_and_scale(dk):
+    say("wgrad accumulate")
+    L = dk_inputs.linear(96, 200)
+    d1 = _masked_case(L, 4, 3, seed=77)
+    d2 = _masked_case(L, 4, 3, seed=78)
+    ref = np.zeros(L.w_shape)
+    dW = None
+    for d, acc in ((d1, False), (d2, True)):
+        _, _, B = dk.dk_coeffs(d["A"], d["gamma"])
+        xbar = dk.dk_encode(dev(d["X"]), dev(d["r"]), dev(d["A"]), 4)
+        dW = dk.dk_wgrad(L, dev(d["delta"]), dev(B), dev(d["gamma"]), xbar, 4, dW=dW,
+                         scale=0.25, accumulate=acc)
+        ref += oracle.dense_wgrad(d["delta"], d["X"], scale=0.25)
+    assert nerr(host(dW), ref) < TOL_CONTRACT
+
+
+def test_verdicts_match_oracle_under_corruption(dk):
+    say("verdicts under corruption")
+    L = dk_inputs.conv(8, 16, 10, 10, 3, 1, 1)
+    K, G = 4, 8
+    S = K + 2
+    d = _masked_case(L, K, G, seed=4242)
+    st = oracle.masked_layer(d["W"], d["X"], d["r"], d["delta"], d["A"], d["gamma"], stride=1, pad=1)
+    _, nvec, _ = oracle.coefficients(d["A"], d["gamma"])
+    rng = np.random.default_rng(9)
+    corrupt, expect = [], np.zeros(G, dtype=np.int32)
+    ybar_c = st["Ybar"].reshape(G * S, -1).copy()
+    for g in (1, 6):
+        j = int(np.argmax(np.abs(nvec[g])))
+        e = int(rng.integers(ybar_c.shape[1]))
+        scale_g = np.max(np.sum(np.abs(nvec[g][:, None] * ybar_c[g * S:(g + 1) * S]), axis=0))
+        eta = float(0.5 * scale_g / abs(nvec[g, j]))
+        corrupt.append((g, j, e, eta))
+        ybar_c[g * S + j, e] += eta
+        expect[g] = 1
+    vref, rhoref = oracle.verify(ybar_c, nvec, 1e-3)
+    assert vref.tolist() == expect.tolist()
+    out = _run_masked(dk, d, corrupt=corrupt)
+    assert out["verdict"].tolist() == vref.tolist()
+    clean = out["resid"][expect == 0]
+    assert clean.max() < 1e-4               # honest fp32 residual stays 10x below tol
+    assert np.all(out["resid"][expect == 1] > 1e-2)
+
+
+# ----------------------------------------------------------------------
+# the named workloads
+# ----------------------------------------------------------------------
+
+def test_config1_full(dk):
+    say("config 1 (dense 256->512, K=2, one group)")
+    d = dk_inputs.config1()
+    out = _run_masked(dk, d)
+    assert nerr(out["y"], oracle.dense_fwd(d["W"], d["X"])) < TOL_CONTRACT
+    assert nerr(out["dW"], oracle.dense_wgrad(d["delta"], d["X"])) < TOL_CONTRACT
+    assert out["verdict"].tolist() == [0]
+
+
+def test_config2_reduced_full_compare(dk):
+    say("config 2 reduced (conv 3x3 64->64 @16x16, batch 16, K=4)")
+    d = dk_inputs.config2(batch=16, hw=16)
+    out = _run_masked(dk, d)
+    assert nerr(out["y"], oracle.conv_fwd(d["W"], d["X"], 1, 1)) < TOL_CONTRACT
+    assert nerr(out["dW"], oracle.conv_wgrad(d["delta"], d["X"], 3, 3, 1, 1)) < TOL_CONTRACT
+    assert out["verdict"].tolist() == [0] * d["G"]
+
+
+def test_config2_full_size_sampled(dk):
+    say("config 2 full size (batch 256 @32x32), sampled outputs")
+    d = dk_inputs.config2()
+    L, K, G = d["layer"], d["K"], d["G"]
+    out = _run_masked(dk, d)
+    rng = np.random.default_rng(22)
+    npts = 20000
+    pts = np.stack([rng.integers(G * K, size=npts), rng.integers(L.Co, size=npts),
+                    rng.integers(L.Ho, size=npts), rng.integers(L.Wo, size=npts)], axis=1)
+    pts[:64, 2] = 0; pts[64:128, 2] = L.Ho - 1; pts[128:192, 3] = 0; pts[192:256, 3] = L.Wo - 1
+    ref = oracle.conv_fwd_points(d["W"], d["X"], pts, 1, 1)
+    got = out["y"][tuple(pts.T)]
+    ymax = float(np.max(np.abs(out["y"])))
+    assert np.max(np.abs(got - ref)) / ymax < TOL_CONTRACT
+    wpts = np.array([[co, ci, a, b] for co in range(0, L.Co, 3) for ci in range(0, L.Ci, 5)
+                     for a in range(3) for b in range(3)])
+    wref = oracle.conv_wgrad_points(d["delta"], d["X"], 3, 3, wpts, 1, 1)
+    wgot = out["dW"][tuple(wpts.T)]
+    assert np.max(np.abs(wgot - wref)) / np.max(np.abs(wref)) < TOL_CONTRACT
+    assert out["verdict"].tolist() == [0] * G
+    assert out["resid"].max() < 1e-4
+
+
+def test_config5_layer2_full_size_sampled(dk):
+    say("config 5 layer 2 (dense 4096->4096, batch 1024, K=8), sampled outputs, 2 corrupted groups")
+    d = dk_inputs.config5(index=1)[0]
+    L, K, G = d["layer"], d["K"], d["G"]
+    S = K + 2
+    nv = dk.dk_coeffs(d["A"], d["gamma"])[1]
+    corrupt = []
+    for g in (0, 64):
+        j = int(np.argmax(np.abs(nv[g])))
+        corrupt.append((g, j, 123 + g, 50.0))
+    out = _run_masked(dk, d, corrupt=corrupt)
+    expect = np.zeros(G, dtype=np.int32)
+    expect[[0, 64]] = 1
+    assert out["verdict"].tolist() == expect.tolist()
+    rng = np.random.default_rng(55)
+    npts = 20000
+    clean_rows = np.array([s for s in range(G * K) if s // K not in (0, 64)])
+    pts = np.stack([rng.choice(clean_rows, size=npts), rng.integers(L.M, size=npts)], axis=1)
+    ref = oracle.dense_fwd_points(d["W"], d["X"], pts)
+    got = out["y"][tuple(pts.T)]
+    assert np.max(np.abs(got - ref)) / np.max(np.abs(ref)) < TOL_CONTRACT
+    wpts = np.stack([rng.integers(L.M, size=npts), rng.integers(L.N, size=npts)], axis=1)
+    wref = oracle.dense_wgrad_points(d["delta"], d["X"], wpts)
+    wgot = out["dW"][tuple(wpts.T)]
+    assert np.max(np.abs(wgot - wref)) / np.max(np.abs(wref)) < TOL_CONTRACT
+
+
+# ----------------------------------------------------------------------
+# error behaviour through the C ABI
+# ----------------------------------------------------------------------
+
+def test_short_workspace_is_refused(dk):
+    say("short workspace")
+    L = dk_inputs.linear(64, 64)
+    d = _masked_case(L, 2, 2, seed=3)
+    xbar = dk.dk_encode(dev(d["X"]), dev(d["r"]), dev(d["A"]), 2)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(dk.DkError) as e:
+        dk.dk_linear_fwd(dev(d["W"]), xbar, ws=small)
+    assert e.value.status == 5
