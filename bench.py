@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the masked-layer hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input that
+is already resident in HBM:
+    dk_encode -> dk_conv_fwd | dk_linear_fwd -> dk_verify -> dk_decode -> dk_wgrad
+Prints ONE JSON line: whole-path executed TFLOP/s (forward + weight gradient
+on all K+2 encoded rows per group), decoded samples/s, the roofline record of
+the dominant kernel (timed with events on the launch stream inside the timed
+region) and the fp64 CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
+HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E
+
+
+def workload(name):
+    import dk_inputs
+    if name == "config1":
+        return dk_inputs.config1(), "config1: dense 256->512, K=2, 1 group"
+    if name == "config2":
+        return dk_inputs.config2(), "config2: conv3x3 s1 p1 64->64 @32x32 NCHW, batch 256, K=4 (G=64, 384 encoded rows)"
+    if name.startswith("config3."):
+        i = int(name.split(".")[1])
+        return dk_inputs.config3(index=i)[0], "config3 layer %d (VGG-16 conv stack @32x32, batch 128, K=4)" % i
+    if name.startswith("config5."):
+        i = int(name.split(".")[1])
+        return dk_inputs.config5(index=i)[0], "config5 layer %d (VGG classifier, batch 1024, K=8)" % i
+    raise SystemExit("unknown workload " + name)
+
+
+def algorithmic_bytes(K, G, n, m):
+    """HBM bytes each bandwidth-bound kernel must move (fp32), per launch."""
+    S = K + 2
+    return {
+        "encode": 4 * G * n * (K + 1 + S),
+        "verify": 4 * G * m * S,
+        "decode": 4 * G * m * (S + K),
+        "delta_mix": 4 * G * m * (K + S),
+    }
+
+
+def cpu_baseline(d, budget_s=15.0):
+    """The fp64 oracle's staged masked layer on the first few groups."""
+    import oracle
+    L, K, G = d["layer"], d["K"], d["G"]
+    S = K + 2
+    flop_per_group = 2 * 2 * S * L.macs_per_row
+
+    def run(ng):
+        sl = slice(0, ng * K)
+        t0 = time.perf_counter()
+        oracle.masked_layer(d["W"], d["X"][sl], d["r"][:ng], d["delta"][sl], d["A"][:ng],
+                            d["gamma"][:ng], stride=L.stride, pad=L.pad)
+        return time.perf_counter() - t0
+
+    oracle.build()
+    t1 = run(1)
+    ng = int(max(1, min(G, budget_s / max(t1, 1e-3))))
+    t = run(ng) if ng > 1 else t1
+    return {
+        "value": flop_per_group * ng / t / 1e12, "unit": "TFLOP/s",
+        "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "staged fp64 oracle (encode, layer on encodings, verify, decode, masked wgrad) on the "
+                  "first %d of %d groups, %.1f s" % (ng, G, t),
+        "samples_per_s": ng * K / t,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="config2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.stderr.write("bench.py: this build covers the one-GPU hot path only; run with --gpus 1\n")
+        raise SystemExit(2)
+
+    import torch
+    import paper_2207_00083_amd as dk
+    dk.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    d, wname = workload(args.workload)
+    L, K, G = d["layer"], d["K"], d["G"]
+    S = K + 2
+    n, m = dk.dk_layer_in_len(L), dk.dk_layer_out_len(L)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    Ainv, nvec, B = dk.dk_coeffs(d["A"], d["gamma"])
+    X, r, W, delta = dev(d["X"]), dev(d["r"]), dev(d["W"]), dev(d["delta"])
+    A_d, Ainv_d, nvec_d, B_d, gamma_d = dev(d["A"]), dev(Ainv), dev(nvec), dev(B), dev(d["gamma"])
+    f32 = dict(dtype=torch.float32, device="cuda")
+    xbar = torch.empty((G * S,) + L.in_shape, **f32)
+    ybar = torch.empty((G * S,) + L.out_shape, **f32)
+    y = torch.empty((G * K,) + L.out_shape, **f32)
+    dW = torch.empty(L.w_shape, **f32)
+    verdict = torch.empty(G, dtype=torch.int32, device="cuda")
+    resid = torch.empty(G, **f32)
+    u8 = dict(dtype=torch.uint8, device="cuda")
+    ws_fwd = torch.empty(dk.dk_workspace_bytes(L, dk.DK_OP_FWD, G, K), **u8)
+    ws_wg = torch.empty(dk.dk_workspace_bytes(L, dk.DK_OP_WGRAD, G, K), **u8)
+    ws_vf = torch.empty(dk.dk_workspace_bytes(None, dk.DK_OP_VERIFY, G, K), **u8)
+    conv = L.kind == "conv"
+
+    stages = ["encode", "fwd", "verify", "decode", "wgrad"]
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        dk.dk_encode(X, r, A_d, K, xbar=xbar)
+        if ev: ev[1].record()
+        if conv:
+            dk.dk_conv_fwd(L, W, xbar, ybar=ybar, ws=ws_fwd)
+        else:
+            dk.dk_linear_fwd(W, xbar, ybar=ybar, ws=ws_fwd)
+        if ev: ev[2].record()
+        dk.dk_verify(ybar, nvec_d, K, tol=1e-3, verdict=verdict, resid=resid, ws=ws_vf)
+        if ev: ev[3].record()
+        dk.dk_decode(ybar, Ainv_d, K, y=y)
+        if ev: ev[4].record()
+        dk.dk_wgrad(L, delta, B_d, gamma_d, xbar, K, dW=dW, scale=1.0, ws=ws_wg)
+        if ev: ev[5].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    assert int(verdict.sum().item()) == 0, "clean synthetic data must verify"
+    ms_per_step = wall / args.steps * 1e3
+    stage_ms = {s: float(np.mean([e[i].elapsed_time(e[i + 1]) for e in events]))
+                for i, s in enumerate(stages)}
+
+    flop_fwd = 2.0 * G * S * L.macs_per_row         # executed: all K+2 encoded rows
+    flop_step = 2.0 * flop_fwd                      # forward + weight gradient
+    tflops = flop_step / (ms_per_step * 1e-3) / 1e12
+    ab = algorithmic_bytes(K, G, n, m)
+
+    # Dominant kernel: the forward contraction (one launch per step, bracketed
+    # exactly by the two events around the forward entry point).
+    fwd_tflops = flop_fwd / (stage_ms["fwd"] * 1e-3) / 1e12
+    roofline = {
+        "kernel": "contract_kernel (forward, implicit-GEMM conv)" if conv else "contract_kernel (forward, dense)",
+        "bound": "mfma", "achieved": fwd_tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+        "frac": fwd_tflops / MFMA_F32_PEAK_TFLOPS, "traffic": None,
+        "avg_launch_ms": stage_ms["fwd"], "flop_per_launch": flop_fwd,
+    }
+    hbm = {k: {"GBps": ab[k] / (stage_ms[k] * 1e-3) / 1e9,
+               "frac": ab[k] / (stage_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+               "bytes": ab[k], "avg_launch_ms": stage_ms[k]}
+           for k in ("encode", "verify", "decode")}
+
+    out = {
+        "metric": "masked-layer TFLOP/s (fwd+wgrad, executed on all K+2 encoded rows), whole hot path",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wname, "K": K, "G": G, "layer": L.asdict()},
+        "pct_mfma_peak": 100.0 * tflops / MFMA_F32_PEAK_TFLOPS,
+        "decoded_samples_per_s": G * K / (ms_per_step * 1e-3),
+        "effective_tflops": tflops * K / S,
+        "stage_ms": stage_ms,
+        "wgrad_tflops": flop_fwd / (stage_ms["wgrad"] * 1e-3) / 1e12,
+        "roofline": roofline,
+        "hbm_kernels": hbm,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(d)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -77,6 +77,10 @@ long long dk_layer_out_len(const dk_layer *L);
  * for invalid arguments (every valid case needs a non-zero workspace). */
 size_t dk_workspace_bytes(const dk_layer *L, int op, int G, int K);
 
+/* The DK_OP_FWD workspace for exactly R encoded rows (R need not be a
+ * multiple of K+2: the forward entry points take any row count). */
+size_t dk_fwd_workspace_bytes(const dk_layer *L, long long R);
+
 /* Trusted-side coefficient derivation (host arithmetic, fp64 internally).
  * From the random draws A[G][S][S] and gamma[G][S] (host) derive, per group:
  *   Ainv = A^{-1}                 [G][S][S]  (Forward Pass, decoding relation

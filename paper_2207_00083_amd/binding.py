@@ -65,6 +65,7 @@ def load():
         "dk_layer_in_len": (ll, [LP]),
         "dk_layer_out_len": (ll, [LP]),
         "dk_workspace_bytes": (sz, [LP, ip, ip, ip]),
+        "dk_fwd_workspace_bytes": (sz, [LP, ll]),
         "dk_coeffs": (ip, [vp, vp, ip, ip, vp, vp, vp]),
         "dk_encode": (ip, [vp, vp, vp, vp, ip, ip, ll, vp]),
         "dk_linear_fwd": (ip, [vp, vp, vp, ip, ip, ip, vp, sz, vp]),
@@ -191,9 +192,7 @@ def dk_linear_fwd(W, xbar, ybar=None, ws=None, stream=None):
 
 
 def _fwd_ws_bytes(lay, R):
-    """Forward workspace for R encoded rows: the C query takes (G, K) with
-    R = G*(K+2); K = 1 and G = ceil(R/3) never undersizes it."""
-    return load().dk_workspace_bytes(C.byref(lay), DK_OP_FWD, (R + 2) // 3, 1)
+    return load().dk_fwd_workspace_bytes(C.byref(lay), R)
 
 
 def dk_conv_fwd(layer, W, xbar, ybar=None, ws=None, stream=None):

@@ -78,6 +78,13 @@ DK_EXPORT size_t dk_workspace_bytes(const dk_layer *L, int op, int G, int K)
     return 0;
 }
 
+DK_EXPORT size_t dk_fwd_workspace_bytes(const dk_layer *L, long long R)
+{
+    dk_geom g;
+    if (R < 1 || R >= (1ll << 31) || dk_layer_geom(L, &g) != DK_OK) return 0;
+    return dk_ws_fwd_bytes(g, R);
+}
+
 dk_split_plan dk_plan_split(long long out_tiles, long long ktiles, long long out_elems)
 {
     // One workgroup per (output tile, K slice).  MI355X has 256 compute units
