@@ -13,6 +13,7 @@
 // step).  What differs per operation is only how an operand tile is fetched
 // from HBM (the loader) and where an output element lives (the epilogue).
 #include "dk_internal.h"
+#include "dk_patch.h"
 
 namespace {
 
@@ -554,6 +555,16 @@ size_t dk_ws_fwd_bytes(const dk_geom &g, long long R)
         b = split_bytes<CfgFlat>(g.Co, R * g.Ho * g.Wo, g.Kg, R * g.m);
     else
         b = split_bytes<CfgSq>(g.Co, R * g.Ho * g.Wo, g.Kg, R * g.m);
+    if (g.conv) {
+        // whichever kernel family the entry point picks (it depends on the
+        // alignment of xbar too), the workspace must be large enough
+        dk_patch_plan pl;
+        for (int aligned = 0; aligned < 2; ++aligned)
+            if (dk_patch_fwd_plan(g, R, aligned != 0, &pl)) {
+                const size_t pb = dk_patch_wp_bytes(pl) + pl.part_bytes;
+                if (pb > b) b = pb;
+            }
+    }
     return b < 256 ? 256 : b;
 }
 
@@ -602,6 +613,9 @@ DK_EXPORT dk_status dk_conv_fwd(const dk_layer *L, const float *W, const float *
     DK_REQUIRE(ws && ws_bytes >= dk_ws_fwd_bytes(g, R), DK_ERR_WORKSPACE);
     DK_REQUIRE(dk_aligned(ws, 16), DK_ERR_ALIGN);
     hipStream_t st = (hipStream_t)stream;
+    dk_patch_plan pl;
+    if (dk_patch_fwd_plan(g, R, dk_aligned(xbar, 16), &pl))
+        return dk_patch_fwd_run(g, pl, W, xbar, ybar, (float *)ws, st);
     const bool vw = (g.Kg % 4 == 0) && dk_aligned(W, 16);
     if (conv_flat(g))
         return vw ? run_conv_fwd<CfgFlat, true>(g, W, xbar, ybar, R, (float *)ws, ws_bytes, st)

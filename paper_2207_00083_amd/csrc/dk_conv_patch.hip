@@ -1,0 +1,357 @@
+// Convolution forward on encoded images with the input staged as a zero-padded
+// PATCH in LDS (stride-1/2 filters of compile-time size).
+//
+// The generic implicit-GEMM loader gathers every im2col element from global
+// memory with its own bounds test (kh*kw-fold re-reads and a dozen VALU
+// instructions per element).  Here a workgroup owns BM output channels x BN
+// consecutive output pixels of one image (or several whole small images) and
+// walks the input channels in chunks of CB: the chunk's input rows are copied
+// once into LDS with the zero border materialised, and the MFMA B operand for
+// filter tap (a, b) of channel c is read at
+//     lane_base(pixel) + c*PLANE + a*PW + b
+// i.e. a per-lane constant plus a wave-uniform offset: no bounds tests and
+// almost no address arithmetic in the inner loop.  The filter bank is repacked
+// once per call into the k-major, channel-pair order the MFMA steps consume,
+// so its tile is a straight 16-byte copy into LDS.
+#include "dk_internal.h"
+#include "dk_patch.h"
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Repack W[Co][Ci][KH][KW] -> wp[chunk][row][Co_pad], row = 2*step + h with
+// step = (c' * KH + a) * KW + b and channel = chunk*CB + c' + h*CB/2; zero
+// beyond Ci and Co.
+__global__ __launch_bounds__(256) void pack_filters_kernel(const float *__restrict__ W,
+                                                           float *__restrict__ wp, int Ci, int Co,
+                                                           int KH, int KW, int CB, int Co_pad,
+                                                           long long total)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int co = (int)(i % Co_pad);
+    long long t = i / Co_pad;
+    const int rows = CB * KH * KW;
+    const int row = (int)(t % rows);
+    const int chunk = (int)(t / rows);
+    const int h = row & 1, step = row >> 1;
+    const int b = step % KW, a = (step / KW) % KH, cp = step / (KW * KH);
+    const int ci = chunk * CB + cp + h * (CB / 2);
+    float v = 0.0f;
+    if (co < Co && ci < Ci) v = W[(((long long)co * Ci + ci) * KH + a) * KW + b];
+    wp[i] = v;
+}
+
+template <int BM, int BN, int WM, int WN, int KH, int KW, int CB, int VEC, int MAXSLOT>
+__global__ __launch_bounds__(64 * WM * WN) void conv_patch_fwd_kernel(dk_patch_params p)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    constexpr int NT = 64 * WM * WN;
+    constexpr int KK = KH * KW;
+    constexpr int LDA = BM + 4;
+    constexpr int WROWS = CB * KK;                  // filter rows per chunk
+    constexpr int W4 = WROWS * (BM / 4);            // 16-byte vectors in a filter tile
+    constexpr int WSLOT = (W4 + NT - 1) / NT;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    static_assert(CB % 2 == 0, "channel pairs");
+
+    float *const patch = lds;
+    float *const As = lds + p.patch_floats;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lh = lane >> 5;
+    const int wm0 = (wave % WM) * (BM / WM);
+    const int wn0 = (wave / WM) * (BN / WN);
+
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int split = blockIdx.x / tiles;
+    const int t = blockIdx.x - split * tiles;
+    const int tile_n = t / p.tiles_m, tile_m = t - tile_n * p.tiles_m;
+    const int co0 = tile_m * BM;
+
+    // which images / pixels this tile covers
+    int r0, p0, ho_a;
+    if (!p.multi) {
+        r0 = tile_n / p.tiles_per_img;
+        p0 = (tile_n - r0 * p.tiles_per_img) * BN;
+        ho_a = p0 / p.Wo;
+    } else {
+        r0 = tile_n * p.IPT;
+        p0 = 0;
+        ho_a = 0;
+    }
+    const int ih_a = ho_a * p.stride - p.pad;
+
+    // per-lane output columns
+    int fbase[TN], ooff[TN];
+    bool okc[TN];
+#pragma unroll
+    for (int ni = 0; ni < TN; ++ni) {
+        const int jn = wn0 + ni * 32 + li;
+        int img_l, pix;
+        bool ok;
+        if (!p.multi) {
+            img_l = 0; pix = p0 + jn; ok = pix < p.HoWo;
+        } else {
+            img_l = jn / p.HoWo; pix = jn - img_l * p.HoWo;
+            ok = jn < p.BN_eff && r0 + img_l < p.R;
+        }
+        if (!ok) { img_l = 0; pix = p0; }
+        const int ho = pix / p.Wo, wo = pix - ho * p.Wo;
+        fbase[ni] = img_l * CB * p.PLANE + (ho - ho_a) * p.stride * p.PW + p.LPAD - p.pad +
+                    wo * p.stride + lh * (CB / 2) * p.PLANE;
+        ooff[ni] = img_l * p.Co * p.HoWo + pix;
+        okc[ni] = ok;
+    }
+
+    // patch copy slots of this lane (same positions for every channel chunk)
+    int goff[MAXSLOT], loff[MAXSLOT], cch[MAXSLOT];
+#pragma unroll
+    for (int e = 0; e < MAXSLOT; ++e) {
+        const int idx = tid + e * NT;
+        const int xv = idx % p.XV;
+        const int t1 = idx / p.XV;
+        const int prow = t1 % p.PH;
+        const int t2 = t1 / p.PH;
+        const int c = t2 % CB;
+        const int img_l = t2 / CB;
+        const int ih = ih_a + prow;
+        const bool act = idx < p.patch_slots && r0 + img_l < p.R && ih >= 0 && ih < p.H;
+        goff[e] = act ? img_l * p.img_g + (c * p.H + ih) * p.W + xv * VEC : -1;
+        loff[e] = img_l * CB * p.PLANE + c * p.PLANE + prow * p.PW + p.LPAD + xv * VEC;
+        cch[e] = c;
+    }
+
+    for (int i = tid; i < p.patch_floats; i += NT) patch[i] = 0.0f;
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+
+    const float *xbase = p.x + (long long)r0 * p.img_g;
+    const int ch0 = split * p.per_split;
+    int ch1 = ch0 + p.per_split;
+    if (ch1 > p.n_chunks) ch1 = p.n_chunks;
+
+    f32x4 pst[MAXSLOT];
+    f32x4 wst[WSLOT];
+
+    // Issue the global loads of one channel chunk into registers.
+#define DK_PATCH_FETCH(CH)                                                                       \
+    {                                                                                            \
+        const int ci0_ = (CH) * CB;                                                              \
+        const float *src_ = xbase + (long long)ci0_ * p.H * p.W;                                 \
+        _Pragma("unroll") for (int e = 0; e < MAXSLOT; ++e) {                                    \
+            const bool ok_ = goff[e] >= 0 && ci0_ + cch[e] < p.Ci;                               \
+            const float *s_ = src_ + (ok_ ? goff[e] : 0);                                        \
+            if constexpr (VEC == 4) {                                                            \
+                f32x4 v_ = {0.f, 0.f, 0.f, 0.f};                                                 \
+                if (ok_) v_ = *reinterpret_cast<const f32x4 *>(s_);                              \
+                pst[e] = v_;                                                                     \
+            } else {                                                                             \
+                float v_ = 0.0f;                                                                 \
+                if (ok_) v_ = *s_;                                                               \
+                pst[e] = f32x4{v_, 0.f, 0.f, 0.f};                                               \
+            }                                                                                    \
+        }                                                                                        \
+        const float *wsrc_ = p.wp + (long long)(CH) * WROWS * p.Co_pad + co0;                    \
+        _Pragma("unroll") for (int e = 0; e < WSLOT; ++e) {                                      \
+            int idx_ = tid + e * NT;                                                             \
+            if (idx_ >= W4) idx_ = W4 - 1;                                                       \
+            const int row_ = idx_ / (BM / 4), c4_ = idx_ % (BM / 4);                             \
+            wst[e] = *reinterpret_cast<const f32x4 *>(wsrc_ + (long long)row_ * p.Co_pad + c4_ * 4); \
+        }                                                                                        \
+    }
+
+    if (ch0 < ch1) DK_PATCH_FETCH(ch0)
+    for (int ch = ch0; ch < ch1; ++ch) {
+        __syncthreads();            // previous chunk fully consumed (and the zero fill done)
+#pragma unroll
+        for (int e = 0; e < MAXSLOT; ++e) {
+            if (goff[e] < 0) continue;
+            if constexpr (VEC == 4)
+                *reinterpret_cast<f32x4 *>(patch + loff[e]) = pst[e];
+            else
+                patch[loff[e]] = pst[e].x;
+        }
+#pragma unroll
+        for (int e = 0; e < WSLOT; ++e) {
+            const int idx = tid + e * NT;
+            const int row = idx / (BM / 4), c4 = idx % (BM / 4);
+            if (idx < W4) *reinterpret_cast<f32x4 *>(As + row * LDA + c4 * 4) = wst[e];
+        }
+        __syncthreads();
+        if (ch + 1 < ch1) DK_PATCH_FETCH(ch + 1)   // in flight during the MFMA loop
+
+        const float *a_s = As + lh * LDA + wm0 + li;
+#pragma unroll
+        for (int cp = 0; cp < CB / 2; ++cp)
+#pragma unroll
+            for (int a = 0; a < KH; ++a) {
+                const int soff = cp * p.PLANE + a * p.PW;      // wave-uniform
+                const float *pb[TN];
+#pragma unroll
+                for (int ni = 0; ni < TN; ++ni) pb[ni] = patch + fbase[ni] + soff;
+#pragma unroll
+                for (int b = 0; b < KW; ++b) {
+                    const int s = (cp * KH + a) * KW + b;
+                    float av[TM], bv[TN];
+#pragma unroll
+                    for (int mi = 0; mi < TM; ++mi) av[mi] = a_s[2 * s * LDA + mi * 32];
+#pragma unroll
+                    for (int ni = 0; ni < TN; ++ni) bv[ni] = pb[ni][b];
+#pragma unroll
+                    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+                        for (int ni = 0; ni < TN; ++ni)
+                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
+                }
+            }
+    }
+
+#undef DK_PATCH_FETCH
+
+    float *dst = (p.splits > 1 ? p.part + (long long)split * p.out_elems : p.out) +
+                 (long long)r0 * p.Co * p.HoWo;
+#pragma unroll
+    for (int ni = 0; ni < TN; ++ni) {
+        if (!okc[ni]) continue;
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = co0 + wm0 + mi * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
+                if (row < p.Co) dst[(long long)row * p.HoWo + ooff[ni]] = acc[mi][ni][v];
+            }
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int KH, int KW, int CB>
+struct PatchCfg {
+    static constexpr int bm = BM, bn = BN, cb = CB, kh = KH, kw = KW;
+    static constexpr int NT = 64 * WM * WN;
+    static constexpr int MAXSLOT4 = 4, MAXSLOT1 = 12;
+
+    static dk_status launch(const dk_patch_params &p, int vec, size_t lds_bytes, hipStream_t st)
+    {
+        const long long blocks = (long long)p.tiles_m * p.tiles_n * p.splits;
+        DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
+        if (vec == 4)
+            conv_patch_fwd_kernel<BM, BN, WM, WN, KH, KW, CB, 4, MAXSLOT4>
+                <<<dim3((unsigned)blocks), dim3(NT), lds_bytes, st>>>(p);
+        else
+            conv_patch_fwd_kernel<BM, BN, WM, WN, KH, KW, CB, 1, MAXSLOT1>
+                <<<dim3((unsigned)blocks), dim3(NT), lds_bytes, st>>>(p);
+        return dk_launch_status();
+    }
+};
+
+using P3Flat = PatchCfg<64, 256, 1, 4, 3, 3, 8>;
+using P3Sq = PatchCfg<128, 128, 2, 2, 3, 3, 8>;
+
+inline int round_up(int v, int a) { return (v + a - 1) / a * a; }
+
+// Tile geometry for one configuration; returns false if the layer does not
+// fit this kernel family (the caller then uses the generic implicit GEMM).
+template <class C>
+bool plan_cfg(const dk_geom &g, long long R, bool x_aligned16, dk_patch_plan *pl)
+{
+    dk_patch_params &p = pl->p;
+    p = dk_patch_params();
+    if (g.kh != C::kh || g.kw != C::kw || g.stride > 2) return false;
+    const int HoWo = g.Ho * g.Wo;
+    p.Ci = g.Ci; p.Co = g.Co; p.H = g.H; p.W = g.W; p.stride = g.stride; p.pad = g.pad;
+    p.Ho = g.Ho; p.Wo = g.Wo; p.HoWo = HoWo; p.R = (int)R;
+    p.img_g = (int)g.n;
+    int n_img, rows_spanned;
+    if (HoWo >= C::bn) {
+        p.multi = 0; p.IPT = 1; p.BN_eff = C::bn;
+        p.tiles_per_img = (HoWo + C::bn - 1) / C::bn;
+        p.tiles_n = (int)(R * p.tiles_per_img);
+        n_img = 1;
+        rows_spanned = (C::bn - 1) / g.Wo + 2;
+        if (rows_spanned > g.Ho) rows_spanned = g.Ho;
+    } else {
+        p.multi = 1; p.IPT = C::bn / HoWo; p.BN_eff = p.IPT * HoWo;
+        p.tiles_per_img = 0;
+        p.tiles_n = (int)((R + p.IPT - 1) / p.IPT);
+        n_img = p.IPT;
+        rows_spanned = g.Ho;
+        if ((long long)p.IPT * g.n >= (1ll << 30)) return false;
+    }
+    p.tiles_m = (g.Co + C::bm - 1) / C::bm;
+    p.Co_pad = p.tiles_m * C::bm;
+    p.LPAD = round_up(g.pad > 4 ? g.pad : 4, 4);
+    p.PH = (rows_spanned - 1) * g.stride + C::kh;
+    p.PW = round_up(p.LPAD + g.W + g.pad, 4);
+    p.PLANE = p.PH * p.PW;
+    p.patch_floats = round_up(n_img * C::cb * p.PLANE, 4);
+    pl->vec = (g.W % 4 == 0 && x_aligned16) ? 4 : 1;
+    p.XV = g.W / pl->vec;
+    p.patch_slots = n_img * C::cb * p.PH * p.XV;
+    const int maxslot = pl->vec == 4 ? C::MAXSLOT4 : C::MAXSLOT1;
+    if ((p.patch_slots + C::NT - 1) / C::NT > maxslot) return false;
+    pl->lds_bytes = (size_t)(p.patch_floats + C::cb * C::kh * C::kw * (C::bm + 4)) * sizeof(float);
+    if (pl->lds_bytes > 64 * 1024) return false;
+    p.n_chunks = (g.Ci + C::cb - 1) / C::cb;
+    const dk_split_plan sp = dk_plan_split((long long)p.tiles_m * p.tiles_n, p.n_chunks, R * g.m);
+    p.splits = sp.splits;
+    p.per_split = sp.ktiles_per_split;
+    p.out_elems = R * g.m;
+    pl->wp_floats = (size_t)p.n_chunks * C::cb * C::kh * C::kw * p.Co_pad;
+    pl->part_bytes = p.splits > 1 ? (size_t)p.splits * p.out_elems * sizeof(float) : 0;
+    pl->cb = C::cb;
+    return true;
+}
+
+} // namespace
+
+bool dk_patch_fwd_plan(const dk_geom &g, long long R, bool x_aligned16, dk_patch_plan *pl)
+{
+    if (!g.conv || R < 1) return false;
+    if (g.kh == 3 && g.kw == 3) {
+        pl->flat = g.Co <= 64;
+        return pl->flat ? plan_cfg<P3Flat>(g, R, x_aligned16, pl) : plan_cfg<P3Sq>(g, R, x_aligned16, pl);
+    }
+    return false;
+}
+
+__global__ __launch_bounds__(256) void dk_patch_splitk_reduce(const float *__restrict__ part,
+                                                              float *__restrict__ out,
+                                                              long long out_elems, int splits)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= out_elems) return;
+    float s = 0.0f;
+    for (int k = 0; k < splits; ++k) s += part[(long long)k * out_elems + i];
+    out[i] = s;
+}
+
+dk_status dk_patch_fwd_run(const dk_geom &g, dk_patch_plan &pl, const float *W, const float *xbar,
+                           float *ybar, float *ws, hipStream_t st)
+{
+    dk_patch_params &p = pl.p;
+    float *wp = ws;
+    float *part = (float *)((char *)ws + dk_patch_wp_bytes(pl));
+    const long long total = (long long)pl.wp_floats;
+    pack_filters_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
+        W, wp, g.Ci, g.Co, g.kh, g.kw, pl.cb, p.Co_pad, total);
+    DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+    p.x = xbar; p.wp = wp; p.out = ybar; p.part = part;
+    dk_status s = pl.flat ? P3Flat::launch(p, pl.vec, pl.lds_bytes, st)
+                          : P3Sq::launch(p, pl.vec, pl.lds_bytes, st);
+    if (s != DK_OK) return s;
+    if (p.splits > 1) {
+        dk_patch_splitk_reduce<<<dim3((unsigned)((p.out_elems + 255) / 256)), dim3(256), 0, st>>>(
+            part, ybar, p.out_elems, p.splits);
+        return dk_launch_status();
+    }
+    return DK_OK;
+}

@@ -172,19 +172,23 @@ __global__ __launch_bounds__(MIX_THREADS) void verify_partial_kernel(
     }
 }
 
-// Integrity check, second pass: one lane per group folds the partial pairs in
-// a fixed order and takes the verdict.
+// Integrity check, second pass: one wave per group folds the (at most 64)
+// partial pairs -- lane c holds chunk c -- and lane 0 takes the verdict.
 __global__ __launch_bounds__(MIX_THREADS) void verify_final_kernel(
     const float *__restrict__ part, int chunks, float tol, int *__restrict__ verdict,
     float *__restrict__ resid, int G)
 {
-    const int g = blockIdx.x * MIX_THREADS + threadIdx.x;
+    const int g = blockIdx.x * (MIX_THREADS / 64) + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
     if (g >= G) return;
     float tmax = 0.0f, smax = 0.0f;
-    for (int c = 0; c < chunks; ++c) {
+    for (int c = lane; c < chunks; c += 64) {
         tmax = fmaxf(tmax, part[((long long)g * chunks + c) * 2 + 0]);
         smax = fmaxf(smax, part[((long long)g * chunks + c) * 2 + 1]);
     }
+    tmax = wave_max(tmax);
+    smax = wave_max(smax);
+    if (lane != 0) return;
     const bool bad = !(tmax <= 3.402823466e+38f);
     const float rho = bad ? __builtin_inff() : (smax > 0.0f ? tmax / smax : 0.0f);
     verdict[g] = (bad || rho > tol) ? 1 : 0;
@@ -275,7 +279,7 @@ dk_status launch_verify_k(const float *ybar, const float *nvec, float tol, int *
         verify_partial_kernel<K, 1><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
             ybar, nvec, part, len, p.nvec, p.chunks, p.span);
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
-    verify_final_kernel<<<dim3((G + MIX_THREADS - 1) / MIX_THREADS), dim3(MIX_THREADS), 0, st>>>(
+    verify_final_kernel<<<dim3((G + MIX_THREADS / 64 - 1) / (MIX_THREADS / 64)), dim3(MIX_THREADS), 0, st>>>(
         part, p.chunks, tol, verdict, resid, G);
     return dk_launch_status();
 }

@@ -1,0 +1,44 @@
+// Interface between the convolution entry points and the LDS-patch
+// convolution kernels (internal).
+#pragma once
+#include "dk_internal.h"
+
+struct dk_patch_params {
+    const float *x;     // encoded images [R][Ci][H][W]
+    const float *wp;    // repacked filters [chunk][CB*KH*KW][Co_pad]
+    float *out;         // ybar [R][Co][Ho][Wo]
+    float *part;        // split-K partial sums [splits][out_elems]
+    int Ci, Co, H, W, stride, pad, Ho, Wo, HoWo, R;
+    int img_g;          // Ci*H*W
+    int multi;          // 0: a tile is BN pixels of one image; 1: IPT whole images
+    int IPT, BN_eff, tiles_per_img;
+    int PH, PW, PLANE, LPAD;      // patch rows, row pitch, plane size, left pad (floats)
+    int patch_floats;             // LDS floats of the patch region
+    int patch_slots, XV;          // vectors to copy per chunk, vectors per image row
+    int n_chunks, per_split, splits, Co_pad;
+    int tiles_m, tiles_n;
+    long long out_elems;
+};
+
+struct dk_patch_plan {
+    dk_patch_params p;
+    int vec;            // 4: 16-byte copies, 1: scalar copies
+    int cb;             // input channels per chunk
+    bool flat;          // 64-row tile (Co <= 64) or 128-row tile
+    size_t lds_bytes;
+    size_t wp_floats;
+    size_t part_bytes;
+};
+
+static inline size_t dk_patch_wp_bytes(const dk_patch_plan &pl)
+{
+    return (pl.wp_floats * sizeof(float) + 255) / 256 * 256;
+}
+
+// Fills the plan and returns true if the layer is covered by a patch kernel.
+bool dk_patch_fwd_plan(const dk_geom &g, long long R, bool x_aligned16, dk_patch_plan *pl);
+
+// Repack the filters, run the kernel (and the split-K fold if any).  ws must
+// hold dk_patch_wp_bytes(pl) + pl.part_bytes.
+dk_status dk_patch_fwd_run(const dk_geom &g, dk_patch_plan &pl, const float *W, const float *xbar,
+                           float *ybar, float *ws, hipStream_t st);
