@@ -570,15 +570,20 @@ size_t dk_ws_fwd_bytes(const dk_geom &g, long long R)
 
 size_t dk_ws_wgrad_bytes(const dk_geom &g, long long R)
 {
-    // mixed gradients dtilde[R][m] first, then the split-K partial sums
-    size_t b = align_up((size_t)R * g.m * sizeof(float), 256);
+    // mixed gradients dtilde[R][m] first, then the partial sums
+    size_t part;
     if (!g.conv)
-        b += split_bytes<CfgSq>(g.M, g.N, R, (long long)g.M * g.N);
+        part = split_bytes<CfgSq>(g.M, g.N, R, (long long)g.M * g.N);
     else if (conv_flat(g))
-        b += split_bytes<CfgWg64>(g.Co, g.Kg, R * g.Ho * g.Wo, g.Co * g.Kg);
+        part = split_bytes<CfgWg64>(g.Co, g.Kg, R * g.Ho * g.Wo, g.Co * g.Kg);
     else
-        b += split_bytes<CfgSq>(g.Co, g.Kg, R * g.Ho * g.Wo, g.Co * g.Kg);
-    return b;
+        part = split_bytes<CfgSq>(g.Co, g.Kg, R * g.Ho * g.Wo, g.Co * g.Kg);
+    if (g.conv) {
+        dk_wgpatch_plan pl;
+        for (int aligned = 0; aligned < 2; ++aligned)
+            if (dk_patch_wgrad_plan(g, R, aligned != 0, &pl) && pl.part_bytes > part) part = pl.part_bytes;
+    }
+    return align_up((size_t)R * g.m * sizeof(float), 256) + part;
 }
 
 DK_EXPORT dk_status dk_linear_fwd(const float *W, const float *xbar, float *ybar, int M, int N, int R,
@@ -657,6 +662,11 @@ DK_EXPORT dk_status dk_wgrad(const dk_layer *L, const float *delta, const float 
                                              part, part_bytes, st);
         return run_dense_tn<CfgSq, false>(dtilde, xbar, dW, g.M, g.N, (int)R, scale, accumulate,
                                           part, part_bytes, st);
+    }
+    dk_wgpatch_plan pl;
+    if (dk_patch_wgrad_plan(g, R, dk_aligned(xbar, 16), &pl)) {
+        DK_REQUIRE(part_bytes >= pl.part_bytes, DK_ERR_WORKSPACE);
+        return dk_patch_wgrad_run(g, pl, dtilde, xbar, dW, scale, accumulate, part, st);
     }
     if (conv_flat(g))
         return run_conv_wgrad<CfgWg64>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);

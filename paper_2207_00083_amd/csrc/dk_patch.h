@@ -42,3 +42,34 @@ bool dk_patch_fwd_plan(const dk_geom &g, long long R, bool x_aligned16, dk_patch
 // hold dk_patch_wp_bytes(pl) + pl.part_bytes.
 dk_status dk_patch_fwd_run(const dk_geom &g, dk_patch_plan &pl, const float *W, const float *xbar,
                            float *ybar, float *ws, hipStream_t st);
+
+// ---- weight gradient with the input patch in LDS ----
+
+struct dk_wgpatch_params {
+    const float *dt;    // mixed gradients dtilde [R][Co][Ho][Wo]
+    const float *x;     // encoded images [R][Ci][H][W]
+    float *part;        // partial sums [splits][KH*KW][Co][Ci]
+    int Ci, Co, H, W, stride, pad, Ho, Wo, HoWo, R;
+    int NI, TR;         // a pixel tile is NI images x TR output rows
+    int row_blocks, n_ptiles, per_split, splits;
+    int PH, PW, PLANE, CPLANE, LPAD;   // patch rows, pitch, per-image plane, per-channel plane
+    int LDQ, QT;        // dtilde tile pitch (odd) and pixels per tile
+    int DV, XV, d_slots, p_slots;
+    int ad_floats, lds_floats;
+    int tiles_co, tiles_ci;
+    long long part_elems;
+};
+
+struct dk_wgpatch_plan {
+    dk_wgpatch_params p;
+    int vec;
+    size_t lds_bytes;
+    size_t part_bytes;
+};
+
+bool dk_patch_wgrad_plan(const dk_geom &g, long long R, bool aligned16, dk_wgpatch_plan *pl);
+
+// part must hold pl.part_bytes.
+dk_status dk_patch_wgrad_run(const dk_geom &g, dk_wgpatch_plan &pl, const float *dtilde,
+                             const float *xbar, float *dW, float scale, int accumulate,
+                             float *part, hipStream_t st);
