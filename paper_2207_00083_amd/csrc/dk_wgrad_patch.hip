@@ -142,16 +142,29 @@ __global__ __launch_bounds__(256) void conv_patch_wgrad_kernel(dk_wgpatch_params
 #pragma unroll
                 for (int a = 0; a < KH; ++a) b_row[a] = b_ptr + a * p.PW;
                 const int npair = p.Wo >> 1;
-#pragma unroll 4
+                // operands of pixel pair cp+1 are fetched while pair cp is in the
+                // MFMA pipe (the last pair re-reads itself instead of running past the row)
+                float av = a_ptr[0], bv[KK];
+#pragma unroll
+                for (int a = 0; a < KH; ++a)
+#pragma unroll
+                    for (int b = 0; b < KW; ++b) bv[a * KW + b] = b_row[a][b];
                 for (int cp = 0; cp < npair; ++cp) {
-                    const float av = a_ptr[2 * cp];
+                    const int cn = cp + 1 < npair ? cp + 1 : cp;
+                    const float av_n = a_ptr[2 * cn];
+                    float bv_n[KK];
 #pragma unroll
                     for (int a = 0; a < KH; ++a)
 #pragma unroll
-                        for (int b = 0; b < KW; ++b) {
-                            const float bv = b_row[a][2 * cp * STRIDE + b];
-                            acc[a * KW + b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[a * KW + b], 0, 0, 0);
-                        }
+                        for (int b = 0; b < KW; ++b) bv_n[a * KW + b] = b_row[a][2 * cn * STRIDE + b];
+                    __builtin_amdgcn_sched_barrier(0);     // keep the LDS reads ahead of the MFMAs
+#pragma unroll
+                    for (int k = 0; k < KK; ++k)
+                        acc[k] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[k], acc[k], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    av = av_n;
+#pragma unroll
+                    for (int k = 0; k < KK; ++k) bv[k] = bv_n[k];
                 }
             }
     }
@@ -171,16 +184,35 @@ __global__ __launch_bounds__(256) void conv_patch_wgrad_kernel(dk_wgpatch_params
     }
 }
 
-// dW[co][ci][tap] = (accumulate ? dW : 0) + scale * sum_s part[s][tap][co][ci]
+// dW[co][ci][tap] = (accumulate ? dW : 0) + scale * sum_s part[s][tap][co][ci].
+// A workgroup folds 64 consecutive elements; its four 64-lane waves each sum
+// every fourth slice (loads batched eight deep) and the four sub-sums are
+// added in wave order, so the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void wgrad_fold_kernel(const float *__restrict__ part,
                                                          float *__restrict__ dW, int Co, int Ci,
                                                          int KK, long long part_elems, int splits,
                                                          float scale, int accumulate)
 {
-    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= part_elems) return;
+    __shared__ float red[4][64];
+    const int io = threadIdx.x & 63, sg = threadIdx.x >> 6;
+    const long long i = (long long)blockIdx.x * 64 + io;
     float s = 0.0f;
-    for (int k = 0; k < splits; ++k) s += part[(long long)k * part_elems + i];
+    if (i < part_elems) {
+        const float *src = part + i;
+        int k = sg;
+        for (; k + 28 < splits; k += 32) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = src[(long long)(k + 4 * u) * part_elems];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; k < splits; k += 4) s += src[(long long)k * part_elems];
+    }
+    red[sg][io] = s;
+    __syncthreads();
+    if (sg != 0 || i >= part_elems) return;
+    s = ((red[0][io] + red[1][io]) + red[2][io]) + red[3][io];
     const int ci = (int)(i % Ci);
     const long long t = i / Ci;
     const int co = (int)(t % Co);
@@ -294,7 +326,7 @@ dk_status dk_patch_wgrad_run(const dk_geom &g, dk_wgpatch_plan &pl, const float 
     p.dt = dtilde; p.x = xbar; p.part = part;
     dk_status s = launch_k<3, 3>(p, pl.vec, pl.lds_bytes, st);
     if (s != DK_OK) return s;
-    wgrad_fold_kernel<<<dim3((unsigned)((p.part_elems + 255) / 256)), dim3(256), 0, st>>>(
+    wgrad_fold_kernel<<<dim3((unsigned)((p.part_elems + 63) / 64)), dim3(256), 0, st>>>(
         part, dW, g.Co, g.Ci, g.kh * g.kw, p.part_elems, p.splits, scale, accumulate);
     return dk_launch_status();
 }
