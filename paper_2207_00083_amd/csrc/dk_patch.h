@@ -55,7 +55,7 @@ struct dk_wgpatch_params {
     int PH, PW, PLANE, CPLANE, LPAD;   // patch rows, pitch, per-image plane, per-channel plane
     int LDQ, QT;        // dtilde tile pitch (odd) and pixels per tile
     int DV, XV, d_slots, p_slots;
-    int ad_floats, lds_floats;
+    int ad_floats, buf_floats;   // dtilde tile floats; one LDS buffer (tile + patch) floats
     int tiles_co, tiles_ci;
     long long part_elems;
 };
@@ -63,6 +63,7 @@ struct dk_wgpatch_params {
 struct dk_wgpatch_plan {
     dk_wgpatch_params p;
     int vec;
+    bool quad;          // 16-byte LDS reads (stride 1, output width a multiple of 8)
     size_t lds_bytes;
     size_t part_bytes;
 };

@@ -25,18 +25,19 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 template <int KH, int KW, int STRIDE, int VEC, int DSLOT, int PSLOT>
-__global__ __launch_bounds__(256) void conv_patch_wgrad_kernel(dk_wgpatch_params p)
+__global__ __launch_bounds__(512) void conv_patch_wgrad_kernel(dk_wgpatch_params p)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    constexpr int NT = 256, BM = 64, BCI = 64, KK = KH * KW;
+    constexpr int NP = 256, BM = 64, BCI = 64, KK = KH * KW;
+    using stage_t = typename std::conditional<VEC == 4, f32x4, float>::type;
 
-    float *const Ad = lds;                       // [BM][LDQ]   dtilde tile
-    float *const Pt = lds + p.ad_floats;         // [BCI][CPLANE] input patch
-
+    // Two LDS buffers of [dtilde tile: BM x LDQ][input patch: BCI x CPLANE].
+    // Waves 0-3 (one per SIMD) only run MFMAs on the current buffer; waves 4-7
+    // only copy the next pixel tile from global memory into the other buffer.
+    // One barrier per tile hands the buffers over.
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int li = lane & 31, lh = lane >> 5;
-    const int wm0 = (wave & 1) * 32, wn0 = (wave >> 1) * 32;
+    const int wave = tid >> 6;
+    const bool producer = wave >= 4;
 
     const int tiles = p.tiles_co * p.tiles_ci;
     const int split = blockIdx.x / tiles;
@@ -44,39 +45,98 @@ __global__ __launch_bounds__(256) void conv_patch_wgrad_kernel(dk_wgpatch_params
     const int tci = t / p.tiles_co, tco = t - tci * p.tiles_co;
     const int co0 = tco * BM, ci0 = tci * BCI;
 
-    // copy slots of this lane (tile-independent parts)
-    int d_g[DSLOT], d_l[DSLOT], d_img[DSLOT], d_q[DSLOT];
+    const int pt0 = split * p.per_split;
+    int pt1 = pt0 + p.per_split;
+    if (pt1 > p.n_ptiles) pt1 = p.n_ptiles;
+
+    for (int i = tid; i < 2 * p.buf_floats; i += 512) lds[i] = 0.0f;
+    __syncthreads();
+
+    if (producer) {
+        const int ptid = tid - 256;
+        // copy slots of this lane: tile-independent global / LDS offsets and a
+        // packed (image-in-tile | position << 8), or -1 for an unused slot
+        unsigned d_g[DSLOT];
+        int d_l[DSLOT], d_m[DSLOT];
 #pragma unroll
-    for (int e = 0; e < DSLOT; ++e) {
-        const int idx = tid + e * NT;
-        const int dv = idx % p.DV;
-        const int t1 = idx / p.DV;
-        const int img_l = t1 % p.NI;
-        const int co_l = t1 / p.NI;
-        const bool act = idx < p.d_slots && co0 + co_l < p.Co;
-        d_g[e] = (img_l * p.Co + co_l) * p.HoWo + dv * VEC;
-        d_l[e] = co_l * p.LDQ + img_l * p.TR * p.Wo + dv * VEC;
-        d_img[e] = act ? img_l : -1;
-        d_q[e] = dv * VEC;                       // pixel offset inside the row block
-    }
-    int p_g[PSLOT], p_l[PSLOT], p_img[PSLOT], p_row[PSLOT];
+        for (int e = 0; e < DSLOT; ++e) {
+            const int idx = ptid + e * NP;
+            const int dv = idx % p.DV;
+            const int t1 = idx / p.DV;
+            const int img_l = t1 % p.NI;
+            const int co_l = t1 / p.NI;
+            const bool act = idx < p.d_slots && co0 + co_l < p.Co;
+            d_g[e] = (unsigned)((img_l * p.Co + co_l) * p.HoWo + dv * VEC);
+            d_l[e] = co_l * p.LDQ + img_l * p.TR * p.Wo + dv * VEC;
+            d_m[e] = act ? (img_l | (dv * VEC) << 8) : -1;
+        }
+        int p_g[PSLOT], p_l[PSLOT], p_m[PSLOT];
 #pragma unroll
-    for (int e = 0; e < PSLOT; ++e) {
-        const int idx = tid + e * NT;
-        const int xv = idx % p.XV;
-        const int t1 = idx / p.XV;
-        const int prow = t1 % p.PH;
-        const int t2 = t1 / p.PH;
-        const int img_l = t2 % p.NI;
-        const int c_l = t2 / p.NI;
-        const bool act = idx < p.p_slots && ci0 + c_l < p.Ci;
-        p_g[e] = (img_l * p.Ci + c_l) * p.H * p.W + prow * p.W + xv * VEC;
-        p_l[e] = c_l * p.CPLANE + img_l * p.PLANE + prow * p.PW + p.LPAD + xv * VEC;
-        p_img[e] = act ? img_l : -1;
-        p_row[e] = prow;
+        for (int e = 0; e < PSLOT; ++e) {
+            const int idx = ptid + e * NP;
+            const int xv = idx % p.XV;
+            const int t1 = idx / p.XV;
+            const int prow = t1 % p.PH;
+            const int t2 = t1 / p.PH;
+            const int img_l = t2 % p.NI;
+            const int c_l = t2 / p.NI;
+            const bool act = idx < p.p_slots && ci0 + c_l < p.Ci;
+            p_g[e] = (img_l * p.Ci + c_l) * p.H * p.W + prow * p.W + xv * VEC;
+            p_l[e] = p.ad_floats + c_l * p.CPLANE + img_l * p.PLANE + prow * p.PW + p.LPAD + xv * VEC;
+            p_m[e] = act ? (img_l | prow << 8) : -1;
+        }
+
+        // tile pt goes to buffer (pt - pt0) & 1; the copy of tile pt+1 overlaps
+        // the MFMA waves' work on tile pt
+        for (int pt = pt0; pt < pt1; ++pt) {
+            float *buf = lds + ((pt - pt0) & 1) * p.buf_floats;
+            const int ig = pt / p.row_blocks;
+            const int rb = pt - ig * p.row_blocks;
+            const int r0 = ig * p.NI, row0 = rb * p.TR;
+            const int qlim = p.HoWo - row0 * p.Wo;   // pixels left in the image from row0
+            const int ilim = p.R - r0;               // images left
+            const float *dsrc = p.dt + ((long long)r0 * p.Co + co0) * p.HoWo + (long long)row0 * p.Wo;
+            const int ih_a = row0 * STRIDE - p.pad;
+            const float *psrc = p.x + ((long long)r0 * p.Ci + ci0) * p.H * p.W;
+            const int poff = ih_a * p.W;
+            // every load goes to uniform base + 32-bit lane offset; a slot that is
+            // out of range for this tile reads offset 0 and is written as zero
+            stage_t dst_[DSLOT], pst_[PSLOT];
+            bool dok[DSLOT], pok[PSLOT];
+#pragma unroll
+            for (int e = 0; e < DSLOT; ++e) {
+                dok[e] = d_m[e] >= 0 && (d_m[e] & 255) < ilim && (d_m[e] >> 8) < qlim;
+                dst_[e] = *reinterpret_cast<const stage_t *>(dsrc + (dok[e] ? d_g[e] : 0u));
+            }
+#pragma unroll
+            for (int e = 0; e < PSLOT; ++e) {
+                const int ih = ih_a + (p_m[e] >> 8);
+                pok[e] = p_m[e] >= 0 && (p_m[e] & 255) < ilim && ih >= 0 && ih < p.H;
+                pst_[e] = *reinterpret_cast<const stage_t *>(psrc + (pok[e] ? (unsigned)(p_g[e] + poff) : 0u));
+            }
+#pragma unroll
+            for (int e = 0; e < DSLOT; ++e) {
+                if (d_m[e] < 0) continue;
+                float *d = buf + d_l[e];
+                const stage_t v = dok[e] ? dst_[e] : stage_t(0.0f);
+                if constexpr (VEC == 4) { d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w; }
+                else d[0] = v;
+            }
+#pragma unroll
+            for (int e = 0; e < PSLOT; ++e) {
+                if (p_m[e] < 0) continue;
+                *reinterpret_cast<stage_t *>(buf + p_l[e]) = pok[e] ? pst_[e] : stage_t(0.0f);
+            }
+            __syncthreads();     // tile pt is in LDS; tile pt-1 has been consumed
+        }
+        if (pt0 < pt1) __syncthreads();   // matches the MFMA waves' last barrier
+        return;
     }
 
-    for (int i = tid; i < p.lds_floats; i += NT) lds[i] = 0.0f;
+    // ---- MFMA waves ----
+    const int lane = tid & 63;
+    const int li = lane & 31, lh = lane >> 5;
+    const int wm0 = (wave & 1) * 32, wn0 = (wave >> 1) * 32;
 
     f32x16 acc[KK];
 #pragma unroll
@@ -84,93 +144,270 @@ __global__ __launch_bounds__(256) void conv_patch_wgrad_kernel(dk_wgpatch_params
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[k][v] = 0.0f;
 
+    const int nrows = p.NI * p.TR;
+    const int npair = p.Wo >> 1;
+    const int total = nrows * npair;      // pixel pairs per tile
+    if (pt0 < pt1) __syncthreads();       // tile pt0 is in LDS
+    for (int pt = pt0; pt < pt1; ++pt) {
+        const float *Ad = lds + ((pt - pt0) & 1) * p.buf_floats;
+        const float *Pt = Ad + p.ad_floats;
+        const float *a_base = Ad + (wm0 + li) * p.LDQ + lh;
+        const float *b_base = Pt + (wn0 + li) * p.CPLANE + p.LPAD - p.pad + lh * STRIDE;
+
+        // Load cursor: walks the tile's pixel pairs (row by row) one step ahead
+        // of the MFMAs.  Past the last pair it stays on the last one.
+        int ld_row = 0, ld_cp = 0;
+        const float *a_ld = a_base, *b_ld[KH];
+#pragma unroll
+        for (int a = 0; a < KH; ++a) b_ld[a] = b_base + a * p.PW;
+#define DK_WG_ADVANCE()                                                                          \
+        if (ld_cp + 1 < npair) {                                                                 \
+            ++ld_cp;                                                                             \
+        } else if (ld_row + 1 < nrows) {                                                         \
+            ld_cp = 0; ++ld_row;                                                                 \
+            const int img_l_ = ld_row / p.TR, row_ = ld_row - img_l_ * p.TR;                     \
+            a_ld = a_base + ld_row * p.Wo;                                                       \
+            _Pragma("unroll") for (int a = 0; a < KH; ++a)                                       \
+                b_ld[a] = b_base + img_l_ * p.PLANE + (row_ * STRIDE + a) * p.PW;                \
+        }
+        // Operands of the next pixel pair are read from LDS while the current
+        // pair is in the MFMA pipe: the reads are spread between the MFMAs, and
+        // two register sets alternate so nothing is copied.
+#define DK_WG_STEP(AVN, BVN, AVC, BVC)                                                           \
+        {                                                                                        \
+            AVN = a_ld[2 * ld_cp];                                                               \
+            _Pragma("unroll") for (int a = 0; a < KH; ++a)                                       \
+                _Pragma("unroll") for (int b = 0; b < KW; ++b)                                   \
+                    BVN[a * KW + b] = b_ld[a][2 * ld_cp * STRIDE + b];                           \
+            _Pragma("unroll") for (int k = 0; k < KK; ++k)                                       \
+                acc[k] = __builtin_amdgcn_mfma_f32_32x32x2f32(AVC, BVC[k], acc[k], 0, 0, 0);     \
+            _Pragma("unroll") for (int k = 0; k < KK; ++k) {                                     \
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   /* one MFMA  */             \
+                __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);   /* one VALU  */             \
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   /* one LDS read */          \
+            }                                                                                    \
+            __builtin_amdgcn_sched_barrier(0);                                                   \
+            /* keep the consumed operand registers live to here: a register that an MFMA */     \
+            /* in flight still reads must not be the target of the interleaved LDS reads */     \
+            asm volatile("" ::"v"(AVC));                                                         \
+            _Pragma("unroll") for (int k = 0; k < KK; ++k) asm volatile("" ::"v"(BVC[k]));       \
+        }
+        float av0, bv0[KK], av1, bv1[KK];
+        av0 = a_ld[0];
+#pragma unroll
+        for (int a = 0; a < KH; ++a)
+#pragma unroll
+            for (int b = 0; b < KW; ++b) bv0[a * KW + b] = b_ld[a][b];
+        __builtin_amdgcn_sched_barrier(0);
+        int f = 0;
+        for (; f + 2 <= total; f += 2) {
+            DK_WG_ADVANCE()
+            DK_WG_STEP(av1, bv1, av0, bv0)
+            DK_WG_ADVANCE()
+            DK_WG_STEP(av0, bv0, av1, bv1)
+        }
+        if (f < total) {                     // odd number of pairs in the tile
+#pragma unroll
+            for (int k = 0; k < KK; ++k)
+                acc[k] = __builtin_amdgcn_mfma_f32_32x32x2f32(av0, bv0[k], acc[k], 0, 0, 0);
+        }
+#undef DK_WG_ADVANCE
+#undef DK_WG_STEP
+        __syncthreads();     // done with this buffer; the next tile is in the other one
+    }
+
+    // partial sums: part[split][tap][co][ci], lanes along ci
+    float *dstp = p.part + (long long)split * p.part_elems;
+    const int ci = ci0 + wn0 + li;
+    if (ci < p.Ci) {
+#pragma unroll
+        for (int k = 0; k < KK; ++k)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int co = co0 + wm0 + 8 * (v / 4) + 4 * lh + (v % 4);
+                if (co < p.Co) dstp[((long long)k * p.Co + co) * p.Ci + ci] = acc[k][v];
+            }
+    }
+}
+
+// Same contraction for stride 1 and output widths that are a multiple of 8,
+// with 16-byte LDS reads.  Handing single floats from LDS to the matrix pipe
+// costs one LDS instruction per operand and those, not the MFMAs, then set the
+// pace.  Here the two half-waves take the left and the right half of an output
+// row instead of even and odd pixels, so four consecutive pixels of a half are
+// one aligned 16-byte read of dtilde, and the three filter columns of those four
+// pixels lie in two aligned 16-byte reads of the patch row (the patch is stored
+// with `pad` columns of left border, which puts output pixel wo over patch
+// columns wo..wo+2).  Seven LDS instructions feed 36 MFMAs.
+template <int DSLOT, int PSLOT>
+__global__ __launch_bounds__(512) void conv_quad_wgrad_kernel(dk_wgpatch_params p)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    constexpr int NP = 256, BM = 64, BCI = 64, KH = 3, KW = 3, KK = 9;
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const bool producer = wave >= 4;
+
+    const int tiles = p.tiles_co * p.tiles_ci;
+    const int split = blockIdx.x / tiles;
+    const int t = blockIdx.x - split * tiles;
+    const int tci = t / p.tiles_co, tco = t - tci * p.tiles_co;
+    const int co0 = tco * BM, ci0 = tci * BCI;
+
     const int pt0 = split * p.per_split;
     int pt1 = pt0 + p.per_split;
     if (pt1 > p.n_ptiles) pt1 = p.n_ptiles;
 
-    using stage_t = typename std::conditional<VEC == 4, f32x4, float>::type;
-    stage_t dst_[DSLOT], pst_[PSLOT];
+    for (int i = tid; i < 2 * p.buf_floats; i += 512) lds[i] = 0.0f;
+    __syncthreads();
 
-#define DK_WG_FETCH(PT)                                                                          \
-    {                                                                                            \
-        const int ig_ = (PT) / p.row_blocks;                                                     \
-        const int rb_ = (PT) - ig_ * p.row_blocks;                                               \
-        const int r0_ = ig_ * p.NI, row0_ = rb_ * p.TR;                                          \
-        const int qlim_ = p.HoWo - row0_ * p.Wo; /* pixels left in the image from row0 */        \
-        const float *dsrc_ = p.dt + ((long long)r0_ * p.Co + co0) * p.HoWo + (long long)row0_ * p.Wo; \
-        _Pragma("unroll") for (int e = 0; e < DSLOT; ++e) {                                      \
-            const bool ok_ = d_img[e] >= 0 && r0_ + d_img[e] < p.R && d_q[e] < qlim_;            \
-            stage_t v_ = stage_t(0.0f);                                                          \
-            if (ok_) v_ = *reinterpret_cast<const stage_t *>(dsrc_ + d_g[e]);                    \
-            dst_[e] = v_;                                                                        \
-        }                                                                                        \
-        const int ih_a_ = row0_ * STRIDE - p.pad;                                                \
-        const long long pbase_ = ((long long)r0_ * p.Ci + ci0) * p.H * p.W + (long long)ih_a_ * p.W; \
-        _Pragma("unroll") for (int e = 0; e < PSLOT; ++e) {                                      \
-            const int ih_ = ih_a_ + p_row[e];                                                    \
-            const bool ok_ = p_img[e] >= 0 && r0_ + p_img[e] < p.R && ih_ >= 0 && ih_ < p.H;     \
-            stage_t v_ = stage_t(0.0f);                                                          \
-            if (ok_) v_ = *reinterpret_cast<const stage_t *>(p.x + pbase_ + p_g[e]);             \
-            pst_[e] = v_;                                                                        \
-        }                                                                                        \
-    }
-
-    if (pt0 < pt1) DK_WG_FETCH(pt0)
-    for (int pt = pt0; pt < pt1; ++pt) {
-        __syncthreads();                 // previous tile consumed (and the zero fill done)
+    if (producer) {
+        const int ptid = tid - 256;
+        unsigned d_g[DSLOT];
+        int d_l[DSLOT], d_m[DSLOT];
 #pragma unroll
         for (int e = 0; e < DSLOT; ++e) {
-            if (d_img[e] < 0) continue;
-            float *d = Ad + d_l[e];
-            if constexpr (VEC == 4) { d[0] = dst_[e].x; d[1] = dst_[e].y; d[2] = dst_[e].z; d[3] = dst_[e].w; }
-            else d[0] = dst_[e];
+            const int idx = ptid + e * NP;
+            const int dv = idx % p.DV;
+            const int t1 = idx / p.DV;
+            const int img_l = t1 % p.NI;
+            const int co_l = t1 / p.NI;
+            const bool act = idx < p.d_slots && co0 + co_l < p.Co;
+            d_g[e] = (unsigned)((img_l * p.Co + co_l) * p.HoWo + dv * 4);
+            d_l[e] = co_l * p.LDQ + img_l * p.TR * p.Wo + dv * 4;
+            d_m[e] = act ? (img_l | (dv * 4) << 8) : -1;
         }
+        int p_g[PSLOT], p_l[PSLOT], p_m[PSLOT];
 #pragma unroll
         for (int e = 0; e < PSLOT; ++e) {
-            if (p_img[e] < 0) continue;
-            *reinterpret_cast<stage_t *>(Pt + p_l[e]) = pst_[e];
+            const int idx = ptid + e * NP;
+            const int xv = idx % p.XV;
+            const int t1 = idx / p.XV;
+            const int prow = t1 % p.PH;
+            const int t2 = t1 / p.PH;
+            const int img_l = t2 % p.NI;
+            const int c_l = t2 / p.NI;
+            const bool act = idx < p.p_slots && ci0 + c_l < p.Ci;
+            p_g[e] = (img_l * p.Ci + c_l) * p.H * p.W + prow * p.W + xv * 4;
+            p_l[e] = p.ad_floats + c_l * p.CPLANE + img_l * p.PLANE + prow * p.PW + p.LPAD + xv * 4;
+            p_m[e] = act ? (img_l | prow << 8) : -1;
         }
-        __syncthreads();
-        if (pt + 1 < pt1) DK_WG_FETCH(pt + 1)   // in flight during the MFMA loop
-
-        for (int img_l = 0; img_l < p.NI; ++img_l)
-            for (int row = 0; row < p.TR; ++row) {
-                const float *a_ptr = Ad + (wm0 + li) * p.LDQ + (img_l * p.TR + row) * p.Wo + lh;
-                const float *b_ptr = Pt + (wn0 + li) * p.CPLANE + img_l * p.PLANE +
-                                     row * STRIDE * p.PW + p.LPAD - p.pad + lh * STRIDE;
-                const float *b_row[KH];
+        for (int pt = pt0; pt < pt1; ++pt) {
+            float *buf = lds + ((pt - pt0) & 1) * p.buf_floats;
+            const int ig = pt / p.row_blocks;
+            const int rb = pt - ig * p.row_blocks;
+            const int r0 = ig * p.NI, row0 = rb * p.TR;
+            const int qlim = p.HoWo - row0 * p.Wo;
+            const int ilim = p.R - r0;
+            const float *dsrc = p.dt + ((long long)r0 * p.Co + co0) * p.HoWo + (long long)row0 * p.Wo;
+            const int ih_a = row0 - p.pad;
+            const float *psrc = p.x + ((long long)r0 * p.Ci + ci0) * p.H * p.W;
+            const int poff = ih_a * p.W;
+            f32x4 dst_[DSLOT], pst_[PSLOT];
+            bool dok[DSLOT], pok[PSLOT];
 #pragma unroll
-                for (int a = 0; a < KH; ++a) b_row[a] = b_ptr + a * p.PW;
-                const int npair = p.Wo >> 1;
-                // operands of pixel pair cp+1 are fetched while pair cp is in the
-                // MFMA pipe (the last pair re-reads itself instead of running past the row)
-                float av = a_ptr[0], bv[KK];
-#pragma unroll
-                for (int a = 0; a < KH; ++a)
-#pragma unroll
-                    for (int b = 0; b < KW; ++b) bv[a * KW + b] = b_row[a][b];
-                for (int cp = 0; cp < npair; ++cp) {
-                    const int cn = cp + 1 < npair ? cp + 1 : cp;
-                    const float av_n = a_ptr[2 * cn];
-                    float bv_n[KK];
-#pragma unroll
-                    for (int a = 0; a < KH; ++a)
-#pragma unroll
-                        for (int b = 0; b < KW; ++b) bv_n[a * KW + b] = b_row[a][2 * cn * STRIDE + b];
-                    __builtin_amdgcn_sched_barrier(0);     // keep the LDS reads ahead of the MFMAs
-#pragma unroll
-                    for (int k = 0; k < KK; ++k)
-                        acc[k] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[k], acc[k], 0, 0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                    av = av_n;
-#pragma unroll
-                    for (int k = 0; k < KK; ++k) bv[k] = bv_n[k];
-                }
+            for (int e = 0; e < DSLOT; ++e) {
+                dok[e] = d_m[e] >= 0 && (d_m[e] & 255) < ilim && (d_m[e] >> 8) < qlim;
+                dst_[e] = *reinterpret_cast<const f32x4 *>(dsrc + (dok[e] ? d_g[e] : 0u));
             }
+#pragma unroll
+            for (int e = 0; e < PSLOT; ++e) {
+                const int ih = ih_a + (p_m[e] >> 8);
+                pok[e] = p_m[e] >= 0 && (p_m[e] & 255) < ilim && ih >= 0 && ih < p.H;
+                pst_[e] = *reinterpret_cast<const f32x4 *>(psrc + (pok[e] ? (unsigned)(p_g[e] + poff) : 0u));
+            }
+#pragma unroll
+            for (int e = 0; e < DSLOT; ++e) {
+                if (d_m[e] < 0) continue;
+                *reinterpret_cast<f32x4 *>(buf + d_l[e]) = dok[e] ? dst_[e] : f32x4(0.0f);
+            }
+#pragma unroll
+            for (int e = 0; e < PSLOT; ++e) {
+                if (p_m[e] < 0) continue;
+                const f32x4 v = pok[e] ? pst_[e] : f32x4(0.0f);
+                float *d = buf + p_l[e];          // one column off 16-byte alignment
+                d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+            }
+            __syncthreads();
+        }
+        if (pt0 < pt1) __syncthreads();
+        return;
     }
-#undef DK_WG_FETCH
 
-    // partial sums: part[split][tap][co][ci], lanes along ci
+    // ---- MFMA waves ----
+    const int lane = tid & 63;
+    const int li = lane & 31, lh = lane >> 5;
+    const int wm0 = (wave & 1) * 32, wn0 = (wave >> 1) * 32;
+    const int half = p.Wo >> 1;              // pixels per half-row (multiple of 4)
+
+    f32x16 acc[KK];
+#pragma unroll
+    for (int k = 0; k < KK; ++k)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[k][v] = 0.0f;
+
+    const int nrows = p.NI * p.TR;
+    const int nquad = half >> 2;             // 4-pixel steps per row
+    const int total = nrows * nquad;
+    if (pt0 < pt1) __syncthreads();
+    for (int pt = pt0; pt < pt1; ++pt) {
+        const float *Ad = lds + ((pt - pt0) & 1) * p.buf_floats;
+        const float *Pt = Ad + p.ad_floats;
+        const float *a_base = Ad + (wm0 + li) * p.LDQ + lh * half;
+        const float *b_base = Pt + (wn0 + li) * p.CPLANE + lh * half;
+
+        // load cursor, one 4-pixel step ahead of the MFMAs; it stays on the
+        // last step of the tile once it gets there
+        int ld_row = 0, ld_q = 0;
+        const float *a_ld = a_base, *b_ld = b_base;
+#define DK_WGQ_ADVANCE()                                                                         \
+        if (ld_q + 1 < nquad) {                                                                  \
+            ++ld_q;                                                                              \
+        } else if (ld_row + 1 < nrows) {                                                         \
+            ld_q = 0; ++ld_row;                                                                  \
+            const int img_l_ = ld_row / p.TR, row_ = ld_row - img_l_ * p.TR;                     \
+            a_ld = a_base + ld_row * p.Wo;                                                       \
+            b_ld = b_base + img_l_ * p.PLANE + row_ * p.PW;                                      \
+        }
+#define DK_WGQ_LOAD(A, B)                                                                        \
+        {                                                                                        \
+            A = *reinterpret_cast<const f32x4 *>(a_ld + 4 * ld_q);                               \
+            _Pragma("unroll") for (int a = 0; a < KH; ++a) {                                     \
+                B[2 * a] = *reinterpret_cast<const f32x4 *>(b_ld + a * p.PW + 4 * ld_q);         \
+                B[2 * a + 1] = *reinterpret_cast<const f32x4 *>(b_ld + a * p.PW + 4 * ld_q + 4); \
+            }                                                                                    \
+            __builtin_amdgcn_sched_barrier(0);   /* the reads go out before the MFMAs */         \
+        }
+#define DK_WGQ_MMA(A, B)                                                                         \
+        {                                                                                        \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i)                                        \
+                _Pragma("unroll") for (int a = 0; a < KH; ++a)                                   \
+                    _Pragma("unroll") for (int b = 0; b < KW; ++b) {                             \
+                        const int c = i + b;                                                     \
+                        const float bv = c < 4 ? B[2 * a][c] : B[2 * a + 1][c - 4];              \
+                        acc[a * KW + b] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[i], bv, acc[a * KW + b], 0, 0, 0); \
+                    }                                                                            \
+            __builtin_amdgcn_sched_barrier(0);                                                   \
+        }
+        f32x4 A0, A1, B0[2 * KH], B1[2 * KH];
+        DK_WGQ_LOAD(A0, B0)
+        int f = 0;
+        for (; f + 2 <= total; f += 2) {
+            DK_WGQ_ADVANCE()
+            DK_WGQ_LOAD(A1, B1)
+            DK_WGQ_MMA(A0, B0)
+            DK_WGQ_ADVANCE()
+            DK_WGQ_LOAD(A0, B0)
+            DK_WGQ_MMA(A1, B1)
+        }
+        if (f < total) DK_WGQ_MMA(A0, B0)    // odd number of steps in the tile
+#undef DK_WGQ_ADVANCE
+#undef DK_WGQ_LOAD
+#undef DK_WGQ_MMA
+        __syncthreads();
+    }
+
     float *dstp = p.part + (long long)split * p.part_elems;
     const int ci = ci0 + wn0 + li;
     if (ci < p.Ci) {
@@ -225,23 +462,35 @@ __global__ __launch_bounds__(256) void wgrad_fold_kernel(const float *__restrict
 
 inline int round_up(int v, int a) { return (v + a - 1) / a * a; }
 
-constexpr int DSLOT4 = 4, PSLOT4 = 8, DSLOT1 = 8, PSLOT1 = 24;
-constexpr size_t LDS_LIMIT = 64 * 1024;
+constexpr int DSLOT4 = 6, PSLOT4 = 10, DSLOT1 = 8, PSLOT1 = 24, DSLOTQ = 6, PSLOTQ = 10;
+constexpr size_t LDS_LIMIT = 150 * 1024;     // of the 160 KB a compute unit has
+
+template <class KernelT>
+dk_status launch_one(KernelT kernel, const dk_wgpatch_params &p, size_t lds_bytes, hipStream_t st)
+{
+    // more than 64 KB of dynamic LDS has to be allowed per kernel, once per process
+    static bool allowed = false;
+    if (!allowed) {
+        DK_REQUIRE(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)LDS_LIMIT) == hipSuccess, DK_ERR_HIP);
+        allowed = true;
+    }
+    const long long blocks = (long long)p.tiles_co * p.tiles_ci * p.splits;
+    DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
+    kernel<<<dim3((unsigned)blocks), dim3(512), lds_bytes, st>>>(p);
+    return dk_launch_status();
+}
 
 template <int KH, int KW>
 dk_status launch_k(const dk_wgpatch_params &p, int vec, size_t lds_bytes, hipStream_t st)
 {
-    const long long blocks = (long long)p.tiles_co * p.tiles_ci * p.splits;
-    DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
-    const dim3 grid((unsigned)blocks), blk(256);
     if (p.stride == 1) {
-        if (vec == 4) conv_patch_wgrad_kernel<KH, KW, 1, 4, DSLOT4, PSLOT4><<<grid, blk, lds_bytes, st>>>(p);
-        else conv_patch_wgrad_kernel<KH, KW, 1, 1, DSLOT1, PSLOT1><<<grid, blk, lds_bytes, st>>>(p);
-    } else {
-        if (vec == 4) conv_patch_wgrad_kernel<KH, KW, 2, 4, DSLOT4, PSLOT4><<<grid, blk, lds_bytes, st>>>(p);
-        else conv_patch_wgrad_kernel<KH, KW, 2, 1, DSLOT1, PSLOT1><<<grid, blk, lds_bytes, st>>>(p);
+        if (vec == 4) return launch_one(conv_patch_wgrad_kernel<KH, KW, 1, 4, DSLOT4, PSLOT4>, p, lds_bytes, st);
+        return launch_one(conv_patch_wgrad_kernel<KH, KW, 1, 1, DSLOT1, PSLOT1>, p, lds_bytes, st);
     }
-    return dk_launch_status();
+    if (vec == 4) return launch_one(conv_patch_wgrad_kernel<KH, KW, 2, 4, DSLOT4, PSLOT4>, p, lds_bytes, st);
+    return launch_one(conv_patch_wgrad_kernel<KH, KW, 2, 1, DSLOT1, PSLOT1>, p, lds_bytes, st);
 }
 
 } // namespace
@@ -258,13 +507,28 @@ bool dk_patch_wgrad_plan(const dk_geom &g, long long R, bool aligned16, dk_wgpat
     p.Ho = g.Ho; p.Wo = g.Wo; p.HoWo = HoWo; p.R = (int)R;
     if ((long long)g.Co * HoWo >= (1ll << 26) || g.n >= (1ll << 26)) return false;
     const bool v4 = aligned16 && g.W % 4 == 0 && g.Wo % 4 == 0;
+    // 16-byte LDS reads need stride 1, vector copies and half-rows of whole quads
+    const bool quad = v4 && g.stride == 1 && g.Wo % 8 == 0 && g.pad <= 4;
     pl->vec = v4 ? 4 : 1;
-    const int dmax = (v4 ? DSLOT4 : DSLOT1) * 256, pmax = (v4 ? PSLOT4 : PSLOT1) * 256;
-    p.LPAD = round_up(g.pad > 4 ? g.pad : 4, 4);
-    p.PW = round_up(p.LPAD + g.W + g.pad, 4);
+    pl->quad = quad;
+    const int dslot = quad ? DSLOTQ : (v4 ? DSLOT4 : DSLOT1);
+    const int pslot = quad ? PSLOTQ : (v4 ? PSLOT4 : PSLOT1);
+    const int dmax = dslot * 256, pmax = pslot * 256;
+    if (quad) {
+        p.LPAD = g.pad;
+        int pw = g.W + 2 * g.pad;
+        if (pw < g.Wo + 4) pw = g.Wo + 4;        // the second quad of the last step
+        p.PW = round_up(pw, 4);
+    } else {
+        p.LPAD = round_up(g.pad > 4 ? g.pad : 4, 4);
+        p.PW = round_up(p.LPAD + g.W + g.pad, 4);
+    }
+    // LDS pitches: odd for 4-byte reads, 4 mod 8 for 16-byte reads (both spread
+    // the 32 rows a half-wave touches over all banks)
+    auto pitch = [&](int n) { return quad ? (n % 8 == 0 ? n + 4 : n) : (n | 1); };
 
     // choose the pixel tile: as many output rows (then whole images) as the
-    // copy slots and 64 KB of LDS allow
+    // copy slots and the LDS allow
     int bestTR = 0, bestNI = 0;
     for (int pass = 0; pass < 2; ++pass) {
         // pass 0: row blocks of one image; pass 1: several whole images
@@ -272,16 +536,16 @@ bool dk_patch_wgrad_plan(const dk_geom &g, long long R, bool aligned16, dk_wgpat
             const int TR = pass == 0 ? cand : g.Ho;
             const int NI = pass == 0 ? 1 : cand;
             if (pass == 0 && TR > g.Ho) break;
-            if (pass == 1 && (NI < 2 || NI > R)) { if (NI > R) break; else continue; }
+            if (pass == 1 && (NI < 2 || NI > R || NI > 255)) { if (NI > R || NI > 255) break; else continue; }
             if (pass == 0 && v4 && (TR * g.Wo) % 4) continue;
             const int PH = (TR - 1) * g.stride + g.kh;
             const int PLANE = PH * p.PW;
-            const int CPLANE = (NI * PLANE) | 1;
+            const int CPLANE = pitch(NI * PLANE);
             const int QT = NI * TR * g.Wo;
-            const int LDQ = QT | 1;
+            const int LDQ = pitch(QT);
             const long long d_slots = 64ll * NI * (TR * g.Wo / pl->vec);
             const long long p_slots = 64ll * NI * PH * (g.W / pl->vec);
-            const size_t bytes = ((size_t)round_up(64 * LDQ, 4) + 64 * (size_t)CPLANE) * 4;
+            const size_t bytes = 2 * ((size_t)round_up(64 * LDQ, 4) + round_up(64 * CPLANE, 4)) * 4;
             if (d_slots > dmax || p_slots > pmax || bytes > LDS_LIMIT) break;
             if ((long long)NI * g.Co * HoWo >= (1ll << 30) || (long long)NI * g.n >= (1ll << 30)) break;
             bestTR = TR; bestNI = NI;
@@ -292,23 +556,23 @@ bool dk_patch_wgrad_plan(const dk_geom &g, long long R, bool aligned16, dk_wgpat
     p.TR = bestTR; p.NI = bestNI;
     p.PH = (p.TR - 1) * g.stride + g.kh;
     p.PLANE = p.PH * p.PW;
-    p.CPLANE = (p.NI * p.PLANE) | 1;
+    p.CPLANE = pitch(p.NI * p.PLANE);
     p.QT = p.NI * p.TR * g.Wo;
-    p.LDQ = p.QT | 1;
+    p.LDQ = pitch(p.QT);
     p.DV = p.TR * g.Wo / pl->vec;
     p.XV = g.W / pl->vec;
     p.d_slots = 64 * p.NI * p.DV;
     p.p_slots = 64 * p.NI * p.PH * p.XV;
     p.ad_floats = round_up(64 * p.LDQ, 4);
-    p.lds_floats = p.ad_floats + 64 * p.CPLANE;
-    pl->lds_bytes = (size_t)p.lds_floats * 4;
+    p.buf_floats = p.ad_floats + round_up(64 * p.CPLANE, 4);
+    pl->lds_bytes = 2 * (size_t)p.buf_floats * 4;
     p.row_blocks = (g.Ho + p.TR - 1) / p.TR;
     p.n_ptiles = (int)((R + p.NI - 1) / p.NI) * p.row_blocks;
     p.tiles_co = (g.Co + 63) / 64;
     p.tiles_ci = (g.Ci + 63) / 64;
     p.part_elems = (long long)g.kh * g.kw * g.Co * g.Ci;
-    // about two workgroups per compute unit; never more partial sums than 256 MB
-    long long s = 256 / ((long long)p.tiles_co * p.tiles_ci);   // one resident workgroup per compute unit
+    // one resident workgroup per compute unit; never more partial sums than 256 MB
+    long long s = 256 / ((long long)p.tiles_co * p.tiles_ci);
     if (s < 1) s = 1;
     if (s > p.n_ptiles) s = p.n_ptiles;
     while (s > 1 && s * p.part_elems * 4 > (256ll << 20)) --s;
@@ -324,7 +588,8 @@ dk_status dk_patch_wgrad_run(const dk_geom &g, dk_wgpatch_plan &pl, const float 
 {
     dk_wgpatch_params &p = pl.p;
     p.dt = dtilde; p.x = xbar; p.part = part;
-    dk_status s = launch_k<3, 3>(p, pl.vec, pl.lds_bytes, st);
+    dk_status s = pl.quad ? launch_one(conv_quad_wgrad_kernel<DSLOTQ, PSLOTQ>, p, pl.lds_bytes, st)
+                          : launch_k<3, 3>(p, pl.vec, pl.lds_bytes, st);
     if (s != DK_OK) return s;
     wgrad_fold_kernel<<<dim3((unsigned)((p.part_elems + 63) / 64)), dim3(256), 0, st>>>(
         part, dW, g.Co, g.Ci, g.kh * g.kw, p.part_elems, p.splits, scale, accumulate);
