@@ -147,6 +147,20 @@ dk_status dk_verify(const float *ybar, const float *nvec, float tol,
                     int *verdict, float *resid, int G, int K, long long m,
                     void *ws, size_t ws_bytes, void *stream);
 
+/* Optional per-kernel timing for benchmarks (not part of the method).  While
+ * enabled (on = 1 also clears earlier records) every kernel the library
+ * launches is bracketed by two HIP events on its launch stream; the library
+ * creates and keeps those events (up to 8192 launches are recorded, later ones
+ * are not timed).  Not thread-safe. */
+dk_status dk_profile_enable(int on);
+
+/* Waits for the recorded events and returns the number of distinct kernel
+ * labels; for 0 <= index < that number also writes the label (host buffer of
+ * name_cap bytes), its average launch duration in milliseconds and its launch
+ * count.  Any output pointer may be NULL. */
+int dk_profile_read(int index, char *name, int name_cap, double *avg_ms,
+                    int *launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -73,6 +73,8 @@ def load():
         "dk_wgrad": (ip, [LP, vp, vp, vp, vp, vp, ip, ip, fl, ip, vp, sz, vp]),
         "dk_decode": (ip, [vp, vp, vp, ip, ip, ll, vp]),
         "dk_verify": (ip, [vp, vp, fl, vp, vp, ip, ip, ll, vp, sz, vp]),
+        "dk_profile_enable": (ip, [ip]),
+        "dk_profile_read": (ip, [ip, C.c_char_p, ip, C.POINTER(C.c_double), C.POINTER(ip)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -284,3 +286,21 @@ def dk_verify(ybar, nvec, K, tol=1e-3, verdict=None, resid=None, ws=None, stream
     _check(load().dk_verify(_ptr(ybar), _ptr(nvec), float(tol), _ptr(verdict), _ptr(resid), G, K, m,
                             _ptr(ws), ws.numel(), _stream(stream)), "dk_verify")
     return verdict, resid
+
+
+def dk_profile_enable(on=True):
+    """Start (clearing old records) or stop per-kernel event timing."""
+    _check(load().dk_profile_enable(1 if on else 0), "dk_profile_enable")
+
+
+def dk_profile_read():
+    """{kernel label: (average launch ms, launches)} of the recorded launches."""
+    lib = load()
+    n = lib.dk_profile_read(-1, None, 0, None, None)
+    out = {}
+    for i in range(n):
+        name = C.create_string_buffer(128)
+        ms, cnt = C.c_double(0.0), C.c_int(0)
+        lib.dk_profile_read(i, name, 128, C.byref(ms), C.byref(cnt))
+        out[name.value.decode()] = (ms.value, cnt.value)
+    return out

@@ -434,7 +434,8 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 template <class C, class LA, class LB, class EP>
 dk_status run(const typename LA::Params &pa, const typename LB::Params &pb, const EP &ep,
               int rows, int cols, long long kdim, float alpha, int accumulate, float *out,
-              long long out_elems, float *part, size_t part_bytes, hipStream_t st)
+              long long out_elems, float *part, size_t part_bytes, hipStream_t st,
+              const char *label)
 {
     RunParams rp;
     rp.tiles_m = (rows + C::BM - 1) / C::BM;
@@ -452,9 +453,13 @@ dk_status run(const typename LA::Params &pa, const typename LB::Params &pb, cons
     DK_REQUIRE(tiles * rp.splits <= 0x7fffffffll, DK_ERR_SHAPE);
     if (rp.splits > 1)
         DK_REQUIRE(part && part_bytes >= (size_t)rp.splits * out_elems * sizeof(float), DK_ERR_WORKSPACE);
-    contract_kernel<C, LA, LB, EP><<<dim3((unsigned)(tiles * rp.splits)), dim3(C::NT), 0, st>>>(pa, pb, ep, rp);
+    {
+        dk_prof_scope ps(label, st);
+        contract_kernel<C, LA, LB, EP><<<dim3((unsigned)(tiles * rp.splits)), dim3(C::NT), 0, st>>>(pa, pb, ep, rp);
+    }
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
     if (rp.splits > 1) {
+        dk_prof_scope ps("splitk_reduce", st);
         splitk_reduce_kernel<<<dim3((unsigned)((out_elems + 255) / 256)), dim3(256), 0, st>>>(
             part, out, out_elems, rp.splits, alpha, accumulate);
         DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
@@ -500,7 +505,7 @@ dk_status run_dense_nt(const float *A, const float *B, float *Cout, int rows, in
     MatParams pa = {A, kdim, rows, kdim}, pb = {B, kdim, cols, kdim};
     EpiDense ep = {cols, rows, cols};
     return run<C, LA, LB, EpiDense>(pa, pb, ep, rows, cols, kdim, 1.0f, 0, Cout,
-                                    (long long)rows * cols, part, part_bytes, st);
+                                    (long long)rows * cols, part, part_bytes, st, "contract_dense_fwd");
 }
 
 template <class C, bool VEC>
@@ -512,7 +517,7 @@ dk_status run_dense_tn(const float *A, const float *B, float *Cout, int rows, in
     MatParams pa = {A, rows, rows, kdim}, pb = {B, cols, cols, kdim};
     EpiDense ep = {cols, rows, cols};
     return run<C, LA, LB, EpiDense>(pa, pb, ep, rows, cols, kdim, alpha, accumulate, Cout,
-                                    (long long)rows * cols, part, part_bytes, st);
+                                    (long long)rows * cols, part, part_bytes, st, "contract_dense_wgrad");
 }
 
 template <class C, bool VW>
@@ -525,7 +530,7 @@ dk_status run_conv_fwd(const dk_geom &g, const float *W, const float *xbar, floa
     MatParams pa = {W, g.Kg, g.Co, (int)g.Kg};
     EpiConvFwd ep = {g.Co, cp.Q, cp.HoWo, (long long)g.Co * cp.HoWo};
     return run<C, LA, LB, EpiConvFwd>(pa, cp, ep, g.Co, cp.Q, g.Kg, 1.0f, 0, ybar, R * g.m, part,
-                                      part_bytes, st);
+                                      part_bytes, st, "contract_conv_fwd_gather");
 }
 
 template <class C>
@@ -539,7 +544,7 @@ dk_status run_conv_wgrad(const dk_geom &g, const float *dtilde, const float *xba
     const ConvParams cb = conv_params(g, xbar, R);
     EpiDense ep = {g.Kg, g.Co, (int)g.Kg};
     return run<C, LA, LB, EpiDense>(ca, cb, ep, g.Co, (int)g.Kg, ca.Q, alpha, accumulate, dW,
-                                    (long long)g.Co * g.Kg, part, part_bytes, st);
+                                    (long long)g.Co * g.Kg, part, part_bytes, st, "contract_conv_wgrad_gather");
 }
 
 bool conv_flat(const dk_geom &g) { return g.Co <= 64; }

@@ -243,6 +243,7 @@ struct PatchCfg {
     {
         const long long blocks = (long long)p.tiles_m * p.tiles_n * p.splits;
         DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
+        dk_prof_scope ps("conv_patch_fwd", st);
         if (vec == 4)
             conv_patch_fwd_kernel<BM, BN, WM, WN, KH, KW, CB, 4, MAXSLOT4>
                 <<<dim3((unsigned)blocks), dim3(NT), lds_bytes, st>>>(p);
@@ -341,14 +342,18 @@ dk_status dk_patch_fwd_run(const dk_geom &g, dk_patch_plan &pl, const float *W, 
     float *wp = ws;
     float *part = (float *)((char *)ws + dk_patch_wp_bytes(pl));
     const long long total = (long long)pl.wp_floats;
-    pack_filters_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
+    {
+        dk_prof_scope ps("pack_filters", st);
+        pack_filters_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
         W, wp, g.Ci, g.Co, g.kh, g.kw, pl.cb, p.Co_pad, total);
+    }
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
     p.x = xbar; p.wp = wp; p.out = ybar; p.part = part;
     dk_status s = pl.flat ? P3Flat::launch(p, pl.vec, pl.lds_bytes, st)
                           : P3Sq::launch(p, pl.vec, pl.lds_bytes, st);
     if (s != DK_OK) return s;
     if (p.splits > 1) {
+        dk_prof_scope ps("splitk_reduce", st);
         dk_patch_splitk_reduce<<<dim3((unsigned)((p.out_elems + 255) / 256)), dim3(256), 0, st>>>(
             part, ybar, p.out_elems, p.splits);
         return dk_launch_status();

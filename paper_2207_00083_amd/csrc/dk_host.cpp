@@ -166,3 +166,67 @@ DK_EXPORT dk_status dk_coeffs(const float *A, const float *gamma, int G, int K,
         }
     return DK_OK;
 }
+
+// ---------------------------------------------------------------------------
+// Per-kernel timing for benchmarks.
+// ---------------------------------------------------------------------------
+namespace {
+constexpr int PROF_MAX = 8192;
+struct prof_state {
+    bool on = false;
+    int used = 0;
+    std::vector<hipEvent_t> ev;          // 2 per record, created on first use
+    std::vector<const char *> name;
+} g_prof;
+} // namespace
+
+dk_prof_scope::dk_prof_scope(const char *kernel, hipStream_t st_) : slot(-1), st(st_)
+{
+    if (!g_prof.on || g_prof.used >= PROF_MAX) return;
+    slot = g_prof.used++;
+    if ((int)g_prof.ev.size() < 2 * (slot + 1)) {
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { slot = -1; --g_prof.used; return; }
+        g_prof.ev.push_back(a);
+        g_prof.ev.push_back(b);
+        g_prof.name.push_back(kernel);
+    }
+    g_prof.name[slot] = kernel;
+    (void)hipEventRecord(g_prof.ev[2 * slot], st);
+}
+
+dk_prof_scope::~dk_prof_scope()
+{
+    if (slot >= 0) (void)hipEventRecord(g_prof.ev[2 * slot + 1], st);
+}
+
+DK_EXPORT dk_status dk_profile_enable(int on)
+{
+    if (on) g_prof.used = 0;
+    g_prof.on = on != 0;
+    return DK_OK;
+}
+
+DK_EXPORT int dk_profile_read(int index, char *name, int name_cap, double *avg_ms, int *launches)
+{
+    // aggregate by kernel label, in order of first appearance
+    std::vector<const char *> labels;
+    std::vector<double> sum;
+    std::vector<int> cnt;
+    for (int i = 0; i < g_prof.used; ++i) {
+        if (hipEventSynchronize(g_prof.ev[2 * i + 1]) != hipSuccess) continue;
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]) != hipSuccess) continue;
+        size_t k = 0;
+        while (k < labels.size() && strcmp(labels[k], g_prof.name[i]) != 0) ++k;
+        if (k == labels.size()) { labels.push_back(g_prof.name[i]); sum.push_back(0.0); cnt.push_back(0); }
+        sum[k] += ms;
+        cnt[k] += 1;
+    }
+    if (index >= 0 && index < (int)labels.size()) {
+        if (name && name_cap > 0) { strncpy(name, labels[index], name_cap - 1); name[name_cap - 1] = 0; }
+        if (avg_ms) *avg_ms = sum[index] / cnt[index];
+        if (launches) *launches = cnt[index];
+    }
+    return (int)labels.size();
+}

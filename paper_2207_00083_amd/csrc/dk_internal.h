@@ -49,3 +49,12 @@ dk_split_plan dk_plan_split(long long out_tiles, long long ktiles, long long out
 // kernels, used by dk_wgrad).
 dk_status dk_delta_mix(const float *delta, const float *B, const float *gamma, float *dtilde,
                        int G, int K, long long m, hipStream_t st);
+
+// Optional per-kernel timing (dk_profile_enable): while enabled, a scope object
+// brackets one kernel launch with two HIP events on the launch stream.
+struct dk_prof_scope {
+    dk_prof_scope(const char *kernel, hipStream_t st);
+    ~dk_prof_scope();
+    int slot;
+    hipStream_t st;
+};

@@ -236,6 +236,7 @@ dk_status launch_mix_k(const float *in0, const float *in1, const float *c0, cons
     const span_plan p = plan_span(len, v4 ? 4 : 1, G, 0);
     const long long blocks = (long long)G * p.chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
+    dk_prof_scope ps(MODE == MIX_ENCODE ? "encode" : (MODE == MIX_DECODE ? "decode" : "delta_mix"), st);
     if (v4)
         mix_kernel<MODE, K, 4><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
             in0, in1, c0, c1, out, len, p.nvec, p.chunks, p.span);
@@ -272,13 +273,17 @@ dk_status launch_verify_k(const float *ybar, const float *nvec, float tol, int *
     const span_plan p = plan_span(len, v4 ? 4 : 1, G, DK_VERIFY_MAX_BLOCKS);
     const long long blocks = (long long)G * p.chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
+    {
+    dk_prof_scope ps("verify_partial", st);
     if (v4)
         verify_partial_kernel<K, 4><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
             ybar, nvec, part, len, p.nvec, p.chunks, p.span);
     else
         verify_partial_kernel<K, 1><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
             ybar, nvec, part, len, p.nvec, p.chunks, p.span);
+    }
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+    dk_prof_scope ps("verify_final", st);
     verify_final_kernel<<<dim3((G + MIX_THREADS / 64 - 1) / (MIX_THREADS / 64)), dim3(MIX_THREADS), 0, st>>>(
         part, p.chunks, tol, verdict, resid, G);
     return dk_launch_status();

@@ -466,7 +466,8 @@ constexpr int DSLOT4 = 6, PSLOT4 = 10, DSLOT1 = 8, PSLOT1 = 24, DSLOTQ = 6, PSLO
 constexpr size_t LDS_LIMIT = 150 * 1024;     // of the 160 KB a compute unit has
 
 template <class KernelT>
-dk_status launch_one(KernelT kernel, const dk_wgpatch_params &p, size_t lds_bytes, hipStream_t st)
+dk_status launch_one(KernelT kernel, const dk_wgpatch_params &p, size_t lds_bytes, hipStream_t st,
+                     const char *label)
 {
     // more than 64 KB of dynamic LDS has to be allowed per kernel, once per process
     static bool allowed = false;
@@ -478,6 +479,7 @@ dk_status launch_one(KernelT kernel, const dk_wgpatch_params &p, size_t lds_byte
     }
     const long long blocks = (long long)p.tiles_co * p.tiles_ci * p.splits;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
+    dk_prof_scope ps(label, st);
     kernel<<<dim3((unsigned)blocks), dim3(512), lds_bytes, st>>>(p);
     return dk_launch_status();
 }
@@ -486,11 +488,11 @@ template <int KH, int KW>
 dk_status launch_k(const dk_wgpatch_params &p, int vec, size_t lds_bytes, hipStream_t st)
 {
     if (p.stride == 1) {
-        if (vec == 4) return launch_one(conv_patch_wgrad_kernel<KH, KW, 1, 4, DSLOT4, PSLOT4>, p, lds_bytes, st);
-        return launch_one(conv_patch_wgrad_kernel<KH, KW, 1, 1, DSLOT1, PSLOT1>, p, lds_bytes, st);
+        if (vec == 4) return launch_one(conv_patch_wgrad_kernel<KH, KW, 1, 4, DSLOT4, PSLOT4>, p, lds_bytes, st, "conv_patch_wgrad");
+        return launch_one(conv_patch_wgrad_kernel<KH, KW, 1, 1, DSLOT1, PSLOT1>, p, lds_bytes, st, "conv_patch_wgrad");
     }
-    if (vec == 4) return launch_one(conv_patch_wgrad_kernel<KH, KW, 2, 4, DSLOT4, PSLOT4>, p, lds_bytes, st);
-    return launch_one(conv_patch_wgrad_kernel<KH, KW, 2, 1, DSLOT1, PSLOT1>, p, lds_bytes, st);
+    if (vec == 4) return launch_one(conv_patch_wgrad_kernel<KH, KW, 2, 4, DSLOT4, PSLOT4>, p, lds_bytes, st, "conv_patch_wgrad");
+    return launch_one(conv_patch_wgrad_kernel<KH, KW, 2, 1, DSLOT1, PSLOT1>, p, lds_bytes, st, "conv_patch_wgrad");
 }
 
 } // namespace
@@ -588,9 +590,10 @@ dk_status dk_patch_wgrad_run(const dk_geom &g, dk_wgpatch_plan &pl, const float 
 {
     dk_wgpatch_params &p = pl.p;
     p.dt = dtilde; p.x = xbar; p.part = part;
-    dk_status s = pl.quad ? launch_one(conv_quad_wgrad_kernel<DSLOTQ, PSLOTQ>, p, pl.lds_bytes, st)
+    dk_status s = pl.quad ? launch_one(conv_quad_wgrad_kernel<DSLOTQ, PSLOTQ>, p, pl.lds_bytes, st, "conv_quad_wgrad")
                           : launch_k<3, 3>(p, pl.vec, pl.lds_bytes, st);
     if (s != DK_OK) return s;
+    dk_prof_scope ps("wgrad_fold", st);
     wgrad_fold_kernel<<<dim3((unsigned)((p.part_elems + 63) / 64)), dim3(256), 0, st>>>(
         part, dW, g.Co, g.Ci, g.kh * g.kw, p.part_elems, p.splits, scale, accumulate);
     return dk_launch_status();
