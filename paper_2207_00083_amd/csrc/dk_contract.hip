@@ -624,7 +624,7 @@ DK_EXPORT dk_status dk_conv_fwd(const dk_layer *L, const float *W, const float *
     DK_REQUIRE(dk_aligned(ws, 16), DK_ERR_ALIGN);
     hipStream_t st = (hipStream_t)stream;
     dk_patch_plan pl;
-    if (dk_patch_fwd_plan(g, R, dk_aligned(xbar, 16), &pl))
+    if (dk_patch_fwd_plan(g, R, dk_aligned(xbar, 16) && dk_aligned(ybar, 16), &pl))
         return dk_patch_fwd_run(g, pl, W, xbar, ybar, (float *)ws, st);
     const bool vw = (g.Kg % 4 == 0) && dk_aligned(W, 16);
     if (conv_flat(g))

@@ -233,6 +233,221 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_patch_fwd_kernel(dk_patch_p
     }
 }
 
+// Repack W[Co][Ci][3][3] -> wq[chunk][Co_pad][72], position h*36 + (c'*3 + a)*3 + b
+// holding channel chunk*8 + c' + 4h: per output channel, the 36 MFMA steps of
+// each half-wave are contiguous, so four steps are one 16-byte LDS read.
+__global__ __launch_bounds__(256) void pack_filters_quad_kernel(const float *__restrict__ W,
+                                                                float *__restrict__ wq, int Ci,
+                                                                int Co, int Co_pad, long long total)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int kk = (int)(i % 72);
+    const long long t = i / 72;
+    const int co = (int)(t % Co_pad);
+    const int chunk = (int)(t / Co_pad);
+    const int h = kk / 36, step = kk - h * 36;
+    const int b = step % 3, a = (step / 3) % 3, cp = step / 9;
+    const int ci = chunk * 8 + cp + 4 * h;
+    float v = 0.0f;
+    if (co < Co && ci < Ci) v = W[(((long long)co * Ci + ci) * 3 + a) * 3 + b];
+    wq[i] = v;
+}
+
+// 3x3 stride-1 forward with 16-byte LDS reads (image and output widths
+// multiples of 4).  A wave owns TM*32 output channels x 128 consecutive output
+// pixels as four 32-column MFMA blocks, block t taking the pixels = t (mod 4):
+// lane j then needs, for filter row a and the three filter columns, patch
+// columns 4j .. 4j+5 -- two aligned 16-byte reads that feed 3 steps x 4 blocks.
+// The filter tile is stored [co][step] so that four steps of a lane are one
+// 16-byte read too: about 0.2 LDS instructions per MFMA instead of one.
+template <int TM, int WM, int WN, int MAXSLOT>
+__global__ __launch_bounds__(64 * WM * WN) void conv_quad_fwd_kernel(dk_patch_params p)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    constexpr int NT = 64 * WM * WN, CB = 8, BM = WM * TM * 32, BN = WN * 128;
+    constexpr int WP = 76;                          // filter tile pitch: 72 steps + 4
+    constexpr int W4 = BM * 18;                     // 16-byte vectors in a filter tile
+    constexpr int WSLOT = (W4 + NT - 1) / NT;
+
+    float *const patch = lds;
+    float *const As = lds + p.patch_floats;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lh = lane >> 5;
+    const int wm0 = (wave % WM) * (TM * 32);
+    const int wn0 = (wave / WM) * 128;
+
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int split = blockIdx.x / tiles;
+    const int t = blockIdx.x - split * tiles;
+    const int tile_n = t / p.tiles_m, tile_m = t - tile_n * p.tiles_m;
+    const int co0 = tile_m * BM;
+
+    int r0, p0, ho_a;
+    if (!p.multi) {
+        r0 = tile_n / p.tiles_per_img;
+        p0 = (tile_n - r0 * p.tiles_per_img) * BN;
+        ho_a = p0 / p.Wo;
+    } else {
+        r0 = tile_n * p.IPT;
+        p0 = 0;
+        ho_a = 0;
+    }
+    const int ih_a = ho_a - p.pad;
+
+    // this lane's four pixels (one quad)
+    int fbase, ooff;
+    bool okc;
+    {
+        const int jn = wn0 + 4 * li;
+        int img_l, pix;
+        if (!p.multi) {
+            img_l = 0; pix = p0 + jn; okc = pix < p.HoWo;
+        } else {
+            img_l = jn / p.HoWo; pix = jn - img_l * p.HoWo;
+            okc = jn < p.BN_eff && r0 + img_l < p.R;
+        }
+        if (!okc) { img_l = 0; pix = p0; }
+        const int ho = pix / p.Wo, wo = pix - ho * p.Wo;
+        fbase = img_l * CB * p.PLANE + (ho - ho_a) * p.PW + wo + lh * (CB / 2) * p.PLANE;
+        ooff = img_l * p.Co * p.HoWo + pix;
+    }
+
+    int goff[MAXSLOT], loff[MAXSLOT], cch[MAXSLOT];
+#pragma unroll
+    for (int e = 0; e < MAXSLOT; ++e) {
+        const int idx = tid + e * NT;
+        const int xv = idx % p.XV;
+        const int t1 = idx / p.XV;
+        const int prow = t1 % p.PH;
+        const int t2 = t1 / p.PH;
+        const int c = t2 % CB;
+        const int img_l = t2 / CB;
+        const int ih = ih_a + prow;
+        const bool act = idx < p.patch_slots && r0 + img_l < p.R && ih >= 0 && ih < p.H;
+        goff[e] = act ? img_l * p.img_g + (c * p.H + ih) * p.W + xv * 4 : -1;
+        loff[e] = img_l * CB * p.PLANE + c * p.PLANE + prow * p.PW + p.LPAD + xv * 4;
+        cch[e] = c;
+    }
+
+    for (int i = tid; i < p.patch_floats; i += NT) patch[i] = 0.0f;
+
+    f32x16 acc[TM][4];
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+
+    const float *xbase = p.x + (long long)r0 * p.img_g;
+    const int ch0 = split * p.per_split;
+    int ch1 = ch0 + p.per_split;
+    if (ch1 > p.n_chunks) ch1 = p.n_chunks;
+
+    f32x4 pst[MAXSLOT];
+    f32x4 wst[WSLOT];
+
+#define DK_QUAD_FETCH(CH)                                                                        \
+    {                                                                                            \
+        const int ci0_ = (CH) * CB;                                                              \
+        const float *src_ = xbase + (long long)ci0_ * p.H * p.W;                                 \
+        _Pragma("unroll") for (int e = 0; e < MAXSLOT; ++e) {                                    \
+            const bool ok_ = goff[e] >= 0 && ci0_ + cch[e] < p.Ci;                               \
+            f32x4 v_ = {0.f, 0.f, 0.f, 0.f};                                                     \
+            if (ok_) v_ = *reinterpret_cast<const f32x4 *>(src_ + goff[e]);                      \
+            pst[e] = v_;                                                                         \
+        }                                                                                        \
+        const float *wsrc_ = p.wp + ((long long)(CH) * p.Co_pad + co0) * 72;                     \
+        _Pragma("unroll") for (int e = 0; e < WSLOT; ++e) {                                      \
+            int idx_ = tid + e * NT;                                                             \
+            if (idx_ >= W4) idx_ = W4 - 1;                                                       \
+            wst[e] = *reinterpret_cast<const f32x4 *>(wsrc_ + idx_ * 4);                         \
+        }                                                                                        \
+    }
+
+    if (ch0 < ch1) DK_QUAD_FETCH(ch0)
+    for (int ch = ch0; ch < ch1; ++ch) {
+        __syncthreads();            // previous chunk fully consumed (and the zero fill done)
+#pragma unroll
+        for (int e = 0; e < MAXSLOT; ++e) {
+            if (goff[e] < 0) continue;
+            float *d = patch + loff[e];          // `pad` columns off 16-byte alignment
+            d[0] = pst[e].x; d[1] = pst[e].y; d[2] = pst[e].z; d[3] = pst[e].w;
+        }
+#pragma unroll
+        for (int e = 0; e < WSLOT; ++e) {
+            const int idx = tid + e * NT;
+            const int row = idx / 18, c4 = idx - row * 18;
+            if (idx < W4) *reinterpret_cast<f32x4 *>(As + row * WP + c4 * 4) = wst[e];
+        }
+        __syncthreads();
+        if (ch + 1 < ch1) DK_QUAD_FETCH(ch + 1)   // in flight during the MFMA loop
+
+        const float *a_s = As + (wm0 + li) * WP + lh * 36;
+        const float *pb = patch + fbase;
+        f32x4 aq[TM];
+#pragma unroll
+        for (int cp = 0; cp < CB / 2; ++cp)
+#pragma unroll
+            for (int a = 0; a < 3; ++a) {
+                const float *pr = pb + cp * p.PLANE + a * p.PW;
+                const f32x4 w0 = *reinterpret_cast<const f32x4 *>(pr);
+                const f32x4 w1 = *reinterpret_cast<const f32x4 *>(pr + 4);
+                const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+#pragma unroll
+                for (int b = 0; b < 3; ++b) {
+                    const int s = (cp * 3 + a) * 3 + b;
+                    if (s % 4 == 0) {
+#pragma unroll
+                        for (int mi = 0; mi < TM; ++mi)
+                            aq[mi] = *reinterpret_cast<const f32x4 *>(a_s + mi * 32 * WP + s);
+                    }
+#pragma unroll
+                    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+                        for (int tt = 0; tt < 4; ++tt)
+                            acc[mi][tt] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[mi][s % 4], w[tt + b], acc[mi][tt], 0, 0, 0);
+                }
+            }
+    }
+#undef DK_QUAD_FETCH
+
+    if (!okc) return;
+    float *dst = (p.splits > 1 ? p.part + (long long)split * p.out_elems : p.out) +
+                 (long long)r0 * p.Co * p.HoWo + ooff;
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = co0 + wm0 + mi * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
+            if (row < p.Co)
+                *reinterpret_cast<f32x4 *>(dst + (long long)row * p.HoWo) =
+                    f32x4{acc[mi][0][v], acc[mi][1][v], acc[mi][2][v], acc[mi][3][v]};
+        }
+}
+
+template <int TM, int WM, int WN>
+struct QuadCfg {
+    static constexpr int bm = WM * TM * 32, bn = WN * 128, cb = 8;
+    static constexpr int NT = 64 * WM * WN;
+    static constexpr int MAXSLOT = 4;
+
+    static dk_status launch(const dk_patch_params &p, size_t lds_bytes, hipStream_t st)
+    {
+        const long long blocks = (long long)p.tiles_m * p.tiles_n * p.splits;
+        DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
+        dk_prof_scope ps("conv_quad_fwd", st);
+        conv_quad_fwd_kernel<TM, WM, WN, MAXSLOT><<<dim3((unsigned)blocks), dim3(NT), lds_bytes, st>>>(p);
+        return dk_launch_status();
+    }
+};
+
+using Q3Flat = QuadCfg<1, 2, 2>;     // 64 co x 256 px
+using Q3Sq = QuadCfg<2, 2, 2>;       // 128 co x 256 px
+
 template <int BM, int BN, int WM, int WN, int KH, int KW, int CB>
 struct PatchCfg {
     static constexpr int bm = BM, bn = BN, cb = CB, kh = KH, kw = KW;
@@ -277,7 +492,7 @@ bool plan_cfg(const dk_geom &g, long long R, bool x_aligned16, dk_patch_plan *pl
         p.tiles_per_img = (HoWo + C::bn - 1) / C::bn;
         p.tiles_n = (int)(R * p.tiles_per_img);
         n_img = 1;
-        rows_spanned = (C::bn - 1) / g.Wo + 2;
+        rows_spanned = C::bn % g.Wo == 0 ? C::bn / g.Wo : (C::bn - 1) / g.Wo + 2;
         if (rows_spanned > g.Ho) rows_spanned = g.Ho;
     } else {
         p.multi = 1; p.IPT = C::bn / HoWo; p.BN_eff = p.IPT * HoWo;
@@ -312,14 +527,71 @@ bool plan_cfg(const dk_geom &g, long long R, bool x_aligned16, dk_patch_plan *pl
     return true;
 }
 
+// Same for the 16-byte-read kernels (3x3, stride 1, widths multiples of 4).
+template <class C>
+bool plan_quad(const dk_geom &g, long long R, dk_patch_plan *pl)
+{
+    dk_patch_params &p = pl->p;
+    p = dk_patch_params();
+    if (g.kh != 3 || g.kw != 3 || g.stride != 1 || g.W % 4 || g.Wo % 4 || g.pad > 4) return false;
+    const int HoWo = g.Ho * g.Wo;
+    p.Ci = g.Ci; p.Co = g.Co; p.H = g.H; p.W = g.W; p.stride = 1; p.pad = g.pad;
+    p.Ho = g.Ho; p.Wo = g.Wo; p.HoWo = HoWo; p.R = (int)R;
+    p.img_g = (int)g.n;
+    int n_img, rows_spanned;
+    if (HoWo >= C::bn) {
+        p.multi = 0; p.IPT = 1; p.BN_eff = C::bn;
+        p.tiles_per_img = (HoWo + C::bn - 1) / C::bn;
+        p.tiles_n = (int)(R * p.tiles_per_img);
+        n_img = 1;
+        rows_spanned = C::bn % g.Wo == 0 ? C::bn / g.Wo : (C::bn - 1) / g.Wo + 2;
+        if (rows_spanned > g.Ho) rows_spanned = g.Ho;
+    } else {
+        p.multi = 1; p.IPT = C::bn / HoWo; p.BN_eff = p.IPT * HoWo;
+        p.tiles_per_img = 0;
+        p.tiles_n = (int)((R + p.IPT - 1) / p.IPT);
+        n_img = p.IPT;
+        rows_spanned = g.Ho;
+        if ((long long)p.IPT * g.n >= (1ll << 30)) return false;
+    }
+    p.tiles_m = (g.Co + C::bm - 1) / C::bm;
+    p.Co_pad = p.tiles_m * C::bm;
+    p.LPAD = g.pad;                      // output pixel wo sits over patch columns wo..wo+2
+    p.PH = rows_spanned - 1 + 3;
+    int pw = g.W + 2 * g.pad;
+    if (pw < g.Wo + 4) pw = g.Wo + 4;    // the second 16-byte read of the last quad
+    p.PW = round_up(pw, 4);
+    p.PLANE = p.PH * p.PW;
+    p.patch_floats = round_up(n_img * C::cb * p.PLANE, 4);
+    pl->vec = 4;
+    p.XV = g.W / 4;
+    p.patch_slots = n_img * C::cb * p.PH * p.XV;
+    if ((p.patch_slots + C::NT - 1) / C::NT > C::MAXSLOT) return false;
+    pl->lds_bytes = (size_t)(p.patch_floats + C::bm * 76) * sizeof(float);
+    if (pl->lds_bytes > 64 * 1024) return false;
+    p.n_chunks = (g.Ci + C::cb - 1) / C::cb;
+    const dk_split_plan sp = dk_plan_split((long long)p.tiles_m * p.tiles_n, p.n_chunks, R * g.m);
+    p.splits = sp.splits;
+    p.per_split = sp.ktiles_per_split;
+    p.out_elems = R * g.m;
+    pl->wp_floats = (size_t)p.n_chunks * 72 * p.Co_pad;
+    pl->part_bytes = p.splits > 1 ? (size_t)p.splits * p.out_elems * sizeof(float) : 0;
+    pl->cb = C::cb;
+    pl->quad = true;
+    return true;
+}
+
 } // namespace
 
-bool dk_patch_fwd_plan(const dk_geom &g, long long R, bool x_aligned16, dk_patch_plan *pl)
+bool dk_patch_fwd_plan(const dk_geom &g, long long R, bool aligned16, dk_patch_plan *pl)
 {
     if (!g.conv || R < 1) return false;
+    pl->quad = false;
     if (g.kh == 3 && g.kw == 3) {
         pl->flat = g.Co <= 64;
-        return pl->flat ? plan_cfg<P3Flat>(g, R, x_aligned16, pl) : plan_cfg<P3Sq>(g, R, x_aligned16, pl);
+        if (aligned16 && (pl->flat ? plan_quad<Q3Flat>(g, R, pl) : plan_quad<Q3Sq>(g, R, pl))) return true;
+        pl->quad = false;
+        return pl->flat ? plan_cfg<P3Flat>(g, R, aligned16, pl) : plan_cfg<P3Sq>(g, R, aligned16, pl);
     }
     return false;
 }
@@ -344,13 +616,20 @@ dk_status dk_patch_fwd_run(const dk_geom &g, dk_patch_plan &pl, const float *W, 
     const long long total = (long long)pl.wp_floats;
     {
         dk_prof_scope ps("pack_filters", st);
-        pack_filters_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
-        W, wp, g.Ci, g.Co, g.kh, g.kw, pl.cb, p.Co_pad, total);
+        if (pl.quad)
+            pack_filters_quad_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
+                W, wp, g.Ci, g.Co, p.Co_pad, total);
+        else
+            pack_filters_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
+                W, wp, g.Ci, g.Co, g.kh, g.kw, pl.cb, p.Co_pad, total);
     }
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
     p.x = xbar; p.wp = wp; p.out = ybar; p.part = part;
-    dk_status s = pl.flat ? P3Flat::launch(p, pl.vec, pl.lds_bytes, st)
-                          : P3Sq::launch(p, pl.vec, pl.lds_bytes, st);
+    dk_status s;
+    if (pl.quad)
+        s = pl.flat ? Q3Flat::launch(p, pl.lds_bytes, st) : Q3Sq::launch(p, pl.lds_bytes, st);
+    else
+        s = pl.flat ? P3Flat::launch(p, pl.vec, pl.lds_bytes, st) : P3Sq::launch(p, pl.vec, pl.lds_bytes, st);
     if (s != DK_OK) return s;
     if (p.splits > 1) {
         dk_prof_scope ps("splitk_reduce", st);

@@ -25,6 +25,7 @@ struct dk_patch_plan {
     int vec;            // 4: 16-byte copies, 1: scalar copies
     int cb;             // input channels per chunk
     bool flat;          // 64-row tile (Co <= 64) or 128-row tile
+    bool quad;          // 16-byte LDS reads (3x3, stride 1, widths multiples of 4)
     size_t lds_bytes;
     size_t wp_floats;
     size_t part_bytes;
@@ -36,7 +37,8 @@ static inline size_t dk_patch_wp_bytes(const dk_patch_plan &pl)
 }
 
 // Fills the plan and returns true if the layer is covered by a patch kernel.
-bool dk_patch_fwd_plan(const dk_geom &g, long long R, bool x_aligned16, dk_patch_plan *pl);
+// aligned16: xbar and ybar are both 16-byte aligned.
+bool dk_patch_fwd_plan(const dk_geom &g, long long R, bool aligned16, dk_patch_plan *pl);
 
 // Repack the filters, run the kernel (and the split-K fold if any).  ws must
 // hold dk_patch_wp_bytes(pl) + pl.part_bytes.
