@@ -3,7 +3,9 @@
 
 One step = one pass of the whole path over one batch of synthetic input that
 is already resident in HBM:
-    dk_encode -> dk_conv_fwd | dk_linear_fwd -> dk_verify -> dk_decode -> dk_wgrad
+    dk_encode -> dk_conv_fwd | dk_linear_fwd -> dk_decode_verify -> dk_wgrad
+(dk_decode_verify = dk_verify + dk_decode in one sweep over the encoded results).
+The step is captured once into a HIP graph and replayed (--no-graph: eager).
 Prints ONE JSON line: whole-path executed TFLOP/s (forward + weight gradient
 on all K+2 encoded rows per group), decoded samples/s, the roofline record of
 the dominant kernel (timed with events on the launch stream inside the timed
@@ -46,8 +48,7 @@ def algorithmic_bytes(K, G, n, m):
     S = K + 2
     return {
         "encode": 4 * G * n * (K + 1 + S),
-        "verify": 4 * G * m * S,
-        "decode": 4 * G * m * (S + K),
+        "decode_verify": 4 * G * m * (S + K),      # one read of ybar serves both
         "delta_mix": 4 * G * m * (K + S),
     }
 
@@ -97,6 +98,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="config2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="first run three plain 1 GiB device copies (a known-size reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -140,7 +142,7 @@ def main():
     ws_vf = torch.empty(dk.dk_workspace_bytes(None, dk.DK_OP_VERIFY, G, K), **u8)
     conv = L.kind == "conv"
 
-    stages = ["encode", "fwd", "verify", "decode", "wgrad"]
+    stages = ["encode", "fwd", "decode_verify", "wgrad"]
 
     def step(ev=None):
         if ev: ev[0].record()
@@ -151,24 +153,57 @@ def main():
         else:
             dk.dk_linear_fwd(W, xbar, ybar=ybar, ws=ws_fwd)
         if ev: ev[2].record()
-        dk.dk_verify(ybar, nvec_d, K, tol=1e-3, verdict=verdict, resid=resid, ws=ws_vf)
+        dk.dk_decode_verify(ybar, Ainv_d, nvec_d, K, tol=1e-3, y=y, verdict=verdict, resid=resid, ws=ws_vf)
         if ev: ev[3].record()
-        dk.dk_decode(ybar, Ainv_d, K, y=y)
-        if ev: ev[4].record()
         dk.dk_wgrad(L, delta, B_d, gamma_d, xbar, K, dW=dW, scale=1.0, ws=ws_wg)
-        if ev: ev[5].record()
+        if ev: ev[4].record()
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+
+    # Capture one step into a HIP graph (the library allocates nothing and never
+    # synchronises, so its launches can be recorded) and check a few replays
+    # against the eager results before trusting it.
+    graph = None
+    if not args.no_graph:
+        ref = [t.clone() for t in (y, dW, verdict)]
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=side):
+                    step()
+            torch.cuda.current_stream().wait_stream(side)
+            for _ in range(3):
+                for t in (y, dW):
+                    t.zero_()
+                torch.cuda.synchronize()
+                graph.replay()
+                torch.cuda.synchronize()
+                if not all(torch.equal(a, b) for a, b in zip((y, dW, verdict), ref)):
+                    raise RuntimeError("graph replay differs from the eager step")
+        except Exception as e:                      # noqa: BLE001 - fall back to eager launches
+            sys.stderr.write("bench.py: HIP graph not used (%s)\n" % e)
+            graph = None
+        for _ in range(args.warmup):
+            graph.replay() if graph else step()
+        torch.cuda.synchronize()
+
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(events[i])
+        graph.replay() if graph else step()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    # Second pass over the same K steps with every kernel launch bracketed by HIP
+    # Eager pass with an event between the entry points (stage times).
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+
+    # Third pass over the same K steps with every kernel launch bracketed by HIP
     # events on its launch stream (the brackets cost a few microseconds per
     # launch, so this pass is not the one `value` is taken from).
     dk.dk_profile_enable(True)
@@ -200,9 +235,9 @@ def main():
         "unit": "TFLOP/s", "frac": dom_tflops / MFMA_F32_PEAK_TFLOPS,
         "traffic": measured_traffic(args.workload, dom),
         "avg_launch_ms": dom_ms, "flop_per_launch": flop_fwd,
-        "timed": "HIP events around every launch of this kernel, %d launches, pass 2" % args.steps,
+        "timed": "HIP events around every launch of this kernel, %d eager launches after the timed region" % args.steps,
     }
-    kname = {"encode": "encode", "verify": "verify_partial", "decode": "decode", "delta_mix": "delta_mix"}
+    kname = {"encode": "encode", "decode_verify": "decode_verify", "delta_mix": "delta_mix"}
     hbm = {}
     for k, label in kname.items():
         if label in kernels:
@@ -215,7 +250,8 @@ def main():
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": wname, "K": K, "G": G, "layer": L.asdict()},
+        "config": {"workload": wname, "K": K, "G": G, "layer": L.asdict(),
+                   "launch": "HIP graph replay of one captured step" if graph else "eager"},
         "pct_mfma_peak": 100.0 * tflops / MFMA_F32_PEAK_TFLOPS,
         "decoded_samples_per_s": G * K / (ms_per_step * 1e-3),
         "effective_tflops": tflops * K / S,

@@ -147,6 +147,15 @@ dk_status dk_verify(const float *ybar, const float *nvec, float tol,
                     int *verdict, float *resid, int G, int K, long long m,
                     void *ws, size_t ws_bytes, void *stream);
 
+/* dk_decode and dk_verify in one sweep over ybar (both read every encoded row
+ * once): same arguments, same results as the two calls, one workspace of
+ * dk_workspace_bytes(NULL, DK_OP_VERIFY, G, K). */
+dk_status dk_decode_verify(const float *ybar, const float *Ainv,
+                           const float *nvec, float tol, float *y,
+                           int *verdict, float *resid, int G, int K,
+                           long long m, void *ws, size_t ws_bytes,
+                           void *stream);
+
 /* Optional per-kernel timing for benchmarks (not part of the method).  While
  * enabled (on = 1 also clears earlier records) every kernel the library
  * launches is bracketed by two HIP events on its launch stream; the library

@@ -8,11 +8,11 @@ PyTorch is used for device memory and streams, nothing else.
 from .binding import (DkError, DkLayer, lib_path, load, dk_version, dk_status_str,
                       dk_workspace_bytes, dk_layer_in_len, dk_layer_out_len, dk_coeffs,
                       dk_encode, dk_linear_fwd, dk_conv_fwd, dk_wgrad, dk_decode, dk_verify,
-                      dk_profile_enable, dk_profile_read,
+                      dk_decode_verify, dk_profile_enable, dk_profile_read,
                       DK_OP_FWD, DK_OP_WGRAD, DK_OP_VERIFY, DK_MAX_K)
 
 __all__ = ["DkError", "DkLayer", "lib_path", "load", "dk_version", "dk_status_str",
            "dk_workspace_bytes", "dk_layer_in_len", "dk_layer_out_len", "dk_coeffs",
            "dk_encode", "dk_linear_fwd", "dk_conv_fwd", "dk_wgrad", "dk_decode", "dk_verify",
-           "dk_profile_enable", "dk_profile_read",
+           "dk_decode_verify", "dk_profile_enable", "dk_profile_read",
            "DK_OP_FWD", "DK_OP_WGRAD", "DK_OP_VERIFY", "DK_MAX_K"]

@@ -73,6 +73,7 @@ def load():
         "dk_wgrad": (ip, [LP, vp, vp, vp, vp, vp, ip, ip, fl, ip, vp, sz, vp]),
         "dk_decode": (ip, [vp, vp, vp, ip, ip, ll, vp]),
         "dk_verify": (ip, [vp, vp, fl, vp, vp, ip, ip, ll, vp, sz, vp]),
+        "dk_decode_verify": (ip, [vp, vp, vp, fl, vp, vp, vp, ip, ip, ll, vp, sz, vp]),
         "dk_profile_enable": (ip, [ip]),
         "dk_profile_read": (ip, [ip, C.c_char_p, ip, C.POINTER(C.c_double), C.POINTER(ip)]),
     }
@@ -286,6 +287,33 @@ def dk_verify(ybar, nvec, K, tol=1e-3, verdict=None, resid=None, ws=None, stream
     _check(load().dk_verify(_ptr(ybar), _ptr(nvec), float(tol), _ptr(verdict), _ptr(resid), G, K, m,
                             _ptr(ws), ws.numel(), _stream(stream)), "dk_verify")
     return verdict, resid
+
+
+def dk_decode_verify(ybar, Ainv, nvec, K, tol=1e-3, y=None, verdict=None, resid=None, ws=None,
+                     stream=None):
+    """dk_decode and dk_verify in one sweep: returns (y, verdict, resid)."""
+    torch = _torch()
+    ybar, Ainv, nvec = _dev(ybar, "ybar"), _dev(Ainv, "Ainv"), _dev(nvec, "nvec")
+    G = Ainv.shape[0]
+    S = K + 2
+    if Ainv.shape != (G, S, S) or nvec.shape != (G, S) or ybar.shape[0] != G * S:
+        raise ValueError("dk_decode_verify: inconsistent shapes")
+    m = ybar[0].numel()
+    if y is None:
+        y = torch.empty((G * K,) + tuple(ybar.shape[1:]), dtype=torch.float32, device=ybar.device)
+    _dev(y, "y")
+    if y.numel() != G * K * m:
+        raise ValueError("dk_decode_verify: y has the wrong size")
+    if verdict is None:
+        verdict = torch.empty(G, dtype=torch.int32, device=ybar.device)
+    if resid is None:
+        resid = torch.empty(G, dtype=torch.float32, device=ybar.device)
+    if ws is None:
+        ws = _workspace(load().dk_workspace_bytes(None, DK_OP_VERIFY, G, K), ybar)
+    _check(load().dk_decode_verify(_ptr(ybar), _ptr(Ainv), _ptr(nvec), float(tol), _ptr(y), _ptr(verdict),
+                                   _ptr(resid), G, K, m, _ptr(ws), ws.numel(), _stream(stream)),
+           "dk_decode_verify")
+    return y, verdict, resid
 
 
 def dk_profile_enable(on=True):

@@ -360,11 +360,12 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_quad_fwd_kernel(dk_patch_pa
             if (ok_) v_ = *reinterpret_cast<const f32x4 *>(src_ + goff[e]);                      \
             pst[e] = v_;                                                                         \
         }                                                                                        \
-        const float *wsrc_ = p.wp + ((long long)(CH) * p.Co_pad + co0) * 72;                     \
+        const float *wsrc_ = p.wp + (long long)(CH) * p.w_chunk + (long long)co0 * p.w_row;      \
         _Pragma("unroll") for (int e = 0; e < WSLOT; ++e) {                                      \
             int idx_ = tid + e * NT;                                                             \
             if (idx_ >= W4) idx_ = W4 - 1;                                                       \
-            wst[e] = *reinterpret_cast<const f32x4 *>(wsrc_ + idx_ * 4);                         \
+            const int row_ = idx_ / 18, c4_ = idx_ - row_ * 18;                                  \
+            wst[e] = *reinterpret_cast<const f32x4 *>(wsrc_ + (long long)row_ * p.w_row + c4_ * 4); \
         }                                                                                        \
     }
 
@@ -575,6 +576,8 @@ bool plan_quad(const dk_geom &g, long long R, dk_patch_plan *pl)
     p.per_split = sp.ktiles_per_split;
     p.out_elems = R * g.m;
     pl->wp_floats = (size_t)p.n_chunks * 72 * p.Co_pad;
+    p.w_row = 72;
+    p.w_chunk = 72ll * p.Co_pad;
     pl->part_bytes = p.splits > 1 ? (size_t)p.splits * p.out_elems * sizeof(float) : 0;
     pl->cb = C::cb;
     pl->quad = true;
@@ -614,7 +617,15 @@ dk_status dk_patch_fwd_run(const dk_geom &g, dk_patch_plan &pl, const float *W, 
     float *wp = ws;
     float *part = (float *)((char *)ws + dk_patch_wp_bytes(pl));
     const long long total = (long long)pl.wp_floats;
-    {
+    // W[co][ci][3][3] already has the quad kernel's order inside a chunk of 8
+    // input channels (position (c' + 4h)*9 + a*3 + b = h*36 + (c'*3 + a)*3 + b), so
+    // with whole chunks, whole tiles and an aligned W the repack is skipped
+    const bool direct = pl.quad && g.Ci % 8 == 0 && p.Co_pad == g.Co && dk_aligned(W, 16);
+    if (direct) {
+        p.w_row = 9ll * g.Ci;
+        p.w_chunk = 72;
+        wp = const_cast<float *>(W);
+    } else {
         dk_prof_scope ps("pack_filters", st);
         if (pl.quad)
             pack_filters_quad_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(

@@ -172,6 +172,82 @@ __global__ __launch_bounds__(MIX_THREADS) void verify_partial_kernel(
     }
 }
 
+// Decode and the first pass of the integrity check in one sweep over ybar:
+// both need every encoded row of the group exactly once.
+template <int K, int VEC>
+__global__ __launch_bounds__(MIX_THREADS) void decode_verify_kernel(
+    const float *__restrict__ ybar, const float *__restrict__ Ainv, const float *__restrict__ nvec_,
+    float *__restrict__ y, float *__restrict__ part, long long len, long long nvec, int chunks,
+    long long span)
+{
+    constexpr int S = K + 2;
+    const int g = blockIdx.x / chunks;
+    const int chunk = blockIdx.x - g * chunks;
+
+    float coef[S][K], nv[S];
+#pragma unroll
+    for (int j = 0; j < S; ++j) {
+        nv[j] = nvec_[(long long)g * S + j];
+#pragma unroll
+        for (int i = 0; i < K; ++i) coef[j][i] = Ainv[((long long)g * S + j) * S + i];
+    }
+    const float *src = ybar + (long long)g * S * len;
+    float *dst = y + (long long)g * K * len;
+
+    float tmax = 0.0f, smax = 0.0f;
+    bool bad = false;
+    const long long v0 = (long long)chunk * span;
+    long long v1 = v0 + span;
+    if (v1 > nvec) v1 = nvec;
+    for (long long v = v0 + threadIdx.x; v < v1; v += MIX_THREADS) {
+        const long long e = v * VEC;
+        float x[S][VEC];
+#pragma unroll
+        for (int j = 0; j < S; ++j) vload<VEC>(x[j], src + (long long)j * len + e);
+#pragma unroll
+        for (int i = 0; i < K; ++i) {
+            float acc[VEC];
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) acc[c] = coef[0][i] * x[0][c];
+#pragma unroll
+            for (int j = 1; j < S; ++j)
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[c] = fmaf(coef[j][i], x[j][c], acc[c]);
+            vstore<VEC>(dst + (long long)i * len + e, acc);
+        }
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            float t = 0.0f, sc = 0.0f;
+#pragma unroll
+            for (int j = 0; j < S; ++j) {
+                const float pr = nv[j] * x[j][c];
+                t += pr;
+                sc += fabsf(pr);
+            }
+            bad |= !(sc <= 3.402823466e+38f) || !(fabsf(t) <= 3.402823466e+38f);
+            tmax = fmaxf(tmax, fabsf(t));
+            smax = fmaxf(smax, sc);
+        }
+    }
+    if (bad) tmax = __builtin_inff();
+
+    __shared__ float red[2][MIX_THREADS / 64];
+    tmax = wave_max(tmax);
+    smax = wave_max(smax);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { red[0][wave] = tmax; red[1][wave] = smax; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < MIX_THREADS / 64; ++w) {
+            tmax = fmaxf(tmax, red[0][w]);
+            smax = fmaxf(smax, red[1][w]);
+        }
+        part[((long long)g * chunks + chunk) * 2 + 0] = tmax;
+        part[((long long)g * chunks + chunk) * 2 + 1] = smax;
+    }
+}
+
 // Integrity check, second pass: one wave per group folds the (at most 64)
 // partial pairs -- lane c holds chunk c -- and lane 0 takes the verdict.
 __global__ __launch_bounds__(MIX_THREADS) void verify_final_kernel(
@@ -289,6 +365,30 @@ dk_status launch_verify_k(const float *ybar, const float *nvec, float tol, int *
     return dk_launch_status();
 }
 
+template <int K>
+dk_status launch_decode_verify_k(const float *ybar, const float *Ainv, const float *nvec, float tol,
+                                 float *y, int *verdict, float *resid, int G, long long len,
+                                 float *part, bool v4, hipStream_t st)
+{
+    const span_plan p = plan_span(len, v4 ? 4 : 1, G, DK_VERIFY_MAX_BLOCKS);
+    const long long blocks = (long long)G * p.chunks;
+    DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
+    {
+    dk_prof_scope ps("decode_verify", st);
+    if (v4)
+        decode_verify_kernel<K, 4><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
+            ybar, Ainv, nvec, y, part, len, p.nvec, p.chunks, p.span);
+    else
+        decode_verify_kernel<K, 1><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
+            ybar, Ainv, nvec, y, part, len, p.nvec, p.chunks, p.span);
+    }
+    DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+    dk_prof_scope ps("verify_final", st);
+    verify_final_kernel<<<dim3((G + MIX_THREADS / 64 - 1) / (MIX_THREADS / 64)), dim3(MIX_THREADS), 0, st>>>(
+        part, p.chunks, tol, verdict, resid, G);
+    return dk_launch_status();
+}
+
 dk_status check_mix_args(int G, int K, long long len)
 {
     DK_REQUIRE(G >= 1 && K >= 1 && K <= DK_MAX_K && len >= 1, DK_ERR_SHAPE);
@@ -348,6 +448,24 @@ DK_EXPORT dk_status dk_verify(const float *ybar, const float *nvec, float tol, i
     DK_REQUIRE(dk_aligned(ws, 4), DK_ERR_ALIGN);
     const bool v4 = can_vec4(m, {ybar});
 #define CALL(KK) launch_verify_k<KK>(ybar, nvec, tol, verdict, resid, G, m, (float *)ws, v4, (hipStream_t)stream)
+    DK_K_SWITCH(K, CALL)
+#undef CALL
+}
+
+DK_EXPORT dk_status dk_decode_verify(const float *ybar, const float *Ainv, const float *nvec, float tol,
+                                     float *y, int *verdict, float *resid, int G, int K, long long m,
+                                     void *ws, size_t ws_bytes, void *stream)
+{
+    DK_REQUIRE(ybar && Ainv && nvec && y && verdict, DK_ERR_NULL);
+    dk_status s = check_mix_args(G, K, m);
+    if (s != DK_OK) return s;
+    DK_REQUIRE(tol >= 0.0f, DK_ERR_SHAPE);
+    DK_REQUIRE(dk_aligned(ybar, 4) && dk_aligned(Ainv, 4) && dk_aligned(nvec, 4) && dk_aligned(y, 4) &&
+                   dk_aligned(verdict, 4) && (!resid || dk_aligned(resid, 4)), DK_ERR_ALIGN);
+    DK_REQUIRE(ws && ws_bytes >= dk_ws_verify_bytes(G), DK_ERR_WORKSPACE);
+    DK_REQUIRE(dk_aligned(ws, 4), DK_ERR_ALIGN);
+    const bool v4 = can_vec4(m, {ybar, y});
+#define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, (float *)ws, v4, (hipStream_t)stream)
     DK_K_SWITCH(K, CALL)
 #undef CALL
 }

@@ -18,6 +18,7 @@ struct dk_patch_params {
     int n_chunks, per_split, splits, Co_pad;
     int tiles_m, tiles_n;
     long long out_elems;
+    long long w_row, w_chunk;     // filter tile addressing: floats between rows / chunks
 };
 
 struct dk_patch_plan {

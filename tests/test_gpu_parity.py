@@ -102,6 +102,12 @@ def test_encode_decode_verify_stages(dk, K, G, n):
     assert host(v).tolist() == vref.tolist()
     assert np.allclose(host(rho)[expect == 1], rhoref[expect == 1], rtol=1e-3)
 
+    # the fused sweep gives what the two calls give
+    y2, v2, rho2 = dk.dk_decode_verify(dev(yc), dev(Ainv), dev(nvec), K, tol=1e-3)
+    assert host(v2).tolist() == vref.tolist()
+    assert np.array_equal(host(rho2), host(rho))
+    assert np.array_equal(host(y2), host(dk.dk_decode(dev(yc), dev(Ainv), K)))
+
 
 def test_verify_nonfinite_and_zero(dk):
     say("verify non-finite / all-zero")
