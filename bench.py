@@ -37,6 +37,12 @@ def workload(name):
     if name.startswith("config3."):
         i = int(name.split(".")[1])
         return dk_inputs.config3(index=i)[0], "config3 layer %d (VGG-16 conv stack @32x32, batch 128, K=4)" % i
+    if name.startswith("config4."):
+        i = int(name.split(".")[1])
+        for k, (d, count) in enumerate(dk_inputs.config4()):
+            if k == i:
+                return d, "config4 shape %d x%d (ResNet-50 convs @224x224 input, batch 64, K=8)" % (i, count)
+        raise SystemExit("config4 has 22 shapes")
     if name.startswith("config5."):
         i = int(name.split(".")[1])
         return dk_inputs.config5(index=i)[0], "config5 layer %d (VGG classifier, batch 1024, K=8)" % i

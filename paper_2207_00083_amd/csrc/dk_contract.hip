@@ -289,6 +289,127 @@ struct LoadIm2colQ {
     }
 };
 
+// 1x1 stride-1 convolution = one product per image: no gather is needed, only
+// addressing that knows where an image starts.
+struct ImgParams {
+    const float *p;     // [R][C][HW]
+    int C, HW;          // channels per image, pixels per image
+    int Q;              // R*HW
+};
+
+// Forward B operand: rows = pixels q = (r, pix), contraction = input channel;
+// element = x[r][k][pix], pixels contiguous.
+template <int ROWS, int BK, int NT, int LD, bool VEC>
+struct LoadKMajorImg {
+    using Params = ImgParams;
+    static constexpr int PER_K = ROWS / 4;
+    static constexpr int N4 = BK * PER_K / NT;
+    static_assert(BK * PER_K % NT == 0 && NT % PER_K == 0, "tile/threads");
+    float4 st[N4];
+    const float *src[VEC ? 1 : 4];   // element (k = 0) of this lane's pixel(s); null = outside
+    int C, HW, tid;
+
+    __device__ __forceinline__ void init(const Params &a, int q0, int tid_)
+    {
+        C = a.C; HW = a.HW; tid = tid_;
+        const int q = q0 + (tid % PER_K) * 4;
+#pragma unroll
+        for (int u = 0; u < (VEC ? 1 : 4); ++u) {
+            const int qq = q + u;
+            const int r = qq / HW, pix = qq - r * HW;
+            src[u] = qq < a.Q ? a.p + (long long)r * C * HW + pix : nullptr;
+        }
+    }
+
+    __device__ __forceinline__ void load(int kt)
+    {
+#pragma unroll
+        for (int e = 0; e < N4; ++e) {
+            const int k = kt * BK + (tid + e * NT) / PER_K;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k < C) {
+                const long long ko = (long long)k * HW;
+                if constexpr (VEC) {
+                    if (src[0]) v = *reinterpret_cast<const float4 *>(src[0] + ko);
+                } else {
+                    if (src[0]) v.x = src[0][ko];
+                    if (src[1]) v.y = src[1][ko];
+                    if (src[2]) v.z = src[2][ko];
+                    if (src[3]) v.w = src[3][ko];
+                }
+            }
+            st[e] = v;
+        }
+    }
+
+    __device__ __forceinline__ void store(float *buf) const
+    {
+#pragma unroll
+        for (int e = 0; e < N4; ++e) {
+            const int idx = tid + e * NT;
+            *reinterpret_cast<float4 *>(buf + (idx / PER_K) * LD + (idx % PER_K) * 4) = st[e];
+        }
+    }
+};
+
+// Weight-gradient operands: rows = channel, contraction = pixels q = (r, pix);
+// element = t[r][row][pix].
+template <int ROWS, int BK, int NT, int LD, bool VEC>
+struct LoadRowMajorKImg {
+    using Params = ImgParams;
+    static constexpr int PER_ROW = BK / 4;
+    static constexpr int N4 = ROWS * PER_ROW / NT;
+    static_assert(ROWS * PER_ROW % NT == 0 && NT % PER_ROW == 0, "tile/threads");
+    float4 st[N4];
+    const float *p; int C, HW, Q, row0, tid;
+
+    __device__ __forceinline__ void init(const Params &a, int row0_, int tid_)
+    { p = a.p; C = a.C; HW = a.HW; Q = a.Q; row0 = row0_; tid = tid_; }
+
+    __device__ __forceinline__ void load(int kt)
+    {
+        const int q = kt * BK + (tid % PER_ROW) * 4;
+        const float *s[VEC ? 1 : 4];
+#pragma unroll
+        for (int u = 0; u < (VEC ? 1 : 4); ++u) {
+            const int qq = q + u;
+            const int r = qq / HW, pix = qq - r * HW;
+            s[u] = qq < Q ? p + (long long)r * C * HW + pix : nullptr;
+        }
+#pragma unroll
+        for (int e = 0; e < N4; ++e) {
+            const int row = row0 + (tid + e * NT) / PER_ROW;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < C) {
+                const long long ro = (long long)row * HW;
+                if constexpr (VEC) {
+                    if (s[0]) v = *reinterpret_cast<const float4 *>(s[0] + ro);
+                } else {
+                    if (s[0]) v.x = s[0][ro];
+                    if (s[1]) v.y = s[1][ro];
+                    if (s[2]) v.z = s[2][ro];
+                    if (s[3]) v.w = s[3][ro];
+                }
+            }
+            st[e] = v;
+        }
+    }
+
+    __device__ __forceinline__ void store(float *buf) const
+    {
+#pragma unroll
+        for (int e = 0; e < N4; ++e) {
+            const int idx = tid + e * NT;
+            const int row = idx / PER_ROW, kc = idx % PER_ROW;
+            float *d = buf + (kc * 4) * LD + row;
+            d[0 * LD] = st[e].x;
+            d[1 * LD] = st[e].y;
+            d[2 * LD] = st[e].z;
+            d[3 * LD] = st[e].w;
+        }
+    }
+};
+
 // ---------------------------------------------------------------------------
 // Epilogues: where output element (row, col) lives.
 // ---------------------------------------------------------------------------
@@ -547,6 +668,37 @@ dk_status run_conv_wgrad(const dk_geom &g, const float *dtilde, const float *xba
                                     (long long)g.Co * g.Kg, part, part_bytes, st, "contract_conv_wgrad_gather");
 }
 
+// 1x1 stride-1 pad-0 convolution through the image-aware loaders.
+template <class C, bool VW, bool VX>
+dk_status run_conv1x1_fwd(const dk_geom &g, const float *W, const float *xbar, float *ybar, long long R,
+                          float *part, size_t part_bytes, hipStream_t st)
+{
+    using LA = LoadRowMajorK<C::BM, C::BK, C::NT, C::LDA, VW>;
+    using LB = LoadKMajorImg<C::BN, C::BK, C::NT, C::LDB, VX>;
+    const int HW = g.H * g.W, Q = (int)(R * HW);
+    MatParams pa = {W, g.Ci, g.Co, g.Ci};
+    ImgParams pb = {xbar, g.Ci, HW, Q};
+    EpiConvFwd ep = {g.Co, Q, HW, (long long)g.Co * HW};
+    return run<C, LA, LB, EpiConvFwd>(pa, pb, ep, g.Co, Q, g.Ci, 1.0f, 0, ybar, R * g.m, part, part_bytes,
+                                      st, "contract_conv1x1_fwd");
+}
+
+template <class C, bool VEC>
+dk_status run_conv1x1_wgrad(const dk_geom &g, const float *dtilde, const float *xbar, float *dW,
+                            long long R, float alpha, int accumulate, float *part, size_t part_bytes,
+                            hipStream_t st)
+{
+    using LA = LoadRowMajorKImg<C::BM, C::BK, C::NT, C::LDA, VEC>;
+    using LB = LoadRowMajorKImg<C::BN, C::BK, C::NT, C::LDB, VEC>;
+    const int HW = g.H * g.W, Q = (int)(R * HW);
+    ImgParams pa = {dtilde, g.Co, HW, Q}, pb = {xbar, g.Ci, HW, Q};
+    EpiDense ep = {g.Ci, g.Co, g.Ci};
+    return run<C, LA, LB, EpiDense>(pa, pb, ep, g.Co, g.Ci, Q, alpha, accumulate, dW,
+                                    (long long)g.Co * g.Ci, part, part_bytes, st, "contract_conv1x1_wgrad");
+}
+
+bool conv_is_1x1(const dk_geom &g) { return g.kh == 1 && g.kw == 1 && g.stride == 1 && g.pad == 0; }
+
 bool conv_flat(const dk_geom &g) { return g.Co <= 64; }
 
 } // namespace
@@ -627,6 +779,16 @@ DK_EXPORT dk_status dk_conv_fwd(const dk_layer *L, const float *W, const float *
     if (dk_patch_fwd_plan(g, R, dk_aligned(xbar, 16) && dk_aligned(ybar, 16), &pl))
         return dk_patch_fwd_run(g, pl, W, xbar, ybar, (float *)ws, st);
     const bool vw = (g.Kg % 4 == 0) && dk_aligned(W, 16);
+    if (conv_is_1x1(g)) {
+        const bool vx = (g.H * g.W) % 4 == 0 && dk_aligned(xbar, 16);
+        float *pw = (float *)ws;
+        if (conv_flat(g)) {
+            if (vw && vx) return run_conv1x1_fwd<CfgFlat, true, true>(g, W, xbar, ybar, R, pw, ws_bytes, st);
+            return run_conv1x1_fwd<CfgFlat, false, false>(g, W, xbar, ybar, R, pw, ws_bytes, st);
+        }
+        if (vw && vx) return run_conv1x1_fwd<CfgSq, true, true>(g, W, xbar, ybar, R, pw, ws_bytes, st);
+        return run_conv1x1_fwd<CfgSq, false, false>(g, W, xbar, ybar, R, pw, ws_bytes, st);
+    }
     if (conv_flat(g))
         return vw ? run_conv_fwd<CfgFlat, true>(g, W, xbar, ybar, R, (float *)ws, ws_bytes, st)
                   : run_conv_fwd<CfgFlat, false>(g, W, xbar, ybar, R, (float *)ws, ws_bytes, st);
@@ -672,6 +834,14 @@ DK_EXPORT dk_status dk_wgrad(const dk_layer *L, const float *delta, const float 
     if (dk_patch_wgrad_plan(g, R, dk_aligned(xbar, 16), &pl)) {
         DK_REQUIRE(part_bytes >= pl.part_bytes, DK_ERR_WORKSPACE);
         return dk_patch_wgrad_run(g, pl, dtilde, xbar, dW, scale, accumulate, part, st);
+    }
+    if (conv_is_1x1(g)) {
+        const bool vec = (g.H * g.W) % 4 == 0 && dk_aligned(xbar, 16);
+        if (conv_flat(g))
+            return vec ? run_conv1x1_wgrad<CfgWg64, true>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st)
+                       : run_conv1x1_wgrad<CfgWg64, false>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
+        return vec ? run_conv1x1_wgrad<CfgSq, true>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st)
+                   : run_conv1x1_wgrad<CfgSq, false>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
     }
     if (conv_flat(g))
         return run_conv_wgrad<CfgWg64>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);

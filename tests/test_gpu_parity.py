@@ -156,6 +156,8 @@ CONV_CASES = [
     (3, 64, 32, 32, 3, 1, 1, 6),
     (16, 130, 9, 11, 3, 1, 1, 5),
     (20, 24, 14, 14, 1, 1, 0, 6),
+    (24, 136, 7, 7, 1, 1, 0, 5),
+    (72, 40, 12, 12, 1, 1, 0, 7),
     (16, 72, 14, 14, 1, 2, 0, 4),
     (8, 8, 15, 13, 3, 2, 1, 3),
     (3, 16, 30, 30, 7, 2, 3, 3),
@@ -231,6 +233,8 @@ CONV_MASKED = [
     (2, 4, 3, 64, 16, 16, 3, 1, 1),
     (4, 2, 16, 130, 9, 11, 3, 1, 1),
     (2, 3, 20, 24, 14, 14, 1, 1, 0),
+    (3, 2, 24, 136, 7, 7, 1, 1, 0),
+    (4, 2, 132, 72, 12, 12, 1, 1, 0),
     (3, 2, 16, 72, 14, 14, 1, 2, 0),
     (2, 2, 8, 8, 15, 13, 3, 2, 1),
     (1, 2, 3, 16, 30, 30, 7, 2, 3),
