@@ -105,6 +105,7 @@ def main():
     ap.add_argument("--workload", default="config2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly")
+    ap.add_argument("--no-fork", action="store_true", help="one branch in the captured graph")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="first run three plain 1 GiB device copies (a known-size reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -150,10 +151,20 @@ def main():
 
     stages = ["encode", "fwd", "decode_verify", "wgrad"]
 
-    def step(ev=None):
+    side2 = torch.cuda.Stream()
+
+    def step(ev=None, fork=False):
+        """fork=True (graph capture only): the weight gradient needs nothing of
+        the forward chain but the encodings, so it goes on a second stream and
+        the two branches of the captured graph may overlap."""
+        cur = torch.cuda.current_stream()
         if ev: ev[0].record()
         dk.dk_encode(X, r, A_d, K, xbar=xbar)
         if ev: ev[1].record()
+        if fork:
+            side2.wait_stream(cur)
+            with torch.cuda.stream(side2):
+                dk.dk_wgrad(L, delta, B_d, gamma_d, xbar, K, dW=dW, scale=1.0, ws=ws_wg)
         if conv:
             dk.dk_conv_fwd(L, W, xbar, ybar=ybar, ws=ws_fwd)
         else:
@@ -161,7 +172,10 @@ def main():
         if ev: ev[2].record()
         dk.dk_decode_verify(ybar, Ainv_d, nvec_d, K, tol=1e-3, y=y, verdict=verdict, resid=resid, ws=ws_vf)
         if ev: ev[3].record()
-        dk.dk_wgrad(L, delta, B_d, gamma_d, xbar, K, dW=dW, scale=1.0, ws=ws_wg)
+        if fork:
+            cur.wait_stream(side2)
+        else:
+            dk.dk_wgrad(L, delta, B_d, gamma_d, xbar, K, dW=dW, scale=1.0, ws=ws_wg)
         if ev: ev[4].record()
 
     for _ in range(args.warmup):
@@ -180,7 +194,7 @@ def main():
             with torch.cuda.stream(side):
                 graph = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(graph, stream=side):
-                    step()
+                    step(fork=not args.no_fork)
             torch.cuda.current_stream().wait_stream(side)
             for _ in range(3):
                 for t in (y, dW):
@@ -257,7 +271,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wname, "K": K, "G": G, "layer": L.asdict(),
-                   "launch": "HIP graph replay of one captured step" if graph else "eager"},
+                   "launch": ("HIP graph replay of one captured step"
+                              + ("" if args.no_fork else ", weight gradient on a second branch")) if graph else "eager"},
         "pct_mfma_peak": 100.0 * tflops / MFMA_F32_PEAK_TFLOPS,
         "decoded_samples_per_s": G * K / (ms_per_step * 1e-3),
         "effective_tflops": tflops * K / S,
