@@ -372,6 +372,61 @@ def test_config5_layer2_full_size_sampled(dk):
     assert np.max(np.abs(wgot - wref)) / np.max(np.abs(wref)) < TOL_CONTRACT
 
 
+def _sampled_conv_check(dk, d, npts=20000, seed=1):
+    L, K, G = d["layer"], d["K"], d["G"]
+    out = _run_masked(dk, d)
+    rng = np.random.default_rng(seed)
+    pts = np.stack([rng.integers(G * K, size=npts), rng.integers(L.Co, size=npts),
+                    rng.integers(L.Ho, size=npts), rng.integers(L.Wo, size=npts)], axis=1)
+    pts[:50, 2] = 0; pts[50:100, 2] = L.Ho - 1; pts[100:150, 3] = 0; pts[150:200, 3] = L.Wo - 1
+    ref = oracle.conv_fwd_points(d["W"], d["X"], pts, L.stride, L.pad)
+    got = out["y"][tuple(pts.T)]
+    assert np.max(np.abs(got - ref)) / float(np.max(np.abs(out["y"]))) < TOL_CONTRACT
+    nw = min(npts, L.Co * L.Ci * L.kh * L.kw)
+    wpts = np.stack([rng.integers(L.Co, size=nw), rng.integers(L.Ci, size=nw),
+                     rng.integers(L.kh, size=nw), rng.integers(L.kw, size=nw)], axis=1)[:4000]
+    wref = oracle.conv_wgrad_points(d["delta"], d["X"], L.kh, L.kw, wpts, L.stride, L.pad)
+    wgot = out["dW"][tuple(wpts.T)]
+    assert np.max(np.abs(wgot - wref)) / float(np.max(np.abs(out["dW"]))) < TOL_CONTRACT
+    assert out["verdict"].tolist() == [0] * G
+    assert out["resid"].max() < 1e-4
+
+
+def test_config3_layer_full_size_sampled(dk):
+    say("config 3 layer 5 (VGG conv 256->256 @8x8, batch 128, K=4), sampled outputs")
+    _sampled_conv_check(dk, dk_inputs.config3(index=5)[0])
+
+
+def test_config3_first_layer_full_size_sampled(dk):
+    say("config 3 layer 0 (VGG conv 3->64 @32x32, images ~U[0,1]), sampled outputs")
+    _sampled_conv_check(dk, dk_inputs.config3(index=0)[0])
+
+
+def test_config4_shapes_full_size_sampled(dk):
+    for idx in (10, 11):       # 1x1 512->256 @28x28 and 3x3 stride 2 256->256 @28x28, batch 64, K=8
+        for k, (d, count) in enumerate(dk_inputs.config4()):
+            if k == idx:
+                say("config 4 shape", idx, d["layer"], "x%d" % count)
+                _sampled_conv_check(dk, d, npts=8000)
+                break
+
+
+def test_config5_last_layer_full_size_sampled(dk):
+    say("config 5 layer 3 (dense 4096->1000, batch 1024, K=8), sampled outputs")
+    d = dk_inputs.config5(index=2)[0]
+    L, K, G = d["layer"], d["K"], d["G"]
+    out = _run_masked(dk, d, scale=1.0 / K)
+    rng = np.random.default_rng(7)
+    npts = 20000
+    pts = np.stack([rng.integers(G * K, size=npts), rng.integers(L.M, size=npts)], axis=1)
+    ref = oracle.dense_fwd_points(d["W"], d["X"], pts)
+    assert np.max(np.abs(out["y"][tuple(pts.T)] - ref)) / np.max(np.abs(ref)) < TOL_CONTRACT
+    wpts = np.stack([rng.integers(L.M, size=npts), rng.integers(L.N, size=npts)], axis=1)
+    wref = oracle.dense_wgrad_points(d["delta"], d["X"], wpts, scale=1.0 / K)
+    assert np.max(np.abs(out["dW"][tuple(wpts.T)] - wref)) / np.max(np.abs(wref)) < TOL_CONTRACT
+    assert out["verdict"].tolist() == [0] * G
+
+
 # ----------------------------------------------------------------------
 # error behaviour through the C ABI
 # ----------------------------------------------------------------------
