@@ -447,7 +447,7 @@ struct QuadCfg {
 };
 
 using Q3Flat = QuadCfg<1, 2, 2>;     // 64 co x 256 px
-using Q3Sq = QuadCfg<2, 2, 2>;       // 128 co x 256 px
+using Q3Sq = QuadCfg<1, 4, 1>;       // 128 co x 128 px
 
 template <int BM, int BN, int WM, int WN, int KH, int KW, int CB>
 struct PatchCfg {

@@ -462,7 +462,7 @@ __global__ __launch_bounds__(256) void wgrad_fold_kernel(const float *__restrict
 
 inline int round_up(int v, int a) { return (v + a - 1) / a * a; }
 
-constexpr int DSLOT4 = 6, PSLOT4 = 10, DSLOT1 = 8, PSLOT1 = 24, DSLOTQ = 6, PSLOTQ = 10;
+constexpr int DSLOT4 = 6, PSLOT4 = 10, DSLOT1 = 8, PSLOT1 = 24, DSLOTQ = 6, PSLOTQ = 11;
 constexpr size_t LDS_LIMIT = 150 * 1024;     // of the 160 KB a compute unit has
 
 template <class KernelT>
