@@ -105,7 +105,9 @@ def main():
     ap.add_argument("--workload", default="config2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly")
-    ap.add_argument("--no-fork", action="store_true", help="one branch in the captured graph")
+    ap.add_argument("--fork", action="store_true",
+                    help="capture the weight gradient on a second graph branch (it may then overlap the "
+                         "forward chain; per-kernel profiler durations of overlapped kernels are inflated)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="first run three plain 1 GiB device copies (a known-size reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -194,7 +196,7 @@ def main():
             with torch.cuda.stream(side):
                 graph = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(graph, stream=side):
-                    step(fork=not args.no_fork)
+                    step(fork=args.fork)
             torch.cuda.current_stream().wait_stream(side)
             for _ in range(3):
                 for t in (y, dW):
@@ -272,7 +274,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wname, "K": K, "G": G, "layer": L.asdict(),
                    "launch": ("HIP graph replay of one captured step"
-                              + ("" if args.no_fork else ", weight gradient on a second branch")) if graph else "eager"},
+                              + (", weight gradient on a second branch" if args.fork else "")) if graph else "eager"},
         "pct_mfma_peak": 100.0 * tflops / MFMA_F32_PEAK_TFLOPS,
         "decoded_samples_per_s": G * K / (ms_per_step * 1e-3),
         "effective_tflops": tflops * K / S,
