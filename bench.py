@@ -108,6 +108,9 @@ def main():
     ap.add_argument("--fork", action="store_true",
                     help="capture the weight gradient on a second graph branch (it may then overlap the "
                          "forward chain; per-kernel profiler durations of overlapped kernels are inflated)")
+    ap.add_argument("--rotate", type=int, default=1,
+                    help="buffer sets the per-kernel pass cycles through, so that no kernel finds its inputs "
+                         "in the 256 MB last-level cache from the previous step (1 = reuse one set)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="first run three plain 1 GiB device copies (a known-size reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -136,48 +139,57 @@ def main():
     n, m = dk.dk_layer_in_len(L), dk.dk_layer_out_len(L)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     Ainv, nvec, B = dk.dk_coeffs(d["A"], d["gamma"])
-    X, r, W, delta = dev(d["X"]), dev(d["r"]), dev(d["W"]), dev(d["delta"])
+    W = dev(d["W"])
     A_d, Ainv_d, nvec_d, B_d, gamma_d = dev(d["A"]), dev(Ainv), dev(nvec), dev(B), dev(d["gamma"])
     f32 = dict(dtype=torch.float32, device="cuda")
-    xbar = torch.empty((G * S,) + L.in_shape, **f32)
-    ybar = torch.empty((G * S,) + L.out_shape, **f32)
-    y = torch.empty((G * K,) + L.out_shape, **f32)
-    dW = torch.empty(L.w_shape, **f32)
-    verdict = torch.empty(G, dtype=torch.int32, device="cuda")
-    resid = torch.empty(G, **f32)
     u8 = dict(dtype=torch.uint8, device="cuda")
-    ws_fwd = torch.empty(dk.dk_workspace_bytes(L, dk.DK_OP_FWD, G, K), **u8)
-    ws_wg = torch.empty(dk.dk_workspace_bytes(L, dk.DK_OP_WGRAD, G, K), **u8)
-    ws_vf = torch.empty(dk.dk_workspace_bytes(None, dk.DK_OP_VERIFY, G, K), **u8)
+
+    class Buffers:
+        """One set of the per-step tensors (inputs, encodings, outputs, workspaces)."""
+        def __init__(self):
+            self.X, self.r, self.delta = dev(d["X"]), dev(d["r"]), dev(d["delta"])
+            self.xbar = torch.empty((G * S,) + L.in_shape, **f32)
+            self.ybar = torch.empty((G * S,) + L.out_shape, **f32)
+            self.y = torch.empty((G * K,) + L.out_shape, **f32)
+            self.dW = torch.empty(L.w_shape, **f32)
+            self.verdict = torch.empty(G, dtype=torch.int32, device="cuda")
+            self.resid = torch.empty(G, **f32)
+            self.ws_fwd = torch.empty(dk.dk_workspace_bytes(L, dk.DK_OP_FWD, G, K), **u8)
+            self.ws_wg = torch.empty(dk.dk_workspace_bytes(L, dk.DK_OP_WGRAD, G, K), **u8)
+            self.ws_vf = torch.empty(dk.dk_workspace_bytes(None, dk.DK_OP_VERIFY, G, K), **u8)
+
+    b0 = Buffers()
+    y, dW, verdict = b0.y, b0.dW, b0.verdict
     conv = L.kind == "conv"
 
     stages = ["encode", "fwd", "decode_verify", "wgrad"]
 
     side2 = torch.cuda.Stream()
 
-    def step(ev=None, fork=False):
+    def step(ev=None, fork=False, b=b0):
         """fork=True (graph capture only): the weight gradient needs nothing of
         the forward chain but the encodings, so it goes on a second stream and
         the two branches of the captured graph may overlap."""
         cur = torch.cuda.current_stream()
         if ev: ev[0].record()
-        dk.dk_encode(X, r, A_d, K, xbar=xbar)
+        dk.dk_encode(b.X, b.r, A_d, K, xbar=b.xbar)
         if ev: ev[1].record()
         if fork:
             side2.wait_stream(cur)
             with torch.cuda.stream(side2):
-                dk.dk_wgrad(L, delta, B_d, gamma_d, xbar, K, dW=dW, scale=1.0, ws=ws_wg)
+                dk.dk_wgrad(L, b.delta, B_d, gamma_d, b.xbar, K, dW=b.dW, scale=1.0, ws=b.ws_wg)
         if conv:
-            dk.dk_conv_fwd(L, W, xbar, ybar=ybar, ws=ws_fwd)
+            dk.dk_conv_fwd(L, W, b.xbar, ybar=b.ybar, ws=b.ws_fwd)
         else:
-            dk.dk_linear_fwd(W, xbar, ybar=ybar, ws=ws_fwd)
+            dk.dk_linear_fwd(W, b.xbar, ybar=b.ybar, ws=b.ws_fwd)
         if ev: ev[2].record()
-        dk.dk_decode_verify(ybar, Ainv_d, nvec_d, K, tol=1e-3, y=y, verdict=verdict, resid=resid, ws=ws_vf)
+        dk.dk_decode_verify(b.ybar, Ainv_d, nvec_d, K, tol=1e-3, y=b.y, verdict=b.verdict, resid=b.resid,
+                            ws=b.ws_vf)
         if ev: ev[3].record()
         if fork:
             cur.wait_stream(side2)
         else:
-            dk.dk_wgrad(L, delta, B_d, gamma_d, xbar, K, dW=dW, scale=1.0, ws=ws_wg)
+            dk.dk_wgrad(L, b.delta, B_d, gamma_d, b.xbar, K, dW=b.dW, scale=1.0, ws=b.ws_wg)
         if ev: ev[4].record()
 
     for _ in range(args.warmup):
@@ -227,15 +239,27 @@ def main():
 
     # Third pass over the same K steps with every kernel launch bracketed by HIP
     # events on its launch stream (the brackets cost a few microseconds per
-    # launch, so this pass is not the one `value` is taken from).
+    # launch, so this pass is not the one `value` is taken from).  It cycles
+    # through several buffer sets: between two uses of a set, the other sets
+    # push more than the last-level cache's 256 MB through it, so a bandwidth
+    # figure from this pass is not flattered by data left over from the step
+    # before.  What one kernel of a step leaves behind for the next (the forward
+    # output read by decode+verify) stays: the path runs that way.
+    sets = [b0] + [Buffers() for _ in range(max(1, args.rotate) - 1)]
+    for b in sets[1:]:
+        step(b=b)
+    torch.cuda.synchronize()
     dk.dk_profile_enable(True)
     for i in range(args.steps):
-        step()
+        step(b=sets[i % len(sets)])
     torch.cuda.synchronize()
     dk.dk_profile_enable(False)
     kernels = dk.dk_profile_read()
 
-    assert int(verdict.sum().item()) == 0, "clean synthetic data must verify"
+    for b in sets:
+        assert int(b.verdict.sum().item()) == 0, "clean synthetic data must verify"
+        assert torch.equal(b.dW, dW) and torch.equal(b.y, y), "buffer sets disagree"
+    set_bytes = sum(t.numel() * t.element_size() for t in vars(b0).values())
     ms_per_step = wall / args.steps * 1e3
     stage_ms = {s: float(np.mean([e[i].elapsed_time(e[i + 1]) for e in events]))
                 for i, s in enumerate(stages)}
@@ -257,7 +281,8 @@ def main():
         "unit": "TFLOP/s", "frac": dom_tflops / MFMA_F32_PEAK_TFLOPS,
         "traffic": measured_traffic(args.workload, dom),
         "avg_launch_ms": dom_ms, "flop_per_launch": flop_fwd,
-        "timed": "HIP events around every launch of this kernel, %d eager launches after the timed region" % args.steps,
+        "timed": "HIP events around every launch of this kernel, %d eager launches after the timed region, "
+                 "cycling through %d buffer sets of %.0f MB" % (args.steps, len(sets), set_bytes / 1e6),
     }
     kname = {"encode": "encode", "decode_verify": "decode_verify", "delta_mix": "delta_mix"}
     hbm = {}
@@ -277,6 +302,8 @@ def main():
                               + (", weight gradient on a second branch" if args.fork else "")) if graph else "eager"},
         "pct_mfma_peak": 100.0 * tflops / MFMA_F32_PEAK_TFLOPS,
         "decoded_samples_per_s": G * K / (ms_per_step * 1e-3),
+        "decoded_samples_per_s_fwd_only": G * K / ((stage_ms["encode"] + stage_ms["fwd"]
+                                                    + stage_ms["decode_verify"]) * 1e-3),
         "effective_tflops": tflops * K / S,
         "stage_ms": stage_ms,
         "fwd_stage_tflops": flop_fwd / (stage_ms["fwd"] * 1e-3) / 1e12,

@@ -459,8 +459,9 @@ __global__ __launch_bounds__(C::NT) void contract_kernel(typename LA::Params pa,
     const int wn0 = (wave / C::WM) * (C::BN / C::WN);
 
     const int tiles = rp.tiles_m * rp.tiles_n;
-    const int split = blockIdx.x / tiles;
-    const int t = blockIdx.x - split * tiles;
+    const int bid = dk_xcd_block();
+    const int split = bid / tiles;
+    const int t = bid - split * tiles;
     const int tile_n = t / rp.tiles_m, tile_m = t - tile_n * rp.tiles_m;
     const int row0 = tile_m * C::BM, col0 = tile_n * C::BN;
 

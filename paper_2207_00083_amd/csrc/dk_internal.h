@@ -58,3 +58,18 @@ struct dk_prof_scope {
     int slot;
     hipStream_t st;
 };
+
+#ifdef __HIPCC__
+// Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD
+// b % 8) and each XCD has its own L2.  This maps the hardware index onto a
+// logical one so that every XCD works through one contiguous run of logical
+// indices: neighbouring tiles, which share operand panels, then share an L2.
+// The mapping is a bijection on [0, gridDim.x) for any grid size.
+static __device__ __forceinline__ int dk_xcd_block()
+{
+    const int nb = gridDim.x, b = blockIdx.x;
+    const int q = nb >> 3, rem = nb & 7;
+    const int xcd = b & 7, idx = b >> 3;
+    return (xcd < rem ? xcd * (q + 1) : rem * (q + 1) + (xcd - rem) * q) + idx;
+}
+#endif
