@@ -138,6 +138,48 @@ def masked_layer_inputs(rng, layer: Layer, K: int, batch: int, *, w_std=None,
     return dict(layer=layer, K=K, G=G, W=W, X=X, r=r, delta=delta, A=A, gamma=gamma)
 
 
+FIELD_P = (1 << 25) - 39     # the prime of the finite-field variant
+
+
+def field_layer_inputs(rng, layer: Layer, K: int, batch: int, *, w_std=None,
+                       delta_std=0.1, p=FIELD_P):
+    """Host arrays for the finite-field variant of one masked layer: fp32 W, X
+    and delta as in the real-valued workloads, and uniform draws from the
+    field for the noise r[G,...] in [0,p), the matrices A[G,S,S] in [0,p) and
+    the non-zero scalars gamma[G,S] in [1,p), all uint32.  A singular A has
+    probability about 1/p per draw and is not screened here (no arithmetic in
+    this module); the coefficient routines report it."""
+    if batch % K:
+        raise ValueError("batch must be a multiple of K")
+    G, S = batch // K, K + 2
+    if w_std is None:
+        w_std = float(np.sqrt(2.0 / layer.fan_in))
+    W = _normal(rng, layer.w_shape, w_std)
+    X = _normal(rng, (batch,) + layer.in_shape, 1.0)
+    r = rng.integers(0, p, size=(G,) + layer.in_shape, dtype=np.uint32)
+    delta = _normal(rng, (batch,) + layer.out_shape, delta_std)
+    A = rng.integers(0, p, size=(G, S, S), dtype=np.uint32)
+    gamma = rng.integers(1, p, size=(G, S), dtype=np.uint32)
+    return dict(layer=layer, K=K, G=G, W=W, X=X, r=r, delta=delta, A=A, gamma=gamma, p=p)
+
+
+def config5_field(seed=5, batch=1024, K=8, index=None):
+    """The classifier shapes of config5 for the finite-field variant."""
+    out = []
+    for li, L in enumerate(config5_layers()):
+        if index is not None and li != index:
+            continue
+        rng = np.random.default_rng([seed, li, 1])
+        out.append(field_layer_inputs(rng, L, K=K, batch=batch))
+    return out
+
+
+def config1_field(seed=0):
+    """Dense 256 -> 512, K=2, one group, finite-field variant."""
+    rng = np.random.default_rng([seed, 0, 1])
+    return field_layer_inputs(rng, linear(512, 256), K=2, batch=2, w_std=1.0 / 16.0, delta_std=1.0)
+
+
 # ----------------------------------------------------------------------
 # The five workloads
 # ----------------------------------------------------------------------

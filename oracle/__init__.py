@@ -34,6 +34,8 @@ def build(force: bool = False) -> str:
         cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
                "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
+    from . import field
+    field.build(force)
     return _LIB
 
 

@@ -1,0 +1,195 @@
+/*
+ * DarKnight finite-field ORACLE: test infrastructure, not product code.
+ *
+ * The paper's privacy guarantee is stated for a variant of the masked layer in
+ * which every value lives in the prime field F_p (section "Privacy Guarantee":
+ * "Quantization", "Random Numbers", and the algorithm "The pseudo-code for
+ * quantization").  This file is that variant written out with one remainder
+ * operation per arithmetic step: no blocking, no deferred reduction, no limb
+ * tricks.  Field elements are unsigned 32-bit integers in [0, p); every
+ * product is taken in 64 bits and reduced at once.
+ *
+ * Layout conventions equal those of the floating-point oracle: rows are
+ * samples, row-major; group g owns input rows gK..gK+K-1, noise row g and
+ * encoded rows gS..gS+S-1 with S = K+2; A[g][i][j] is the weight of source i
+ * (K inputs, the noise, a phantom all-zero source) in encoded row j.
+ *
+ * Shares no code with the HIP library.
+ */
+#include <math.h>
+#include <stdint.h>
+
+typedef uint32_t fe;    /* field element */
+typedef uint64_t u64;
+
+static inline fe mulmod(fe a, fe b, fe p) { return (fe)(((u64)a * (u64)b) % p); }
+static inline fe addmod(fe a, fe b, fe p) { return (fe)(((u64)a + (u64)b) % p); }
+
+/* Round, then Field (algorithm "The pseudo-code for quantization", procedures
+ * Round and Field).  Round takes floor(v) when the fractional part is below
+ * one half and floor(v)+1 otherwise, i.e. floor(v + 1/2) for either sign.
+ * The scaling by 2^l and the rounding are done in fp64, where they are exact
+ * for every fp32 input of interest.  Reading where the paper is silent:
+ * the rounded value is clamped to the int32 range and NaN maps to 0.
+ * Field maps an integer to its least non-negative residue. */
+void orf_quantize(const float *x, fe *xq, long count, int l, fe p)
+{
+    const double s = ldexp(1.0, l);
+#pragma omp parallel for schedule(static)
+    for (long i = 0; i < count; ++i) {
+        double v = floor((double)x[i] * s + 0.5);
+        if (v != v) v = 0.0;
+        if (v > 2147483647.0) v = 2147483647.0;
+        if (v < -2147483648.0) v = -2147483648.0;
+        int64_t z = (int64_t)v % (int64_t)p;
+        if (z < 0) z += p;
+        xq[i] = (fe)z;
+    }
+}
+
+/* Inverse of quantisation for a result that carries the factor 2^(2l) (a
+ * product of two quantised values): lift to the centred representative
+ * (subtract p from everything above p/2; section "Quantization"), then
+ * Round(v * 2^-l) * 2^-l (last step of the quantisation algorithm). */
+void orf_dequantize(const fe *yq, float *y, long count, int l, fe p)
+{
+    const double s = ldexp(1.0, -l);
+#pragma omp parallel for schedule(static)
+    for (long i = 0; i < count; ++i) {
+        int64_t v = yq[i];
+        if (v > (int64_t)(p / 2)) v -= p;
+        y[i] = (float)(floor((double)v * s + 0.5) * s);
+    }
+}
+
+/* Encoding in the field (Forward Pass, "DarKnight Encoding", with the extra
+ * integrity combination): xbar[gS+j] = sum_i A[g][i][j] xq[gK+i] + A[g][K][j] r[g]. */
+void orf_encode(const fe *xq, const fe *r, const fe *A, fe *xbar,
+                long G, long K, long n, fe p)
+{
+    const long S = K + 2;
+#pragma omp parallel for schedule(static)
+    for (long g = 0; g < G; ++g)
+        for (long j = 0; j < S; ++j)
+            for (long e = 0; e < n; ++e) {
+                fe acc = 0;
+                for (long i = 0; i < K; ++i)
+                    acc = addmod(acc, mulmod(A[(g * S + i) * S + j], xq[(g * K + i) * n + e], p), p);
+                acc = addmod(acc, mulmod(A[(g * S + K) * S + j], r[g * n + e], p), p);
+                xbar[(g * S + j) * n + e] = acc;
+            }
+}
+
+/* The linear operation the accelerator performs on encoded rows, over the
+ * field: Y[s][o] = sum_k W[o][k] X[s][k]  (mod p). */
+void orf_dense_fwd(const fe *W, const fe *X, fe *Y, long R, long M, long N, fe p)
+{
+#pragma omp parallel for schedule(static) collapse(2)
+    for (long s = 0; s < R; ++s)
+        for (long o = 0; o < M; ++o) {
+            fe acc = 0;
+            for (long k = 0; k < N; ++k)
+                acc = addmod(acc, mulmod(W[o * N + k], X[s * N + k], p), p);
+            Y[s * M + o] = acc;
+        }
+}
+
+/* Same, for a list of (s, o) output positions only. */
+void orf_dense_fwd_points(const fe *W, const fe *X, long M, long N, const long *pts,
+                          long npts, fe *out, fe p)
+{
+#pragma omp parallel for schedule(static)
+    for (long q = 0; q < npts; ++q) {
+        const long s = pts[2 * q], o = pts[2 * q + 1];
+        fe acc = 0;
+        for (long k = 0; k < N; ++k)
+            acc = addmod(acc, mulmod(W[o * N + k], X[s * N + k], p), p);
+        out[q] = acc;
+    }
+}
+
+/* Decoding in the field (Forward Pass, "DarKnight Decoding"; the quantisation
+ * algorithm applies it to the field values): yq[gK+i] = sum_j Ainv[g][j][i] ybar[gS+j]
+ * for i < ncols (ncols = K gives the outputs, K+2 every column). */
+void orf_decode(const fe *ybar, const fe *Ainv, fe *yq, long G, long K, long m,
+                long ncols, fe p)
+{
+    const long S = K + 2;
+#pragma omp parallel for schedule(static)
+    for (long g = 0; g < G; ++g)
+        for (long i = 0; i < ncols; ++i)
+            for (long e = 0; e < m; ++e) {
+                fe acc = 0;
+                for (long j = 0; j < S; ++j)
+                    acc = addmod(acc, mulmod(Ainv[(g * S + j) * S + i], ybar[(g * S + j) * m + e], p), p);
+                yq[(g * ncols + i) * m + e] = acc;
+            }
+}
+
+/* Integrity check (section "Computational Integrity"): the extra combination
+ * makes the system overdetermined; with nvec the last column of A^{-1},
+ * sum_j nvec[g][j] ybar[gS+j] must vanish in the field.  verdict[g] = 1 if any
+ * element's combination is non-zero or any ybar entry is not a field element. */
+void orf_verify(const fe *ybar, const fe *nvec, int *verdict, long G, long K, long m, fe p)
+{
+    const long S = K + 2;
+#pragma omp parallel for schedule(static)
+    for (long g = 0; g < G; ++g) {
+        int bad = 0;
+        for (long e = 0; e < m; ++e) {
+            fe acc = 0;
+            for (long j = 0; j < S; ++j) {
+                const fe v = ybar[(g * S + j) * m + e];
+                if (v >= p) bad = 1;
+                acc = addmod(acc, mulmod(nvec[g * S + j], v % p, p), p);
+            }
+            if (acc != 0) bad = 1;
+        }
+        verdict[g] = bad;
+    }
+}
+
+/* Gradient mixing (Backward Propagation: the accelerators see delta B^T, the
+ * enclave's gamma_j scales combination j):
+ * dtilde[gS+j] = gamma[g][j] * sum_i B[g][j][i] dq[gK+i]. */
+void orf_delta_mix(const fe *dq, const fe *B, const fe *gamma, fe *dtilde,
+                   long G, long K, long m, fe p)
+{
+    const long S = K + 2;
+#pragma omp parallel for schedule(static)
+    for (long g = 0; g < G; ++g)
+        for (long j = 0; j < S; ++j)
+            for (long e = 0; e < m; ++e) {
+                fe acc = 0;
+                for (long i = 0; i < K; ++i)
+                    acc = addmod(acc, mulmod(B[(g * S + j) * K + i], dq[(g * K + i) * m + e], p), p);
+                dtilde[(g * S + j) * m + e] = mulmod(gamma[g * S + j], acc, p);
+            }
+}
+
+/* Weight-gradient contraction over encoded rows, over the field:
+ * dWq[o][k] = sum_rho D[rho][o] X[rho][k]. */
+void orf_dense_wgrad(const fe *D, const fe *X, fe *dWq, long R, long M, long N, fe p)
+{
+#pragma omp parallel for schedule(static) collapse(2)
+    for (long o = 0; o < M; ++o)
+        for (long k = 0; k < N; ++k) {
+            fe acc = 0;
+            for (long s = 0; s < R; ++s)
+                acc = addmod(acc, mulmod(D[s * M + o], X[s * N + k], p), p);
+            dWq[o * N + k] = acc;
+        }
+}
+
+void orf_dense_wgrad_points(const fe *D, const fe *X, long R, long M, long N,
+                            const long *pts, long npts, fe *out, fe p)
+{
+#pragma omp parallel for schedule(static)
+    for (long q = 0; q < npts; ++q) {
+        const long o = pts[2 * q], k = pts[2 * q + 1];
+        fe acc = 0;
+        for (long s = 0; s < R; ++s)
+            acc = addmod(acc, mulmod(D[s * M + o], X[s * N + k], p), p);
+        out[q] = acc;
+    }
+}

@@ -1,0 +1,233 @@
+"""DarKnight finite-field ORACLE (Python side): test infrastructure, not product code.
+
+The variant of the masked layer in which all values live in the prime field
+F_p, p = 2^25 - 39, with l fractional bits of fixed point (section "Privacy
+Guarantee": "Quantization", "Random Numbers", algorithm "The pseudo-code for
+quantization").  The element-wise loops are in ``dk_field_oracle.c``; this
+module marshals numpy arrays and derives the per-group coefficient matrices
+with exact Python integers.
+
+Only the tests, the smoke check and the benchmark's ``cpu_baseline`` leg may
+import this module.  It imports nothing from the HIP library or its binding.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+P = (1 << 25) - 39          # section "Privacy Guarantee": the largest 25-bit prime
+L_BITS = 8                  # fractional bits used for the paper's experiments
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dk_field_oracle.c")
+_LIB = os.path.join(_HERE, "libdk_field_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.run(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+                        "-o", _LIB, _SRC, "-lm"], check=True)
+    return _LIB
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+    return _lib
+
+
+def _u(a):
+    return np.ascontiguousarray(a, dtype=np.uint32)
+
+
+def _p(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _l(v):
+    return C.c_long(int(v))
+
+
+def _fe(p):
+    return C.c_uint32(int(p))
+
+
+# ----------------------------------------------------------------------
+# Coefficients, exact integer arithmetic
+# ----------------------------------------------------------------------
+
+def inv_mod_matrix(A, p=P):
+    """Inverse of a square integer matrix over F_p by Gauss-Jordan elimination
+    on Python integers; the scalar inverse is Fermat's a^(p-2).  Raises
+    ValueError for a singular matrix."""
+    n = len(A)
+    M = [[int(A[i][j]) % p for j in range(n)] + [int(i == j) for j in range(n)] for i in range(n)]
+    for c in range(n):
+        piv = next((r for r in range(c, n) if M[r][c]), None)
+        if piv is None:
+            raise ValueError("matrix is singular over F_p")
+        M[c], M[piv] = M[piv], M[c]
+        inv = pow(M[c][c], p - 2, p)
+        M[c] = [v * inv % p for v in M[c]]
+        for r in range(n):
+            if r != c and M[r][c]:
+                f = M[r][c]
+                M[r] = [(v - f * w) % p for v, w in zip(M[r], M[c])]
+    return [row[n:] for row in M]
+
+
+def coefficients(A, gamma, p=P):
+    """A[G,S,S], gamma[G,S] (field elements; gamma non-zero) ->
+    (Ainv[G,S,S], nvec[G,S], B[G,S,K]) as uint32.
+
+    Same construction as in the real-valued path, over the field
+    ("Random Numbers": A, B, Gamma are field elements and encoding and decoding
+    are defined over F_p): Ainv = A^{-1}; its first K columns decode, its last
+    column is the combination that must vanish (section "Computational
+    Integrity"), and B[j][i] = Ainv[j][i] / gamma_j satisfies
+    B^T Gamma A_ext^T = [I_K | 0] (Backward Propagation)."""
+    A = np.asarray(A)
+    gamma = np.asarray(gamma)
+    G, S, _ = A.shape
+    K = S - 2
+    Ainv = np.zeros((G, S, S), dtype=np.uint32)
+    nvec = np.zeros((G, S), dtype=np.uint32)
+    B = np.zeros((G, S, K), dtype=np.uint32)
+    for g in range(G):
+        inv = inv_mod_matrix(A[g].tolist(), p)
+        for j in range(S):
+            gi = pow(int(gamma[g, j]), p - 2, p)
+            if int(gamma[g, j]) % p == 0:
+                raise ValueError("gamma must be non-zero")
+            for i in range(S):
+                Ainv[g, j, i] = inv[j][i]
+            nvec[g, j] = inv[j][S - 1]
+            for i in range(K):
+                B[g, j, i] = inv[j][i] * gi % p
+    return Ainv, nvec, B
+
+
+# ----------------------------------------------------------------------
+# Steps
+# ----------------------------------------------------------------------
+
+def quantize(x, l=L_BITS, p=P):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint32)
+    _L().orf_quantize(_p(x), _p(out), _l(x.size), C.c_int(l), _fe(p))
+    return out
+
+
+def dequantize(yq, l=L_BITS, p=P):
+    yq = _u(yq)
+    out = np.empty(yq.shape, dtype=np.float32)
+    _L().orf_dequantize(_p(yq), _p(out), _l(yq.size), C.c_int(l), _fe(p))
+    return out
+
+
+def encode(xq, r, A, p=P):
+    xq, r, A = _u(xq), _u(r), _u(A)
+    G, S, _ = A.shape
+    K = S - 2
+    feat = xq.shape[1:]
+    n = int(np.prod(feat))
+    assert xq.shape[0] == G * K and r.shape[0] == G
+    out = np.empty((G * S,) + feat, dtype=np.uint32)
+    _L().orf_encode(_p(xq), _p(r), _p(A), _p(out), _l(G), _l(K), _l(n), _fe(p))
+    return out
+
+
+def dense_fwd(Wq, X, p=P):
+    Wq, X = _u(Wq), _u(X)
+    M, N = Wq.shape
+    R = X.shape[0]
+    Y = np.empty((R, M), dtype=np.uint32)
+    _L().orf_dense_fwd(_p(Wq), _p(X), _p(Y), _l(R), _l(M), _l(N), _fe(p))
+    return Y
+
+
+def dense_fwd_points(Wq, X, pts, p=P):
+    Wq, X = _u(Wq), _u(X)
+    pts = np.ascontiguousarray(pts, dtype=np.int64).reshape(-1, 2)
+    out = np.empty(len(pts), dtype=np.uint32)
+    _L().orf_dense_fwd_points(_p(Wq), _p(X), _l(Wq.shape[0]), _l(Wq.shape[1]), _p(pts),
+                              _l(len(pts)), _p(out), _fe(p))
+    return out
+
+
+def decode(ybar, Ainv, ncols=None, p=P):
+    ybar, Ainv = _u(ybar), _u(Ainv)
+    G, S, _ = Ainv.shape
+    K = S - 2
+    ncols = K if ncols is None else ncols
+    feat = ybar.shape[1:]
+    m = int(np.prod(feat))
+    out = np.empty((G * ncols,) + feat, dtype=np.uint32)
+    _L().orf_decode(_p(ybar), _p(Ainv), _p(out), _l(G), _l(K), _l(m), _l(ncols), _fe(p))
+    return out
+
+
+def verify(ybar, nvec, p=P):
+    ybar, nvec = _u(ybar), _u(nvec)
+    G, S = nvec.shape
+    m = int(np.prod(ybar.shape[1:]))
+    verdict = np.zeros(G, dtype=np.int32)
+    _L().orf_verify(_p(ybar), _p(nvec), _p(verdict), _l(G), _l(S - 2), _l(m), _fe(p))
+    return verdict
+
+
+def delta_mix(dq, B, gamma, p=P):
+    dq, B, gamma = _u(dq), _u(B), _u(gamma)
+    G, S, K = B.shape
+    feat = dq.shape[1:]
+    m = int(np.prod(feat))
+    out = np.empty((G * S,) + feat, dtype=np.uint32)
+    _L().orf_delta_mix(_p(dq), _p(B), _p(gamma), _p(out), _l(G), _l(K), _l(m), _fe(p))
+    return out
+
+
+def dense_wgrad(D, X, p=P):
+    D, X = _u(D), _u(X)
+    R, M = D.shape
+    N = X.shape[1]
+    out = np.empty((M, N), dtype=np.uint32)
+    _L().orf_dense_wgrad(_p(D), _p(X), _p(out), _l(R), _l(M), _l(N), _fe(p))
+    return out
+
+
+def dense_wgrad_points(D, X, pts, p=P):
+    D, X = _u(D), _u(X)
+    pts = np.ascontiguousarray(pts, dtype=np.int64).reshape(-1, 2)
+    out = np.empty(len(pts), dtype=np.uint32)
+    _L().orf_dense_wgrad_points(_p(D), _p(X), _l(D.shape[0]), _l(D.shape[1]), _l(X.shape[1]),
+                                _p(pts), _l(len(pts)), _p(out), _fe(p))
+    return out
+
+
+def masked_dense_layer(W, X, r, delta, A, gamma, l=L_BITS, p=P):
+    """The staged field path for a dense layer, in the order of the
+    quantisation algorithm: quantise W and X, encode, multiply on encodings,
+    verify, decode, de-quantise; then the masked weight gradient from the
+    quantised output gradients.
+
+    W[M,N], X[G*K,N], delta[G*K,M] are fp32; r[G,N], A[G,S,S], gamma[G,S] are
+    field elements.  Returns dict(Wq, Xq, Xbar, Ybar, verdict, Yq, Y, Dq,
+    Dtilde, dWq, dW)."""
+    Ainv, nvec, B = coefficients(A, gamma, p)
+    Wq, Xq = quantize(W, l, p), quantize(X, l, p)
+    Xbar = encode(Xq, r, A, p)
+    Ybar = dense_fwd(Wq, Xbar, p)
+    verdict = verify(Ybar, nvec, p)
+    Yq = decode(Ybar, Ainv, None, p)
+    Y = dequantize(Yq, l, p)
+    Dq = quantize(delta, l, p)
+    Dtilde = delta_mix(Dq, B, gamma, p)
+    dWq = dense_wgrad(Dtilde, Xbar, p)
+    dW = dequantize(dWq, l, p)
+    return dict(Wq=Wq, Xq=Xq, Xbar=Xbar, Ybar=Ybar, verdict=verdict, Yq=Yq, Y=Y, Dq=Dq,
+                Dtilde=Dtilde, dWq=dWq, dW=dW)
