@@ -1,0 +1,116 @@
+/*
+ * darknight_field.h -- C ABI of the finite-field variant of the masked layer
+ * (MI355X / gfx950), dense layers.
+ *
+ * The paper's privacy statement holds for a version of the scheme in which
+ * every value is an element of the prime field F_p, p = 2^25 - 39 (section
+ * "Privacy Guarantee", paragraphs "Quantization" and "Random Numbers", and the
+ * algorithm "The pseudo-code for quantization"): inputs, weights and output
+ * gradients are turned into fixed point with l fractional bits
+ * (Round(v * 2^l): floor when the fractional part is below one half, floor + 1
+ * otherwise) and mapped to their least non-negative residue (Field); the
+ * noise, the matrices A and B and the scalars gamma are uniform field
+ * elements; encoding, the layer's linear operation, decoding and the
+ * integrity check are exact arithmetic modulo p.  Decoded values are lifted
+ * to the centred representative (subtract p above p/2) and brought back to
+ * floating point by Round(v * 2^-l) * 2^-l.
+ *
+ * All conventions of darknight.h hold (K, S = K+2, G, R = G*S, row layout,
+ * meaning of A, "device" and "host" pointers, streams, error channel,
+ * `dk_layer`).  Field elements are uint32_t in [0, DKF_P).  Readings where the
+ * paper is silent: a rounded value is clamped to the int32 range before Field
+ * and NaN becomes 0; an encoded result that is not a field element (>= p)
+ * counts as corrupted.
+ *
+ * Results are exact, so they do not depend on launch configuration.
+ */
+#ifndef DARKNIGHT_FIELD_H
+#define DARKNIGHT_FIELD_H
+
+#include <stddef.h>
+#include <stdint.h>
+#include "darknight.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DKF_P 33554393u      /* 2^25 - 39 */
+#define DKF_MAX_L 12         /* largest number of fractional bits accepted */
+
+/* Trusted-side coefficient derivation over the field (host arithmetic).
+ * From uniform draws A[G][S][S] and gamma[G][S] (host, gamma non-zero):
+ *   Ainv = A^{-1} mod p            [G][S][S]  (decoding, Forward Pass);
+ *   nvec = last column of Ainv     [G][S]     (the combination of the K+2
+ *                                             results that must vanish,
+ *                                             section Computational Integrity);
+ *   B[j][i] = Ainv[j][i]/gamma[j]  [G][S][K]  (B^T Gamma A^T = [I|0],
+ *                                             Backward Propagation).
+ * Outputs may be NULL to skip them.  DK_ERR_SINGULAR if some A[g] is singular
+ * modulo p or a gamma is 0; DK_ERR_SHAPE if an entry is not below p. */
+dk_status dkf_coeffs(const uint32_t *A, const uint32_t *gamma, int G, int K,
+                     uint32_t *Ainv, uint32_t *nvec, uint32_t *B);
+
+/* Field(Round(x * 2^l)) for `count` floats (quantisation algorithm, lines for
+ * W_q and X_q).  x, xq device.  Used for the weights; dkf_encode and dkf_wgrad
+ * quantise their float operand themselves. */
+dk_status dkf_quantize(const float *x, uint32_t *xq, long long count, int l, void *stream);
+
+/* Centred lift, then Round(v * 2^-l) * 2^-l (last step of the quantisation
+ * algorithm), for `count` field elements.  yq, y device. */
+dk_status dkf_dequantize(const uint32_t *yq, float *y, long long count, int l, void *stream);
+
+/* Quantise and encode (quantisation algorithm, X_q then Encode; Forward Pass
+ * encoding equation with the extra integrity combination), over the field:
+ *   xbar[gS+j][e] = sum_{i<K} A[g][i][j] Xq[gK+i][e] + A[g][K][j] r[g][e]  mod p
+ * with Xq = Field(Round(x * 2^l)).  x[G*K][n] float, r[G][n], A[G][S][S] field
+ * elements (all device) -> xbar[G*S][n] (device). */
+dk_status dkf_encode(const float *x, const uint32_t *r, const uint32_t *A, uint32_t *xbar,
+                     int G, int K, long long n, int l, void *stream);
+
+/* The accelerator's linear operation on encoded rows, over the field
+ * (quantisation algorithm, the step in which the accelerators apply W_q to
+ * the encodings):
+ *   ybar[rho][o] = sum_k Wq[o][k] xbar[rho][k]  mod p.
+ * Wq[M][N], xbar[R][N] -> ybar[R][M], all device, any R >= 1.  Workspace:
+ * dkf_fwd_workspace_bytes(M, N, R), 256-byte aligned. */
+dk_status dkf_linear_fwd(const uint32_t *Wq, const uint32_t *xbar, uint32_t *ybar,
+                         int M, int N, int R, void *ws, size_t ws_bytes, void *stream);
+
+/* Integrity check and decoding of the forward results in one pass over ybar
+ * (section Computational Integrity; quantisation algorithm, Y_q and Y):
+ *   t[e]      = sum_j nvec[g][j] ybar[gS+j][e]  mod p;
+ *   verdict[g] = 1 if some t[e] != 0 or some ybar entry of the group is >= p,
+ *                else 0  (exact: no tolerance);
+ *   Yq[gK+i][e] = sum_j Ainv[g][j][i] ybar[gS+j][e]  mod p,  i < K;
+ *   y = Round(lift(Yq) * 2^-l) * 2^-l.
+ * ybar[G*S][m], Ainv[G][S][S], nvec[G][S] -> y[G*K][m] float, verdict[G] int
+ * (all device); yq[G*K][m] (device) receives the field values if not NULL. */
+dk_status dkf_decode_verify(const uint32_t *ybar, const uint32_t *Ainv, const uint32_t *nvec,
+                            float *y, uint32_t *yq, int *verdict,
+                            int G, int K, long long m, int l, void *stream);
+
+/* Masked weight gradient of a dense layer over the field (Backward
+ * Propagation: the accelerator forms delta-bar = delta B^T and the
+ * per-encoding products with the stored xbar; gamma_j weights term j):
+ *   Dq = Field(Round(delta * 2^l));
+ *   dtilde[gS+j] = gamma[g][j] * sum_{i<K} B[g][j][i] Dq[gK+i]   mod p;
+ *   dWq[o][k] = sum_rho dtilde[rho][o] xbar[rho][k]               mod p;
+ *   dW = (accumulate ? dW : 0) + scale * Round(lift(dWq) * 2^-l) * 2^-l.
+ * L must be a dense layer (DK_ERR_UNSUPPORTED otherwise).  delta[G*K][M]
+ * float, B[G][S][K], gamma[G][S], xbar[G*S][N] -> dW[M][N] float, all device.
+ * dwq[M][N] (device) receives the field values if not NULL.  Workspace:
+ * dkf_wgrad_workspace_bytes(L, G, K), 256-byte aligned. */
+dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint32_t *B,
+                    const uint32_t *gamma, const uint32_t *xbar, float *dW, uint32_t *dwq,
+                    int G, int K, int l, float scale, int accumulate,
+                    void *ws, size_t ws_bytes, void *stream);
+
+/* Workspace sizes in bytes (0 for invalid arguments). */
+size_t dkf_fwd_workspace_bytes(int M, int N, int R);
+size_t dkf_wgrad_workspace_bytes(const dk_layer *L, int G, int K);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

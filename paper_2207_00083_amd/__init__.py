@@ -1,7 +1,8 @@
 """MI355X-native masked-layer hot path of DarKnight (matrix masking).
 
 The product is the C-ABI library ``libdarknight.so`` (hand-written HIP for
-gfx950, declared in ``include/darknight.h``).  This package is the thin
+gfx950, declared in ``include/darknight.h`` and, for the finite-field
+variant, ``include/darknight_field.h``).  This package is the thin
 Python binding over it: same entry-point names, argument marshalling only.
 PyTorch is used for device memory and streams, nothing else.
 """
@@ -11,7 +12,13 @@ from .binding import (DkError, DkLayer, lib_path, load, dk_version, dk_status_st
                       dk_decode_verify, dk_profile_enable, dk_profile_read,
                       DK_OP_FWD, DK_OP_WGRAD, DK_OP_VERIFY, DK_MAX_K)
 
-__all__ = ["DkError", "DkLayer", "lib_path", "load", "dk_version", "dk_status_str",
+from .field import (DKF_P, DKF_L, dkf_coeffs, dkf_quantize, dkf_dequantize, dkf_encode, dkf_linear_fwd,
+                    dkf_decode_verify, dkf_wgrad, dkf_fwd_workspace_bytes, dkf_wgrad_workspace_bytes)
+
+__all__ = ["DKF_P", "DKF_L", "dkf_coeffs", "dkf_quantize", "dkf_dequantize", "dkf_encode",
+           "dkf_linear_fwd", "dkf_decode_verify", "dkf_wgrad", "dkf_fwd_workspace_bytes",
+           "dkf_wgrad_workspace_bytes",
+           "DkError", "DkLayer", "lib_path", "load", "dk_version", "dk_status_str",
            "dk_workspace_bytes", "dk_layer_in_len", "dk_layer_out_len", "dk_coeffs",
            "dk_encode", "dk_linear_fwd", "dk_conv_fwd", "dk_wgrad", "dk_decode", "dk_verify",
            "dk_decode_verify", "dk_profile_enable", "dk_profile_read",

@@ -74,6 +74,15 @@ def load():
         "dk_decode": (ip, [vp, vp, vp, ip, ip, ll, vp]),
         "dk_verify": (ip, [vp, vp, fl, vp, vp, ip, ip, ll, vp, sz, vp]),
         "dk_decode_verify": (ip, [vp, vp, vp, fl, vp, vp, vp, ip, ip, ll, vp, sz, vp]),
+        "dkf_coeffs": (ip, [vp, vp, ip, ip, vp, vp, vp]),
+        "dkf_quantize": (ip, [vp, vp, ll, ip, vp]),
+        "dkf_dequantize": (ip, [vp, vp, ll, ip, vp]),
+        "dkf_encode": (ip, [vp, vp, vp, vp, ip, ip, ll, ip, vp]),
+        "dkf_linear_fwd": (ip, [vp, vp, vp, ip, ip, ip, vp, sz, vp]),
+        "dkf_decode_verify": (ip, [vp, vp, vp, vp, vp, vp, ip, ip, ll, ip, vp]),
+        "dkf_wgrad": (ip, [LP, vp, vp, vp, vp, vp, vp, ip, ip, ip, fl, ip, vp, sz, vp]),
+        "dkf_fwd_workspace_bytes": (sz, [ip, ip, ip]),
+        "dkf_wgrad_workspace_bytes": (sz, [LP, ip, ip]),
         "dk_profile_enable": (ip, [ip]),
         "dk_profile_read": (ip, [ip, C.c_char_p, ip, C.POINTER(C.c_double), C.POINTER(ip)]),
     }

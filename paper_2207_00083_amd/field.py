@@ -1,0 +1,166 @@
+"""ctypes binding of the finite-field entry points (include/darknight_field.h).
+
+Argument marshalling only.  Field elements travel as 4-byte integer tensors:
+torch.int32 on the device (every element is below 2^25, so the bit pattern
+equals the uint32 the C ABI names) and numpy uint32 on the host.
+"""
+from __future__ import annotations
+
+import ctypes as C
+
+import numpy as np
+
+from .binding import DkLayer, _check, _dev, _ptr, _stream, _torch, _workspace, load
+
+DKF_P = (1 << 25) - 39
+DKF_L = 8
+
+
+def _fe(t, name):
+    torch = _torch()
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a device tensor" % name)
+    if t.dtype not in (torch.int32, torch.uint32) or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous 4-byte integer tensor" % name)
+    return t
+
+
+def _new_fe(shape, like):
+    torch = _torch()
+    return torch.empty(shape, dtype=torch.int32, device=like.device)
+
+
+def dkf_coeffs(A, gamma):
+    """Host arrays A[G,S,S], gamma[G,S] (uint32 field elements) ->
+    host Ainv[G,S,S], nvec[G,S], B[G,S,K] (uint32)."""
+    A = np.ascontiguousarray(A, dtype=np.uint32)
+    gamma = np.ascontiguousarray(gamma, dtype=np.uint32)
+    G, S, _ = A.shape
+    K = S - 2
+    Ainv = np.empty((G, S, S), dtype=np.uint32)
+    nvec = np.empty((G, S), dtype=np.uint32)
+    B = np.empty((G, S, K), dtype=np.uint32)
+    _check(load().dkf_coeffs(A.ctypes.data, gamma.ctypes.data, G, K, Ainv.ctypes.data,
+                             nvec.ctypes.data, B.ctypes.data), "dkf_coeffs")
+    return Ainv, nvec, B
+
+
+def dkf_quantize(x, l=DKF_L, xq=None, stream=None):
+    x = _dev(x, "x")
+    if xq is None:
+        xq = _new_fe(tuple(x.shape), x)
+    _fe(xq, "xq")
+    if xq.numel() != x.numel():
+        raise ValueError("dkf_quantize: xq has the wrong size")
+    _check(load().dkf_quantize(_ptr(x), _ptr(xq), x.numel(), int(l), _stream(stream)), "dkf_quantize")
+    return xq
+
+
+def dkf_dequantize(yq, l=DKF_L, y=None, stream=None):
+    torch = _torch()
+    yq = _fe(yq, "yq")
+    if y is None:
+        y = torch.empty(tuple(yq.shape), dtype=torch.float32, device=yq.device)
+    _dev(y, "y")
+    if y.numel() != yq.numel():
+        raise ValueError("dkf_dequantize: y has the wrong size")
+    _check(load().dkf_dequantize(_ptr(yq), _ptr(y), yq.numel(), int(l), _stream(stream)), "dkf_dequantize")
+    return y
+
+
+def dkf_encode(x, r, A, K, l=DKF_L, xbar=None, stream=None):
+    """x[G*K, ...] float, r[G, ...], A[G,S,S] field elements (device) -> xbar[G*S, ...]."""
+    x, r, A = _dev(x, "x"), _fe(r, "r"), _fe(A, "A")
+    G, S = r.shape[0], K + 2
+    n = x[0].numel()
+    if x.shape[0] != G * K or tuple(A.shape) != (G, S, S) or r[0].numel() != n:
+        raise ValueError("dkf_encode: inconsistent shapes")
+    if xbar is None:
+        xbar = _new_fe((G * S,) + tuple(x.shape[1:]), x)
+    _fe(xbar, "xbar")
+    if xbar.numel() != G * S * n:
+        raise ValueError("dkf_encode: xbar has the wrong size")
+    _check(load().dkf_encode(_ptr(x), _ptr(r), _ptr(A), _ptr(xbar), G, K, n, int(l), _stream(stream)),
+           "dkf_encode")
+    return xbar
+
+
+def dkf_fwd_workspace_bytes(M, N, R) -> int:
+    return int(load().dkf_fwd_workspace_bytes(int(M), int(N), int(R)))
+
+
+def dkf_wgrad_workspace_bytes(layer, G, K) -> int:
+    return int(load().dkf_wgrad_workspace_bytes(C.byref(DkLayer.of(layer)), int(G), int(K)))
+
+
+def dkf_linear_fwd(Wq, xbar, ybar=None, ws=None, stream=None):
+    """Wq[M,N], xbar[R,N] field elements (device) -> ybar[R,M]."""
+    Wq, xbar = _fe(Wq, "Wq"), _fe(xbar, "xbar")
+    M, N = Wq.shape
+    R = xbar.shape[0]
+    if xbar[0].numel() != N:
+        raise ValueError("dkf_linear_fwd: inconsistent shapes")
+    if ybar is None:
+        ybar = _new_fe((R, M), Wq)
+    _fe(ybar, "ybar")
+    if ybar.numel() != R * M:
+        raise ValueError("dkf_linear_fwd: ybar has the wrong size")
+    if ws is None:
+        ws = _workspace(dkf_fwd_workspace_bytes(M, N, R), Wq)
+    _check(load().dkf_linear_fwd(_ptr(Wq), _ptr(xbar), _ptr(ybar), M, N, R, _ptr(ws), ws.numel(),
+                                 _stream(stream)), "dkf_linear_fwd")
+    return ybar
+
+
+def dkf_decode_verify(ybar, Ainv, nvec, K, l=DKF_L, y=None, yq=None, verdict=None, want_yq=False,
+                      stream=None):
+    """Returns (y float, yq or None, verdict int32)."""
+    torch = _torch()
+    ybar, Ainv, nvec = _fe(ybar, "ybar"), _fe(Ainv, "Ainv"), _fe(nvec, "nvec")
+    G, S = Ainv.shape[0], K + 2
+    if tuple(Ainv.shape) != (G, S, S) or tuple(nvec.shape) != (G, S) or ybar.shape[0] != G * S:
+        raise ValueError("dkf_decode_verify: inconsistent shapes")
+    m = ybar[0].numel()
+    if y is None:
+        y = torch.empty((G * K,) + tuple(ybar.shape[1:]), dtype=torch.float32, device=ybar.device)
+    _dev(y, "y")
+    if yq is None and want_yq:
+        yq = _new_fe(tuple(y.shape), ybar)
+    if yq is not None:
+        _fe(yq, "yq")
+    if y.numel() != G * K * m or (yq is not None and yq.numel() != G * K * m):
+        raise ValueError("dkf_decode_verify: output has the wrong size")
+    if verdict is None:
+        verdict = torch.empty(G, dtype=torch.int32, device=ybar.device)
+    _check(load().dkf_decode_verify(_ptr(ybar), _ptr(Ainv), _ptr(nvec), _ptr(y), _ptr(yq), _ptr(verdict),
+                                    G, K, m, int(l), _stream(stream)), "dkf_decode_verify")
+    return y, yq, verdict
+
+
+def dkf_wgrad(layer, delta, B, gamma, xbar, K, l=DKF_L, dW=None, dwq=None, want_dwq=False, scale=1.0,
+              accumulate=False, ws=None, stream=None):
+    """delta[G*K,M] float, B[G,S,K], gamma[G,S], xbar[G*S,N] (device) -> (dW float, dwq or None)."""
+    torch = _torch()
+    lay = DkLayer.of(layer)
+    delta, B, gamma, xbar = _dev(delta, "delta"), _fe(B, "B"), _fe(gamma, "gamma"), _fe(xbar, "xbar")
+    G, S = gamma.shape
+    if (S != K + 2 or tuple(B.shape) != (G, S, K) or delta.numel() != G * K * lay.M
+            or xbar.numel() != G * S * lay.N):
+        raise ValueError("dkf_wgrad: inconsistent shapes")
+    if dW is None:
+        if accumulate:
+            raise ValueError("dkf_wgrad: accumulate needs an existing dW")
+        dW = torch.empty((lay.M, lay.N), dtype=torch.float32, device=delta.device)
+    _dev(dW, "dW")
+    if dwq is None and want_dwq:
+        dwq = _new_fe((lay.M, lay.N), delta)
+    if dwq is not None:
+        _fe(dwq, "dwq")
+    if dW.numel() != lay.M * lay.N or (dwq is not None and dwq.numel() != lay.M * lay.N):
+        raise ValueError("dkf_wgrad: output has the wrong size")
+    if ws is None:
+        ws = _workspace(dkf_wgrad_workspace_bytes(lay, G, K), delta)
+    _check(load().dkf_wgrad(C.byref(lay), _ptr(delta), _ptr(B), _ptr(gamma), _ptr(xbar), _ptr(dW),
+                            _ptr(dwq), G, K, int(l), float(scale), int(bool(accumulate)), _ptr(ws),
+                            ws.numel(), _stream(stream)), "dkf_wgrad")
+    return dW, dwq

@@ -1,5 +1,5 @@
-"""The C-ABI library loads, exports every symbol include/darknight.h declares
-and rejects bad arguments on the host, before anything is launched (so these
+"""The C-ABI library loads, exports every symbol include/*.h declares and
+rejects bad arguments on the host, before anything is launched (so these
 run without a GPU)."""
 import ctypes as C
 import os
@@ -25,15 +25,22 @@ def dk():
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "darknight.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(dk_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for f in sorted(os.listdir(inc)):
+        if f.endswith(".h"):
+            text = open(os.path.join(inc, f)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(dkf?_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(dk):
     names = declared_symbols()
     for must in ("dk_encode", "dk_linear_fwd", "dk_conv_fwd", "dk_wgrad", "dk_decode", "dk_verify",
-                 "dk_coeffs", "dk_workspace_bytes"):
+                 "dk_coeffs", "dk_workspace_bytes", "dkf_coeffs", "dkf_quantize", "dkf_dequantize",
+                 "dkf_encode", "dkf_linear_fwd", "dkf_decode_verify", "dkf_wgrad",
+                 "dkf_fwd_workspace_bytes", "dkf_wgrad_workspace_bytes"):
         assert must in names
     lib = C.CDLL(dk.lib_path())
     for n in names:
@@ -127,3 +134,47 @@ def test_product_does_not_import_the_oracle():
         for f in files:
             if f.endswith((".py", ".hip", ".cpp", ".h")):
                 assert "oracle" not in open(os.path.join(root, f)).read().lower().replace("no fallback", ""), f
+
+
+def test_field_errors_before_launch(dk):
+    lib = dk.load()
+    one, null = C.c_void_p(256), C.c_void_p(0)
+    assert lib.dkf_quantize(null, one, 8, 8, null) == 1
+    assert lib.dkf_quantize(one, one, 0, 8, null) == 2
+    assert lib.dkf_quantize(one, one, 8, 13, null) == 2
+    assert lib.dkf_dequantize(one, one, 8, -1, null) == 2
+    assert lib.dkf_encode(one, one, one, null, 1, 2, 8, 8, null) == 1
+    assert lib.dkf_encode(one, one, one, one, 1, 17, 8, 8, null) == 2
+    assert lib.dkf_encode(one, C.c_void_p(258), one, one, 1, 2, 8, 8, null) == 4
+    assert lib.dkf_linear_fwd(one, one, one, 4, 4, 4, null, 0, null) == 5
+    assert lib.dkf_linear_fwd(one, one, one, 4, 4, 4, one, 16, null) == 5
+    assert lib.dkf_linear_fwd(one, one, one, 0, 4, 4, one, 1 << 30, null) == 2
+    assert lib.dkf_decode_verify(one, one, one, one, null, null, 1, 2, 8, 8, null) == 1
+    lin = dk.DkLayer.of(dk_inputs.linear(4, 4))
+    conv = dk.DkLayer.of(dk_inputs.conv(4, 4, 8, 8, 3))
+    assert lib.dkf_wgrad(C.byref(conv), one, one, one, one, one, null, 1, 2, 8, 1.0, 0, one, 1 << 30, null) == 3
+    assert lib.dkf_wgrad(C.byref(lin), one, one, one, one, one, null, 1, 2, 8, 1.0, 0, one, 64, null) == 5
+    assert dk.dkf_fwd_workspace_bytes(4, 4, 4) > 0 and dk.dkf_fwd_workspace_bytes(0, 4, 4) == 0
+    assert dk.dkf_wgrad_workspace_bytes(dk_inputs.linear(4, 4), 1, 2) > 0
+
+
+def test_field_coeffs_match_the_oracle_and_report_singular(dk):
+    from oracle import field as F
+    rng = np.random.default_rng(3)
+    for K in (1, 4, 16):
+        S = K + 2
+        A = rng.integers(0, F.P, size=(3, S, S), dtype=np.uint32)
+        gamma = rng.integers(1, F.P, size=(3, S), dtype=np.uint32)
+        for got, want in zip(dk.dkf_coeffs(A, gamma), F.coefficients(A, gamma)):
+            assert np.array_equal(got, want)
+    A = np.ones((1, 3, 3), dtype=np.uint32)
+    with pytest.raises(dk.DkError) as e:
+        dk.dkf_coeffs(A, np.ones((1, 3), dtype=np.uint32))
+    assert e.value.status == 7
+    A = np.eye(3, dtype=np.uint32)[None]
+    with pytest.raises(dk.DkError) as e:
+        dk.dkf_coeffs(A, np.array([[1, 0, 1]], dtype=np.uint32))
+    assert e.value.status == 7
+    with pytest.raises(dk.DkError) as e:
+        dk.dkf_coeffs(A * np.uint32(F.P), np.ones((1, 3), dtype=np.uint32))
+    assert e.value.status == 2

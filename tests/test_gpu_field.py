@@ -1,0 +1,217 @@
+"""GPU parity of the finite-field variant against the field oracle, through
+the C ABI.  Everything is integer arithmetic modulo p, so every comparison is
+exact; the float outputs are exact too (a rounded integer times 2^-l)."""
+import numpy as np
+import pytest
+
+import dk_inputs
+from oracle import field as F
+
+pytestmark = pytest.mark.gpu
+
+P = F.P
+
+
+@pytest.fixture(scope="module")
+def dk():
+    import torch
+    import paper_2207_00083_amd as m
+    m.load()
+    assert torch.cuda.is_available()
+    return m
+
+
+def dev(a):
+    import torch
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(a).cuda()
+
+
+def host(t):
+    import torch
+    a = t.cpu().numpy()
+    return a.view(np.uint32) if a.dtype == np.int32 else a
+
+
+def test_quantize_and_dequantize(dk):
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.normal(0, 3, 1003), rng.normal(0, 1e5, 50),
+                        [0.0, -0.0, 1 / 512, -1 / 512, 1e30, -1e30, np.nan, np.inf, -np.inf,
+                         0.49999997, -2.5 / 256, 2.5 / 256]]).astype(np.float32)
+    for l in (0, 1, 8, 12):
+        assert np.array_equal(host(dk.dkf_quantize(dev(x), l=l)), F.quantize(x, l=l))
+    q = rng.integers(0, P, size=4099, dtype=np.uint32)
+    q[:4] = [0, P - 1, P // 2, P // 2 + 1]
+    for l in (0, 3, 8):
+        assert np.array_equal(host(dk.dkf_dequantize(dev(q), l=l)), F.dequantize(q, l=l))
+
+
+@pytest.mark.parametrize("K,G,n", [(1, 3, 17), (2, 2, 1024), (4, 5, 4100), (8, 3, 2051), (16, 2, 260)])
+def test_encode(dk, K, G, n):
+    rng = np.random.default_rng([K, G, n])
+    d = dk_inputs.field_layer_inputs(rng, dk_inputs.linear(3, n), K=K, batch=G * K)
+    got = host(dk.dkf_encode(dev(d["X"]), dev(d["r"]), dev(d["A"]), K))
+    want = F.encode(F.quantize(d["X"]), d["r"], d["A"])
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("R,M,N,small", [(5, 7, 9, False), (130, 200, 300, False), (130, 200, 300, True),
+                                         (384, 257, 1000, False), (64, 129, 4099, True), (1, 1, 1, False)])
+def test_linear_fwd_full(dk, R, M, N, small):
+    rng = np.random.default_rng([R, M, N, int(small)])
+    X = rng.integers(0, P, size=(R, N), dtype=np.uint32)
+    if small:   # field images of small signed integers: only the low digits are non-zero
+        W = (rng.integers(-3000, 3000, size=(M, N)) % P).astype(np.uint32)
+    else:
+        W = rng.integers(0, P, size=(M, N), dtype=np.uint32)
+    got = host(dk.dkf_linear_fwd(dev(W), dev(X)))
+    assert np.array_equal(got, F.dense_fwd(W, X))
+
+
+def test_linear_fwd_extreme_digits(dk):
+    """Operands at the ends of the centred range and at digit boundaries."""
+    vals = np.array([0, 1, P - 1, P // 2, P // 2 + 1, 63, 64, 65, P - 64, P - 65, 8191, 8192, 8256, 8257,
+                     P - 8256, P - 8257, 1 << 21, (1 << 24) - 1], dtype=np.uint32)
+    X = np.tile(vals, (len(vals), 1))
+    W = np.tile(vals[:, None], (1, len(vals)))
+    got = host(dk.dkf_linear_fwd(dev(np.ascontiguousarray(W)), dev(X)))
+    assert np.array_equal(got, F.dense_fwd(W, X))
+    # long rows of the largest digit products (every digit -64) exercise the
+    # int32 accumulators close to the longest k slice the plan allows
+    N = 1_500_000
+    v = P - 64 * (1 + 128 + 128 * 128)
+    X = np.full((2, N), v, dtype=np.uint32)
+    W = np.full((3, N), v, dtype=np.uint32)
+    assert np.array_equal(host(dk.dkf_linear_fwd(dev(W), dev(X))), F.dense_fwd(W, X))
+
+
+@pytest.mark.parametrize("K,G,m", [(1, 2, 33), (2, 3, 512), (4, 4, 1028), (8, 2, 1000), (16, 1, 77)])
+def test_decode_verify(dk, K, G, m):
+    import torch
+    rng = np.random.default_rng([K, G, m, 5])
+    S = K + 2
+    A = rng.integers(0, P, size=(G, S, S), dtype=np.uint32)
+    gamma = rng.integers(1, P, size=(G, S), dtype=np.uint32)
+    Ainv, nvec, _ = F.coefficients(A, gamma)
+    # consistent results: encodings of random sources with a zero phantom row
+    src = rng.integers(0, P, size=(G * S, m), dtype=np.uint32)
+    src.reshape(G, S, m)[:, S - 1] = 0
+    ybar = np.empty_like(src)
+    for g in range(G):
+        ybar[g * S:(g + 1) * S] = (A[g].astype(object).T @ src[g * S:(g + 1) * S].astype(object) % P).astype(np.uint32)
+    y, yq, verdict = dk.dkf_decode_verify(dev(ybar), dev(Ainv), dev(nvec), K, want_yq=True)
+    want_q = F.decode(ybar, Ainv)
+    assert np.array_equal(host(yq), want_q)
+    assert np.array_equal(host(y), F.dequantize(want_q))
+    assert np.array_equal(host(verdict), F.verify(ybar, nvec)) and not host(verdict).any()
+    assert np.array_equal(want_q, src.reshape(G, S, m)[:, :K].reshape(G * K, m))
+    # corrupt one element of the last group, and put a non-element into group 0
+    bad = ybar.copy()
+    bad[G * S - 2, m - 1] = (int(bad[G * S - 2, m - 1]) + 1) % P
+    if G > 1:
+        bad[1, 0] = P + 5
+    _, _, verdict = dk.dkf_decode_verify(dev(bad), dev(Ainv), dev(nvec), K)
+    want = F.verify(bad, nvec)
+    assert np.array_equal(host(verdict), want) and want[G - 1] == 1 and (G == 1 or want[0] == 1)
+    # stale verdicts are overwritten
+    v = torch.full((G,), 7, dtype=torch.int32, device="cuda")
+    dk.dkf_decode_verify(dev(ybar), dev(Ainv), dev(nvec), K, verdict=v)
+    assert not host(v).any()
+
+
+@pytest.mark.parametrize("K,G,M,N", [(2, 1, 512, 256), (4, 3, 70, 130), (8, 4, 257, 300), (1, 5, 33, 129)])
+def test_masked_dense_layer(dk, K, G, M, N):
+    rng = np.random.default_rng([K, G, M, N, 9])
+    L = dk_inputs.linear(M, N)
+    d = dk_inputs.field_layer_inputs(rng, L, K=K, batch=G * K, delta_std=1.0)
+    o = F.masked_dense_layer(d["W"], d["X"], d["r"], d["delta"], d["A"], d["gamma"])
+    Ainv, nvec, B = dk.dkf_coeffs(d["A"], d["gamma"])
+    Wq = dk.dkf_quantize(dev(d["W"]))
+    assert np.array_equal(host(Wq), o["Wq"])
+    xbar = dk.dkf_encode(dev(d["X"]), dev(d["r"]), dev(d["A"]), K)
+    assert np.array_equal(host(xbar), o["Xbar"])
+    ybar = dk.dkf_linear_fwd(Wq, xbar)
+    assert np.array_equal(host(ybar), o["Ybar"])
+    y, yq, verdict = dk.dkf_decode_verify(ybar, dev(Ainv), dev(nvec), K, want_yq=True)
+    assert np.array_equal(host(yq), o["Yq"]) and np.array_equal(host(y), o["Y"])
+    assert np.array_equal(host(verdict), o["verdict"])
+    dW, dwq = dk.dkf_wgrad(L, dev(d["delta"]), dev(B), dev(d["gamma"]), xbar, K, want_dwq=True)
+    assert np.array_equal(host(dwq), o["dWq"]) and np.array_equal(host(dW), o["dW"])
+    # scale and accumulate
+    import torch
+    base = torch.full((M, N), 0.5, dtype=torch.float32, device="cuda")
+    dk.dkf_wgrad(L, dev(d["delta"]), dev(B), dev(d["gamma"]), xbar, K, dW=base, scale=0.25, accumulate=True)
+    assert np.array_equal(host(base), (0.5 + 0.25 * o["dW"]).astype(np.float32))
+    # and the decoded values are the plain integer layer (no masking, no field)
+    Wi, Xi = (np.floor(a.astype(np.float64) * 256 + 0.5).astype(np.int64) for a in (d["W"], d["X"]))
+    lift = host(yq).astype(np.int64)
+    lift = np.where(lift > P // 2, lift - P, lift)
+    assert np.array_equal(lift, Xi @ Wi.T)
+
+
+def test_config1_field(dk):
+    d = dk_inputs.config1_field()
+    L, K = d["layer"], d["K"]
+    o = F.masked_dense_layer(d["W"], d["X"], d["r"], d["delta"], d["A"], d["gamma"])
+    Ainv, nvec, B = dk.dkf_coeffs(d["A"], d["gamma"])
+    xbar = dk.dkf_encode(dev(d["X"]), dev(d["r"]), dev(d["A"]), K)
+    ybar = dk.dkf_linear_fwd(dk.dkf_quantize(dev(d["W"])), xbar)
+    y, _, verdict = dk.dkf_decode_verify(ybar, dev(Ainv), dev(nvec), K)
+    dW, _ = dk.dkf_wgrad(L, dev(d["delta"]), dev(B), dev(d["gamma"]), xbar, K)
+    assert np.array_equal(host(y), o["Y"]) and np.array_equal(host(dW), o["dW"]) and not host(verdict).any()
+
+
+@pytest.mark.parametrize("index", [2, 0])
+def test_config5_field_sampled(dk, index):
+    """Classifier layers at full size; the oracle evaluates sampled outputs of
+    the two contractions and the whole of the cheap stages."""
+    d = dk_inputs.config5_field(index=index)[0]
+    L, K, G = d["layer"], d["K"], d["G"]
+    S = K + 2
+    rng = np.random.default_rng([5, index, 99])
+    Ainv, nvec, B = dk.dkf_coeffs(d["A"], d["gamma"])
+    Wq_o = F.quantize(d["W"])
+    xbar_o = F.encode(F.quantize(d["X"]), d["r"], d["A"])
+    Wq = dk.dkf_quantize(dev(d["W"]))
+    xbar = dk.dkf_encode(dev(d["X"]), dev(d["r"]), dev(d["A"]), K)
+    assert np.array_equal(host(xbar), xbar_o)
+    ybar = dk.dkf_linear_fwd(Wq, xbar)
+    yb = host(ybar)
+    pts = np.stack([rng.integers(0, G * S, 3000), rng.integers(0, L.M, 3000)], 1)
+    assert np.array_equal(yb[pts[:, 0], pts[:, 1]], F.dense_fwd_points(Wq_o, xbar_o, pts))
+    # decode and verify the accelerator's own ybar with the oracle: clean, and
+    # the decoded values are the plain integer layer at the sampled positions
+    y, yq, verdict = dk.dkf_decode_verify(ybar, dev(Ainv), dev(nvec), K, want_yq=True)
+    assert not host(verdict).any() and not F.verify(yb, nvec).any()
+    assert np.array_equal(host(yq), F.decode(yb, Ainv))
+    assert np.array_equal(host(y), F.dequantize(host(yq)))
+    Wi = np.floor(d["W"].astype(np.float64) * 256 + 0.5).astype(np.int64)
+    Xi = np.floor(d["X"].astype(np.float64) * 256 + 0.5).astype(np.int64)
+    spts = np.stack([rng.integers(0, G * K, 500), rng.integers(0, L.M, 500)], 1)
+    lift = host(yq).astype(np.int64)
+    lift = np.where(lift > P // 2, lift - P, lift)
+    assert np.array_equal(lift[spts[:, 0], spts[:, 1]], np.einsum("pk,pk->p", Xi[spts[:, 0]], Wi[spts[:, 1]]))
+    # weight gradient
+    dW, dwq = dk.dkf_wgrad(L, dev(d["delta"]), dev(B), dev(d["gamma"]), xbar, K, want_dwq=True)
+    dt_o = F.delta_mix(F.quantize(d["delta"]), B, d["gamma"])
+    wpts = np.stack([rng.integers(0, L.M, 3000), rng.integers(0, L.N, 3000)], 1)
+    got = host(dwq)
+    assert np.array_equal(got[wpts[:, 0], wpts[:, 1]], F.dense_wgrad_points(dt_o, xbar_o, wpts))
+    assert np.array_equal(host(dW), F.dequantize(got))
+
+
+def test_field_arguments_refused(dk):
+    import torch
+    from paper_2207_00083_amd import DkError
+    W = torch.zeros((8, 8), dtype=torch.int32, device="cuda")
+    X = torch.zeros((4, 8), dtype=torch.int32, device="cuda")
+    with pytest.raises(DkError) as e:
+        dk.dkf_linear_fwd(W, X, ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == 5
+    with pytest.raises(DkError) as e:
+        dk.dkf_quantize(torch.zeros(4, device="cuda"), l=13)
+    assert e.value.status == 2
+    conv = dk_inputs.conv(4, 4, 8, 8, 3)
+    assert dk.dkf_wgrad_workspace_bytes(conv, 1, 2) == 0
