@@ -25,6 +25,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_F32_PEAK_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
+MFMA_I8_PEAK_TOPS = 5000.0        # MI355X dense int8 matrix peak
 HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E
 
 
@@ -97,6 +98,185 @@ def cpu_baseline(d, budget_s=15.0):
     }
 
 
+def field_workload(name):
+    import dk_inputs
+    if name == "field1":
+        return dk_inputs.config1_field(), "config1 over F_p: dense 256->512, K=2, 1 group"
+    if name.startswith("field5."):
+        i = int(name.split(".")[1])
+        return (dk_inputs.config5_field(index=i)[0],
+                "config5 layer %d over F_p, p=2^25-39, l=8 (VGG classifier, batch 1024, K=8)" % i)
+    raise SystemExit("unknown workload " + name)
+
+
+def field_cpu_baseline(d, budget_s=15.0):
+    """The field oracle's staged dense layer on the first few groups."""
+    from oracle import field as F
+    L, K, G = d["layer"], d["K"], d["G"]
+    S = K + 2
+    op_per_group = 2 * 2 * S * L.macs_per_row
+
+    def run(ng):
+        sl = slice(0, ng * K)
+        t0 = time.perf_counter()
+        F.masked_dense_layer(d["W"], d["X"][sl], d["r"][:ng], d["delta"][sl], d["A"][:ng], d["gamma"][:ng])
+        return time.perf_counter() - t0
+
+    import oracle
+    oracle.build()
+    t1 = run(1)
+    ng = int(max(1, min(G, budget_s / max(t1, 1e-3))))
+    t = run(ng) if ng > 1 else t1
+    return {
+        "value": op_per_group * ng / t / 1e12, "unit": "TOP/s (one field multiply-add = 2)",
+        "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "staged field oracle (quantise, encode, product on encodings, verify, decode, masked "
+                  "wgrad, one remainder per operation) on the first %d of %d groups, %.1f s" % (ng, G, t),
+        "samples_per_s": ng * K / t,
+    }
+
+
+def field_main(args):
+    """The finite-field variant of a dense layer:
+    dkf_quantize(W) -> dkf_encode -> dkf_linear_fwd -> dkf_decode_verify -> dkf_wgrad."""
+    import torch
+    import paper_2207_00083_amd as dk
+    dk.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    d, wname = field_workload(args.workload)
+    L, K, G = d["layer"], d["K"], d["G"]
+    S = K + 2
+    R = G * S
+
+    def dev(a):
+        a = np.ascontiguousarray(a)
+        return torch.from_numpy(a.view(np.int32) if a.dtype == np.uint32 else a).cuda()
+
+    Ainv, nvec, B = dk.dkf_coeffs(d["A"], d["gamma"])
+    W, X, r, delta = dev(d["W"]), dev(d["X"]), dev(d["r"]), dev(d["delta"])
+    A_d, Ainv_d, nvec_d, B_d, gamma_d = dev(d["A"]), dev(Ainv), dev(nvec), dev(B), dev(d["gamma"])
+    i32 = dict(dtype=torch.int32, device="cuda")
+    f32 = dict(dtype=torch.float32, device="cuda")
+    Wq = torch.empty((L.M, L.N), **i32)
+    xbar = torch.empty((R, L.N), **i32)
+    ybar = torch.empty((R, L.M), **i32)
+    y = torch.empty((G * K, L.M), **f32)
+    dW = torch.empty((L.M, L.N), **f32)
+    verdict = torch.empty(G, **i32)
+    ws_f = torch.empty(dk.dkf_fwd_workspace_bytes(L.M, L.N, R), dtype=torch.uint8, device="cuda")
+    ws_w = torch.empty(dk.dkf_wgrad_workspace_bytes(L, G, K), dtype=torch.uint8, device="cuda")
+    stages = ["quantize_w", "encode", "fwd", "decode_verify", "wgrad"]
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        dk.dkf_quantize(W, xq=Wq)
+        if ev: ev[1].record()
+        dk.dkf_encode(X, r, A_d, K, xbar=xbar)
+        if ev: ev[2].record()
+        dk.dkf_linear_fwd(Wq, xbar, ybar=ybar, ws=ws_f)
+        if ev: ev[3].record()
+        dk.dkf_decode_verify(ybar, Ainv_d, nvec_d, K, y=y, verdict=verdict)
+        if ev: ev[4].record()
+        dk.dkf_wgrad(L, delta, B_d, gamma_d, xbar, K, dW=dW, ws=ws_w)
+        if ev: ev[5].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    graph = None
+    if not args.no_graph:
+        ref = [t.clone() for t in (y, dW, verdict)]
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=side):
+                    step()
+            torch.cuda.current_stream().wait_stream(side)
+            for _ in range(3):
+                for t in (y, dW):
+                    t.zero_()
+                torch.cuda.synchronize()
+                graph.replay()
+                torch.cuda.synchronize()
+                if not all(torch.equal(a, b) for a, b in zip((y, dW, verdict), ref)):
+                    raise RuntimeError("graph replay differs from the eager step")
+        except Exception as e:                      # noqa: BLE001 - fall back to eager launches
+            sys.stderr.write("bench.py: HIP graph not used (%s)\n" % e)
+            graph = None
+        for _ in range(args.warmup):
+            graph.replay() if graph else step()
+        torch.cuda.synchronize()
+
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay() if graph else step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    dk.dk_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dk.dk_profile_enable(False)
+    kernels = dk.dk_profile_read()
+    assert int(verdict.sum().item()) == 0, "clean synthetic data must verify"
+
+    ms_per_step = wall / args.steps * 1e3
+    stage_ms = {s: float(np.mean([e[i].elapsed_time(e[i + 1]) for e in events])) for i, s in enumerate(stages)}
+    mac = float(R) * L.M * L.N                     # field multiply-adds per contraction
+    op_step = 2.0 * 2.0 * mac                       # forward + weight gradient
+    tops = op_step / (ms_per_step * 1e-3) / 1e12
+    # The contraction kernel runs twice a step.  The forward multiplies 4 digit
+    # planes of the encodings with the 2 non-zero planes of ordinary weights
+    # (8 int8 products per field product), the weight gradient 4 x 4 planes (16).
+    # The roofline record is the longer of the two launches.
+    gemm = {"f_gemm_fwd": 8, "f_gemm_wgrad": 16}
+    dom = max(gemm, key=lambda k: kernels[k][0])
+    gemm_ms = kernels[dom][0]
+    int8_ops = 2.0 * mac * gemm[dom]
+    ach = int8_ops / (gemm_ms * 1e-3) / 1e12
+    roofline = {
+        "kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s",
+        "frac": ach / MFMA_I8_PEAK_TOPS, "traffic": measured_traffic(args.workload, dom),
+        "avg_launch_ms": gemm_ms, "int8_op_per_launch": int8_ops,
+        "field_top_per_s": 2.0 * mac / (gemm_ms * 1e-3) / 1e12,
+        "other_contraction": {k: {"avg_launch_ms": kernels[k][0],
+                                  "int8_TOPs": 2.0 * mac * c / (kernels[k][0] * 1e-3) / 1e12}
+                              for k, c in gemm.items() if k != dom},
+        "timed": "HIP events around every launch of this kernel, %d eager steps after the timed region" % args.steps,
+    }
+    n, m = L.N, L.M
+    ab = {"f_encode": 4 * G * n * (K + 1 + S), "f_decode_verify": 4 * G * m * (S + K),
+          "f_delta_mix": 4 * G * m * (K + S)}
+    hbm = {k: {"GBps": b / (kernels[k][0] * 1e-3) / 1e9, "frac": b / (kernels[k][0] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+               "bytes": b, "avg_launch_ms": kernels[k][0]} for k, b in ab.items() if k in kernels}
+    out = {
+        "metric": "masked-layer TOP/s over F_p (fwd+wgrad, one field multiply-add = 2, executed on all K+2 "
+                  "encoded rows), whole hot path",
+        "value": tops, "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 field elements, int8 digit MFMA", "data": "synthetic",
+        "config": {"workload": wname, "K": K, "G": G, "layer": L.asdict(),
+                   "launch": "HIP graph replay of one captured step" if graph else "eager"},
+        "decoded_samples_per_s": G * K / (ms_per_step * 1e-3),
+        "stage_ms": stage_ms,
+        "fwd_stage_tops": 2.0 * mac / (stage_ms["fwd"] * 1e-3) / 1e12,
+        "wgrad_stage_tops": 2.0 * mac / (stage_ms["wgrad"] * 1e-3) / 1e12,
+        "roofline": roofline, "hbm_kernels": hbm,
+        "kernel_ms": {k: v[0] for k, v in kernels.items()},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = field_cpu_baseline(d)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -118,6 +298,9 @@ def main():
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.stderr.write("bench.py: this build covers the one-GPU hot path only; run with --gpus 1\n")
         raise SystemExit(2)
+
+    if args.workload.startswith("field"):
+        return field_main(args)
 
     import torch
     import paper_2207_00083_amd as dk

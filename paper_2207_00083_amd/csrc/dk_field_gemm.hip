@@ -13,12 +13,13 @@
 // at most two digit products per k, each at most 2^12 in magnitude, so 2^17
 // values of k fit with room to spare.  The epilogue recombines the three
 // accumulators in 64 bits, reduces modulo p and applies the part's weight
-// 128^(2 (ha + hb)).  The four parts are sets of workgroups of one launch; a part
-// that involves a high half whose digits are all zero (quantised weights of
-// ordinary magnitude) exits at once: the digit kernels record that in device
-// flags, so nothing is read back to the host.  Partial results (parts, k
-// slices) are residues and are folded by modular addition.  All of it is exact:
-// the result is the field product whatever the tiling.
+// 128^(2 (ha + hb)).  A workgroup runs the four parts of its tile one after the
+// other and adds their residues in registers; a part that involves a high half
+// whose digits are all zero (quantised weights of ordinary magnitude) is
+// skipped: the digit kernels record that in device flags, so nothing is read
+// back to the host.  With more than one k slice the slices are residues too and
+// are folded by modular addition.  All of it is exact: the result is the field
+// product whatever the tiling.
 //
 // The contraction index has to be contiguous for both operands; digit planes
 // are written k-major by the digit kernels (straight for row-major operands,
@@ -35,16 +36,20 @@ constexpr int A_PLANE = BI * PITCH, B_PLANE = BJ * PITCH;
 constexpr int BUF_BYTES = 2 * A_PLANE + 2 * B_PLANE;     // 73728
 constexpr int LDS_BYTES = 2 * BUF_BYTES;                  // 147456
 constexpr int MAX_KSPLIT = 1 << 17;    // k values per slice (int32 accumulators)
-constexpr int MAX_SPLITS = 16;         // the fold adds at most 4 * 16 residues in 32 bits
+constexpr int MAX_SPLITS = 16;         // the fold adds the slices' residues in 32 bits
 
 struct fgemm_params {
     const int8_t *Ap;      // [4][I_pad][Kp]
     const int8_t *Bp;      // [4][J_pad][Kp]
-    uint32_t *part;        // [4][splits][I][J]
+    uint32_t *out_q;       // residues [splits][I][J] (a slice per k split), or NULL
+    float *out_f;          // de-quantised result [I][J] (only with one split), or NULL
     const int *flags;      // [0]: A has non-zero high digits, [1]: B has (device)
     long long a_plane, b_plane;   // bytes per plane
     int I, J, Kp;
     int tiles_i, tiles_j, splits, ktiles_per_split, ktiles;
+    double s_inv;          // 2^-l for out_f
+    float scale;
+    int accumulate;
 };
 
 // Four balanced base-128 digits of the centred lift of q, packed one per byte.
@@ -70,21 +75,37 @@ __device__ __forceinline__ uint32_t gather_byte(const uint32_t (&d)[4], int a)
            ((d[3] >> sh) & 255u) << 24;
 }
 
-// Row-major operand src[rows][K] -> planes[4][rows_pad][Kp].  One thread per
-// four consecutive k; rows and k beyond the operand are written as zeros.
+// Record "some high digit is non-zero".  One lane per wave looks at the flag
+// first, so once it is set the other waves of the launch only read it.
+__device__ __forceinline__ void raise_flag(int *flag, bool mine)
+{
+    if (flag && __any(mine) && (threadIdx.x & 63) == 0) {
+        if (__atomic_load_n(flag, __ATOMIC_RELAXED) == 0) atomicOr(flag, 1);
+    }
+}
+
+// Row-major operand src[rows][K] -> planes[4][rows_pad][Kp].  A workgroup
+// converts 1024 consecutive k of one row, a thread four of them; rows and k
+// beyond the operand are written as zeros.
 __global__ __launch_bounds__(256) void f_digits_kernel(const uint32_t *__restrict__ src,
                                                        int8_t *__restrict__ planes, int rows, int K,
-                                                       int rows_pad, int Kp, int *flag)
+                                                       int rows_pad, int Kp, int chunks, int vec,
+                                                       int *flag)
 {
-    const int kq = Kp >> 2;
-    const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (id >= (long long)rows_pad * kq) return;
-    const int row = (int)(id / kq), k0 = (int)(id - (long long)row * kq) * 4;
+    const int row = blockIdx.x / chunks;                       // workgroup-uniform
+    const int k0 = ((blockIdx.x - row * chunks) * 256 + threadIdx.x) * 4;
+    if (k0 >= Kp) return;
     uint32_t d[4] = {0, 0, 0, 0};
     if (row < rows) {
+        const uint32_t *s = src + (long long)row * K + k0;
+        if (vec && k0 + 3 < K) {
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(s);
+            d[0] = digits_of(v.x); d[1] = digits_of(v.y); d[2] = digits_of(v.z); d[3] = digits_of(v.w);
+        } else {
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-            if (k0 + c < K) d[c] = digits_of(src[(long long)row * K + k0 + c]);
+            for (int c = 0; c < 4; ++c)
+                if (k0 + c < K) d[c] = digits_of(s[c]);
+        }
     }
     const long long plane = (long long)rows_pad * Kp;
     uint32_t hi = 0;
@@ -94,20 +115,22 @@ __global__ __launch_bounds__(256) void f_digits_kernel(const uint32_t *__restric
         if (a >= 2) hi |= w;
         *reinterpret_cast<uint32_t *>(planes + a * plane + (long long)row * Kp + k0) = w;
     }
-    if (flag && __any(hi != 0) && (threadIdx.x & 63) == 0) atomicOr(flag, 1);
+    raise_flag(flag, hi != 0);
 }
 
 // Operand stored with the contraction index slow, src[K][cols] ->
-// planes[4][cols_pad][Kp]: a 64 x 64 tile goes through LDS as packed digits.
+// planes[4][cols_pad][Kp]: a tile of 128 k x 64 columns goes through LDS as
+// packed digits; a thread then writes 16 consecutive k of one column to each
+// plane.
 __global__ __launch_bounds__(256) void f_digits_t_kernel(const uint32_t *__restrict__ src,
                                                          int8_t *__restrict__ planes, int K, int cols,
                                                          int cols_pad, int Kp, int *flag)
 {
-    __shared__ uint32_t tile[64][65];
-    const int c0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
+    __shared__ uint32_t tile[128][65];
+    const int c0 = blockIdx.x * 64, k0 = blockIdx.y * 128;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
+#pragma unroll 8
+    for (int r = 0; r < 32; ++r) {
         const int k = k0 + ty + 4 * r, c = c0 + tx;
         tile[ty + 4 * r][tx] = (k < K && c < cols) ? digits_of(src[(long long)k * cols + c]) : 0u;
     }
@@ -115,20 +138,24 @@ __global__ __launch_bounds__(256) void f_digits_t_kernel(const uint32_t *__restr
     const long long plane = (long long)cols_pad * Kp;
     uint32_t hi = 0;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int item = threadIdx.x + 256 * r;       // (col, k group of four)
-        const int kg = item & 15, col = item >> 4;
-        uint32_t d[4];
+    for (int r = 0; r < 2; ++r) {
+        const int item = threadIdx.x + 256 * r;       // (column, 16 k)
+        const int kq = item & 7, col = item >> 3;
+        u32x4 w[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) d[c] = tile[4 * kg + c][col];
+        for (int g = 0; g < 4; ++g) {
+            uint32_t d[4];
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            const uint32_t w = gather_byte(d, a);
-            if (a >= 2) hi |= w;
-            *reinterpret_cast<uint32_t *>(planes + a * plane + (long long)(c0 + col) * Kp + k0 + 4 * kg) = w;
+            for (int c = 0; c < 4; ++c) d[c] = tile[16 * kq + 4 * g + c][col];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) w[a][g] = gather_byte(d, a);
         }
+        hi |= w[2].x | w[2].y | w[2].z | w[2].w | w[3].x | w[3].y | w[3].z | w[3].w;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+            *reinterpret_cast<u32x4 *>(planes + a * plane + (long long)(c0 + col) * Kp + k0 + 16 * kq) = w[a];
     }
-    if (flag && __any(hi != 0) && (threadIdx.x & 63) == 0) atomicOr(flag, 1);
+    raise_flag(flag, hi != 0);
 }
 
 __global__ void f_flag_clear_kernel(int *flags) { if (threadIdx.x < 2) flags[threadIdx.x] = 0; }
@@ -143,6 +170,12 @@ __device__ __forceinline__ uint32_t reduce_signed(long long v)
     return (neg && r) ? DKF_P - r : r;
 }
 
+// One workgroup: a 128 x 128 tile of C over one k slice, all four digit-half
+// parts one after the other; four waves, each a 64 x 64 quarter (2 x 2 blocks
+// of 32 x 32).  Global loads of the next k tile are in flight in registers while
+// the current one is multiplied out of LDS (two LDS buffers, one barrier per
+// tile); the operands of the next 32-k step are read from LDS while the MFMAs
+// of the current one run.
 __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 {
     extern __shared__ __attribute__((aligned(16))) int8_t flds[];
@@ -152,14 +185,11 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     const int li = lane & 31, lh = lane >> 5;
 
     const int tiles = p.tiles_i * p.tiles_j;
-    int bid = dk_xcd_block();
-    const int part = bid / (tiles * p.splits);
-    bid -= part * tiles * p.splits;
+    const int bid = dk_xcd_block();
     const int split = bid / tiles;
     const int t = bid - split * tiles;
     const int tj = t / p.tiles_i, ti = t - tj * p.tiles_i;
-    const int ha = part & 1, hb = part >> 1;
-    if ((ha && p.flags[0] == 0) || (hb && p.flags[1] == 0)) return;      // workgroup-uniform
+    const bool fa = p.flags[0] != 0, fb = p.flags[1] != 0;     // workgroup-uniform
 
     const int kt0 = split * p.ktiles_per_split;
     int kt1 = kt0 + p.ktiles_per_split;
@@ -168,11 +198,23 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     // global -> register staging: 8 + 8 sixteen-byte pieces per thread and tile.
     // A thread owns one 16-byte column of the 128-byte rows (piece tid & 7) and
     // rows (tid >> 3) + 32 q, q = 0..3, of both planes of both operands.
+    // Their addresses are a workgroup-uniform base plus this 32-bit offset.
     const int srow = tid >> 3, spiece = tid & 7;
-    const int8_t *a_src = p.Ap + 2 * ha * p.a_plane + (long long)(ti * BI + srow) * p.Kp + 16 * spiece;
-    const int8_t *b_src = p.Bp + 2 * hb * p.b_plane + (long long)(tj * BJ + srow) * p.Kp + 16 * spiece;
     const long long q_rows = 32ll * p.Kp;
+    const unsigned s_off = (unsigned)srow * (unsigned)p.Kp + 16u * spiece;
     const int s_dst = srow * PITCH + 16 * spiece;
+
+    const int wi0 = (wave & 1) * 64, wj0 = (wave >> 1) * 64;
+    const int a_rd = (wi0 + li) * PITCH + 16 * lh;
+    const int b_rd = 2 * A_PLANE + (wj0 + li) * PITCH + 16 * lh;
+
+    uint32_t res[2][2][16];
+#pragma unroll
+    for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < 2; ++bj)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) res[bi][bj][v] = 0;
 
     i32x16 acc[2][2][3];
 #pragma unroll
@@ -184,17 +226,26 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[bi][bj][s][v] = 0;
 
-    const int wi0 = (wave & 1) * 64, wj0 = (wave >> 1) * 64;
-    const int a_rd = (wi0 + li) * PITCH + 16 * lh;
-    const int b_rd = 2 * A_PLANE + (wj0 + li) * PITCH + 16 * lh;
+    // The active parts in the order (lo,lo), (hi,lo), (lo,hi), (hi,hi): weights
+    // 128^0, 128^2, 128^2, 128^4, so the two middle parts share accumulators.
+    // Steps (part, k tile) form one software-pipelined sequence.
+    int plist = 0, nparts = 0;           // two bits per active part
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        if (!((q & 1) && !fa) && !((q >> 1) && !fb)) plist |= q << (2 * nparts++);
+#define DKF_PART(I) ((plist >> (2 * (I))) & 3)
+    const int nsteps = nparts * (kt1 - kt0);
 
     i32x4 sa[8], sb[8];
-#define DKF_FETCH(KTILE)                                                                          \
+#define DKF_FETCH(PI, KTILE)                                                                      \
     {                                                                                             \
+        const int q_ = DKF_PART(PI);                                                              \
+        const int8_t *as_ = p.Ap + 2 * (q_ & 1) * p.a_plane + ((long long)ti * BI * p.Kp + (long long)(KTILE) * KT); \
+        const int8_t *bs_ = p.Bp + 2 * (q_ >> 1) * p.b_plane + ((long long)tj * BJ * p.Kp + (long long)(KTILE) * KT); \
         _Pragma("unroll") for (int e = 0; e < 8; ++e)                                             \
-            sa[e] = *reinterpret_cast<const i32x4 *>(a_src + (e >> 2) * p.a_plane + (e & 3) * q_rows + (long long)(KTILE) * KT); \
+            sa[e] = *reinterpret_cast<const i32x4 *>((as_ + ((e >> 2) * p.a_plane + (e & 3) * q_rows)) + s_off); \
         _Pragma("unroll") for (int e = 0; e < 8; ++e)                                             \
-            sb[e] = *reinterpret_cast<const i32x4 *>(b_src + (e >> 2) * p.b_plane + (e & 3) * q_rows + (long long)(KTILE) * KT); \
+            sb[e] = *reinterpret_cast<const i32x4 *>((bs_ + ((e >> 2) * p.b_plane + (e & 3) * q_rows)) + s_off); \
     }
 #define DKF_STASH(BUF)                                                                            \
     {                                                                                             \
@@ -203,50 +254,139 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         _Pragma("unroll") for (int e = 0; e < 8; ++e)                                             \
             *reinterpret_cast<i32x4 *>((BUF) + 2 * A_PLANE + (e >> 2) * B_PLANE + (e & 3) * 32 * PITCH + s_dst) = sb[e]; \
     }
-    if (kt0 < kt1) {
-        DKF_FETCH(kt0)
+    // in the order the MFMAs of a step consume them: A and B planes 0 first
+#define DKF_READ(A, B, KS)                                                                        \
+    {                                                                                             \
+        _Pragma("unroll") for (int bi = 0; bi < 2; ++bi)                                          \
+            A[bi][0] = *reinterpret_cast<const i32x4 *>(cur + a_rd + bi * 32 * PITCH + (KS) * 32); \
+        _Pragma("unroll") for (int bj = 0; bj < 2; ++bj)                                          \
+            B[bj][0] = *reinterpret_cast<const i32x4 *>(cur + b_rd + bj * 32 * PITCH + (KS) * 32); \
+        _Pragma("unroll") for (int bj = 0; bj < 2; ++bj)                                          \
+            B[bj][1] = *reinterpret_cast<const i32x4 *>(cur + B_PLANE + b_rd + bj * 32 * PITCH + (KS) * 32); \
+        _Pragma("unroll") for (int bi = 0; bi < 2; ++bi)                                          \
+            A[bi][1] = *reinterpret_cast<const i32x4 *>(cur + A_PLANE + a_rd + bi * 32 * PITCH + (KS) * 32); \
+    }
+    // digit pairs outermost: four independent accumulators lie between two
+    // MFMAs into the same one
+#define DKF_MMA(A, B)                                                                             \
+    {                                                                                             \
+        _Pragma("unroll") for (int pa = 0; pa < 2; ++pa)                                          \
+            _Pragma("unroll") for (int pb = 0; pb < 2; ++pb)                                      \
+                _Pragma("unroll") for (int bi = 0; bi < 2; ++bi)                                  \
+                    _Pragma("unroll") for (int bj = 0; bj < 2; ++bj)                              \
+                        acc[bi][bj][pa + pb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(             \
+                            A[bi][pa], B[bj][pb], acc[bi][bj][pa + pb], 0, 0, 0);                 \
+    }
+    // eight times one MFMA and one LDS read, then the other eight MFMAs: the
+    // reads have half a step to come back
+#define DKF_PACE_READS()                                                                          \
+    {                                                                                             \
+        _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                           \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                    \
+        }                                                                                         \
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                        \
+        __builtin_amdgcn_sched_barrier(0);                                                        \
+    }
+    // keep consumed operand registers live up to here, so that a read issued
+    // between the MFMAs does not target a register an MFMA in flight still reads
+#define DKF_KEEP(A, B)                                                                            \
+    {                                                                                             \
+        _Pragma("unroll") for (int x = 0; x < 2; ++x)                                             \
+            _Pragma("unroll") for (int y = 0; y < 2; ++y) {                                       \
+                asm volatile("" ::"v"(A[x][y]));                                                  \
+                asm volatile("" ::"v"(B[x][y]));                                                  \
+            }                                                                                     \
+    }
+    if (nsteps > 0) {
+        DKF_FETCH(0, kt0)
         DKF_STASH(flds)
     }
     __syncthreads();
 
-    for (int kt = kt0; kt < kt1; ++kt) {
-        const int8_t *cur = flds + ((kt - kt0) & 1) * BUF_BYTES;
-        int8_t *nxt = flds + ((kt - kt0 + 1) & 1) * BUF_BYTES;
-        const bool more = kt + 1 < kt1;
-        if (more) DKF_FETCH(kt + 1)
+    // Outer loop: weight groups; inner loop: the steps of one group, a plain
+    // pipelined MFMA loop (its last step already fetches the first tile of the
+    // next group, so only the first tile of the workgroup waits for memory).
+    int pi = 0, kt = kt0, step = 0;       // part index, k tile and number of the current step
+    while (step < nsteps) {
+        const int q = DKF_PART(pi);
+        const int w = (q & 1) + (q >> 1);
+        const int qn = DKF_PART(pi + 1);
+        const int gparts = (pi + 1 < nparts && (qn & 1) + (qn >> 1) == w) ? 2 : 1;
+        const int g_end = step + gparts * (kt1 - kt0);
+        for (; step < g_end; ++step) {
+            const int8_t *cur = flds + (step & 1) * BUF_BYTES;
+            int8_t *nxt = flds + ((step + 1) & 1) * BUF_BYTES;
+            const bool more = step + 1 < nsteps;
+            const bool part_ends = kt + 1 == kt1;
+            const int pi_n = part_ends ? pi + 1 : pi, kt_n = part_ends ? kt0 : kt + 1;
+            if (more) DKF_FETCH(pi_n, kt_n)
+            // Four 32-k steps.  The operands of step s+1 are read from LDS while
+            // the 16 MFMAs of step s issue (one read per two MFMAs); the LDS
+            // writes of the next tile go between the MFMAs of the last step.
+            i32x4 a0[2][2], b0[2][2], a1[2][2], b1[2][2];
+            DKF_READ(a0, b0, 0)
+            __builtin_amdgcn_sched_barrier(0);
+            DKF_READ(a1, b1, 1)
+            DKF_MMA(a0, b0)
+            DKF_PACE_READS()
+            DKF_KEEP(a0, b0)
+            DKF_READ(a0, b0, 2)
+            DKF_MMA(a1, b1)
+            DKF_PACE_READS()
+            DKF_KEEP(a1, b1)
+            DKF_READ(a1, b1, 3)
+            DKF_MMA(a0, b0)
+            DKF_PACE_READS()
+            DKF_KEEP(a0, b0)
+            DKF_MMA(a1, b1)
+            // (after the last step this stores stale registers to the idle buffer)
+            DKF_STASH(nxt)
 #pragma unroll
-        for (int ks = 0; ks < KT / 32; ++ks) {
-            i32x4 a[2][2], b[2][2];
-#pragma unroll
-            for (int bi = 0; bi < 2; ++bi)
-#pragma unroll
-                for (int pl = 0; pl < 2; ++pl)
-                    a[bi][pl] = *reinterpret_cast<const i32x4 *>(cur + pl * A_PLANE + a_rd + bi * 32 * PITCH + ks * 32);
-#pragma unroll
-            for (int bj = 0; bj < 2; ++bj)
-#pragma unroll
-                for (int pl = 0; pl < 2; ++pl)
-                    b[bj][pl] = *reinterpret_cast<const i32x4 *>(cur + pl * B_PLANE + b_rd + bj * 32 * PITCH + ks * 32);
-#pragma unroll
-            for (int bi = 0; bi < 2; ++bi)
-#pragma unroll
-                for (int bj = 0; bj < 2; ++bj)
-#pragma unroll
-                    for (int pa = 0; pa < 2; ++pa)
-#pragma unroll
-                        for (int pb = 0; pb < 2; ++pb)
-                            acc[bi][bj][pa + pb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                                a[bi][pa], b[bj][pb], acc[bi][bj][pa + pb], 0, 0, 0);
+            for (int e = 0; e < 16; ++e) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            pi = pi_n; kt = kt_n;
         }
-        if (more) DKF_STASH(nxt)
-        __syncthreads();
+
+        // End of a weight group: recombine the three accumulators with the
+        // constants 128^(2w + s) mod p in 64 bits, reduce, add to the running
+        // residues and clear the accumulators.
+        const int c0 = (int)dkf_reduce(1ull << (14 * w));
+        const int c1 = (int)dkf_reduce(1ull << (14 * w + 7));
+        const int c2 = (int)dkf_reduce(1ull << (14 * w + 14));
+#pragma unroll
+        for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+            for (int bj = 0; bj < 2; ++bj) {
+                __builtin_amdgcn_sched_barrier(0);     // one block at a time: short live ranges
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const long long val = (long long)acc[bi][bj][0][v] * c0 +
+                                          (long long)acc[bi][bj][1][v] * c1 +
+                                          (long long)acc[bi][bj][2][v] * c2;      // |val| < 2^58
+                    const uint32_t u = res[bi][bj][v] + reduce_signed(val);
+                    res[bi][bj][v] = u >= DKF_P ? u - DKF_P : u;
+                }
+#pragma unroll
+                for (int s = 0; s < 3; ++s)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[bi][bj][s][v] = 0;
+            }
+        __builtin_amdgcn_sched_barrier(0);
     }
+#undef DKF_PART
+#undef DKF_PACE_READS
+#undef DKF_KEEP
 #undef DKF_FETCH
 #undef DKF_STASH
+#undef DKF_READ
+#undef DKF_MMA
 
-    // recombine the three weights in 64 bits, reduce, apply the part's weight
-    uint32_t *dst = p.part + ((long long)part * p.splits + split) * p.I * p.J;
-    const int wshift = 14 * (ha + hb);
+    uint32_t *dst_q = p.out_q ? p.out_q + (long long)split * p.I * p.J : nullptr;
 #pragma unroll
     for (int bi = 0; bi < 2; ++bi)
 #pragma unroll
@@ -255,54 +395,37 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int i = ti * BI + wi0 + bi * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
-                long long val = 0;
-#pragma unroll
-                for (int s = 0; s < 3; ++s) val += (long long)acc[bi][bj][s][v] << (7 * s);
-                const uint32_t r = dkf_reduce((uint64_t)reduce_signed(val) << wshift);   // < 2^53
-                if (i < p.I && j < p.J) dst[(long long)i * p.J + j] = r;
+                if (i < p.I && j < p.J) {
+                    const long long o = (long long)i * p.J + j;
+                    const uint32_t q = res[bi][bj][v];
+                    if (dst_q) dst_q[o] = q;
+                    if (p.out_f) {
+                        const float f = p.scale * dkf_dequant(q, p.s_inv);
+                        p.out_f[o] = p.accumulate ? p.out_f[o] + f : f;
+                    }
+                }
             }
         }
 }
 
-// Number of residue slices to add and where they are: part q of the launch is
-// present when the high halves it uses are non-zero.
-__device__ __forceinline__ uint32_t fold_slices(const uint32_t *__restrict__ part,
-                                                const int *__restrict__ flags, long long elems,
-                                                long long e, int splits)
-{
-    const bool fa = flags[0] != 0, fb = flags[1] != 0;
-    uint32_t s = 0;                          // at most 4 * 16 residues below 2^25
-    for (int q = 0; q < 4; ++q) {
-        if (((q & 1) && !fa) || ((q >> 1) && !fb)) continue;
-        for (int k = 0; k < splits; ++k) s += part[((long long)q * splits + k) * elems + e];
-    }
-    return dkf_reduce(s);
-}
-
+// Fold of the k slices: out[e] = sum_k part[k][e] (mod p); at most 16 residues
+// below 2^25 are added in 32 bits.  With dW != NULL the sum is de-quantised:
+// dW = (accumulate ? dW : 0) + scale * Round(lift(q) * 2^-l) * 2^-l.
 __global__ __launch_bounds__(256) void f_fold_kernel(const uint32_t *__restrict__ part,
-                                                     const int *__restrict__ flags,
-                                                     uint32_t *__restrict__ out, long long elems,
-                                                     int splits)
+                                                     uint32_t *__restrict__ out_q, float *__restrict__ dW,
+                                                     long long elems, int splits, double s_inv,
+                                                     float scale, int accumulate)
 {
     const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
     if (e >= elems) return;
-    out[e] = fold_slices(part, flags, elems, e, splits);
-}
-
-// Same fold for the weight gradient, followed by de-quantisation:
-// dW = (accumulate ? dW : 0) + scale * Round(lift(dWq) * 2^-l) * 2^-l.
-__global__ __launch_bounds__(256) void f_fold_dw_kernel(const uint32_t *__restrict__ part,
-                                                        const int *__restrict__ flags,
-                                                        float *__restrict__ dW, uint32_t *__restrict__ dwq,
-                                                        long long elems, int splits, double s_inv,
-                                                        float scale, int accumulate)
-{
-    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (e >= elems) return;
-    const uint32_t q = fold_slices(part, flags, elems, e, splits);
-    if (dwq) dwq[e] = q;
-    const float v = scale * dkf_dequant(q, s_inv);
-    dW[e] = accumulate ? dW[e] + v : v;
+    uint32_t s = 0;
+    for (int k = 0; k < splits; ++k) s += part[(long long)k * elems + e];
+    const uint32_t q = dkf_reduce(s);
+    if (out_q) out_q[e] = q;
+    if (dW) {
+        const float v = scale * dkf_dequant(q, s_inv);
+        dW[e] = accumulate ? dW[e] + v : v;
+    }
 }
 
 inline int round_up(int v, int a) { return (v + a - 1) / a * a; }
@@ -317,7 +440,7 @@ struct fgemm_plan {
 // I, J: output dimensions; K: contraction length.
 bool plan_fgemm(long long I, long long J, long long K, fgemm_plan *pl)
 {
-    if (I < 1 || J < 1 || K < 1 || I > (1 << 24) || J > (1 << 24) || K > (1 << 28)) return false;
+    if (I < 1 || J < 1 || K < 1 || I > (1 << 24) || J > (1 << 24) || K > (1 << 26)) return false;
     pl->I = (int)I; pl->J = (int)J; pl->K = (int)K;
     pl->I_pad = round_up((int)I, BI);
     pl->J_pad = round_up((int)J, BJ);
@@ -327,28 +450,40 @@ bool plan_fgemm(long long I, long long J, long long K, fgemm_plan *pl)
     pl->ktiles = pl->Kp / KT;
     const long long tiles = (long long)pl->tiles_i * pl->tiles_j;
     if (tiles > (1 << 24)) return false;
-    // enough workgroups to fill 256 compute units twice over, slices short
-    // enough for the int32 accumulators, not more slices than the fold sums
-    long long splits = 1;
-    if (tiles < 512) splits = (512 + tiles - 1) / tiles;
+    // Number of k slices: at least what the int32 accumulators need, at most
+    // what the fold adds in 32 bits, and among those the count that wastes the
+    // least of the last round of workgroups on the 256 compute units (one
+    // workgroup per unit), with a small charge per extra slice for its fold.
     const long long need = ((long long)pl->Kp + MAX_KSPLIT - 1) / MAX_KSPLIT;
-    if (splits < need) splits = need;
+    long long splits = need;
+    double best = 1e30;
+    for (long long sp = need; sp <= MAX_SPLITS && sp <= pl->ktiles; ++sp) {
+        const double rounds = (double)(tiles * sp) / 256.0;
+        const double cost = (double)((tiles * sp + 255) / 256) / rounds * (1.0 + 0.02 * (double)(sp - 1));
+        if (cost < best - 1e-9) { best = cost; splits = sp; }
+        if (tiles * sp >= 256 * 8) break;          // many rounds: the tail no longer matters
+    }
     if (splits > pl->ktiles) splits = pl->ktiles;
-    if (splits > MAX_SPLITS) splits = MAX_SPLITS;
+    if (splits < 1) splits = 1;
     int per = (int)((pl->ktiles + splits - 1) / splits);
     if ((long long)per * KT > MAX_KSPLIT) return false;
     pl->ktiles_per_split = per;
     pl->splits = (pl->ktiles + per - 1) / per;
     pl->a_bytes = align256((size_t)4 * pl->I_pad * pl->Kp);
     pl->b_bytes = align256((size_t)4 * pl->J_pad * pl->Kp);
-    pl->part_bytes = align256((size_t)4 * pl->splits * (size_t)I * (size_t)J * sizeof(uint32_t));
+    pl->part_bytes = pl->splits > 1
+        ? align256((size_t)pl->splits * (size_t)I * (size_t)J * sizeof(uint32_t)) : 0;
     return true;
 }
 
 constexpr size_t FLAG_BYTES = 256;
 
+// C = A B^T over the field from digit planes.  out_q / out_f as in the kernel
+// parameters; with more than one k slice the slices go to `part` and a fold
+// kernel finishes.
 dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, uint32_t *part,
-                    const int *flags, hipStream_t st)
+                    const int *flags, uint32_t *out_q, float *out_f, int l, float scale,
+                    int accumulate, const char *label, hipStream_t st)
 {
     static bool allowed = false;
     if (!allowed) {
@@ -357,36 +492,52 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
                    DK_ERR_HIP);
         allowed = true;
     }
+    const bool direct = pl.splits == 1;
     fgemm_params p;
-    p.Ap = Ap; p.Bp = Bp; p.part = part; p.flags = flags;
+    p.Ap = Ap; p.Bp = Bp; p.flags = flags;
+    p.out_q = direct ? out_q : part;
+    p.out_f = direct ? out_f : nullptr;
     p.a_plane = (long long)pl.I_pad * pl.Kp;
     p.b_plane = (long long)pl.J_pad * pl.Kp;
     p.I = pl.I; p.J = pl.J; p.Kp = pl.Kp;
     p.tiles_i = pl.tiles_i; p.tiles_j = pl.tiles_j; p.splits = pl.splits;
     p.ktiles_per_split = pl.ktiles_per_split; p.ktiles = pl.ktiles;
-    const long long blocks = 4ll * pl.splits * pl.tiles_i * pl.tiles_j;
+    p.s_inv = ldexp(1.0, -l); p.scale = scale; p.accumulate = accumulate;
+    const long long blocks = (long long)pl.splits * pl.tiles_i * pl.tiles_j;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
-    dk_prof_scope ps("f_gemm", st);
-    f_gemm_kernel<<<dim3((unsigned)blocks), dim3(256), LDS_BYTES, st>>>(p);
+    {
+        dk_prof_scope ps(label, st);
+        f_gemm_kernel<<<dim3((unsigned)blocks), dim3(256), LDS_BYTES, st>>>(p);
+    }
+    if (direct) return dk_launch_status();
+    DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+    const long long elems = (long long)pl.I * pl.J;
+    dk_prof_scope ps("f_fold", st);
+    f_fold_kernel<<<dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st>>>(
+        part, out_q, out_f, elems, pl.splits, p.s_inv, scale, accumulate);
     return dk_launch_status();
 }
 
 dk_status run_digits(const uint32_t *src, int8_t *planes, int rows, int K, int rows_pad, int Kp,
                      int *flag, hipStream_t st)
 {
-    const long long items = (long long)rows_pad * (Kp / 4);
+    const int chunks = (Kp / 4 + 255) / 256;
+    const long long blocks = (long long)rows_pad * chunks;
+    DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
+    const int vec = (K % 4 == 0) && dk_aligned(src, 16);
     dk_prof_scope ps("f_digits", st);
-    f_digits_kernel<<<dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st>>>(src, planes, rows, K,
-                                                                                rows_pad, Kp, flag);
+    f_digits_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(src, planes, rows, K, rows_pad, Kp,
+                                                                  chunks, vec, flag);
     return dk_launch_status();
 }
 
 dk_status run_digits_t(const uint32_t *src, int8_t *planes, int K, int cols, int cols_pad, int Kp,
                        int *flag, hipStream_t st)
 {
+    DK_REQUIRE(Kp / 128 <= 65535, DK_ERR_SHAPE);
     dk_prof_scope ps("f_digits_t", st);
-    f_digits_t_kernel<<<dim3(cols_pad / 64, Kp / 64), dim3(256), 0, st>>>(src, planes, K, cols, cols_pad,
-                                                                        Kp, flag);
+    f_digits_t_kernel<<<dim3(cols_pad / 64, Kp / 128), dim3(256), 0, st>>>(src, planes, K, cols, cols_pad,
+                                                                         Kp, flag);
     return dk_launch_status();
 }
 
@@ -437,12 +588,7 @@ DK_EXPORT dk_status dkf_linear_fwd(const uint32_t *Wq, const uint32_t *xbar, uin
     if (s != DK_OK) return s;
     s = run_digits(Wq, Bp, M, N, pl.J_pad, pl.Kp, flag + 1, st);
     if (s != DK_OK) return s;
-    s = run_fgemm(pl, Ap, Bp, part, flag, st);
-    if (s != DK_OK) return s;
-    const long long elems = (long long)R * M;
-    dk_prof_scope ps("f_fold", st);
-    f_fold_kernel<<<dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st>>>(part, flag, ybar, elems, pl.splits);
-    return dk_launch_status();
+    return run_fgemm(pl, Ap, Bp, part, flag, ybar, nullptr, 0, 1.0f, 0, "f_gemm_fwd", st);
 }
 
 DK_EXPORT dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint32_t *B,
@@ -459,7 +605,7 @@ DK_EXPORT dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint3
     const long long R = (long long)G * (K + 2);
     fgemm_plan pl;
     DK_REQUIRE(plan_fgemm(g.M, g.N, R, &pl), DK_ERR_SHAPE);
-    DK_REQUIRE(pl.Kp / 64 <= 65535, DK_ERR_SHAPE);          // grid.y of the transposing digit kernel
+    DK_REQUIRE(pl.Kp / 128 <= 65535, DK_ERR_SHAPE);         // grid.y of the transposing digit kernel
     DK_REQUIRE(dk_aligned(delta, 4) && dk_aligned(B, 4) && dk_aligned(gamma, 4) && dk_aligned(xbar, 4) &&
                    dk_aligned(dW, 4) && (!dwq || dk_aligned(dwq, 4)), DK_ERR_ALIGN);
     const size_t dt_bytes = align256((size_t)R * g.M * sizeof(uint32_t));
@@ -486,11 +632,5 @@ DK_EXPORT dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint3
     if (s != DK_OK) return s;
     s = run_digits_t(xbar, Bp, (int)R, g.N, pl.J_pad, pl.Kp, flag + 1, st);
     if (s != DK_OK) return s;
-    s = run_fgemm(pl, Ap, Bp, part, flag, st);
-    if (s != DK_OK) return s;
-    const long long elems = (long long)g.M * g.N;
-    dk_prof_scope ps("f_fold_dw", st);
-    f_fold_dw_kernel<<<dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st>>>(
-        part, flag, dW, dwq, elems, pl.splits, ldexp(1.0, -l), scale, accumulate);
-    return dk_launch_status();
+    return run_fgemm(pl, Ap, Bp, part, flag, dwq, dW, l, scale, accumulate, "f_gemm_wgrad", st);
 }
