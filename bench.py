@@ -98,6 +98,17 @@ def cpu_baseline(d, budget_s=15.0):
     }
 
 
+def pmc_calibration_copies(torch):
+    """Three plain 1 GiB device copies: a transfer of known size against which
+    rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled."""
+    src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def field_workload(name):
     import dk_inputs
     if name == "field1":
@@ -144,6 +155,8 @@ def field_main(args):
     dk.load()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.pmc_calibration:
+        pmc_calibration_copies(torch)
     d, wname = field_workload(args.workload)
     L, K, G = d["layer"], d["K"], d["G"]
     S = K + 2
@@ -309,12 +322,7 @@ def main():
     torch.cuda.set_device(0)
 
     if args.pmc_calibration:
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        pmc_calibration_copies(torch)
 
     d, wname = workload(args.workload)
     L, K, G = d["layer"], d["K"], d["G"]

@@ -298,16 +298,29 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
                 asm volatile("" ::"v"(B[x][y]));                                                  \
             }                                                                                     \
     }
+    // (part index, k tile) of a step advance like a two-digit counter
+#define DKF_ADVANCE(PI, KT)                                                                       \
+    {                                                                                             \
+        if (KT + 1 == kt1) { KT = kt0; ++PI; } else ++KT;                                         \
+    }
+    int pi = 0, kt = kt0;                 // part index and k tile of the current step
+    int pi2 = 0, kt2 = kt0;               // ... of the step the next fetch is for
     if (nsteps > 0) {
         DKF_FETCH(0, kt0)
         DKF_STASH(flds)
+        DKF_ADVANCE(pi2, kt2)
+        if (nsteps > 1) DKF_FETCH(pi2, kt2)
+        DKF_ADVANCE(pi2, kt2)
     }
     __syncthreads();
 
     // Outer loop: weight groups; inner loop: the steps of one group, a plain
-    // pipelined MFMA loop (its last step already fetches the first tile of the
-    // next group, so only the first tile of the workgroup waits for memory).
-    int pi = 0, kt = kt0, step = 0;       // part index, k tile and number of the current step
+    // pipelined MFMA loop that runs on across part and group boundaries, so only
+    // the first tile of the workgroup waits for memory.  During step s the
+    // staging registers hold tile s+1 (its loads were issued before the barrier
+    // that opened step s); they go to the other LDS buffer during the last 32-k
+    // sub-step, and the loads of tile s+2 are issued right behind them.
+    int step = 0;
     while (step < nsteps) {
         const int q = DKF_PART(pi);
         const int w = (q & 1) + (q >> 1);
@@ -317,11 +330,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         for (; step < g_end; ++step) {
             const int8_t *cur = flds + (step & 1) * BUF_BYTES;
             int8_t *nxt = flds + ((step + 1) & 1) * BUF_BYTES;
-            const bool more = step + 1 < nsteps;
-            const bool part_ends = kt + 1 == kt1;
-            const int pi_n = part_ends ? pi + 1 : pi, kt_n = part_ends ? kt0 : kt + 1;
-            if (more) DKF_FETCH(pi_n, kt_n)
-            // Four 32-k steps.  The operands of step s+1 are read from LDS while
+            // Four 32-k sub-steps.  The operands of step s+1 are read from LDS while
             // the 16 MFMAs of step s issue (one read per two MFMAs); the LDS
             // writes of the next tile go between the MFMAs of the last step.
             i32x4 a0[2][2], b0[2][2], a1[2][2], b1[2][2];
@@ -348,8 +357,10 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
                 __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
             }
             __builtin_amdgcn_sched_barrier(0);
+            if (step + 2 < nsteps) DKF_FETCH(pi2, kt2)
             __syncthreads();
-            pi = pi_n; kt = kt_n;
+            DKF_ADVANCE(pi, kt)
+            DKF_ADVANCE(pi2, kt2)
         }
 
         // End of a weight group: recombine the three accumulators with the
@@ -379,6 +390,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         __builtin_amdgcn_sched_barrier(0);
     }
 #undef DKF_PART
+#undef DKF_ADVANCE
 #undef DKF_PACE_READS
 #undef DKF_KEEP
 #undef DKF_FETCH
