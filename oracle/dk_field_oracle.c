@@ -193,3 +193,96 @@ void orf_dense_wgrad_points(const fe *D, const fe *X, long R, long M, long N,
         out[q] = acc;
     }
 }
+
+/* NCHW cross-correlation over the field, no bias (the linear operation of a
+ * convolution layer on encoded rows):
+ * Y[s][co][h][w] = sum_{ci,a,b} W[co][ci][a][b] X[s][ci][h*st+a-pad][w*st+b-pad]  (mod p),
+ * zero outside the image. */
+void orf_conv_fwd(const fe *W, const fe *X, fe *Y, long R, long Ci, long H, long Wd,
+                  long Co, long kh, long kw, long st, long pad, fe p)
+{
+    const long Ho = (H + 2 * pad - kh) / st + 1, Wo = (Wd + 2 * pad - kw) / st + 1;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (long s = 0; s < R; ++s)
+        for (long co = 0; co < Co; ++co)
+            for (long h = 0; h < Ho; ++h)
+                for (long w = 0; w < Wo; ++w) {
+                    fe acc = 0;
+                    for (long ci = 0; ci < Ci; ++ci)
+                        for (long a = 0; a < kh; ++a)
+                            for (long b = 0; b < kw; ++b) {
+                                const long ih = h * st + a - pad, iw = w * st + b - pad;
+                                if (ih < 0 || ih >= H || iw < 0 || iw >= Wd) continue;
+                                acc = addmod(acc, mulmod(W[((co * Ci + ci) * kh + a) * kw + b],
+                                                         X[((s * Ci + ci) * H + ih) * Wd + iw], p), p);
+                            }
+                    Y[((s * Co + co) * Ho + h) * Wo + w] = acc;
+                }
+}
+
+/* Same, for a list of (s, co, h, w) output positions only. */
+void orf_conv_fwd_points(const fe *W, const fe *X, long Ci, long H, long Wd, long Co,
+                         long kh, long kw, long st, long pad, const long *pts, long npts,
+                         fe *out, fe p)
+{
+#pragma omp parallel for schedule(static)
+    for (long q = 0; q < npts; ++q) {
+        const long s = pts[4 * q], co = pts[4 * q + 1], h = pts[4 * q + 2], w = pts[4 * q + 3];
+        fe acc = 0;
+        for (long ci = 0; ci < Ci; ++ci)
+            for (long a = 0; a < kh; ++a)
+                for (long b = 0; b < kw; ++b) {
+                    const long ih = h * st + a - pad, iw = w * st + b - pad;
+                    if (ih < 0 || ih >= H || iw < 0 || iw >= Wd) continue;
+                    acc = addmod(acc, mulmod(W[((co * Ci + ci) * kh + a) * kw + b],
+                                             X[((s * Ci + ci) * H + ih) * Wd + iw], p), p);
+                }
+        out[q] = acc;
+    }
+}
+
+/* Weight-gradient correlation over the field:
+ * dWq[co][ci][a][b] = sum_{s,h,w} D[s][co][h][w] X[s][ci][h*st+a-pad][w*st+b-pad]  (mod p). */
+void orf_conv_wgrad(const fe *D, const fe *X, fe *dWq, long R, long Ci, long H, long Wd,
+                    long Co, long kh, long kw, long st, long pad, fe p)
+{
+    const long Ho = (H + 2 * pad - kh) / st + 1, Wo = (Wd + 2 * pad - kw) / st + 1;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (long co = 0; co < Co; ++co)
+        for (long ci = 0; ci < Ci; ++ci)
+            for (long a = 0; a < kh; ++a)
+                for (long b = 0; b < kw; ++b) {
+                    fe acc = 0;
+                    for (long s = 0; s < R; ++s)
+                        for (long h = 0; h < Ho; ++h)
+                            for (long w = 0; w < Wo; ++w) {
+                                const long ih = h * st + a - pad, iw = w * st + b - pad;
+                                if (ih < 0 || ih >= H || iw < 0 || iw >= Wd) continue;
+                                acc = addmod(acc, mulmod(D[((s * Co + co) * Ho + h) * Wo + w],
+                                                         X[((s * Ci + ci) * H + ih) * Wd + iw], p), p);
+                            }
+                    dWq[((co * Ci + ci) * kh + a) * kw + b] = acc;
+                }
+}
+
+/* Same, for a list of (co, ci, a, b) positions only. */
+void orf_conv_wgrad_points(const fe *D, const fe *X, long R, long Ci, long H, long Wd,
+                           long Co, long kh, long kw, long st, long pad, const long *pts,
+                           long npts, fe *out, fe p)
+{
+    const long Ho = (H + 2 * pad - kh) / st + 1, Wo = (Wd + 2 * pad - kw) / st + 1;
+#pragma omp parallel for schedule(static)
+    for (long q = 0; q < npts; ++q) {
+        const long co = pts[4 * q], ci = pts[4 * q + 1], a = pts[4 * q + 2], b = pts[4 * q + 3];
+        fe acc = 0;
+        for (long s = 0; s < R; ++s)
+            for (long h = 0; h < Ho; ++h)
+                for (long w = 0; w < Wo; ++w) {
+                    const long ih = h * st + a - pad, iw = w * st + b - pad;
+                    if (ih < 0 || ih >= H || iw < 0 || iw >= Wd) continue;
+                    acc = addmod(acc, mulmod(D[((s * Co + co) * Ho + h) * Wo + w],
+                                             X[((s * Ci + ci) * H + ih) * Wd + iw], p), p);
+                }
+        out[q] = acc;
+    }
+}

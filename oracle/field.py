@@ -209,6 +209,74 @@ def dense_wgrad_points(D, X, pts, p=P):
     return out
 
 
+def conv_out_hw(H, W, kh, kw, stride, pad):
+    return (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+
+
+def conv_fwd(Wq, X, stride=1, pad=0, p=P):
+    Wq, X = _u(Wq), _u(X)
+    Co, Ci, kh, kw = Wq.shape
+    R, _, H, Wd = X.shape
+    Ho, Wo = conv_out_hw(H, Wd, kh, kw, stride, pad)
+    Y = np.empty((R, Co, Ho, Wo), dtype=np.uint32)
+    _L().orf_conv_fwd(_p(Wq), _p(X), _p(Y), _l(R), _l(Ci), _l(H), _l(Wd), _l(Co), _l(kh), _l(kw),
+                      _l(stride), _l(pad), _fe(p))
+    return Y
+
+
+def conv_fwd_points(Wq, X, pts, stride=1, pad=0, p=P):
+    Wq, X = _u(Wq), _u(X)
+    Co, Ci, kh, kw = Wq.shape
+    _, _, H, Wd = X.shape
+    pts = np.ascontiguousarray(pts, dtype=np.int64).reshape(-1, 4)
+    out = np.empty(len(pts), dtype=np.uint32)
+    _L().orf_conv_fwd_points(_p(Wq), _p(X), _l(Ci), _l(H), _l(Wd), _l(Co), _l(kh), _l(kw), _l(stride),
+                             _l(pad), _p(pts), _l(len(pts)), _p(out), _fe(p))
+    return out
+
+
+def conv_wgrad(D, X, kh, kw, stride=1, pad=0, p=P):
+    D, X = _u(D), _u(X)
+    R, Co = D.shape[:2]
+    _, Ci, H, Wd = X.shape
+    out = np.empty((Co, Ci, kh, kw), dtype=np.uint32)
+    _L().orf_conv_wgrad(_p(D), _p(X), _p(out), _l(R), _l(Ci), _l(H), _l(Wd), _l(Co), _l(kh), _l(kw),
+                        _l(stride), _l(pad), _fe(p))
+    return out
+
+
+def conv_wgrad_points(D, X, kh, kw, pts, stride=1, pad=0, p=P):
+    D, X = _u(D), _u(X)
+    R, Co = D.shape[:2]
+    _, Ci, H, Wd = X.shape
+    pts = np.ascontiguousarray(pts, dtype=np.int64).reshape(-1, 4)
+    out = np.empty(len(pts), dtype=np.uint32)
+    _L().orf_conv_wgrad_points(_p(D), _p(X), _l(R), _l(Ci), _l(H), _l(Wd), _l(Co), _l(kh), _l(kw),
+                               _l(stride), _l(pad), _p(pts), _l(len(pts)), _p(out), _fe(p))
+    return out
+
+
+def masked_layer(W, X, r, delta, A, gamma, stride=1, pad=0, l=L_BITS, p=P):
+    """masked_dense_layer for either kind of layer: W 2-D is the dense layer,
+    W 4-D the NCHW convolution (same steps, the convolution as the linear
+    operation and the correlation as the weight-gradient contraction)."""
+    if np.ndim(W) == 2:
+        return masked_dense_layer(W, X, r, delta, A, gamma, l, p)
+    Ainv, nvec, B = coefficients(A, gamma, p)
+    Wq, Xq = quantize(W, l, p), quantize(X, l, p)
+    Xbar = encode(Xq, r, A, p)
+    Ybar = conv_fwd(Wq, Xbar, stride, pad, p)
+    verdict = verify(Ybar, nvec, p)
+    Yq = decode(Ybar, Ainv, None, p)
+    Y = dequantize(Yq, l, p)
+    Dq = quantize(delta, l, p)
+    Dtilde = delta_mix(Dq, B, gamma, p)
+    dWq = conv_wgrad(Dtilde, Xbar, W.shape[2], W.shape[3], stride, pad, p)
+    dW = dequantize(dWq, l, p)
+    return dict(Wq=Wq, Xq=Xq, Xbar=Xbar, Ybar=Ybar, verdict=verdict, Yq=Yq, Y=Y, Dq=Dq,
+                Dtilde=Dtilde, dWq=dWq, dW=dW)
+
+
 def masked_dense_layer(W, X, r, delta, A, gamma, l=L_BITS, p=P):
     """The staged field path for a dense layer, in the order of the
     quantisation algorithm: quantise W and X, encode, multiply on encodings,

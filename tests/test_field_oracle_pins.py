@@ -236,3 +236,59 @@ def test_planted_mistakes_are_caught():
     wrong = np.ascontiguousarray(Ainv.transpose(0, 2, 1))
     assert not np.array_equal(F.decode(o["Ybar"], wrong), o["Yq"])
     assert F.verify(o["Ybar"], np.ascontiguousarray(Ainv[:, :, K])).any()
+
+
+def _int_corr(Wi, Xi, stride, pad):
+    """Cross-correlation of int64 arrays with scipy's correlate2d (valid mode on
+    a zero-padded image, then subsampled): an independent library routine."""
+    from scipy.signal import correlate2d
+    R, Ci, H, W = Xi.shape
+    Co, _, kh, kw = Wi.shape
+    Xp = np.pad(Xi, ((0, 0), (0, 0), (pad, pad), (pad, pad)))
+    out = []
+    for s in range(R):
+        rows = []
+        for co in range(Co):
+            acc = sum(correlate2d(Xp[s, ci], Wi[co, ci], mode="valid") for ci in range(Ci))
+            rows.append(acc[::stride, ::stride])
+        out.append(rows)
+    return np.array(out, dtype=np.int64)
+
+
+@pytest.mark.parametrize("K,G,Ci,Co,H,W,k,stride,pad", [(2, 1, 3, 4, 6, 5, 3, 1, 1), (1, 2, 2, 3, 7, 7, 3, 2, 1),
+                                                        (4, 1, 3, 2, 5, 6, 1, 1, 0), (2, 2, 2, 2, 6, 6, 2, 2, 0)])
+def test_staged_conv_path_equals_plain_integer_convolution(K, G, Ci, Co, H, W, k, stride, pad):
+    rng = np.random.default_rng([K, G, Ci, Co, H, 21])
+    L = dk_inputs.conv(Ci, Co, H, W, k, stride, pad)
+    d = dk_inputs.field_layer_inputs(rng, L, K=K, batch=G * K, w_std=0.5, delta_std=1.0)
+    o = F.masked_layer(d["W"], d["X"], d["r"], d["delta"], d["A"], d["gamma"], stride=stride, pad=pad)
+    Wi, Xi, Di = (np.floor(a.astype(np.float64) * 256 + 0.5).astype(np.int64) for a in (d["W"], d["X"], d["delta"]))
+    assert np.array_equal(_lift(o["Yq"]), _int_corr(Wi, Xi, stride, pad))
+    assert not o["verdict"].any()
+    # weight gradient: dW[co][ci] = sum_s correlate(X[s][ci] padded, D[s][co] dilated by the stride)
+    from scipy.signal import correlate2d
+    Ho, Wo = F.conv_out_hw(H, W, k, k, stride, pad)
+    Xp = np.pad(Xi, ((0, 0), (0, 0), (pad, pad), (pad, pad)))
+    want = np.zeros((Co, Ci, k, k), dtype=np.int64)
+    for s in range(G * K):
+        for co in range(Co):
+            Dd = np.zeros(((Ho - 1) * stride + 1, (Wo - 1) * stride + 1), dtype=np.int64)
+            Dd[::stride, ::stride] = Di[s, co]
+            for ci in range(Ci):
+                want[co, ci] += correlate2d(Xp[s, ci], Dd, mode="valid")[:k, :k]
+    assert np.array_equal(_lift(o["dWq"]), want)
+    # sampled evaluators agree with the full ones
+    pts = [(0, 0, 0, 0), (G * (K + 2) - 1, Co - 1, Ho - 1, Wo - 1), (1, Co // 2, Ho // 2, 0)]
+    assert F.conv_fwd_points(o["Wq"], o["Xbar"], pts, stride, pad).tolist() == [int(o["Ybar"][t]) for t in pts]
+    wpts = [(0, 0, 0, 0), (Co - 1, Ci - 1, k - 1, k - 1)]
+    assert F.conv_wgrad_points(o["Dtilde"], o["Xbar"], k, k, wpts, stride, pad).tolist() == [int(o["dWq"][t]) for t in wpts]
+
+
+def test_field_conv_1x1_is_a_matmul_over_pixels():
+    rng = np.random.default_rng(31)
+    R, Ci, Co, H, W = 2, 5, 3, 4, 3
+    X = rng.integers(0, P, size=(R, Ci, H, W), dtype=np.uint32)
+    Wq = rng.integers(0, P, size=(Co, Ci, 1, 1), dtype=np.uint32)
+    Y = F.conv_fwd(Wq, X)
+    flat = F.dense_fwd(Wq.reshape(Co, Ci), np.ascontiguousarray(X.transpose(0, 2, 3, 1).reshape(-1, Ci)))
+    assert np.array_equal(Y, flat.reshape(R, H, W, Co).transpose(0, 3, 1, 2))
