@@ -1,6 +1,6 @@
 /*
  * darknight_field.h -- C ABI of the finite-field variant of the masked layer
- * (MI355X / gfx950), dense layers.
+ * (MI355X / gfx950), dense layers and NCHW convolutions.
  *
  * The paper's privacy statement holds for a version of the scheme in which
  * every value is an element of the prime field F_p, p = 2^25 - 39 (section
@@ -77,6 +77,16 @@ dk_status dkf_encode(const float *x, const uint32_t *r, const uint32_t *A, uint3
 dk_status dkf_linear_fwd(const uint32_t *Wq, const uint32_t *xbar, uint32_t *ybar,
                          int M, int N, int R, void *ws, size_t ws_bytes, void *stream);
 
+/* The same step for a convolution layer (kind DK_CONV2D): NCHW
+ * cross-correlation without bias over the field,
+ *   ybar[rho][co][h][w] = sum_{ci,a,b} Wq[co][ci][a][b]
+ *                         * xbar[rho][ci][h*stride+a-pad][w*stride+b-pad]  mod p
+ * (zero outside the image).  Wq[Co][Ci][kh][kw], xbar[R][Ci][H][W] ->
+ * ybar[R][Co][Ho][Wo], all device.  DK_ERR_UNSUPPORTED for a dense layer.
+ * Workspace: dkf_conv_fwd_workspace_bytes(L, R), 256-byte aligned. */
+dk_status dkf_conv_fwd(const dk_layer *L, const uint32_t *Wq, const uint32_t *xbar,
+                       uint32_t *ybar, int R, void *ws, size_t ws_bytes, void *stream);
+
 /* Integrity check and decoding of the forward results in one pass over ybar
  * (section Computational Integrity; quantisation algorithm, Y_q and Y):
  *   t[e]      = sum_j nvec[g][j] ybar[gS+j][e]  mod p;
@@ -90,17 +100,19 @@ dk_status dkf_decode_verify(const uint32_t *ybar, const uint32_t *Ainv, const ui
                             float *y, uint32_t *yq, int *verdict,
                             int G, int K, long long m, int l, void *stream);
 
-/* Masked weight gradient of a dense layer over the field (Backward
- * Propagation: the accelerator forms delta-bar = delta B^T and the
- * per-encoding products with the stored xbar; gamma_j weights term j):
+/* Masked weight gradient over the field (Backward Propagation: the
+ * accelerator forms delta-bar = delta B^T and the per-encoding products with
+ * the stored xbar; gamma_j weights term j):
  *   Dq = Field(Round(delta * 2^l));
  *   dtilde[gS+j] = gamma[g][j] * sum_{i<K} B[g][j][i] Dq[gK+i]   mod p;
- *   dWq[o][k] = sum_rho dtilde[rho][o] xbar[rho][k]               mod p;
+ *   dense: dWq[o][k] = sum_rho dtilde[rho][o] xbar[rho][k]        mod p;
+ *   conv:  dWq[co][ci][a][b] = sum_{rho,h,w} dtilde[rho][co][h][w]
+ *                              * xbar[rho][ci][h*stride+a-pad][w*stride+b-pad]  mod p;
  *   dW = (accumulate ? dW : 0) + scale * Round(lift(dWq) * 2^-l) * 2^-l.
- * L must be a dense layer (DK_ERR_UNSUPPORTED otherwise).  delta[G*K][M]
- * float, B[G][S][K], gamma[G][S], xbar[G*S][N] -> dW[M][N] float, all device.
- * dwq[M][N] (device) receives the field values if not NULL.  Workspace:
- * dkf_wgrad_workspace_bytes(L, G, K), 256-byte aligned. */
+ * delta[G*K][m] float, B[G][S][K], gamma[G][S], xbar[G*S][n] -> dW (shape of
+ * the layer's weights) float, all device.  dwq (same shape, device) receives
+ * the field values if not NULL.  Workspace: dkf_wgrad_workspace_bytes(L, G, K),
+ * 256-byte aligned. */
 dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint32_t *B,
                     const uint32_t *gamma, const uint32_t *xbar, float *dW, uint32_t *dwq,
                     int G, int K, int l, float scale, int accumulate,
@@ -108,6 +120,7 @@ dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint32_t *B,
 
 /* Workspace sizes in bytes (0 for invalid arguments). */
 size_t dkf_fwd_workspace_bytes(int M, int N, int R);
+size_t dkf_conv_fwd_workspace_bytes(const dk_layer *L, int R);
 size_t dkf_wgrad_workspace_bytes(const dk_layer *L, int G, int K);
 
 #ifdef __cplusplus

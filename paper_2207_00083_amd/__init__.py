@@ -13,11 +13,12 @@ from .binding import (DkError, DkLayer, lib_path, load, dk_version, dk_status_st
                       DK_OP_FWD, DK_OP_WGRAD, DK_OP_VERIFY, DK_MAX_K)
 
 from .field import (DKF_P, DKF_L, dkf_coeffs, dkf_quantize, dkf_dequantize, dkf_encode, dkf_linear_fwd,
-                    dkf_decode_verify, dkf_wgrad, dkf_fwd_workspace_bytes, dkf_wgrad_workspace_bytes)
+                    dkf_decode_verify, dkf_wgrad, dkf_fwd_workspace_bytes, dkf_wgrad_workspace_bytes,
+                    dkf_conv_fwd, dkf_conv_fwd_workspace_bytes)
 
 __all__ = ["DKF_P", "DKF_L", "dkf_coeffs", "dkf_quantize", "dkf_dequantize", "dkf_encode",
            "dkf_linear_fwd", "dkf_decode_verify", "dkf_wgrad", "dkf_fwd_workspace_bytes",
-           "dkf_wgrad_workspace_bytes",
+           "dkf_wgrad_workspace_bytes", "dkf_conv_fwd", "dkf_conv_fwd_workspace_bytes",
            "DkError", "DkLayer", "lib_path", "load", "dk_version", "dk_status_str",
            "dk_workspace_bytes", "dk_layer_in_len", "dk_layer_out_len", "dk_coeffs",
            "dk_encode", "dk_linear_fwd", "dk_conv_fwd", "dk_wgrad", "dk_decode", "dk_verify",

@@ -81,6 +81,8 @@ def load():
         "dkf_linear_fwd": (ip, [vp, vp, vp, ip, ip, ip, vp, sz, vp]),
         "dkf_decode_verify": (ip, [vp, vp, vp, vp, vp, vp, ip, ip, ll, ip, vp]),
         "dkf_wgrad": (ip, [LP, vp, vp, vp, vp, vp, vp, ip, ip, ip, fl, ip, vp, sz, vp]),
+        "dkf_conv_fwd": (ip, [LP, vp, vp, vp, ip, vp, sz, vp]),
+        "dkf_conv_fwd_workspace_bytes": (sz, [LP, ip]),
         "dkf_fwd_workspace_bytes": (sz, [ip, ip, ip]),
         "dkf_wgrad_workspace_bytes": (sz, [LP, ip, ip]),
         "dk_profile_enable": (ip, [ip]),

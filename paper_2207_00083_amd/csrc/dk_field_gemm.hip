@@ -47,6 +47,7 @@ struct fgemm_params {
     long long a_plane, b_plane;   // bytes per plane
     int I, J, Kp;
     int tiles_i, tiles_j, splits, ktiles_per_split, ktiles;
+    int out_hw;            // 0: C[i][j] at i*J + j;  hw > 0: j = (image, pixel), C at ((image*I + i)*hw + pixel
     double s_inv;          // 2^-l for out_f
     float scale;
     int accumulate;
@@ -154,6 +155,77 @@ __global__ __launch_bounds__(256) void f_digits_t_kernel(const uint32_t *__restr
 #pragma unroll
         for (int a = 0; a < 4; ++a)
             *reinterpret_cast<u32x4 *>(planes + a * plane + (long long)(c0 + col) * Kp + k0 + 16 * kq) = w[a];
+    }
+    raise_flag(flag, hi != 0);
+}
+
+// Digit planes of the operands of a convolution, gathered from NCHW field
+// tensors.  A workgroup converts 1024 consecutive k of one row, a thread four.
+//   MODE 0 (forward, B): row = (image r, oh, ow), k = (ci, a, b):
+//                        xbar[r][ci][oh*stride + a - pad][ow*stride + b - pad]
+//   MODE 1 (weight gradient, A): row = co, k = (r, pixel): dtilde[r][co][pixel]
+//   MODE 2 (weight gradient, B): row = (ci, a, b), k = (r, oh, ow): the same
+//                        xbar element as in MODE 0
+// Positions outside the image, rows beyond `rows` and k beyond K give zeros.
+struct fconv_geom {
+    int Ci, Co, H, W, kh, kw, stride, pad, Ho, Wo, HoWo;
+};
+
+template <int MODE>
+__global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__restrict__ src,
+                                                            int8_t *__restrict__ planes, fconv_geom g,
+                                                            int rows, int K, int rows_pad, int Kp,
+                                                            int chunks, int *flag)
+{
+    const int row = blockIdx.x / chunks;                       // workgroup-uniform
+    const int k0 = ((blockIdx.x - row * chunks) * 256 + threadIdx.x) * 4;
+    if (k0 >= Kp) return;
+    const int khw = g.kh * g.kw;
+    // what the row fixes
+    int r_img = 0, r_oh = 0, r_ow = 0, r_ci = 0, r_a = 0, r_b = 0;
+    if (MODE == 0) {
+        r_img = row / g.HoWo;
+        const int px = row - r_img * g.HoWo;
+        r_oh = px / g.Wo; r_ow = px - r_oh * g.Wo;
+    } else if (MODE == 2) {
+        r_ci = row / khw;
+        const int ab = row - r_ci * khw;
+        r_a = ab / g.kw; r_b = ab - r_a * g.kw;
+    }
+    uint32_t d[4] = {0, 0, 0, 0};
+    if (row < rows) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int k = k0 + c;
+            if (k >= K) continue;
+            long long idx = -1;
+            if (MODE == 1) {
+                const int img = k / g.HoWo, px = k - img * g.HoWo;
+                idx = ((long long)img * g.Co + row) * g.HoWo + px;
+            } else {
+                int img, ci, ih, iw;
+                if (MODE == 0) {
+                    ci = k / khw;
+                    const int ab = k - ci * khw, a = ab / g.kw, b = ab - a * g.kw;
+                    img = r_img; ih = r_oh * g.stride + a - g.pad; iw = r_ow * g.stride + b - g.pad;
+                } else {
+                    img = k / g.HoWo;
+                    const int px = k - img * g.HoWo, oh = px / g.Wo, ow = px - oh * g.Wo;
+                    ci = r_ci; ih = oh * g.stride + r_a - g.pad; iw = ow * g.stride + r_b - g.pad;
+                }
+                if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)
+                    idx = (((long long)img * g.Ci + ci) * g.H + ih) * g.W + iw;
+            }
+            if (idx >= 0) d[c] = digits_of(src[idx]);
+        }
+    }
+    const long long plane = (long long)rows_pad * Kp;
+    uint32_t hi = 0;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const uint32_t w = gather_byte(d, a);
+        if (a >= 2) hi |= w;
+        *reinterpret_cast<uint32_t *>(planes + a * plane + (long long)row * Kp + k0) = w;
     }
     raise_flag(flag, hi != 0);
 }
@@ -398,17 +470,19 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 #undef DKF_READ
 #undef DKF_MMA
 
-    uint32_t *dst_q = p.out_q ? p.out_q + (long long)split * p.I * p.J : nullptr;
+    uint32_t *dst_q = p.out_q ? p.out_q + (long long)split * p.I * p.J : nullptr;   // (one slice if remapped)
 #pragma unroll
     for (int bi = 0; bi < 2; ++bi)
 #pragma unroll
         for (int bj = 0; bj < 2; ++bj) {
             const int j = tj * BJ + wj0 + bj * 32 + li;
+            const int jimg = p.out_hw ? j / p.out_hw : 0, jpix = p.out_hw ? j - jimg * p.out_hw : 0;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int i = ti * BI + wi0 + bi * 32 + 8 * (v / 4) + 4 * lh + (v % 4);
                 if (i < p.I && j < p.J) {
-                    const long long o = (long long)i * p.J + j;
+                    const long long o = p.out_hw ? ((long long)jimg * p.I + i) * p.out_hw + jpix
+                                                 : (long long)i * p.J + j;
                     const uint32_t q = res[bi][bj][v];
                     if (dst_q) dst_q[o] = q;
                     if (p.out_f) {
@@ -421,19 +495,28 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 }
 
 // Fold of the k slices: out[e] = sum_k part[k][e] (mod p); at most 16 residues
-// below 2^25 are added in 32 bits.  With dW != NULL the sum is de-quantised:
+// below 2^25 are added in 32 bits.  With dW != NULL the sum is de-quantised
+// (dW is never remapped: a weight gradient is [I][J] already):
 // dW = (accumulate ? dW : 0) + scale * Round(lift(q) * 2^-l) * 2^-l.
 __global__ __launch_bounds__(256) void f_fold_kernel(const uint32_t *__restrict__ part,
                                                      uint32_t *__restrict__ out_q, float *__restrict__ dW,
                                                      long long elems, int splits, double s_inv,
-                                                     float scale, int accumulate)
+                                                     float scale, int accumulate, int I, int J, int out_hw)
 {
     const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
     if (e >= elems) return;
     uint32_t s = 0;
     for (int k = 0; k < splits; ++k) s += part[(long long)k * elems + e];
     const uint32_t q = dkf_reduce(s);
-    if (out_q) out_q[e] = q;
+    if (out_q) {
+        long long o = e;
+        if (out_hw) {                         // slices are [I][J]; the result is image-major
+            const int i = (int)(e / J), j = (int)(e - (long long)i * J);
+            const int img = j / out_hw;
+            o = ((long long)img * I + i) * out_hw + (j - img * out_hw);
+        }
+        out_q[o] = q;
+    }
     if (dW) {
         const float v = scale * dkf_dequant(q, s_inv);
         dW[e] = accumulate ? dW[e] + v : v;
@@ -495,7 +578,7 @@ constexpr size_t FLAG_BYTES = 256;
 // kernel finishes.
 dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, uint32_t *part,
                     const int *flags, uint32_t *out_q, float *out_f, int l, float scale,
-                    int accumulate, const char *label, hipStream_t st)
+                    int accumulate, int out_hw, const char *label, hipStream_t st)
 {
     static bool allowed = false;
     if (!allowed) {
@@ -515,6 +598,7 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
     p.tiles_i = pl.tiles_i; p.tiles_j = pl.tiles_j; p.splits = pl.splits;
     p.ktiles_per_split = pl.ktiles_per_split; p.ktiles = pl.ktiles;
     p.s_inv = ldexp(1.0, -l); p.scale = scale; p.accumulate = accumulate;
+    p.out_hw = direct ? out_hw : 0;
     const long long blocks = (long long)pl.splits * pl.tiles_i * pl.tiles_j;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     {
@@ -526,7 +610,7 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
     const long long elems = (long long)pl.I * pl.J;
     dk_prof_scope ps("f_fold", st);
     f_fold_kernel<<<dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st>>>(
-        part, out_q, out_f, elems, pl.splits, p.s_inv, scale, accumulate);
+        part, out_q, out_f, elems, pl.splits, p.s_inv, scale, accumulate, pl.I, pl.J, out_hw);
     return dk_launch_status();
 }
 
@@ -553,6 +637,86 @@ dk_status run_digits_t(const uint32_t *src, int8_t *planes, int K, int cols, int
     return dk_launch_status();
 }
 
+template <int MODE>
+dk_status run_digits_conv(const uint32_t *src, int8_t *planes, const fconv_geom &cg, int rows, int K,
+                          int rows_pad, int Kp, int *flag, hipStream_t st)
+{
+    const int chunks = (Kp / 4 + 255) / 256;
+    const long long blocks = (long long)rows_pad * chunks;
+    DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
+    dk_prof_scope ps(MODE == 0 ? "f_digits_im2col" : (MODE == 1 ? "f_digits_dt" : "f_digits_im2col_t"), st);
+    f_digits_conv_kernel<MODE><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(src, planes, cg, rows, K,
+                                                                             rows_pad, Kp, chunks, flag);
+    return dk_launch_status();
+}
+
+fconv_geom conv_geom_of(const dk_geom &g)
+{
+    fconv_geom c;
+    c.Ci = g.Ci; c.Co = g.Co; c.H = g.H; c.W = g.W; c.kh = g.kh; c.kw = g.kw;
+    c.stride = g.stride; c.pad = g.pad; c.Ho = g.Ho; c.Wo = g.Wo; c.HoWo = g.Ho * g.Wo;
+    return c;
+}
+
+// Convolution forward as C[co][(r, pixel)] = W[co][(ci,a,b)] . patches: I = Co,
+// J = R*Ho*Wo, K = Ci*kh*kw.  Weight gradient as C[co][(ci,a,b)] over
+// k = (r, pixel): I = Co, J = Ci*kh*kw, K = R*Ho*Wo.
+bool plan_conv_fwd(const dk_geom &g, long long R, fgemm_plan *pl)
+{
+    return plan_fgemm(g.Co, R * g.Ho * g.Wo, g.Kg, pl);
+}
+bool plan_conv_wgrad(const dk_geom &g, long long R, fgemm_plan *pl)
+{
+    return plan_fgemm(g.Co, g.Kg, R * g.Ho * g.Wo, pl);
+}
+
+} // namespace
+
+DK_EXPORT size_t dkf_conv_fwd_workspace_bytes(const dk_layer *L, int R)
+{
+    dk_geom g;
+    if (dk_layer_geom(L, &g) != DK_OK || !g.conv || R < 1) return 0;
+    fgemm_plan pl;
+    if (!plan_conv_fwd(g, R, &pl)) return 0;
+    return FLAG_BYTES + pl.a_bytes + pl.b_bytes + pl.part_bytes;
+}
+
+DK_EXPORT dk_status dkf_conv_fwd(const dk_layer *L, const uint32_t *Wq, const uint32_t *xbar,
+                                 uint32_t *ybar, int R, void *ws, size_t ws_bytes, void *stream)
+{
+    DK_REQUIRE(L && Wq && xbar && ybar, DK_ERR_NULL);
+    dk_geom g;
+    const dk_status gs = dk_layer_geom(L, &g);
+    if (gs != DK_OK) return gs;
+    DK_REQUIRE(g.conv, DK_ERR_UNSUPPORTED);
+    DK_REQUIRE(R >= 1, DK_ERR_SHAPE);
+    fgemm_plan pl;
+    DK_REQUIRE(plan_conv_fwd(g, R, &pl), DK_ERR_SHAPE);
+    DK_REQUIRE(dk_aligned(Wq, 4) && dk_aligned(xbar, 4) && dk_aligned(ybar, 4), DK_ERR_ALIGN);
+    DK_REQUIRE(ws && ws_bytes >= FLAG_BYTES + pl.a_bytes + pl.b_bytes + pl.part_bytes, DK_ERR_WORKSPACE);
+    DK_REQUIRE(dk_aligned(ws, 256), DK_ERR_ALIGN);
+    hipStream_t st = (hipStream_t)stream;
+
+    char *w = (char *)ws;
+    int *flag = (int *)w;                          w += FLAG_BYTES;
+    int8_t *Ap = (int8_t *)w;                      w += pl.a_bytes;
+    int8_t *Bp = (int8_t *)w;                      w += pl.b_bytes;
+    uint32_t *part = (uint32_t *)w;
+
+    {
+        dk_prof_scope ps("f_flag_clear", st);
+        f_flag_clear_kernel<<<dim3(1), dim3(64), 0, st>>>(flag);
+    }
+    DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+    dk_status s = run_digits(Wq, Ap, g.Co, (int)g.Kg, pl.I_pad, pl.Kp, flag, st);
+    if (s != DK_OK) return s;
+    s = run_digits_conv<0>(xbar, Bp, conv_geom_of(g), pl.J, (int)g.Kg, pl.J_pad, pl.Kp, flag + 1, st);
+    if (s != DK_OK) return s;
+    return run_fgemm(pl, Ap, Bp, part, flag, ybar, nullptr, 0, 1.0f, 0, g.Ho * g.Wo, "f_gemm_fwd", st);
+}
+
+namespace {
+
 } // namespace
 
 DK_EXPORT size_t dkf_fwd_workspace_bytes(int M, int N, int R)
@@ -565,12 +729,12 @@ DK_EXPORT size_t dkf_fwd_workspace_bytes(int M, int N, int R)
 DK_EXPORT size_t dkf_wgrad_workspace_bytes(const dk_layer *L, int G, int K)
 {
     dk_geom g;
-    if (dk_layer_geom(L, &g) != DK_OK || g.conv) return 0;
+    if (dk_layer_geom(L, &g) != DK_OK) return 0;
     if (G < 1 || K < 1 || K > DK_MAX_K) return 0;
     const long long R = (long long)G * (K + 2);
     fgemm_plan pl;
-    if (!plan_fgemm(g.M, g.N, R, &pl)) return 0;
-    return FLAG_BYTES + align256((size_t)R * g.M * sizeof(uint32_t)) + pl.a_bytes + pl.b_bytes + pl.part_bytes;
+    if (!(g.conv ? plan_conv_wgrad(g, R, &pl) : plan_fgemm(g.M, g.N, R, &pl))) return 0;
+    return FLAG_BYTES + align256((size_t)R * g.m * sizeof(uint32_t)) + pl.a_bytes + pl.b_bytes + pl.part_bytes;
 }
 
 DK_EXPORT dk_status dkf_linear_fwd(const uint32_t *Wq, const uint32_t *xbar, uint32_t *ybar,
@@ -600,7 +764,7 @@ DK_EXPORT dk_status dkf_linear_fwd(const uint32_t *Wq, const uint32_t *xbar, uin
     if (s != DK_OK) return s;
     s = run_digits(Wq, Bp, M, N, pl.J_pad, pl.Kp, flag + 1, st);
     if (s != DK_OK) return s;
-    return run_fgemm(pl, Ap, Bp, part, flag, ybar, nullptr, 0, 1.0f, 0, "f_gemm_fwd", st);
+    return run_fgemm(pl, Ap, Bp, part, flag, ybar, nullptr, 0, 1.0f, 0, 0, "f_gemm_fwd", st);
 }
 
 DK_EXPORT dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint32_t *B,
@@ -612,15 +776,14 @@ DK_EXPORT dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint3
     dk_geom g;
     const dk_status gs = dk_layer_geom(L, &g);
     if (gs != DK_OK) return gs;
-    DK_REQUIRE(!g.conv, DK_ERR_UNSUPPORTED);
     DK_REQUIRE(G >= 1 && K >= 1 && K <= DK_MAX_K && l >= 0 && l <= DKF_MAX_L, DK_ERR_SHAPE);
     const long long R = (long long)G * (K + 2);
     fgemm_plan pl;
-    DK_REQUIRE(plan_fgemm(g.M, g.N, R, &pl), DK_ERR_SHAPE);
-    DK_REQUIRE(pl.Kp / 128 <= 65535, DK_ERR_SHAPE);         // grid.y of the transposing digit kernel
+    DK_REQUIRE(g.conv ? plan_conv_wgrad(g, R, &pl) : plan_fgemm(g.M, g.N, R, &pl), DK_ERR_SHAPE);
+    DK_REQUIRE(g.conv || pl.Kp / 128 <= 65535, DK_ERR_SHAPE);   // grid.y of the transposing digit kernel
     DK_REQUIRE(dk_aligned(delta, 4) && dk_aligned(B, 4) && dk_aligned(gamma, 4) && dk_aligned(xbar, 4) &&
                    dk_aligned(dW, 4) && (!dwq || dk_aligned(dwq, 4)), DK_ERR_ALIGN);
-    const size_t dt_bytes = align256((size_t)R * g.M * sizeof(uint32_t));
+    const size_t dt_bytes = align256((size_t)R * g.m * sizeof(uint32_t));
     DK_REQUIRE(ws && ws_bytes >= FLAG_BYTES + dt_bytes + pl.a_bytes + pl.b_bytes + pl.part_bytes, DK_ERR_WORKSPACE);
     DK_REQUIRE(dk_aligned(ws, 256), DK_ERR_ALIGN);
     hipStream_t st = (hipStream_t)stream;
@@ -632,17 +795,26 @@ DK_EXPORT dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint3
     int8_t *Bp = (int8_t *)w;                      w += pl.b_bytes;
     uint32_t *part = (uint32_t *)w;
 
-    dk_status s = dkf_delta_mix(delta, B, gamma, dtilde, G, K, g.M, l, st);
+    dk_status s = dkf_delta_mix(delta, B, gamma, dtilde, G, K, g.m, l, st);
     if (s != DK_OK) return s;
     {
         dk_prof_scope ps("f_flag_clear", st);
         f_flag_clear_kernel<<<dim3(1), dim3(64), 0, st>>>(flag);
     }
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
-    // the contraction index is the encoded row: both operands are transposed
-    s = run_digits_t(dtilde, Ap, (int)R, g.M, pl.I_pad, pl.Kp, flag, st);
-    if (s != DK_OK) return s;
-    s = run_digits_t(xbar, Bp, (int)R, g.N, pl.J_pad, pl.Kp, flag + 1, st);
-    if (s != DK_OK) return s;
-    return run_fgemm(pl, Ap, Bp, part, flag, dwq, dW, l, scale, accumulate, "f_gemm_wgrad", st);
+    if (g.conv) {
+        // the contraction index is (encoded row, output pixel)
+        const fconv_geom cg = conv_geom_of(g);
+        s = run_digits_conv<1>(dtilde, Ap, cg, g.Co, pl.K, pl.I_pad, pl.Kp, flag, st);
+        if (s != DK_OK) return s;
+        s = run_digits_conv<2>(xbar, Bp, cg, (int)g.Kg, pl.K, pl.J_pad, pl.Kp, flag + 1, st);
+        if (s != DK_OK) return s;
+    } else {
+        // the contraction index is the encoded row: both operands are transposed
+        s = run_digits_t(dtilde, Ap, (int)R, g.M, pl.I_pad, pl.Kp, flag, st);
+        if (s != DK_OK) return s;
+        s = run_digits_t(xbar, Bp, (int)R, g.N, pl.J_pad, pl.Kp, flag + 1, st);
+        if (s != DK_OK) return s;
+    }
+    return run_fgemm(pl, Ap, Bp, part, flag, dwq, dW, l, scale, accumulate, 0, "f_gemm_wgrad", st);
 }

@@ -10,7 +10,8 @@ import ctypes as C
 
 import numpy as np
 
-from .binding import DkLayer, _check, _dev, _ptr, _stream, _torch, _workspace, load
+from .binding import (DkError, DkLayer, _check, _dev, _ptr, _stream, _torch, _workspace, dk_layer_in_len,
+                      dk_layer_out_len, load)
 
 DKF_P = (1 << 25) - 39
 DKF_L = 8
@@ -112,6 +113,31 @@ def dkf_linear_fwd(Wq, xbar, ybar=None, ws=None, stream=None):
     return ybar
 
 
+def dkf_conv_fwd_workspace_bytes(layer, R) -> int:
+    return int(load().dkf_conv_fwd_workspace_bytes(C.byref(DkLayer.of(layer)), int(R)))
+
+
+def dkf_conv_fwd(layer, Wq, xbar, ybar=None, ws=None, stream=None):
+    """Wq[Co,Ci,kh,kw], xbar[R,Ci,H,W] field elements (device) -> ybar[R,Co,Ho,Wo]."""
+    lay = DkLayer.of(layer)
+    Wq, xbar = _fe(Wq, "Wq"), _fe(xbar, "xbar")
+    R = xbar.shape[0]
+    Ho = (lay.H + 2 * lay.pad - lay.kh) // lay.stride + 1
+    Wo = (lay.W + 2 * lay.pad - lay.kw) // lay.stride + 1
+    if xbar[0].numel() != lay.Ci * lay.H * lay.W or Wq.numel() != lay.Co * lay.Ci * lay.kh * lay.kw:
+        raise ValueError("dkf_conv_fwd: inconsistent shapes")
+    if ybar is None:
+        ybar = _new_fe((R, lay.Co, Ho, Wo), Wq)
+    _fe(ybar, "ybar")
+    if ybar.numel() != R * lay.Co * Ho * Wo:
+        raise ValueError("dkf_conv_fwd: ybar has the wrong size")
+    if ws is None:
+        ws = _workspace(dkf_conv_fwd_workspace_bytes(lay, R), Wq)
+    _check(load().dkf_conv_fwd(C.byref(lay), _ptr(Wq), _ptr(xbar), _ptr(ybar), R, _ptr(ws), ws.numel(),
+                               _stream(stream)), "dkf_conv_fwd")
+    return ybar
+
+
 def dkf_decode_verify(ybar, Ainv, nvec, K, l=DKF_L, y=None, yq=None, verdict=None, want_yq=False,
                       stream=None):
     """Returns (y float, yq or None, verdict int32)."""
@@ -139,24 +165,29 @@ def dkf_decode_verify(ybar, Ainv, nvec, K, l=DKF_L, y=None, yq=None, verdict=Non
 
 def dkf_wgrad(layer, delta, B, gamma, xbar, K, l=DKF_L, dW=None, dwq=None, want_dwq=False, scale=1.0,
               accumulate=False, ws=None, stream=None):
-    """delta[G*K,M] float, B[G,S,K], gamma[G,S], xbar[G*S,N] (device) -> (dW float, dwq or None)."""
+    """delta[G*K, ...] float, B[G,S,K], gamma[G,S], xbar[G*S, ...] (device) -> (dW float, dwq or None)."""
     torch = _torch()
     lay = DkLayer.of(layer)
     delta, B, gamma, xbar = _dev(delta, "delta"), _fe(B, "B"), _fe(gamma, "gamma"), _fe(xbar, "xbar")
     G, S = gamma.shape
-    if (S != K + 2 or tuple(B.shape) != (G, S, K) or delta.numel() != G * K * lay.M
-            or xbar.numel() != G * S * lay.N):
+    n, m = dk_layer_in_len(lay), dk_layer_out_len(lay)
+    if n == 0:
+        raise DkError(2, "dkf_wgrad")
+    if (S != K + 2 or tuple(B.shape) != (G, S, K) or delta.numel() != G * K * m
+            or xbar.numel() != G * S * n):
         raise ValueError("dkf_wgrad: inconsistent shapes")
+    wshape = (lay.M, lay.N) if lay.kind == 0 else (lay.Co, lay.Ci, lay.kh, lay.kw)
+    wcount = int(np.prod(wshape))
     if dW is None:
         if accumulate:
             raise ValueError("dkf_wgrad: accumulate needs an existing dW")
-        dW = torch.empty((lay.M, lay.N), dtype=torch.float32, device=delta.device)
+        dW = torch.empty(wshape, dtype=torch.float32, device=delta.device)
     _dev(dW, "dW")
     if dwq is None and want_dwq:
-        dwq = _new_fe((lay.M, lay.N), delta)
+        dwq = _new_fe(wshape, delta)
     if dwq is not None:
         _fe(dwq, "dwq")
-    if dW.numel() != lay.M * lay.N or (dwq is not None and dwq.numel() != lay.M * lay.N):
+    if dW.numel() != wcount or (dwq is not None and dwq.numel() != wcount):
         raise ValueError("dkf_wgrad: output has the wrong size")
     if ws is None:
         ws = _workspace(dkf_wgrad_workspace_bytes(lay, G, K), delta)

@@ -40,7 +40,8 @@ def test_every_declared_symbol_is_exported(dk):
     for must in ("dk_encode", "dk_linear_fwd", "dk_conv_fwd", "dk_wgrad", "dk_decode", "dk_verify",
                  "dk_coeffs", "dk_workspace_bytes", "dkf_coeffs", "dkf_quantize", "dkf_dequantize",
                  "dkf_encode", "dkf_linear_fwd", "dkf_decode_verify", "dkf_wgrad",
-                 "dkf_fwd_workspace_bytes", "dkf_wgrad_workspace_bytes"):
+                 "dkf_fwd_workspace_bytes", "dkf_wgrad_workspace_bytes", "dkf_conv_fwd",
+                 "dkf_conv_fwd_workspace_bytes"):
         assert must in names
     lib = C.CDLL(dk.lib_path())
     for n in names:
@@ -152,7 +153,10 @@ def test_field_errors_before_launch(dk):
     assert lib.dkf_decode_verify(one, one, one, one, null, null, 1, 2, 8, 8, null) == 1
     lin = dk.DkLayer.of(dk_inputs.linear(4, 4))
     conv = dk.DkLayer.of(dk_inputs.conv(4, 4, 8, 8, 3))
-    assert lib.dkf_wgrad(C.byref(conv), one, one, one, one, one, null, 1, 2, 8, 1.0, 0, one, 1 << 30, null) == 3
+    assert lib.dkf_wgrad(C.byref(conv), one, one, one, one, one, null, 1, 2, 8, 1.0, 0, one, 64, null) == 5
+    assert lib.dkf_conv_fwd(C.byref(lin), one, one, one, 4, one, 1 << 30, null) == 3
+    assert lib.dkf_conv_fwd(C.byref(conv), one, one, one, 0, one, 1 << 30, null) == 2
+    assert lib.dkf_conv_fwd(C.byref(conv), one, one, one, 4, one, 64, null) == 5
     assert lib.dkf_wgrad(C.byref(lin), one, one, one, one, one, null, 1, 2, 8, 1.0, 0, one, 64, null) == 5
     assert dk.dkf_fwd_workspace_bytes(4, 4, 4) > 0 and dk.dkf_fwd_workspace_bytes(0, 4, 4) == 0
     assert dk.dkf_wgrad_workspace_bytes(dk_inputs.linear(4, 4), 1, 2) > 0

@@ -202,6 +202,65 @@ def test_config5_field_sampled(dk, index):
     assert np.array_equal(host(dW), F.dequantize(got))
 
 
+@pytest.mark.parametrize("K,G,Ci,Co,H,W,k,stride,pad", [
+    (2, 1, 3, 5, 9, 7, 3, 1, 1), (4, 2, 16, 24, 12, 12, 3, 1, 1), (2, 3, 8, 130, 10, 10, 3, 2, 1),
+    (8, 1, 20, 12, 7, 7, 1, 1, 0), (1, 2, 6, 9, 11, 8, 5, 2, 2), (4, 1, 64, 64, 16, 16, 3, 1, 1)])
+def test_masked_conv_layer(dk, K, G, Ci, Co, H, W, k, stride, pad):
+    rng = np.random.default_rng([K, G, Ci, Co, H, k, 17])
+    L = dk_inputs.conv(Ci, Co, H, W, k, stride, pad)
+    d = dk_inputs.field_layer_inputs(rng, L, K=K, batch=G * K, delta_std=1.0)
+    o = F.masked_layer(d["W"], d["X"], d["r"], d["delta"], d["A"], d["gamma"], stride=stride, pad=pad)
+    Ainv, nvec, B = dk.dkf_coeffs(d["A"], d["gamma"])
+    Wq = dk.dkf_quantize(dev(d["W"]))
+    xbar = dk.dkf_encode(dev(d["X"]), dev(d["r"]), dev(d["A"]), K)
+    assert np.array_equal(host(xbar), o["Xbar"])
+    ybar = dk.dkf_conv_fwd(L, Wq, xbar)
+    assert np.array_equal(host(ybar), o["Ybar"])
+    y, yq, verdict = dk.dkf_decode_verify(ybar, dev(Ainv), dev(nvec), K, want_yq=True)
+    assert np.array_equal(host(yq), o["Yq"]) and np.array_equal(host(y), o["Y"])
+    assert not host(verdict).any()
+    dW, dwq = dk.dkf_wgrad(L, dev(d["delta"]), dev(B), dev(d["gamma"]), xbar, K, want_dwq=True)
+    assert np.array_equal(host(dwq), o["dWq"]) and np.array_equal(host(dW), o["dW"])
+    # a corrupted encoded result is caught, in its group only
+    bad = o["Ybar"].copy()
+    bad.reshape(-1)[bad.size - 1] = (int(bad.reshape(-1)[-1]) + 3) % P
+    _, _, verdict = dk.dkf_decode_verify(dev(bad), dev(Ainv), dev(nvec), K)
+    assert host(verdict).tolist() == [0] * (G - 1) + [1]
+
+
+def test_config2_field_sampled(dk):
+    """Config 2 (conv 3x3 64->64 @32x32, batch 256, K=4) over the field at full
+    size; the oracle evaluates sampled outputs of the two contractions."""
+    rng0 = np.random.default_rng([2, 0, 1])
+    L = dk_inputs.conv(64, 64, 32, 32, 3)
+    d = dk_inputs.field_layer_inputs(rng0, L, K=4, batch=256)
+    K, G = d["K"], d["G"]
+    S = K + 2
+    rng = np.random.default_rng(77)
+    Ainv, nvec, B = dk.dkf_coeffs(d["A"], d["gamma"])
+    Wq_o = F.quantize(d["W"])
+    xbar_o = F.encode(F.quantize(d["X"]), d["r"], d["A"])
+    xbar = dk.dkf_encode(dev(d["X"]), dev(d["r"]), dev(d["A"]), K)
+    assert np.array_equal(host(xbar), xbar_o)
+    ybar = dk.dkf_conv_fwd(L, dk.dkf_quantize(dev(d["W"])), xbar)
+    yb = host(ybar)
+    pts = np.stack([rng.integers(0, G * S, 4000), rng.integers(0, 64, 4000), rng.integers(0, 32, 4000),
+                    rng.integers(0, 32, 4000)], 1)
+    pts[:8, 2:] = [[0, 0], [0, 31], [31, 0], [31, 31], [0, 5], [31, 7], [9, 0], [13, 31]]
+    assert np.array_equal(yb[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]], F.conv_fwd_points(Wq_o, xbar_o, pts, 1, 1))
+    y, yq, verdict = dk.dkf_decode_verify(ybar, dev(Ainv), dev(nvec), K, want_yq=True)
+    assert not host(verdict).any() and not F.verify(yb, nvec).any()
+    assert np.array_equal(host(yq), F.decode(yb, Ainv))
+    dW, dwq = dk.dkf_wgrad(L, dev(d["delta"]), dev(B), dev(d["gamma"]), xbar, K, want_dwq=True)
+    dt_o = F.delta_mix(F.quantize(d["delta"]), B, d["gamma"])
+    wpts = np.stack([rng.integers(0, 64, 300), rng.integers(0, 64, 300), rng.integers(0, 3, 300),
+                     rng.integers(0, 3, 300)], 1)
+    got = host(dwq)
+    assert np.array_equal(got[wpts[:, 0], wpts[:, 1], wpts[:, 2], wpts[:, 3]],
+                          F.conv_wgrad_points(dt_o, xbar_o, 3, 3, wpts, 1, 1))
+    assert np.array_equal(host(dW), F.dequantize(got))
+
+
 def test_field_arguments_refused(dk):
     import torch
     from paper_2207_00083_amd import DkError
@@ -214,4 +273,5 @@ def test_field_arguments_refused(dk):
         dk.dkf_quantize(torch.zeros(4, device="cuda"), l=13)
     assert e.value.status == 2
     conv = dk_inputs.conv(4, 4, 8, 8, 3)
-    assert dk.dkf_wgrad_workspace_bytes(conv, 1, 2) == 0
+    assert dk.dkf_wgrad_workspace_bytes(conv, 1, 2) > 0 and dk.dkf_conv_fwd_workspace_bytes(conv, 4) > 0
+    assert dk.dkf_conv_fwd_workspace_bytes(dk_inputs.linear(4, 4), 4) == 0
