@@ -113,6 +113,15 @@ def field_workload(name):
     import dk_inputs
     if name == "field1":
         return dk_inputs.config1_field(), "config1 over F_p: dense 256->512, K=2, 1 group"
+    if name == "field2":
+        return dk_inputs.config2_field(), "config2 over F_p: conv3x3 s1 p1 64->64 @32x32 NCHW, batch 256, K=4"
+    if name.startswith("field3."):
+        i = int(name.split(".")[1])
+        return dk_inputs.config3_field(index=i), "config3 layer %d over F_p (VGG-16 conv stack @32x32, batch 128, K=4)" % i
+    if name.startswith("field4."):
+        i = int(name.split(".")[1])
+        d, count = dk_inputs.config4_field(index=i)
+        return d, "config4 shape %d x%d over F_p (ResNet-50 convs @224x224 input, batch 64, K=8)" % (i, count)
     if name.startswith("field5."):
         i = int(name.split(".")[1])
         return (dk_inputs.config5_field(index=i)[0],
@@ -121,7 +130,7 @@ def field_workload(name):
 
 
 def field_cpu_baseline(d, budget_s=15.0):
-    """The field oracle's staged dense layer on the first few groups."""
+    """The field oracle's staged layer on the first few groups."""
     from oracle import field as F
     L, K, G = d["layer"], d["K"], d["G"]
     S = K + 2
@@ -130,7 +139,8 @@ def field_cpu_baseline(d, budget_s=15.0):
     def run(ng):
         sl = slice(0, ng * K)
         t0 = time.perf_counter()
-        F.masked_dense_layer(d["W"], d["X"][sl], d["r"][:ng], d["delta"][sl], d["A"][:ng], d["gamma"][:ng])
+        F.masked_layer(d["W"], d["X"][sl], d["r"][:ng], d["delta"][sl], d["A"][:ng], d["gamma"][:ng],
+                       stride=L.stride, pad=L.pad)
         return time.perf_counter() - t0
 
     import oracle
@@ -148,8 +158,8 @@ def field_cpu_baseline(d, budget_s=15.0):
 
 
 def field_main(args):
-    """The finite-field variant of a dense layer:
-    dkf_quantize(W) -> dkf_encode -> dkf_linear_fwd -> dkf_decode_verify -> dkf_wgrad."""
+    """The finite-field variant of a layer:
+    dkf_quantize(W) -> dkf_encode -> dkf_linear_fwd | dkf_conv_fwd -> dkf_decode_verify -> dkf_wgrad."""
     import torch
     import paper_2207_00083_amd as dk
     dk.load()
@@ -171,13 +181,15 @@ def field_main(args):
     A_d, Ainv_d, nvec_d, B_d, gamma_d = dev(d["A"]), dev(Ainv), dev(nvec), dev(B), dev(d["gamma"])
     i32 = dict(dtype=torch.int32, device="cuda")
     f32 = dict(dtype=torch.float32, device="cuda")
-    Wq = torch.empty((L.M, L.N), **i32)
-    xbar = torch.empty((R, L.N), **i32)
-    ybar = torch.empty((R, L.M), **i32)
-    y = torch.empty((G * K, L.M), **f32)
-    dW = torch.empty((L.M, L.N), **f32)
+    conv = L.kind == "conv"
+    Wq = torch.empty(L.w_shape, **i32)
+    xbar = torch.empty((R,) + L.in_shape, **i32)
+    ybar = torch.empty((R,) + L.out_shape, **i32)
+    y = torch.empty((G * K,) + L.out_shape, **f32)
+    dW = torch.empty(L.w_shape, **f32)
     verdict = torch.empty(G, **i32)
-    ws_f = torch.empty(dk.dkf_fwd_workspace_bytes(L.M, L.N, R), dtype=torch.uint8, device="cuda")
+    ws_f = torch.empty(dk.dkf_conv_fwd_workspace_bytes(L, R) if conv else dk.dkf_fwd_workspace_bytes(L.M, L.N, R),
+                       dtype=torch.uint8, device="cuda")
     ws_w = torch.empty(dk.dkf_wgrad_workspace_bytes(L, G, K), dtype=torch.uint8, device="cuda")
     stages = ["quantize_w", "encode", "fwd", "decode_verify", "wgrad"]
 
@@ -187,7 +199,10 @@ def field_main(args):
         if ev: ev[1].record()
         dk.dkf_encode(X, r, A_d, K, xbar=xbar)
         if ev: ev[2].record()
-        dk.dkf_linear_fwd(Wq, xbar, ybar=ybar, ws=ws_f)
+        if conv:
+            dk.dkf_conv_fwd(L, Wq, xbar, ybar=ybar, ws=ws_f)
+        else:
+            dk.dkf_linear_fwd(Wq, xbar, ybar=ybar, ws=ws_f)
         if ev: ev[3].record()
         dk.dkf_decode_verify(ybar, Ainv_d, nvec_d, K, y=y, verdict=verdict)
         if ev: ev[4].record()
@@ -243,7 +258,7 @@ def field_main(args):
 
     ms_per_step = wall / args.steps * 1e3
     stage_ms = {s: float(np.mean([e[i].elapsed_time(e[i + 1]) for e in events])) for i, s in enumerate(stages)}
-    mac = float(R) * L.M * L.N                     # field multiply-adds per contraction
+    mac = float(R) * L.macs_per_row                # field multiply-adds per contraction
     op_step = 2.0 * 2.0 * mac                       # forward + weight gradient
     tops = op_step / (ms_per_step * 1e-3) / 1e12
     # The contraction kernel runs twice a step.  The forward multiplies 4 digit
@@ -265,7 +280,7 @@ def field_main(args):
                               for k, c in gemm.items() if k != dom},
         "timed": "HIP events around every launch of this kernel, %d eager steps after the timed region" % args.steps,
     }
-    n, m = L.N, L.M
+    n, m = dk.dk_layer_in_len(L), dk.dk_layer_out_len(L)
     ab = {"f_encode": 4 * G * n * (K + 1 + S), "f_decode_verify": 4 * G * m * (S + K),
           "f_delta_mix": 4 * G * m * (K + S)}
     hbm = {k: {"GBps": b / (kernels[k][0] * 1e-3) / 1e9, "frac": b / (kernels[k][0] * 1e-3) / 1e9 / HBM_PEAK_GBPS,

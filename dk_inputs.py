@@ -174,6 +174,25 @@ def config5_field(seed=5, batch=1024, K=8, index=None):
     return out
 
 
+def config2_field(seed=2, batch=256, hw=32, ch=64):
+    """Conv 3x3 s1 p1, 64 -> 64 channels at 32x32, batch 256, K=4, finite-field variant."""
+    rng = np.random.default_rng([seed, 0, 1])
+    return field_layer_inputs(rng, conv(ch, ch, hw, hw, 3), K=4, batch=batch)
+
+
+def config3_field(seed=3, batch=128, K=4, index=0):
+    """One layer of the VGG-16 conv stack, finite-field variant."""
+    rng = np.random.default_rng([seed, index, 1])
+    return field_layer_inputs(rng, config3_layers()[index], K=K, batch=batch)
+
+
+def config4_field(seed=4, batch=64, K=8, index=0):
+    """One ResNet-50 conv shape, finite-field variant: (inputs, multiplicity)."""
+    lay, count = resnet50_convs()[index]
+    rng = np.random.default_rng([seed, index, 1])
+    return field_layer_inputs(rng, lay, K=K, batch=batch), count
+
+
 def config1_field(seed=0):
     """Dense 256 -> 512, K=2, one group, finite-field variant."""
     rng = np.random.default_rng([seed, 0, 1])

@@ -36,7 +36,7 @@ constexpr int A_PLANE = BI * PITCH, B_PLANE = BJ * PITCH;
 constexpr int BUF_BYTES = 2 * A_PLANE + 2 * B_PLANE;     // 73728
 constexpr int LDS_BYTES = 2 * BUF_BYTES;                  // 147456
 constexpr int MAX_KSPLIT = 1 << 17;    // k values per slice (int32 accumulators)
-constexpr int MAX_SPLITS = 16;         // the fold adds the slices' residues in 32 bits
+constexpr int MAX_SPLITS = 256;        // k slices per output tile (the fold adds their residues in 64 bits)
 
 struct fgemm_params {
     const int8_t *Ap;      // [4][I_pad][Kp]
@@ -119,28 +119,60 @@ __global__ __launch_bounds__(256) void f_digits_kernel(const uint32_t *__restric
     raise_flag(flag, hi != 0);
 }
 
-// Operand stored with the contraction index slow, src[K][cols] ->
-// planes[4][cols_pad][Kp]: a tile of 128 k x 64 columns goes through LDS as
-// packed digits; a thread then writes 16 consecutive k of one column to each
-// plane.
+struct fconv_geom {
+    int Ci, Co, H, W, kh, kw, stride, pad, Ho, Wo, HoWo;
+};
+
+// Operands whose source is contiguous along the *row* index of the planes, not
+// along k: a tile of 128 k x 64 rows goes through LDS as packed digits, read
+// with consecutive lanes on consecutive rows; a thread then writes 16
+// consecutive k of one row to each plane.
+//   IM2COL false: src[K][cols] (operands of the dense weight gradient, whose
+//                 contraction index is the encoded row);
+//   IM2COL true:  row = (image r, oh, ow), k = (ci, a, b), the element is
+//                 xbar[r][ci][oh*stride + a - pad][ow*stride + b - pad] or 0
+//                 outside the image (forward operand of a convolution).
+template <bool IM2COL>
 __global__ __launch_bounds__(256) void f_digits_t_kernel(const uint32_t *__restrict__ src,
-                                                         int8_t *__restrict__ planes, int K, int cols,
-                                                         int cols_pad, int Kp, int *flag)
+                                                         int8_t *__restrict__ planes, fconv_geom g,
+                                                         int K, int cols, int cols_pad, int Kp,
+                                                         int *flag)
 {
     __shared__ uint32_t tile[128][65];
     const int c0 = blockIdx.x * 64, k0 = blockIdx.y * 128;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int c = c0 + tx;
+    long long base = 0;             // IM2COL: offset of (image, channel 0, oh*stride - pad, ow*stride - pad)
+    int ih0 = 0, iw0 = 0;
+    if (IM2COL && c < cols) {
+        const int img = c / g.HoWo, px = c - img * g.HoWo;
+        const int oh = px / g.Wo, ow = px - oh * g.Wo;
+        ih0 = oh * g.stride - g.pad; iw0 = ow * g.stride - g.pad;
+        base = (long long)img * g.Ci * g.H * g.W;
+    }
+    const int khw = g.kh * g.kw;
 #pragma unroll 8
     for (int r = 0; r < 32; ++r) {
-        const int k = k0 + ty + 4 * r, c = c0 + tx;
-        tile[ty + 4 * r][tx] = (k < K && c < cols) ? digits_of(src[(long long)k * cols + c]) : 0u;
+        const int k = k0 + ty + 4 * r;                 // wave-uniform
+        uint32_t v = 0;
+        if (k < K && c < cols) {
+            if (IM2COL) {
+                const int ci = k / khw, ab = k - ci * khw, a = ab / g.kw, b = ab - a * g.kw;
+                const int ih = ih0 + a, iw = iw0 + b;
+                if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)
+                    v = digits_of(src[base + ((long long)ci * g.H + ih) * g.W + iw]);
+            } else {
+                v = digits_of(src[(long long)k * cols + c]);
+            }
+        }
+        tile[ty + 4 * r][tx] = v;
     }
     __syncthreads();
     const long long plane = (long long)cols_pad * Kp;
     uint32_t hi = 0;
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
-        const int item = threadIdx.x + 256 * r;       // (column, 16 k)
+        const int item = threadIdx.x + 256 * r;       // (row, 16 k): eight lanes write 128 contiguous bytes
         const int kq = item & 7, col = item >> 3;
         u32x4 w[4];
 #pragma unroll
@@ -159,18 +191,14 @@ __global__ __launch_bounds__(256) void f_digits_t_kernel(const uint32_t *__restr
     raise_flag(flag, hi != 0);
 }
 
-// Digit planes of the operands of a convolution, gathered from NCHW field
-// tensors.  A workgroup converts 1024 consecutive k of one row, a thread four.
-//   MODE 0 (forward, B): row = (image r, oh, ow), k = (ci, a, b):
-//                        xbar[r][ci][oh*stride + a - pad][ow*stride + b - pad]
-//   MODE 1 (weight gradient, A): row = co, k = (r, pixel): dtilde[r][co][pixel]
-//   MODE 2 (weight gradient, B): row = (ci, a, b), k = (r, oh, ow): the same
-//                        xbar element as in MODE 0
-// Positions outside the image, rows beyond `rows` and k beyond K give zeros.
-struct fconv_geom {
-    int Ci, Co, H, W, kh, kw, stride, pad, Ho, Wo, HoWo;
-};
-
+// Digit planes of the operands of a convolution's weight gradient, gathered
+// from NCHW field tensors; the contraction index is k = (image r, oh, ow), which
+// is contiguous in both sources.  A workgroup converts 1024 consecutive k of
+// one row, a thread four.
+//   MODE 1 (A): row = co, the element is dtilde[r][co][oh][ow];
+//   MODE 2 (B): row = (ci, a, b), the element is
+//               xbar[r][ci][oh*stride + a - pad][ow*stride + b - pad] or 0 outside.
+// Rows beyond `rows` and k beyond K give zeros.
 template <int MODE>
 __global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__restrict__ src,
                                                             int8_t *__restrict__ planes, fconv_geom g,
@@ -180,43 +208,34 @@ __global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__re
     const int row = blockIdx.x / chunks;                       // workgroup-uniform
     const int k0 = ((blockIdx.x - row * chunks) * 256 + threadIdx.x) * 4;
     if (k0 >= Kp) return;
-    const int khw = g.kh * g.kw;
-    // what the row fixes
-    int r_img = 0, r_oh = 0, r_ow = 0, r_ci = 0, r_a = 0, r_b = 0;
-    if (MODE == 0) {
-        r_img = row / g.HoWo;
-        const int px = row - r_img * g.HoWo;
-        r_oh = px / g.Wo; r_ow = px - r_oh * g.Wo;
-    } else if (MODE == 2) {
+    int r_ci = 0, r_a = 0, r_b = 0;                            // what the row fixes
+    if (MODE == 2) {
+        const int khw = g.kh * g.kw;
         r_ci = row / khw;
         const int ab = row - r_ci * khw;
         r_a = ab / g.kw; r_b = ab - r_a * g.kw;
     }
+    // what k0 fixes; the three following k advance it like a mixed-radix counter
+    int k_img = k0 / g.HoWo;
+    int k_px = k0 - k_img * g.HoWo;
+    int k_oh = k_px / g.Wo, k_ow = k_px - k_oh * g.Wo;
     uint32_t d[4] = {0, 0, 0, 0};
     if (row < rows) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const int k = k0 + c;
-            if (k >= K) continue;
-            long long idx = -1;
-            if (MODE == 1) {
-                const int img = k / g.HoWo, px = k - img * g.HoWo;
-                idx = ((long long)img * g.Co + row) * g.HoWo + px;
-            } else {
-                int img, ci, ih, iw;
-                if (MODE == 0) {
-                    ci = k / khw;
-                    const int ab = k - ci * khw, a = ab / g.kw, b = ab - a * g.kw;
-                    img = r_img; ih = r_oh * g.stride + a - g.pad; iw = r_ow * g.stride + b - g.pad;
+            if (k0 + c < K) {
+                long long idx = -1;
+                if (MODE == 1) {
+                    idx = ((long long)k_img * g.Co + row) * g.HoWo + k_px;
                 } else {
-                    img = k / g.HoWo;
-                    const int px = k - img * g.HoWo, oh = px / g.Wo, ow = px - oh * g.Wo;
-                    ci = r_ci; ih = oh * g.stride + r_a - g.pad; iw = ow * g.stride + r_b - g.pad;
+                    const int ih = k_oh * g.stride + r_a - g.pad, iw = k_ow * g.stride + r_b - g.pad;
+                    if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)
+                        idx = (((long long)k_img * g.Ci + r_ci) * g.H + ih) * g.W + iw;
                 }
-                if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)
-                    idx = (((long long)img * g.Ci + ci) * g.H + ih) * g.W + iw;
+                if (idx >= 0) d[c] = digits_of(src[idx]);
             }
-            if (idx >= 0) d[c] = digits_of(src[idx]);
+            ++k_px;
+            if (++k_ow == g.Wo) { k_ow = 0; if (++k_oh == g.Ho) { k_oh = 0; k_px = 0; ++k_img; } }
         }
     }
     const long long plane = (long long)rows_pad * Kp;
@@ -494,8 +513,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         }
 }
 
-// Fold of the k slices: out[e] = sum_k part[k][e] (mod p); at most 16 residues
-// below 2^25 are added in 32 bits.  With dW != NULL the sum is de-quantised
+// Fold of the k slices: out[e] = sum_k part[k][e] (mod p).  With dW != NULL the sum is de-quantised
 // (dW is never remapped: a weight gradient is [I][J] already):
 // dW = (accumulate ? dW : 0) + scale * Round(lift(q) * 2^-l) * 2^-l.
 __global__ __launch_bounds__(256) void f_fold_kernel(const uint32_t *__restrict__ part,
@@ -505,7 +523,7 @@ __global__ __launch_bounds__(256) void f_fold_kernel(const uint32_t *__restrict_
 {
     const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
     if (e >= elems) return;
-    uint32_t s = 0;
+    uint64_t s = 0;
     for (int k = 0; k < splits; ++k) s += part[(long long)k * elems + e];
     const uint32_t q = dkf_reduce(s);
     if (out_q) {
@@ -546,7 +564,7 @@ bool plan_fgemm(long long I, long long J, long long K, fgemm_plan *pl)
     const long long tiles = (long long)pl->tiles_i * pl->tiles_j;
     if (tiles > (1 << 24)) return false;
     // Number of k slices: at least what the int32 accumulators need, at most
-    // what the fold adds in 32 bits, and among those the count that wastes the
+    // MAX_SPLITS, and among those the count that wastes the
     // least of the last round of workgroups on the 256 compute units (one
     // workgroup per unit), with a small charge per extra slice for its fold.
     const long long need = ((long long)pl->Kp + MAX_KSPLIT - 1) / MAX_KSPLIT;
@@ -632,8 +650,8 @@ dk_status run_digits_t(const uint32_t *src, int8_t *planes, int K, int cols, int
 {
     DK_REQUIRE(Kp / 128 <= 65535, DK_ERR_SHAPE);
     dk_prof_scope ps("f_digits_t", st);
-    f_digits_t_kernel<<<dim3(cols_pad / 64, Kp / 128), dim3(256), 0, st>>>(src, planes, K, cols, cols_pad,
-                                                                         Kp, flag);
+    f_digits_t_kernel<false><<<dim3(cols_pad / 64, Kp / 128), dim3(256), 0, st>>>(src, planes, fconv_geom{},
+                                                                                K, cols, cols_pad, Kp, flag);
     return dk_launch_status();
 }
 
@@ -644,7 +662,7 @@ dk_status run_digits_conv(const uint32_t *src, int8_t *planes, const fconv_geom 
     const int chunks = (Kp / 4 + 255) / 256;
     const long long blocks = (long long)rows_pad * chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
-    dk_prof_scope ps(MODE == 0 ? "f_digits_im2col" : (MODE == 1 ? "f_digits_dt" : "f_digits_im2col_t"), st);
+    dk_prof_scope ps(MODE == 1 ? "f_digits_dt" : "f_digits_im2col_t", st);
     f_digits_conv_kernel<MODE><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(src, planes, cg, rows, K,
                                                                              rows_pad, Kp, chunks, flag);
     return dk_launch_status();
@@ -710,8 +728,13 @@ DK_EXPORT dk_status dkf_conv_fwd(const dk_layer *L, const uint32_t *Wq, const ui
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
     dk_status s = run_digits(Wq, Ap, g.Co, (int)g.Kg, pl.I_pad, pl.Kp, flag, st);
     if (s != DK_OK) return s;
-    s = run_digits_conv<0>(xbar, Bp, conv_geom_of(g), pl.J, (int)g.Kg, pl.J_pad, pl.Kp, flag + 1, st);
-    if (s != DK_OK) return s;
+    {
+        DK_REQUIRE(pl.Kp / 128 <= 65535, DK_ERR_SHAPE);
+        dk_prof_scope ps("f_digits_im2col", st);
+        f_digits_t_kernel<true><<<dim3(pl.J_pad / 64, pl.Kp / 128), dim3(256), 0, st>>>(
+            xbar, Bp, conv_geom_of(g), (int)g.Kg, pl.J, pl.J_pad, pl.Kp, flag + 1);
+    }
+    DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
     return run_fgemm(pl, Ap, Bp, part, flag, ybar, nullptr, 0, 1.0f, 0, g.Ho * g.Wo, "f_gemm_fwd", st);
 }
 

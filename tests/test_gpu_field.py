@@ -231,10 +231,8 @@ def test_masked_conv_layer(dk, K, G, Ci, Co, H, W, k, stride, pad):
 def test_config2_field_sampled(dk):
     """Config 2 (conv 3x3 64->64 @32x32, batch 256, K=4) over the field at full
     size; the oracle evaluates sampled outputs of the two contractions."""
-    rng0 = np.random.default_rng([2, 0, 1])
-    L = dk_inputs.conv(64, 64, 32, 32, 3)
-    d = dk_inputs.field_layer_inputs(rng0, L, K=4, batch=256)
-    K, G = d["K"], d["G"]
+    d = dk_inputs.config2_field()
+    L, K, G = d["layer"], d["K"], d["G"]
     S = K + 2
     rng = np.random.default_rng(77)
     Ainv, nvec, B = dk.dkf_coeffs(d["A"], d["gamma"])
