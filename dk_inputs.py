@@ -138,6 +138,30 @@ def masked_layer_inputs(rng, layer: Layer, K: int, batch: int, *, w_std=None,
     return dict(layer=layer, K=K, G=G, W=W, X=X, r=r, delta=delta, A=A, gamma=gamma)
 
 
+def collusion_layer_inputs(rng, layer: Layer, K: int, M: int, batch: int, *, w_std=None,
+                           noise_std=10.0, delta_std=0.1, cond_max=100.0):
+    """Host arrays for a masked layer that tolerates M colluding accelerators:
+    as masked_layer_inputs, but M noise rows per group (r[G*M, ...]) and square
+    matrices of size S = K+M+1 (A[G,S,S], gamma[G,S]); A is resampled until
+    its 2-norm condition number is below cond_max."""
+    if batch % K:
+        raise ValueError("batch must be a multiple of K")
+    G, S = batch // K, K + M + 1
+    if w_std is None:
+        w_std = float(np.sqrt(2.0 / layer.fan_in))
+    W = _normal(rng, layer.w_shape, w_std)
+    X = _normal(rng, (batch,) + layer.in_shape, 1.0)
+    r = _normal(rng, (G * M,) + layer.in_shape, noise_std)
+    delta = _normal(rng, (batch,) + layer.out_shape, delta_std)
+    A = np.empty((G, S, S), dtype=np.float32)
+    gamma = np.empty((G, S), dtype=np.float32)
+    for g in range(G):
+        A[g] = sample_A(rng, S, cond_max)
+        sign = np.where(rng.random(S) < 0.5, -1.0, 1.0)
+        gamma[g] = (sign * rng.uniform(0.5, 1.5, S)).astype(np.float32)
+    return dict(layer=layer, K=K, M=M, G=G, W=W, X=X, r=r, delta=delta, A=A, gamma=gamma)
+
+
 FIELD_P = (1 << 25) - 39     # the prime of the finite-field variant
 
 

@@ -296,3 +296,84 @@ def masked_layer(W, X, r, D, A, gamma, stride=1, pad=0, tol=1e-3, scale=1.0):
     else:
         dW = masked_dense_wgrad(D, B, gamma, Xbar, scale)
     return dict(Xbar=Xbar, Ybar=Ybar, verdict=verdict, rho=rho, Y=Y, dW=dW)
+
+
+# ----------------------------------------------------------------------
+# Colluding accelerators: M noise vectors per group (section "Colluding GPUs")
+# ----------------------------------------------------------------------
+
+def coefficients_m(A, gamma, K):
+    """A[G,S,S], gamma[G,S] with S = K+M+1 -> (Ainv[G,S,S], nvec[G,S], B[G,S,K]).
+
+    Rows 0..K-1 of A are A_1, rows K..K+M-1 are A_2 (section "Colluding
+    GPUs"), the last row is the phantom source of the integrity redundancy.
+    B = Gamma^{-1} Ainv[:, :K] satisfies B^T Gamma A = [I_K | 0] over the K+M
+    real sources (the section's matrix relation)."""
+    A = _d(A)
+    gamma = _d(gamma)
+    S = A.shape[1]
+    Ainv = np.linalg.inv(A)
+    nvec = np.ascontiguousarray(Ainv[:, :, S - 1])
+    B = np.ascontiguousarray(Ainv[:, :, :K] / gamma[:, :, None])
+    return Ainv, nvec, B
+
+
+def encode_m(X, Rn, A, K):
+    """X[G*K, ...], Rn[G*M, ...], A[G,S,S] -> Xbar[G*S, ...]."""
+    X, Rn, A = _d(X), _d(Rn), _d(A)
+    G, S, _ = A.shape
+    M = S - K - 1
+    feat = X.shape[1:]
+    n = int(np.prod(feat))
+    assert M >= 1 and X.shape[0] == G * K and Rn.shape[0] == G * M
+    Xbar = np.empty((G * S,) + feat)
+    _L().ora_encode_m(_p(X), _p(Rn), _p(A), _p(Xbar), _l(G), _l(K), _l(M), _l(n))
+    return Xbar
+
+
+def decode_m(Ybar, Ainv, ncols):
+    Ybar, Ainv = _d(Ybar), _d(Ainv)
+    G, S, _ = Ainv.shape
+    feat = Ybar.shape[1:]
+    Y = np.empty((G * ncols,) + feat)
+    _L().ora_decode_s(_p(Ybar), _p(Ainv), _p(Y), _l(G), _l(S), _l(int(np.prod(feat))), _l(ncols))
+    return Y
+
+
+def verify_m(Ybar, nvec, tol):
+    Ybar, nvec = _d(Ybar), _d(nvec)
+    G, S = nvec.shape
+    verdict = np.zeros(G, dtype=np.int32)
+    rho = np.zeros(G)
+    _L().ora_verify_s(_p(Ybar), _p(nvec), C.c_double(tol), _p(verdict), _p(rho), _l(G), _l(S),
+                      _l(int(np.prod(Ybar.shape[1:]))))
+    return verdict, rho
+
+
+def delta_mix_m(D, B, gamma):
+    D, B, gamma = _d(D), _d(B), _d(gamma)
+    G, S, K = B.shape
+    feat = D.shape[1:]
+    Dt = np.empty((G * S,) + feat)
+    _L().ora_delta_mix_s(_p(D), _p(B), _p(gamma), _p(Dt), _l(G), _l(K), _l(S), _l(int(np.prod(feat))))
+    return Dt
+
+
+def masked_layer_m(W, X, Rn, D, A, gamma, K, stride=1, pad=0, tol=1e-3, scale=1.0):
+    """The staged path with M = S-K-1 noise vectors per group, fp64:
+    encode -> linear op on encodings -> verify -> decode -> mixed gradients ->
+    the plain weight-gradient contraction of the mixed gradients with the
+    encodings (the gamma-weighted sum of the Eq_j).
+    Returns dict(Xbar, Ybar, verdict, rho, Y, Dt, dW)."""
+    Ainv, nvec, B = coefficients_m(A, gamma, K)
+    Xbar = encode_m(X, Rn, A, K)
+    conv = np.ndim(W) == 4
+    Ybar = conv_fwd(W, Xbar, stride, pad) if conv else dense_fwd(W, Xbar)
+    verdict, rho = verify_m(Ybar, nvec, tol)
+    Y = decode_m(Ybar, Ainv, K)
+    Dt = delta_mix_m(D, B, gamma)
+    if conv:
+        dW = conv_wgrad(Dt, Xbar, W.shape[2], W.shape[3], stride, pad, scale)
+    else:
+        dW = dense_wgrad(Dt, Xbar, scale)
+    return dict(Xbar=Xbar, Ybar=Ybar, verdict=verdict, rho=rho, Y=Y, Dt=Dt, dW=dW)

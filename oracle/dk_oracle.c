@@ -451,3 +451,86 @@ void ora_masked_conv_wgrad(const double *D, const double *B,
     for (long q = 0; q < nw; ++q) dW[q] *= scale;
     free(dbar); free(Eq);
 }
+
+/* ---------------------------------------------------------------------- */
+/* Colluding accelerators (section "Colluding GPUs"): M noise vectors.     */
+/* ---------------------------------------------------------------------- */
+
+/* Encoding with M noise vectors, Xbar = X A_1 + R A_2, plus the extra
+ * integrity combination: S = K + M + 1 encodings per group.  A[g] is S x S;
+ * its rows 0..K-1 are A_1, rows K..K+M-1 are A_2, its last row belongs to the
+ * phantom all-zero source.  X[G*K][n], Rn[G*M][n] -> Xbar[G*S][n]. */
+void ora_encode_m(const double *X, const double *Rn, const double *A, double *Xbar,
+                  long G, long K, long M, long n)
+{
+    const long S = K + M + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (long g = 0; g < G; ++g)
+        for (long j = 0; j < S; ++j)
+            for (long e = 0; e < n; ++e) {
+                double acc = 0.0;
+                for (long i = 0; i < K; ++i)
+                    acc += A[(g * S + i) * S + j] * X[(g * K + i) * n + e];
+                for (long q = 0; q < M; ++q)
+                    acc += A[(g * S + K + q) * S + j] * Rn[(g * M + q) * n + e];
+                Xbar[(g * S + j) * n + e] = acc;
+            }
+}
+
+/* Decoding, integrity check and gradient mixing for S encodings per group
+ * (the formulas of ora_decode, ora_verify and ora_delta_mix with S free). */
+void ora_decode_s(const double *Ybar, const double *Ainv, double *Y,
+                  long G, long S, long m, long ncols)
+{
+#pragma omp parallel for collapse(2) schedule(static)
+    for (long g = 0; g < G; ++g)
+        for (long i = 0; i < ncols; ++i)
+            for (long e = 0; e < m; ++e) {
+                double acc = 0.0;
+                for (long j = 0; j < S; ++j)
+                    acc += Ybar[(g * S + j) * m + e] * Ainv[(g * S + j) * S + i];
+                Y[(g * ncols + i) * m + e] = acc;
+            }
+}
+
+void ora_verify_s(const double *Ybar, const double *nvec, double tol,
+                  int *verdict, double *rho, long G, long S, long m)
+{
+#pragma omp parallel for schedule(static)
+    for (long g = 0; g < G; ++g) {
+        double tmax = 0.0, smax = 0.0;
+        int bad = 0;
+        for (long e = 0; e < m; ++e) {
+            double t = 0.0, sc = 0.0;
+            for (long j = 0; j < S; ++j) {
+                const double v = nvec[g * S + j] * Ybar[(g * S + j) * m + e];
+                t += v;
+                sc += fabs(v);
+            }
+            if (!isfinite(t) || !isfinite(sc))
+                bad = 1;
+            if (fabs(t) > tmax) tmax = fabs(t);
+            if (sc > smax) smax = sc;
+        }
+        const double ratio = (smax > 0.0) ? tmax / smax : 0.0;
+        if (rho) rho[g] = bad ? INFINITY : ratio;
+        verdict[g] = (bad || tmax > tol * smax) ? 1 : 0;
+    }
+}
+
+/* Eq. of the weight update with colluding accelerators:
+ * Eq_j = < sum_{i<=K} beta_{j,i} delta^(i), xbar^(j) >, j = 1..S; here the
+ * mixed gradient of encoding j, already times gamma_j. */
+void ora_delta_mix_s(const double *D, const double *B, const double *gamma,
+                     double *Dt, long G, long K, long S, long m)
+{
+#pragma omp parallel for collapse(2) schedule(static)
+    for (long g = 0; g < G; ++g)
+        for (long j = 0; j < S; ++j)
+            for (long e = 0; e < m; ++e) {
+                double acc = 0.0;
+                for (long i = 0; i < K; ++i)
+                    acc += B[(g * S + j) * K + i] * D[(g * K + i) * m + e];
+                Dt[(g * S + j) * m + e] = gamma[g * S + j] * acc;
+            }
+}
