@@ -14,6 +14,7 @@ region) and the fp64 CPU oracle timed on a bounded sample of the same workload.
 from __future__ import annotations
 
 import argparse
+import ctypes as C
 import json
 import os
 import sys
@@ -50,11 +51,11 @@ def workload(name):
     raise SystemExit("unknown workload " + name)
 
 
-def algorithmic_bytes(K, G, n, m):
+def algorithmic_bytes(K, G, n, m, M=1):
     """HBM bytes each bandwidth-bound kernel must move (fp32), per launch."""
-    S = K + 2
+    S = K + M + 1
     return {
-        "encode": 4 * G * n * (K + 1 + S),
+        "encode": 4 * G * n * (K + M + S),
         "decode_verify": 4 * G * m * (S + K),      # one read of ybar serves both
         "delta_mix": 4 * G * m * (K + S),
     }
@@ -75,14 +76,19 @@ def cpu_baseline(d, budget_s=15.0):
     """The fp64 oracle's staged masked layer on the first few groups."""
     import oracle
     L, K, G = d["layer"], d["K"], d["G"]
-    S = K + 2
+    M = d.get("M", 1)
+    S = K + M + 1
     flop_per_group = 2 * 2 * S * L.macs_per_row
 
     def run(ng):
         sl = slice(0, ng * K)
         t0 = time.perf_counter()
-        oracle.masked_layer(d["W"], d["X"][sl], d["r"][:ng], d["delta"][sl], d["A"][:ng],
-                            d["gamma"][:ng], stride=L.stride, pad=L.pad)
+        if M == 1:
+            oracle.masked_layer(d["W"], d["X"][sl], d["r"][:ng], d["delta"][sl], d["A"][:ng],
+                                d["gamma"][:ng], stride=L.stride, pad=L.pad)
+        else:
+            oracle.masked_layer_m(d["W"], d["X"][sl], d["r"][:ng * M], d["delta"][sl], d["A"][:ng],
+                                  d["gamma"][:ng], K, stride=L.stride, pad=L.pad)
         return time.perf_counter() - t0
 
     oracle.build()
@@ -311,6 +317,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="config2")
+    ap.add_argument("--noise-vectors", type=int, default=1, metavar="M",
+                    help="noise vectors per group (M > 1: tolerate M colluding accelerators, K+M+1 encodings "
+                         "per group; same layer shape, batch and K as the named workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly")
     ap.add_argument("--fork", action="store_true",
@@ -341,10 +350,15 @@ def main():
 
     d, wname = workload(args.workload)
     L, K, G = d["layer"], d["K"], d["G"]
-    S = K + 2
+    M = args.noise_vectors
+    if M > 1:
+        import dk_inputs
+        d = dk_inputs.collusion_layer_inputs(np.random.default_rng([7, M]), L, K=K, M=M, batch=G * K)
+        wname += ", %d noise vectors per group" % M
+    S = K + M + 1
     n, m = dk.dk_layer_in_len(L), dk.dk_layer_out_len(L)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
-    Ainv, nvec, B = dk.dk_coeffs(d["A"], d["gamma"])
+    Ainv, nvec, B = dk.dk_coeffs_m(d["A"], d["gamma"], K)
     W = dev(d["W"])
     A_d, Ainv_d, nvec_d, B_d, gamma_d = dev(d["A"]), dev(Ainv), dev(nvec), dev(B), dev(d["gamma"])
     f32 = dict(dtype=torch.float32, device="cuda")
@@ -360,9 +374,10 @@ def main():
             self.dW = torch.empty(L.w_shape, **f32)
             self.verdict = torch.empty(G, dtype=torch.int32, device="cuda")
             self.resid = torch.empty(G, **f32)
-            self.ws_fwd = torch.empty(dk.dk_workspace_bytes(L, dk.DK_OP_FWD, G, K), **u8)
-            self.ws_wg = torch.empty(dk.dk_workspace_bytes(L, dk.DK_OP_WGRAD, G, K), **u8)
-            self.ws_vf = torch.empty(dk.dk_workspace_bytes(None, dk.DK_OP_VERIFY, G, K), **u8)
+            lib = dk.load()
+            self.ws_fwd = torch.empty(lib.dk_fwd_workspace_bytes(C.byref(dk.DkLayer.of(L)), G * S), **u8)
+            self.ws_wg = torch.empty(lib.dk_workspace_bytes_m(C.byref(dk.DkLayer.of(L)), dk.DK_OP_WGRAD, G, K, M), **u8)
+            self.ws_vf = torch.empty(lib.dk_workspace_bytes_m(None, dk.DK_OP_VERIFY, G, K, M), **u8)
 
     b0 = Buffers()
     y, dW, verdict = b0.y, b0.dW, b0.verdict
@@ -378,24 +393,24 @@ def main():
         the two branches of the captured graph may overlap."""
         cur = torch.cuda.current_stream()
         if ev: ev[0].record()
-        dk.dk_encode(b.X, b.r, A_d, K, xbar=b.xbar)
+        dk.dk_encode_m(b.X, b.r, A_d, K, M, xbar=b.xbar)
         if ev: ev[1].record()
         if fork:
             side2.wait_stream(cur)
             with torch.cuda.stream(side2):
-                dk.dk_wgrad(L, b.delta, B_d, gamma_d, b.xbar, K, dW=b.dW, scale=1.0, ws=b.ws_wg)
+                dk.dk_wgrad_m(L, b.delta, B_d, gamma_d, b.xbar, K, M, dW=b.dW, scale=1.0, ws=b.ws_wg)
         if conv:
             dk.dk_conv_fwd(L, W, b.xbar, ybar=b.ybar, ws=b.ws_fwd)
         else:
             dk.dk_linear_fwd(W, b.xbar, ybar=b.ybar, ws=b.ws_fwd)
         if ev: ev[2].record()
-        dk.dk_decode_verify(b.ybar, Ainv_d, nvec_d, K, tol=1e-3, y=b.y, verdict=b.verdict, resid=b.resid,
-                            ws=b.ws_vf)
+        dk.dk_decode_verify_m(b.ybar, Ainv_d, nvec_d, K, M, tol=1e-3, y=b.y, verdict=b.verdict, resid=b.resid,
+                              ws=b.ws_vf)
         if ev: ev[3].record()
         if fork:
             cur.wait_stream(side2)
         else:
-            dk.dk_wgrad(L, b.delta, B_d, gamma_d, b.xbar, K, dW=b.dW, scale=1.0, ws=b.ws_wg)
+            dk.dk_wgrad_m(L, b.delta, B_d, gamma_d, b.xbar, K, M, dW=b.dW, scale=1.0, ws=b.ws_wg)
         if ev: ev[4].record()
 
     for _ in range(args.warmup):
@@ -473,7 +488,7 @@ def main():
     flop_fwd = 2.0 * G * S * L.macs_per_row         # executed: all K+2 encoded rows
     flop_step = 2.0 * flop_fwd                      # forward + weight gradient
     tflops = flop_step / (ms_per_step * 1e-3) / 1e12
-    ab = algorithmic_bytes(K, G, n, m)
+    ab = algorithmic_bytes(K, G, n, m, M)
 
     # Dominant kernel = the contraction kernel with the longest average launch
     # (forward and weight gradient execute the same FLOP count per launch).

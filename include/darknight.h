@@ -170,6 +170,48 @@ dk_status dk_profile_enable(int on);
 int dk_profile_read(int index, char *name, int name_cap, double *avg_ms,
                     int *launches);
 
+/* ------------------------------------------------------------------------
+ * Several colluding accelerators (section "Colluding GPUs").  To keep the
+ * inputs private from any M accelerators that pool what they see, a group is
+ * encoded with M independent noise vectors: Xbar = X A_1 + R A_2 with
+ * S = K + M encodings, plus the one redundant encoding of section
+ * "Computational Integrity", so S = K + M + 1 here.  A[g] is S x S: rows
+ * 0..K-1 are A_1, rows K..K+M-1 are A_2, the last row belongs to the phantom
+ * all-zero source.  Everything else is as in the entry points above, which
+ * are the case M = 1; the forward entry points take R = G*S rows unchanged.
+ * Requires K + M - 1 <= DK_MAX_K.
+ * ------------------------------------------------------------------------ */
+
+/* dk_coeffs for S = K+M+1: Ainv[G][S][S], nvec[G][S] (last column of Ainv),
+ * B[G][S][K] with B[j][i] = Ainv[j][i]/gamma[j], which satisfies the
+ * section's relation B^T Gamma A = [I_K | 0] over the K+M real sources.
+ * Host pointers. */
+dk_status dk_coeffs_m(const float *A, const float *gamma, int G, int K, int M,
+                      float *Ainv, float *nvec, float *B);
+
+/* xbar[gS+j] = sum_{i<K} A[g][i][j] x[gK+i] + sum_{q<M} A[g][K+q][j] r[gM+q].
+ * x[G*K][n], r[G*M][n], A[G][S][S] -> xbar[G*S][n], all device. */
+dk_status dk_encode_m(const float *x, const float *r, const float *A, float *xbar,
+                      int G, int K, int M, long long n, void *stream);
+
+/* dk_decode_verify for S = K+M+1 encodings per group: y[G*K][m] are the first
+ * K columns of ybar A^{-1} (the M columns <W, r_q> are dropped), the verdict
+ * tests the combination nvec as in dk_verify. */
+dk_status dk_decode_verify_m(const float *ybar, const float *Ainv, const float *nvec, float tol,
+                             float *y, int *verdict, float *resid, int G, int K, int M,
+                             long long m, void *ws, size_t ws_bytes, void *stream);
+
+/* dk_wgrad for S = K+M+1: Eq_j = < sum_{i<K} beta_{j,i} delta_i, xbar_j >,
+ * dW = (accumulate ? dW : 0) + scale * sum_g sum_{j<S} gamma_j Eq_j.
+ * delta[G*K][m], B[G][S][K], gamma[G][S], xbar[G*S][n] -> dW, all device.
+ * Workspace: dk_workspace_bytes_m(L, DK_OP_WGRAD, G, K, M). */
+dk_status dk_wgrad_m(const dk_layer *L, const float *delta, const float *B, const float *gamma,
+                     const float *xbar, float *dW, int G, int K, int M, float scale,
+                     int accumulate, void *ws, size_t ws_bytes, void *stream);
+
+/* dk_workspace_bytes for S = K+M+1. */
+size_t dk_workspace_bytes_m(const dk_layer *L, int op, int G, int K, int M);
+
 #ifdef __cplusplus
 }
 #endif

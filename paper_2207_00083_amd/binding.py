@@ -74,6 +74,11 @@ def load():
         "dk_decode": (ip, [vp, vp, vp, ip, ip, ll, vp]),
         "dk_verify": (ip, [vp, vp, fl, vp, vp, ip, ip, ll, vp, sz, vp]),
         "dk_decode_verify": (ip, [vp, vp, vp, fl, vp, vp, vp, ip, ip, ll, vp, sz, vp]),
+        "dk_coeffs_m": (ip, [vp, vp, ip, ip, ip, vp, vp, vp]),
+        "dk_encode_m": (ip, [vp, vp, vp, vp, ip, ip, ip, ll, vp]),
+        "dk_decode_verify_m": (ip, [vp, vp, vp, fl, vp, vp, vp, ip, ip, ip, ll, vp, sz, vp]),
+        "dk_wgrad_m": (ip, [LP, vp, vp, vp, vp, vp, ip, ip, ip, fl, ip, vp, sz, vp]),
+        "dk_workspace_bytes_m": (sz, [LP, ip, ip, ip, ip]),
         "dkf_coeffs": (ip, [vp, vp, ip, ip, vp, vp, vp]),
         "dkf_quantize": (ip, [vp, vp, ll, ip, vp]),
         "dkf_dequantize": (ip, [vp, vp, ll, ip, vp]),
@@ -325,6 +330,97 @@ def dk_decode_verify(ybar, Ainv, nvec, K, tol=1e-3, y=None, verdict=None, resid=
                                    _ptr(resid), G, K, m, _ptr(ws), ws.numel(), _stream(stream)),
            "dk_decode_verify")
     return y, verdict, resid
+
+
+# ---- several colluding accelerators: M noise rows per group, S = K+M+1 ----
+
+def dk_coeffs_m(A, gamma, K):
+    """Host arrays A[G,S,S], gamma[G,S] (fp32), S = K+M+1 -> Ainv[G,S,S], nvec[G,S], B[G,S,K]."""
+    A = np.ascontiguousarray(A, dtype=np.float32)
+    gamma = np.ascontiguousarray(gamma, dtype=np.float32)
+    G, S, _ = A.shape
+    M = S - K - 1
+    Ainv = np.empty((G, S, S), dtype=np.float32)
+    nvec = np.empty((G, S), dtype=np.float32)
+    B = np.empty((G, S, K), dtype=np.float32)
+    _check(load().dk_coeffs_m(A.ctypes.data, gamma.ctypes.data, G, K, M, Ainv.ctypes.data,
+                              nvec.ctypes.data, B.ctypes.data), "dk_coeffs_m")
+    return Ainv, nvec, B
+
+
+def dk_encode_m(x, r, A, K, M, xbar=None, stream=None):
+    """x[G*K, ...], r[G*M, ...], A[G,S,S] (device) -> xbar[G*S, ...] (device)."""
+    torch = _torch()
+    x, r, A = _dev(x, "x"), _dev(r, "r"), _dev(A, "A")
+    G = A.shape[0]
+    S = K + M + 1
+    n = x[0].numel()
+    if x.shape[0] != G * K or r.shape[0] != G * M or A.shape != (G, S, S) or r[0].numel() != n:
+        raise ValueError("dk_encode_m: inconsistent shapes")
+    if xbar is None:
+        xbar = torch.empty((G * S,) + tuple(x.shape[1:]), dtype=torch.float32, device=x.device)
+    _dev(xbar, "xbar")
+    if xbar.numel() != G * S * n:
+        raise ValueError("dk_encode_m: xbar has the wrong size")
+    _check(load().dk_encode_m(_ptr(x), _ptr(r), _ptr(A), _ptr(xbar), G, K, M, n, _stream(stream)),
+           "dk_encode_m")
+    return xbar
+
+
+def dk_decode_verify_m(ybar, Ainv, nvec, K, M, tol=1e-3, y=None, verdict=None, resid=None, ws=None,
+                       stream=None):
+    """Returns (y[G*K, ...], verdict[G], resid[G])."""
+    torch = _torch()
+    ybar, Ainv, nvec = _dev(ybar, "ybar"), _dev(Ainv, "Ainv"), _dev(nvec, "nvec")
+    G = Ainv.shape[0]
+    S = K + M + 1
+    if Ainv.shape != (G, S, S) or nvec.shape != (G, S) or ybar.shape[0] != G * S:
+        raise ValueError("dk_decode_verify_m: inconsistent shapes")
+    m = ybar[0].numel()
+    if y is None:
+        y = torch.empty((G * K,) + tuple(ybar.shape[1:]), dtype=torch.float32, device=ybar.device)
+    _dev(y, "y")
+    if y.numel() != G * K * m:
+        raise ValueError("dk_decode_verify_m: y has the wrong size")
+    if verdict is None:
+        verdict = torch.empty(G, dtype=torch.int32, device=ybar.device)
+    if resid is None:
+        resid = torch.empty(G, dtype=torch.float32, device=ybar.device)
+    if ws is None:
+        ws = _workspace(load().dk_workspace_bytes_m(None, DK_OP_VERIFY, G, K, M), ybar)
+    _check(load().dk_decode_verify_m(_ptr(ybar), _ptr(Ainv), _ptr(nvec), float(tol), _ptr(y), _ptr(verdict),
+                                     _ptr(resid), G, K, M, m, _ptr(ws), ws.numel(), _stream(stream)),
+           "dk_decode_verify_m")
+    return y, verdict, resid
+
+
+def dk_wgrad_m(layer, delta, B, gamma, xbar, K, M, dW=None, scale=1.0, accumulate=False, ws=None,
+               stream=None):
+    """delta[G*K, ...], B[G,S,K], gamma[G,S], xbar[G*S, ...] (device) -> dW (device)."""
+    torch = _torch()
+    lay = DkLayer.of(layer)
+    delta, B, gamma, xbar = _dev(delta, "delta"), _dev(B, "B"), _dev(gamma, "gamma"), _dev(xbar, "xbar")
+    G, S = gamma.shape
+    n, m = dk_layer_in_len(lay), dk_layer_out_len(lay)
+    if n == 0:
+        raise DkError(2, "dk_wgrad_m")
+    if (S != K + M + 1 or B.shape != (G, S, K) or delta.numel() != G * K * m
+            or xbar.numel() != G * S * n):
+        raise ValueError("dk_wgrad_m: inconsistent shapes")
+    wshape = (lay.M, lay.N) if lay.kind == 0 else (lay.Co, lay.Ci, lay.kh, lay.kw)
+    if dW is None:
+        if accumulate:
+            raise ValueError("dk_wgrad_m: accumulate needs an existing dW")
+        dW = torch.empty(wshape, dtype=torch.float32, device=delta.device)
+    _dev(dW, "dW")
+    if dW.numel() != int(np.prod(wshape)):
+        raise ValueError("dk_wgrad_m: dW has the wrong size")
+    if ws is None:
+        ws = _workspace(load().dk_workspace_bytes_m(C.byref(lay), DK_OP_WGRAD, G, K, M), delta)
+    _check(load().dk_wgrad_m(C.byref(lay), _ptr(delta), _ptr(B), _ptr(gamma), _ptr(xbar), _ptr(dW),
+                             G, K, M, float(scale), int(bool(accumulate)), _ptr(ws), ws.numel(),
+                             _stream(stream)), "dk_wgrad_m")
+    return dW
 
 
 def dk_profile_enable(on=True):

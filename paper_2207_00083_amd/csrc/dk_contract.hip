@@ -797,16 +797,17 @@ DK_EXPORT dk_status dk_conv_fwd(const dk_layer *L, const float *W, const float *
               : run_conv_fwd<CfgSq, false>(g, W, xbar, ybar, R, (float *)ws, ws_bytes, st);
 }
 
-DK_EXPORT dk_status dk_wgrad(const dk_layer *L, const float *delta, const float *B, const float *gamma,
-                             const float *xbar, float *dW, int G, int K, float scale, int accumulate,
-                             void *ws, size_t ws_bytes, void *stream)
+// dk_wgrad for K private inputs and M noise rows per group (S = K + M + 1).
+static dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *B, const float *gamma,
+                            const float *xbar, float *dW, int G, int K, int M, float scale,
+                            int accumulate, void *ws, size_t ws_bytes, void *stream)
 {
     DK_REQUIRE(L && delta && B && gamma && xbar && dW, DK_ERR_NULL);
-    DK_REQUIRE(G >= 1 && K >= 1 && K <= DK_MAX_K, DK_ERR_SHAPE);
+    DK_REQUIRE(G >= 1 && K >= 1 && M >= 1 && K + M - 1 <= DK_MAX_K, DK_ERR_SHAPE);
     dk_geom g;
     dk_status s = dk_layer_geom(L, &g);
     if (s != DK_OK) return s;
-    const long long R = (long long)G * (K + 2);
+    const long long R = (long long)G * (K + M + 1);
     DK_REQUIRE(R < (1ll << 31), DK_ERR_SHAPE);
     if (g.conv) DK_REQUIRE(R * g.Ho * g.Wo < (1ll << 31) - 512, DK_ERR_SHAPE);
     DK_REQUIRE(dk_aligned(delta, 4) && dk_aligned(B, 4) && dk_aligned(gamma, 4) &&
@@ -820,7 +821,7 @@ DK_EXPORT dk_status dk_wgrad(const dk_layer *L, const float *delta, const float 
     float *part = (float *)((char *)ws + dt_bytes);
     const size_t part_bytes = ws_bytes - dt_bytes;
 
-    s = dk_delta_mix(delta, B, gamma, dtilde, G, K, g.m, st);
+    s = dk_delta_mix(delta, B, gamma, dtilde, G, K, M, g.m, st);
     if (s != DK_OK) return s;
 
     if (!g.conv) {
@@ -847,4 +848,18 @@ DK_EXPORT dk_status dk_wgrad(const dk_layer *L, const float *delta, const float 
     if (conv_flat(g))
         return run_conv_wgrad<CfgWg64>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
     return run_conv_wgrad<CfgSq>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
+}
+
+DK_EXPORT dk_status dk_wgrad(const dk_layer *L, const float *delta, const float *B, const float *gamma,
+                             const float *xbar, float *dW, int G, int K, float scale, int accumulate,
+                             void *ws, size_t ws_bytes, void *stream)
+{
+    return wgrad_impl(L, delta, B, gamma, xbar, dW, G, K, 1, scale, accumulate, ws, ws_bytes, stream);
+}
+
+DK_EXPORT dk_status dk_wgrad_m(const dk_layer *L, const float *delta, const float *B, const float *gamma,
+                               const float *xbar, float *dW, int G, int K, int M, float scale,
+                               int accumulate, void *ws, size_t ws_bytes, void *stream)
+{
+    return wgrad_impl(L, delta, B, gamma, xbar, dW, G, K, M, scale, accumulate, ws, ws_bytes, stream);
 }

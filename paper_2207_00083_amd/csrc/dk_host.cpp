@@ -78,6 +78,18 @@ DK_EXPORT size_t dk_workspace_bytes(const dk_layer *L, int op, int G, int K)
     return 0;
 }
 
+DK_EXPORT size_t dk_workspace_bytes_m(const dk_layer *L, int op, int G, int K, int M)
+{
+    if (G < 1 || K < 1 || M < 1 || K + M - 1 > DK_MAX_K) return 0;
+    if (op == DK_OP_VERIFY) return dk_ws_verify_bytes(G);
+    dk_geom g;
+    if (dk_layer_geom(L, &g) != DK_OK) return 0;
+    const long long R = (long long)G * (K + M + 1);
+    if (op == DK_OP_FWD) return dk_ws_fwd_bytes(g, R);
+    if (op == DK_OP_WGRAD) return dk_ws_wgrad_bytes(g, R);
+    return 0;
+}
+
 DK_EXPORT size_t dk_fwd_workspace_bytes(const dk_layer *L, long long R)
 {
     dk_geom g;
@@ -135,13 +147,13 @@ static bool invert(std::vector<double> &a, std::vector<double> &inv, int n)
     return true;
 }
 
-DK_EXPORT dk_status dk_coeffs(const float *A, const float *gamma, int G, int K,
-                              float *Ainv, float *nvec, float *B)
+// Coefficients for K private inputs and S encodings per group.
+static dk_status coeffs_impl(const float *A, const float *gamma, int G, int K, int S,
+                             float *Ainv, float *nvec, float *B)
 {
     DK_REQUIRE(A, DK_ERR_NULL);
-    DK_REQUIRE(G >= 1 && K >= 1 && K <= DK_MAX_K, DK_ERR_SHAPE);
+    DK_REQUIRE(G >= 1 && K >= 1 && S >= K + 2 && S <= DK_MAX_K + 2, DK_ERR_SHAPE);
     DK_REQUIRE(!B || gamma, DK_ERR_NULL);
-    const int S = K + 2;
     std::vector<double> a(S * S), inv(S * S);
     // first pass: validate everything so that nothing is written on error
     for (int pass = 0; pass < 2; ++pass)
@@ -165,6 +177,20 @@ DK_EXPORT dk_status dk_coeffs(const float *A, const float *gamma, int G, int K,
                             (float)(inv[j * S + i] / (double)gamma[(size_t)g * S + j]);
         }
     return DK_OK;
+}
+
+DK_EXPORT dk_status dk_coeffs(const float *A, const float *gamma, int G, int K,
+                              float *Ainv, float *nvec, float *B)
+{
+    DK_REQUIRE(K >= 1 && K <= DK_MAX_K, DK_ERR_SHAPE);
+    return coeffs_impl(A, gamma, G, K, K + 2, Ainv, nvec, B);
+}
+
+DK_EXPORT dk_status dk_coeffs_m(const float *A, const float *gamma, int G, int K, int M,
+                                float *Ainv, float *nvec, float *B)
+{
+    DK_REQUIRE(K >= 1 && M >= 1 && K + M - 1 <= DK_MAX_K, DK_ERR_SHAPE);
+    return coeffs_impl(A, gamma, G, K, K + M + 1, Ainv, nvec, B);
 }
 
 // ---------------------------------------------------------------------------

@@ -48,7 +48,7 @@ dk_split_plan dk_plan_split(long long out_tiles, long long ktiles, long long out
 // Gradient mixing kernel launcher (defined with the other bandwidth-bound
 // kernels, used by dk_wgrad).
 dk_status dk_delta_mix(const float *delta, const float *B, const float *gamma, float *dtilde,
-                       int G, int K, long long m, hipStream_t st);
+                       int G, int K, int M, long long m, hipStream_t st);
 
 // Optional per-kernel timing (dk_profile_enable): while enabled, a scope object
 // brackets one kernel launch with two HIP events on the launch stream.

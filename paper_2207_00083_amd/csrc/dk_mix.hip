@@ -41,15 +41,22 @@ __device__ __forceinline__ void vstore(float *p, const float (&src)[VEC])
 //   MIX_ENCODE: in = K inputs + noise row, out = S encodings, coef = A[g][i][o]
 //   MIX_DECODE: in = S results,            out = K outputs,   coef = Ainv[g][i][o]
 //   MIX_DMIX:   in = K gradients,          out = S mixed,     coef = gamma[g][o] * B[g][o][i]
-template <int MODE, int K, int VEC>
+// With FULL = false the group has nk <= K private inputs and K + 1 - nk noise
+// rows (several colluding accelerators): the template's K counts inputs plus all
+// noise rows but one, S = K + 2 stays the number of encodings, the first nk
+// sources come from in0 and the others from in1, and only nk outputs are decoded
+// and nk gradients mixed.  FULL = true is the case nk = K with every test
+// compiled away.
+template <int MODE, int K, int VEC, bool FULL>
 __global__ __launch_bounds__(MIX_THREADS) void mix_kernel(
     const float *__restrict__ in0, const float *__restrict__ in1,
     const float *__restrict__ c0, const float *__restrict__ c1,
-    float *__restrict__ out, long long len, long long nvec, int chunks, long long span)
+    float *__restrict__ out, long long len, long long nvec, int chunks, long long span, int nk_rt)
 {
     constexpr int S = K + 2;
     constexpr int NIN = MODE == MIX_ENCODE ? K + 1 : (MODE == MIX_DECODE ? S : K);
     constexpr int NOUT = MODE == MIX_DECODE ? K : S;
+    const int nk = FULL ? K : nk_rt;            // wave-uniform
 
     const int g = blockIdx.x / chunks;          // wave-uniform
     const int chunk = blockIdx.x - g * chunks;
@@ -64,20 +71,22 @@ __global__ __launch_bounds__(MIX_THREADS) void mix_kernel(
             else if constexpr (MODE == MIX_DECODE)
                 coef[i][o] = c0[((long long)g * S + i) * S + o];
             else
-                coef[i][o] = c1[(long long)g * S + o] * c0[((long long)g * S + o) * K + i];
+                coef[i][o] = (FULL || i < nk)
+                                 ? c1[(long long)g * S + o] * c0[((long long)g * S + o) * nk + i] : 0.0f;
         }
 
     const float *src[NIN];
 #pragma unroll
     for (int i = 0; i < NIN; ++i) {
         if constexpr (MODE == MIX_ENCODE)
-            src[i] = (i < K) ? in0 + ((long long)g * K + i) * len : in1 + (long long)g * len;
+            src[i] = (i < nk) ? in0 + ((long long)g * nk + i) * len
+                              : in1 + ((long long)g * (K + 1 - nk) + (i - nk)) * len;
         else if constexpr (MODE == MIX_DECODE)
             src[i] = in0 + ((long long)g * S + i) * len;
         else
-            src[i] = in0 + ((long long)g * K + i) * len;
+            src[i] = in0 + ((long long)g * nk + ((FULL || i < nk) ? i : 0)) * len;
     }
-    float *dst = out + (long long)g * NOUT * len;
+    float *dst = out + (long long)g * (MODE == MIX_DECODE ? nk : NOUT) * len;
 
     const long long v0 = (long long)chunk * span;
     long long v1 = v0 + span;
@@ -89,6 +98,7 @@ __global__ __launch_bounds__(MIX_THREADS) void mix_kernel(
         for (int i = 0; i < NIN; ++i) vload<VEC>(x[i], src[i] + e);
 #pragma unroll
         for (int o = 0; o < NOUT; ++o) {
+            if (!FULL && MODE == MIX_DECODE && o >= nk) continue;
             float acc[VEC];
 #pragma unroll
             for (int c = 0; c < VEC; ++c) acc[c] = coef[0][o] * x[0][c];
@@ -174,13 +184,16 @@ __global__ __launch_bounds__(MIX_THREADS) void verify_partial_kernel(
 
 // Decode and the first pass of the integrity check in one sweep over ybar:
 // both need every encoded row of the group exactly once.
-template <int K, int VEC>
+// (FULL = false: only the first nk of the template's K columns are outputs,
+// see mix_kernel.)
+template <int K, int VEC, bool FULL>
 __global__ __launch_bounds__(MIX_THREADS) void decode_verify_kernel(
     const float *__restrict__ ybar, const float *__restrict__ Ainv, const float *__restrict__ nvec_,
     float *__restrict__ y, float *__restrict__ part, long long len, long long nvec, int chunks,
-    long long span)
+    long long span, int nk_rt)
 {
     constexpr int S = K + 2;
+    const int nk = FULL ? K : nk_rt;
     const int g = blockIdx.x / chunks;
     const int chunk = blockIdx.x - g * chunks;
 
@@ -192,7 +205,7 @@ __global__ __launch_bounds__(MIX_THREADS) void decode_verify_kernel(
         for (int i = 0; i < K; ++i) coef[j][i] = Ainv[((long long)g * S + j) * S + i];
     }
     const float *src = ybar + (long long)g * S * len;
-    float *dst = y + (long long)g * K * len;
+    float *dst = y + (long long)g * nk * len;
 
     float tmax = 0.0f, smax = 0.0f;
     bool bad = false;
@@ -206,6 +219,7 @@ __global__ __launch_bounds__(MIX_THREADS) void decode_verify_kernel(
         for (int j = 0; j < S; ++j) vload<VEC>(x[j], src + (long long)j * len + e);
 #pragma unroll
         for (int i = 0; i < K; ++i) {
+            if (!FULL && i >= nk) continue;
             float acc[VEC];
 #pragma unroll
             for (int c = 0; c < VEC; ++c) acc[c] = coef[0][i] * x[0][c];
@@ -307,18 +321,21 @@ bool can_vec4(long long len, std::initializer_list<const void *> ptrs)
 
 template <int MODE, int K>
 dk_status launch_mix_k(const float *in0, const float *in1, const float *c0, const float *c1,
-                       float *out, int G, long long len, bool v4, hipStream_t st)
+                       float *out, int G, long long len, bool v4, int nk, hipStream_t st)
 {
     const span_plan p = plan_span(len, v4 ? 4 : 1, G, 0);
     const long long blocks = (long long)G * p.chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     dk_prof_scope ps(MODE == MIX_ENCODE ? "encode" : (MODE == MIX_DECODE ? "decode" : "delta_mix"), st);
-    if (v4)
-        mix_kernel<MODE, K, 4><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
-            in0, in1, c0, c1, out, len, p.nvec, p.chunks, p.span);
-    else
-        mix_kernel<MODE, K, 1><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
-            in0, in1, c0, c1, out, len, p.nvec, p.chunks, p.span);
+#define DK_MIX_LAUNCH(V, F)                                                                     \
+    mix_kernel<MODE, K, V, F><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(                \
+        in0, in1, c0, c1, out, len, p.nvec, p.chunks, p.span, nk)
+    if (nk == K) {
+        if (v4) DK_MIX_LAUNCH(4, true); else DK_MIX_LAUNCH(1, true);
+    } else {
+        if (v4) DK_MIX_LAUNCH(4, false); else DK_MIX_LAUNCH(1, false);
+    }
+#undef DK_MIX_LAUNCH
     return dk_launch_status();
 }
 
@@ -333,12 +350,14 @@ dk_status launch_mix_k(const float *in0, const float *in1, const float *c0, cons
     default: return DK_ERR_SHAPE;                                               \
     }
 
+// K: private inputs per group; M: noise rows per group.  The kernels are
+// instantiated on KT = K + M - 1 (S = KT + 2 encodings).
 template <int MODE>
 dk_status launch_mix(const float *in0, const float *in1, const float *c0, const float *c1,
-                     float *out, int G, int K, long long len, bool v4, hipStream_t st)
+                     float *out, int G, int K, int M, long long len, bool v4, hipStream_t st)
 {
-#define CALL(KK) launch_mix_k<MODE, KK>(in0, in1, c0, c1, out, G, len, v4, st)
-    DK_K_SWITCH(K, CALL)
+#define CALL(KK) launch_mix_k<MODE, KK>(in0, in1, c0, c1, out, G, len, v4, K, st)
+    DK_K_SWITCH(K + M - 1, CALL)
 #undef CALL
 }
 
@@ -368,19 +387,22 @@ dk_status launch_verify_k(const float *ybar, const float *nvec, float tol, int *
 template <int K>
 dk_status launch_decode_verify_k(const float *ybar, const float *Ainv, const float *nvec, float tol,
                                  float *y, int *verdict, float *resid, int G, long long len,
-                                 float *part, bool v4, hipStream_t st)
+                                 float *part, bool v4, int nk, hipStream_t st)
 {
     const span_plan p = plan_span(len, v4 ? 4 : 1, G, DK_VERIFY_MAX_BLOCKS);
     const long long blocks = (long long)G * p.chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     {
     dk_prof_scope ps("decode_verify", st);
-    if (v4)
-        decode_verify_kernel<K, 4><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
-            ybar, Ainv, nvec, y, part, len, p.nvec, p.chunks, p.span);
-    else
-        decode_verify_kernel<K, 1><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
-            ybar, Ainv, nvec, y, part, len, p.nvec, p.chunks, p.span);
+#define DK_DV_LAUNCH(V, F)                                                                       \
+    decode_verify_kernel<K, V, F><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(            \
+        ybar, Ainv, nvec, y, part, len, p.nvec, p.chunks, p.span, nk)
+    if (nk == K) {
+        if (v4) DK_DV_LAUNCH(4, true); else DK_DV_LAUNCH(1, true);
+    } else {
+        if (v4) DK_DV_LAUNCH(4, false); else DK_DV_LAUNCH(1, false);
+    }
+#undef DK_DV_LAUNCH
     }
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
     dk_prof_scope ps("verify_final", st);
@@ -411,7 +433,19 @@ DK_EXPORT dk_status dk_encode(const float *x, const float *r, const float *A, fl
     dk_status s = check_mix_args(G, K, n);
     if (s != DK_OK) return s;
     DK_REQUIRE(dk_aligned(x, 4) && dk_aligned(r, 4) && dk_aligned(A, 4) && dk_aligned(xbar, 4), DK_ERR_ALIGN);
-    return launch_mix<MIX_ENCODE>(x, r, A, nullptr, xbar, G, K, n, can_vec4(n, {x, r, xbar}),
+    return launch_mix<MIX_ENCODE>(x, r, A, nullptr, xbar, G, K, 1, n, can_vec4(n, {x, r, xbar}),
+                                  (hipStream_t)stream);
+}
+
+DK_EXPORT dk_status dk_encode_m(const float *x, const float *r, const float *A, float *xbar,
+                                int G, int K, int M, long long n, void *stream)
+{
+    DK_REQUIRE(x && r && A && xbar, DK_ERR_NULL);
+    DK_REQUIRE(M >= 1 && K >= 1 && K + M - 1 <= DK_MAX_K, DK_ERR_SHAPE);
+    dk_status s = check_mix_args(G, K + M - 1, n);
+    if (s != DK_OK) return s;
+    DK_REQUIRE(dk_aligned(x, 4) && dk_aligned(r, 4) && dk_aligned(A, 4) && dk_aligned(xbar, 4), DK_ERR_ALIGN);
+    return launch_mix<MIX_ENCODE>(x, r, A, nullptr, xbar, G, K, M, n, can_vec4(n, {x, r, xbar}),
                                   (hipStream_t)stream);
 }
 
@@ -422,15 +456,16 @@ DK_EXPORT dk_status dk_decode(const float *ybar, const float *Ainv, float *y, in
     dk_status s = check_mix_args(G, K, m);
     if (s != DK_OK) return s;
     DK_REQUIRE(dk_aligned(ybar, 4) && dk_aligned(Ainv, 4) && dk_aligned(y, 4), DK_ERR_ALIGN);
-    return launch_mix<MIX_DECODE>(ybar, nullptr, Ainv, nullptr, y, G, K, m, can_vec4(m, {ybar, y}),
+    return launch_mix<MIX_DECODE>(ybar, nullptr, Ainv, nullptr, y, G, K, 1, m, can_vec4(m, {ybar, y}),
                                   (hipStream_t)stream);
 }
 
-// Gradient mixing used by dk_wgrad: dtilde[gS+j] = gamma[g][j] sum_i B[g][j][i] delta[gK+i].
+// Gradient mixing used by dk_wgrad: dtilde[gS+j] = gamma[g][j] sum_i B[g][j][i] delta[gK+i],
+// S = K + M + 1.
 dk_status dk_delta_mix(const float *delta, const float *B, const float *gamma, float *dtilde,
-                       int G, int K, long long m, hipStream_t st)
+                       int G, int K, int M, long long m, hipStream_t st)
 {
-    return launch_mix<MIX_DMIX>(delta, nullptr, B, gamma, dtilde, G, K, m,
+    return launch_mix<MIX_DMIX>(delta, nullptr, B, gamma, dtilde, G, K, M, m,
                                 can_vec4(m, {delta, dtilde}), st);
 }
 
@@ -465,7 +500,26 @@ DK_EXPORT dk_status dk_decode_verify(const float *ybar, const float *Ainv, const
     DK_REQUIRE(ws && ws_bytes >= dk_ws_verify_bytes(G), DK_ERR_WORKSPACE);
     DK_REQUIRE(dk_aligned(ws, 4), DK_ERR_ALIGN);
     const bool v4 = can_vec4(m, {ybar, y});
-#define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, (float *)ws, v4, (hipStream_t)stream)
+#define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, (float *)ws, v4, K, (hipStream_t)stream)
     DK_K_SWITCH(K, CALL)
+#undef CALL
+}
+
+DK_EXPORT dk_status dk_decode_verify_m(const float *ybar, const float *Ainv, const float *nvec, float tol,
+                                       float *y, int *verdict, float *resid, int G, int K, int M,
+                                       long long m, void *ws, size_t ws_bytes, void *stream)
+{
+    DK_REQUIRE(ybar && Ainv && nvec && y && verdict, DK_ERR_NULL);
+    DK_REQUIRE(M >= 1 && K >= 1 && K + M - 1 <= DK_MAX_K, DK_ERR_SHAPE);
+    dk_status s = check_mix_args(G, K + M - 1, m);
+    if (s != DK_OK) return s;
+    DK_REQUIRE(tol >= 0.0f, DK_ERR_SHAPE);
+    DK_REQUIRE(dk_aligned(ybar, 4) && dk_aligned(Ainv, 4) && dk_aligned(nvec, 4) && dk_aligned(y, 4) &&
+                   dk_aligned(verdict, 4) && (!resid || dk_aligned(resid, 4)), DK_ERR_ALIGN);
+    DK_REQUIRE(ws && ws_bytes >= dk_ws_verify_bytes(G), DK_ERR_WORKSPACE);
+    DK_REQUIRE(dk_aligned(ws, 4), DK_ERR_ALIGN);
+    const bool v4 = can_vec4(m, {ybar, y});
+#define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, (float *)ws, v4, K, (hipStream_t)stream)
+    DK_K_SWITCH(K + M - 1, CALL)
 #undef CALL
 }
