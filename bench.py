@@ -6,6 +6,10 @@ is already resident in HBM:
     dk_encode -> dk_conv_fwd | dk_linear_fwd -> dk_decode_verify -> dk_wgrad
 (dk_decode_verify = dk_verify + dk_decode in one sweep over the encoded results).
 The step is captured once into a HIP graph and replayed (--no-graph: eager).
+--noise-vectors M uses the *_m entry points (M noise vectors per group);
+--workload field1 | field2 | field3.i | field4.i | field5.i runs the finite-field
+variant instead (dkf_quantize -> dkf_encode -> dkf_linear_fwd | dkf_conv_fwd ->
+dkf_decode_verify -> dkf_wgrad).
 Prints ONE JSON line: whole-path executed TFLOP/s (forward + weight gradient
 on all K+2 encoded rows per group), decoded samples/s, the roofline record of
 the dominant kernel (timed with events on the launch stream inside the timed

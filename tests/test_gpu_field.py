@@ -70,6 +70,22 @@ def test_linear_fwd_full(dk, R, M, N, small):
     assert np.array_equal(got, F.dense_fwd(W, X))
 
 
+@pytest.mark.parametrize("x_small,w_small", [(True, True), (True, False), (False, True)])
+def test_linear_fwd_digit_halves_skipped(dk, x_small, w_small):
+    """Operands whose high digit halves are all zero take the short path (the
+    device flags switch parts off); every combination must stay exact."""
+    rng = np.random.default_rng([int(x_small), int(w_small), 3])
+    R, M, N = 150, 140, 260
+    small = lambda shape: (rng.integers(-8000, 8000, size=shape) % P).astype(np.uint32)
+    big = lambda shape: rng.integers(0, P, size=shape, dtype=np.uint32)
+    X = small((R, N)) if x_small else big((R, N))
+    W = small((M, N)) if w_small else big((M, N))
+    assert np.array_equal(host(dk.dkf_linear_fwd(dev(W), dev(X))), F.dense_fwd(W, X))
+    # all-zero operands
+    Z = np.zeros((R, N), dtype=np.uint32)
+    assert not host(dk.dkf_linear_fwd(dev(W), dev(Z))).any()
+
+
 def test_linear_fwd_extreme_digits(dk):
     """Operands at the ends of the centred range and at digit boundaries."""
     vals = np.array([0, 1, P - 1, P // 2, P // 2 + 1, 63, 64, 65, P - 64, P - 65, 8191, 8192, 8256, 8257,
