@@ -377,3 +377,24 @@ def masked_layer_m(W, X, Rn, D, A, gamma, K, stride=1, pad=0, tol=1e-3, scale=1.
     else:
         dW = dense_wgrad(Dt, Xbar, scale)
     return dict(Xbar=Xbar, Ybar=Ybar, verdict=verdict, rho=rho, Y=Y, Dt=Dt, dW=dW)
+
+
+# ----------------------------------------------------------------------
+# Noise from a counter-based generator
+# ----------------------------------------------------------------------
+
+def philox4x32_10(ctr, key):
+    c = (C.c_uint32 * 4)(*[int(v) for v in ctr])
+    k = (C.c_uint32 * 2)(*[int(v) for v in key])
+    out = (C.c_uint32 * 4)()
+    _L().ora_philox4x32_10(c, k, out)
+    return [int(v) for v in out]
+
+
+def noise_philox(G, M, feat, seed, sigma):
+    """r[G*M, *feat] (fp64): the noise rows a seed stands for."""
+    feat = tuple(int(v) for v in np.atleast_1d(feat))
+    n = int(np.prod(feat))
+    r = np.empty((G * M,) + feat)
+    _L().ora_noise_philox(_p(r), _l(G), _l(M), _l(n), C.c_uint64(int(seed)), C.c_double(sigma))
+    return r

@@ -286,3 +286,37 @@ void orf_conv_wgrad_points(const fe *D, const fe *X, long R, long Ci, long H, lo
         out[q] = acc;
     }
 }
+
+/* Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11), as in the
+ * real-valued oracle. */
+static void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; ++r) {
+        const u64 p0 = (u64)0xD2511F53u * c0, p1 = (u64)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1, n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Uniform field noise drawn on the fly ("Random Numbers": the noise is uniform
+ * over F_p): elements 2t, 2t+1 of the noise row of group g come from one
+ * generator call with counter (t mod 2^32, t div 2^32, g, 0) and key
+ * (seed mod 2^32, seed div 2^32); each element is a 64-bit word
+ * (first word high) reduced mod p, which is uniform up to 2^-39.  r[G][n]. */
+void orf_noise_philox(fe *r, long G, long n, uint64_t seed, fe p)
+{
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+#pragma omp parallel for schedule(static)
+    for (long g = 0; g < G; ++g)
+        for (long t = 0; 2 * t < n; ++t) {
+            const uint32_t ctr[4] = {(uint32_t)t, (uint32_t)((u64)t >> 32), (uint32_t)g, 0u};
+            uint32_t w[4];
+            philox4x32_10(ctr, key, w);
+            r[g * n + 2 * t] = (fe)((((u64)w[0] << 32) | w[1]) % p);
+            if (2 * t + 1 < n) r[g * n + 2 * t + 1] = (fe)((((u64)w[2] << 32) | w[3]) % p);
+        }
+}

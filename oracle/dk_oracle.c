@@ -19,6 +19,7 @@
  *   vector, then an all-zero phantom source) in encoding j.
  */
 #include <math.h>
+#include <stdint.h>
 #include <stddef.h>
 #include <stdlib.h>
 #include <string.h>
@@ -532,5 +533,55 @@ void ora_delta_mix_s(const double *D, const double *B, const double *gamma,
                 for (long i = 0; i < K; ++i)
                     acc += B[(g * S + j) * K + i] * D[(g * K + i) * m + e];
                 Dt[(g * S + j) * m + e] = gamma[g * S + j] * acc;
+            }
+}
+
+/* ---------------------------------------------------------------------- */
+/* Noise drawn by a counter-based generator instead of being passed in.    */
+/* ---------------------------------------------------------------------- */
+
+/* Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random
+ * numbers: as easy as 1, 2, 3", SC'11): a keyed bijection of a 128-bit
+ * counter.  Each round multiplies two counter words by fixed odd constants
+ * and mixes the high halves with the other words and the key; the key words
+ * advance by Weyl constants. */
+void ora_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1, n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The noise rows of the encoding (each virtual batch gets fresh noise;
+ * Forward Pass, "Key Insight") drawn on the fly: elements 4b..4b+3 of noise
+ * row q of group g come from one generator call with counter
+ * (b mod 2^32, b div 2^32, g, q) and key (seed mod 2^32, seed div 2^32); the
+ * four words become uniforms u = ((word >> 8) + 1/2) 2^-24 in (0,1) and two
+ * Box-Muller pairs  sqrt(-2 ln u0) (cos, sin)(2 pi u1),  same with (u2, u3);
+ * the values are sigma times these.  r[G*M][n]. */
+void ora_noise_philox(double *r, long G, long M, long n, uint64_t seed, double sigma)
+{
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    const double two_pi = 6.283185307179586476925286766559;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (long g = 0; g < G; ++g)
+        for (long q = 0; q < M; ++q)
+            for (long b = 0; 4 * b < n; ++b) {
+                const uint32_t ctr[4] = {(uint32_t)b, (uint32_t)((uint64_t)b >> 32), (uint32_t)g, (uint32_t)q};
+                uint32_t w[4];
+                ora_philox4x32_10(ctr, key, w);
+                double u[4], z[4];
+                for (int k = 0; k < 4; ++k) u[k] = ((double)(w[k] >> 8) + 0.5) * (1.0 / 16777216.0);
+                const double m0 = sqrt(-2.0 * log(u[0])), m1 = sqrt(-2.0 * log(u[2]));
+                z[0] = m0 * cos(two_pi * u[1]); z[1] = m0 * sin(two_pi * u[1]);
+                z[2] = m1 * cos(two_pi * u[3]); z[3] = m1 * sin(two_pi * u[3]);
+                for (int k = 0; k < 4 && 4 * b + k < n; ++k)
+                    r[(g * M + q) * n + 4 * b + k] = sigma * z[k];
             }
 }

@@ -209,6 +209,14 @@ def dense_wgrad_points(D, X, pts, p=P):
     return out
 
 
+def noise_philox(G, feat, seed, p=P):
+    """r[G, *feat] (uint32): the uniform field noise a seed stands for."""
+    feat = tuple(int(v) for v in np.atleast_1d(feat))
+    r = np.empty((G,) + feat, dtype=np.uint32)
+    _L().orf_noise_philox(_p(r), _l(G), _l(int(np.prod(feat))), C.c_uint64(int(seed)), _fe(p))
+    return r
+
+
 def conv_out_hw(H, W, kh, kw, stride, pad):
     return (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
 
