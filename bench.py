@@ -207,7 +207,10 @@ def field_main(args):
         if ev: ev[0].record()
         dk.dkf_quantize(W, xq=Wq)
         if ev: ev[1].record()
-        dk.dkf_encode(X, r, A_d, K, xbar=xbar)
+        if args.rng_noise:
+            dk.dkf_encode_rng(X, A_d, K, 20220701, xbar=xbar)
+        else:
+            dk.dkf_encode(X, r, A_d, K, xbar=xbar)
         if ev: ev[2].record()
         if conv:
             dk.dkf_conv_fwd(L, Wq, xbar, ybar=ybar, ws=ws_f)
@@ -324,6 +327,9 @@ def main():
     ap.add_argument("--noise-vectors", type=int, default=1, metavar="M",
                     help="noise vectors per group (M > 1: tolerate M colluding accelerators, K+M+1 encodings "
                          "per group; same layer shape, batch and K as the named workload)")
+    ap.add_argument("--rng-noise", action="store_true",
+                    help="draw the noise inside the encoding kernel (dk_encode_rng / dkf_encode_rng, one seed "
+                         "per step) instead of reading noise rows from HBM")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly")
     ap.add_argument("--fork", action="store_true",
@@ -397,7 +403,10 @@ def main():
         the two branches of the captured graph may overlap."""
         cur = torch.cuda.current_stream()
         if ev: ev[0].record()
-        dk.dk_encode_m(b.X, b.r, A_d, K, M, xbar=b.xbar)
+        if args.rng_noise:
+            dk.dk_encode_rng(b.X, A_d, K, M, 20220701, 10.0, xbar=b.xbar)
+        else:
+            dk.dk_encode_m(b.X, b.r, A_d, K, M, xbar=b.xbar)
         if ev: ev[1].record()
         if fork:
             side2.wait_stream(cur)
@@ -509,7 +518,10 @@ def main():
         "timed": "HIP events around every launch of this kernel, %d eager launches after the timed region, "
                  "cycling through %d buffer sets of %.0f MB" % (args.steps, len(sets), set_bytes / 1e6),
     }
-    kname = {"encode": "encode", "decode_verify": "decode_verify", "delta_mix": "delta_mix"}
+    kname = {"encode": "encode_rng" if args.rng_noise else "encode", "decode_verify": "decode_verify",
+             "delta_mix": "delta_mix"}
+    if args.rng_noise:
+        ab["encode"] -= 4 * G * M * n          # the noise rows are not read
     hbm = {}
     for k, label in kname.items():
         if label in kernels:
@@ -522,7 +534,8 @@ def main():
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": wname, "K": K, "G": G, "layer": L.asdict(),
+        "config": {"workload": wname + (", noise drawn in the encoding kernel" if args.rng_noise else ""),
+                   "K": K, "G": G, "layer": L.asdict(),
                    "launch": ("HIP graph replay of one captured step"
                               + (", weight gradient on a second branch" if args.fork else "")) if graph else "eager"},
         "pct_mfma_peak": 100.0 * tflops / MFMA_F32_PEAK_TFLOPS,

@@ -212,6 +212,31 @@ dk_status dk_wgrad_m(const dk_layer *L, const float *delta, const float *B, cons
 /* dk_workspace_bytes for S = K+M+1. */
 size_t dk_workspace_bytes_m(const dk_layer *L, int op, int G, int K, int M);
 
+/* ------------------------------------------------------------------------
+ * Noise drawn inside the encoding kernel.  The noise vector of a virtual batch
+ * is random and only ever used for that batch's encodings (Forward Pass, text
+ * after the encoding equation: scalars and noise are generated at random, anew
+ * for each virtual batch; it cancels in decoding and is never needed again), so
+ * it does not have to exist in memory: a 64-bit seed stands for it.
+ * Generator: Philox4x32, 10 rounds.  Elements 4b..4b+3 of noise row q of group
+ * g come from one call with counter (b mod 2^32, b div 2^32, g, q) and key
+ * (seed mod 2^32, seed div 2^32): the four words w give uniforms
+ * u = ((w >> 8) + 1/2) 2^-24 and the two Box-Muller pairs
+ * sqrt(-2 ln u0) (cos, sin)(2 pi u1), sqrt(-2 ln u2) (cos, sin)(2 pi u3),
+ * times noise_std.  Use a fresh seed for every layer and step.
+ * ------------------------------------------------------------------------ */
+
+/* The noise rows a seed stands for, written out: r[G*M][n] (device).  For
+ * tests and for callers that want the rows; dk_encode_rng does not need it. */
+dk_status dk_noise_rng(float *r, int G, int M, long long n, unsigned long long seed,
+                       float noise_std, void *stream);
+
+/* dk_encode_m (M = 1: dk_encode) with r = dk_noise_rng(seed, noise_std)
+ * generated on the fly; the result equals dk_encode_m on those rows bit for
+ * bit.  x[G*K][n], A[G][S][S] -> xbar[G*S][n], S = K+M+1, all device. */
+dk_status dk_encode_rng(const float *x, const float *A, float *xbar, int G, int K, int M,
+                        long long n, unsigned long long seed, float noise_std, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

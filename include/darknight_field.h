@@ -68,6 +68,18 @@ dk_status dkf_dequantize(const uint32_t *yq, float *y, long long count, int l, v
 dk_status dkf_encode(const float *x, const uint32_t *r, const uint32_t *A, uint32_t *xbar,
                      int G, int K, long long n, int l, void *stream);
 
+/* Uniform field noise from a counter-based generator ("Random Numbers": the
+ * noise is uniform over F_p; it is fresh for every virtual batch and cancels
+ * in decoding, so a 64-bit seed can stand for it).  Philox4x32, 10 rounds:
+ * elements 2t, 2t+1 of the noise row of group g come from one call with
+ * counter (t mod 2^32, t div 2^32, g, 0) and key (seed mod 2^32, seed div
+ * 2^32); an element is the 64-bit word (first word high) mod p, uniform up to
+ * 2^-39.  dkf_noise_rng writes the rows r[G][n] (device); dkf_encode_rng is
+ * dkf_encode with r generated on the fly (same result, r never in memory). */
+dk_status dkf_noise_rng(uint32_t *r, int G, long long n, unsigned long long seed, void *stream);
+dk_status dkf_encode_rng(const float *x, const uint32_t *A, uint32_t *xbar, int G, int K,
+                         long long n, int l, unsigned long long seed, void *stream);
+
 /* The accelerator's linear operation on encoded rows, over the field
  * (quantisation algorithm, the step in which the accelerators apply W_q to
  * the encodings):

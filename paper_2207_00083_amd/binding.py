@@ -79,6 +79,10 @@ def load():
         "dk_decode_verify_m": (ip, [vp, vp, vp, fl, vp, vp, vp, ip, ip, ip, ll, vp, sz, vp]),
         "dk_wgrad_m": (ip, [LP, vp, vp, vp, vp, vp, ip, ip, ip, fl, ip, vp, sz, vp]),
         "dk_workspace_bytes_m": (sz, [LP, ip, ip, ip, ip]),
+        "dk_noise_rng": (ip, [vp, ip, ip, ll, C.c_ulonglong, fl, vp]),
+        "dk_encode_rng": (ip, [vp, vp, vp, ip, ip, ip, ll, C.c_ulonglong, fl, vp]),
+        "dkf_noise_rng": (ip, [vp, ip, ll, C.c_ulonglong, vp]),
+        "dkf_encode_rng": (ip, [vp, vp, vp, ip, ip, ll, ip, C.c_ulonglong, vp]),
         "dkf_coeffs": (ip, [vp, vp, ip, ip, vp, vp, vp]),
         "dkf_quantize": (ip, [vp, vp, ll, ip, vp]),
         "dkf_dequantize": (ip, [vp, vp, ll, ip, vp]),
@@ -421,6 +425,37 @@ def dk_wgrad_m(layer, delta, B, gamma, xbar, K, M, dW=None, scale=1.0, accumulat
                              G, K, M, float(scale), int(bool(accumulate)), _ptr(ws), ws.numel(),
                              _stream(stream)), "dk_wgrad_m")
     return dW
+
+
+# ---- noise drawn by the library's counter-based generator ----
+
+def dk_noise_rng(G, M, feat, seed, noise_std, device="cuda", stream=None):
+    """r[G*M, *feat] (device): the noise rows the seed stands for."""
+    torch = _torch()
+    feat = tuple(int(v) for v in np.atleast_1d(feat))
+    r = torch.empty((G * M,) + feat, dtype=torch.float32, device=device)
+    _check(load().dk_noise_rng(_ptr(r), G, M, int(np.prod(feat)), int(seed), float(noise_std),
+                               _stream(stream)), "dk_noise_rng")
+    return r
+
+
+def dk_encode_rng(x, A, K, M, seed, noise_std, xbar=None, stream=None):
+    """x[G*K, ...], A[G,S,S] (device), S = K+M+1 -> xbar[G*S, ...]; noise from the seed."""
+    torch = _torch()
+    x, A = _dev(x, "x"), _dev(A, "A")
+    G = A.shape[0]
+    S = K + M + 1
+    n = x[0].numel()
+    if x.shape[0] != G * K or A.shape != (G, S, S):
+        raise ValueError("dk_encode_rng: inconsistent shapes")
+    if xbar is None:
+        xbar = torch.empty((G * S,) + tuple(x.shape[1:]), dtype=torch.float32, device=x.device)
+    _dev(xbar, "xbar")
+    if xbar.numel() != G * S * n:
+        raise ValueError("dk_encode_rng: xbar has the wrong size")
+    _check(load().dk_encode_rng(_ptr(x), _ptr(A), _ptr(xbar), G, K, M, n, int(seed), float(noise_std),
+                                _stream(stream)), "dk_encode_rng")
+    return xbar
 
 
 def dk_profile_enable(on=True):

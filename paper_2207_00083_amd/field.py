@@ -86,6 +86,32 @@ def dkf_encode(x, r, A, K, l=DKF_L, xbar=None, stream=None):
     return xbar
 
 
+def dkf_noise_rng(G, feat, seed, device="cuda", stream=None):
+    """r[G, *feat] (device, field elements): the uniform noise the seed stands for."""
+    torch = _torch()
+    feat = tuple(int(v) for v in np.atleast_1d(feat))
+    r = torch.empty((G,) + feat, dtype=torch.int32, device=device)
+    _check(load().dkf_noise_rng(_ptr(r), G, int(np.prod(feat)), int(seed), _stream(stream)), "dkf_noise_rng")
+    return r
+
+
+def dkf_encode_rng(x, A, K, seed, l=DKF_L, xbar=None, stream=None):
+    """x[G*K, ...] float, A[G,S,S] field elements (device) -> xbar[G*S, ...]; noise from the seed."""
+    x, A = _dev(x, "x"), _fe(A, "A")
+    G, S = A.shape[0], K + 2
+    n = x[0].numel()
+    if x.shape[0] != G * K or tuple(A.shape) != (G, S, S):
+        raise ValueError("dkf_encode_rng: inconsistent shapes")
+    if xbar is None:
+        xbar = _new_fe((G * S,) + tuple(x.shape[1:]), x)
+    _fe(xbar, "xbar")
+    if xbar.numel() != G * S * n:
+        raise ValueError("dkf_encode_rng: xbar has the wrong size")
+    _check(load().dkf_encode_rng(_ptr(x), _ptr(A), _ptr(xbar), G, K, n, int(l), int(seed), _stream(stream)),
+           "dkf_encode_rng")
+    return xbar
+
+
 def dkf_fwd_workspace_bytes(M, N, R) -> int:
     return int(load().dkf_fwd_workspace_bytes(int(M), int(N), int(R)))
 
