@@ -398,3 +398,67 @@ def noise_philox(G, M, feat, seed, sigma):
     r = np.empty((G * M,) + feat)
     _L().ora_noise_philox(_p(r), _l(G), _l(M), _l(n), C.c_uint64(int(seed)), C.c_double(sigma))
     return r
+
+
+# ----------------------------------------------------------------------
+# Depthwise convolution and data gradients
+# ----------------------------------------------------------------------
+
+def dwconv_fwd(W, X, stride=1, pad=0):
+    """W[C,kh,kw], X[R,C,H,W] -> Y[R,C,Ho,Wo] (one filter per channel)."""
+    W, X = _d(W), _d(X)
+    Cc, kh, kw = W.shape
+    R, _, H, Wd = X.shape
+    Ho, Wo = conv_out_hw(H, Wd, kh, kw, stride, pad)
+    Y = np.empty((R, Cc, Ho, Wo))
+    _L().ora_dwconv_fwd(_p(W), _p(X), _p(Y), _l(R), _l(Cc), _l(H), _l(Wd), _l(kh), _l(kw), _l(stride), _l(pad))
+    return Y
+
+
+def dwconv_wgrad(D, X, kh, kw, stride=1, pad=0, scale=1.0):
+    D, X = _d(D), _d(X)
+    R, Cc, H, Wd = X.shape
+    dW = np.empty((Cc, kh, kw))
+    _L().ora_dwconv_wgrad(_p(D), _p(X), _p(dW), _l(R), _l(Cc), _l(H), _l(Wd), _l(kh), _l(kw), _l(stride),
+                          _l(pad), C.c_double(scale))
+    return dW
+
+
+def dense_dgrad(D, W):
+    D, W = _d(D), _d(W)
+    M, N = W.shape
+    dX = np.empty((D.shape[0], N))
+    _L().ora_dense_dgrad(_p(D), _p(W), _p(dX), _l(D.shape[0]), _l(M), _l(N))
+    return dX
+
+
+def conv_dgrad(D, W, H, Wd, stride=1, pad=0):
+    D, W = _d(D), _d(W)
+    Co, Ci, kh, kw = W.shape
+    R = D.shape[0]
+    dX = np.empty((R, Ci, H, Wd))
+    _L().ora_conv_dgrad(_p(D), _p(W), _p(dX), _l(R), _l(Ci), _l(H), _l(Wd), _l(Co), _l(kh), _l(kw),
+                        _l(stride), _l(pad))
+    return dX
+
+
+def dwconv_dgrad(D, W, H, Wd, stride=1, pad=0):
+    D, W = _d(D), _d(W)
+    Cc, kh, kw = W.shape
+    R = D.shape[0]
+    dX = np.empty((R, Cc, H, Wd))
+    _L().ora_dwconv_dgrad(_p(D), _p(W), _p(dX), _l(R), _l(Cc), _l(H), _l(Wd), _l(kh), _l(kw), _l(stride), _l(pad))
+    return dX
+
+
+def masked_dw_layer(W, X, r, D, A, gamma, stride=1, pad=0, tol=1e-3, scale=1.0):
+    """masked_layer for a depthwise convolution W[C,kh,kw]: the same staged
+    steps with the depthwise correlation as the bilinear operation."""
+    Ainv, nvec, B = coefficients(A, gamma)
+    Xbar = encode(X, r, A)
+    Ybar = dwconv_fwd(W, Xbar, stride, pad)
+    verdict, rho = verify(Ybar, nvec, tol)
+    Y = decode(Ybar, Ainv)
+    Dt = delta_mix(D, B, gamma)
+    dW = dwconv_wgrad(Dt, Xbar, W.shape[1], W.shape[2], stride, pad, scale)
+    return dict(Xbar=Xbar, Ybar=Ybar, verdict=verdict, rho=rho, Y=Y, dW=dW)

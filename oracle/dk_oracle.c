@@ -585,3 +585,115 @@ void ora_noise_philox(double *r, long G, long M, long n, uint64_t seed, double s
                     r[(g * M + q) * n + 4 * b + k] = sigma * z[k];
             }
 }
+
+/* ---------------------------------------------------------------------- */
+/* Depthwise convolution (one filter per channel) and data gradients.      */
+/* ---------------------------------------------------------------------- */
+
+/* Depthwise NCHW cross-correlation, the spatial half of a depthwise-separable
+ * layer: Y[s][c][h][w] = sum_{a,b} W[c][a][b] X[s][c][h*st+a-p][w*st+b-p]. */
+void ora_dwconv_fwd(const double *W, const double *X, double *Y, long R, long Cc, long H,
+                    long Wd, long kh, long kw, long st, long p)
+{
+    const long Ho = (H + 2 * p - kh) / st + 1, Wo = (Wd + 2 * p - kw) / st + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (long s = 0; s < R; ++s)
+        for (long c = 0; c < Cc; ++c)
+            for (long h = 0; h < Ho; ++h)
+                for (long w = 0; w < Wo; ++w) {
+                    double acc = 0.0;
+                    for (long a = 0; a < kh; ++a)
+                        for (long b = 0; b < kw; ++b) {
+                            const long ih = h * st + a - p, iw = w * st + b - p;
+                            if (ih < 0 || ih >= H || iw < 0 || iw >= Wd) continue;
+                            acc += W[(c * kh + a) * kw + b] * X[((s * Cc + c) * H + ih) * Wd + iw];
+                        }
+                    Y[((s * Cc + c) * Ho + h) * Wo + w] = acc;
+                }
+}
+
+/* Its weight gradient, the same pairing <delta, x> per channel:
+ * dW[c][a][b] = scale * sum_{s,h,w} D[s][c][h][w] X[s][c][h*st+a-p][w*st+b-p]. */
+void ora_dwconv_wgrad(const double *D, const double *X, double *dW, long R, long Cc, long H,
+                      long Wd, long kh, long kw, long st, long p, double scale)
+{
+    const long Ho = (H + 2 * p - kh) / st + 1, Wo = (Wd + 2 * p - kw) / st + 1;
+#pragma omp parallel for schedule(static)
+    for (long c = 0; c < Cc; ++c)
+        for (long a = 0; a < kh; ++a)
+            for (long b = 0; b < kw; ++b) {
+                double acc = 0.0;
+                for (long s = 0; s < R; ++s)
+                    for (long h = 0; h < Ho; ++h)
+                        for (long w = 0; w < Wo; ++w) {
+                            const long ih = h * st + a - p, iw = w * st + b - p;
+                            if (ih < 0 || ih >= H || iw < 0 || iw >= Wd) continue;
+                            acc += D[((s * Cc + c) * Ho + h) * Wo + w] * X[((s * Cc + c) * H + ih) * Wd + iw];
+                        }
+                dW[(c * kh + a) * kw + b] = scale * acc;
+            }
+}
+
+/* Data gradients (Backward Propagation, second linear operation: the gradient
+ * with respect to the layer input; it holds no private input and runs
+ * un-encoded).  Each is the transpose of the forward map:
+ * dense   dX[s][k]        = sum_o D[s][o] W[o][k];
+ * conv    dX[s][ci][i][j] = sum_{co,a,b} D[s][co][h][w] W[co][ci][a][b]
+ *                           over the (h, w) with h*st+a-p = i, w*st+b-p = j;
+ * depthwise the same with co = ci = c. */
+void ora_dense_dgrad(const double *D, const double *W, double *dX, long R, long M, long N)
+{
+#pragma omp parallel for collapse(2) schedule(static)
+    for (long s = 0; s < R; ++s)
+        for (long k = 0; k < N; ++k) {
+            double acc = 0.0;
+            for (long o = 0; o < M; ++o) acc += D[s * M + o] * W[o * N + k];
+            dX[s * N + k] = acc;
+        }
+}
+
+void ora_conv_dgrad(const double *D, const double *W, double *dX, long R, long Ci, long H,
+                    long Wd, long Co, long kh, long kw, long st, long p)
+{
+    const long Ho = (H + 2 * p - kh) / st + 1, Wo = (Wd + 2 * p - kw) / st + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (long s = 0; s < R; ++s)
+        for (long ci = 0; ci < Ci; ++ci)
+            for (long i = 0; i < H; ++i)
+                for (long j = 0; j < Wd; ++j) {
+                    double acc = 0.0;
+                    for (long co = 0; co < Co; ++co)
+                        for (long a = 0; a < kh; ++a)
+                            for (long b = 0; b < kw; ++b) {
+                                const long hn = i + p - a, wn = j + p - b;
+                                if (hn < 0 || wn < 0 || hn % st || wn % st) continue;
+                                const long h = hn / st, w = wn / st;
+                                if (h >= Ho || w >= Wo) continue;
+                                acc += D[((s * Co + co) * Ho + h) * Wo + w] *
+                                       W[((co * Ci + ci) * kh + a) * kw + b];
+                            }
+                    dX[((s * Ci + ci) * H + i) * Wd + j] = acc;
+                }
+}
+
+void ora_dwconv_dgrad(const double *D, const double *W, double *dX, long R, long Cc, long H,
+                      long Wd, long kh, long kw, long st, long p)
+{
+    const long Ho = (H + 2 * p - kh) / st + 1, Wo = (Wd + 2 * p - kw) / st + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (long s = 0; s < R; ++s)
+        for (long c = 0; c < Cc; ++c)
+            for (long i = 0; i < H; ++i)
+                for (long j = 0; j < Wd; ++j) {
+                    double acc = 0.0;
+                    for (long a = 0; a < kh; ++a)
+                        for (long b = 0; b < kw; ++b) {
+                            const long hn = i + p - a, wn = j + p - b;
+                            if (hn < 0 || wn < 0 || hn % st || wn % st) continue;
+                            const long h = hn / st, w = wn / st;
+                            if (h >= Ho || w >= Wo) continue;
+                            acc += D[((s * Cc + c) * Ho + h) * Wo + w] * W[(c * kh + a) * kw + b];
+                        }
+                    dX[((s * Cc + c) * H + i) * Wd + j] = acc;
+                }
+}
