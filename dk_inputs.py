@@ -22,7 +22,8 @@ import numpy as np
 @dataclass(frozen=True)
 class Layer:
     """kind 'linear': y = W x, W[M, N].  kind 'conv': NCHW cross-correlation,
-    W[Co, Ci, kh, kw], no bias."""
+    W[Co, Ci, kh, kw], no bias.  kind 'dwconv': depthwise cross-correlation,
+    one filter per channel, W[Ci, kh, kw], Co == Ci."""
     kind: str
     M: int = 0
     N: int = 0
@@ -53,10 +54,14 @@ class Layer:
 
     @property
     def w_shape(self):
+        if self.kind == "dwconv":
+            return (self.Ci, self.kh, self.kw)
         return (self.M, self.N) if self.kind == "linear" else (self.Co, self.Ci, self.kh, self.kw)
 
     @property
     def fan_in(self):
+        if self.kind == "dwconv":
+            return self.kh * self.kw
         return self.N if self.kind == "linear" else self.Ci * self.kh * self.kw
 
     @property
@@ -64,6 +69,8 @@ class Layer:
         """Multiply-accumulates of the layer for one (encoded) input row."""
         if self.kind == "linear":
             return self.M * self.N
+        if self.kind == "dwconv":
+            return self.Ci * self.Ho * self.Wo * self.kh * self.kw
         return self.Co * self.Ho * self.Wo * self.Ci * self.kh * self.kw
 
     def asdict(self):
@@ -76,6 +83,11 @@ def linear(M, N):
 
 def conv(Ci, Co, H, W, k=3, stride=1, pad=None):
     return Layer("conv", Ci=Ci, Co=Co, H=H, W=W, kh=k, kw=k, stride=stride,
+                 pad=(k // 2 if pad is None else pad))
+
+
+def dwconv(C, H, W, k=3, stride=1, pad=None):
+    return Layer("dwconv", Ci=C, Co=C, H=H, W=W, kh=k, kw=k, stride=stride,
                  pad=(k // 2 if pad is None else pad))
 
 

@@ -53,14 +53,17 @@ typedef enum {
 
 /* Layer descriptor.  kind 0: dense y = W x with W[M][N].  kind 1: NCHW
  * cross-correlation without bias, W[Co][Ci][kh][kw], zero padding, output
- * Ho = (H + 2 pad - kh)/stride + 1 (same for Wo). */
+ * Ho = (H + 2 pad - kh)/stride + 1 (same for Wo).  kind 2: depthwise
+ * cross-correlation, one filter per channel, W[Ci][kh][kw], Co == Ci, filter
+ * edges up to 7 (the spatial half of a depthwise-separable layer; the
+ * entry points that take a convolution layer take this kind too). */
 typedef struct dk_layer {
     int kind;
     int M, N;
     int Ci, Co, H, W, kh, kw, stride, pad;
 } dk_layer;
 
-enum { DK_LINEAR = 0, DK_CONV2D = 1 };
+enum { DK_LINEAR = 0, DK_CONV2D = 1, DK_DWCONV2D = 2 };
 enum { DK_OP_FWD = 0, DK_OP_WGRAD = 1, DK_OP_VERIFY = 2 };
 
 const char *dk_status_str(int status);

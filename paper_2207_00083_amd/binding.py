@@ -33,12 +33,12 @@ class DkLayer(C.Structure):
     @classmethod
     def of(cls, layer):
         """Accepts a DkLayer or any object with the same attribute names
-        (kind may be 'linear'/'conv' or 0/1)."""
+        (kind may be 'linear'/'conv'/'dwconv' or 0/1/2)."""
         if isinstance(layer, cls):
             return layer
         kind = layer.kind
         if isinstance(kind, str):
-            kind = {"linear": 0, "conv": 1}[kind]
+            kind = {"linear": 0, "conv": 1, "dwconv": 2}[kind]
         return cls(kind, *[int(getattr(layer, n)) for n in
                            ("M", "N", "Ci", "Co", "H", "W", "kh", "kw", "stride", "pad")])
 
@@ -147,6 +147,14 @@ def _workspace(nbytes, like):
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=like.device)
 
 
+def _wshape(lay):
+    if lay.kind == 0:
+        return (lay.M, lay.N)
+    if lay.kind == 2:
+        return (lay.Ci, lay.kh, lay.kw)
+    return (lay.Co, lay.Ci, lay.kh, lay.kw)
+
+
 def dk_layer_in_len(layer) -> int:
     return int(load().dk_layer_in_len(C.byref(DkLayer.of(layer))))
 
@@ -227,7 +235,7 @@ def dk_conv_fwd(layer, W, xbar, ybar=None, ws=None, stream=None):
     n, m = dk_layer_in_len(lay), dk_layer_out_len(lay)
     if n == 0:
         raise DkError(2, "dk_conv_fwd")
-    if xbar[0].numel() != n or W.numel() != lay.Co * lay.Ci * lay.kh * lay.kw:
+    if xbar[0].numel() != n or W.numel() != int(np.prod(_wshape(lay))):
         raise ValueError("dk_conv_fwd: inconsistent shapes")
     if ybar is None:
         Ho = (lay.H + 2 * lay.pad - lay.kh) // lay.stride + 1
@@ -256,7 +264,7 @@ def dk_wgrad(layer, delta, B, gamma, xbar, K, dW=None, scale=1.0, accumulate=Fal
     if (S != K + 2 or B.shape != (G, S, K) or delta.numel() != G * K * m
             or xbar.numel() != G * S * n):
         raise ValueError("dk_wgrad: inconsistent shapes")
-    wshape = (lay.M, lay.N) if lay.kind == 0 else (lay.Co, lay.Ci, lay.kh, lay.kw)
+    wshape = _wshape(lay)
     if dW is None:
         if accumulate:
             raise ValueError("dk_wgrad: accumulate needs an existing dW")
@@ -411,7 +419,7 @@ def dk_wgrad_m(layer, delta, B, gamma, xbar, K, M, dW=None, scale=1.0, accumulat
     if (S != K + M + 1 or B.shape != (G, S, K) or delta.numel() != G * K * m
             or xbar.numel() != G * S * n):
         raise ValueError("dk_wgrad_m: inconsistent shapes")
-    wshape = (lay.M, lay.N) if lay.kind == 0 else (lay.Co, lay.Ci, lay.kh, lay.kw)
+    wshape = _wshape(lay)
     if dW is None:
         if accumulate:
             raise ValueError("dk_wgrad_m: accumulate needs an existing dW")

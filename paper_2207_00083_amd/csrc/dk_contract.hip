@@ -706,6 +706,7 @@ bool conv_flat(const dk_geom &g) { return g.Co <= 64; }
 
 size_t dk_ws_fwd_bytes(const dk_geom &g, long long R)
 {
+    if (g.dw) return 256;
     size_t b;
     if (!g.conv)
         b = split_bytes<CfgSq>(R, g.M, g.N, R * g.m);
@@ -729,6 +730,7 @@ size_t dk_ws_fwd_bytes(const dk_geom &g, long long R)
 size_t dk_ws_wgrad_bytes(const dk_geom &g, long long R)
 {
     // mixed gradients dtilde[R][m] first, then the partial sums
+    if (g.dw) return align_up((size_t)R * g.m * sizeof(float), 256) + dk_dw_wgrad_part_bytes(g, R);
     size_t part;
     if (!g.conv)
         part = split_bytes<CfgSq>(g.M, g.N, R, (long long)g.M * g.N);
@@ -776,6 +778,7 @@ DK_EXPORT dk_status dk_conv_fwd(const dk_layer *L, const float *W, const float *
     DK_REQUIRE(ws && ws_bytes >= dk_ws_fwd_bytes(g, R), DK_ERR_WORKSPACE);
     DK_REQUIRE(dk_aligned(ws, 16), DK_ERR_ALIGN);
     hipStream_t st = (hipStream_t)stream;
+    if (g.dw) return dk_dw_fwd_run(g, W, xbar, ybar, R, st);
     dk_patch_plan pl;
     if (dk_patch_fwd_plan(g, R, dk_aligned(xbar, 16) && dk_aligned(ybar, 16), &pl))
         return dk_patch_fwd_run(g, pl, W, xbar, ybar, (float *)ws, st);
@@ -824,6 +827,7 @@ static dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *
     s = dk_delta_mix(delta, B, gamma, dtilde, G, K, M, g.m, st);
     if (s != DK_OK) return s;
 
+    if (g.dw) return dk_dw_wgrad_run(g, dtilde, xbar, dW, R, scale, accumulate, part, st);
     if (!g.conv) {
         const bool vec = (g.M % 4 == 0) && (g.N % 4 == 0) && dk_aligned(xbar, 16);
         if (vec)

@@ -693,7 +693,7 @@ bool plan_conv_wgrad(const dk_geom &g, long long R, fgemm_plan *pl)
 DK_EXPORT size_t dkf_conv_fwd_workspace_bytes(const dk_layer *L, int R)
 {
     dk_geom g;
-    if (dk_layer_geom(L, &g) != DK_OK || !g.conv || R < 1) return 0;
+    if (dk_layer_geom(L, &g) != DK_OK || !g.conv || g.dw || R < 1) return 0;
     fgemm_plan pl;
     if (!plan_conv_fwd(g, R, &pl)) return 0;
     return FLAG_BYTES + pl.a_bytes + pl.b_bytes + pl.part_bytes;
@@ -706,7 +706,7 @@ DK_EXPORT dk_status dkf_conv_fwd(const dk_layer *L, const uint32_t *Wq, const ui
     dk_geom g;
     const dk_status gs = dk_layer_geom(L, &g);
     if (gs != DK_OK) return gs;
-    DK_REQUIRE(g.conv, DK_ERR_UNSUPPORTED);
+    DK_REQUIRE(g.conv && !g.dw, DK_ERR_UNSUPPORTED);
     DK_REQUIRE(R >= 1, DK_ERR_SHAPE);
     fgemm_plan pl;
     DK_REQUIRE(plan_conv_fwd(g, R, &pl), DK_ERR_SHAPE);
@@ -752,7 +752,7 @@ DK_EXPORT size_t dkf_fwd_workspace_bytes(int M, int N, int R)
 DK_EXPORT size_t dkf_wgrad_workspace_bytes(const dk_layer *L, int G, int K)
 {
     dk_geom g;
-    if (dk_layer_geom(L, &g) != DK_OK) return 0;
+    if (dk_layer_geom(L, &g) != DK_OK || g.dw) return 0;
     if (G < 1 || K < 1 || K > DK_MAX_K) return 0;
     const long long R = (long long)G * (K + 2);
     fgemm_plan pl;
@@ -799,6 +799,7 @@ DK_EXPORT dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint3
     dk_geom g;
     const dk_status gs = dk_layer_geom(L, &g);
     if (gs != DK_OK) return gs;
+    DK_REQUIRE(!g.dw, DK_ERR_UNSUPPORTED);
     DK_REQUIRE(G >= 1 && K >= 1 && K <= DK_MAX_K && l >= 0 && l <= DKF_MAX_L, DK_ERR_SHAPE);
     const long long R = (long long)G * (K + 2);
     fgemm_plan pl;

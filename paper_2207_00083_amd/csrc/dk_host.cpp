@@ -36,8 +36,9 @@ dk_status dk_layer_geom(const dk_layer *L, dk_geom *g)
         g->m = L->M;
         return DK_OK;
     }
-    DK_REQUIRE(L->kind == DK_CONV2D, DK_ERR_UNSUPPORTED);
+    DK_REQUIRE(L->kind == DK_CONV2D || L->kind == DK_DWCONV2D, DK_ERR_UNSUPPORTED);
     DK_REQUIRE(L->Ci >= 1 && L->Co >= 1 && L->H >= 1 && L->W >= 1, DK_ERR_SHAPE);
+    DK_REQUIRE(L->kind == DK_CONV2D || L->Co == L->Ci, DK_ERR_SHAPE);
     DK_REQUIRE(L->kh >= 1 && L->kw >= 1 && L->stride >= 1 && L->pad >= 0, DK_ERR_SHAPE);
     DK_REQUIRE(L->kh <= 16 && L->kw <= 16 && L->stride <= 16 && L->pad <= 16, DK_ERR_UNSUPPORTED);
     DK_REQUIRE(L->H + 2 * L->pad >= L->kh && L->W + 2 * L->pad >= L->kw, DK_ERR_SHAPE);
@@ -49,6 +50,11 @@ dk_status dk_layer_geom(const dk_layer *L, dk_geom *g)
     g->n = (long long)L->Ci * L->H * L->W;
     g->m = (long long)L->Co * g->Ho * g->Wo;
     g->Kg = (long long)L->Ci * L->kh * L->kw;
+    if (L->kind == DK_DWCONV2D) {
+        g->dw = true;
+        g->Kg = (long long)L->kh * L->kw;
+        DK_REQUIRE(dk_dw_supported(*g), DK_ERR_UNSUPPORTED);
+    }
     // the kernels index one sample's image and the filter bank with 32-bit ints
     DK_REQUIRE(g->n < (1ll << 30) && g->m < (1ll << 30) && g->Kg * L->Co < (1ll << 30), DK_ERR_SHAPE);
     return DK_OK;

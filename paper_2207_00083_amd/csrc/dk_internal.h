@@ -21,6 +21,7 @@ static inline dk_status dk_launch_status()
 // Validated geometry of a layer, filled by dk_layer_geom().
 struct dk_geom {
     bool conv;
+    bool dw;              // depthwise convolution (conv is true too; Co == Ci, one filter per channel)
     long long n, m;       // per-sample input / output length
     int M, N;             // dense
     int Ci, Co, H, W, kh, kw, stride, pad, Ho, Wo;
@@ -44,6 +45,16 @@ dk_split_plan dk_plan_split(long long out_tiles, long long ktiles, long long out
 #define DK_VERIFY_MAX_BLOCKS 64
 #define DK_MAX_SPLITS 256
 #define DK_SPLIT_WS_CAP_BYTES (1ll << 30)
+
+// Depthwise convolution kernels.
+bool dk_dw_supported(const dk_geom &g);
+size_t dk_dw_wgrad_part_bytes(const dk_geom &g, long long R);
+dk_status dk_dw_fwd_run(const dk_geom &g, const float *W, const float *xbar, float *ybar, long long R,
+                        hipStream_t st);
+dk_status dk_dw_wgrad_run(const dk_geom &g, const float *dtilde, const float *xbar, float *dW, long long R,
+                          float scale, int accumulate, float *part, hipStream_t st);
+dk_status dk_dw_dgrad_run(const dk_geom &g, const float *W, const float *delta, float *dx, long long R,
+                          hipStream_t st);
 
 // Gradient mixing kernel launcher (defined with the other bandwidth-bound
 // kernels, used by dk_wgrad).
