@@ -52,6 +52,10 @@ def workload(name):
     if name.startswith("config5."):
         i = int(name.split(".")[1])
         return dk_inputs.config5(index=i)[0], "config5 layer %d (VGG classifier, batch 1024, K=8)" % i
+    if name.startswith("mbv2dw."):
+        i = int(name.split(".")[1])
+        d, count = dk_inputs.mobilenetv2_dw(index=i)[0]
+        return d, "MobileNetV2 depthwise 3x3 layer %d x%d (224x224 input, batch 64, K=8)" % (i, count)
     raise SystemExit("unknown workload " + name)
 
 
@@ -191,7 +195,7 @@ def field_main(args):
     A_d, Ainv_d, nvec_d, B_d, gamma_d = dev(d["A"]), dev(Ainv), dev(nvec), dev(B), dev(d["gamma"])
     i32 = dict(dtype=torch.int32, device="cuda")
     f32 = dict(dtype=torch.float32, device="cuda")
-    conv = L.kind == "conv"
+    conv = L.kind in ("conv", "dwconv")
     Wq = torch.empty(L.w_shape, **i32)
     xbar = torch.empty((R,) + L.in_shape, **i32)
     ybar = torch.empty((R,) + L.out_shape, **i32)
@@ -363,6 +367,8 @@ def sub_workloads(name):
         return [("config4.%d" % i, c) for i, (_, c) in enumerate(dk_inputs.resnet50_convs())]
     if name == "config5":
         return [("config5.%d" % i, 1) for i in range(len(dk_inputs.config5_layers()))]
+    if name == "mbv2dw":
+        return [("mbv2dw.%d" % i, c[3]) for i, c in enumerate(dk_inputs.MOBILENETV2_DW)]
     if name == "field5":
         return [("field5.%d" % i, 1) for i in range(len(dk_inputs.config5_layers()))]
     return None
@@ -455,7 +461,7 @@ def layer_main(args):
 
     b0 = Buffers()
     y, dW, verdict = b0.y, b0.dW, b0.verdict
-    conv = L.kind == "conv"
+    conv = L.kind in ("conv", "dwconv")
 
     stages = ["encode", "fwd", "decode_verify", "wgrad"]
 
@@ -570,18 +576,31 @@ def layer_main(args):
     # Dominant kernel = the contraction kernel with the longest average launch
     # (forward and weight gradient execute the same FLOP count per launch).
     contraction = {k: v for k, v in kernels.items()
-                   if k.startswith(("conv_", "contract_")) and v[1] == args.steps}
+                   if k.startswith(("conv_", "contract_", "dw_")) and v[1] == args.steps}
     dom = max(contraction, key=lambda k: contraction[k][0])
     dom_ms = contraction[dom][0]
     dom_tflops = flop_fwd / (dom_ms * 1e-3) / 1e12
-    roofline = {
+    if L.kind == "dwconv":
+        # nine multiply-adds per element moved: the depthwise kernels are bandwidth-bound;
+        # each reads one tensor of the input size and reads or writes one of the output size
+        dw_bytes = 4.0 * G * S * (n + m)
+        gbps = dw_bytes / (dom_ms * 1e-3) / 1e9
+        roofline = {
+            "kernel": dom, "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": gbps / HBM_PEAK_GBPS, "traffic": measured_traffic(args.workload, dom),
+            "avg_launch_ms": dom_ms, "bytes_per_launch": dw_bytes,
+            "timed": "HIP events around every launch of this kernel, %d eager launches after the timed region"
+                     % args.steps,
+        }
+    else:
+      roofline = {
         "kernel": dom, "bound": "mfma", "achieved": dom_tflops, "peak": MFMA_F32_PEAK_TFLOPS,
         "unit": "TFLOP/s", "frac": dom_tflops / MFMA_F32_PEAK_TFLOPS,
         "traffic": measured_traffic(args.workload, dom),
         "avg_launch_ms": dom_ms, "flop_per_launch": flop_fwd,
         "timed": "HIP events around every launch of this kernel, %d eager launches after the timed region, "
                  "cycling through %d buffer sets of %.0f MB" % (args.steps, len(sets), set_bytes / 1e6),
-    }
+      }
     kname = {"encode": "encode_rng" if args.rng_noise else "encode", "decode_verify": "decode_verify",
              "delta_mix": "delta_mix"}
     if args.rng_noise:

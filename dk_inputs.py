@@ -311,6 +311,23 @@ def config4(seed=4, batch=64, K=8, include_stem=False):
         yield d, count
 
 
+MOBILENETV2_DW = [(32, 112, 1, 1), (96, 112, 2, 1), (144, 56, 1, 1), (144, 56, 2, 1), (192, 28, 1, 2),
+                  (192, 28, 2, 1), (384, 14, 1, 4), (576, 14, 1, 2), (576, 14, 2, 1), (960, 7, 1, 3)]
+
+
+def mobilenetv2_dw(seed=6, batch=64, K=8, index=None):
+    """The depthwise 3x3 layers of MobileNetV2 at 224x224 input (channels,
+    input size, stride, multiplicity): list of (inputs dict, multiplicity)."""
+    out = []
+    for li, (c, hw, st, count) in enumerate(MOBILENETV2_DW):
+        if index is not None and li != index:
+            continue
+        rng = np.random.default_rng([seed, li])
+        out.append((masked_layer_inputs(rng, dwconv(c, hw, hw, 3, st), K=K, batch=batch,
+                                        x_dist="relu_normal"), count))
+    return out
+
+
 def config5_layers():
     return [linear(4096, 25088), linear(4096, 4096), linear(1000, 4096)]
 
