@@ -240,6 +240,26 @@ dk_status dk_noise_rng(float *r, int G, int M, long long n, unsigned long long s
 dk_status dk_encode_rng(const float *x, const float *A, float *xbar, int G, int K, int M,
                         long long n, unsigned long long seed, float noise_std, void *stream);
 
+/* ------------------------------------------------------------------------
+ * Data gradient (Backward Propagation, second linear operation: the gradient
+ * with respect to a layer's input is computed from the next layer's gradient
+ * and the weights only; it holds no private input and runs un-encoded).  Not
+ * part of the masked path; provided so that a whole backward pass can run on
+ * the library.  It is the transpose of the layer's forward map:
+ *   dense      dx[r][k]        = sum_o delta[r][o] W[o][k];
+ *   conv       dx[r][ci][i][j] = sum_{co,a,b} delta[r][co][h][w] W[co][ci][a][b]
+ *                                over the (h, w) with h*stride+a-pad = i,
+ *                                w*stride+b-pad = j;
+ *   depthwise  the same with co = ci.
+ * W (shape of the layer's weights), delta[R][m] -> dx[R][n], all device.
+ * Stride-1 convolutions with square filters run as a forward convolution with
+ * transposed, flipped filters; other convolution geometries use a plain
+ * gather kernel.  Workspace: dk_dgrad_workspace_bytes(L, R), 256-byte aligned.
+ * ------------------------------------------------------------------------ */
+dk_status dk_dgrad(const dk_layer *L, const float *W, const float *delta, float *dx, int R,
+                   void *ws, size_t ws_bytes, void *stream);
+size_t dk_dgrad_workspace_bytes(const dk_layer *L, int R);
+
 #ifdef __cplusplus
 }
 #endif

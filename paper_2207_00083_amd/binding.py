@@ -79,6 +79,8 @@ def load():
         "dk_decode_verify_m": (ip, [vp, vp, vp, fl, vp, vp, vp, ip, ip, ip, ll, vp, sz, vp]),
         "dk_wgrad_m": (ip, [LP, vp, vp, vp, vp, vp, ip, ip, ip, fl, ip, vp, sz, vp]),
         "dk_workspace_bytes_m": (sz, [LP, ip, ip, ip, ip]),
+        "dk_dgrad": (ip, [LP, vp, vp, vp, ip, vp, sz, vp]),
+        "dk_dgrad_workspace_bytes": (sz, [LP, ip]),
         "dk_noise_rng": (ip, [vp, ip, ip, ll, C.c_ulonglong, fl, vp]),
         "dk_encode_rng": (ip, [vp, vp, vp, ip, ip, ip, ll, C.c_ulonglong, fl, vp]),
         "dkf_noise_rng": (ip, [vp, ip, ll, C.c_ulonglong, vp]),
@@ -433,6 +435,30 @@ def dk_wgrad_m(layer, delta, B, gamma, xbar, K, M, dW=None, scale=1.0, accumulat
                              G, K, M, float(scale), int(bool(accumulate)), _ptr(ws), ws.numel(),
                              _stream(stream)), "dk_wgrad_m")
     return dW
+
+
+def dk_dgrad(layer, W, delta, dx=None, ws=None, stream=None):
+    """Un-encoded data gradient: W (layer's weight shape), delta[R, ...out] -> dx[R, ...in] (device)."""
+    torch = _torch()
+    lay = DkLayer.of(layer)
+    W, delta = _dev(W, "W"), _dev(delta, "delta")
+    R = delta.shape[0]
+    n, m = dk_layer_in_len(lay), dk_layer_out_len(lay)
+    if n == 0:
+        raise DkError(2, "dk_dgrad")
+    if delta[0].numel() != m or W.numel() != int(np.prod(_wshape(lay))):
+        raise ValueError("dk_dgrad: inconsistent shapes")
+    if dx is None:
+        shape = (R, lay.N) if lay.kind == 0 else (R, lay.Ci, lay.H, lay.W)
+        dx = torch.empty(shape, dtype=torch.float32, device=W.device)
+    _dev(dx, "dx")
+    if dx.numel() != R * n:
+        raise ValueError("dk_dgrad: dx has the wrong size")
+    if ws is None:
+        ws = _workspace(load().dk_dgrad_workspace_bytes(C.byref(lay), R), W)
+    _check(load().dk_dgrad(C.byref(lay), _ptr(W), _ptr(delta), _ptr(dx), R, _ptr(ws), ws.numel(),
+                           _stream(stream)), "dk_dgrad")
+    return dx
 
 
 # ---- noise drawn by the library's counter-based generator ----

@@ -630,6 +630,19 @@ dk_status run_dense_nt(const float *A, const float *B, float *Cout, int rows, in
                                     (long long)rows * cols, part, part_bytes, st, "contract_dense_fwd");
 }
 
+// C[rows][cols] = A[rows][k] . B[k][cols]  (A contiguous along k, B along cols)
+template <class C, bool VA, bool VB>
+dk_status run_dense_nn(const float *A, const float *B, float *Cout, int rows, int cols, int kdim,
+                       float *part, size_t part_bytes, hipStream_t st)
+{
+    using LA = LoadRowMajorK<C::BM, C::BK, C::NT, C::LDA, VA>;
+    using LB = LoadKMajor<C::BN, C::BK, C::NT, C::LDB, VB>;
+    MatParams pa = {A, kdim, rows, kdim}, pb = {B, cols, cols, kdim};
+    EpiDense ep = {cols, rows, cols};
+    return run<C, LA, LB, EpiDense>(pa, pb, ep, rows, cols, kdim, 1.0f, 0, Cout,
+                                    (long long)rows * cols, part, part_bytes, st, "contract_dense_dgrad");
+}
+
 template <class C, bool VEC>
 dk_status run_dense_tn(const float *A, const float *B, float *Cout, int rows, int cols, int kdim,
                        float alpha, int accumulate, float *part, size_t part_bytes, hipStream_t st)
@@ -765,18 +778,12 @@ DK_EXPORT dk_status dk_linear_fwd(const float *W, const float *xbar, float *ybar
     return run_dense_nt<CfgSq, false, false>(xbar, W, ybar, R, M, N, (float *)ws, ws_bytes, st);
 }
 
-DK_EXPORT dk_status dk_conv_fwd(const dk_layer *L, const float *W, const float *xbar, float *ybar,
-                                int R, void *ws, size_t ws_bytes, void *stream)
+// The convolution forward dispatch for a validated geometry (also the engine
+// behind the stride-1 data gradient, which is a forward convolution with
+// transposed, flipped filters).
+static dk_status conv_fwd_impl(const dk_geom &g, const float *W, const float *xbar, float *ybar, int R,
+                               void *ws, size_t ws_bytes, void *stream)
 {
-    DK_REQUIRE(L && W && xbar && ybar, DK_ERR_NULL);
-    dk_geom g;
-    dk_status s = dk_layer_geom(L, &g);
-    if (s != DK_OK) return s;
-    DK_REQUIRE(g.conv, DK_ERR_UNSUPPORTED);
-    DK_REQUIRE(R >= 1 && (long long)R * g.Ho * g.Wo < (1ll << 31) - 512, DK_ERR_SHAPE);
-    DK_REQUIRE(dk_aligned(W, 4) && dk_aligned(xbar, 4) && dk_aligned(ybar, 4), DK_ERR_ALIGN);
-    DK_REQUIRE(ws && ws_bytes >= dk_ws_fwd_bytes(g, R), DK_ERR_WORKSPACE);
-    DK_REQUIRE(dk_aligned(ws, 16), DK_ERR_ALIGN);
     hipStream_t st = (hipStream_t)stream;
     if (g.dw) return dk_dw_fwd_run(g, W, xbar, ybar, R, st);
     dk_patch_plan pl;
@@ -798,6 +805,21 @@ DK_EXPORT dk_status dk_conv_fwd(const dk_layer *L, const float *W, const float *
                   : run_conv_fwd<CfgFlat, false>(g, W, xbar, ybar, R, (float *)ws, ws_bytes, st);
     return vw ? run_conv_fwd<CfgSq, true>(g, W, xbar, ybar, R, (float *)ws, ws_bytes, st)
               : run_conv_fwd<CfgSq, false>(g, W, xbar, ybar, R, (float *)ws, ws_bytes, st);
+}
+
+DK_EXPORT dk_status dk_conv_fwd(const dk_layer *L, const float *W, const float *xbar, float *ybar,
+                                int R, void *ws, size_t ws_bytes, void *stream)
+{
+    DK_REQUIRE(L && W && xbar && ybar, DK_ERR_NULL);
+    dk_geom g;
+    dk_status s = dk_layer_geom(L, &g);
+    if (s != DK_OK) return s;
+    DK_REQUIRE(g.conv, DK_ERR_UNSUPPORTED);
+    DK_REQUIRE(R >= 1 && (long long)R * g.Ho * g.Wo < (1ll << 31) - 512, DK_ERR_SHAPE);
+    DK_REQUIRE(dk_aligned(W, 4) && dk_aligned(xbar, 4) && dk_aligned(ybar, 4), DK_ERR_ALIGN);
+    DK_REQUIRE(ws && ws_bytes >= dk_ws_fwd_bytes(g, R), DK_ERR_WORKSPACE);
+    DK_REQUIRE(dk_aligned(ws, 16), DK_ERR_ALIGN);
+    return conv_fwd_impl(g, W, xbar, ybar, R, ws, ws_bytes, stream);
 }
 
 // dk_wgrad for K private inputs and M noise rows per group (S = K + M + 1).
@@ -866,4 +888,129 @@ DK_EXPORT dk_status dk_wgrad_m(const dk_layer *L, const float *delta, const floa
                                int accumulate, void *ws, size_t ws_bytes, void *stream)
 {
     return wgrad_impl(L, delta, B, gamma, xbar, dW, G, K, M, scale, accumulate, ws, ws_bytes, stream);
+}
+
+// ---------------------------------------------------------------------------
+// Data gradients (un-encoded: they hold no private input).
+// ---------------------------------------------------------------------------
+namespace {
+
+// Wt[ci][co][a][b] = W[co][ci][kh-1-a][kw-1-b]
+__global__ __launch_bounds__(256) void dgrad_filter_kernel(const float *__restrict__ W, float *__restrict__ Wt,
+                                                           int Co, int Ci, int kh, int kw)
+{
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= Co * Ci * kh * kw) return;
+    const int khw = kh * kw;
+    const int ci = e / (Co * khw);
+    int rem = e - ci * (Co * khw);
+    const int co = rem / khw;
+    rem -= co * khw;
+    const int a = rem / kw, b = rem - a * kw;
+    Wt[e] = W[((long long)(co * Ci + ci) * kh + (kh - 1 - a)) * kw + (kw - 1 - b)];
+}
+
+// Any geometry, one thread per input element:
+// dx[r][ci][i][j] = sum_{co,a,b} d[r][co][(i+pad-a)/stride][(j+pad-b)/stride] W[co][ci][a][b]
+// over the taps whose quotients are whole and inside the output.
+__global__ __launch_bounds__(256) void conv_dgrad_direct_kernel(const float *__restrict__ W,
+                                                                const float *__restrict__ d,
+                                                                float *__restrict__ dx, long long total, int Ci,
+                                                                int Co, int H, int Wd, int kh, int kw,
+                                                                int stride, int pad, int Ho, int Wo)
+{
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int HW = H * Wd;
+    const long long rc = idx / HW;
+    const int px = (int)(idx - rc * HW);
+    const int i = px / Wd, j = px - i * Wd;
+    const long long r = rc / Ci;
+    const int ci = (int)(rc - r * Ci);
+    float acc = 0.0f;
+    for (int a = 0; a < kh; ++a) {
+        const int hn = i + pad - a;
+        if (hn < 0 || hn % stride) continue;
+        const int h = hn / stride;
+        if (h >= Ho) continue;
+        for (int b = 0; b < kw; ++b) {
+            const int wn = j + pad - b;
+            if (wn < 0 || wn % stride) continue;
+            const int w = wn / stride;
+            if (w >= Wo) continue;
+            const float *dp = d + ((long long)r * Co * Ho + h) * Wo + w;
+            const float *wp = W + ((long long)ci * kh + a) * kw + b;
+            for (int co = 0; co < Co; ++co)
+                acc = fmaf(dp[(long long)co * Ho * Wo], wp[(long long)co * Ci * kh * kw], acc);
+        }
+    }
+    dx[idx] = acc;
+}
+
+// stride 1 with pad <= k-1 and a square filter: a forward convolution of delta
+bool dgrad_as_forward(const dk_geom &g, dk_geom *t)
+{
+    if (g.dw || g.stride != 1 || g.kh != g.kw || g.pad > g.kh - 1) return false;
+    *t = g;
+    t->Ci = g.Co; t->Co = g.Ci; t->H = g.Ho; t->W = g.Wo; t->pad = g.kh - 1 - g.pad;
+    t->Ho = g.H; t->Wo = g.W;
+    t->n = (long long)t->Ci * t->H * t->W;
+    t->m = (long long)t->Co * t->Ho * t->Wo;
+    t->Kg = (long long)t->Ci * t->kh * t->kw;
+    return t->pad <= 16;
+}
+
+} // namespace
+
+DK_EXPORT size_t dk_dgrad_workspace_bytes(const dk_layer *L, int R)
+{
+    dk_geom g, t;
+    if (R < 1 || dk_layer_geom(L, &g) != DK_OK) return 0;
+    if (!g.conv) {
+        dk_geom d = {};
+        d.M = g.N; d.N = g.M; d.n = g.M; d.m = g.N;          // C[R][N] over k = M
+        return dk_ws_fwd_bytes(d, R);
+    }
+    if (dgrad_as_forward(g, &t))
+        return align_up((size_t)g.Co * g.Ci * g.kh * g.kw * sizeof(float), 256) + dk_ws_fwd_bytes(t, R);
+    return 256;
+}
+
+DK_EXPORT dk_status dk_dgrad(const dk_layer *L, const float *W, const float *delta, float *dx, int R,
+                             void *ws, size_t ws_bytes, void *stream)
+{
+    DK_REQUIRE(L && W && delta && dx, DK_ERR_NULL);
+    dk_geom g, t;
+    dk_status s = dk_layer_geom(L, &g);
+    if (s != DK_OK) return s;
+    DK_REQUIRE(R >= 1 && (long long)R * g.n < (1ll << 40) && (long long)R * g.m < (1ll << 40), DK_ERR_SHAPE);
+    DK_REQUIRE(dk_aligned(W, 4) && dk_aligned(delta, 4) && dk_aligned(dx, 4), DK_ERR_ALIGN);
+    DK_REQUIRE(ws && ws_bytes >= dk_dgrad_workspace_bytes(L, R), DK_ERR_WORKSPACE);
+    DK_REQUIRE(dk_aligned(ws, 256), DK_ERR_ALIGN);
+    hipStream_t st = (hipStream_t)stream;
+    if (!g.conv) {
+        const bool vec = (g.M % 4 == 0) && (g.N % 4 == 0) && dk_aligned(W, 16) && dk_aligned(delta, 16);
+        if (vec)
+            return run_dense_nn<CfgSq, true, true>(delta, W, dx, R, g.N, g.M, (float *)ws, ws_bytes, st);
+        return run_dense_nn<CfgSq, false, false>(delta, W, dx, R, g.N, g.M, (float *)ws, ws_bytes, st);
+    }
+    if (g.dw) return dk_dw_dgrad_run(g, W, delta, dx, R, st);
+    if (dgrad_as_forward(g, &t)) {
+        DK_REQUIRE((long long)R * t.Ho * t.Wo < (1ll << 31) - 512, DK_ERR_SHAPE);
+        float *Wt = (float *)ws;
+        const size_t wt_bytes = align_up((size_t)g.Co * g.Ci * g.kh * g.kw * sizeof(float), 256);
+        const int count = g.Co * g.Ci * g.kh * g.kw;
+        {
+            dk_prof_scope ps("dgrad_filter", st);
+            dgrad_filter_kernel<<<dim3((count + 255) / 256), dim3(256), 0, st>>>(W, Wt, g.Co, g.Ci, g.kh, g.kw);
+        }
+        DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+        return conv_fwd_impl(t, Wt, delta, dx, R, (char *)ws + wt_bytes, ws_bytes - wt_bytes, stream);
+    }
+    const long long total = (long long)R * g.n;
+    DK_REQUIRE((total + 255) / 256 <= 0x7fffffffll, DK_ERR_SHAPE);
+    dk_prof_scope ps("conv_dgrad_direct", st);
+    conv_dgrad_direct_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
+        W, delta, dx, total, g.Ci, g.Co, g.H, g.W, g.kh, g.kw, g.stride, g.pad, g.Ho, g.Wo);
+    return dk_launch_status();
 }

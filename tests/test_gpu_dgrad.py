@@ -1,0 +1,59 @@
+"""GPU parity of the un-encoded data gradient against the fp64 oracle."""
+import numpy as np
+import pytest
+
+import dk_inputs
+import oracle
+from conftest import normwise_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dk():
+    import torch
+    import paper_2207_00083_amd as m
+    m.load()
+    assert torch.cuda.is_available()
+    return m
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+@pytest.mark.parametrize("R,M,N", [(5, 7, 9), (130, 200, 300), (64, 512, 256), (33, 129, 1027)])
+def test_dense_dgrad(dk, R, M, N):
+    rng = np.random.default_rng([R, M, N])
+    W = rng.normal(size=(M, N)).astype(np.float32)
+    D = rng.normal(size=(R, M)).astype(np.float32)
+    dx = dk.dk_dgrad(dk_inputs.linear(M, N), dev(W), dev(D))
+    assert normwise_err(dx.cpu().numpy(), oracle.dense_dgrad(D, W)) < 1e-5
+
+
+CONVS = [dk_inputs.conv(16, 24, 12, 12, 3), dk_inputs.conv(64, 64, 16, 16, 3), dk_inputs.conv(8, 130, 10, 10, 3, 2, 1),
+         dk_inputs.conv(20, 12, 7, 7, 1), dk_inputs.conv(6, 9, 11, 8, 5, 2, 2), dk_inputs.conv(24, 40, 14, 14, 1, 2, 0),
+         dk_inputs.conv(5, 7, 9, 9, 3, 1, 0), dk_inputs.conv(12, 16, 8, 8, 5, 1, 2)]
+
+
+@pytest.mark.parametrize("L", CONVS)
+def test_conv_dgrad(dk, L):
+    rng = np.random.default_rng([L.Ci, L.Co, L.H, L.kh, L.stride])
+    R = 6
+    W = rng.normal(size=L.w_shape).astype(np.float32)
+    D = rng.normal(size=(R,) + L.out_shape).astype(np.float32)
+    dx = dk.dk_dgrad(L, dev(W), dev(D))
+    assert tuple(dx.shape) == (R,) + L.in_shape
+    assert normwise_err(dx.cpu().numpy(), oracle.conv_dgrad(D, W, L.H, L.W, L.stride, L.pad)) < 1e-5
+
+
+@pytest.mark.parametrize("L", [dk_inputs.dwconv(32, 16, 16, 3), dk_inputs.dwconv(24, 15, 13, 3, 2),
+                               dk_inputs.dwconv(8, 7, 7, 5, 1, 2)])
+def test_depthwise_dgrad(dk, L):
+    rng = np.random.default_rng([L.Ci, L.H, L.stride, 2])
+    R = 5
+    W = rng.normal(size=L.w_shape).astype(np.float32)
+    D = rng.normal(size=(R,) + L.out_shape).astype(np.float32)
+    dx = dk.dk_dgrad(L, dev(W), dev(D))
+    assert normwise_err(dx.cpu().numpy(), oracle.dwconv_dgrad(D, W, L.H, L.W, L.stride, L.pad)) < 1e-5
