@@ -334,6 +334,9 @@ def main():
     ap.add_argument("--rng-noise", action="store_true",
                     help="draw the noise inside the encoding kernel (dk_encode_rng / dkf_encode_rng, one seed "
                          "per step) instead of reading noise rows from HBM")
+    ap.add_argument("--with-dgrad", action="store_true",
+                    help="also time the un-encoded data gradient of the layer (dk_dgrad on the K*G real "
+                         "gradients); reported as dgrad_ms, not part of the masked path or of `value`")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every step eagerly")
     ap.add_argument("--fork", action="store_true",
@@ -633,6 +636,20 @@ def layer_main(args):
         "hbm_kernels": hbm,
         "kernel_ms": {k: v[0] for k, v in kernels.items()},
     }
+    if args.with_dgrad:
+        dx = torch.empty((G * K,) + L.in_shape, **f32)
+        ws_dg = torch.empty(dk.load().dk_dgrad_workspace_bytes(C.byref(dk.DkLayer.of(L)), G * K), **u8)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        for _ in range(3):
+            dk.dk_dgrad(L, W, b0.delta, dx=dx, ws=ws_dg)
+        ev[0].record()
+        for _ in range(args.steps):
+            dk.dk_dgrad(L, W, b0.delta, dx=dx, ws=ws_dg)
+        ev[1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[1]) / args.steps
+        out["dgrad_ms"] = ms
+        out["dgrad_tflops"] = 2.0 * G * K * L.macs_per_row / (ms * 1e-3) / 1e12
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(d)
     return out
