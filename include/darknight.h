@@ -253,8 +253,8 @@ dk_status dk_encode_rng(const float *x, const float *A, float *xbar, int G, int 
  *   depthwise  the same with co = ci.
  * W (shape of the layer's weights), delta[R][m] -> dx[R][n], all device.
  * Stride-1 convolutions with square filters run as a forward convolution with
- * transposed, flipped filters; other convolution geometries use a plain
- * gather kernel.  Workspace: dk_dgrad_workspace_bytes(L, R), 256-byte aligned.
+ * transposed, flipped filters; other convolution geometries gather delta
+ * through the generic contraction engine.  Workspace: dk_dgrad_workspace_bytes(L, R), 256-byte aligned.
  * ------------------------------------------------------------------------ */
 dk_status dk_dgrad(const dk_layer *L, const float *W, const float *delta, float *dx, int R,
                    void *ws, size_t ws_bytes, void *stream);

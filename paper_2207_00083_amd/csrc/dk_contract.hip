@@ -199,6 +199,59 @@ struct LoadIm2colFwd {
     }
 };
 
+// Convolution data gradient, B operand: rows = input pixels q = (r, i, j),
+// contraction k = (co, a, b); element = delta[r][co][(i+p-a)/s][(j+p-b)/s] when
+// both quotients are whole and inside the output, else 0.  ConvParams are those
+// of the layer with p pointing at delta; Q = R*H*W, HoWo stands for H*W here.
+template <int ROWS, int BK, int NT, int LD>
+struct LoadIm2colDgrad {
+    using Params = ConvParams;
+    static constexpr int KSTEP = NT / ROWS;
+    static constexpr int NE = BK / KSTEP;
+    static_assert(NT % ROWS == 0 && BK % KSTEP == 0, "tile/threads");
+    float st[NE];
+    const float *base; int Ho, Wo, kh, kw, Kg, stride, ip, jp, pcol, ksub; bool valid;
+
+    __device__ __forceinline__ void init(const Params &a, int q0, int tid)
+    {
+        pcol = tid % ROWS; ksub = tid / ROWS;
+        Ho = a.Ho; Wo = a.Wo; kh = a.kh; kw = a.kw; Kg = a.Co * a.kh * a.kw; stride = a.stride;
+        const int q = q0 + pcol;
+        const int HW = a.H * a.W;
+        valid = q < a.Q;
+        const int r = valid ? q / HW : 0;
+        const int pix = valid ? q - r * HW : 0;
+        const int i = pix / a.W, j = pix - i * a.W;
+        ip = i + a.pad; jp = j + a.pad;
+        base = a.p + (long long)r * a.Co * a.Ho * a.Wo;
+    }
+
+    __device__ __forceinline__ void load(int kt)
+    {
+        int k = kt * BK + ksub;
+        int co = k / (kh * kw);
+        int rem = k - co * (kh * kw);
+        int fa = rem / kw, fb = rem - fa * kw;
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            const int hn = ip - fa, wn = jp - fb;
+            const int h = hn / stride, w = wn / stride;
+            const bool ok = valid && k < Kg && hn >= 0 && wn >= 0 && h * stride == hn && w * stride == wn &&
+                            h < Ho && w < Wo;
+            st[e] = ok ? base[((long long)co * Ho + h) * Wo + w] : 0.0f;
+            k += KSTEP; fb += KSTEP;
+            while (fb >= kw) { fb -= kw; ++fa; }
+            while (fa >= kh) { fa -= kh; ++co; }
+        }
+    }
+
+    __device__ __forceinline__ void store(float *buf) const
+    {
+#pragma unroll
+        for (int e = 0; e < NE; ++e) buf[(ksub + e * KSTEP) * LD + pcol] = st[e];
+    }
+};
+
 // Convolution weight gradient, A operand: rows = co, contraction q = (r, pix);
 // element = dtilde[r][co][pix].
 template <int ROWS, int BK, int NT, int LD>
@@ -668,6 +721,23 @@ dk_status run_conv_fwd(const dk_geom &g, const float *W, const float *xbar, floa
                                       part_bytes, st, "contract_conv_fwd_gather");
 }
 
+// dx[r][ci][pix] = sum_k Wt[ci][k] * gathered delta, k = (co, a, b); Wt is the
+// filter bank regrouped as [ci][co][a][b].
+template <class C, bool VW>
+dk_status run_conv_dgrad(const dk_geom &g, const float *Wt, const float *delta, float *dx, long long R,
+                         float *part, size_t part_bytes, hipStream_t st)
+{
+    using LA = LoadRowMajorK<C::BM, C::BK, C::NT, C::LDA, VW>;
+    using LB = LoadIm2colDgrad<C::BN, C::BK, C::NT, C::LDB>;
+    ConvParams cp = conv_params(g, delta, R);
+    const int HW = g.H * g.W, Kd = g.Co * g.kh * g.kw;
+    cp.Q = (int)(R * HW);
+    MatParams pa = {Wt, Kd, g.Ci, Kd};
+    EpiConvFwd ep = {g.Ci, cp.Q, HW, (long long)g.Ci * HW};
+    return run<C, LA, LB, EpiConvFwd>(pa, cp, ep, g.Ci, cp.Q, Kd, 1.0f, 0, dx, R * g.n, part, part_bytes,
+                                      st, "contract_conv_dgrad_gather");
+}
+
 template <class C>
 dk_status run_conv_wgrad(const dk_geom &g, const float *dtilde, const float *xbar, float *dW,
                          long long R, float alpha, int accumulate, float *part, size_t part_bytes,
@@ -895,9 +965,9 @@ DK_EXPORT dk_status dk_wgrad_m(const dk_layer *L, const float *delta, const floa
 // ---------------------------------------------------------------------------
 namespace {
 
-// Wt[ci][co][a][b] = W[co][ci][kh-1-a][kw-1-b]
+// Wt[ci][co][a][b] = W[co][ci][kh-1-a][kw-1-b] (flip) or W[co][ci][a][b]
 __global__ __launch_bounds__(256) void dgrad_filter_kernel(const float *__restrict__ W, float *__restrict__ Wt,
-                                                           int Co, int Ci, int kh, int kw)
+                                                           int Co, int Ci, int kh, int kw, int flip)
 {
     const int e = blockIdx.x * 256 + threadIdx.x;
     if (e >= Co * Ci * kh * kw) return;
@@ -907,7 +977,8 @@ __global__ __launch_bounds__(256) void dgrad_filter_kernel(const float *__restri
     const int co = rem / khw;
     rem -= co * khw;
     const int a = rem / kw, b = rem - a * kw;
-    Wt[e] = W[((long long)(co * Ci + ci) * kh + (kh - 1 - a)) * kw + (kw - 1 - b)];
+    Wt[e] = flip ? W[((long long)(co * Ci + ci) * kh + (kh - 1 - a)) * kw + (kw - 1 - b)]
+                 : W[((long long)(co * Ci + ci) * kh + a) * kw + b];
 }
 
 // Any geometry, one thread per input element:
@@ -947,6 +1018,8 @@ __global__ __launch_bounds__(256) void conv_dgrad_direct_kernel(const float *__r
     dx[idx] = acc;
 }
 
+bool conv_flat_dgrad(const dk_geom &g) { return g.Ci <= 64; }
+
 // stride 1 with pad <= k-1 and a square filter: a forward convolution of delta
 bool dgrad_as_forward(const dk_geom &g, dk_geom *t)
 {
@@ -971,9 +1044,14 @@ DK_EXPORT size_t dk_dgrad_workspace_bytes(const dk_layer *L, int R)
         d.M = g.N; d.N = g.M; d.n = g.M; d.m = g.N;          // C[R][N] over k = M
         return dk_ws_fwd_bytes(d, R);
     }
-    if (dgrad_as_forward(g, &t))
-        return align_up((size_t)g.Co * g.Ci * g.kh * g.kw * sizeof(float), 256) + dk_ws_fwd_bytes(t, R);
-    return 256;
+    const size_t wt = align_up((size_t)g.Co * g.Ci * g.kh * g.kw * sizeof(float), 256);
+    if (g.dw) return 256;
+    if (dgrad_as_forward(g, &t)) return wt + dk_ws_fwd_bytes(t, R);
+    // gather engine: C[Ci][R*H*W] over k = Co*kh*kw
+    const long long Kd = (long long)g.Co * g.kh * g.kw;
+    const size_t part = conv_flat_dgrad(g) ? split_bytes<CfgFlat>(g.Ci, (long long)R * g.H * g.W, Kd, R * g.n)
+                                           : split_bytes<CfgSq>(g.Ci, (long long)R * g.H * g.W, Kd, R * g.n);
+    return wt + (part < 256 ? 256 : part);
 }
 
 DK_EXPORT dk_status dk_dgrad(const dk_layer *L, const float *W, const float *delta, float *dx, int R,
@@ -1002,10 +1080,29 @@ DK_EXPORT dk_status dk_dgrad(const dk_layer *L, const float *W, const float *del
         const int count = g.Co * g.Ci * g.kh * g.kw;
         {
             dk_prof_scope ps("dgrad_filter", st);
-            dgrad_filter_kernel<<<dim3((count + 255) / 256), dim3(256), 0, st>>>(W, Wt, g.Co, g.Ci, g.kh, g.kw);
+            dgrad_filter_kernel<<<dim3((count + 255) / 256), dim3(256), 0, st>>>(W, Wt, g.Co, g.Ci, g.kh, g.kw, 1);
         }
         DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
         return conv_fwd_impl(t, Wt, delta, dx, R, (char *)ws + wt_bytes, ws_bytes - wt_bytes, stream);
+    }
+    if ((long long)R * g.H * g.W < (1ll << 31) - 512) {
+        // any other geometry: gather loader on the generic contraction engine
+        float *Wt = (float *)ws;
+        const size_t wt_bytes = align_up((size_t)g.Co * g.Ci * g.kh * g.kw * sizeof(float), 256);
+        const int count = g.Co * g.Ci * g.kh * g.kw;
+        {
+            dk_prof_scope ps("dgrad_filter", st);
+            dgrad_filter_kernel<<<dim3((count + 255) / 256), dim3(256), 0, st>>>(W, Wt, g.Co, g.Ci, g.kh, g.kw, 0);
+        }
+        DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+        float *part = (float *)((char *)ws + wt_bytes);
+        const size_t part_bytes = ws_bytes - wt_bytes;
+        const bool vw = ((g.Co * g.kh * g.kw) % 4 == 0);
+        if (conv_flat_dgrad(g))
+            return vw ? run_conv_dgrad<CfgFlat, true>(g, Wt, delta, dx, R, part, part_bytes, st)
+                      : run_conv_dgrad<CfgFlat, false>(g, Wt, delta, dx, R, part, part_bytes, st);
+        return vw ? run_conv_dgrad<CfgSq, true>(g, Wt, delta, dx, R, part, part_bytes, st)
+                  : run_conv_dgrad<CfgSq, false>(g, Wt, delta, dx, R, part, part_bytes, st);
     }
     const long long total = (long long)R * g.n;
     DK_REQUIRE((total + 255) / 256 <= 0x7fffffffll, DK_ERR_SHAPE);
