@@ -47,6 +47,8 @@ struct fgemm_params {
     long long a_plane, b_plane;   // bytes per plane
     int I, J, Kp;
     int tiles_i, tiles_j, splits, ktiles_per_split, ktiles;
+    // implicit convolution operand (B read from channels-last digit planes [R][H][W][cp])
+    int cp, cH, cW, ckh, ckw, cstride, cpad, cWo, cHoWo;
     int out_hw;            // 0: C[i][j] at i*J + j;  hw > 0: j = (image, pixel), C at ((image*I + i)*hw + pixel
     double s_inv;          // 2^-l for out_f
     float scale;
@@ -249,6 +251,77 @@ __global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__re
     raise_flag(flag, hi != 0);
 }
 
+// Encodings xbar[R][Ci][H*W] -> channels-last digit planes [4][R][H*W][cp]
+// (cp = Ci, a multiple of 16): per image a tile of 128 channels x 64 pixels goes
+// through LDS as packed digits; a thread then writes 16 consecutive channels of
+// one pixel to each plane.
+__global__ __launch_bounds__(256) void f_digits_nhwc_kernel(const uint32_t *__restrict__ src,
+                                                            int8_t *__restrict__ planes, int Ci, int HW,
+                                                            int cp, long long plane, int *flag)
+{
+    __shared__ uint32_t tile[128][65];
+    const int c0 = blockIdx.x * 64, k0 = blockIdx.y * 128, img = blockIdx.z;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const uint32_t *s = src + (long long)img * Ci * HW;
+#pragma unroll 8
+    for (int r = 0; r < 32; ++r) {
+        const int k = k0 + ty + 4 * r, c = c0 + tx;
+        tile[ty + 4 * r][tx] = (k < Ci && c < HW) ? digits_of(s[(long long)k * HW + c]) : 0u;
+    }
+    __syncthreads();
+    uint32_t hi = 0;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int item = threadIdx.x + 256 * r;       // (pixel, 16 channels)
+        const int kq = item & 7, col = item >> 3;
+        if (c0 + col >= HW || k0 + 16 * kq >= cp) continue;
+        u32x4 w[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            uint32_t d[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) d[c] = tile[16 * kq + 4 * g + c][col];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) w[a][g] = gather_byte(d, a);
+        }
+        hi |= w[2].x | w[2].y | w[2].z | w[2].w | w[3].x | w[3].y | w[3].z | w[3].w;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+            *reinterpret_cast<u32x4 *>(planes + a * plane + ((long long)img * HW + c0 + col) * cp + k0 + 16 * kq) = w[a];
+    }
+    raise_flag(flag, hi != 0);
+}
+
+// Filters W[Co][Ci][kh*kw] -> digit planes [4][rows_pad][Kp] with the
+// contraction index ordered k = tap * cp + ci (to match the channels-last
+// operand); rows beyond Co and k beyond kh*kw*cp are zeros.
+__global__ __launch_bounds__(256) void f_digits_wconv_kernel(const uint32_t *__restrict__ W,
+                                                             int8_t *__restrict__ planes, int Co, int Ci,
+                                                             int taps, int cp, int rows_pad, int Kp,
+                                                             int chunks, int *flag)
+{
+    const int row = blockIdx.x / chunks;
+    const int k0 = ((blockIdx.x - row * chunks) * 256 + threadIdx.x) * 4;
+    if (k0 >= Kp) return;
+    uint32_t d[4] = {0, 0, 0, 0};
+    if (row < Co) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int k = k0 + c, tap = k / cp, ci = k - tap * cp;
+            if (tap < taps && ci < Ci) d[c] = digits_of(W[((long long)row * Ci + ci) * taps + tap]);
+        }
+    }
+    const long long plane = (long long)rows_pad * Kp;
+    uint32_t hi = 0;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const uint32_t w = gather_byte(d, a);
+        if (a >= 2) hi |= w;
+        *reinterpret_cast<uint32_t *>(planes + a * plane + (long long)row * Kp + k0) = w;
+    }
+    raise_flag(flag, hi != 0);
+}
+
 __global__ void f_flag_clear_kernel(int *flags) { if (threadIdx.x < 2) flags[threadIdx.x] = 0; }
 
 // |v| < 2^62 -> v mod p in [0, p)
@@ -267,6 +340,11 @@ __device__ __forceinline__ uint32_t reduce_signed(long long v)
 // the current one is multiplied out of LDS (two LDS buffers, one barrier per
 // tile); the operands of the next 32-k step are read from LDS while the MFMAs
 // of the current one run.
+// IMPL: the B operand of a convolution forward is not a stored matrix: row
+// j = (image, oh, ow) and k = (a, b, ci) address the channels-last digit planes
+// of the encodings directly (16 consecutive channels per piece, zeros outside
+// the image), so no patch matrix exists in memory.
+template <bool IMPL>
 __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 {
     extern __shared__ __attribute__((aligned(16))) int8_t flds[];
@@ -294,6 +372,24 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     const long long q_rows = 32ll * p.Kp;
     const unsigned s_off = (unsigned)srow * (unsigned)p.Kp + 16u * spiece;
     const int s_dst = srow * PITCH + 16 * spiece;
+
+    // implicit operand: what this thread's four rows fix
+    unsigned r_base[4];
+    int r_ih[4], r_iw[4];
+    bool r_ok[4];
+    if (IMPL) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int j = tj * BJ + srow + 32 * q;
+            r_ok[q] = j < p.J;
+            const int img = r_ok[q] ? j / p.cHoWo : 0;
+            const int px = r_ok[q] ? j - img * p.cHoWo : 0;
+            const int oh = px / p.cWo, ow = px - oh * p.cWo;
+            r_ih[q] = oh * p.cstride - p.cpad;
+            r_iw[q] = ow * p.cstride - p.cpad;
+            r_base[q] = (unsigned)img * (unsigned)(p.cH * p.cW) * (unsigned)p.cp;
+        }
+    }
 
     const int wi0 = (wave & 1) * 64, wj0 = (wave >> 1) * 64;
     const int a_rd = (wi0 + li) * PITCH + 16 * lh;
@@ -335,8 +431,26 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         const int8_t *bs_ = p.Bp + 2 * (q_ >> 1) * p.b_plane + ((long long)tj * BJ * p.Kp + (long long)(KTILE) * KT); \
         _Pragma("unroll") for (int e = 0; e < 8; ++e)                                             \
             sa[e] = *reinterpret_cast<const i32x4 *>((as_ + ((e >> 2) * p.a_plane + (e & 3) * q_rows)) + s_off); \
-        _Pragma("unroll") for (int e = 0; e < 8; ++e)                                             \
-            sb[e] = *reinterpret_cast<const i32x4 *>((bs_ + ((e >> 2) * p.b_plane + (e & 3) * q_rows)) + s_off); \
+        if (!IMPL) {                                                                              \
+            _Pragma("unroll") for (int e = 0; e < 8; ++e)                                         \
+                sb[e] = *reinterpret_cast<const i32x4 *>((bs_ + ((e >> 2) * p.b_plane + (e & 3) * q_rows)) + s_off); \
+        } else {                                                                                  \
+            const int k0_ = (KTILE) * KT + 16 * spiece;                                           \
+            const int tap_ = k0_ / p.cp, ci0_ = k0_ - tap_ * p.cp;                                \
+            const int fa_ = tap_ / p.ckw, fb_ = tap_ - fa_ * p.ckw;                               \
+            const bool tap_ok_ = tap_ < p.ckh * p.ckw;                                            \
+            const int8_t *bp_ = p.Bp + 2 * (q_ >> 1) * p.b_plane + ci0_;                          \
+            _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                       \
+                const int ih_ = r_ih[q] + fa_, iw_ = r_iw[q] + fb_;                               \
+                const bool ok_ = tap_ok_ && r_ok[q] && ih_ >= 0 && ih_ < p.cH && iw_ >= 0 && iw_ < p.cW; \
+                const unsigned off_ = r_base[q] + (unsigned)(ih_ * p.cW + iw_) * (unsigned)p.cp;  \
+                _Pragma("unroll") for (int pl = 0; pl < 2; ++pl) {                                \
+                    i32x4 v_ = {0, 0, 0, 0};                                                      \
+                    if (ok_) v_ = *reinterpret_cast<const i32x4 *>(bp_ + pl * p.b_plane + off_);  \
+                    sb[pl * 4 + q] = v_;                                                          \
+                }                                                                                 \
+            }                                                                                     \
+        }                                                                                         \
     }
 #define DKF_STASH(BUF)                                                                            \
     {                                                                                             \
@@ -596,11 +710,15 @@ constexpr size_t FLAG_BYTES = 256;
 // kernel finishes.
 dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, uint32_t *part,
                     const int *flags, uint32_t *out_q, float *out_f, int l, float scale,
-                    int accumulate, int out_hw, const char *label, hipStream_t st)
+                    int accumulate, int out_hw, const char *label, hipStream_t st,
+                    const fconv_geom *impl = nullptr, long long impl_plane = 0)
 {
     static bool allowed = false;
     if (!allowed) {
-        DK_REQUIRE(hipFuncSetAttribute(reinterpret_cast<const void *>(f_gemm_kernel),
+        DK_REQUIRE(hipFuncSetAttribute(reinterpret_cast<const void *>(f_gemm_kernel<false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) == hipSuccess,
+                   DK_ERR_HIP);
+        DK_REQUIRE(hipFuncSetAttribute(reinterpret_cast<const void *>(f_gemm_kernel<true>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) == hipSuccess,
                    DK_ERR_HIP);
         allowed = true;
@@ -617,11 +735,20 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
     p.ktiles_per_split = pl.ktiles_per_split; p.ktiles = pl.ktiles;
     p.s_inv = ldexp(1.0, -l); p.scale = scale; p.accumulate = accumulate;
     p.out_hw = direct ? out_hw : 0;
+    p.cp = p.cH = p.cW = p.ckh = p.ckw = p.cstride = p.cpad = p.cWo = p.cHoWo = 0;
+    if (impl) {
+        p.cp = impl->Ci; p.cH = impl->H; p.cW = impl->W; p.ckh = impl->kh; p.ckw = impl->kw;
+        p.cstride = impl->stride; p.cpad = impl->pad; p.cWo = impl->Wo; p.cHoWo = impl->HoWo;
+        p.b_plane = impl_plane;
+    }
     const long long blocks = (long long)pl.splits * pl.tiles_i * pl.tiles_j;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     {
         dk_prof_scope ps(label, st);
-        f_gemm_kernel<<<dim3((unsigned)blocks), dim3(256), LDS_BYTES, st>>>(p);
+        if (impl)
+            f_gemm_kernel<true><<<dim3((unsigned)blocks), dim3(256), LDS_BYTES, st>>>(p);
+        else
+            f_gemm_kernel<false><<<dim3((unsigned)blocks), dim3(256), LDS_BYTES, st>>>(p);
     }
     if (direct) return dk_launch_status();
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
@@ -679,9 +806,19 @@ fconv_geom conv_geom_of(const dk_geom &g)
 // Convolution forward as C[co][(r, pixel)] = W[co][(ci,a,b)] . patches: I = Co,
 // J = R*Ho*Wo, K = Ci*kh*kw.  Weight gradient as C[co][(ci,a,b)] over
 // k = (r, pixel): I = Co, J = Ci*kh*kw, K = R*Ho*Wo.
+// Channel counts that are multiples of 16 take the implicit operand (16-byte
+// pieces of the contraction never straddle two filter taps; offsets fit 32 bits).
+bool conv_implicit(const dk_geom &g, long long R)
+{
+    return g.Ci % 16 == 0 && R * g.H * g.W * g.Ci < (1ll << 31);
+}
+
 bool plan_conv_fwd(const dk_geom &g, long long R, fgemm_plan *pl)
 {
-    return plan_fgemm(g.Co, R * g.Ho * g.Wo, g.Kg, pl);
+    if (!plan_fgemm(g.Co, R * g.Ho * g.Wo, g.Kg, pl)) return false;
+    if (conv_implicit(g, R))        // the B operand is the channels-last planes, not a patch matrix
+        pl->b_bytes = align256((size_t)4 * R * g.H * g.W * g.Ci);
+    return true;
 }
 bool plan_conv_wgrad(const dk_geom &g, long long R, fgemm_plan *pl)
 {
@@ -726,6 +863,27 @@ DK_EXPORT dk_status dkf_conv_fwd(const dk_layer *L, const uint32_t *Wq, const ui
         f_flag_clear_kernel<<<dim3(1), dim3(64), 0, st>>>(flag);
     }
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+    if (conv_implicit(g, R)) {
+        const int taps = g.kh * g.kw, HW = g.H * g.W;
+        const int chunks = (pl.Kp / 4 + 255) / 256;
+        {
+            dk_prof_scope ps("f_digits_w", st);
+            f_digits_wconv_kernel<<<dim3((unsigned)(pl.I_pad * chunks)), dim3(256), 0, st>>>(
+                Wq, Ap, g.Co, g.Ci, taps, g.Ci, pl.I_pad, pl.Kp, chunks, flag);
+        }
+        DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+        const long long plane = (long long)R * HW * g.Ci;
+        DK_REQUIRE(R <= 65535 && (g.Ci + 127) / 128 <= 65535, DK_ERR_SHAPE);
+        {
+            dk_prof_scope ps("f_digits_nhwc", st);
+            f_digits_nhwc_kernel<<<dim3((HW + 63) / 64, (g.Ci + 127) / 128, R), dim3(256), 0, st>>>(
+                xbar, Bp, g.Ci, HW, g.Ci, plane, flag + 1);
+        }
+        DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+        const fconv_geom cg = conv_geom_of(g);
+        return run_fgemm(pl, Ap, Bp, part, flag, ybar, nullptr, 0, 1.0f, 0, g.Ho * g.Wo, "f_gemm_fwd", st,
+                         &cg, plane);
+    }
     dk_status s = run_digits(Wq, Ap, g.Co, (int)g.Kg, pl.I_pad, pl.Kp, flag, st);
     if (s != DK_OK) return s;
     {
