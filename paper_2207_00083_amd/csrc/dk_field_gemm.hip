@@ -32,9 +32,8 @@ namespace {
 constexpr int BI = 128, BJ = 128;      // workgroup tile
 constexpr int KT = 128;                // k bytes per LDS tile
 constexpr int PITCH = 144;             // LDS row pitch in bytes: 16 (mod 32) keeps 16-byte reads conflict-free
-constexpr int A_PLANE = BI * PITCH, B_PLANE = BJ * PITCH;
-constexpr int BUF_BYTES = 2 * A_PLANE + 2 * B_PLANE;     // 73728
-constexpr int LDS_BYTES = 2 * BUF_BYTES;                  // 147456
+constexpr int B_PLANE = BJ * PITCH;
+constexpr int LDS_BYTES = 2 * (2 * BI * PITCH + 2 * B_PLANE);   // 147456: two buffers of the 128-row tile
 constexpr int MAX_KSPLIT = 1 << 17;    // k values per slice (int32 accumulators)
 constexpr int MAX_SPLITS = 256;        // k slices per output tile (the fold adds their residues in 64 bits)
 
@@ -344,9 +343,13 @@ __device__ __forceinline__ uint32_t reduce_signed(long long v)
 // j = (image, oh, ow) and k = (a, b, ci) address the channels-last digit planes
 // of the encodings directly (16 consecutive channels per piece, zeros outside
 // the image), so no patch matrix exists in memory.
-template <bool IMPL>
+// NBI: 32-row blocks of A per wave; the workgroup tile is (64 NBI) x 128 (a
+// 64-row tile keeps operands with at most 64 rows from wasting half the MFMAs).
+template <bool IMPL, int NBI>
 __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 {
+    constexpr int BI = 64 * NBI, A_PLANE = BI * PITCH, BUF_BYTES = 2 * A_PLANE + 2 * B_PLANE;
+    constexpr int NA = 4 * NBI;          // 16-byte pieces of A per thread and tile
     extern __shared__ __attribute__((aligned(16))) int8_t flds[];
 
     const int tid = threadIdx.x;
@@ -391,21 +394,21 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         }
     }
 
-    const int wi0 = (wave & 1) * 64, wj0 = (wave >> 1) * 64;
+    const int wi0 = (wave & 1) * 32 * NBI, wj0 = (wave >> 1) * 64;
     const int a_rd = (wi0 + li) * PITCH + 16 * lh;
     const int b_rd = 2 * A_PLANE + (wj0 + li) * PITCH + 16 * lh;
 
-    uint32_t res[2][2][16];
+    uint32_t res[NBI][2][16];
 #pragma unroll
-    for (int bi = 0; bi < 2; ++bi)
+    for (int bi = 0; bi < NBI; ++bi)
 #pragma unroll
         for (int bj = 0; bj < 2; ++bj)
 #pragma unroll
             for (int v = 0; v < 16; ++v) res[bi][bj][v] = 0;
 
-    i32x16 acc[2][2][3];
+    i32x16 acc[NBI][2][3];
 #pragma unroll
-    for (int bi = 0; bi < 2; ++bi)
+    for (int bi = 0; bi < NBI; ++bi)
 #pragma unroll
         for (int bj = 0; bj < 2; ++bj)
 #pragma unroll
@@ -423,14 +426,14 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 #define DKF_PART(I) ((plist >> (2 * (I))) & 3)
     const int nsteps = nparts * (kt1 - kt0);
 
-    i32x4 sa[8], sb[8];
+    i32x4 sa[NA], sb[8];
 #define DKF_FETCH(PI, KTILE)                                                                      \
     {                                                                                             \
         const int q_ = DKF_PART(PI);                                                              \
         const int8_t *as_ = p.Ap + 2 * (q_ & 1) * p.a_plane + ((long long)ti * BI * p.Kp + (long long)(KTILE) * KT); \
         const int8_t *bs_ = p.Bp + 2 * (q_ >> 1) * p.b_plane + ((long long)tj * BJ * p.Kp + (long long)(KTILE) * KT); \
-        _Pragma("unroll") for (int e = 0; e < 8; ++e)                                             \
-            sa[e] = *reinterpret_cast<const i32x4 *>((as_ + ((e >> 2) * p.a_plane + (e & 3) * q_rows)) + s_off); \
+        _Pragma("unroll") for (int e = 0; e < NA; ++e)                                            \
+            sa[e] = *reinterpret_cast<const i32x4 *>((as_ + ((e / (2 * NBI)) * p.a_plane + (e % (2 * NBI)) * q_rows)) + s_off); \
         if (!IMPL) {                                                                              \
             _Pragma("unroll") for (int e = 0; e < 8; ++e)                                         \
                 sb[e] = *reinterpret_cast<const i32x4 *>((bs_ + ((e >> 2) * p.b_plane + (e & 3) * q_rows)) + s_off); \
@@ -454,21 +457,21 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     }
 #define DKF_STASH(BUF)                                                                            \
     {                                                                                             \
-        _Pragma("unroll") for (int e = 0; e < 8; ++e)                                             \
-            *reinterpret_cast<i32x4 *>((BUF) + (e >> 2) * A_PLANE + (e & 3) * 32 * PITCH + s_dst) = sa[e]; \
+        _Pragma("unroll") for (int e = 0; e < NA; ++e)                                            \
+            *reinterpret_cast<i32x4 *>((BUF) + (e / (2 * NBI)) * A_PLANE + (e % (2 * NBI)) * 32 * PITCH + s_dst) = sa[e]; \
         _Pragma("unroll") for (int e = 0; e < 8; ++e)                                             \
             *reinterpret_cast<i32x4 *>((BUF) + 2 * A_PLANE + (e >> 2) * B_PLANE + (e & 3) * 32 * PITCH + s_dst) = sb[e]; \
     }
     // in the order the MFMAs of a step consume them: A and B planes 0 first
 #define DKF_READ(A, B, KS)                                                                        \
     {                                                                                             \
-        _Pragma("unroll") for (int bi = 0; bi < 2; ++bi)                                          \
+        _Pragma("unroll") for (int bi = 0; bi < NBI; ++bi)                                          \
             A[bi][0] = *reinterpret_cast<const i32x4 *>(cur + a_rd + bi * 32 * PITCH + (KS) * 32); \
         _Pragma("unroll") for (int bj = 0; bj < 2; ++bj)                                          \
             B[bj][0] = *reinterpret_cast<const i32x4 *>(cur + b_rd + bj * 32 * PITCH + (KS) * 32); \
         _Pragma("unroll") for (int bj = 0; bj < 2; ++bj)                                          \
             B[bj][1] = *reinterpret_cast<const i32x4 *>(cur + B_PLANE + b_rd + bj * 32 * PITCH + (KS) * 32); \
-        _Pragma("unroll") for (int bi = 0; bi < 2; ++bi)                                          \
+        _Pragma("unroll") for (int bi = 0; bi < NBI; ++bi)                                          \
             A[bi][1] = *reinterpret_cast<const i32x4 *>(cur + A_PLANE + a_rd + bi * 32 * PITCH + (KS) * 32); \
     }
     // digit pairs outermost: four independent accumulators lie between two
@@ -477,20 +480,20 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     {                                                                                             \
         _Pragma("unroll") for (int pa = 0; pa < 2; ++pa)                                          \
             _Pragma("unroll") for (int pb = 0; pb < 2; ++pb)                                      \
-                _Pragma("unroll") for (int bi = 0; bi < 2; ++bi)                                  \
+                _Pragma("unroll") for (int bi = 0; bi < NBI; ++bi)                                  \
                     _Pragma("unroll") for (int bj = 0; bj < 2; ++bj)                              \
                         acc[bi][bj][pa + pb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(             \
                             A[bi][pa], B[bj][pb], acc[bi][bj][pa + pb], 0, 0, 0);                 \
     }
-    // eight times one MFMA and one LDS read, then the other eight MFMAs: the
-    // reads have half a step to come back
+    // one MFMA and one LDS read per operand piece of the next sub-step (2 NBI + 4
+    // of them), then the remaining MFMAs: the reads have time to come back
 #define DKF_PACE_READS()                                                                          \
     {                                                                                             \
-        _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                           \
+        _Pragma("unroll") for (int e = 0; e < 2 * NBI + 4; ++e) {                                 \
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    \
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                    \
         }                                                                                         \
-        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                        \
+        __builtin_amdgcn_sched_group_barrier(0x008, 8 * NBI - (2 * NBI + 4), 0);                  \
         __builtin_amdgcn_sched_barrier(0);                                                        \
     }
     // keep consumed operand registers live up to here, so that a read issued
@@ -499,7 +502,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     {                                                                                             \
         _Pragma("unroll") for (int x = 0; x < 2; ++x)                                             \
             _Pragma("unroll") for (int y = 0; y < 2; ++y) {                                       \
-                asm volatile("" ::"v"(A[x][y]));                                                  \
+                if (x < NBI) asm volatile("" ::"v"(A[x][y]));                                     \
                 asm volatile("" ::"v"(B[x][y]));                                                  \
             }                                                                                     \
     }
@@ -538,7 +541,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
             // Four 32-k sub-steps.  The operands of step s+1 are read from LDS while
             // the 16 MFMAs of step s issue (one read per two MFMAs); the LDS
             // writes of the next tile go between the MFMAs of the last step.
-            i32x4 a0[2][2], b0[2][2], a1[2][2], b1[2][2];
+            i32x4 a0[NBI][2], b0[2][2], a1[NBI][2], b1[2][2];
             DKF_READ(a0, b0, 0)
             __builtin_amdgcn_sched_barrier(0);
             DKF_READ(a1, b1, 1)
@@ -557,7 +560,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
             // (after the last step this stores stale registers to the idle buffer)
             DKF_STASH(nxt)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
+            for (int e = 0; e < 8 * NBI; ++e) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
                 __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
             }
@@ -575,7 +578,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         const int c1 = (int)dkf_reduce(1ull << (14 * w + 7));
         const int c2 = (int)dkf_reduce(1ull << (14 * w + 14));
 #pragma unroll
-        for (int bi = 0; bi < 2; ++bi)
+        for (int bi = 0; bi < NBI; ++bi)
 #pragma unroll
             for (int bj = 0; bj < 2; ++bj) {
                 __builtin_amdgcn_sched_barrier(0);     // one block at a time: short live ranges
@@ -605,7 +608,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 
     uint32_t *dst_q = p.out_q ? p.out_q + (long long)split * p.I * p.J : nullptr;   // (one slice if remapped)
 #pragma unroll
-    for (int bi = 0; bi < 2; ++bi)
+    for (int bi = 0; bi < NBI; ++bi)
 #pragma unroll
         for (int bj = 0; bj < 2; ++bj) {
             const int j = tj * BJ + wj0 + bj * 32 + li;
@@ -661,6 +664,7 @@ inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 struct fgemm_plan {
     int I, J, K, I_pad, J_pad, Kp;
     int tiles_i, tiles_j, ktiles, splits, ktiles_per_split;
+    int nbi;              // 1: 64-row tiles, 2: 128-row tiles
     size_t a_bytes, b_bytes, part_bytes;
 };
 
@@ -669,10 +673,11 @@ bool plan_fgemm(long long I, long long J, long long K, fgemm_plan *pl)
 {
     if (I < 1 || J < 1 || K < 1 || I > (1 << 24) || J > (1 << 24) || K > (1 << 26)) return false;
     pl->I = (int)I; pl->J = (int)J; pl->K = (int)K;
-    pl->I_pad = round_up((int)I, BI);
+    pl->nbi = (I % 128 != 0 && I % 128 <= 64) ? 1 : 2;      // a last half-empty 128-row tile: use 64-row tiles
+    pl->I_pad = round_up((int)I, 64 * pl->nbi);
     pl->J_pad = round_up((int)J, BJ);
     pl->Kp = round_up((int)K, KT);
-    pl->tiles_i = pl->I_pad / BI;
+    pl->tiles_i = pl->I_pad / (64 * pl->nbi);
     pl->tiles_j = pl->J_pad / BJ;
     pl->ktiles = pl->Kp / KT;
     const long long tiles = (long long)pl->tiles_i * pl->tiles_j;
@@ -715,12 +720,13 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
 {
     static bool allowed = false;
     if (!allowed) {
-        DK_REQUIRE(hipFuncSetAttribute(reinterpret_cast<const void *>(f_gemm_kernel<false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) == hipSuccess,
-                   DK_ERR_HIP);
-        DK_REQUIRE(hipFuncSetAttribute(reinterpret_cast<const void *>(f_gemm_kernel<true>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) == hipSuccess,
-                   DK_ERR_HIP);
+        const void *kernels[4] = {reinterpret_cast<const void *>(f_gemm_kernel<false, 1>),
+                                  reinterpret_cast<const void *>(f_gemm_kernel<false, 2>),
+                                  reinterpret_cast<const void *>(f_gemm_kernel<true, 1>),
+                                  reinterpret_cast<const void *>(f_gemm_kernel<true, 2>)};
+        for (const void *kf : kernels)
+            DK_REQUIRE(hipFuncSetAttribute(kf, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) == hipSuccess,
+                       DK_ERR_HIP);
         allowed = true;
     }
     const bool direct = pl.splits == 1;
@@ -745,10 +751,11 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     {
         dk_prof_scope ps(label, st);
-        if (impl)
-            f_gemm_kernel<true><<<dim3((unsigned)blocks), dim3(256), LDS_BYTES, st>>>(p);
-        else
-            f_gemm_kernel<false><<<dim3((unsigned)blocks), dim3(256), LDS_BYTES, st>>>(p);
+        const dim3 grid((unsigned)blocks), block(256);
+        if (impl && pl.nbi == 1) f_gemm_kernel<true, 1><<<grid, block, LDS_BYTES, st>>>(p);
+        else if (impl)           f_gemm_kernel<true, 2><<<grid, block, LDS_BYTES, st>>>(p);
+        else if (pl.nbi == 1)    f_gemm_kernel<false, 1><<<grid, block, LDS_BYTES, st>>>(p);
+        else                     f_gemm_kernel<false, 2><<<grid, block, LDS_BYTES, st>>>(p);
     }
     if (direct) return dk_launch_status();
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
