@@ -28,6 +28,8 @@ struct Cfg {
     static constexpr int LDA = BM + 4;               // LDS row pitch (floats)
     static constexpr int LDB = BN + 4;
     static constexpr int LDS_FLOATS = 2 * BK * (LDA + LDB);
+    // one contraction step of a wave: TM*TN MFMAs of 64 cycles per k pair, at about 2.1 GHz
+    static constexpr double STEP_US = TM * TN * (BK / 2) * 64 / 2100.0;
     static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 4 == 0, "tile shape");
 };
 
@@ -588,21 +590,107 @@ __global__ __launch_bounds__(C::NT) void contract_kernel(typename LA::Params pa,
     }
 }
 
-// out[i] = (accumulate ? out[i] : 0) + alpha * sum_s part[s][i], slices added
-// in index order so that reruns are bitwise identical.
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part,
-                                                            float *__restrict__ out,
-                                                            long long out_elems, int splits,
-                                                            float alpha, int accumulate)
+// out[i] = (accumulate ? out[i] : 0) + alpha * sum_s part[s][i].  The order of
+// the additions depends only on (splits, kernel variant), so reruns are bitwise
+// identical.
+//
+// Few slices over a large output: one thread per 16 bytes of output walks the
+// slices (bandwidth-bound, every byte read once).
+template <bool VEC>
+__global__ __launch_bounds__(256) void fold_wide_kernel(const float *__restrict__ part,
+                                                        float *__restrict__ out, long long out_elems,
+                                                        int splits, float alpha, int accumulate)
 {
-    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long i = ((long long)blockIdx.x * 256 + threadIdx.x) * (VEC ? 4 : 1);
     if (i >= out_elems) return;
+    if constexpr (VEC) {
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        int k = 0;
+        for (; k + 4 <= splits; k += 4) {
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                v[u] = *reinterpret_cast<const float4 *>(part + (long long)(k + u) * out_elems + i);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+        }
+        for (; k < splits; ++k) {
+            const float4 v = *reinterpret_cast<const float4 *>(part + (long long)k * out_elems + i);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        s.x *= alpha; s.y *= alpha; s.z *= alpha; s.w *= alpha;
+        float4 *d = reinterpret_cast<float4 *>(out + i);
+        if (accumulate) { const float4 o = *d; s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w; }
+        *d = s;
+    } else {
+        float s = 0.0f;
+        for (int k = 0; k < splits; ++k) s += part[(long long)k * out_elems + i];
+        s *= alpha;
+        if (accumulate) s += out[i];
+        out[i] = s;
+    }
+}
+
+// Many slices over a small output: a workgroup folds 64 consecutive elements,
+// wave w of its SG waves sums slices w, w+SG, ... (loads batched eight deep)
+// and the SG sub-sums are added in wave order.
+template <int SG>
+__global__ __launch_bounds__(64 * SG) void fold_deep_kernel(const float *__restrict__ part,
+                                                            float *__restrict__ out, long long out_elems,
+                                                            int splits, float alpha, int accumulate)
+{
+    __shared__ float red[SG][64];
+    const int io = threadIdx.x & 63, sg = threadIdx.x >> 6;
+    const long long i = (long long)blockIdx.x * 64 + io;
     float s = 0.0f;
-    for (int k = 0; k < splits; ++k) s += part[(long long)k * out_elems + i];
+    if (i < out_elems) {
+        const float *src = part + i;
+        int k = sg;
+        for (; k + 7 * SG < splits; k += 8 * SG) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = src[(long long)(k + SG * u) * out_elems];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; k < splits; k += SG) s += src[(long long)k * out_elems];
+    }
+    red[sg][io] = s;
+    __syncthreads();
+    if (sg != 0 || i >= out_elems) return;
+    s = red[0][io];
+#pragma unroll
+    for (int w = 1; w < SG; ++w) s += red[w][io];
     s *= alpha;
     if (accumulate) s += out[i];
     out[i] = s;
 }
+
+} // namespace
+
+dk_status dk_fold_slices(const float *part, float *out, long long out_elems, int splits, float alpha,
+                         int accumulate, hipStream_t st)
+{
+    dk_prof_scope ps("splitk_reduce", st);
+    // enough 16-byte columns to fill the chip: stream them; else spread the
+    // slices of each column over the waves of a workgroup
+    const bool vec = out_elems % 4 == 0 && dk_aligned(part, 16) && dk_aligned(out, 16);
+    const long long cols = vec ? out_elems / 4 : out_elems;
+    if (cols >= 256 * 1024 || splits <= 4) {
+        const unsigned blocks = (unsigned)((cols + 255) / 256);
+        if (vec) fold_wide_kernel<true><<<dim3(blocks), dim3(256), 0, st>>>(part, out, out_elems, splits, alpha, accumulate);
+        else fold_wide_kernel<false><<<dim3(blocks), dim3(256), 0, st>>>(part, out, out_elems, splits, alpha, accumulate);
+    } else {
+        const unsigned blocks = (unsigned)((out_elems + 63) / 64);
+        if (splits >= 64 && blocks < 2048)
+            fold_deep_kernel<16><<<dim3(blocks), dim3(1024), 0, st>>>(part, out, out_elems, splits, alpha, accumulate);
+        else
+            fold_deep_kernel<4><<<dim3(blocks), dim3(256), 0, st>>>(part, out, out_elems, splits, alpha, accumulate);
+    }
+    return dk_launch_status();
+}
+
+namespace {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -617,7 +705,7 @@ dk_status run(const typename LA::Params &pa, const typename LB::Params &pb, cons
     rp.tiles_n = (cols + C::BN - 1) / C::BN;
     rp.ktiles = (int)((kdim + C::BK - 1) / C::BK);
     const long long tiles = (long long)rp.tiles_m * rp.tiles_n;
-    const dk_split_plan sp = dk_plan_split(tiles, rp.ktiles, out_elems);
+    const dk_split_plan sp = dk_plan_split(tiles, rp.ktiles, out_elems, C::STEP_US);
     rp.splits = sp.splits;
     rp.per_split = sp.ktiles_per_split;
     rp.alpha = alpha;
@@ -633,12 +721,7 @@ dk_status run(const typename LA::Params &pa, const typename LB::Params &pb, cons
         contract_kernel<C, LA, LB, EP><<<dim3((unsigned)(tiles * rp.splits)), dim3(C::NT), 0, st>>>(pa, pb, ep, rp);
     }
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
-    if (rp.splits > 1) {
-        dk_prof_scope ps("splitk_reduce", st);
-        splitk_reduce_kernel<<<dim3((unsigned)((out_elems + 255) / 256)), dim3(256), 0, st>>>(
-            part, out, out_elems, rp.splits, alpha, accumulate);
-        DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
-    }
+    if (rp.splits > 1) return dk_fold_slices(part, out, out_elems, rp.splits, alpha, accumulate, st);
     return DK_OK;
 }
 
@@ -647,7 +730,7 @@ size_t split_bytes(long long rows, long long cols, long long kdim, long long out
 {
     const long long tiles = ((rows + C::BM - 1) / C::BM) * ((cols + C::BN - 1) / C::BN);
     const long long ktiles = (kdim + C::BK - 1) / C::BK;
-    const dk_split_plan sp = dk_plan_split(tiles, ktiles, out_elems);
+    const dk_split_plan sp = dk_plan_split(tiles, ktiles, out_elems, C::STEP_US);
     return sp.splits > 1 ? (size_t)sp.splits * out_elems * sizeof(float) : 0;
 }
 

@@ -435,6 +435,8 @@ struct QuadCfg {
     static constexpr int bm = WM * TM * 32, bn = WN * 128, cb = 8;
     static constexpr int NT = 64 * WM * WN;
     static constexpr int MAXSLOT = 4;
+    // a chunk of 8 channels: 36 k pairs on TM x 4 accumulator blocks, 64 cycles each, ~2.1 GHz
+    static constexpr double STEP_US = TM * 4 * 36 * 64 / 2100.0;
 
     static dk_status launch(const dk_patch_params &p, size_t lds_bytes, hipStream_t st)
     {
@@ -454,6 +456,7 @@ struct PatchCfg {
     static constexpr int bm = BM, bn = BN, cb = CB, kh = KH, kw = KW;
     static constexpr int NT = 64 * WM * WN;
     static constexpr int MAXSLOT4 = 4, MAXSLOT1 = 12;
+    static constexpr double STEP_US = (BM / WM / 32) * (BN / WN / 32) * (CB / 2 * KH * KW) * 64 / 2100.0;
 
     static dk_status launch(const dk_patch_params &p, int vec, size_t lds_bytes, hipStream_t st)
     {
@@ -518,7 +521,7 @@ bool plan_cfg(const dk_geom &g, long long R, bool x_aligned16, dk_patch_plan *pl
     pl->lds_bytes = (size_t)(p.patch_floats + C::cb * C::kh * C::kw * (C::bm + 4)) * sizeof(float);
     if (pl->lds_bytes > 64 * 1024) return false;
     p.n_chunks = (g.Ci + C::cb - 1) / C::cb;
-    const dk_split_plan sp = dk_plan_split((long long)p.tiles_m * p.tiles_n, p.n_chunks, R * g.m);
+    const dk_split_plan sp = dk_plan_split((long long)p.tiles_m * p.tiles_n, p.n_chunks, R * g.m, C::STEP_US);
     p.splits = sp.splits;
     p.per_split = sp.ktiles_per_split;
     p.out_elems = R * g.m;
@@ -571,7 +574,7 @@ bool plan_quad(const dk_geom &g, long long R, dk_patch_plan *pl)
     pl->lds_bytes = (size_t)(p.patch_floats + C::bm * 76) * sizeof(float);
     if (pl->lds_bytes > 64 * 1024) return false;
     p.n_chunks = (g.Ci + C::cb - 1) / C::cb;
-    const dk_split_plan sp = dk_plan_split((long long)p.tiles_m * p.tiles_n, p.n_chunks, R * g.m);
+    const dk_split_plan sp = dk_plan_split((long long)p.tiles_m * p.tiles_n, p.n_chunks, R * g.m, C::STEP_US);
     p.splits = sp.splits;
     p.per_split = sp.ktiles_per_split;
     p.out_elems = R * g.m;
@@ -597,17 +600,6 @@ bool dk_patch_fwd_plan(const dk_geom &g, long long R, bool aligned16, dk_patch_p
         return pl->flat ? plan_cfg<P3Flat>(g, R, aligned16, pl) : plan_cfg<P3Sq>(g, R, aligned16, pl);
     }
     return false;
-}
-
-__global__ __launch_bounds__(256) void dk_patch_splitk_reduce(const float *__restrict__ part,
-                                                              float *__restrict__ out,
-                                                              long long out_elems, int splits)
-{
-    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= out_elems) return;
-    float s = 0.0f;
-    for (int k = 0; k < splits; ++k) s += part[(long long)k * out_elems + i];
-    out[i] = s;
 }
 
 dk_status dk_patch_fwd_run(const dk_geom &g, dk_patch_plan &pl, const float *W, const float *xbar,
@@ -642,11 +634,6 @@ dk_status dk_patch_fwd_run(const dk_geom &g, dk_patch_plan &pl, const float *W, 
     else
         s = pl.flat ? P3Flat::launch(p, pl.vec, pl.lds_bytes, st) : P3Sq::launch(p, pl.vec, pl.lds_bytes, st);
     if (s != DK_OK) return s;
-    if (p.splits > 1) {
-        dk_prof_scope ps("splitk_reduce", st);
-        dk_patch_splitk_reduce<<<dim3((unsigned)((p.out_elems + 255) / 256)), dim3(256), 0, st>>>(
-            part, ybar, p.out_elems, p.splits);
-        return dk_launch_status();
-    }
+    if (p.splits > 1) return dk_fold_slices(part, ybar, p.out_elems, p.splits, 1.0f, 0, st);
     return DK_OK;
 }

@@ -1,5 +1,6 @@
 // Host-side parts of the library: status strings, layer geometry, workspace
 // sizing and the trusted-side coefficient derivation.  No device code here.
+#include <cstdlib>
 #include <cmath>
 #include <cstring>
 #include <vector>
@@ -103,21 +104,33 @@ DK_EXPORT size_t dk_fwd_workspace_bytes(const dk_layer *L, long long R)
     return dk_ws_fwd_bytes(g, R);
 }
 
-dk_split_plan dk_plan_split(long long out_tiles, long long ktiles, long long out_elems)
+dk_split_plan dk_plan_split(long long out_tiles, long long ktiles, long long out_elems, double step_us)
 {
-    // One workgroup per (output tile, K slice).  MI355X has 256 compute units
-    // and a contraction workgroup leaves room for about four per unit, so aim
-    // for ~1024 workgroups when the output alone has too few tiles.
+    // One workgroup per (output tile, K slice), handed out evenly over the 256
+    // compute units.  A unit's matrix pipe is shared by the workgroups resident
+    // on it, so the kernel lasts about
+    //     (workgroups on the busiest unit) x (steps per slice x step_us + fixed cost per workgroup),
+    // a single workgroup per unit cannot hide its own load latency
+    // (measured: about 12 % slower), and the slices are written and read once
+    // more by the fold.  Take the slice count that minimises the sum.
     dk_split_plan p = {1, (int)ktiles};
     if (ktiles < 1) { p.ktiles_per_split = 0; return p; }
-    if (out_tiles >= 512 || ktiles == 1) return p;
-    long long s = (1024 + out_tiles - 1) / out_tiles;
-    if (s > ktiles) s = ktiles;
-    if (s > DK_MAX_SPLITS) s = DK_MAX_SPLITS;
-    while (s > 1 && s * out_elems * 4 > DK_SPLIT_WS_CAP_BYTES) --s;
-    const long long per = (ktiles + s - 1) / s;
-    p.ktiles_per_split = (int)per;
-    p.splits = (int)((ktiles + per - 1) / per);
+    if (ktiles == 1) return p;
+    const double fixed_us = 3.0;                    // prologue latency + epilogue of a workgroup
+    const double fold_us_per_byte = 1.5 / 5.0e6;    // one write + about half a read at 5 TB/s
+    long long smax = ktiles < DK_MAX_SPLITS ? ktiles : DK_MAX_SPLITS;
+    double best = 0.0;
+    for (long long s = 1; s <= smax; ++s) {
+        if (s > 1 && s * out_elems * 4 > DK_SPLIT_WS_CAP_BYTES) break;
+        const long long per = (ktiles + s - 1) / s;
+        const long long sl = (ktiles + per - 1) / per;       // slices actually used
+        if (sl != s) continue;
+        const long long per_cu = (out_tiles * s + 255) / 256;
+        double t = (double)per_cu * ((double)per * step_us + fixed_us);
+        if (per_cu < 2) t *= 1.12;
+        if (s > 1) t += (double)s * (double)out_elems * 4.0 * fold_us_per_byte;
+        if (s == 1 || t < best) { best = t; p.splits = (int)s; p.ktiles_per_split = (int)per; }
+    }
     return p;
 }
 

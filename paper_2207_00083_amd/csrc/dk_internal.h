@@ -35,12 +35,18 @@ size_t dk_ws_fwd_bytes(const dk_geom &g, long long R);
 size_t dk_ws_wgrad_bytes(const dk_geom &g, long long R);
 size_t dk_ws_verify_bytes(int G);
 
-// Split-K plan for a contraction: how many slices, tiles per slice.
+// Split-K plan for a contraction: how many slices, steps per slice.  step_us =
+// time one workgroup needs for one contraction step with a SIMD to itself.
 struct dk_split_plan {
     int splits;
     int ktiles_per_split;
 };
-dk_split_plan dk_plan_split(long long out_tiles, long long ktiles, long long out_elems);
+dk_split_plan dk_plan_split(long long out_tiles, long long ktiles, long long out_elems, double step_us);
+
+// Second pass of a sliced contraction:
+// out[i] = (accumulate ? out[i] : 0) + alpha * sum_s part[s][i], in a fixed order.
+dk_status dk_fold_slices(const float *part, float *out, long long out_elems, int splits, float alpha,
+                         int accumulate, hipStream_t st);
 
 #define DK_VERIFY_MAX_BLOCKS 64
 #define DK_MAX_SPLITS 256

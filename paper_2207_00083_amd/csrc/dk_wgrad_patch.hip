@@ -529,9 +529,15 @@ bool dk_patch_wgrad_plan(const dk_geom &g, long long R, bool aligned16, dk_wgpat
     // the 32 rows a half-wave touches over all banks)
     auto pitch = [&](int n) { return quad ? (n % 8 == 0 ? n + 4 : n) : (n | 1); };
 
-    // choose the pixel tile: as many output rows (then whole images) as the
-    // copy slots and the LDS allow
+    // choose the pixel tile among those the copy slots and the LDS allow: the
+    // one with the fewest matrix-pipe cycles on the busiest workgroup (large
+    // tiles amortise the per-tile barrier, but a tile count that does not
+    // divide over the workgroups, or a ragged last row block, leaves MFMA slots
+    // empty)
     int bestTR = 0, bestNI = 0;
+    double bestCost = 0.0;
+    const long long wg_tiles = (long long)((g.Co + 63) / 64) * ((g.Ci + 63) / 64);
+    bool fits_image = false;
     for (int pass = 0; pass < 2; ++pass) {
         // pass 0: row blocks of one image; pass 1: several whole images
         for (int cand = 1; cand <= 64; ++cand) {
@@ -550,9 +556,19 @@ bool dk_patch_wgrad_plan(const dk_geom &g, long long R, bool aligned16, dk_wgpat
             const size_t bytes = 2 * ((size_t)round_up(64 * LDQ, 4) + round_up(64 * CPLANE, 4)) * 4;
             if (d_slots > dmax || p_slots > pmax || bytes > LDS_LIMIT) break;
             if ((long long)NI * g.Co * HoWo >= (1ll << 30) || (long long)NI * g.n >= (1ll << 30)) break;
-            bestTR = TR; bestNI = NI;
+            if (pass == 0) fits_image = TR == g.Ho;
+            const long long n_pt = ((R + NI - 1) / NI) * ((g.Ho + TR - 1) / TR);
+            long long sp = 256 / wg_tiles;
+            if (sp < 1) sp = 1;
+            if (sp > n_pt) sp = n_pt;
+            const long long per = (n_pt + sp - 1) / sp;
+            // a step is 36 MFMAs on 8 pixels (16-byte reads) or 9 on 2; the single-float
+            // reads pace the latter at about 730 cycles instead of 576
+            const double steps = quad ? NI * TR * (g.Wo / 8.0) : NI * TR * (g.Wo / 2.0);
+            const double cost = (double)per * (steps * (quad ? 2304.0 : 730.0) + 1000.0);
+            if (bestTR == 0 || cost < bestCost) { bestTR = TR; bestNI = NI; bestCost = cost; }
         }
-        if (bestTR < g.Ho) break;      // could not even fit one whole image: stay with row blocks
+        if (!fits_image) break;        // could not even fit one whole image: stay with row blocks
     }
     if (bestTR == 0) return false;
     p.TR = bestTR; p.NI = bestNI;
