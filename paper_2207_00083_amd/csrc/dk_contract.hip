@@ -740,6 +740,20 @@ size_t split_bytes(long long rows, long long cols, long long kdim, long long out
 using CfgSq = Cfg<128, 128, 16, 2, 2>;
 using CfgFlat = Cfg<64, 256, 16, 1, 4>;
 using CfgWg64 = Cfg<64, 128, 16, 2, 2>;
+using CfgTall = Cfg<128, 64, 16, 2, 2>;
+using CfgSmall = Cfg<64, 64, 16, 2, 2>;
+
+// Weight gradients have small outputs (rows = output channels, columns = input
+// channels or filter elements): pick the tile that wastes no MFMA rows or
+// columns on a 64-wide side.
+template <class Fn>
+auto with_wgrad_cfg(long long rows, long long cols, Fn fn)
+{
+    if (rows <= 64 && cols <= 64) return fn(CfgSmall{});
+    if (rows <= 64) return fn(CfgWg64{});
+    if (cols <= 64) return fn(CfgTall{});
+    return fn(CfgSq{});
+}
 
 ConvParams conv_params(const dk_geom &g, const float *p, long long R)
 {
@@ -899,11 +913,11 @@ size_t dk_ws_wgrad_bytes(const dk_geom &g, long long R)
     if (g.dw) return align_up((size_t)R * g.m * sizeof(float), 256) + dk_dw_wgrad_part_bytes(g, R);
     size_t part;
     if (!g.conv)
-        part = split_bytes<CfgSq>(g.M, g.N, R, (long long)g.M * g.N);
-    else if (conv_flat(g))
-        part = split_bytes<CfgWg64>(g.Co, g.Kg, R * g.Ho * g.Wo, g.Co * g.Kg);
+        part = with_wgrad_cfg(g.M, g.N, [&](auto c) {
+            return split_bytes<decltype(c)>(g.M, g.N, R, (long long)g.M * g.N); });
     else
-        part = split_bytes<CfgSq>(g.Co, g.Kg, R * g.Ho * g.Wo, g.Co * g.Kg);
+        part = with_wgrad_cfg(g.Co, g.Kg, [&](auto c) {
+            return split_bytes<decltype(c)>(g.Co, g.Kg, R * g.Ho * g.Wo, g.Co * g.Kg); });
     if (g.conv) {
         dk_wgpatch_plan pl;
         for (int aligned = 0; aligned < 2; ++aligned)
@@ -1005,11 +1019,11 @@ static dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *
     if (g.dw) return dk_dw_wgrad_run(g, dtilde, xbar, dW, R, scale, accumulate, part, st);
     if (!g.conv) {
         const bool vec = (g.M % 4 == 0) && (g.N % 4 == 0) && dk_aligned(xbar, 16);
-        if (vec)
-            return run_dense_tn<CfgSq, true>(dtilde, xbar, dW, g.M, g.N, (int)R, scale, accumulate,
-                                             part, part_bytes, st);
-        return run_dense_tn<CfgSq, false>(dtilde, xbar, dW, g.M, g.N, (int)R, scale, accumulate,
-                                          part, part_bytes, st);
+        return with_wgrad_cfg(g.M, g.N, [&](auto c) {
+            using C = decltype(c);
+            return vec ? run_dense_tn<C, true>(dtilde, xbar, dW, g.M, g.N, (int)R, scale, accumulate, part, part_bytes, st)
+                       : run_dense_tn<C, false>(dtilde, xbar, dW, g.M, g.N, (int)R, scale, accumulate, part, part_bytes, st);
+        });
     }
     dk_wgpatch_plan pl;
     if (dk_patch_wgrad_plan(g, R, dk_aligned(xbar, 16), &pl)) {
@@ -1018,15 +1032,15 @@ static dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *
     }
     if (conv_is_1x1(g)) {
         const bool vec = (g.H * g.W) % 4 == 0 && dk_aligned(xbar, 16);
-        if (conv_flat(g))
-            return vec ? run_conv1x1_wgrad<CfgWg64, true>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st)
-                       : run_conv1x1_wgrad<CfgWg64, false>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
-        return vec ? run_conv1x1_wgrad<CfgSq, true>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st)
-                   : run_conv1x1_wgrad<CfgSq, false>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
+        return with_wgrad_cfg(g.Co, g.Kg, [&](auto c) {
+            using C = decltype(c);
+            return vec ? run_conv1x1_wgrad<C, true>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st)
+                       : run_conv1x1_wgrad<C, false>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
+        });
     }
-    if (conv_flat(g))
-        return run_conv_wgrad<CfgWg64>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
-    return run_conv_wgrad<CfgSq>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
+    return with_wgrad_cfg(g.Co, g.Kg, [&](auto c) {
+        return run_conv_wgrad<decltype(c)>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
+    });
 }
 
 DK_EXPORT dk_status dk_wgrad(const dk_layer *L, const float *delta, const float *B, const float *gamma,
