@@ -272,6 +272,51 @@ def test_wgrad_accumulate_and_scale(dk):
     assert nerr(host(dW), ref) < TOL_CONTRACT
 
 
+# Contractions cut into slices along the contraction axis, one case per fold
+# variant and tile shape: (many slices, tiny output), (a few slices, small
+# output), (odd output length), (slices over a large output), narrow tiles.
+SLICED_WGRAD = [
+    # K, G, M, N
+    (2, 700, 40, 50),      # contraction 2800 over a 40x50 output: >= 64 slices
+    (2, 40, 40, 50),       # ~10 slices
+    (2, 300, 33, 91),      # odd output length, 64-row tile
+    (2, 300, 150, 47),     # 64-column tile
+]
+
+
+@pytest.mark.parametrize("K,G,M,N", SLICED_WGRAD)
+def test_sliced_wgrad_folds(dk, K, G, M, N):
+    L = dk_inputs.linear(M, N)
+    say("sliced dense wgrad", dict(K=K, G=G, M=M, N=N))
+    d = _masked_case(L, K, G, seed=K * 7 + G + M * 3 + N)
+    _, _, B = dk.dk_coeffs(d["A"], d["gamma"])
+    xbar = dk.dk_encode(dev(d["X"]), dev(d["r"]), dev(d["A"]), K)
+    args = (L, dev(d["delta"]), dev(B), dev(d["gamma"]), xbar, K)
+    dW = host(dk.dk_wgrad(*args, scale=0.5))
+    ref = oracle.dense_wgrad(d["delta"], d["X"], scale=0.5)
+    assert nerr(dW, ref) < TOL_CONTRACT
+    # slices are folded in a fixed order: a rerun is bitwise identical
+    assert np.array_equal(dW, host(dk.dk_wgrad(*args, scale=0.5)))
+
+
+def test_sliced_forward_folds(dk):
+    # dense: 130 x 257 outputs (odd length) over a contraction of 4096;
+    # conv: 1.5 M outputs over 256 input channels (a few slices, vector fold)
+    say("sliced dense fwd")
+    rng = np.random.default_rng(4242)
+    W = rng.standard_normal((257, 4096)).astype(np.float32)
+    X = rng.standard_normal((130, 4096)).astype(np.float32)
+    assert nerr(host(dk.dk_linear_fwd(dev(W), dev(X))), oracle.dense_fwd(W, X)) < TOL_GEMM
+    L = dk_inputs.conv(256, 128, 16, 16, 3, 1, 1)
+    say("sliced conv fwd", L)
+    Wt = rng.standard_normal(L.w_shape).astype(np.float32)
+    Xc = rng.standard_normal((48,) + L.in_shape).astype(np.float32)
+    got = host(dk.dk_conv_fwd(L, dev(Wt), dev(Xc)))
+    pts = np.stack([rng.integers(0, s, 4000) for s in got.shape], axis=1)
+    ref = oracle.conv_fwd_points(Wt, Xc, pts, 1, 1)
+    assert np.max(np.abs(got[tuple(pts.T)] - ref)) / np.max(np.abs(ref)) < TOL_GEMM
+
+
 def test_verdicts_match_oracle_under_corruption(dk):
     say("verdicts under corruption")
     L = dk_inputs.conv(8, 16, 10, 10, 3, 1, 1)
