@@ -770,14 +770,15 @@ ConvParams conv_params(const dk_geom &g, const float *p, long long R)
 
 template <class C, bool VA, bool VB>
 dk_status run_dense_nt(const float *A, const float *B, float *Cout, int rows, int cols, int kdim,
-                       float *part, size_t part_bytes, hipStream_t st)
+                       float *part, size_t part_bytes, hipStream_t st,
+                       const char *label = "contract_dense_fwd")
 {
     using LA = LoadRowMajorK<C::BM, C::BK, C::NT, C::LDA, VA>;
     using LB = LoadRowMajorK<C::BN, C::BK, C::NT, C::LDB, VB>;
     MatParams pa = {A, kdim, rows, kdim}, pb = {B, kdim, cols, kdim};
     EpiDense ep = {cols, rows, cols};
     return run<C, LA, LB, EpiDense>(pa, pb, ep, rows, cols, kdim, 1.0f, 0, Cout,
-                                    (long long)rows * cols, part, part_bytes, st, "contract_dense_fwd");
+                                    (long long)rows * cols, part, part_bytes, st, label);
 }
 
 // C[rows][cols] = A[rows][k] . B[k][cols]  (A contiguous along k, B along cols)
@@ -795,14 +796,15 @@ dk_status run_dense_nn(const float *A, const float *B, float *Cout, int rows, in
 
 template <class C, bool VEC>
 dk_status run_dense_tn(const float *A, const float *B, float *Cout, int rows, int cols, int kdim,
-                       float alpha, int accumulate, float *part, size_t part_bytes, hipStream_t st)
+                       float alpha, int accumulate, float *part, size_t part_bytes, hipStream_t st,
+                       const char *label = "contract_dense_wgrad")
 {
     using LA = LoadKMajor<C::BM, C::BK, C::NT, C::LDA, VEC>;
     using LB = LoadKMajor<C::BN, C::BK, C::NT, C::LDB, VEC>;
     MatParams pa = {A, rows, rows, kdim}, pb = {B, cols, cols, kdim};
     EpiDense ep = {cols, rows, cols};
     return run<C, LA, LB, EpiDense>(pa, pb, ep, rows, cols, kdim, alpha, accumulate, Cout,
-                                    (long long)rows * cols, part, part_bytes, st, "contract_dense_wgrad");
+                                    (long long)rows * cols, part, part_bytes, st, label);
 }
 
 template <class C, bool VW>
@@ -878,6 +880,103 @@ dk_status run_conv1x1_wgrad(const dk_geom &g, const float *dtilde, const float *
                                     (long long)g.Co * g.Ci, part, part_bytes, st, "contract_conv1x1_wgrad");
 }
 
+// A convolution over images of at most 2x2 pixels is a small dense layer: every
+// output pixel sees the whole image, and most taps of the im2col form fall on
+// padding.  Its matrix is
+//   Wd[(co, oh, ow)][(ci, ih, iw)] = W[co][ci][ih - oh*s + p][iw - ow*s + p]   (0 outside the filter)
+// so ybar[r] = Wd . xbar[r] in the NCHW flattening both sides already have, and
+// the weight gradient is the dense one folded back over the pixel pairs.
+bool conv_as_dense(const dk_geom &g)
+{
+    return g.conv && !g.dw && g.H * g.W <= 4 && g.Ho * g.Wo <= 4 &&
+           (long long)g.Co * g.Ho * g.Wo * g.Ci * g.H * g.W <= (16ll << 20);
+}
+
+size_t conv_dense_matrix_bytes(const dk_geom &g)
+{
+    return align_up((size_t)g.Co * g.Ho * g.Wo * g.Ci * g.H * g.W * sizeof(float), 256);
+}
+
+// One thread per (matrix row, input channel): the H*W <= 4 entries of that
+// channel are consecutive in the row.
+__global__ __launch_bounds__(256) void conv_unfold_filters_kernel(const float *__restrict__ W,
+                                                                  float *__restrict__ Wd, int Ci, int H,
+                                                                  int Wi, int Ho, int Wo, int kh, int kw,
+                                                                  int stride, int pad, long long total)
+{
+    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int HW = H * Wi, HoWo = Ho * Wo;
+    const int ci = (int)(e % Ci);
+    const long long row = e / Ci;
+    const int po = (int)(row % HoWo);
+    const long long co = row / HoWo;
+    const float *w = W + (co * Ci + ci) * kh * kw;
+    const int a0 = pad - (po / Wo) * stride, b0 = pad - (po % Wo) * stride;
+    float v[4];
+#pragma unroll
+    for (int pi = 0; pi < 4; ++pi) {
+        const int a = pi / Wi + a0, b = pi % Wi + b0;
+        v[pi] = (pi < HW && a >= 0 && a < kh && b >= 0 && b < kw) ? w[a * kw + b] : 0.0f;
+    }
+    float *d = Wd + (row * Ci + ci) * HW;
+    if (HW == 4) {
+        *reinterpret_cast<float4 *>(d) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+#pragma unroll
+        for (int pi = 0; pi < 4; ++pi)
+            if (pi < HW) d[pi] = v[pi];
+    }
+}
+
+// dW[co][ci][a][b] = (accumulate ? dW : 0) + scale * sum over output pixels (oh, ow) whose
+// tap (a, b) lies inside the image of dWd[(co, oh, ow)][(ci, oh*s + a - p, ow*s + b - p)].
+// One thread per (co, ci): it reads its block of at most 4 x 4 dense entries
+// (consecutive threads read consecutive 16-byte pieces) and writes the kh*kw
+// consecutive taps.
+__global__ __launch_bounds__(256) void conv_refold_wgrad_kernel(const float *__restrict__ dWd,
+                                                                float *__restrict__ dW, int Ci, int H,
+                                                                int Wi, int Ho, int Wo, int kh, int kw,
+                                                                int stride, int pad, float scale,
+                                                                int accumulate, long long total)
+{
+    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int ci = (int)(e % Ci);
+    const long long co = e / Ci;
+    const int HW = H * Wi, HoWo = Ho * Wo;
+    const long long ncol = (long long)Ci * HW;
+    float blk[4][4];
+#pragma unroll
+    for (int po = 0; po < 4; ++po) {
+        const float *src = dWd + (co * HoWo + po) * ncol + (long long)ci * HW;
+        if (po < HoWo && HW == 4) {
+            const float4 v = *reinterpret_cast<const float4 *>(src);
+            blk[po][0] = v.x; blk[po][1] = v.y; blk[po][2] = v.z; blk[po][3] = v.w;
+        } else {
+#pragma unroll
+            for (int pi = 0; pi < 4; ++pi) blk[po][pi] = (po < HoWo && pi < HW) ? src[pi] : 0.0f;
+        }
+    }
+    float *d = dW + (co * Ci + ci) * kh * kw;
+    for (int a = 0; a < kh; ++a)
+        for (int b = 0; b < kw; ++b) {
+            float s = 0.0f;
+#pragma unroll
+            for (int po = 0; po < 4; ++po)
+#pragma unroll
+                for (int pi = 0; pi < 4; ++pi) {
+                    // entry (po, pi) belongs to tap (pi/W - (po/Wo)*s + p, pi%W - (po%Wo)*s + p)
+                    const bool hit = po < HoWo && pi < HW && pi / Wi - (po / Wo) * stride + pad == a &&
+                                     pi % Wi - (po % Wo) * stride + pad == b;
+                    s += hit ? blk[po][pi] : 0.0f;
+                }
+            s *= scale;
+            if (accumulate) s += d[a * kw + b];
+            d[a * kw + b] = s;
+        }
+}
+
 bool conv_is_1x1(const dk_geom &g) { return g.kh == 1 && g.kw == 1 && g.stride == 1 && g.pad == 0; }
 
 bool conv_flat(const dk_geom &g) { return g.Co <= 64; }
@@ -887,6 +986,10 @@ bool conv_flat(const dk_geom &g) { return g.Co <= 64; }
 size_t dk_ws_fwd_bytes(const dk_geom &g, long long R)
 {
     if (g.dw) return 256;
+    if (conv_as_dense(g)) {
+        const long long Md = (long long)g.Co * g.Ho * g.Wo, Nd = (long long)g.Ci * g.H * g.W;
+        return conv_dense_matrix_bytes(g) + split_bytes<CfgSq>(R, Md, Nd, R * Md);
+    }
     size_t b;
     if (!g.conv)
         b = split_bytes<CfgSq>(R, g.M, g.N, R * g.m);
@@ -912,13 +1015,17 @@ size_t dk_ws_wgrad_bytes(const dk_geom &g, long long R)
     // mixed gradients dtilde[R][m] first, then the partial sums
     if (g.dw) return align_up((size_t)R * g.m * sizeof(float), 256) + dk_dw_wgrad_part_bytes(g, R);
     size_t part;
-    if (!g.conv)
+    if (conv_as_dense(g)) {
+        const long long Md = (long long)g.Co * g.Ho * g.Wo, Nd = (long long)g.Ci * g.H * g.W;
+        part = conv_dense_matrix_bytes(g) + with_wgrad_cfg(Md, Nd, [&](auto c) {
+            return split_bytes<decltype(c)>(Md, Nd, R, Md * Nd); });
+    } else if (!g.conv)
         part = with_wgrad_cfg(g.M, g.N, [&](auto c) {
             return split_bytes<decltype(c)>(g.M, g.N, R, (long long)g.M * g.N); });
     else
         part = with_wgrad_cfg(g.Co, g.Kg, [&](auto c) {
             return split_bytes<decltype(c)>(g.Co, g.Kg, R * g.Ho * g.Wo, g.Co * g.Kg); });
-    if (g.conv) {
+    if (g.conv && !conv_as_dense(g)) {
         dk_wgpatch_plan pl;
         for (int aligned = 0; aligned < 2; ++aligned)
             if (dk_patch_wgrad_plan(g, R, aligned != 0, &pl) && pl.part_bytes > part) part = pl.part_bytes;
@@ -953,6 +1060,22 @@ static dk_status conv_fwd_impl(const dk_geom &g, const float *W, const float *xb
 {
     hipStream_t st = (hipStream_t)stream;
     if (g.dw) return dk_dw_fwd_run(g, W, xbar, ybar, R, st);
+    if (conv_as_dense(g)) {
+        const int Md = g.Co * g.Ho * g.Wo, Nd = g.Ci * g.H * g.W;
+        float *Wd = (float *)ws;
+        const size_t wd_bytes = conv_dense_matrix_bytes(g);
+        const long long total = (long long)Md * g.Ci;
+        {
+            dk_prof_scope ps("conv_unfold_filters", st);
+            conv_unfold_filters_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
+                W, Wd, g.Ci, g.H, g.W, g.Ho, g.Wo, g.kh, g.kw, g.stride, g.pad, total);
+        }
+        DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+        float *part = (float *)((char *)ws + wd_bytes);
+        const bool v = (Nd % 4 == 0) && dk_aligned(xbar, 16);
+        if (v) return run_dense_nt<CfgSq, true, true>(xbar, Wd, ybar, R, Md, Nd, part, ws_bytes - wd_bytes, st, "contract_conv_dense_fwd");
+        return run_dense_nt<CfgSq, false, false>(xbar, Wd, ybar, R, Md, Nd, part, ws_bytes - wd_bytes, st, "contract_conv_dense_fwd");
+    }
     dk_patch_plan pl;
     if (dk_patch_fwd_plan(g, R, dk_aligned(xbar, 16) && dk_aligned(ybar, 16), &pl))
         return dk_patch_fwd_run(g, pl, W, xbar, ybar, (float *)ws, st);
@@ -1024,6 +1147,24 @@ static dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *
             return vec ? run_dense_tn<C, true>(dtilde, xbar, dW, g.M, g.N, (int)R, scale, accumulate, part, part_bytes, st)
                        : run_dense_tn<C, false>(dtilde, xbar, dW, g.M, g.N, (int)R, scale, accumulate, part, part_bytes, st);
         });
+    }
+    if (conv_as_dense(g)) {
+        const int Md = g.Co * g.Ho * g.Wo, Nd = g.Ci * g.H * g.W;
+        float *dWd = part;
+        const size_t wd_bytes = conv_dense_matrix_bytes(g);
+        float *part2 = (float *)((char *)part + wd_bytes);
+        const bool vec = (Md % 4 == 0) && (Nd % 4 == 0) && dk_aligned(xbar, 16);
+        s = with_wgrad_cfg(Md, Nd, [&](auto c) {
+            using C = decltype(c);
+            return vec ? run_dense_tn<C, true>(dtilde, xbar, dWd, Md, Nd, (int)R, 1.0f, 0, part2, part_bytes - wd_bytes, st, "contract_conv_dense_wgrad")
+                       : run_dense_tn<C, false>(dtilde, xbar, dWd, Md, Nd, (int)R, 1.0f, 0, part2, part_bytes - wd_bytes, st, "contract_conv_dense_wgrad");
+        });
+        if (s != DK_OK) return s;
+        const long long total = (long long)g.Co * g.Ci;
+        dk_prof_scope ps("conv_refold_wgrad", st);
+        conv_refold_wgrad_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
+            dWd, dW, g.Ci, g.H, g.W, g.Ho, g.Wo, g.kh, g.kw, g.stride, g.pad, scale, accumulate, total);
+        return dk_launch_status();
     }
     dk_wgpatch_plan pl;
     if (dk_patch_wgrad_plan(g, R, dk_aligned(xbar, 16), &pl)) {

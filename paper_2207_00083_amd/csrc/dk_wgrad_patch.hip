@@ -502,6 +502,9 @@ bool dk_patch_wgrad_plan(const dk_geom &g, long long R, bool aligned16, dk_wgpat
     if (!g.conv || R < 1) return false;
     if (!(g.kh == 3 && g.kw == 3)) return false;
     if (g.stride > 2 || (g.Wo & 1)) return false;
+    // a workgroup's 64 input-channel columns would be mostly empty: the gather
+    // engine packs (ci, tap) into its columns instead
+    if (g.Ci <= 16) return false;
     dk_wgpatch_params &p = pl->p;
     p = dk_wgpatch_params();
     const int HoWo = g.Ho * g.Wo;

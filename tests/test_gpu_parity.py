@@ -240,6 +240,11 @@ CONV_MASKED = [
     (1, 2, 3, 16, 30, 30, 7, 2, 3),
     (8, 1, 32, 40, 2, 2, 3, 1, 1),
     (4, 2, 70, 20, 4, 4, 3, 1, 1),
+    # images of at most 2x2 pixels (run as a dense layer on unfolded filters)
+    (2, 3, 24, 40, 1, 1, 3, 1, 1),
+    (3, 2, 12, 20, 2, 2, 3, 2, 1),
+    (2, 2, 16, 8, 2, 2, 2, 1, 0),
+    (4, 4, 130, 70, 2, 2, 3, 1, 1),
 ]
 
 
