@@ -6,6 +6,8 @@
 // moves 16-byte vectors, and every input row is read exactly once.
 #include "dk_internal.h"
 
+static int verify_max_chunks(int G);
+
 namespace {
 
 constexpr int MIX_THREADS = 256;
@@ -24,6 +26,32 @@ __device__ __forceinline__ void vload(float (&dst)[VEC], const float *p)
         dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
     } else {
         dst[0] = *p;
+    }
+}
+
+// Streaming variants for data that is not touched again soon (the decoded
+// outputs; the encoded results once they have been decoded).
+template <int VEC>
+__device__ __forceinline__ void vload_nt(float (&dst)[VEC], const float *p)
+{
+    if constexpr (VEC == 4) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        const f4 v = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p));
+        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+    } else {
+        dst[0] = __builtin_nontemporal_load(p);
+    }
+}
+
+template <int VEC>
+__device__ __forceinline__ void vstore_nt(float *p, const float (&src)[VEC])
+{
+    if constexpr (VEC == 4) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        f4 v = {src[0], src[1], src[2], src[3]};
+        __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(p));
+    } else {
+        __builtin_nontemporal_store(src[0], p);
     }
 }
 
@@ -216,7 +244,7 @@ __global__ __launch_bounds__(MIX_THREADS) void decode_verify_kernel(
         const long long e = v * VEC;
         float x[S][VEC];
 #pragma unroll
-        for (int j = 0; j < S; ++j) vload<VEC>(x[j], src + (long long)j * len + e);
+        for (int j = 0; j < S; ++j) vload_nt<VEC>(x[j], src + (long long)j * len + e);
 #pragma unroll
         for (int i = 0; i < K; ++i) {
             if (!FULL && i >= nk) continue;
@@ -227,7 +255,7 @@ __global__ __launch_bounds__(MIX_THREADS) void decode_verify_kernel(
             for (int j = 1; j < S; ++j)
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) acc[c] = fmaf(coef[j][i], x[j][c], acc[c]);
-            vstore<VEC>(dst + (long long)i * len + e, acc);
+            vstore_nt<VEC>(dst + (long long)i * len + e, acc);
         }
 #pragma unroll
         for (int c = 0; c < VEC; ++c) {
@@ -365,7 +393,7 @@ template <int K>
 dk_status launch_verify_k(const float *ybar, const float *nvec, float tol, int *verdict,
                           float *resid, int G, long long len, float *part, bool v4, hipStream_t st)
 {
-    const span_plan p = plan_span(len, v4 ? 4 : 1, G, DK_VERIFY_MAX_BLOCKS);
+    const span_plan p = plan_span(len, v4 ? 4 : 1, G, verify_max_chunks(G));
     const long long blocks = (long long)G * p.chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     {
@@ -389,7 +417,7 @@ dk_status launch_decode_verify_k(const float *ybar, const float *Ainv, const flo
                                  float *y, int *verdict, float *resid, int G, long long len,
                                  float *part, bool v4, int nk, hipStream_t st)
 {
-    const span_plan p = plan_span(len, v4 ? 4 : 1, G, DK_VERIFY_MAX_BLOCKS);
+    const span_plan p = plan_span(len, v4 ? 4 : 1, G, verify_max_chunks(G));
     const long long blocks = (long long)G * p.chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     {
@@ -421,9 +449,19 @@ dk_status check_mix_args(int G, int K, long long len)
 
 } // namespace
 
+// Workgroups per group in the integrity check's first pass: 64 when there are
+// many groups, more when a few groups alone would leave most of the chip idle.
+static int verify_max_chunks(int G)
+{
+    int c = (4096 + G - 1) / G;
+    if (c < DK_VERIFY_MAX_BLOCKS) c = DK_VERIFY_MAX_BLOCKS;
+    if (c > 1024) c = 1024;
+    return c;
+}
+
 size_t dk_ws_verify_bytes(int G)
 {
-    return (size_t)G * DK_VERIFY_MAX_BLOCKS * 2 * sizeof(float);
+    return (size_t)G * verify_max_chunks(G) * 2 * sizeof(float);
 }
 
 DK_EXPORT dk_status dk_encode(const float *x, const float *r, const float *A, float *xbar,
