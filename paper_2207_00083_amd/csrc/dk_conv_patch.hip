@@ -455,7 +455,7 @@ template <int BM, int BN, int WM, int WN, int KH, int KW, int CB>
 struct PatchCfg {
     static constexpr int bm = BM, bn = BN, cb = CB, kh = KH, kw = KW;
     static constexpr int NT = 64 * WM * WN;
-    static constexpr int MAXSLOT4 = 4, MAXSLOT1 = 12;
+    static constexpr int MAXSLOT4 = 6, MAXSLOT1 = 14;
     static constexpr double STEP_US = (BM / WM / 32) * (BN / WN / 32) * (CB / 2 * KH * KW) * 64 / 2100.0;
 
     static dk_status launch(const dk_patch_params &p, int vec, size_t lds_bytes, hipStream_t st)

@@ -15,7 +15,6 @@
 // sums of all workgroups are folded in a fixed order by a second kernel, which
 // also applies scale / accumulate and writes dW's [co][ci][kh][kw] layout.
 #include "dk_internal.h"
-#include <type_traits>
 
 #include "dk_patch.h"
 
@@ -24,12 +23,13 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-template <int KH, int KW, int STRIDE, int VEC, int DSLOT, int PSLOT>
+template <int KH, int KW, int DSLOT, int PSLOT>
 __global__ __launch_bounds__(512) void conv_patch_wgrad_kernel(dk_wgpatch_params p)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     constexpr int NP = 256, BM = 64, BCI = 64, KK = KH * KW;
-    using stage_t = typename std::conditional<VEC == 4, f32x4, float>::type;
+    constexpr int STRIDE = 1, VEC = 4;     // stride-1 layers whose rows are whole 16-byte vectors
+    using stage_t = f32x4;
 
     // Two LDS buffers of [dtilde tile: BM x LDQ][input patch: BCI x CPLANE].
     // Waves 0-3 (one per SIMD) only run MFMAs on the current buffer; waves 4-7
@@ -119,8 +119,7 @@ __global__ __launch_bounds__(512) void conv_patch_wgrad_kernel(dk_wgpatch_params
                 if (d_m[e] < 0) continue;
                 float *d = buf + d_l[e];
                 const stage_t v = dok[e] ? dst_[e] : stage_t(0.0f);
-                if constexpr (VEC == 4) { d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w; }
-                else d[0] = v;
+                d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
             }
 #pragma unroll
             for (int e = 0; e < PSLOT; ++e) {
@@ -462,7 +461,7 @@ __global__ __launch_bounds__(256) void wgrad_fold_kernel(const float *__restrict
 
 inline int round_up(int v, int a) { return (v + a - 1) / a * a; }
 
-constexpr int DSLOT4 = 6, PSLOT4 = 10, DSLOT1 = 8, PSLOT1 = 24, DSLOTQ = 6, PSLOTQ = 11;
+constexpr int DSLOT4 = 6, PSLOT4 = 10, DSLOTQ = 6, PSLOTQ = 11;
 constexpr size_t LDS_LIMIT = 150 * 1024;     // of the 160 KB a compute unit has
 
 template <class KernelT>
@@ -484,24 +483,16 @@ dk_status launch_one(KernelT kernel, const dk_wgpatch_params &p, size_t lds_byte
     return dk_launch_status();
 }
 
-template <int KH, int KW>
-dk_status launch_k(const dk_wgpatch_params &p, int vec, size_t lds_bytes, hipStream_t st)
-{
-    if (p.stride == 1) {
-        if (vec == 4) return launch_one(conv_patch_wgrad_kernel<KH, KW, 1, 4, DSLOT4, PSLOT4>, p, lds_bytes, st, "conv_patch_wgrad");
-        return launch_one(conv_patch_wgrad_kernel<KH, KW, 1, 1, DSLOT1, PSLOT1>, p, lds_bytes, st, "conv_patch_wgrad");
-    }
-    if (vec == 4) return launch_one(conv_patch_wgrad_kernel<KH, KW, 2, 4, DSLOT4, PSLOT4>, p, lds_bytes, st, "conv_patch_wgrad");
-    return launch_one(conv_patch_wgrad_kernel<KH, KW, 2, 1, DSLOT1, PSLOT1>, p, lds_bytes, st, "conv_patch_wgrad");
-}
-
 } // namespace
 
 bool dk_patch_wgrad_plan(const dk_geom &g, long long R, bool aligned16, dk_wgpatch_plan *pl)
 {
     if (!g.conv || R < 1) return false;
     if (!(g.kh == 3 && g.kw == 3)) return false;
-    if (g.stride > 2 || (g.Wo & 1)) return false;
+    // stride 1 and rows of whole 16-byte vectors only: with scalar copies or
+    // stride 2 this kernel measured slower (51-74 TFLOP/s) than the gather
+    // engine (78-80) on the same layers
+    if (g.stride != 1 || (g.Wo & 1)) return false;
     // a workgroup's 64 input-channel columns would be mostly empty: the gather
     // engine packs (ci, tap) into its columns instead
     if (g.Ci <= 16) return false;
@@ -512,12 +503,13 @@ bool dk_patch_wgrad_plan(const dk_geom &g, long long R, bool aligned16, dk_wgpat
     p.Ho = g.Ho; p.Wo = g.Wo; p.HoWo = HoWo; p.R = (int)R;
     if ((long long)g.Co * HoWo >= (1ll << 26) || g.n >= (1ll << 26)) return false;
     const bool v4 = aligned16 && g.W % 4 == 0 && g.Wo % 4 == 0;
+    if (!v4) return false;
     // 16-byte LDS reads need stride 1, vector copies and half-rows of whole quads
     const bool quad = v4 && g.stride == 1 && g.Wo % 8 == 0 && g.pad <= 4;
     pl->vec = v4 ? 4 : 1;
     pl->quad = quad;
-    const int dslot = quad ? DSLOTQ : (v4 ? DSLOT4 : DSLOT1);
-    const int pslot = quad ? PSLOTQ : (v4 ? PSLOT4 : PSLOT1);
+    const int dslot = quad ? DSLOTQ : DSLOT4;
+    const int pslot = quad ? PSLOTQ : PSLOT4;
     const int dmax = dslot * 256, pmax = pslot * 256;
     if (quad) {
         p.LPAD = g.pad;
@@ -610,7 +602,7 @@ dk_status dk_patch_wgrad_run(const dk_geom &g, dk_wgpatch_plan &pl, const float 
     dk_wgpatch_params &p = pl.p;
     p.dt = dtilde; p.x = xbar; p.part = part;
     dk_status s = pl.quad ? launch_one(conv_quad_wgrad_kernel<DSLOTQ, PSLOTQ>, p, pl.lds_bytes, st, "conv_quad_wgrad")
-                          : launch_k<3, 3>(p, pl.vec, pl.lds_bytes, st);
+                          : launch_one(conv_patch_wgrad_kernel<3, 3, DSLOT4, PSLOT4>, p, pl.lds_bytes, st, "conv_patch_wgrad");
     if (s != DK_OK) return s;
     dk_prof_scope ps("wgrad_fold", st);
     wgrad_fold_kernel<<<dim3((unsigned)((p.part_elems + 63) / 64)), dim3(256), 0, st>>>(
