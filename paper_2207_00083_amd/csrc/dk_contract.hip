@@ -344,12 +344,22 @@ struct LoadIm2colQ {
     }
 };
 
-// 1x1 stride-1 convolution = one product per image: no gather is needed, only
-// addressing that knows where an image starts.
+// 1x1 convolution without padding = one product per image: no gather is
+// needed, only addressing that knows where an image starts (and, with a
+// stride, which pixels of the stored image the output pixels sit on).
 struct ImgParams {
-    const float *p;     // [R][C][HW]
-    int C, HW;          // channels per image, pixels per image
+    const float *p;     // [R][C][chs]
+    int C, HW;          // channels per image, pixels per image that take part
     int Q;              // R*HW
+    int chs;            // floats between channels (= HW without a stride)
+    int Wo, Wi, stride; // pixel pix = (ho, wo) is stored at (ho*stride)*Wi + wo*stride
+    __device__ __forceinline__ const float *pixel(int q) const
+    {
+        const int r = q / HW, pix = q - r * HW;
+        int off = pix;
+        if (stride != 1) { const int ho = pix / Wo; off = (ho * Wi + (pix - ho * Wo)) * stride; }
+        return p + (long long)r * C * chs + off;
+    }
 };
 
 // Forward B operand: rows = pixels q = (r, pix), contraction = input channel;
@@ -362,17 +372,16 @@ struct LoadKMajorImg {
     static_assert(BK * PER_K % NT == 0 && NT % PER_K == 0, "tile/threads");
     float4 st[N4];
     const float *src[VEC ? 1 : 4];   // element (k = 0) of this lane's pixel(s); null = outside
-    int C, HW, tid;
+    int C, chs, tid;
 
     __device__ __forceinline__ void init(const Params &a, int q0, int tid_)
     {
-        C = a.C; HW = a.HW; tid = tid_;
+        C = a.C; chs = a.chs; tid = tid_;
         const int q = q0 + (tid % PER_K) * 4;
 #pragma unroll
         for (int u = 0; u < (VEC ? 1 : 4); ++u) {
             const int qq = q + u;
-            const int r = qq / HW, pix = qq - r * HW;
-            src[u] = qq < a.Q ? a.p + (long long)r * C * HW + pix : nullptr;
+            src[u] = qq < a.Q ? a.pixel(qq) : nullptr;
         }
     }
 
@@ -383,7 +392,7 @@ struct LoadKMajorImg {
             const int k = kt * BK + (tid + e * NT) / PER_K;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (k < C) {
-                const long long ko = (long long)k * HW;
+                const long long ko = (long long)k * chs;
                 if constexpr (VEC) {
                     if (src[0]) v = *reinterpret_cast<const float4 *>(src[0] + ko);
                 } else {
@@ -418,6 +427,7 @@ struct LoadRowMajorKImg {
     float4 st[N4];
     const float *p; int C, HW, Q, row0, tid;
 
+    // (stride-1 layers only: chs == HW)
     __device__ __forceinline__ void init(const Params &a, int row0_, int tid_)
     { p = a.p; C = a.C; HW = a.HW; Q = a.Q; row0 = row0_; tid = tid_; }
 
@@ -851,30 +861,31 @@ dk_status run_conv_wgrad(const dk_geom &g, const float *dtilde, const float *xba
                                     (long long)g.Co * g.Kg, part, part_bytes, st, "contract_conv_wgrad_gather");
 }
 
-// 1x1 stride-1 pad-0 convolution through the image-aware loaders.
+// 1x1 pad-0 convolution (any stride) through the image-aware loaders.
 template <class C, bool VW, bool VX>
 dk_status run_conv1x1_fwd(const dk_geom &g, const float *W, const float *xbar, float *ybar, long long R,
                           float *part, size_t part_bytes, hipStream_t st)
 {
     using LA = LoadRowMajorK<C::BM, C::BK, C::NT, C::LDA, VW>;
     using LB = LoadKMajorImg<C::BN, C::BK, C::NT, C::LDB, VX>;
-    const int HW = g.H * g.W, Q = (int)(R * HW);
+    const int HW = g.Ho * g.Wo, Q = (int)(R * HW);
     MatParams pa = {W, g.Ci, g.Co, g.Ci};
-    ImgParams pb = {xbar, g.Ci, HW, Q};
+    ImgParams pb = {xbar, g.Ci, HW, Q, g.H * g.W, g.Wo, g.W, g.stride};
     EpiConvFwd ep = {g.Co, Q, HW, (long long)g.Co * HW};
     return run<C, LA, LB, EpiConvFwd>(pa, pb, ep, g.Co, Q, g.Ci, 1.0f, 0, ybar, R * g.m, part, part_bytes,
                                       st, "contract_conv1x1_fwd");
 }
 
-template <class C, bool VEC>
+template <class C, bool VD, bool VX>
 dk_status run_conv1x1_wgrad(const dk_geom &g, const float *dtilde, const float *xbar, float *dW,
                             long long R, float alpha, int accumulate, float *part, size_t part_bytes,
                             hipStream_t st)
 {
-    using LA = LoadRowMajorKImg<C::BM, C::BK, C::NT, C::LDA, VEC>;
-    using LB = LoadRowMajorKImg<C::BN, C::BK, C::NT, C::LDB, VEC>;
-    const int HW = g.H * g.W, Q = (int)(R * HW);
-    ImgParams pa = {dtilde, g.Co, HW, Q}, pb = {xbar, g.Ci, HW, Q};
+    using LA = LoadRowMajorKImg<C::BM, C::BK, C::NT, C::LDA, VD>;
+    using LB = LoadRowMajorKImg<C::BN, C::BK, C::NT, C::LDB, VX>;
+    const int HW = g.H * g.W, Q = (int)(R * HW);          // stride 1
+    ImgParams pa = {dtilde, g.Co, HW, Q, HW, g.W, g.W, 1};
+    ImgParams pb = {xbar, g.Ci, HW, Q, HW, g.W, g.W, 1};
     EpiDense ep = {g.Ci, g.Co, g.Ci};
     return run<C, LA, LB, EpiDense>(pa, pb, ep, g.Co, g.Ci, Q, alpha, accumulate, dW,
                                     (long long)g.Co * g.Ci, part, part_bytes, st, "contract_conv1x1_wgrad");
@@ -977,7 +988,7 @@ __global__ __launch_bounds__(256) void conv_refold_wgrad_kernel(const float *__r
         }
 }
 
-bool conv_is_1x1(const dk_geom &g) { return g.kh == 1 && g.kw == 1 && g.stride == 1 && g.pad == 0; }
+bool conv_is_1x1(const dk_geom &g) { return g.kh == 1 && g.kw == 1 && g.pad == 0; }
 
 bool conv_flat(const dk_geom &g) { return g.Co <= 64; }
 
@@ -1081,13 +1092,15 @@ static dk_status conv_fwd_impl(const dk_geom &g, const float *W, const float *xb
         return dk_patch_fwd_run(g, pl, W, xbar, ybar, (float *)ws, st);
     const bool vw = (g.Kg % 4 == 0) && dk_aligned(W, 16);
     if (conv_is_1x1(g)) {
-        const bool vx = (g.H * g.W) % 4 == 0 && dk_aligned(xbar, 16);
+        const bool vx = g.stride == 1 && (g.H * g.W) % 4 == 0 && dk_aligned(xbar, 16);
         float *pw = (float *)ws;
         if (conv_flat(g)) {
             if (vw && vx) return run_conv1x1_fwd<CfgFlat, true, true>(g, W, xbar, ybar, R, pw, ws_bytes, st);
+            if (vw) return run_conv1x1_fwd<CfgFlat, true, false>(g, W, xbar, ybar, R, pw, ws_bytes, st);
             return run_conv1x1_fwd<CfgFlat, false, false>(g, W, xbar, ybar, R, pw, ws_bytes, st);
         }
         if (vw && vx) return run_conv1x1_fwd<CfgSq, true, true>(g, W, xbar, ybar, R, pw, ws_bytes, st);
+        if (vw) return run_conv1x1_fwd<CfgSq, true, false>(g, W, xbar, ybar, R, pw, ws_bytes, st);
         return run_conv1x1_fwd<CfgSq, false, false>(g, W, xbar, ybar, R, pw, ws_bytes, st);
     }
     if (conv_flat(g))
@@ -1171,12 +1184,15 @@ static dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *
         DK_REQUIRE(part_bytes >= pl.part_bytes, DK_ERR_WORKSPACE);
         return dk_patch_wgrad_run(g, pl, dtilde, xbar, dW, scale, accumulate, part, st);
     }
-    if (conv_is_1x1(g)) {
-        const bool vec = (g.H * g.W) % 4 == 0 && dk_aligned(xbar, 16);
+    // (with a stride the scalar image loads of xbar measured slower here than the gather engine)
+    if (conv_is_1x1(g) && g.stride == 1) {
+        const bool vd = (g.Ho * g.Wo) % 4 == 0;           // dtilde rows (the workspace is aligned)
+        const bool vx = vd && dk_aligned(xbar, 16);
         return with_wgrad_cfg(g.Co, g.Kg, [&](auto c) {
             using C = decltype(c);
-            return vec ? run_conv1x1_wgrad<C, true>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st)
-                       : run_conv1x1_wgrad<C, false>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
+            if (vx) return run_conv1x1_wgrad<C, true, true>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
+            if (vd) return run_conv1x1_wgrad<C, true, false>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
+            return run_conv1x1_wgrad<C, false, false>(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
         });
     }
     return with_wgrad_cfg(g.Co, g.Kg, [&](auto c) {

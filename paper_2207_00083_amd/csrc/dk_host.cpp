@@ -111,7 +111,7 @@ dk_split_plan dk_plan_split(long long out_tiles, long long ktiles, long long out
     // on it, so the kernel lasts about
     //     (workgroups on the busiest unit) x (steps per slice x step_us + fixed cost per workgroup),
     // a single workgroup per unit cannot hide its own load latency
-    // (measured: about 12 % slower), and the slices are written and read once
+    // (measured: 10-25 % slower; two hide most of it), and the slices are written and read once
     // more by the fold.  Take the slice count that minimises the sum.
     dk_split_plan p = {1, (int)ktiles};
     if (ktiles < 1) { p.ktiles_per_split = 0; return p; }
@@ -127,7 +127,7 @@ dk_split_plan dk_plan_split(long long out_tiles, long long ktiles, long long out
         if (sl != s) continue;
         const long long per_cu = (out_tiles * s + 255) / 256;
         double t = (double)per_cu * ((double)per * step_us + fixed_us);
-        if (per_cu < 2) t *= 1.12;
+        if (per_cu < 2) t *= 1.25; else if (per_cu < 3) t *= 1.05;
         if (s > 1) t += (double)s * (double)out_elems * 4.0 * fold_us_per_byte;
         if (s == 1 || t < best) { best = t; p.splits = (int)s; p.ktiles_per_split = (int)per; }
     }

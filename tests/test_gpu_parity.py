@@ -240,6 +240,9 @@ CONV_MASKED = [
     (1, 2, 3, 16, 30, 30, 7, 2, 3),
     (8, 1, 32, 40, 2, 2, 3, 1, 1),
     (4, 2, 70, 20, 4, 4, 3, 1, 1),
+    # strided 1x1 (ragged sizes, stride 3)
+    (2, 2, 20, 24, 9, 7, 1, 2, 0),
+    (2, 2, 12, 130, 10, 10, 1, 3, 0),
     # images of at most 2x2 pixels (run as a dense layer on unfolded filters)
     (2, 3, 24, 40, 1, 1, 3, 1, 1),
     (3, 2, 12, 20, 2, 2, 3, 2, 1),
