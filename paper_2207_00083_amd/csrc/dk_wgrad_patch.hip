@@ -15,6 +15,7 @@
 // sums of all workgroups are folded in a fixed order by a second kernel, which
 // also applies scale / accumulate and writes dW's [co][ci][kh][kw] layout.
 #include "dk_internal.h"
+#include <type_traits>
 
 #include "dk_patch.h"
 
@@ -22,6 +23,10 @@ namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// last word of a raw (untyped, unstrided) buffer resource on gfx9-family parts
+constexpr int DK_BUFFER_RSRC_FLAGS = 0x00020000;
 
 template <int KH, int KW, int DSLOT, int PSLOT>
 __global__ __launch_bounds__(512) void conv_patch_wgrad_kernel(dk_wgpatch_params p)
@@ -262,9 +267,21 @@ __global__ __launch_bounds__(512) void conv_quad_wgrad_kernel(dk_wgpatch_params 
     __syncthreads();
 
     if (producer) {
+        // Vector-ALU instructions of this wave queue behind the matrix
+        // instructions of the MFMA wave on the same SIMD (measured: about one
+        // issue slot per MFMA), so a tile must cost as few of them as possible.
+        // Everything a lane needs is computed once: byte offsets from a
+        // wave-uniform base for the loads, LDS addresses in both buffers for the
+        // stores (an unused slot loads offset 0 and stores into a dump area
+        // behind the buffers, so nothing is predicated).  The tile position
+        // advances in scalar registers, and a tile that lies wholly inside its
+        // images and their rows is copied without any test.
+        __builtin_amdgcn_s_setprio(3);
         const int ptid = tid - 256;
-        unsigned d_g[DSLOT];
-        int d_l[DSLOT], d_m[DSLOT];
+        float *const dump = lds + 2 * p.buf_floats + (ptid & 63) * 4;
+        unsigned d_g[DSLOT], p_g[PSLOT];          // byte offsets
+        float *d_l[2][DSLOT], *p_l[2][PSLOT];
+        int d_m[DSLOT], p_m[PSLOT];
 #pragma unroll
         for (int e = 0; e < DSLOT; ++e) {
             const int idx = ptid + e * NP;
@@ -273,11 +290,12 @@ __global__ __launch_bounds__(512) void conv_quad_wgrad_kernel(dk_wgpatch_params 
             const int img_l = t1 % p.NI;
             const int co_l = t1 / p.NI;
             const bool act = idx < p.d_slots && co0 + co_l < p.Co;
-            d_g[e] = (unsigned)((img_l * p.Co + co_l) * p.HoWo + dv * 4);
-            d_l[e] = co_l * p.LDQ + img_l * p.TR * p.Wo + dv * 4;
+            d_g[e] = act ? 4u * (unsigned)((img_l * p.Co + co_l) * p.HoWo + dv * 4) : 0u;
+            const int l = co_l * p.LDQ + img_l * p.TR * p.Wo + dv * 4;
+            d_l[0][e] = act ? lds + l : dump;
+            d_l[1][e] = act ? lds + p.buf_floats + l : dump;
             d_m[e] = act ? (img_l | (dv * 4) << 8) : -1;
         }
-        int p_g[PSLOT], p_l[PSLOT], p_m[PSLOT];
 #pragma unroll
         for (int e = 0; e < PSLOT; ++e) {
             const int idx = ptid + e * NP;
@@ -288,49 +306,73 @@ __global__ __launch_bounds__(512) void conv_quad_wgrad_kernel(dk_wgpatch_params 
             const int img_l = t2 % p.NI;
             const int c_l = t2 / p.NI;
             const bool act = idx < p.p_slots && ci0 + c_l < p.Ci;
-            p_g[e] = (img_l * p.Ci + c_l) * p.H * p.W + prow * p.W + xv * 4;
-            p_l[e] = p.ad_floats + c_l * p.CPLANE + img_l * p.PLANE + prow * p.PW + p.LPAD + xv * 4;
+            p_g[e] = act ? 4u * (unsigned)((img_l * p.Ci + c_l) * p.H * p.W + prow * p.W + xv * 4) : 0u;
+            const int l = p.ad_floats + c_l * p.CPLANE + img_l * p.PLANE + prow * p.PW + p.LPAD + xv * 4;
+            p_l[0][e] = act ? lds + l : dump;
+            p_l[1][e] = act ? lds + p.buf_floats + l : dump;
             p_m[e] = act ? (img_l | prow << 8) : -1;
         }
-        for (int pt = pt0; pt < pt1; ++pt) {
-            float *buf = lds + ((pt - pt0) & 1) * p.buf_floats;
-            const int ig = pt / p.row_blocks;
-            const int rb = pt - ig * p.row_blocks;
+        int ig = pt0 / p.row_blocks, rb = pt0 - ig * p.row_blocks;
+        // tile pt goes to buffer (pt - pt0) & 1: two tiles per trip, so that the
+        // buffer is known at compile time
+        auto copy_tile = [&](auto bufc) {
+            constexpr int BUF = decltype(bufc)::value;
             const int r0 = ig * p.NI, row0 = rb * p.TR;
-            const int qlim = p.HoWo - row0 * p.Wo;
-            const int ilim = p.R - r0;
-            const float *dsrc = p.dt + ((long long)r0 * p.Co + co0) * p.HoWo + (long long)row0 * p.Wo;
+            const char *dsrc = reinterpret_cast<const char *>(
+                p.dt + ((long long)r0 * p.Co + co0) * p.HoWo + (long long)row0 * p.Wo);
             const int ih_a = row0 - p.pad;
-            const float *psrc = p.x + ((long long)r0 * p.Ci + ci0) * p.H * p.W;
-            const int poff = ih_a * p.W;
+            const char *psrc = reinterpret_cast<const char *>(
+                p.x + ((long long)r0 * p.Ci + ci0) * p.H * p.W + (long long)ih_a * p.W);
             f32x4 dst_[DSLOT], pst_[PSLOT];
-            bool dok[DSLOT], pok[PSLOT];
+            const bool clean = r0 + p.NI <= p.R && row0 + p.TR <= p.Ho && ih_a >= 0 && ih_a + p.PH <= p.H;
+            if (clean) {
+                // buffer loads: wave-uniform base in a scalar resource, the lane's
+                // byte offset as it is -- no address arithmetic on the vector ALU
+                const __amdgpu_buffer_rsrc_t rd =
+                    __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(dsrc), 0, -1, DK_BUFFER_RSRC_FLAGS);
+                const __amdgpu_buffer_rsrc_t rp =
+                    __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(psrc), 0, -1, DK_BUFFER_RSRC_FLAGS);
 #pragma unroll
-            for (int e = 0; e < DSLOT; ++e) {
-                dok[e] = d_m[e] >= 0 && (d_m[e] & 255) < ilim && (d_m[e] >> 8) < qlim;
-                dst_[e] = *reinterpret_cast<const f32x4 *>(dsrc + (dok[e] ? d_g[e] : 0u));
+                for (int e = 0; e < DSLOT; ++e)
+                    dst_[e] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rd, (int)d_g[e], 0, 0));
+#pragma unroll
+                for (int e = 0; e < PSLOT; ++e)
+                    pst_[e] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rp, (int)p_g[e], 0, 0));
+            } else {
+                // out of range for this tile: read the tile's first element, store zero
+                const int qlim = p.HoWo - row0 * p.Wo;
+                const int ilim = p.R - r0;
+                const char *psrc0 = reinterpret_cast<const char *>(p.x + ((long long)r0 * p.Ci + ci0) * p.H * p.W);
+                const int poffb = 4 * ih_a * p.W;
+#pragma unroll
+                for (int e = 0; e < DSLOT; ++e) {
+                    const bool ok = d_m[e] >= 0 && (d_m[e] & 255) < ilim && (d_m[e] >> 8) < qlim;
+                    const f32x4 v = *reinterpret_cast<const f32x4 *>(dsrc + (ok ? d_g[e] : 0u));
+                    dst_[e] = ok ? v : f32x4(0.0f);
+                }
+#pragma unroll
+                for (int e = 0; e < PSLOT; ++e) {
+                    const int ih = ih_a + (p_m[e] >> 8);
+                    const bool ok = p_m[e] >= 0 && (p_m[e] & 255) < ilim && ih >= 0 && ih < p.H;
+                    const f32x4 v = *reinterpret_cast<const f32x4 *>(psrc0 + (ok ? (unsigned)((int)p_g[e] + poffb) : 0u));
+                    pst_[e] = ok ? v : f32x4(0.0f);
+                }
             }
+#pragma unroll
+            for (int e = 0; e < DSLOT; ++e) *reinterpret_cast<f32x4 *>(d_l[BUF][e]) = dst_[e];
 #pragma unroll
             for (int e = 0; e < PSLOT; ++e) {
-                const int ih = ih_a + (p_m[e] >> 8);
-                pok[e] = p_m[e] >= 0 && (p_m[e] & 255) < ilim && ih >= 0 && ih < p.H;
-                pst_[e] = *reinterpret_cast<const f32x4 *>(psrc + (pok[e] ? (unsigned)(p_g[e] + poff) : 0u));
+                float *d = p_l[BUF][e];               // one column off 16-byte alignment
+                d[0] = pst_[e].x; d[1] = pst_[e].y; d[2] = pst_[e].z; d[3] = pst_[e].w;
             }
-#pragma unroll
-            for (int e = 0; e < DSLOT; ++e) {
-                if (d_m[e] < 0) continue;
-                *reinterpret_cast<f32x4 *>(buf + d_l[e]) = dok[e] ? dst_[e] : f32x4(0.0f);
-            }
-#pragma unroll
-            for (int e = 0; e < PSLOT; ++e) {
-                if (p_m[e] < 0) continue;
-                const f32x4 v = pok[e] ? pst_[e] : f32x4(0.0f);
-                float *d = buf + p_l[e];          // one column off 16-byte alignment
-                d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
-            }
-            __syncthreads();
+            if (++rb == p.row_blocks) { rb = 0; ++ig; }
+            __syncthreads();     // this tile is in LDS; the one before has been consumed
+        };
+        for (int pt = pt0; pt < pt1; pt += 2) {
+            copy_tile(std::integral_constant<int, 0>());
+            if (pt + 1 < pt1) copy_tile(std::integral_constant<int, 1>());
         }
-        if (pt0 < pt1) __syncthreads();
+        if (pt0 < pt1) __syncthreads();   // matches the MFMA waves' last barrier
         return;
     }
 
@@ -358,49 +400,54 @@ __global__ __launch_bounds__(512) void conv_quad_wgrad_kernel(dk_wgpatch_params 
 
         // load cursor, one 4-pixel step ahead of the MFMAs; it stays on the
         // last step of the tile once it gets there
-        int ld_row = 0, ld_q = 0;
+        int ld_row = 0, ld_q = 0, ld_img = 0, ld_r = 0;       // ld_row = ld_img * TR + ld_r
         const float *a_ld = a_base, *b_ld = b_base;
 #define DK_WGQ_ADVANCE()                                                                         \
         if (ld_q + 1 < nquad) {                                                                  \
             ++ld_q;                                                                              \
         } else if (ld_row + 1 < nrows) {                                                         \
             ld_q = 0; ++ld_row;                                                                  \
-            const int img_l_ = ld_row / p.TR, row_ = ld_row - img_l_ * p.TR;                     \
+            if (++ld_r == p.TR) { ld_r = 0; ++ld_img; }                                          \
             a_ld = a_base + ld_row * p.Wo;                                                       \
-            b_ld = b_base + img_l_ * p.PLANE + row_ * p.PW;                                      \
+            b_ld = b_base + ld_img * p.PLANE + ld_r * p.PW;                                      \
         }
-#define DK_WGQ_LOAD(A, B)                                                                        \
+        // The six patch columns of a filter row come as a 16-byte and an 8-byte
+        // read: a second 16-byte read would leave two registers dead, the
+        // register allocator would overlap the tuples, and overlapping read
+        // targets force a full wait between the reads.
+#define DK_WGQ_LOAD(A, B, C)                                                                     \
         {                                                                                        \
             A = *reinterpret_cast<const f32x4 *>(a_ld + 4 * ld_q);                               \
             _Pragma("unroll") for (int a = 0; a < KH; ++a) {                                     \
-                B[2 * a] = *reinterpret_cast<const f32x4 *>(b_ld + a * p.PW + 4 * ld_q);         \
-                B[2 * a + 1] = *reinterpret_cast<const f32x4 *>(b_ld + a * p.PW + 4 * ld_q + 4); \
+                B[a] = *reinterpret_cast<const f32x4 *>(b_ld + a * p.PW + 4 * ld_q);             \
+                C[a] = *reinterpret_cast<const f32x2 *>(b_ld + a * p.PW + 4 * ld_q + 4);         \
             }                                                                                    \
             __builtin_amdgcn_sched_barrier(0);   /* the reads go out before the MFMAs */         \
         }
-#define DK_WGQ_MMA(A, B)                                                                         \
+#define DK_WGQ_MMA(A, B, C)                                                                      \
         {                                                                                        \
             _Pragma("unroll") for (int i = 0; i < 4; ++i)                                        \
                 _Pragma("unroll") for (int a = 0; a < KH; ++a)                                   \
                     _Pragma("unroll") for (int b = 0; b < KW; ++b) {                             \
                         const int c = i + b;                                                     \
-                        const float bv = c < 4 ? B[2 * a][c] : B[2 * a + 1][c - 4];              \
+                        const float bv = c < 4 ? B[a][c] : C[a][c - 4];                          \
                         acc[a * KW + b] = __builtin_amdgcn_mfma_f32_32x32x2f32(A[i], bv, acc[a * KW + b], 0, 0, 0); \
                     }                                                                            \
             __builtin_amdgcn_sched_barrier(0);                                                   \
         }
-        f32x4 A0, A1, B0[2 * KH], B1[2 * KH];
-        DK_WGQ_LOAD(A0, B0)
+        f32x4 A0, A1, B0[KH], B1[KH];
+        f32x2 C0[KH], C1[KH];
+        DK_WGQ_LOAD(A0, B0, C0)
         int f = 0;
         for (; f + 2 <= total; f += 2) {
             DK_WGQ_ADVANCE()
-            DK_WGQ_LOAD(A1, B1)
-            DK_WGQ_MMA(A0, B0)
+            DK_WGQ_LOAD(A1, B1, C1)
+            DK_WGQ_MMA(A0, B0, C0)
             DK_WGQ_ADVANCE()
-            DK_WGQ_LOAD(A0, B0)
-            DK_WGQ_MMA(A1, B1)
+            DK_WGQ_LOAD(A0, B0, C0)
+            DK_WGQ_MMA(A1, B1, C1)
         }
-        if (f < total) DK_WGQ_MMA(A0, B0)    // odd number of steps in the tile
+        if (f < total) DK_WGQ_MMA(A0, B0, C0)    // odd number of steps in the tile
 #undef DK_WGQ_ADVANCE
 #undef DK_WGQ_LOAD
 #undef DK_WGQ_MMA
@@ -463,6 +510,7 @@ inline int round_up(int v, int a) { return (v + a - 1) / a * a; }
 
 constexpr int DSLOT4 = 6, PSLOT4 = 10, DSLOTQ = 6, PSLOTQ = 11;
 constexpr size_t LDS_LIMIT = 150 * 1024;     // of the 160 KB a compute unit has
+constexpr size_t DUMP_BYTES = 1024;          // behind the buffers: where unused copy slots store
 
 template <class KernelT>
 dk_status launch_one(KernelT kernel, const dk_wgpatch_params &p, size_t lds_bytes, hipStream_t st,
@@ -473,7 +521,7 @@ dk_status launch_one(KernelT kernel, const dk_wgpatch_params &p, size_t lds_byte
     if (!allowed) {
         DK_REQUIRE(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)LDS_LIMIT) == hipSuccess, DK_ERR_HIP);
+                                       (int)(LDS_LIMIT + DUMP_BYTES)) == hipSuccess, DK_ERR_HIP);
         allowed = true;
     }
     const long long blocks = (long long)p.tiles_co * p.tiles_ci * p.splits;
@@ -578,7 +626,7 @@ bool dk_patch_wgrad_plan(const dk_geom &g, long long R, bool aligned16, dk_wgpat
     p.p_slots = 64 * p.NI * p.PH * p.XV;
     p.ad_floats = round_up(64 * p.LDQ, 4);
     p.buf_floats = p.ad_floats + round_up(64 * p.CPLANE, 4);
-    pl->lds_bytes = 2 * (size_t)p.buf_floats * 4;
+    pl->lds_bytes = 2 * (size_t)p.buf_floats * 4 + DUMP_BYTES;
     p.row_blocks = (g.Ho + p.TR - 1) / p.TR;
     p.n_ptiles = (int)((R + p.NI - 1) / p.NI) * p.row_blocks;
     p.tiles_co = (g.Co + 63) / 64;
