@@ -20,6 +20,7 @@ namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 // Repack W[Co][Ci][KH][KW] -> wp[chunk][row][Co_pad], row = 2*step + h with
 // step = (c' * KH + a) * KW + b and channel = chunk*CB + c' + h*CB/2; zero
@@ -258,9 +259,22 @@ __global__ __launch_bounds__(256) void pack_filters_quad_kernel(const float *__r
 // multiples of 4).  A wave owns TM*32 output channels x 128 consecutive output
 // pixels as four 32-column MFMA blocks, block t taking the pixels = t (mod 4):
 // lane j then needs, for filter row a and the three filter columns, patch
-// columns 4j .. 4j+5 -- two aligned 16-byte reads that feed 3 steps x 4 blocks.
-// The filter tile is stored [co][step] so that four steps of a lane are one
-// 16-byte read too: about 0.2 LDS instructions per MFMA instead of one.
+// columns 4j .. 4j+5 -- an aligned 16-byte and an 8-byte read that feed 3 steps
+// x 4 blocks.  The filter tile is stored [co][step] so that four steps of a lane
+// are one 16-byte read too: about 0.2 LDS instructions per MFMA instead of one.
+//
+// Vector-ALU instructions of a wave that is copying queue behind the matrix
+// instructions of the other waves on its SIMD, so the copy costs none per
+// chunk: global reads are buffer loads (wave-uniform base in a scalar resource,
+// the lane's byte offset precomputed; a slot outside the image or beyond the
+// tile gets an offset past the resource's range and so reads as zero), LDS
+// addresses are precomputed, and an unused slot stores into a dump area behind
+// the tiles.  Only a last chunk with fewer than 8 channels tests its channels.
+// Operands of the next filter row are read from LDS before the MFMAs of the
+// current one are issued.
+constexpr int DK_FWD_RSRC_FLAGS = 0x00020000;     // raw buffer resource, gfx9 family
+constexpr unsigned DK_FWD_RANGE = 0x80000000u;    // resource range in bytes; offsets beyond read 0
+
 template <int TM, int WM, int WN, int MAXSLOT>
 __global__ __launch_bounds__(64 * WM * WN) void conv_quad_fwd_kernel(dk_patch_params p)
 {
@@ -278,6 +292,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_quad_fwd_kernel(dk_patch_pa
     const int li = lane & 31, lh = lane >> 5;
     const int wm0 = (wave % WM) * (TM * 32);
     const int wn0 = (wave / WM) * 128;
+    float *const dump = As + BM * WP + lane * 4;    // 1 KB behind the filter tile
 
     const int tiles = p.tiles_m * p.tiles_n;
     const int split = blockIdx.x / tiles;
@@ -315,7 +330,10 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_quad_fwd_kernel(dk_patch_pa
         ooff = img_l * p.Co * p.HoWo + pix;
     }
 
-    int goff[MAXSLOT], loff[MAXSLOT], cch[MAXSLOT];
+    // copy slots of this lane, the same for every channel chunk
+    unsigned goff[MAXSLOT];       // byte offset from the chunk's first channel, or out of range
+    float *pdst[MAXSLOT];
+    int cch[MAXSLOT];
 #pragma unroll
     for (int e = 0; e < MAXSLOT; ++e) {
         const int idx = tid + e * NT;
@@ -326,10 +344,21 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_quad_fwd_kernel(dk_patch_pa
         const int c = t2 % CB;
         const int img_l = t2 / CB;
         const int ih = ih_a + prow;
-        const bool act = idx < p.patch_slots && r0 + img_l < p.R && ih >= 0 && ih < p.H;
-        goff[e] = act ? img_l * p.img_g + (c * p.H + ih) * p.W + xv * 4 : -1;
-        loff[e] = img_l * CB * p.PLANE + c * p.PLANE + prow * p.PW + p.LPAD + xv * 4;
+        const bool slot = idx < p.patch_slots;
+        const bool act = slot && r0 + img_l < p.R && ih >= 0 && ih < p.H;
+        goff[e] = act ? 4u * (unsigned)(img_l * p.img_g + (c * p.H + ih) * p.W + xv * 4) : DK_FWD_RANGE;
+        // a slot outside the image still stores (zeros): the border stays clean
+        pdst[e] = slot ? patch + img_l * CB * p.PLANE + c * p.PLANE + prow * p.PW + p.LPAD + xv * 4 : dump;
         cch[e] = c;
+    }
+    unsigned woff[WSLOT];
+    float *wdst[WSLOT];
+#pragma unroll
+    for (int e = 0; e < WSLOT; ++e) {
+        const int idx = tid + e * NT;
+        const int row = idx / 18, c4 = idx - row * 18;
+        woff[e] = idx < W4 ? 4u * (unsigned)(row * p.w_row + c4 * 4) : DK_FWD_RANGE;
+        wdst[e] = idx < W4 ? As + row * WP + c4 * 4 : dump;
     }
 
     for (int i = tid; i < p.patch_floats; i += NT) patch[i] = 0.0f;
@@ -353,20 +382,22 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_quad_fwd_kernel(dk_patch_pa
 #define DK_QUAD_FETCH(CH)                                                                        \
     {                                                                                            \
         const int ci0_ = (CH) * CB;                                                              \
-        const float *src_ = xbase + (long long)ci0_ * p.H * p.W;                                 \
-        _Pragma("unroll") for (int e = 0; e < MAXSLOT; ++e) {                                    \
-            const bool ok_ = goff[e] >= 0 && ci0_ + cch[e] < p.Ci;                               \
-            f32x4 v_ = {0.f, 0.f, 0.f, 0.f};                                                     \
-            if (ok_) v_ = *reinterpret_cast<const f32x4 *>(src_ + goff[e]);                      \
-            pst[e] = v_;                                                                         \
+        const __amdgpu_buffer_rsrc_t rx_ = __builtin_amdgcn_make_buffer_rsrc(                     \
+            const_cast<float *>(xbase + (long long)ci0_ * p.H * p.W), 0, (int)DK_FWD_RANGE, DK_FWD_RSRC_FLAGS); \
+        if (ci0_ + CB <= p.Ci) {                                                                 \
+            _Pragma("unroll") for (int e = 0; e < MAXSLOT; ++e)                                  \
+                pst[e] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rx_, (int)goff[e], 0, 0)); \
+        } else {                                                                                 \
+            _Pragma("unroll") for (int e = 0; e < MAXSLOT; ++e) {                                \
+                const unsigned o_ = ci0_ + cch[e] < p.Ci ? goff[e] : DK_FWD_RANGE;               \
+                pst[e] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rx_, (int)o_, 0, 0)); \
+            }                                                                                    \
         }                                                                                        \
-        const float *wsrc_ = p.wp + (long long)(CH) * p.w_chunk + (long long)co0 * p.w_row;      \
-        _Pragma("unroll") for (int e = 0; e < WSLOT; ++e) {                                      \
-            int idx_ = tid + e * NT;                                                             \
-            if (idx_ >= W4) idx_ = W4 - 1;                                                       \
-            const int row_ = idx_ / 18, c4_ = idx_ - row_ * 18;                                  \
-            wst[e] = *reinterpret_cast<const f32x4 *>(wsrc_ + (long long)row_ * p.w_row + c4_ * 4); \
-        }                                                                                        \
+        const __amdgpu_buffer_rsrc_t rw_ = __builtin_amdgcn_make_buffer_rsrc(                     \
+            const_cast<float *>(p.wp + (long long)(CH) * p.w_chunk + (long long)co0 * p.w_row), 0, \
+            (int)DK_FWD_RANGE, DK_FWD_RSRC_FLAGS);                                               \
+        _Pragma("unroll") for (int e = 0; e < WSLOT; ++e)                                        \
+            wst[e] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rw_, (int)woff[e], 0, 0)); \
     }
 
     if (ch0 < ch1) DK_QUAD_FETCH(ch0)
@@ -374,45 +405,59 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_quad_fwd_kernel(dk_patch_pa
         __syncthreads();            // previous chunk fully consumed (and the zero fill done)
 #pragma unroll
         for (int e = 0; e < MAXSLOT; ++e) {
-            if (goff[e] < 0) continue;
-            float *d = patch + loff[e];          // `pad` columns off 16-byte alignment
+            float *d = pdst[e];                  // `pad` columns off 16-byte alignment
             d[0] = pst[e].x; d[1] = pst[e].y; d[2] = pst[e].z; d[3] = pst[e].w;
         }
 #pragma unroll
-        for (int e = 0; e < WSLOT; ++e) {
-            const int idx = tid + e * NT;
-            const int row = idx / 18, c4 = idx - row * 18;
-            if (idx < W4) *reinterpret_cast<f32x4 *>(As + row * WP + c4 * 4) = wst[e];
-        }
+        for (int e = 0; e < WSLOT; ++e) *reinterpret_cast<f32x4 *>(wdst[e]) = wst[e];
         __syncthreads();
         if (ch + 1 < ch1) DK_QUAD_FETCH(ch + 1)   // in flight during the MFMA loop
 
         const float *a_s = As + (wm0 + li) * WP + lh * 36;
         const float *pb = patch + fbase;
-        f32x4 aq[TM];
+        // group g = (cp, a): three steps (b = 0..2) on one patch row; its six
+        // columns are read one group ahead, the filter quads one quad ahead
+        // (filter quad q = steps 4q .. 4q+3 lives in buffer q % 3: a group touches
+        // at most two quads and the one after them is being read meanwhile)
+        f32x4 wq[2];
+        f32x2 wh[2];
+        f32x4 aq[3][TM];
+        wq[0] = *reinterpret_cast<const f32x4 *>(pb);
+        wh[0] = *reinterpret_cast<const f32x2 *>(pb + 4);
 #pragma unroll
-        for (int cp = 0; cp < CB / 2; ++cp)
+        for (int mi = 0; mi < TM; ++mi) aq[0][mi] = *reinterpret_cast<const f32x4 *>(a_s + mi * 32 * WP);
 #pragma unroll
-            for (int a = 0; a < 3; ++a) {
-                const float *pr = pb + cp * p.PLANE + a * p.PW;
-                const f32x4 w0 = *reinterpret_cast<const f32x4 *>(pr);
-                const f32x4 w1 = *reinterpret_cast<const f32x4 *>(pr + 4);
-                const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-#pragma unroll
-                for (int b = 0; b < 3; ++b) {
-                    const int s = (cp * 3 + a) * 3 + b;
-                    if (s % 4 == 0) {
-#pragma unroll
-                        for (int mi = 0; mi < TM; ++mi)
-                            aq[mi] = *reinterpret_cast<const f32x4 *>(a_s + mi * 32 * WP + s);
-                    }
+        for (int g = 0; g < 12; ++g) {
+            if (g + 1 < 12) {
+                const int cpn = (g + 1) / 3, an = (g + 1) % 3;
+                const float *pr = pb + cpn * p.PLANE + an * p.PW;
+                wq[(g + 1) & 1] = *reinterpret_cast<const f32x4 *>(pr);
+                wh[(g + 1) & 1] = *reinterpret_cast<const f32x2 *>(pr + 4);
+            }
+            {
+                const int qn = (3 * g + 2) / 4 + 1;                   // quad after this group's last
+                const int qp = g ? (3 * (g - 1) + 2) / 4 + 1 : 0;     // what the group before fetched
+                if (qn != qp && qn < 9) {
 #pragma unroll
                     for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-                        for (int tt = 0; tt < 4; ++tt)
-                            acc[mi][tt] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[mi][s % 4], w[tt + b], acc[mi][tt], 0, 0, 0);
+                        aq[qn % 3][mi] = *reinterpret_cast<const f32x4 *>(a_s + mi * 32 * WP + 4 * qn);
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);   // the reads go out before this group's MFMAs
+            const f32x4 w0 = wq[g & 1];
+            const f32x2 w1 = wh[g & 1];
+            const float w[6] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y};
+#pragma unroll
+            for (int b = 0; b < 3; ++b) {
+                const int s = 3 * g + b;
+#pragma unroll
+                for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+                    for (int tt = 0; tt < 4; ++tt)
+                        acc[mi][tt] = __builtin_amdgcn_mfma_f32_32x32x2f32(aq[(s / 4) % 3][mi][s % 4], w[tt + b], acc[mi][tt], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 #undef DK_QUAD_FETCH
 
@@ -558,6 +603,9 @@ bool plan_quad(const dk_geom &g, long long R, dk_patch_plan *pl)
         rows_spanned = g.Ho;
         if ((long long)p.IPT * g.n >= (1ll << 30)) return false;
     }
+    // the copy addresses a tile through 32-bit byte offsets below 2^31
+    if ((long long)(n_img - 1) * g.n + 8ll * g.H * g.W >= (1ll << 29)) return false;
+    if (128ll * 9 * g.Ci >= (1ll << 29)) return false;
     p.tiles_m = (g.Co + C::bm - 1) / C::bm;
     p.Co_pad = p.tiles_m * C::bm;
     p.LPAD = g.pad;                      // output pixel wo sits over patch columns wo..wo+2
@@ -571,7 +619,7 @@ bool plan_quad(const dk_geom &g, long long R, dk_patch_plan *pl)
     p.XV = g.W / 4;
     p.patch_slots = n_img * C::cb * p.PH * p.XV;
     if ((p.patch_slots + C::NT - 1) / C::NT > C::MAXSLOT) return false;
-    pl->lds_bytes = (size_t)(p.patch_floats + C::bm * 76) * sizeof(float);
+    pl->lds_bytes = (size_t)(p.patch_floats + C::bm * 76) * sizeof(float) + 1024;   // + dump area
     if (pl->lds_bytes > 64 * 1024) return false;
     p.n_chunks = (g.Ci + C::cb - 1) / C::cb;
     const dk_split_plan sp = dk_plan_split((long long)p.tiles_m * p.tiles_n, p.n_chunks, R * g.m, C::STEP_US);
