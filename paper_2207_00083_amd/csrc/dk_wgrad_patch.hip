@@ -28,6 +28,135 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 // last word of a raw (untyped, unstrided) buffer resource on gfx9-family parts
 constexpr int DK_BUFFER_RSRC_FLAGS = 0x00020000;
 
+// The copy waves (waves 4-7) of the weight-gradient kernels: tile pt of the
+// workgroup's range goes to LDS buffer (pt - pt0) & 1 while the MFMA waves work
+// on the other buffer; one barrier per tile hands the buffers over.  DVEC /
+// PVEC: the dtilde tile / the patch take 16-byte LDS stores (else four 4-byte
+// ones: odd pitch, or a position one column off alignment).
+template <int DSLOT, int PSLOT, bool DVEC, bool PVEC>
+__device__ __forceinline__ void wg_copy_waves(const dk_wgpatch_params &p, float *lds, int tid, int co0,
+                                              int ci0, int pt0, int pt1)
+{
+    constexpr int NP = 256;
+    // Vector-ALU instructions of this wave queue behind the matrix
+    // instructions of the MFMA wave on the same SIMD (measured: about one
+    // issue slot per MFMA), so a tile must cost as few of them as possible.
+    // Everything a lane needs is computed once: byte offsets from a
+    // wave-uniform base for the loads, LDS addresses in both buffers for the
+    // stores (an unused slot loads offset 0 and stores into a dump area
+    // behind the buffers, so nothing is predicated).  The tile position
+    // advances in scalar registers, and a tile that lies wholly inside its
+    // images and their rows is copied without any test.
+    if constexpr (DVEC) __builtin_amdgcn_s_setprio(3);   // (measured: helps the 16-byte-read kernel, hurts the other)
+    const int ptid = tid - 256;
+    float *const dump = lds + 2 * p.buf_floats + (ptid & 63) * 4;
+    unsigned d_g[DSLOT], p_g[PSLOT];          // byte offsets
+    float *d_l[2][DSLOT], *p_l[2][PSLOT];
+    int d_m[DSLOT], p_m[PSLOT];
+#pragma unroll
+    for (int e = 0; e < DSLOT; ++e) {
+        const int idx = ptid + e * NP;
+        const int dv = idx % p.DV;
+        const int t1 = idx / p.DV;
+        const int img_l = t1 % p.NI;
+        const int co_l = t1 / p.NI;
+        const bool act = idx < p.d_slots && co0 + co_l < p.Co;
+        d_g[e] = act ? 4u * (unsigned)((img_l * p.Co + co_l) * p.HoWo + dv * 4) : 0u;
+        const int l = co_l * p.LDQ + img_l * p.TR * p.Wo + dv * 4;
+        d_l[0][e] = act ? lds + l : dump;
+        d_l[1][e] = act ? lds + p.buf_floats + l : dump;
+        d_m[e] = act ? (img_l | (dv * 4) << 8) : -1;
+    }
+#pragma unroll
+    for (int e = 0; e < PSLOT; ++e) {
+        const int idx = ptid + e * NP;
+        const int xv = idx % p.XV;
+        const int t1 = idx / p.XV;
+        const int prow = t1 % p.PH;
+        const int t2 = t1 / p.PH;
+        const int img_l = t2 % p.NI;
+        const int c_l = t2 / p.NI;
+        const bool act = idx < p.p_slots && ci0 + c_l < p.Ci;
+        p_g[e] = act ? 4u * (unsigned)((img_l * p.Ci + c_l) * p.H * p.W + prow * p.W + xv * 4) : 0u;
+        const int l = p.ad_floats + c_l * p.CPLANE + img_l * p.PLANE + prow * p.PW + p.LPAD + xv * 4;
+        p_l[0][e] = act ? lds + l : dump;
+        p_l[1][e] = act ? lds + p.buf_floats + l : dump;
+        p_m[e] = act ? (img_l | prow << 8) : -1;
+    }
+    int ig = pt0 / p.row_blocks, rb = pt0 - ig * p.row_blocks;
+    // tile pt goes to buffer (pt - pt0) & 1: two tiles per trip, so that the
+    // buffer is known at compile time
+    auto copy_tile = [&](auto bufc) {
+        constexpr int BUF = decltype(bufc)::value;
+        const int r0 = ig * p.NI, row0 = rb * p.TR;
+        const char *dsrc = reinterpret_cast<const char *>(
+            p.dt + ((long long)r0 * p.Co + co0) * p.HoWo + (long long)row0 * p.Wo);
+        const int ih_a = row0 - p.pad;
+        const char *psrc = reinterpret_cast<const char *>(
+            p.x + ((long long)r0 * p.Ci + ci0) * p.H * p.W + (long long)ih_a * p.W);
+        f32x4 dst_[DSLOT], pst_[PSLOT];
+        const bool clean = r0 + p.NI <= p.R && row0 + p.TR <= p.Ho && ih_a >= 0 && ih_a + p.PH <= p.H;
+        if (clean) {
+            // buffer loads: wave-uniform base in a scalar resource, the lane's
+            // byte offset as it is -- no address arithmetic on the vector ALU
+            const __amdgpu_buffer_rsrc_t rd =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(dsrc), 0, -1, DK_BUFFER_RSRC_FLAGS);
+            const __amdgpu_buffer_rsrc_t rp =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(psrc), 0, -1, DK_BUFFER_RSRC_FLAGS);
+#pragma unroll
+            for (int e = 0; e < DSLOT; ++e)
+                dst_[e] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rd, (int)d_g[e], 0, 0));
+#pragma unroll
+            for (int e = 0; e < PSLOT; ++e)
+                pst_[e] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rp, (int)p_g[e], 0, 0));
+        } else {
+            // out of range for this tile: read the tile's first element, store zero
+            const int qlim = p.HoWo - row0 * p.Wo;
+            const int ilim = p.R - r0;
+            const char *psrc0 = reinterpret_cast<const char *>(p.x + ((long long)r0 * p.Ci + ci0) * p.H * p.W);
+            const int poffb = 4 * ih_a * p.W;
+#pragma unroll
+            for (int e = 0; e < DSLOT; ++e) {
+                const bool ok = d_m[e] >= 0 && (d_m[e] & 255) < ilim && (d_m[e] >> 8) < qlim;
+                const f32x4 v = *reinterpret_cast<const f32x4 *>(dsrc + (ok ? d_g[e] : 0u));
+                dst_[e] = ok ? v : f32x4(0.0f);
+            }
+#pragma unroll
+            for (int e = 0; e < PSLOT; ++e) {
+                const int ih = ih_a + (p_m[e] >> 8);
+                const bool ok = p_m[e] >= 0 && (p_m[e] & 255) < ilim && ih >= 0 && ih < p.H;
+                const f32x4 v = *reinterpret_cast<const f32x4 *>(psrc0 + (ok ? (unsigned)((int)p_g[e] + poffb) : 0u));
+                pst_[e] = ok ? v : f32x4(0.0f);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < DSLOT; ++e) {
+            if constexpr (DVEC) {
+                *reinterpret_cast<f32x4 *>(d_l[BUF][e]) = dst_[e];
+            } else {
+                float *d = d_l[BUF][e];           // odd pitch
+                d[0] = dst_[e].x; d[1] = dst_[e].y; d[2] = dst_[e].z; d[3] = dst_[e].w;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < PSLOT; ++e) {
+            if constexpr (PVEC) {
+                *reinterpret_cast<f32x4 *>(p_l[BUF][e]) = pst_[e];
+            } else {
+                float *d = p_l[BUF][e];           // one column off 16-byte alignment
+                d[0] = pst_[e].x; d[1] = pst_[e].y; d[2] = pst_[e].z; d[3] = pst_[e].w;
+            }
+        }
+        if (++rb == p.row_blocks) { rb = 0; ++ig; }
+        __syncthreads();     // this tile is in LDS; the one before has been consumed
+    };
+    for (int pt = pt0; pt < pt1; pt += 2) {
+        copy_tile(std::integral_constant<int, 0>());
+        if (pt + 1 < pt1) copy_tile(std::integral_constant<int, 1>());
+    }
+    if (pt0 < pt1) __syncthreads();   // matches the MFMA waves' last barrier
+}
+
 template <int KH, int KW, int DSLOT, int PSLOT>
 __global__ __launch_bounds__(512) void conv_patch_wgrad_kernel(dk_wgpatch_params p)
 {
@@ -58,82 +187,7 @@ __global__ __launch_bounds__(512) void conv_patch_wgrad_kernel(dk_wgpatch_params
     __syncthreads();
 
     if (producer) {
-        const int ptid = tid - 256;
-        // copy slots of this lane: tile-independent global / LDS offsets and a
-        // packed (image-in-tile | position << 8), or -1 for an unused slot
-        unsigned d_g[DSLOT];
-        int d_l[DSLOT], d_m[DSLOT];
-#pragma unroll
-        for (int e = 0; e < DSLOT; ++e) {
-            const int idx = ptid + e * NP;
-            const int dv = idx % p.DV;
-            const int t1 = idx / p.DV;
-            const int img_l = t1 % p.NI;
-            const int co_l = t1 / p.NI;
-            const bool act = idx < p.d_slots && co0 + co_l < p.Co;
-            d_g[e] = (unsigned)((img_l * p.Co + co_l) * p.HoWo + dv * VEC);
-            d_l[e] = co_l * p.LDQ + img_l * p.TR * p.Wo + dv * VEC;
-            d_m[e] = act ? (img_l | (dv * VEC) << 8) : -1;
-        }
-        int p_g[PSLOT], p_l[PSLOT], p_m[PSLOT];
-#pragma unroll
-        for (int e = 0; e < PSLOT; ++e) {
-            const int idx = ptid + e * NP;
-            const int xv = idx % p.XV;
-            const int t1 = idx / p.XV;
-            const int prow = t1 % p.PH;
-            const int t2 = t1 / p.PH;
-            const int img_l = t2 % p.NI;
-            const int c_l = t2 / p.NI;
-            const bool act = idx < p.p_slots && ci0 + c_l < p.Ci;
-            p_g[e] = (img_l * p.Ci + c_l) * p.H * p.W + prow * p.W + xv * VEC;
-            p_l[e] = p.ad_floats + c_l * p.CPLANE + img_l * p.PLANE + prow * p.PW + p.LPAD + xv * VEC;
-            p_m[e] = act ? (img_l | prow << 8) : -1;
-        }
-
-        // tile pt goes to buffer (pt - pt0) & 1; the copy of tile pt+1 overlaps
-        // the MFMA waves' work on tile pt
-        for (int pt = pt0; pt < pt1; ++pt) {
-            float *buf = lds + ((pt - pt0) & 1) * p.buf_floats;
-            const int ig = pt / p.row_blocks;
-            const int rb = pt - ig * p.row_blocks;
-            const int r0 = ig * p.NI, row0 = rb * p.TR;
-            const int qlim = p.HoWo - row0 * p.Wo;   // pixels left in the image from row0
-            const int ilim = p.R - r0;               // images left
-            const float *dsrc = p.dt + ((long long)r0 * p.Co + co0) * p.HoWo + (long long)row0 * p.Wo;
-            const int ih_a = row0 * STRIDE - p.pad;
-            const float *psrc = p.x + ((long long)r0 * p.Ci + ci0) * p.H * p.W;
-            const int poff = ih_a * p.W;
-            // every load goes to uniform base + 32-bit lane offset; a slot that is
-            // out of range for this tile reads offset 0 and is written as zero
-            stage_t dst_[DSLOT], pst_[PSLOT];
-            bool dok[DSLOT], pok[PSLOT];
-#pragma unroll
-            for (int e = 0; e < DSLOT; ++e) {
-                dok[e] = d_m[e] >= 0 && (d_m[e] & 255) < ilim && (d_m[e] >> 8) < qlim;
-                dst_[e] = *reinterpret_cast<const stage_t *>(dsrc + (dok[e] ? d_g[e] : 0u));
-            }
-#pragma unroll
-            for (int e = 0; e < PSLOT; ++e) {
-                const int ih = ih_a + (p_m[e] >> 8);
-                pok[e] = p_m[e] >= 0 && (p_m[e] & 255) < ilim && ih >= 0 && ih < p.H;
-                pst_[e] = *reinterpret_cast<const stage_t *>(psrc + (pok[e] ? (unsigned)(p_g[e] + poff) : 0u));
-            }
-#pragma unroll
-            for (int e = 0; e < DSLOT; ++e) {
-                if (d_m[e] < 0) continue;
-                float *d = buf + d_l[e];
-                const stage_t v = dok[e] ? dst_[e] : stage_t(0.0f);
-                d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
-            }
-#pragma unroll
-            for (int e = 0; e < PSLOT; ++e) {
-                if (p_m[e] < 0) continue;
-                *reinterpret_cast<stage_t *>(buf + p_l[e]) = pok[e] ? pst_[e] : stage_t(0.0f);
-            }
-            __syncthreads();     // tile pt is in LDS; tile pt-1 has been consumed
-        }
-        if (pt0 < pt1) __syncthreads();   // matches the MFMA waves' last barrier
+        wg_copy_waves<DSLOT, PSLOT, false, true>(p, lds, tid, co0, ci0, pt0, pt1);
         return;
     }
 
@@ -234,15 +288,16 @@ __global__ __launch_bounds__(512) void conv_patch_wgrad_kernel(dk_wgpatch_params
     }
 }
 
-// Same contraction for stride 1 and output widths that are a multiple of 8,
-// with 16-byte LDS reads.  Handing single floats from LDS to the matrix pipe
+// Same contraction for stride 1 and output widths that are a multiple of 8
+// (or of 4, with an even number of output rows), with 16-byte LDS reads.  Handing single floats from LDS to the matrix pipe
 // costs one LDS instruction per operand and those, not the MFMAs, then set the
 // pace.  Here the two half-waves take the left and the right half of an output
 // row instead of even and odd pixels, so four consecutive pixels of a half are
 // one aligned 16-byte read of dtilde, and the three filter columns of those four
 // pixels lie in two aligned 16-byte reads of the patch row (the patch is stored
 // with `pad` columns of left border, which puts output pixel wo over patch
-// columns wo..wo+2).  Seven LDS instructions feed 36 MFMAs.
+// columns wo..wo+2).  Seven LDS instructions feed 36 MFMAs.  For widths that are
+// not a multiple of 8 the half-waves take the even and the odd rows instead.
 template <int DSLOT, int PSLOT>
 __global__ __launch_bounds__(512) void conv_quad_wgrad_kernel(dk_wgpatch_params p)
 {
@@ -267,112 +322,7 @@ __global__ __launch_bounds__(512) void conv_quad_wgrad_kernel(dk_wgpatch_params 
     __syncthreads();
 
     if (producer) {
-        // Vector-ALU instructions of this wave queue behind the matrix
-        // instructions of the MFMA wave on the same SIMD (measured: about one
-        // issue slot per MFMA), so a tile must cost as few of them as possible.
-        // Everything a lane needs is computed once: byte offsets from a
-        // wave-uniform base for the loads, LDS addresses in both buffers for the
-        // stores (an unused slot loads offset 0 and stores into a dump area
-        // behind the buffers, so nothing is predicated).  The tile position
-        // advances in scalar registers, and a tile that lies wholly inside its
-        // images and their rows is copied without any test.
-        __builtin_amdgcn_s_setprio(3);
-        const int ptid = tid - 256;
-        float *const dump = lds + 2 * p.buf_floats + (ptid & 63) * 4;
-        unsigned d_g[DSLOT], p_g[PSLOT];          // byte offsets
-        float *d_l[2][DSLOT], *p_l[2][PSLOT];
-        int d_m[DSLOT], p_m[PSLOT];
-#pragma unroll
-        for (int e = 0; e < DSLOT; ++e) {
-            const int idx = ptid + e * NP;
-            const int dv = idx % p.DV;
-            const int t1 = idx / p.DV;
-            const int img_l = t1 % p.NI;
-            const int co_l = t1 / p.NI;
-            const bool act = idx < p.d_slots && co0 + co_l < p.Co;
-            d_g[e] = act ? 4u * (unsigned)((img_l * p.Co + co_l) * p.HoWo + dv * 4) : 0u;
-            const int l = co_l * p.LDQ + img_l * p.TR * p.Wo + dv * 4;
-            d_l[0][e] = act ? lds + l : dump;
-            d_l[1][e] = act ? lds + p.buf_floats + l : dump;
-            d_m[e] = act ? (img_l | (dv * 4) << 8) : -1;
-        }
-#pragma unroll
-        for (int e = 0; e < PSLOT; ++e) {
-            const int idx = ptid + e * NP;
-            const int xv = idx % p.XV;
-            const int t1 = idx / p.XV;
-            const int prow = t1 % p.PH;
-            const int t2 = t1 / p.PH;
-            const int img_l = t2 % p.NI;
-            const int c_l = t2 / p.NI;
-            const bool act = idx < p.p_slots && ci0 + c_l < p.Ci;
-            p_g[e] = act ? 4u * (unsigned)((img_l * p.Ci + c_l) * p.H * p.W + prow * p.W + xv * 4) : 0u;
-            const int l = p.ad_floats + c_l * p.CPLANE + img_l * p.PLANE + prow * p.PW + p.LPAD + xv * 4;
-            p_l[0][e] = act ? lds + l : dump;
-            p_l[1][e] = act ? lds + p.buf_floats + l : dump;
-            p_m[e] = act ? (img_l | prow << 8) : -1;
-        }
-        int ig = pt0 / p.row_blocks, rb = pt0 - ig * p.row_blocks;
-        // tile pt goes to buffer (pt - pt0) & 1: two tiles per trip, so that the
-        // buffer is known at compile time
-        auto copy_tile = [&](auto bufc) {
-            constexpr int BUF = decltype(bufc)::value;
-            const int r0 = ig * p.NI, row0 = rb * p.TR;
-            const char *dsrc = reinterpret_cast<const char *>(
-                p.dt + ((long long)r0 * p.Co + co0) * p.HoWo + (long long)row0 * p.Wo);
-            const int ih_a = row0 - p.pad;
-            const char *psrc = reinterpret_cast<const char *>(
-                p.x + ((long long)r0 * p.Ci + ci0) * p.H * p.W + (long long)ih_a * p.W);
-            f32x4 dst_[DSLOT], pst_[PSLOT];
-            const bool clean = r0 + p.NI <= p.R && row0 + p.TR <= p.Ho && ih_a >= 0 && ih_a + p.PH <= p.H;
-            if (clean) {
-                // buffer loads: wave-uniform base in a scalar resource, the lane's
-                // byte offset as it is -- no address arithmetic on the vector ALU
-                const __amdgpu_buffer_rsrc_t rd =
-                    __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(dsrc), 0, -1, DK_BUFFER_RSRC_FLAGS);
-                const __amdgpu_buffer_rsrc_t rp =
-                    __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(psrc), 0, -1, DK_BUFFER_RSRC_FLAGS);
-#pragma unroll
-                for (int e = 0; e < DSLOT; ++e)
-                    dst_[e] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rd, (int)d_g[e], 0, 0));
-#pragma unroll
-                for (int e = 0; e < PSLOT; ++e)
-                    pst_[e] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rp, (int)p_g[e], 0, 0));
-            } else {
-                // out of range for this tile: read the tile's first element, store zero
-                const int qlim = p.HoWo - row0 * p.Wo;
-                const int ilim = p.R - r0;
-                const char *psrc0 = reinterpret_cast<const char *>(p.x + ((long long)r0 * p.Ci + ci0) * p.H * p.W);
-                const int poffb = 4 * ih_a * p.W;
-#pragma unroll
-                for (int e = 0; e < DSLOT; ++e) {
-                    const bool ok = d_m[e] >= 0 && (d_m[e] & 255) < ilim && (d_m[e] >> 8) < qlim;
-                    const f32x4 v = *reinterpret_cast<const f32x4 *>(dsrc + (ok ? d_g[e] : 0u));
-                    dst_[e] = ok ? v : f32x4(0.0f);
-                }
-#pragma unroll
-                for (int e = 0; e < PSLOT; ++e) {
-                    const int ih = ih_a + (p_m[e] >> 8);
-                    const bool ok = p_m[e] >= 0 && (p_m[e] & 255) < ilim && ih >= 0 && ih < p.H;
-                    const f32x4 v = *reinterpret_cast<const f32x4 *>(psrc0 + (ok ? (unsigned)((int)p_g[e] + poffb) : 0u));
-                    pst_[e] = ok ? v : f32x4(0.0f);
-                }
-            }
-#pragma unroll
-            for (int e = 0; e < DSLOT; ++e) *reinterpret_cast<f32x4 *>(d_l[BUF][e]) = dst_[e];
-#pragma unroll
-            for (int e = 0; e < PSLOT; ++e) {
-                float *d = p_l[BUF][e];               // one column off 16-byte alignment
-                d[0] = pst_[e].x; d[1] = pst_[e].y; d[2] = pst_[e].z; d[3] = pst_[e].w;
-            }
-            if (++rb == p.row_blocks) { rb = 0; ++ig; }
-            __syncthreads();     // this tile is in LDS; the one before has been consumed
-        };
-        for (int pt = pt0; pt < pt1; pt += 2) {
-            copy_tile(std::integral_constant<int, 0>());
-            if (pt + 1 < pt1) copy_tile(std::integral_constant<int, 1>());
-        }
-        if (pt0 < pt1) __syncthreads();   // matches the MFMA waves' last barrier
+        wg_copy_waves<DSLOT, PSLOT, true, false>(p, lds, tid, co0, ci0, pt0, pt1);
         return;
     }
 
@@ -380,7 +330,14 @@ __global__ __launch_bounds__(512) void conv_quad_wgrad_kernel(dk_wgpatch_params 
     const int lane = tid & 63;
     const int li = lane & 31, lh = lane >> 5;
     const int wm0 = (wave & 1) * 32, wn0 = (wave >> 1) * 32;
-    const int half = p.Wo >> 1;              // pixels per half-row (multiple of 4)
+    // The two half-waves split every output row in a left and a right half
+    // (widths that are multiples of 8), or take the even and the odd rows of
+    // the tile (other multiples of 4; tiles then have an even number of rows
+    // per image): either way a half-wave walks whole 4-pixel steps.
+    const bool rowsplit = (p.Wo & 7) != 0;
+    const int rstep = rowsplit ? 2 : 1;
+    const int a_half = rowsplit ? p.Wo : p.Wo >> 1;     // dtilde offset of the second half-wave
+    const int b_half = rowsplit ? p.PW : p.Wo >> 1;     // patch offset of the second half-wave
 
     f32x16 acc[KK];
 #pragma unroll
@@ -389,14 +346,14 @@ __global__ __launch_bounds__(512) void conv_quad_wgrad_kernel(dk_wgpatch_params 
         for (int v = 0; v < 16; ++v) acc[k][v] = 0.0f;
 
     const int nrows = p.NI * p.TR;
-    const int nquad = half >> 2;             // 4-pixel steps per row
-    const int total = nrows * nquad;
+    const int nquad = (rowsplit ? p.Wo : p.Wo >> 1) >> 2;    // 4-pixel steps per row of a half-wave
+    const int total = (nrows / rstep) * nquad;
     if (pt0 < pt1) __syncthreads();
     for (int pt = pt0; pt < pt1; ++pt) {
         const float *Ad = lds + ((pt - pt0) & 1) * p.buf_floats;
         const float *Pt = Ad + p.ad_floats;
-        const float *a_base = Ad + (wm0 + li) * p.LDQ + lh * half;
-        const float *b_base = Pt + (wn0 + li) * p.CPLANE + lh * half;
+        const float *a_base = Ad + (wm0 + li) * p.LDQ + lh * a_half;
+        const float *b_base = Pt + (wn0 + li) * p.CPLANE + lh * b_half;
 
         // load cursor, one 4-pixel step ahead of the MFMAs; it stays on the
         // last step of the tile once it gets there
@@ -405,9 +362,9 @@ __global__ __launch_bounds__(512) void conv_quad_wgrad_kernel(dk_wgpatch_params 
 #define DK_WGQ_ADVANCE()                                                                         \
         if (ld_q + 1 < nquad) {                                                                  \
             ++ld_q;                                                                              \
-        } else if (ld_row + 1 < nrows) {                                                         \
-            ld_q = 0; ++ld_row;                                                                  \
-            if (++ld_r == p.TR) { ld_r = 0; ++ld_img; }                                          \
+        } else if (ld_row + rstep < nrows) {                                                     \
+            ld_q = 0; ld_row += rstep; ld_r += rstep;                                            \
+            if (ld_r == p.TR) { ld_r = 0; ++ld_img; }                                            \
             a_ld = a_base + ld_row * p.Wo;                                                       \
             b_ld = b_base + ld_img * p.PLANE + ld_r * p.PW;                                      \
         }
@@ -553,7 +510,9 @@ bool dk_patch_wgrad_plan(const dk_geom &g, long long R, bool aligned16, dk_wgpat
     const bool v4 = aligned16 && g.W % 4 == 0 && g.Wo % 4 == 0;
     if (!v4) return false;
     // 16-byte LDS reads need stride 1, vector copies and half-rows of whole quads
-    const bool quad = v4 && g.stride == 1 && g.Wo % 8 == 0 && g.pad <= 4;
+    // (widths that are multiples of 4 but not of 8 split the tile by rows: even row counts only)
+    const bool quad = v4 && g.stride == 1 && g.pad <= 4 && (g.Wo % 8 == 0 || g.Ho % 2 == 0);
+    const bool rowsplit = quad && g.Wo % 8 != 0;
     pl->vec = v4 ? 4 : 1;
     pl->quad = quad;
     const int dslot = quad ? DSLOTQ : DSLOT4;
@@ -589,6 +548,7 @@ bool dk_patch_wgrad_plan(const dk_geom &g, long long R, bool aligned16, dk_wgpat
             if (pass == 0 && TR > g.Ho) break;
             if (pass == 1 && (NI < 2 || NI > R || NI > 255)) { if (NI > R || NI > 255) break; else continue; }
             if (pass == 0 && v4 && (TR * g.Wo) % 4) continue;
+            if (rowsplit && TR % 2) continue;
             const int PH = (TR - 1) * g.stride + g.kh;
             const int PLANE = PH * p.PW;
             const int CPLANE = pitch(NI * PLANE);

@@ -240,6 +240,11 @@ CONV_MASKED = [
     (1, 2, 3, 16, 30, 30, 7, 2, 3),
     (8, 1, 32, 40, 2, 2, 3, 1, 1),
     (4, 2, 70, 20, 4, 4, 3, 1, 1),
+    # widths that are 4 mod 8 (weight gradient splits the tile by rows)
+    (4, 2, 40, 24, 12, 12, 3, 1, 1),
+    (2, 3, 24, 70, 20, 20, 3, 1, 1),
+    (2, 2, 32, 32, 28, 28, 3, 1, 1),
+    (3, 5, 70, 130, 4, 4, 3, 1, 1),
     # strided 1x1 (ragged sizes, stride 3)
     (2, 2, 20, 24, 9, 7, 1, 2, 0),
     (2, 2, 12, 130, 10, 10, 1, 3, 0),
