@@ -18,6 +18,24 @@
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Loader fast path.  Vector-ALU instructions of a wave that is fetching queue
+// behind the matrix instructions of the other waves on its SIMD, so the common
+// case -- a whole contraction step of an operand whose rows are whole 16-byte
+// vectors -- is fetched with buffer loads: the matrix is a scalar resource, the
+// step advances a scalar offset, and each lane keeps one precomputed byte
+// offset per vector (an offset past the resource's range for rows outside the
+// matrix, which then read as zero).  No address arithmetic, no predicates.
+constexpr int DK_RSRC_FLAGS = 0x00020000;         // raw buffer resource, gfx9 family
+constexpr unsigned DK_OOB = 0x80000000u;          // beyond any resource range used here
+constexpr long long DK_RSRC_MAX = 0x7fffffffll;   // largest operand (bytes) the fast path takes
+
+__device__ __forceinline__ float4 dk_buffer_load4(__amdgpu_buffer_rsrc_t rs, unsigned voff, unsigned soff)
+{
+    const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff, (int)soff, 0));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
 
 template <int BM_, int BN_, int BK_, int WM_, int WN_>
 struct Cfg {
@@ -55,12 +73,30 @@ struct LoadKMajor {
     static_assert(BK * PER_K % NT == 0, "tile/threads");
     float4 st[N4];
     const float *p; long long ld; int rows, kdim, row0, tid;
+    __amdgpu_buffer_rsrc_t rs; unsigned voff[N4]; bool fast;
 
     __device__ __forceinline__ void init(const Params &a, int row0_, int tid_)
-    { p = a.p; ld = a.ld; rows = a.rows; kdim = a.kdim; row0 = row0_; tid = tid_; }
+    {
+        p = a.p; ld = a.ld; rows = a.rows; kdim = a.kdim; row0 = row0_; tid = tid_;
+        const long long bytes = (long long)a.kdim * a.ld * 4;
+        fast = VEC && bytes <= DK_RSRC_MAX;
+        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
+#pragma unroll
+        for (int e = 0; e < N4; ++e) {
+            const int idx = tid + e * NT;
+            const int kr = idx / PER_K, row = row0 + (idx % PER_K) * 4;
+            voff[e] = row + 3 < rows ? 4u * (unsigned)(kr * (int)ld + row) : DK_OOB;
+        }
+    }
 
     __device__ __forceinline__ void load(int kt)
     {
+        if (fast && (kt + 1) * BK <= kdim) {
+            const unsigned soff = 4u * (unsigned)(kt * BK) * (unsigned)ld;
+#pragma unroll
+            for (int e = 0; e < N4; ++e) st[e] = dk_buffer_load4(rs, voff[e], soff);
+            return;
+        }
 #pragma unroll
         for (int e = 0; e < N4; ++e) {
             const int idx = tid + e * NT;
@@ -102,12 +138,30 @@ struct LoadRowMajorK {
     static_assert(ROWS * PER_ROW % NT == 0, "tile/threads");
     float4 st[N4];
     const float *p; long long ld; int rows, kdim, row0, tid;
+    __amdgpu_buffer_rsrc_t rs; unsigned voff[N4]; bool fast;
 
     __device__ __forceinline__ void init(const Params &a, int row0_, int tid_)
-    { p = a.p; ld = a.ld; rows = a.rows; kdim = a.kdim; row0 = row0_; tid = tid_; }
+    {
+        p = a.p; ld = a.ld; rows = a.rows; kdim = a.kdim; row0 = row0_; tid = tid_;
+        const long long bytes = (long long)a.rows * a.ld * 4;
+        fast = VEC && bytes <= DK_RSRC_MAX;
+        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
+#pragma unroll
+        for (int e = 0; e < N4; ++e) {
+            const int idx = tid + e * NT;
+            const int r = row0 + idx / PER_ROW, kc = idx % PER_ROW;
+            voff[e] = r < rows ? 4u * (unsigned)(r * (int)ld + kc * 4) : DK_OOB;
+        }
+    }
 
     __device__ __forceinline__ void load(int kt)
     {
+        if (fast && (kt + 1) * BK <= kdim) {
+            const unsigned soff = 4u * (unsigned)(kt * BK);
+#pragma unroll
+            for (int e = 0; e < N4; ++e) st[e] = dk_buffer_load4(rs, voff[e], soff);
+            return;
+        }
 #pragma unroll
         for (int e = 0; e < N4; ++e) {
             const int idx = tid + e * NT;
