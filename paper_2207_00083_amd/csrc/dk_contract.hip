@@ -427,6 +427,7 @@ struct LoadKMajorImg {
     float4 st[N4];
     const float *src[VEC ? 1 : 4];   // element (k = 0) of this lane's pixel(s); null = outside
     int C, chs, tid;
+    __amdgpu_buffer_rsrc_t rs; unsigned voff[N4]; bool fast;
 
     __device__ __forceinline__ void init(const Params &a, int q0, int tid_)
     {
@@ -437,10 +438,25 @@ struct LoadKMajorImg {
             const int qq = q + u;
             src[u] = qq < a.Q ? a.pixel(qq) : nullptr;
         }
+        // whole tensor as one resource: [R][C][chs]
+        const long long bytes = (long long)(a.Q / a.HW) * a.C * a.chs * 4;
+        fast = VEC && bytes <= DK_RSRC_MAX;
+        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
+#pragma unroll
+        for (int e = 0; e < N4; ++e) {
+            const int kr = (tid + e * NT) / PER_K;
+            voff[e] = src[0] ? 4u * (unsigned)((src[0] - a.p) + (long long)kr * chs) : DK_OOB;
+        }
     }
 
     __device__ __forceinline__ void load(int kt)
     {
+        if (fast && (kt + 1) * BK <= C) {
+            const unsigned soff = 4u * (unsigned)(kt * BK) * (unsigned)chs;
+#pragma unroll
+            for (int e = 0; e < N4; ++e) st[e] = dk_buffer_load4(rs, voff[e], soff);
+            return;
+        }
 #pragma unroll
         for (int e = 0; e < N4; ++e) {
             const int k = kt * BK + (tid + e * NT) / PER_K;
@@ -480,13 +496,44 @@ struct LoadRowMajorKImg {
     static_assert(ROWS * PER_ROW % NT == 0 && NT % PER_ROW == 0, "tile/threads");
     float4 st[N4];
     const float *p; int C, HW, Q, row0, tid;
+    // fast path: the lane's pixel quad as a cursor (pixel within its image, byte
+    // offset of (image, channel 0, pixel)) that moves on by BK pixels per step
+    __amdgpu_buffer_rsrc_t rs; unsigned roff[N4]; bool fast;
+    int cur_kt, cur_pix; unsigned cur_off;
 
     // (stride-1 layers only: chs == HW)
     __device__ __forceinline__ void init(const Params &a, int row0_, int tid_)
-    { p = a.p; C = a.C; HW = a.HW; Q = a.Q; row0 = row0_; tid = tid_; }
+    {
+        p = a.p; C = a.C; HW = a.HW; Q = a.Q; row0 = row0_; tid = tid_;
+        const long long bytes = (long long)(a.Q / a.HW) * a.C * a.HW * 4;
+        fast = VEC && bytes <= DK_RSRC_MAX && HW >= BK;
+        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
+#pragma unroll
+        for (int e = 0; e < N4; ++e) {
+            const int row = row0 + (tid + e * NT) / PER_ROW;
+            roff[e] = row < C ? 4u * (unsigned)row * (unsigned)HW : DK_OOB;
+        }
+        cur_kt = -2; cur_pix = 0; cur_off = 0;      // no step fetched yet
+    }
 
     __device__ __forceinline__ void load(int kt)
     {
+        if (fast && (kt + 1) * BK <= Q) {
+            if (cur_kt + 1 == kt) {              // the usual case: one step on
+                cur_pix += BK; cur_off += 4u * BK;
+                if (cur_pix >= HW) { cur_pix -= HW; cur_off += 4u * (unsigned)(C - 1) * (unsigned)HW; }
+            } else {
+                const int q = kt * BK + (tid % PER_ROW) * 4;
+                const int r = q / HW;
+                cur_pix = q - r * HW;
+                cur_off = 4u * ((unsigned)r * (unsigned)C * (unsigned)HW + (unsigned)cur_pix);
+            }
+            cur_kt = kt;
+#pragma unroll
+            for (int e = 0; e < N4; ++e) st[e] = dk_buffer_load4(rs, roff[e] + cur_off, 0u);
+            return;
+        }
+        cur_kt = -2;
         const int q = kt * BK + (tid % PER_ROW) * 4;
         const float *s[VEC ? 1 : 4];
 #pragma unroll
