@@ -485,6 +485,28 @@ def test_config5_last_layer_full_size_sampled(dk):
     assert out["verdict"].tolist() == [0] * G
 
 
+def test_verify_flags_tampered_stored_encodings(dk):
+    # The encodings kept for the backward pass satisfy Xbar . nvec = 0 like the
+    # forward results do: the same check, run on them before dk_wgrad, flags a
+    # group whose stored encodings were changed after the forward pass.
+    say("verify on stored encodings")
+    K, G = 4, 5
+    L = dk_inputs.conv(6, 10, 9, 9, 3, 1, 1)
+    d = _masked_case(L, K, G, seed=2024)
+    S = K + 2
+    _, nvec, _ = dk.dk_coeffs(d["A"], d["gamma"])
+    xbar = dk.dk_encode(dev(d["X"]), dev(d["r"]), dev(d["A"]), K)
+    v, rho = dk.dk_verify(xbar, dev(nvec), K, tol=1e-3)
+    assert host(v).tolist() == [0] * G and float(host(rho).max()) < 1e-4
+    xb = host(xbar).reshape(G * S, -1).copy()
+    g, j = 3, int(np.argmax(np.abs(nvec[3])))
+    xb[g * S + j, 123] += 0.5 * float(np.max(np.abs(xb[g * S:(g + 1) * S])))
+    v, rho = dk.dk_verify(dev(xb), dev(nvec), K, tol=1e-3)
+    vref, _ = oracle.verify(xb, nvec, 1e-3)
+    assert vref.tolist() == [0, 0, 0, 1, 0]
+    assert host(v).tolist() == vref.tolist()
+
+
 # ----------------------------------------------------------------------
 # error behaviour through the C ABI
 # ----------------------------------------------------------------------
