@@ -318,12 +318,46 @@ struct LoadDeltaQ {
     static_assert(NT % BK == 0 && ROWS % RSTEP == 0, "tile/threads");
     float st[NE];
     const float *p; int Co, HoWo, Q, row0, kq, rsub;
+    // fast path (whole steps): the lane's pixel as a cursor (pixel within its
+    // image, byte offset of the image) that moves on by BK pixels per step, one
+    // precomputed byte offset per row, buffer loads
+    __amdgpu_buffer_rsrc_t rs; unsigned coff[NE]; bool fast;
+    int cur_kt, cur_pix; unsigned cur_img;
 
     __device__ __forceinline__ void init(const Params &a, int row0_, int tid)
-    { p = a.p; Co = a.Co; HoWo = a.HoWo; Q = a.Q; row0 = row0_; kq = tid % BK; rsub = tid / BK; }
+    {
+        p = a.p; Co = a.Co; HoWo = a.HoWo; Q = a.Q; row0 = row0_; kq = tid % BK; rsub = tid / BK;
+        const long long bytes = (long long)(a.Q / a.HoWo) * a.Co * a.HoWo * 4;
+        fast = bytes <= DK_RSRC_MAX && HoWo >= BK;
+        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            const int co = row0 + rsub + e * RSTEP;
+            coff[e] = co < Co ? 4u * (unsigned)co * (unsigned)HoWo : DK_OOB;
+        }
+        cur_kt = -2; cur_pix = 0; cur_img = 0;
+    }
 
     __device__ __forceinline__ void load(int kt)
     {
+        if (fast && (kt + 1) * BK <= Q) {
+            if (cur_kt + 1 == kt) {
+                cur_pix += BK;
+                if (cur_pix >= HoWo) { cur_pix -= HoWo; cur_img += 4u * (unsigned)Co * (unsigned)HoWo; }
+            } else {
+                const int q = kt * BK + kq;
+                const int r = q / HoWo;
+                cur_pix = q - r * HoWo;
+                cur_img = 4u * (unsigned)r * (unsigned)Co * (unsigned)HoWo;
+            }
+            cur_kt = kt;
+            const unsigned base = cur_img + 4u * (unsigned)cur_pix;
+#pragma unroll
+            for (int e = 0; e < NE; ++e)
+                st[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(base + coff[e]), 0, 0));
+            return;
+        }
+        cur_kt = -2;
         const int q = kt * BK + kq;
         const bool ok = q < Q;
         const int r = ok ? q / HoWo : 0;
@@ -355,12 +389,21 @@ struct LoadIm2colQ {
     int joff[NE];          // (ci*H + a)*W + b
     short fa[NE], fb[NE];  // filter tap; fa = -20000 marks a row beyond Kg
     const float *p; int H, W, Wo, HoWo, Q, stride, pad, kq, rsub; long long img;
+    // fast path (whole steps): pixel cursor as in LoadDeltaQ; the output row of
+    // the pixel comes from a multiplication by ceil(2^32 / Wo) (exact below 2^16)
+    __amdgpu_buffer_rsrc_t rs; bool fast;
+    int cur_kt, cur_pix; unsigned cur_img, wo_magic;
 
     __device__ __forceinline__ void init(const Params &a, int row0, int tid)
     {
         p = a.p; H = a.H; W = a.W; Wo = a.Wo; HoWo = a.HoWo; Q = a.Q;
         stride = a.stride; pad = a.pad; img = a.img;
         kq = tid % BK; rsub = tid / BK;
+        const long long bytes = (long long)(a.Q / a.HoWo) * a.img * 4;
+        fast = bytes <= DK_RSRC_MAX && HoWo >= BK && HoWo < 65536 && Wo > 1;
+        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
+        wo_magic = (unsigned)((0x100000000ull + (unsigned)Wo - 1) / (unsigned)Wo);
+        cur_kt = -2; cur_pix = 0; cur_img = 0;
 #pragma unroll
         for (int e = 0; e < NE; ++e) {
             const int j = row0 + rsub + e * RSTEP;
@@ -376,6 +419,30 @@ struct LoadIm2colQ {
 
     __device__ __forceinline__ void load(int kt)
     {
+        if (fast && (kt + 1) * BK <= Q) {
+            if (cur_kt + 1 == kt) {
+                cur_pix += BK;
+                if (cur_pix >= HoWo) { cur_pix -= HoWo; cur_img += 4u * (unsigned)img; }
+            } else {
+                const int q = kt * BK + kq;
+                const int r = q / HoWo;
+                cur_pix = q - r * HoWo;
+                cur_img = 4u * (unsigned)r * (unsigned)img;
+            }
+            cur_kt = kt;
+            const int ho = (int)__umulhi((unsigned)cur_pix, wo_magic), wo = cur_pix - ho * Wo;
+            const int ih0 = ho * stride - pad, iw0 = wo * stride - pad;
+            // (wraps below zero for border pixels; adding a valid tap's offset brings it back)
+            const unsigned base = cur_img + 4u * (unsigned)(ih0 * W + iw0);
+#pragma unroll
+            for (int e = 0; e < NE; ++e) {
+                const bool ok = (unsigned)(ih0 + fa[e]) < (unsigned)H && (unsigned)(iw0 + fb[e]) < (unsigned)W;
+                const unsigned off = ok ? base + 4u * (unsigned)joff[e] : DK_OOB;
+                st[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (int)off, 0, 0));
+            }
+            return;
+        }
+        cur_kt = -2;
         const int q = kt * BK + kq;
         const bool okq = q < Q;
         const int r = okq ? q / HoWo : 0;
