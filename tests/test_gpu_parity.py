@@ -485,6 +485,67 @@ def test_config5_last_layer_full_size_sampled(dk):
     assert out["verdict"].tolist() == [0] * G
 
 
+def _off1(a):
+    """Device copy of `a` that starts 4 bytes past a 16-byte boundary."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    buf = torch.empty(a.size + 1, dtype=torch.float32, device="cuda")
+    v = buf[1:].view(a.shape)
+    v.copy_(torch.from_numpy(a))
+    assert v.data_ptr() % 16 == 4
+    return v
+
+
+UNALIGNED = [
+    (4, 3, dk_inputs.linear(96, 200)),
+    (2, 3, dk_inputs.conv(16, 24, 16, 16, 3, 1, 1)),      # the 16-byte-read kernels must step aside
+    (2, 2, dk_inputs.conv(32, 40, 8, 8, 1, 1, 0)),
+    (3, 2, dk_inputs.dwconv(12, 16, 16, 3, 1)),
+]
+
+
+@pytest.mark.parametrize("K,G,L", UNALIGNED)
+def test_bases_off_16_byte_alignment(dk, K, G, L):
+    # every tensor (inputs, outputs, workspaces aside) sits 4 bytes off a 16-byte
+    # boundary although its sizes would allow vector accesses
+    say("unaligned bases", dict(K=K, G=G), L)
+    d = _masked_case(L, K, G, seed=K * 31 + G)
+    S = K + 2
+    Ainv, nvec, B = dk.dk_coeffs(d["A"], d["gamma"])
+    xbar = dk.dk_encode(_off1(d["X"]), _off1(d["r"]), dev(d["A"]), K,
+                        xbar=_off1(np.zeros((G * S,) + L.in_shape)))
+    W = _off1(d["W"])
+    ybar0 = _off1(np.zeros((G * S,) + L.out_shape))
+    ybar = dk.dk_linear_fwd(W, xbar, ybar=ybar0) if L.kind == "linear" else dk.dk_conv_fwd(L, W, xbar, ybar=ybar0)
+    y, v, rho = dk.dk_decode_verify(ybar, dev(Ainv), dev(nvec), K, y=_off1(np.zeros((G * K,) + L.out_shape)))
+    dW = dk.dk_wgrad(L, _off1(d["delta"]), dev(B), dev(d["gamma"]), xbar, K, dW=_off1(np.zeros(L.w_shape)))
+    if L.kind == "linear":
+        Y, dWr = oracle.dense_fwd(d["W"], d["X"]), oracle.dense_wgrad(d["delta"], d["X"])
+    elif L.kind == "dwconv":
+        Y = oracle.dwconv_fwd(d["W"], d["X"], L.stride, L.pad)
+        dWr = oracle.dwconv_wgrad(d["delta"], d["X"], L.kh, L.kw, L.stride, L.pad)
+    else:
+        Y = oracle.conv_fwd(d["W"], d["X"], L.stride, L.pad)
+        dWr = oracle.conv_wgrad(d["delta"], d["X"], L.kh, L.kw, L.stride, L.pad)
+    assert nerr(host(y), Y) < TOL_CONTRACT
+    assert nerr(host(dW), dWr) < TOL_CONTRACT
+    assert host(v).tolist() == [0] * G
+
+
+def test_operand_beyond_two_gigabytes(dk):
+    # W is 2.56 GB: past the 32-bit byte offsets of the loaders' fast path, which
+    # must step aside for it (the encodings, 16 MB, still take it)
+    say("dense forward, W of 2.56 GB")
+    M, N, R = 640, 1_000_000, 4
+    rng = np.random.default_rng(99)
+    W = rng.standard_normal((M, N), dtype=np.float32)
+    X = rng.standard_normal((R, N), dtype=np.float32)
+    got = host(dk.dk_linear_fwd(dev(W), dev(X)))
+    pts = np.stack([rng.integers(0, R, 300), rng.integers(0, M, 300)], axis=1)
+    pts[:4] = [[0, 0], [R - 1, M - 1], [0, M - 1], [R - 1, 0]]
+    ref = oracle.dense_fwd_points(W, X, pts)
+    assert np.max(np.abs(got[tuple(pts.T)] - ref)) / np.max(np.abs(ref)) < TOL_GEMM
+
+
 def test_verify_flags_tampered_stored_encodings(dk):
     # The encodings kept for the backward pass satisfy Xbar . nvec = 0 like the
     # forward results do: the same check, run on them before dk_wgrad, flags a
