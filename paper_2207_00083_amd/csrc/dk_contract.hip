@@ -573,7 +573,7 @@ struct LoadRowMajorKImg {
     {
         p = a.p; C = a.C; HW = a.HW; Q = a.Q; row0 = row0_; tid = tid_;
         const long long bytes = (long long)(a.Q / a.HW) * a.C * a.HW * 4;
-        fast = VEC && bytes <= DK_RSRC_MAX && HW >= BK;
+        fast = bytes <= DK_RSRC_MAX && HW >= BK;
         rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
 #pragma unroll
         for (int e = 0; e < N4; ++e) {
@@ -596,8 +596,24 @@ struct LoadRowMajorKImg {
                 cur_off = 4u * ((unsigned)r * (unsigned)C * (unsigned)HW + (unsigned)cur_pix);
             }
             cur_kt = kt;
+            if constexpr (VEC) {
 #pragma unroll
-            for (int e = 0; e < N4; ++e) st[e] = dk_buffer_load4(rs, roff[e] + cur_off, 0u);
+                for (int e = 0; e < N4; ++e) st[e] = dk_buffer_load4(rs, roff[e] + cur_off, 0u);
+            } else {
+                // four single pixels; one that runs past its image is the next image's first
+                unsigned po[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    po[u] = cur_off + 4u * u + (cur_pix + u >= HW ? 4u * (unsigned)(C - 1) * (unsigned)HW : 0u);
+#pragma unroll
+                for (int e = 0; e < N4; ++e) {
+                    float v[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        v[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(roff[e] + po[u]), 0, 0));
+                    st[e] = make_float4(v[0], v[1], v[2], v[3]);
+                }
+            }
             return;
         }
         cur_kt = -2;
