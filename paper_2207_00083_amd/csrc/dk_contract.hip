@@ -711,7 +711,19 @@ __global__ __launch_bounds__(C::NT) void contract_kernel(typename LA::Params pa,
     const int bid = dk_xcd_block();
     const int split = bid / tiles;
     const int t = bid - split * tiles;
-    const int tile_n = t / rp.tiles_m, tile_m = t - tile_n * rp.tiles_m;
+    // Tiles that run at the same time should share operand panels in both
+    // directions: walk the output in bands of 8 tile rows, column by column
+    // inside a band, so that the ~100 tiles resident on an XCD form a block of
+    // about 8 x 12 instead of one or two whole tile columns.
+    int tile_m, tile_n;
+    {
+        constexpr int GM = 8;
+        const int band = t / (GM * rp.tiles_n);
+        const int in_band = t - band * (GM * rp.tiles_n);
+        const int rows_here = rp.tiles_m - band * GM < GM ? rp.tiles_m - band * GM : GM;
+        tile_n = in_band / rows_here;
+        tile_m = band * GM + (in_band - tile_n * rows_here);
+    }
     const int row0 = tile_m * C::BM, col0 = tile_n * C::BN;
 
     LA la; LB lb;
