@@ -161,9 +161,8 @@ template <int KH, int KW, int DSLOT, int PSLOT>
 __global__ __launch_bounds__(512) void conv_patch_wgrad_kernel(dk_wgpatch_params p)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    constexpr int NP = 256, BM = 64, BCI = 64, KK = KH * KW;
-    constexpr int STRIDE = 1, VEC = 4;     // stride-1 layers whose rows are whole 16-byte vectors
-    using stage_t = f32x4;
+    constexpr int BM = 64, BCI = 64, KK = KH * KW;
+    constexpr int STRIDE = 1;              // stride-1 layers whose rows are whole 16-byte vectors
 
     // Two LDS buffers of [dtilde tile: BM x LDQ][input patch: BCI x CPLANE].
     // Waves 0-3 (one per SIMD) only run MFMAs on the current buffer; waves 4-7
@@ -302,7 +301,7 @@ template <int DSLOT, int PSLOT>
 __global__ __launch_bounds__(512) void conv_quad_wgrad_kernel(dk_wgpatch_params p)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    constexpr int NP = 256, BM = 64, BCI = 64, KH = 3, KW = 3, KK = 9;
+    constexpr int BM = 64, BCI = 64, KH = 3, KW = 3, KK = 9;
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
