@@ -1273,7 +1273,7 @@ static dk_status conv_fwd_impl(const dk_geom &g, const float *W, const float *xb
         const size_t wd_bytes = conv_dense_matrix_bytes(g);
         const long long total = (long long)Md * g.Ci;
         {
-            dk_prof_scope ps("conv_unfold_filters", st);
+            dk_prof_scope ps("unfold_filters", st);
             conv_unfold_filters_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
                 W, Wd, g.Ci, g.H, g.W, g.Ho, g.Wo, g.kh, g.kw, g.stride, g.pad, total);
         }
@@ -1370,7 +1370,7 @@ static dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *
         });
         if (s != DK_OK) return s;
         const long long total = (long long)g.Co * g.Ci;
-        dk_prof_scope ps("conv_refold_wgrad", st);
+        dk_prof_scope ps("refold_wgrad", st);
         conv_refold_wgrad_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
             dWd, dW, g.Ci, g.H, g.W, g.Ho, g.Wo, g.kh, g.kw, g.stride, g.pad, scale, accumulate, total);
         return dk_launch_status();
