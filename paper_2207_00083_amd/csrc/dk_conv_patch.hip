@@ -68,8 +68,11 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_patch_fwd_kernel(dk_patch_p
     const int wn0 = (wave / WM) * (BN / WN);
 
     const int tiles = p.tiles_m * p.tiles_n;
-    const int split = blockIdx.x / tiles;
-    const int t = blockIdx.x - split * tiles;
+    // each XCD takes one contiguous run of tiles: neighbouring pixel tiles of an
+    // image, which share their halo rows, then share an L2
+    const int bid = dk_xcd_block();
+    const int split = bid / tiles;
+    const int t = bid - split * tiles;
     const int tile_n = t / p.tiles_m, tile_m = t - tile_n * p.tiles_m;
     const int co0 = tile_m * BM;
 
@@ -295,8 +298,11 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_quad_fwd_kernel(dk_patch_pa
     float *const dump = As + BM * WP + lane * 4;    // 1 KB behind the filter tile
 
     const int tiles = p.tiles_m * p.tiles_n;
-    const int split = blockIdx.x / tiles;
-    const int t = blockIdx.x - split * tiles;
+    // each XCD takes one contiguous run of tiles: neighbouring pixel tiles of an
+    // image, which share their halo rows, then share an L2
+    const int bid = dk_xcd_block();
+    const int split = bid / tiles;
+    const int t = bid - split * tiles;
     const int tile_n = t / p.tiles_m, tile_m = t - tile_n * p.tiles_m;
     const int co0 = tile_m * BM;
 
