@@ -307,3 +307,102 @@ def masked_dense_layer(W, X, r, delta, A, gamma, l=L_BITS, p=P):
     dW = dequantize(dWq, l, p)
     return dict(Wq=Wq, Xq=Xq, Xbar=Xbar, Ybar=Ybar, verdict=verdict, Yq=Yq, Y=Y, Dq=Dq,
                 Dtilde=Dtilde, dWq=dWq, dW=dW)
+
+
+# ----------------------------------------------------------------------
+# Dynamic normalisation ("Quantization", the variant for networks without
+# normalisation layers)
+# ----------------------------------------------------------------------
+
+def norm_scales(x, limit):
+    """One factor per row of x (a row is one vector: one sample's features, or
+    the whole weight tensor given as a single row).
+
+    The paper divides a vector by its largest absolute entry when its values
+    pass the limits.  Reading: the vector passes the limit when that largest
+    entry m exceeds `limit`; its factor is then the fp32 value nearest to 1/m,
+    otherwise 1.  NaN entries do not take part in the maximum, and an infinite
+    maximum leaves the factor at 1 (the quantiser's clamp deals with it)."""
+    x = np.asarray(x, dtype=np.float32)
+    x = x.reshape(x.shape[0], -1)
+    s = np.ones(x.shape[0], dtype=np.float32)
+    for i in range(x.shape[0]):
+        # fmax skips NaN operands
+        m = float(np.fmax.reduce(np.abs(x[i]).astype(np.float64), initial=0.0))
+        if m > float(np.float32(limit)) and m != np.inf:
+            s[i] = np.float32(1.0 / m)
+    return s
+
+
+def quantize_scaled(x, scale, l=L_BITS, p=P):
+    """Field(Round(x[i] * scale[i] * 2^l)), row i of x times its factor.  The
+    product of two fp32 values and a power of two is exact in fp64, so Round
+    sees the exact scaled value.  Clamp and NaN as in quantize()."""
+    x = np.asarray(x, dtype=np.float32)
+    scale = np.asarray(scale, dtype=np.float32).reshape(-1)
+    rows = x.reshape(x.shape[0], -1).astype(np.float64)
+    assert scale.shape[0] == rows.shape[0]
+    v = np.floor(rows * scale.astype(np.float64)[:, None] * float(2 ** l) + 0.5)
+    v = np.where(np.isnan(v), 0.0, v)
+    v = np.clip(v, -2147483648.0, 2147483647.0).astype(np.int64)
+    return np.mod(v, p).astype(np.uint32).reshape(x.shape)
+
+
+def reciprocal(scale):
+    """fp64 reciprocal of fp32 factors (one IEEE division each)."""
+    return 1.0 / np.asarray(scale, dtype=np.float32).astype(np.float64)
+
+
+def unscale(y, row_scale, wscale):
+    """Undo the factors on de-quantised results: row i of y is multiplied by
+    the fp64 reciprocal of (row_scale[i] * wscale) (that product is exact in
+    fp64) and rounded to fp32."""
+    y = np.asarray(y, dtype=np.float32)
+    rs = np.asarray(row_scale, dtype=np.float32).astype(np.float64).reshape(-1)
+    inv = 1.0 / (rs * float(np.float32(wscale)))
+    out = y.reshape(y.shape[0], -1).astype(np.float64) * inv[:, None]
+    return out.astype(np.float32).reshape(y.shape)
+
+
+def quantize_unscaled_delta(delta, xscale, l=L_BITS, p=P):
+    """Output gradients for the weight gradient when the stored encodings hold
+    inputs times xscale: the sum over samples of delta_i (x) x_i equals the sum
+    of (delta_i / s_i) (x) (s_i x_i), so row i is multiplied by the fp64
+    reciprocal of s_i (product rounded to fp64 once), then Round and Field."""
+    d = np.asarray(delta, dtype=np.float32)
+    inv = reciprocal(xscale).reshape(-1)
+    rows = d.reshape(d.shape[0], -1).astype(np.float64) * inv[:, None]
+    v = np.floor(rows * float(2 ** l) + 0.5)
+    v = np.where(np.isnan(v), 0.0, v)
+    v = np.clip(v, -2147483648.0, 2147483647.0).astype(np.int64)
+    return np.mod(v, p).astype(np.uint32).reshape(d.shape)
+
+
+def masked_layer_normalized(W, X, r, delta, A, gamma, limit, stride=1, pad=0, l=L_BITS, p=P):
+    """masked_layer with dynamic normalisation of the inputs (one factor per
+    sample) and of the weights (one factor for the tensor).  The steps between
+    quantisation and de-quantisation are those of masked_layer.  Y and dW come
+    back in the units of the un-normalised layer: Y row i is divided by
+    wscale * xscale[i]; the output gradients carry 1 / xscale[i] into the
+    weight gradient, which therefore needs no factor afterwards."""
+    W = np.asarray(W, dtype=np.float32)
+    X = np.asarray(X, dtype=np.float32)
+    Ainv, nvec, B = coefficients(A, gamma, p)
+    xscale = norm_scales(X, limit)
+    wscale = norm_scales(W.reshape(1, -1), limit)
+    Wq = quantize_scaled(W.reshape(1, -1), wscale, l, p).reshape(W.shape)
+    Xq = quantize_scaled(X, xscale, l, p)
+    Xbar = encode(Xq, r, A, p)
+    dense = W.ndim == 2
+    Ybar = dense_fwd(Wq, Xbar, p) if dense else conv_fwd(Wq, Xbar, stride, pad, p)
+    verdict = verify(Ybar, nvec, p)
+    Yq = decode(Ybar, Ainv, None, p)
+    Yn = dequantize(Yq, l, p)
+    Y = unscale(Yn, xscale, wscale[0])
+    Dq = quantize_unscaled_delta(delta, xscale, l, p)
+    Dtilde = delta_mix(Dq, B, gamma, p)
+    dWq = (dense_wgrad(Dtilde, Xbar, p) if dense
+           else conv_wgrad(Dtilde, Xbar, W.shape[2], W.shape[3], stride, pad, p))
+    dW = dequantize(dWq, l, p)
+    return dict(xscale=xscale, wscale=wscale, Wq=Wq, Xq=Xq, Xbar=Xbar, Ybar=Ybar, verdict=verdict,
+                Yq=Yq, Yn=Yn, Y=Y, Dq=Dq, Dtilde=Dtilde, dWq=dWq, dW=dW)
