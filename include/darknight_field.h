@@ -130,6 +130,60 @@ dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint32_t *B,
                     int G, int K, int l, float scale, int accumulate,
                     void *ws, size_t ws_bytes, void *stream);
 
+/* ---- Dynamic normalisation ("Quantization": networks without normalisation
+ * layers divide a vector whose values pass the limits by its largest absolute
+ * entry before quantisation).
+ *
+ * Readings where the paper is silent.  A vector is one row: one sample's
+ * features, or the whole weight tensor given as a single row.  It passes the
+ * limit when its largest absolute entry m (NaN entries skipped) exceeds
+ * `limit`; its factor is then the fp32 value nearest to 1/m, and 1 otherwise
+ * (also for m = infinity: the quantiser's clamp deals with that row).  The
+ * factors are applied and taken back as follows, every step defined so that
+ * the result is one fixed bit pattern:
+ *   forward   Xq[i] = Field(Round(x[i] * xscale[i] * 2^l)) (the scaled value is
+ *             exact in fp64), Wq likewise with wscale[0];
+ *   decode    y[i] = fp32(fp64(Round(lift(Yq[i]) 2^-l) 2^-l)
+ *                         * (1 / (xscale[i] * wscale[0])))   (fp64 reciprocal);
+ *   backward  the stored encodings hold s_i x_i, and sum_i delta_i (x) x_i =
+ *             sum_i (delta_i / s_i) (x) (s_i x_i), so
+ *             Dq[i] = Field(Round(fp64(delta[i] * (1 / xscale[i])) * 2^l))
+ *             and dW needs no factor afterwards.
+ * With all factors equal to 1 every _norm call returns exactly what the call
+ * without the suffix returns. */
+
+/* scale[row] from x[rows][len] (both device) as defined above.  rows <= 65535,
+ * 0 < limit < infinity.  Three short launches on `stream`, no workspace. */
+dk_status dkf_norm_scales(const float *x, float *scale, long long rows, long long len,
+                          float limit, void *stream);
+
+/* dkf_quantize of x[rows][len] with row i multiplied by scale[i] first
+ * (device pointers; rows = 1 for a weight tensor). */
+dk_status dkf_quantize_norm(const float *x, const float *scale, uint32_t *xq, long long rows,
+                            long long len, int l, void *stream);
+
+/* dkf_encode / dkf_encode_rng with input row gK+i multiplied by xscale[gK+i]
+ * before quantisation.  xscale[G*K] device. */
+dk_status dkf_encode_norm(const float *x, const float *xscale, const uint32_t *r, const uint32_t *A,
+                          uint32_t *xbar, int G, int K, long long n, int l, void *stream);
+dk_status dkf_encode_rng_norm(const float *x, const float *xscale, const uint32_t *A, uint32_t *xbar,
+                              int G, int K, long long n, int l, unsigned long long seed,
+                              void *stream);
+
+/* dkf_decode_verify whose float rows are brought back to the units of the
+ * un-normalised layer.  xscale[G*K], wscale[1] device; yq, verdict unaffected. */
+dk_status dkf_decode_verify_norm(const uint32_t *ybar, const uint32_t *Ainv, const uint32_t *nvec,
+                                 const float *xscale, const float *wscale, float *y, uint32_t *yq,
+                                 int *verdict, int G, int K, long long m, int l, void *stream);
+
+/* dkf_wgrad for encodings made by dkf_encode_norm with the same xscale[G*K]
+ * (device): row i of delta is divided by xscale[i] before quantisation.  Same
+ * workspace as dkf_wgrad. */
+dk_status dkf_wgrad_norm(const dk_layer *L, const float *delta, const float *xscale,
+                         const uint32_t *B, const uint32_t *gamma, const uint32_t *xbar, float *dW,
+                         uint32_t *dwq, int G, int K, int l, float scale, int accumulate,
+                         void *ws, size_t ws_bytes, void *stream);
+
 /* Workspace sizes in bytes (0 for invalid arguments). */
 size_t dkf_fwd_workspace_bytes(int M, int N, int R);
 size_t dkf_conv_fwd_workspace_bytes(const dk_layer *L, int R);

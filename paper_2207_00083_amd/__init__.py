@@ -15,7 +15,7 @@ from .binding import (DkError, DkLayer, lib_path, load, dk_version, dk_status_st
 
 from .field import (DKF_P, DKF_L, dkf_coeffs, dkf_quantize, dkf_dequantize, dkf_encode, dkf_linear_fwd,
                     dkf_decode_verify, dkf_wgrad, dkf_fwd_workspace_bytes, dkf_wgrad_workspace_bytes,
-                    dkf_conv_fwd, dkf_conv_fwd_workspace_bytes, dkf_noise_rng, dkf_encode_rng)
+                    dkf_conv_fwd, dkf_conv_fwd_workspace_bytes, dkf_noise_rng, dkf_encode_rng, dkf_norm_scales)
 
 __all__ = ["DKF_P", "DKF_L", "dkf_coeffs", "dkf_quantize", "dkf_dequantize", "dkf_encode",
            "dkf_linear_fwd", "dkf_decode_verify", "dkf_wgrad", "dkf_fwd_workspace_bytes",
@@ -25,5 +25,5 @@ __all__ = ["DKF_P", "DKF_L", "dkf_coeffs", "dkf_quantize", "dkf_dequantize", "dk
            "dk_encode", "dk_linear_fwd", "dk_conv_fwd", "dk_wgrad", "dk_decode", "dk_verify",
            "dk_decode_verify", "dk_profile_enable", "dk_profile_read",
            "dk_coeffs_m", "dk_encode_m", "dk_decode_verify_m", "dk_wgrad_m", "dk_noise_rng", "dk_encode_rng", "dk_dgrad",
-           "dkf_noise_rng", "dkf_encode_rng",
+           "dkf_noise_rng", "dkf_encode_rng", "dkf_norm_scales",
            "DK_OP_FWD", "DK_OP_WGRAD", "DK_OP_VERIFY", "DK_MAX_K"]

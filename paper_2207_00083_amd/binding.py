@@ -93,6 +93,12 @@ def load():
         "dkf_decode_verify": (ip, [vp, vp, vp, vp, vp, vp, ip, ip, ll, ip, vp]),
         "dkf_wgrad": (ip, [LP, vp, vp, vp, vp, vp, vp, ip, ip, ip, fl, ip, vp, sz, vp]),
         "dkf_conv_fwd": (ip, [LP, vp, vp, vp, ip, vp, sz, vp]),
+        "dkf_norm_scales": (ip, [vp, vp, ll, ll, fl, vp]),
+        "dkf_quantize_norm": (ip, [vp, vp, vp, ll, ll, ip, vp]),
+        "dkf_encode_norm": (ip, [vp, vp, vp, vp, vp, ip, ip, ll, ip, vp]),
+        "dkf_encode_rng_norm": (ip, [vp, vp, vp, vp, ip, ip, ll, ip, C.c_ulonglong, vp]),
+        "dkf_decode_verify_norm": (ip, [vp, vp, vp, vp, vp, vp, vp, vp, ip, ip, ll, ip, vp]),
+        "dkf_wgrad_norm": (ip, [LP, vp, vp, vp, vp, vp, vp, vp, ip, ip, ip, fl, ip, vp, sz, vp]),
         "dkf_conv_fwd_workspace_bytes": (sz, [LP, ip]),
         "dkf_fwd_workspace_bytes": (sz, [ip, ip, ip]),
         "dkf_wgrad_workspace_bytes": (sz, [LP, ip, ip]),

@@ -5,9 +5,11 @@
 #include "dk_internal.h"
 #include "darknight_field.h"
 
-// Gradient mixing over the field (launcher; used by dkf_wgrad).
-dk_status dkf_delta_mix(const float *delta, const uint32_t *B, const uint32_t *gamma,
-                        uint32_t *dtilde, int G, int K, long long m, int l, hipStream_t st);
+// Gradient mixing over the field (launcher; used by dkf_wgrad).  xscale (one
+// normalisation factor per sample, device) may be null.
+dk_status dkf_delta_mix(const float *delta, const float *xscale, const uint32_t *B,
+                        const uint32_t *gamma, uint32_t *dtilde, int G, int K, long long m, int l,
+                        hipStream_t st);
 
 #ifdef __HIPCC__
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));

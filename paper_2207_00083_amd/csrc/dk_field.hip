@@ -57,19 +57,64 @@ __device__ __forceinline__ void st_f32(float *p, const float (&src)[VEC])
     }
 }
 
+// One row per blockIdx.y; `scale` (one factor per row) may be null.
 template <int VEC>
 __global__ __launch_bounds__(FT) void quantize_kernel(const float *__restrict__ x,
+                                                      const float *__restrict__ scale,
                                                       uint32_t *__restrict__ xq,
                                                       long long nvec, double s)
 {
     const long long v = (long long)blockIdx.x * FT + threadIdx.x;
     if (v >= nvec) return;
+    const long long row0 = (long long)blockIdx.y * nvec * VEC;
+    if (scale) s *= (double)scale[blockIdx.y];      // exact: 24 bits times a power of two
     float in[VEC];
     uint32_t out[VEC];
-    ld_f32<VEC>(in, x + v * VEC);
+    ld_f32<VEC>(in, x + row0 + v * VEC);
 #pragma unroll
     for (int c = 0; c < VEC; ++c) out[c] = dkf_quant(in[c], s);
-    st_u32<VEC>(xq + v * VEC, out);
+    st_u32<VEC>(xq + row0 + v * VEC, out);
+}
+
+// Largest absolute entry of each row, NaN skipped, gathered with an integer
+// maximum on the bit patterns (non-negative floats order like their bits).
+// bits[row] was cleared by the launch before this one.
+template <int VEC>
+__global__ __launch_bounds__(FT) void absmax_kernel(const float *__restrict__ x,
+                                                    uint32_t *__restrict__ bits,
+                                                    long long nvec, long long span)
+{
+    const long long row0 = (long long)blockIdx.y * nvec * VEC;
+    const long long v0 = (long long)blockIdx.x * span;
+    long long v1 = v0 + span;
+    if (v1 > nvec) v1 = nvec;
+    float m = 0.0f;
+    for (long long v = v0 + threadIdx.x; v < v1; v += FT) {
+        float in[VEC];
+        ld_f32<VEC>(in, x + row0 + v * VEC);
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) m = fmaxf(m, fabsf(in[c]));   // fmaxf drops a NaN operand
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    if ((threadIdx.x & 63) == 0 && m > 0.0f) atomicMax(bits + blockIdx.y, __float_as_uint(m));
+}
+
+// bits[row] -> factor[row] in place: 1/m (nearest fp32 to the fp64 quotient)
+// when limit < m < infinity, else 1.
+__global__ void norm_scale_kernel(uint32_t *bits, long long rows, float limit)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows) return;
+    const float m = __uint_as_float(bits[i]);
+    const float f = (m > limit && m < INFINITY) ? (float)(1.0 / (double)m) : 1.0f;
+    bits[i] = __float_as_uint(f);
+}
+
+__global__ void f_clear_u32_kernel(uint32_t *p, long long count)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0;
 }
 
 template <int VEC>
@@ -91,8 +136,9 @@ __global__ __launch_bounds__(FT) void dequantize_kernel(const uint32_t *__restri
 // Xq quantised on the fly from the float rows.
 template <int K, int VEC>
 __global__ __launch_bounds__(FT) void f_encode_kernel(
-    const float *__restrict__ x, const uint32_t *__restrict__ r, const uint32_t *__restrict__ A,
-    uint32_t *__restrict__ xbar, long long len, long long nvec, int chunks, long long span, double s)
+    const float *__restrict__ x, const float *__restrict__ xscale, const uint32_t *__restrict__ r,
+    const uint32_t *__restrict__ A, uint32_t *__restrict__ xbar, long long len, long long nvec,
+    int chunks, long long span, double s)
 {
     constexpr int S = K + 2;
     const int g = blockIdx.x / chunks;          // wave-uniform
@@ -101,6 +147,10 @@ __global__ __launch_bounds__(FT) void f_encode_kernel(
     const float *xs = x + (long long)g * K * len;
     const uint32_t *rs = r + (long long)g * len;
     uint32_t *dst = xbar + (long long)g * S * len;
+    // 2^l times the row's normalisation factor, if any (exact in fp64)
+    double si[K];
+#pragma unroll
+    for (int i = 0; i < K; ++i) si[i] = xscale ? s * (double)xscale[(long long)g * K + i] : s;
 
     const long long v0 = (long long)chunk * span;
     long long v1 = v0 + span;
@@ -119,7 +169,7 @@ __global__ __launch_bounds__(FT) void f_encode_kernel(
                 float f[VEC];
                 ld_f32<VEC>(f, xs + (long long)i * len + e);
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) q[c] = dkf_quant(f[c], s);
+                for (int c = 0; c < VEC; ++c) q[c] = dkf_quant(f[c], si[i]);
             } else {
                 ld_u32<VEC>(q, rs + e);
             }
@@ -144,7 +194,8 @@ __global__ __launch_bounds__(FT) void f_encode_kernel(
 template <int K, int VEC>
 __global__ __launch_bounds__(FT) void f_decode_verify_kernel(
     const uint32_t *__restrict__ ybar, const uint32_t *__restrict__ Ainv,
-    const uint32_t *__restrict__ nvec_, float *__restrict__ y, uint32_t *__restrict__ yq,
+    const uint32_t *__restrict__ nvec_, const float *__restrict__ xscale,
+    const float *__restrict__ wscale, float *__restrict__ y, uint32_t *__restrict__ yq,
     int *__restrict__ verdict, long long len, long long nvec, int chunks, long long span, double s)
 {
     constexpr int S = K + 2;
@@ -153,6 +204,13 @@ __global__ __launch_bounds__(FT) void f_decode_verify_kernel(
     const uint32_t *Ag = Ainv + (long long)g * S * S;
     const uint32_t *ng = nvec_ + (long long)g * S;
     const uint32_t *src = ybar + (long long)g * S * len;
+    // fp64 reciprocal of (input factor * weight factor): that product is exact
+    double back[K];
+    if (xscale) {
+        const double ws = (double)wscale[0];
+#pragma unroll
+        for (int i = 0; i < K; ++i) back[i] = 1.0 / ((double)xscale[(long long)g * K + i] * ws);
+    }
 
     bool bad = false;
     const long long v0 = (long long)chunk * span;
@@ -194,6 +252,7 @@ __global__ __launch_bounds__(FT) void f_decode_verify_kernel(
             for (int c = 0; c < VEC; ++c) {
                 o[c] = dkf_reduce(acc[i][c]);
                 f[c] = dkf_dequant(o[c], s);
+                if (xscale) f[c] = (float)((double)f[c] * back[i]);
             }
             st_f32<VEC>(y + ((long long)g * K + i) * len + e, f);
             if (yq) st_u32<VEC>(yq + ((long long)g * K + i) * len + e, o);
@@ -206,9 +265,9 @@ __global__ __launch_bounds__(FT) void f_decode_verify_kernel(
 // dtilde[gS+j] = gamma[g][j] * (sum_i B[g][j][i] * Dq[gK+i])  (mod p).
 template <int K, int VEC>
 __global__ __launch_bounds__(FT) void f_delta_mix_kernel(
-    const float *__restrict__ delta, const uint32_t *__restrict__ B,
-    const uint32_t *__restrict__ gamma, uint32_t *__restrict__ dtilde, long long len,
-    long long nvec, int chunks, long long span, double s)
+    const float *__restrict__ delta, const float *__restrict__ xscale,
+    const uint32_t *__restrict__ B, const uint32_t *__restrict__ gamma,
+    uint32_t *__restrict__ dtilde, long long len, long long nvec, int chunks, long long span, double s)
 {
     constexpr int S = K + 2;
     const int g = blockIdx.x / chunks;
@@ -217,6 +276,11 @@ __global__ __launch_bounds__(FT) void f_delta_mix_kernel(
     const uint32_t *gg = gamma + (long long)g * S;
     const float *src = delta + (long long)g * K * len;
     uint32_t *dst = dtilde + (long long)g * S * len;
+    // 2^l over the factor of the sample's stored input: the fp64 reciprocal,
+    // scaled by a power of two (so the product below rounds once, in fp64)
+    double si[K];
+#pragma unroll
+    for (int i = 0; i < K; ++i) si[i] = xscale ? s * (1.0 / (double)xscale[(long long)g * K + i]) : s;
 
     const long long v0 = (long long)chunk * span;
     long long v1 = v0 + span;
@@ -229,7 +293,7 @@ __global__ __launch_bounds__(FT) void f_delta_mix_kernel(
             float f[VEC];
             ld_f32<VEC>(f, src + (long long)i * len + e);
 #pragma unroll
-            for (int c = 0; c < VEC; ++c) q[i][c] = dkf_quant(f[c], s);
+            for (int c = 0; c < VEC; ++c) q[i][c] = dkf_quant(f[c], si[i]);
         }
 #pragma unroll
         for (int j = 0; j < S; ++j) {
@@ -303,8 +367,8 @@ dk_status check_args(int G, int K, long long len, int l)
     }
 
 template <int K>
-dk_status launch_encode(const float *x, const uint32_t *r, const uint32_t *A, uint32_t *xbar,
-                        int G, long long n, int l, hipStream_t st)
+dk_status launch_encode(const float *x, const float *xscale, const uint32_t *r, const uint32_t *A,
+                        uint32_t *xbar, int G, long long n, int l, hipStream_t st)
 {
     const bool v4 = vec4_ok(n, {x, r, xbar});
     const fspan p = plan_fspan(n, v4 ? 4 : 1, G);
@@ -313,16 +377,16 @@ dk_status launch_encode(const float *x, const uint32_t *r, const uint32_t *A, ui
     const double s = ldexp(1.0, l);
     dk_prof_scope ps("f_encode", st);
     if (v4)
-        f_encode_kernel<K, 4><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(x, r, A, xbar, n, p.nvec, p.chunks, p.span, s);
+        f_encode_kernel<K, 4><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(x, xscale, r, A, xbar, n, p.nvec, p.chunks, p.span, s);
     else
-        f_encode_kernel<K, 1><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(x, r, A, xbar, n, p.nvec, p.chunks, p.span, s);
+        f_encode_kernel<K, 1><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(x, xscale, r, A, xbar, n, p.nvec, p.chunks, p.span, s);
     return dk_launch_status();
 }
 
 template <int K>
 dk_status launch_decode_verify(const uint32_t *ybar, const uint32_t *Ainv, const uint32_t *nvec,
-                               float *y, uint32_t *yq, int *verdict, int G, long long m, int l,
-                               hipStream_t st)
+                               const float *xscale, const float *wscale, float *y, uint32_t *yq,
+                               int *verdict, int G, long long m, int l, hipStream_t st)
 {
     const bool v4 = vec4_ok(m, {ybar, y, yq});
     const fspan p = plan_fspan(m, v4 ? 4 : 1, G);
@@ -337,16 +401,17 @@ dk_status launch_decode_verify(const uint32_t *ybar, const uint32_t *Ainv, const
     dk_prof_scope ps("f_decode_verify", st);
     if (v4)
         f_decode_verify_kernel<K, 4><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(
-            ybar, Ainv, nvec, y, yq, verdict, m, p.nvec, p.chunks, p.span, s);
+            ybar, Ainv, nvec, xscale, wscale, y, yq, verdict, m, p.nvec, p.chunks, p.span, s);
     else
         f_decode_verify_kernel<K, 1><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(
-            ybar, Ainv, nvec, y, yq, verdict, m, p.nvec, p.chunks, p.span, s);
+            ybar, Ainv, nvec, xscale, wscale, y, yq, verdict, m, p.nvec, p.chunks, p.span, s);
     return dk_launch_status();
 }
 
 template <int K>
-dk_status launch_delta_mix(const float *delta, const uint32_t *B, const uint32_t *gamma,
-                           uint32_t *dtilde, int G, long long m, int l, hipStream_t st)
+dk_status launch_delta_mix(const float *delta, const float *xscale, const uint32_t *B,
+                           const uint32_t *gamma, uint32_t *dtilde, int G, long long m, int l,
+                           hipStream_t st)
 {
     const bool v4 = vec4_ok(m, {delta, dtilde});
     const fspan p = plan_fspan(m, v4 ? 4 : 1, G);
@@ -355,38 +420,95 @@ dk_status launch_delta_mix(const float *delta, const uint32_t *B, const uint32_t
     const double s = ldexp(1.0, l);
     dk_prof_scope ps("f_delta_mix", st);
     if (v4)
-        f_delta_mix_kernel<K, 4><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(delta, B, gamma, dtilde, m, p.nvec, p.chunks, p.span, s);
+        f_delta_mix_kernel<K, 4><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(delta, xscale, B, gamma, dtilde, m, p.nvec, p.chunks, p.span, s);
     else
-        f_delta_mix_kernel<K, 1><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(delta, B, gamma, dtilde, m, p.nvec, p.chunks, p.span, s);
+        f_delta_mix_kernel<K, 1><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(delta, xscale, B, gamma, dtilde, m, p.nvec, p.chunks, p.span, s);
     return dk_launch_status();
 }
 
 } // namespace
 
-dk_status dkf_delta_mix(const float *delta, const uint32_t *B, const uint32_t *gamma,
-                        uint32_t *dtilde, int G, int K, long long m, int l, hipStream_t st)
+dk_status dkf_delta_mix(const float *delta, const float *xscale, const uint32_t *B,
+                        const uint32_t *gamma, uint32_t *dtilde, int G, int K, long long m, int l,
+                        hipStream_t st)
 {
-#define CALL(KK) launch_delta_mix<KK>(delta, B, gamma, dtilde, G, m, l, st)
+#define CALL(KK) launch_delta_mix<KK>(delta, xscale, B, gamma, dtilde, G, m, l, st)
     DKF_K_SWITCH(K, CALL)
 #undef CALL
 }
+
+namespace {
+
+dk_status quantize_rows(const float *x, const float *scale, uint32_t *xq, long long rows,
+                        long long len, int l, hipStream_t st)
+{
+    const bool v4 = vec4_ok(len, {x, xq});
+    const long long nvec = v4 ? len / 4 : len;
+    const long long blocks = (nvec + FT - 1) / FT;
+    DK_REQUIRE(blocks <= 0x7fffffffll && rows <= 65535, DK_ERR_SHAPE);
+    const double s = ldexp(1.0, l);
+    dk_prof_scope ps("f_quantize", st);
+    const dim3 grid((unsigned)blocks, (unsigned)rows);
+    if (v4)
+        quantize_kernel<4><<<grid, dim3(FT), 0, st>>>(x, scale, xq, nvec, s);
+    else
+        quantize_kernel<1><<<grid, dim3(FT), 0, st>>>(x, scale, xq, nvec, s);
+    return dk_launch_status();
+}
+
+} // namespace
 
 DK_EXPORT dk_status dkf_quantize(const float *x, uint32_t *xq, long long count, int l, void *stream)
 {
     DK_REQUIRE(x && xq, DK_ERR_NULL);
     DK_REQUIRE(count >= 1 && count <= (1ll << 40) && l >= 0 && l <= DKF_MAX_L, DK_ERR_SHAPE);
     DK_REQUIRE(dk_aligned(x, 4) && dk_aligned(xq, 4), DK_ERR_ALIGN);
+    return quantize_rows(x, nullptr, xq, 1, count, l, (hipStream_t)stream);
+}
+
+DK_EXPORT dk_status dkf_quantize_norm(const float *x, const float *scale, uint32_t *xq, long long rows,
+                                      long long len, int l, void *stream)
+{
+    DK_REQUIRE(x && scale && xq, DK_ERR_NULL);
+    DK_REQUIRE(rows >= 1 && rows <= 65535 && len >= 1 && len <= (1ll << 40) && l >= 0 && l <= DKF_MAX_L,
+               DK_ERR_SHAPE);
+    DK_REQUIRE(dk_aligned(x, 4) && dk_aligned(scale, 4) && dk_aligned(xq, 4), DK_ERR_ALIGN);
+    return quantize_rows(x, scale, xq, rows, len, l, (hipStream_t)stream);
+}
+
+DK_EXPORT dk_status dkf_norm_scales(const float *x, float *scale, long long rows, long long len,
+                                    float limit, void *stream)
+{
+    DK_REQUIRE(x && scale, DK_ERR_NULL);
+    DK_REQUIRE(rows >= 1 && rows <= 65535 && len >= 1 && len <= (1ll << 40), DK_ERR_SHAPE);
+    DK_REQUIRE(limit > 0.0f && limit < INFINITY, DK_ERR_SHAPE);
+    DK_REQUIRE(dk_aligned(x, 4) && dk_aligned(scale, 4), DK_ERR_ALIGN);
     hipStream_t st = (hipStream_t)stream;
-    const bool v4 = vec4_ok(count, {x, xq});
-    const long long nvec = v4 ? count / 4 : count;
-    const long long blocks = (nvec + FT - 1) / FT;
-    DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
-    const double s = ldexp(1.0, l);
-    dk_prof_scope ps("f_quantize", st);
-    if (v4)
-        quantize_kernel<4><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(x, xq, nvec, s);
-    else
-        quantize_kernel<1><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(x, xq, nvec, s);
+    const bool v4 = vec4_ok(len, {x});
+    const long long nvec = v4 ? len / 4 : len;
+    // each lane reads up to `iters` vectors; spans shrink until the launch fills the chip
+    long long iters = 16;
+    while (iters > 1 && rows * ((nvec + FT * iters - 1) / (FT * iters)) < 4096) iters >>= 1;
+    const long long span = FT * iters;
+    const long long chunks = (nvec + span - 1) / span;
+    DK_REQUIRE(chunks <= 0x7fffffffll, DK_ERR_SHAPE);
+    uint32_t *bits = reinterpret_cast<uint32_t *>(scale);
+    {
+        dk_prof_scope ps("f_clear", st);
+        f_clear_u32_kernel<<<dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st>>>(bits, rows);
+    }
+    DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+    {
+        dk_prof_scope ps("f_absmax", st);
+        const dim3 grid((unsigned)chunks, (unsigned)rows);
+        if (v4)
+            absmax_kernel<4><<<grid, dim3(FT), 0, st>>>(x, bits, nvec, span);
+        else
+            absmax_kernel<1><<<grid, dim3(FT), 0, st>>>(x, bits, nvec, span);
+    }
+    DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+    dk_prof_scope ps("f_norm_scale", st);
+    norm_scale_kernel<<<dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st>>>(bits, rows, limit);
     return dk_launch_status();
 }
 
@@ -417,7 +539,22 @@ DK_EXPORT dk_status dkf_encode(const float *x, const uint32_t *r, const uint32_t
     if (s != DK_OK) return s;
     DK_REQUIRE(dk_aligned(x, 4) && dk_aligned(r, 4) && dk_aligned(A, 4) && dk_aligned(xbar, 4), DK_ERR_ALIGN);
     hipStream_t st = (hipStream_t)stream;
-#define CALL(KK) launch_encode<KK>(x, r, A, xbar, G, n, l, st)
+#define CALL(KK) launch_encode<KK>(x, nullptr, r, A, xbar, G, n, l, st)
+    DKF_K_SWITCH(K, CALL)
+#undef CALL
+}
+
+DK_EXPORT dk_status dkf_encode_norm(const float *x, const float *xscale, const uint32_t *r,
+                                    const uint32_t *A, uint32_t *xbar, int G, int K, long long n,
+                                    int l, void *stream)
+{
+    DK_REQUIRE(x && xscale && r && A && xbar, DK_ERR_NULL);
+    const dk_status s = check_args(G, K, n, l);
+    if (s != DK_OK) return s;
+    DK_REQUIRE(dk_aligned(x, 4) && dk_aligned(xscale, 4) && dk_aligned(r, 4) && dk_aligned(A, 4) &&
+                   dk_aligned(xbar, 4), DK_ERR_ALIGN);
+    hipStream_t st = (hipStream_t)stream;
+#define CALL(KK) launch_encode<KK>(x, xscale, r, A, xbar, G, n, l, st)
     DKF_K_SWITCH(K, CALL)
 #undef CALL
 }
@@ -432,7 +569,24 @@ DK_EXPORT dk_status dkf_decode_verify(const uint32_t *ybar, const uint32_t *Ainv
     DK_REQUIRE(dk_aligned(ybar, 4) && dk_aligned(Ainv, 4) && dk_aligned(nvec, 4) && dk_aligned(y, 4) &&
                    dk_aligned(verdict, 4) && (!yq || dk_aligned(yq, 4)), DK_ERR_ALIGN);
     hipStream_t st = (hipStream_t)stream;
-#define CALL(KK) launch_decode_verify<KK>(ybar, Ainv, nvec, y, yq, verdict, G, m, l, st)
+#define CALL(KK) launch_decode_verify<KK>(ybar, Ainv, nvec, nullptr, nullptr, y, yq, verdict, G, m, l, st)
+    DKF_K_SWITCH(K, CALL)
+#undef CALL
+}
+
+DK_EXPORT dk_status dkf_decode_verify_norm(const uint32_t *ybar, const uint32_t *Ainv,
+                                           const uint32_t *nvec, const float *xscale,
+                                           const float *wscale, float *y, uint32_t *yq, int *verdict,
+                                           int G, int K, long long m, int l, void *stream)
+{
+    DK_REQUIRE(ybar && Ainv && nvec && xscale && wscale && y && verdict, DK_ERR_NULL);
+    const dk_status s = check_args(G, K, m, l);
+    if (s != DK_OK) return s;
+    DK_REQUIRE(dk_aligned(ybar, 4) && dk_aligned(Ainv, 4) && dk_aligned(nvec, 4) && dk_aligned(y, 4) &&
+                   dk_aligned(xscale, 4) && dk_aligned(wscale, 4) && dk_aligned(verdict, 4) &&
+                   (!yq || dk_aligned(yq, 4)), DK_ERR_ALIGN);
+    hipStream_t st = (hipStream_t)stream;
+#define CALL(KK) launch_decode_verify<KK>(ybar, Ainv, nvec, xscale, wscale, y, yq, verdict, G, m, l, st)
     DKF_K_SWITCH(K, CALL)
 #undef CALL
 }

@@ -955,10 +955,12 @@ DK_EXPORT dk_status dkf_linear_fwd(const uint32_t *Wq, const uint32_t *xbar, uin
     return run_fgemm(pl, Ap, Bp, part, flag, ybar, nullptr, 0, 1.0f, 0, 0, "f_gemm_fwd", st);
 }
 
-DK_EXPORT dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint32_t *B,
-                              const uint32_t *gamma, const uint32_t *xbar, float *dW, uint32_t *dwq,
-                              int G, int K, int l, float scale, int accumulate,
-                              void *ws, size_t ws_bytes, void *stream)
+namespace {
+
+dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *xscale, const uint32_t *B,
+                     const uint32_t *gamma, const uint32_t *xbar, float *dW, uint32_t *dwq,
+                     int G, int K, int l, float scale, int accumulate,
+                     void *ws, size_t ws_bytes, void *stream)
 {
     DK_REQUIRE(L && delta && B && gamma && xbar && dW, DK_ERR_NULL);
     dk_geom g;
@@ -984,7 +986,7 @@ DK_EXPORT dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint3
     int8_t *Bp = (int8_t *)w;                      w += pl.b_bytes;
     uint32_t *part = (uint32_t *)w;
 
-    dk_status s = dkf_delta_mix(delta, B, gamma, dtilde, G, K, g.m, l, st);
+    dk_status s = dkf_delta_mix(delta, xscale, B, gamma, dtilde, G, K, g.m, l, st);
     if (s != DK_OK) return s;
     {
         dk_prof_scope ps("f_flag_clear", st);
@@ -1006,4 +1008,26 @@ DK_EXPORT dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint3
         if (s != DK_OK) return s;
     }
     return run_fgemm(pl, Ap, Bp, part, flag, dwq, dW, l, scale, accumulate, 0, "f_gemm_wgrad", st);
+}
+
+} // namespace
+
+DK_EXPORT dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint32_t *B,
+                              const uint32_t *gamma, const uint32_t *xbar, float *dW, uint32_t *dwq,
+                              int G, int K, int l, float scale, int accumulate,
+                              void *ws, size_t ws_bytes, void *stream)
+{
+    return wgrad_impl(L, delta, nullptr, B, gamma, xbar, dW, dwq, G, K, l, scale, accumulate, ws,
+                      ws_bytes, stream);
+}
+
+DK_EXPORT dk_status dkf_wgrad_norm(const dk_layer *L, const float *delta, const float *xscale,
+                                   const uint32_t *B, const uint32_t *gamma, const uint32_t *xbar,
+                                   float *dW, uint32_t *dwq, int G, int K, int l, float scale,
+                                   int accumulate, void *ws, size_t ws_bytes, void *stream)
+{
+    DK_REQUIRE(xscale, DK_ERR_NULL);
+    DK_REQUIRE(dk_aligned(xscale, 4), DK_ERR_ALIGN);
+    return wgrad_impl(L, delta, xscale, B, gamma, xbar, dW, dwq, G, K, l, scale, accumulate, ws,
+                      ws_bytes, stream);
 }

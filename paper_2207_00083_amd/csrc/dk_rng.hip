@@ -153,7 +153,8 @@ __global__ __launch_bounds__(RT) void encode_rng_kernel(const float *__restrict_
 
 // Field version: Xq quantised on the fly, one noise row, exact arithmetic.
 template <int K, bool VEC>
-__global__ __launch_bounds__(RT) void f_encode_rng_kernel(const float *__restrict__ x, const uint32_t *__restrict__ A,
+__global__ __launch_bounds__(RT) void f_encode_rng_kernel(const float *__restrict__ x, const float *__restrict__ xscale,
+                                                          const uint32_t *__restrict__ A,
                                                           uint32_t *__restrict__ xbar, long long len,
                                                           long long nblk, int chunks, long long span, double s,
                                                           uint32_t k0, uint32_t k1)
@@ -164,6 +165,10 @@ __global__ __launch_bounds__(RT) void f_encode_rng_kernel(const float *__restric
     const uint32_t *Ag = A + (long long)g * S * S;
     const float *src = x + (long long)g * K * len;
     uint32_t *dst = xbar + (long long)g * S * len;
+    // 2^l times the row's normalisation factor, if any (exact in fp64)
+    double si[K];
+#pragma unroll
+    for (int i = 0; i < K; ++i) si[i] = xscale ? s * (double)xscale[(long long)g * K + i] : s;
 
     const long long b0 = (long long)chunk * span;
     long long b1 = b0 + span;
@@ -181,10 +186,10 @@ __global__ __launch_bounds__(RT) void f_encode_rng_kernel(const float *__restric
             if (i < K) {
                 if (VEC) {
                     const f32x4 t = *reinterpret_cast<const f32x4 *>(src + (long long)i * len + e);
-                    q[0] = dkf_quant(t.x, s); q[1] = dkf_quant(t.y, s); q[2] = dkf_quant(t.z, s); q[3] = dkf_quant(t.w, s);
+                    q[0] = dkf_quant(t.x, si[i]); q[1] = dkf_quant(t.y, si[i]); q[2] = dkf_quant(t.z, si[i]); q[3] = dkf_quant(t.w, si[i]);
                 } else {
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) q[c] = e + c < len ? dkf_quant(src[(long long)i * len + e + c], s) : 0u;
+                    for (int c = 0; c < 4; ++c) q[c] = e + c < len ? dkf_quant(src[(long long)i * len + e + c], si[i]) : 0u;
                 }
             } else {
                 uint32_t lo[2], hi[2];
@@ -268,8 +273,8 @@ dk_status launch_encode_rng(const float *x, const float *A, float *xbar, int G, 
 }
 
 template <int K>
-dk_status launch_f_encode_rng(const float *x, const uint32_t *A, uint32_t *xbar, int G, long long n, int l,
-                              uint32_t k0, uint32_t k1, hipStream_t st)
+dk_status launch_f_encode_rng(const float *x, const float *xscale, const uint32_t *A, uint32_t *xbar, int G,
+                              long long n, int l, uint32_t k0, uint32_t k1, hipStream_t st)
 {
     const rspan p = plan_rspan(n, G);
     const long long blocks = (long long)G * p.chunks;
@@ -277,10 +282,10 @@ dk_status launch_f_encode_rng(const float *x, const uint32_t *A, uint32_t *xbar,
     const double s = ldexp(1.0, l);
     dk_prof_scope ps("f_encode_rng", st);
     if (vec_ok(n, {x, xbar}))
-        f_encode_rng_kernel<K, true><<<dim3((unsigned)blocks), dim3(RT), 0, st>>>(x, A, xbar, n, p.nblk, p.chunks,
+        f_encode_rng_kernel<K, true><<<dim3((unsigned)blocks), dim3(RT), 0, st>>>(x, xscale, A, xbar, n, p.nblk, p.chunks,
                                                                                 p.span, s, k0, k1);
     else
-        f_encode_rng_kernel<K, false><<<dim3((unsigned)blocks), dim3(RT), 0, st>>>(x, A, xbar, n, p.nblk, p.chunks,
+        f_encode_rng_kernel<K, false><<<dim3((unsigned)blocks), dim3(RT), 0, st>>>(x, xscale, A, xbar, n, p.nblk, p.chunks,
                                                                                  p.span, s, k0, k1);
     return dk_launch_status();
 }
@@ -341,7 +346,22 @@ DK_EXPORT dk_status dkf_encode_rng(const float *x, const uint32_t *A, uint32_t *
     DK_REQUIRE(dk_aligned(x, 4) && dk_aligned(A, 4) && dk_aligned(xbar, 4), DK_ERR_ALIGN);
     hipStream_t st = (hipStream_t)stream;
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
-#define CALL(KK) launch_f_encode_rng<KK>(x, A, xbar, G, n, l, k0, k1, st)
+#define CALL(KK) launch_f_encode_rng<KK>(x, nullptr, A, xbar, G, n, l, k0, k1, st)
+    DKR_K_SWITCH(K, CALL)
+#undef CALL
+}
+
+DK_EXPORT dk_status dkf_encode_rng_norm(const float *x, const float *xscale, const uint32_t *A,
+                                        uint32_t *xbar, int G, int K, long long n, int l,
+                                        unsigned long long seed, void *stream)
+{
+    DK_REQUIRE(x && xscale && A && xbar, DK_ERR_NULL);
+    DK_REQUIRE(G >= 1 && K >= 1 && K <= DK_MAX_K && n >= 1 && n <= (1ll << 40), DK_ERR_SHAPE);
+    DK_REQUIRE(l >= 0 && l <= DKF_MAX_L, DK_ERR_SHAPE);
+    DK_REQUIRE(dk_aligned(x, 4) && dk_aligned(xscale, 4) && dk_aligned(A, 4) && dk_aligned(xbar, 4), DK_ERR_ALIGN);
+    hipStream_t st = (hipStream_t)stream;
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+#define CALL(KK) launch_f_encode_rng<KK>(x, xscale, A, xbar, G, n, l, k0, k1, st)
     DKR_K_SWITCH(K, CALL)
 #undef CALL
 }

@@ -31,6 +31,33 @@ def _new_fe(shape, like):
     return torch.empty(shape, dtype=torch.int32, device=like.device)
 
 
+def _scales(t, count, name):
+    """A float32 device tensor of `count` normalisation factors, or None."""
+    if t is None:
+        return None
+    t = _dev(t, name)
+    if t.numel() != count:
+        raise ValueError("%s must hold %d factors" % (name, count))
+    return t
+
+
+def dkf_norm_scales(x, limit, rows=None, scale=None, stream=None):
+    """One normalisation factor per row of x (device): 1/max|row| when that
+    maximum exceeds `limit`, else 1.  rows defaults to x.shape[0]; rows=1 treats
+    the whole tensor (a weight tensor) as one vector."""
+    torch = _torch()
+    x = _dev(x, "x")
+    rows = int(x.shape[0] if rows is None else rows)
+    if rows < 1 or x.numel() % rows:
+        raise ValueError("dkf_norm_scales: rows does not divide the tensor")
+    if scale is None:
+        scale = torch.empty(rows, dtype=torch.float32, device=x.device)
+    _scales(scale, rows, "scale")
+    _check(load().dkf_norm_scales(_ptr(x), _ptr(scale), rows, x.numel() // rows, float(limit),
+                                  _stream(stream)), "dkf_norm_scales")
+    return scale
+
+
 def dkf_coeffs(A, gamma):
     """Host arrays A[G,S,S], gamma[G,S] (uint32 field elements) ->
     host Ainv[G,S,S], nvec[G,S], B[G,S,K] (uint32)."""
@@ -46,13 +73,22 @@ def dkf_coeffs(A, gamma):
     return Ainv, nvec, B
 
 
-def dkf_quantize(x, l=DKF_L, xq=None, stream=None):
+def dkf_quantize(x, l=DKF_L, xq=None, stream=None, scale=None):
+    """scale (device, one factor per row; numel gives the number of rows)
+    selects dkf_quantize_norm."""
     x = _dev(x, "x")
     if xq is None:
         xq = _new_fe(tuple(x.shape), x)
     _fe(xq, "xq")
     if xq.numel() != x.numel():
         raise ValueError("dkf_quantize: xq has the wrong size")
+    if scale is not None:
+        rows = _dev(scale, "scale").numel()
+        if rows < 1 or x.numel() % rows:
+            raise ValueError("dkf_quantize: the number of factors does not divide the tensor")
+        _check(load().dkf_quantize_norm(_ptr(x), _ptr(scale), _ptr(xq), rows, x.numel() // rows, int(l),
+                                        _stream(stream)), "dkf_quantize_norm")
+        return xq
     _check(load().dkf_quantize(_ptr(x), _ptr(xq), x.numel(), int(l), _stream(stream)), "dkf_quantize")
     return xq
 
@@ -69,8 +105,9 @@ def dkf_dequantize(yq, l=DKF_L, y=None, stream=None):
     return y
 
 
-def dkf_encode(x, r, A, K, l=DKF_L, xbar=None, stream=None):
-    """x[G*K, ...] float, r[G, ...], A[G,S,S] field elements (device) -> xbar[G*S, ...]."""
+def dkf_encode(x, r, A, K, l=DKF_L, xbar=None, stream=None, xscale=None):
+    """x[G*K, ...] float, r[G, ...], A[G,S,S] field elements (device) -> xbar[G*S, ...].
+    xscale[G*K] (device) selects dkf_encode_norm."""
     x, r, A = _dev(x, "x"), _fe(r, "r"), _fe(A, "A")
     G, S = r.shape[0], K + 2
     n = x[0].numel()
@@ -81,6 +118,11 @@ def dkf_encode(x, r, A, K, l=DKF_L, xbar=None, stream=None):
     _fe(xbar, "xbar")
     if xbar.numel() != G * S * n:
         raise ValueError("dkf_encode: xbar has the wrong size")
+    if xscale is not None:
+        _scales(xscale, G * K, "xscale")
+        _check(load().dkf_encode_norm(_ptr(x), _ptr(xscale), _ptr(r), _ptr(A), _ptr(xbar), G, K, n, int(l),
+                                      _stream(stream)), "dkf_encode_norm")
+        return xbar
     _check(load().dkf_encode(_ptr(x), _ptr(r), _ptr(A), _ptr(xbar), G, K, n, int(l), _stream(stream)),
            "dkf_encode")
     return xbar
@@ -95,8 +137,9 @@ def dkf_noise_rng(G, feat, seed, device="cuda", stream=None):
     return r
 
 
-def dkf_encode_rng(x, A, K, seed, l=DKF_L, xbar=None, stream=None):
-    """x[G*K, ...] float, A[G,S,S] field elements (device) -> xbar[G*S, ...]; noise from the seed."""
+def dkf_encode_rng(x, A, K, seed, l=DKF_L, xbar=None, stream=None, xscale=None):
+    """x[G*K, ...] float, A[G,S,S] field elements (device) -> xbar[G*S, ...]; noise from the seed.
+    xscale[G*K] (device) selects dkf_encode_rng_norm."""
     x, A = _dev(x, "x"), _fe(A, "A")
     G, S = A.shape[0], K + 2
     n = x[0].numel()
@@ -107,6 +150,11 @@ def dkf_encode_rng(x, A, K, seed, l=DKF_L, xbar=None, stream=None):
     _fe(xbar, "xbar")
     if xbar.numel() != G * S * n:
         raise ValueError("dkf_encode_rng: xbar has the wrong size")
+    if xscale is not None:
+        _scales(xscale, G * K, "xscale")
+        _check(load().dkf_encode_rng_norm(_ptr(x), _ptr(xscale), _ptr(A), _ptr(xbar), G, K, n, int(l), int(seed),
+                                          _stream(stream)), "dkf_encode_rng_norm")
+        return xbar
     _check(load().dkf_encode_rng(_ptr(x), _ptr(A), _ptr(xbar), G, K, n, int(l), int(seed), _stream(stream)),
            "dkf_encode_rng")
     return xbar
@@ -165,8 +213,9 @@ def dkf_conv_fwd(layer, Wq, xbar, ybar=None, ws=None, stream=None):
 
 
 def dkf_decode_verify(ybar, Ainv, nvec, K, l=DKF_L, y=None, yq=None, verdict=None, want_yq=False,
-                      stream=None):
-    """Returns (y float, yq or None, verdict int32)."""
+                      stream=None, xscale=None, wscale=None):
+    """Returns (y float, yq or None, verdict int32).  xscale[G*K] and wscale[1]
+    (device, both or neither) select dkf_decode_verify_norm."""
     torch = _torch()
     ybar, Ainv, nvec = _fe(ybar, "ybar"), _fe(Ainv, "Ainv"), _fe(nvec, "nvec")
     G, S = Ainv.shape[0], K + 2
@@ -184,14 +233,24 @@ def dkf_decode_verify(ybar, Ainv, nvec, K, l=DKF_L, y=None, yq=None, verdict=Non
         raise ValueError("dkf_decode_verify: output has the wrong size")
     if verdict is None:
         verdict = torch.empty(G, dtype=torch.int32, device=ybar.device)
+    if (xscale is None) != (wscale is None):
+        raise ValueError("dkf_decode_verify: xscale and wscale come together")
+    if xscale is not None:
+        _scales(xscale, G * K, "xscale")
+        _scales(wscale, 1, "wscale")
+        _check(load().dkf_decode_verify_norm(_ptr(ybar), _ptr(Ainv), _ptr(nvec), _ptr(xscale), _ptr(wscale),
+                                             _ptr(y), _ptr(yq), _ptr(verdict), G, K, m, int(l),
+                                             _stream(stream)), "dkf_decode_verify_norm")
+        return y, yq, verdict
     _check(load().dkf_decode_verify(_ptr(ybar), _ptr(Ainv), _ptr(nvec), _ptr(y), _ptr(yq), _ptr(verdict),
                                     G, K, m, int(l), _stream(stream)), "dkf_decode_verify")
     return y, yq, verdict
 
 
 def dkf_wgrad(layer, delta, B, gamma, xbar, K, l=DKF_L, dW=None, dwq=None, want_dwq=False, scale=1.0,
-              accumulate=False, ws=None, stream=None):
-    """delta[G*K, ...] float, B[G,S,K], gamma[G,S], xbar[G*S, ...] (device) -> (dW float, dwq or None)."""
+              accumulate=False, ws=None, stream=None, xscale=None):
+    """delta[G*K, ...] float, B[G,S,K], gamma[G,S], xbar[G*S, ...] (device) -> (dW float, dwq or None).
+    xscale[G*K] (device, the factors the encodings were made with) selects dkf_wgrad_norm."""
     torch = _torch()
     lay = DkLayer.of(layer)
     delta, B, gamma, xbar = _dev(delta, "delta"), _fe(B, "B"), _fe(gamma, "gamma"), _fe(xbar, "xbar")
@@ -217,6 +276,12 @@ def dkf_wgrad(layer, delta, B, gamma, xbar, K, l=DKF_L, dW=None, dwq=None, want_
         raise ValueError("dkf_wgrad: output has the wrong size")
     if ws is None:
         ws = _workspace(dkf_wgrad_workspace_bytes(lay, G, K), delta)
+    if xscale is not None:
+        _scales(xscale, G * K, "xscale")
+        _check(load().dkf_wgrad_norm(C.byref(lay), _ptr(delta), _ptr(xscale), _ptr(B), _ptr(gamma), _ptr(xbar),
+                                     _ptr(dW), _ptr(dwq), G, K, int(l), float(scale), int(bool(accumulate)),
+                                     _ptr(ws), ws.numel(), _stream(stream)), "dkf_wgrad_norm")
+        return dW, dwq
     _check(load().dkf_wgrad(C.byref(lay), _ptr(delta), _ptr(B), _ptr(gamma), _ptr(xbar), _ptr(dW),
                             _ptr(dwq), G, K, int(l), float(scale), int(bool(accumulate)), _ptr(ws),
                             ws.numel(), _stream(stream)), "dkf_wgrad")

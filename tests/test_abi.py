@@ -158,6 +158,19 @@ def test_field_errors_before_launch(dk):
     assert lib.dkf_conv_fwd(C.byref(conv), one, one, one, 0, one, 1 << 30, null) == 2
     assert lib.dkf_conv_fwd(C.byref(conv), one, one, one, 4, one, 64, null) == 5
     assert lib.dkf_wgrad(C.byref(lin), one, one, one, one, one, null, 1, 2, 8, 1.0, 0, one, 64, null) == 5
+    f = C.c_float
+    assert lib.dkf_norm_scales(null, one, 1, 8, f(1.0), null) == 1
+    assert lib.dkf_norm_scales(one, one, 0, 8, f(1.0), null) == 2
+    assert lib.dkf_norm_scales(one, one, 65536, 8, f(1.0), null) == 2
+    assert lib.dkf_norm_scales(one, one, 1, 8, f(0.0), null) == 2
+    assert lib.dkf_quantize_norm(one, null, one, 1, 8, 8, null) == 1
+    assert lib.dkf_quantize_norm(one, one, one, 1, 8, 13, null) == 2
+    assert lib.dkf_encode_norm(one, null, one, one, one, 1, 2, 8, 8, null) == 1
+    assert lib.dkf_encode_rng_norm(one, null, one, one, 1, 2, 8, 8, 0, null) == 1
+    assert lib.dkf_encode_rng_norm(one, one, one, one, 1, 17, 8, 8, 0, null) == 2
+    assert lib.dkf_decode_verify_norm(one, one, one, one, null, one, null, one, 1, 2, 8, 8, null) == 1
+    assert lib.dkf_wgrad_norm(C.byref(lin), one, null, one, one, one, one, null, 1, 2, 8, f(1.0), 0, one, 64,
+                              null) == 1
     assert dk.dkf_fwd_workspace_bytes(4, 4, 4) > 0 and dk.dkf_fwd_workspace_bytes(0, 4, 4) == 0
     assert dk.dkf_wgrad_workspace_bytes(dk_inputs.linear(4, 4), 1, 2) > 0
 
