@@ -280,9 +280,12 @@ def field_main(args):
     tops = op_step / (ms_per_step * 1e-3) / 1e12
     # The contraction kernel runs twice a step.  The forward multiplies 4 digit
     # planes of the encodings with the 2 non-zero planes of ordinary weights
-    # (8 int8 products per field product), the weight gradient 4 x 4 planes (16).
-    # The roofline record is the longer of the two launches.
-    gemm = {"f_gemm_fwd": 8, "f_gemm_wgrad": 16}
+    # (8 int8 products per field product), the weight gradient 4 x 4 planes (16),
+    # or three products of half against half (12) where the operands come with
+    # digit-sum planes: dense layers and 1x1 convolutions.  Executed products
+    # are counted.  The roofline record is the longer of the two launches.
+    three_part = L.kind == "linear" or L.kh * L.kw == 1
+    gemm = {"f_gemm_fwd": 8, "f_gemm_wgrad": 12 if three_part else 16}
     dom = max(gemm, key=lambda k: kernels[k][0])
     gemm_ms = kernels[dom][0]
     int8_ops = 2.0 * mac * gemm[dom]

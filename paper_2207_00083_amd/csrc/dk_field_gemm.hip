@@ -21,6 +21,15 @@
 // are folded by modular addition.  All of it is exact: the result is the field
 // product whatever the tiling.
 //
+// When both operands have non-zero high halves (the weight gradient: masked
+// values are uniform over the field) the four parts become three: with
+// L, H the halves and S = L + H taken digit by digit (e0 + e2 in [-128, 126],
+// e1 + e3 in [-72, 71]: still int8),
+//     A B = L_A L_B (1 - 128^2) + S_A S_B 128^2 + H_A H_B (128^4 - 128^2),
+// so a third pair of planes holding S replaces a quarter of the MFMAs, of the
+// LDS traffic and of the operand fetches.  A sum-half accumulator grows by at
+// most 2 * 128 * 72 per k, so 2^16 values of k fit an int32.
+//
 // The contraction index has to be contiguous for both operands; digit planes
 // are written k-major by the digit kernels (straight for row-major operands,
 // through an LDS transpose for the weight gradient, whose contraction index is
@@ -35,11 +44,12 @@ constexpr int PITCH = 144;             // LDS row pitch in bytes: 16 (mod 32) ke
 constexpr int B_PLANE = BJ * PITCH;
 constexpr int LDS_BYTES = 2 * (2 * BI * PITCH + 2 * B_PLANE);   // 147456: two buffers of the 128-row tile
 constexpr int MAX_KSPLIT = 1 << 17;    // k values per slice (int32 accumulators)
+constexpr int MAX_KSPLIT_SUMS = 1 << 16;   // ... when the digit-sum planes are multiplied
 constexpr int MAX_SPLITS = 256;        // k slices per output tile (the fold adds their residues in 64 bits)
 
 struct fgemm_params {
-    const int8_t *Ap;      // [4][I_pad][Kp]
-    const int8_t *Bp;      // [4][J_pad][Kp]
+    const int8_t *Ap;      // [4 or 6][I_pad][Kp]
+    const int8_t *Bp;      // [4 or 6][J_pad][Kp]
     uint32_t *out_q;       // residues [splits][I][J] (a slice per k split), or NULL
     float *out_f;          // de-quantised result [I][J] (only with one split), or NULL
     const int *flags;      // [0]: A has non-zero high digits, [1]: B has (device)
@@ -52,6 +62,7 @@ struct fgemm_params {
     double s_inv;          // 2^-l for out_f
     float scale;
     int accumulate;
+    int sums;              // planes 4, 5 of both operands hold the digit sums of the halves
 };
 
 // Four balanced base-128 digits of the centred lift of q, packed one per byte.
@@ -67,6 +78,14 @@ __device__ __forceinline__ uint32_t digits_of(uint32_t q)
     const int e3 = (w - e2) >> 7;
     return (uint32_t)(e0 & 255) | (uint32_t)(e1 & 255) << 8 | (uint32_t)(e2 & 255) << 16 |
            (uint32_t)(e3 & 255) << 24;
+}
+
+// (e0 + e2, e1 + e3) of a packed-digit word in its two low bytes: a byte-wise
+// add of the two half-words (no carry from one byte into the next)
+__device__ __forceinline__ uint32_t half_sums(uint32_t d)
+{
+    const uint32_t lo = d & 0xffffu, hi = d >> 16;
+    return ((lo & 0x7f7fu) + (hi & 0x7f7fu)) ^ ((lo ^ hi) & 0x8080u);
 }
 
 // byte `a` of four packed-digit words -> one word of plane a
@@ -137,7 +156,7 @@ template <bool IM2COL>
 __global__ __launch_bounds__(256) void f_digits_t_kernel(const uint32_t *__restrict__ src,
                                                          int8_t *__restrict__ planes, fconv_geom g,
                                                          int K, int cols, int cols_pad, int Kp,
-                                                         int *flag)
+                                                         int sums, int *flag)
 {
     __shared__ uint32_t tile[128][65];
     const int c0 = blockIdx.x * 64, k0 = blockIdx.y * 128;
@@ -175,19 +194,25 @@ __global__ __launch_bounds__(256) void f_digits_t_kernel(const uint32_t *__restr
     for (int r = 0; r < 2; ++r) {
         const int item = threadIdx.x + 256 * r;       // (row, 16 k): eight lanes write 128 contiguous bytes
         const int kq = item & 7, col = item >> 3;
-        u32x4 w[4];
+        u32x4 w[6];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            uint32_t d[4];
+            uint32_t d[4], ds[4];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) d[c] = tile[16 * kq + 4 * g + c][col];
+            for (int c = 0; c < 4; ++c) {
+                d[c] = tile[16 * kq + 4 * g + c][col];
+                ds[c] = half_sums(d[c]);
+            }
 #pragma unroll
             for (int a = 0; a < 4; ++a) w[a][g] = gather_byte(d, a);
+            w[4][g] = gather_byte(ds, 0);
+            w[5][g] = gather_byte(ds, 1);
         }
         hi |= w[2].x | w[2].y | w[2].z | w[2].w | w[3].x | w[3].y | w[3].z | w[3].w;
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
-            *reinterpret_cast<u32x4 *>(planes + a * plane + (long long)(c0 + col) * Kp + k0 + 16 * kq) = w[a];
+        for (int a = 0; a < 6; ++a)
+            if (a < 4 || sums)
+                *reinterpret_cast<u32x4 *>(planes + a * plane + (long long)(c0 + col) * Kp + k0 + 16 * kq) = w[a];
     }
     raise_flag(flag, hi != 0);
 }
@@ -204,7 +229,7 @@ template <int MODE>
 __global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__restrict__ src,
                                                             int8_t *__restrict__ planes, fconv_geom g,
                                                             int rows, int K, int rows_pad, int Kp,
-                                                            int chunks, int *flag)
+                                                            int chunks, int sums, int *flag)
 {
     const int row = blockIdx.x / chunks;                       // workgroup-uniform
     const int k0 = ((blockIdx.x - row * chunks) * 256 + threadIdx.x) * 4;
@@ -246,6 +271,14 @@ __global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__re
         const uint32_t w = gather_byte(d, a);
         if (a >= 2) hi |= w;
         *reinterpret_cast<uint32_t *>(planes + a * plane + (long long)row * Kp + k0) = w;
+    }
+    if (sums) {
+        uint32_t ds[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) ds[c] = half_sums(d[c]);
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+            *reinterpret_cast<uint32_t *>(planes + (4 + a) * plane + (long long)row * Kp + k0) = gather_byte(ds, a);
     }
     raise_flag(flag, hi != 0);
 }
@@ -416,22 +449,32 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[bi][bj][s][v] = 0;
 
-    // The active parts in the order (lo,lo), (hi,lo), (lo,hi), (hi,hi): weights
-    // 128^0, 128^2, 128^2, 128^4, so the two middle parts share accumulators.
+    // A part is a pair of plane pairs (0 low, 1 high, 2 digit sums), A's in bits
+    // 0-1 and B's in bits 2-3.  The active parts in the order (lo,lo), (hi,lo),
+    // (lo,hi), (hi,hi): weights 128^0, 128^2, 128^2, 128^4, so the two middle parts
+    // share accumulators (one weight group).  With the sum planes and both high
+    // halves present: (lo,lo), (sum,sum), (hi,hi), a group each.
     // Steps (part, k tile) form one software-pipelined sequence.
-    int plist = 0, nparts = 0;           // two bits per active part
+    const bool three = p.sums && fa && fb;
+    int plist = 0, nparts = 0;           // four bits per active part
+    if (three) {
+        plist = 0x0 | 0xA << 4 | 0x5 << 8;
+        nparts = 3;
+    } else {
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-        if (!((q & 1) && !fa) && !((q >> 1) && !fb)) plist |= q << (2 * nparts++);
-#define DKF_PART(I) ((plist >> (2 * (I))) & 3)
+        for (int q = 0; q < 4; ++q)
+            if (!((q & 1) && !fa) && !((q >> 1) && !fb)) plist |= ((q & 1) | (q >> 1) << 2) << (4 * nparts++);
+    }
+#define DKF_PART(I) ((plist >> (4 * (I))) & 15)
+#define DKF_GROUP(Q) ((Q) == 0xA ? 1 : ((Q) & 1) + ((Q) >> 2))
     const int nsteps = nparts * (kt1 - kt0);
 
     i32x4 sa[NA], sb[8];
 #define DKF_FETCH(PI, KTILE)                                                                      \
     {                                                                                             \
         const int q_ = DKF_PART(PI);                                                              \
-        const int8_t *as_ = p.Ap + 2 * (q_ & 1) * p.a_plane + ((long long)ti * BI * p.Kp + (long long)(KTILE) * KT); \
-        const int8_t *bs_ = p.Bp + 2 * (q_ >> 1) * p.b_plane + ((long long)tj * BJ * p.Kp + (long long)(KTILE) * KT); \
+        const int8_t *as_ = p.Ap + 2 * (q_ & 3) * p.a_plane + ((long long)ti * BI * p.Kp + (long long)(KTILE) * KT); \
+        const int8_t *bs_ = p.Bp + 2 * (q_ >> 2) * p.b_plane + ((long long)tj * BJ * p.Kp + (long long)(KTILE) * KT); \
         _Pragma("unroll") for (int e = 0; e < NA; ++e)                                            \
             sa[e] = *reinterpret_cast<const i32x4 *>((as_ + ((e / (2 * NBI)) * p.a_plane + (e % (2 * NBI)) * q_rows)) + s_off); \
         if (!IMPL) {                                                                              \
@@ -442,7 +485,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
             const int tap_ = k0_ / p.cp, ci0_ = k0_ - tap_ * p.cp;                                \
             const int fa_ = tap_ / p.ckw, fb_ = tap_ - fa_ * p.ckw;                               \
             const bool tap_ok_ = tap_ < p.ckh * p.ckw;                                            \
-            const int8_t *bp_ = p.Bp + 2 * (q_ >> 1) * p.b_plane + ci0_;                          \
+            const int8_t *bp_ = p.Bp + 2 * (q_ >> 2) * p.b_plane + ci0_;                          \
             _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                       \
                 const int ih_ = r_ih[q] + fa_, iw_ = r_iw[q] + fb_;                               \
                 const bool ok_ = tap_ok_ && r_ok[q] && ih_ >= 0 && ih_ < p.cH && iw_ >= 0 && iw_ < p.cW; \
@@ -530,10 +573,8 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     // sub-step, and the loads of tile s+2 are issued right behind them.
     int step = 0;
     while (step < nsteps) {
-        const int q = DKF_PART(pi);
-        const int w = (q & 1) + (q >> 1);
-        const int qn = DKF_PART(pi + 1);
-        const int gparts = (pi + 1 < nparts && (qn & 1) + (qn >> 1) == w) ? 2 : 1;
+        const int w = DKF_GROUP(DKF_PART(pi));
+        const int gparts = (pi + 1 < nparts && DKF_GROUP(DKF_PART(pi + 1)) == w) ? 2 : 1;
         const int g_end = step + gparts * (kt1 - kt0);
         for (; step < g_end; ++step) {
             const int8_t *cur = flds + (step & 1) * BUF_BYTES;
@@ -572,11 +613,15 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         }
 
         // End of a weight group: recombine the three accumulators with the
-        // constants 128^(2w + s) mod p in 64 bits, reduce, add to the running
+        // constants gw 128^s mod p in 64 bits (gw = 128^(2w), or the weight of
+        // the group in the three-part form), reduce, add to the running
         // residues and clear the accumulators.
-        const int c0 = (int)dkf_reduce(1ull << (14 * w));
-        const int c1 = (int)dkf_reduce(1ull << (14 * w + 7));
-        const int c2 = (int)dkf_reduce(1ull << (14 * w + 14));
+        uint64_t gw = 1ull << (14 * w);
+        if (three) gw = w == 0 ? (uint64_t)DKF_P + 1 - (1u << 14) : w == 1 ? 1ull << 14 : (1ull << 28) - (1u << 14);
+        gw = dkf_reduce(gw);
+        const int c0 = (int)gw;
+        const int c1 = (int)dkf_reduce(gw << 7);
+        const int c2 = (int)dkf_reduce(gw << 14);
 #pragma unroll
         for (int bi = 0; bi < NBI; ++bi)
 #pragma unroll
@@ -598,6 +643,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         __builtin_amdgcn_sched_barrier(0);
     }
 #undef DKF_PART
+#undef DKF_GROUP
 #undef DKF_ADVANCE
 #undef DKF_PACE_READS
 #undef DKF_KEEP
@@ -665,12 +711,16 @@ struct fgemm_plan {
     int I, J, K, I_pad, J_pad, Kp;
     int tiles_i, tiles_j, ktiles, splits, ktiles_per_split;
     int nbi;              // 1: 64-row tiles, 2: 128-row tiles
+    int sums;             // the operands carry the digit-sum planes (six planes each)
     size_t a_bytes, b_bytes, part_bytes;
 };
 
-// I, J: output dimensions; K: contraction length.
-bool plan_fgemm(long long I, long long J, long long K, fgemm_plan *pl)
+// I, J: output dimensions; K: contraction length; sums: both operands come
+// with digit-sum planes (shorter k slices, see the top of the file).
+bool plan_fgemm(long long I, long long J, long long K, fgemm_plan *pl, bool sums = false)
 {
+    const int max_kslice = sums ? MAX_KSPLIT_SUMS : MAX_KSPLIT;
+    pl->sums = sums ? 1 : 0;
     if (I < 1 || J < 1 || K < 1 || I > (1 << 24) || J > (1 << 24) || K > (1 << 26)) return false;
     pl->I = (int)I; pl->J = (int)J; pl->K = (int)K;
     pl->nbi = (I % 128 != 0 && I % 128 <= 64) ? 1 : 2;      // a last half-empty 128-row tile: use 64-row tiles
@@ -686,7 +736,7 @@ bool plan_fgemm(long long I, long long J, long long K, fgemm_plan *pl)
     // MAX_SPLITS, and among those the count that wastes the
     // least of the last round of workgroups on the 256 compute units (one
     // workgroup per unit), with a small charge per extra slice for its fold.
-    const long long need = ((long long)pl->Kp + MAX_KSPLIT - 1) / MAX_KSPLIT;
+    const long long need = ((long long)pl->Kp + max_kslice - 1) / max_kslice;
     long long splits = need;
     double best = 1e30;
     for (long long sp = need; sp <= MAX_SPLITS && sp <= pl->ktiles; ++sp) {
@@ -698,11 +748,12 @@ bool plan_fgemm(long long I, long long J, long long K, fgemm_plan *pl)
     if (splits > pl->ktiles) splits = pl->ktiles;
     if (splits < 1) splits = 1;
     int per = (int)((pl->ktiles + splits - 1) / splits);
-    if ((long long)per * KT > MAX_KSPLIT) return false;
+    if ((long long)per * KT > max_kslice) return false;
     pl->ktiles_per_split = per;
     pl->splits = (pl->ktiles + per - 1) / per;
-    pl->a_bytes = align256((size_t)4 * pl->I_pad * pl->Kp);
-    pl->b_bytes = align256((size_t)4 * pl->J_pad * pl->Kp);
+    const size_t nplanes = sums ? 6 : 4;
+    pl->a_bytes = align256(nplanes * pl->I_pad * pl->Kp);
+    pl->b_bytes = align256(nplanes * pl->J_pad * pl->Kp);
     pl->part_bytes = pl->splits > 1
         ? align256((size_t)pl->splits * (size_t)I * (size_t)J * sizeof(uint32_t)) : 0;
     return true;
@@ -740,6 +791,7 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
     p.tiles_i = pl.tiles_i; p.tiles_j = pl.tiles_j; p.splits = pl.splits;
     p.ktiles_per_split = pl.ktiles_per_split; p.ktiles = pl.ktiles;
     p.s_inv = ldexp(1.0, -l); p.scale = scale; p.accumulate = accumulate;
+    p.sums = pl.sums;
     p.out_hw = direct ? out_hw : 0;
     p.cp = p.cH = p.cW = p.ckh = p.ckw = p.cstride = p.cpad = p.cWo = p.cHoWo = 0;
     if (impl) {
@@ -780,25 +832,25 @@ dk_status run_digits(const uint32_t *src, int8_t *planes, int rows, int K, int r
 }
 
 dk_status run_digits_t(const uint32_t *src, int8_t *planes, int K, int cols, int cols_pad, int Kp,
-                       int *flag, hipStream_t st)
+                       int sums, int *flag, hipStream_t st)
 {
     DK_REQUIRE(Kp / 128 <= 65535, DK_ERR_SHAPE);
     dk_prof_scope ps("f_digits_t", st);
     f_digits_t_kernel<false><<<dim3(cols_pad / 64, Kp / 128), dim3(256), 0, st>>>(src, planes, fconv_geom{},
-                                                                                K, cols, cols_pad, Kp, flag);
+                                                                                K, cols, cols_pad, Kp, sums, flag);
     return dk_launch_status();
 }
 
 template <int MODE>
 dk_status run_digits_conv(const uint32_t *src, int8_t *planes, const fconv_geom &cg, int rows, int K,
-                          int rows_pad, int Kp, int *flag, hipStream_t st)
+                          int rows_pad, int Kp, int sums, int *flag, hipStream_t st)
 {
     const int chunks = (Kp / 4 + 255) / 256;
     const long long blocks = (long long)rows_pad * chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     dk_prof_scope ps(MODE == 1 ? "f_digits_dt" : "f_digits_im2col_t", st);
     f_digits_conv_kernel<MODE><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(src, planes, cg, rows, K,
-                                                                             rows_pad, Kp, chunks, flag);
+                                                                             rows_pad, Kp, chunks, sums, flag);
     return dk_launch_status();
 }
 
@@ -829,7 +881,9 @@ bool plan_conv_fwd(const dk_geom &g, long long R, fgemm_plan *pl)
 }
 bool plan_conv_wgrad(const dk_geom &g, long long R, fgemm_plan *pl)
 {
-    return plan_fgemm(g.Co, g.Kg, R * g.Ho * g.Wo, pl);
+    // digit-sum planes only for 1x1 filters: otherwise every shifted copy of the
+    // encodings would grow by half, which costs more than the shorter product saves
+    return plan_fgemm(g.Co, g.Kg, R * g.Ho * g.Wo, pl, g.kh * g.kw == 1);
 }
 
 } // namespace
@@ -897,7 +951,7 @@ DK_EXPORT dk_status dkf_conv_fwd(const dk_layer *L, const uint32_t *Wq, const ui
         DK_REQUIRE(pl.Kp / 128 <= 65535, DK_ERR_SHAPE);
         dk_prof_scope ps("f_digits_im2col", st);
         f_digits_t_kernel<true><<<dim3(pl.J_pad / 64, pl.Kp / 128), dim3(256), 0, st>>>(
-            xbar, Bp, conv_geom_of(g), (int)g.Kg, pl.J, pl.J_pad, pl.Kp, flag + 1);
+            xbar, Bp, conv_geom_of(g), (int)g.Kg, pl.J, pl.J_pad, pl.Kp, 0, flag + 1);
     }
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
     return run_fgemm(pl, Ap, Bp, part, flag, ybar, nullptr, 0, 1.0f, 0, g.Ho * g.Wo, "f_gemm_fwd", st);
@@ -921,7 +975,7 @@ DK_EXPORT size_t dkf_wgrad_workspace_bytes(const dk_layer *L, int G, int K)
     if (G < 1 || K < 1 || K > DK_MAX_K) return 0;
     const long long R = (long long)G * (K + 2);
     fgemm_plan pl;
-    if (!(g.conv ? plan_conv_wgrad(g, R, &pl) : plan_fgemm(g.M, g.N, R, &pl))) return 0;
+    if (!(g.conv ? plan_conv_wgrad(g, R, &pl) : plan_fgemm(g.M, g.N, R, &pl, true))) return 0;
     return FLAG_BYTES + align256((size_t)R * g.m * sizeof(uint32_t)) + pl.a_bytes + pl.b_bytes + pl.part_bytes;
 }
 
@@ -970,7 +1024,7 @@ dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *xscale,
     DK_REQUIRE(G >= 1 && K >= 1 && K <= DK_MAX_K && l >= 0 && l <= DKF_MAX_L, DK_ERR_SHAPE);
     const long long R = (long long)G * (K + 2);
     fgemm_plan pl;
-    DK_REQUIRE(g.conv ? plan_conv_wgrad(g, R, &pl) : plan_fgemm(g.M, g.N, R, &pl), DK_ERR_SHAPE);
+    DK_REQUIRE(g.conv ? plan_conv_wgrad(g, R, &pl) : plan_fgemm(g.M, g.N, R, &pl, true), DK_ERR_SHAPE);
     DK_REQUIRE(g.conv || pl.Kp / 128 <= 65535, DK_ERR_SHAPE);   // grid.y of the transposing digit kernel
     DK_REQUIRE(dk_aligned(delta, 4) && dk_aligned(B, 4) && dk_aligned(gamma, 4) && dk_aligned(xbar, 4) &&
                    dk_aligned(dW, 4) && (!dwq || dk_aligned(dwq, 4)), DK_ERR_ALIGN);
@@ -996,15 +1050,15 @@ dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *xscale,
     if (g.conv) {
         // the contraction index is (encoded row, output pixel)
         const fconv_geom cg = conv_geom_of(g);
-        s = run_digits_conv<1>(dtilde, Ap, cg, g.Co, pl.K, pl.I_pad, pl.Kp, flag, st);
+        s = run_digits_conv<1>(dtilde, Ap, cg, g.Co, pl.K, pl.I_pad, pl.Kp, pl.sums, flag, st);
         if (s != DK_OK) return s;
-        s = run_digits_conv<2>(xbar, Bp, cg, (int)g.Kg, pl.K, pl.J_pad, pl.Kp, flag + 1, st);
+        s = run_digits_conv<2>(xbar, Bp, cg, (int)g.Kg, pl.K, pl.J_pad, pl.Kp, pl.sums, flag + 1, st);
         if (s != DK_OK) return s;
     } else {
         // the contraction index is the encoded row: both operands are transposed
-        s = run_digits_t(dtilde, Ap, (int)R, g.M, pl.I_pad, pl.Kp, flag, st);
+        s = run_digits_t(dtilde, Ap, (int)R, g.M, pl.I_pad, pl.Kp, pl.sums, flag, st);
         if (s != DK_OK) return s;
-        s = run_digits_t(xbar, Bp, (int)R, g.N, pl.J_pad, pl.Kp, flag + 1, st);
+        s = run_digits_t(xbar, Bp, (int)R, g.N, pl.J_pad, pl.Kp, pl.sums, flag + 1, st);
         if (s != DK_OK) return s;
     }
     return run_fgemm(pl, Ap, Bp, part, flag, dwq, dW, l, scale, accumulate, 0, "f_gemm_wgrad", st);

@@ -167,6 +167,26 @@ def test_masked_dense_layer(dk, K, G, M, N):
     assert np.array_equal(lift, Xi @ Wi.T)
 
 
+@pytest.mark.parametrize("va,vb", [(-15736896, -15736896), (-15736896, 15720383), (15720383, 15720383)])
+def test_wgrad_extreme_digit_sums(dk, va, vb):
+    """Operands whose base-128 digits are all at one end (-64, -64, -64, -7 or
+    63, 63, 63, 7), on every row: the digit sums of the halves reach -128 and
+    126, the largest accumulator growth per term of the weight gradient."""
+    G, K, M, N = 700, 1, 70, 130
+    S = K + 2
+    L = dk_inputs.linear(M, N)
+    B = np.full((G, S, K), va % P, dtype=np.uint32)        # dtilde = gamma * B * Dq with Dq = 1
+    gamma = np.ones((G, S), dtype=np.uint32)
+    delta = np.full((G * K, M), 1.0 / 256, dtype=np.float32)
+    xbar = np.full((G * S, N), vb % P, dtype=np.uint32)
+    rng = np.random.default_rng(3)
+    xbar[rng.integers(0, G * S, 50), rng.integers(0, N, 50)] = rng.integers(0, P, 50, dtype=np.uint32)
+    dt = F.delta_mix(F.quantize(delta), B, gamma)
+    assert (dt == va % P).all()
+    _, dwq = dk.dkf_wgrad(L, dev(delta), dev(B), dev(gamma), dev(xbar), K, want_dwq=True)
+    assert np.array_equal(host(dwq), F.dense_wgrad(dt, xbar))
+
+
 def test_config1_field(dk):
     d = dk_inputs.config1_field()
     L, K = d["layer"], d["K"]
