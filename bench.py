@@ -282,9 +282,12 @@ def field_main(args):
     # planes of the encodings with the 2 non-zero planes of ordinary weights
     # (8 int8 products per field product), the weight gradient 4 x 4 planes (16),
     # or three products of half against half (12) where the operands come with
-    # digit-sum planes: dense layers and 1x1 convolutions.  Executed products
+    # digit-sum planes: dense layers, 1x1 and most stride-1 convolutions.  Executed products
     # are counted.  The roofline record is the longer of the two launches.
-    three_part = L.kind == "linear" or L.kh * L.kw == 1
+    # (the library's own choice, restated: the three-part form also serves
+    # stride-1 filters whose output width grows by at most 1/7 when rounded up to 16)
+    three_part = (L.kind == "linear" or L.kh * L.kw == 1 or
+                  (L.stride == 1 and (L.Wo + 15) // 16 * 16 * 7 <= L.Wo * 8))
     gemm = {"f_gemm_fwd": 8, "f_gemm_wgrad": 12 if three_part else 16}
     dom = max(gemm, key=lambda k: kernels[k][0])
     gemm_ms = kernels[dom][0]

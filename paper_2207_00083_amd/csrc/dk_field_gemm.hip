@@ -58,6 +58,12 @@ struct fgemm_params {
     int tiles_i, tiles_j, splits, ktiles_per_split, ktiles;
     // implicit convolution operand (B read from channels-last digit planes [R][H][W][cp])
     int cp, cH, cW, ckh, ckw, cstride, cpad, cWo, cHoWo;
+    // shifted-rows operand (B of a stride-1 convolution's weight gradient, see f_digits_rows_kernel):
+    // with it cp = Ci, ckh, ckw = filter size, cWo = row pitch Wp of the contraction index
+    int sRow;              // bytes per (shift, channel) row of a plane: R * Hp * Wp
+    int sImgK;             // contraction indices per image: Ho * Wp
+    int sSkip;             // (Hp - Ho) * Wp: what an image adds to the offset beyond its k
+    int sK;                // contraction length R * Ho * Wp
     int out_hw;            // 0: C[i][j] at i*J + j;  hw > 0: j = (image, pixel), C at ((image*I + i)*hw + pixel
     double s_inv;          // 2^-l for out_f
     float scale;
@@ -283,6 +289,68 @@ __global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__re
     raise_flag(flag, hi != 0);
 }
 
+// Digit planes of the operands of a stride-1 convolution's weight gradient with
+// the contraction index k = (image r, row h, column wq), wq < Wp = Wo rounded up
+// to 16 (so a 16-byte piece of k never leaves its row).  A workgroup converts
+// 1024 consecutive k of one plane row, a thread four (all in one image row).
+//   SHIFTED false (A): plane row = co, h < Ho: dtilde[r][co][h][wq], zero for
+//       wq >= Wo; rows beyond `rows` and k beyond R*Ho*Wp are zeros.
+//   SHIFTED true (B):  plane row = (b, ci), h < Hp = Ho + kh - 1:
+//       xbar[r][ci][h - pad][wq + b - pad], zero outside the image and for
+//       wq >= Wo.  Filter tap (a, b) of channel ci is this row read from h = oh + a:
+//       three (kw) shifted copies serve all kh * kw taps.
+template <bool SHIFTED>
+__global__ __launch_bounds__(256) void f_digits_rows_kernel(const uint32_t *__restrict__ src,
+                                                            int8_t *__restrict__ planes, fconv_geom g,
+                                                            int rows, int rows_pad, int Hk, int Wp,
+                                                            int len, int pitch, int chunks, int sums,
+                                                            int *flag)
+{
+    const int row = blockIdx.x / chunks;                       // workgroup-uniform
+    const int k0 = ((blockIdx.x - row * chunks) * 256 + threadIdx.x) * 4;
+    if (k0 >= pitch) return;
+    uint32_t d[4] = {0, 0, 0, 0};
+    if (row < rows && k0 < len) {
+        const int img = k0 / (Hk * Wp);
+        const int rem = k0 - img * (Hk * Wp);
+        const int h = rem / Wp, wq = rem - h * Wp;
+        if (!SHIFTED) {
+            const uint32_t *s = src + (((long long)img * g.Co + row) * g.Ho + h) * g.Wo;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (wq + c < g.Wo) d[c] = digits_of(s[wq + c]);
+        } else {
+            const int b = row / g.Ci, ci = row - b * g.Ci;
+            const int ih = h - g.pad;
+            if (ih >= 0 && ih < g.H) {
+                const uint32_t *s = src + (((long long)img * g.Ci + ci) * g.H + ih) * g.W;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int iw = wq + c + b - g.pad;
+                    if (wq + c < g.Wo && iw >= 0 && iw < g.W) d[c] = digits_of(s[iw]);
+                }
+            }
+        }
+    }
+    const long long plane = (long long)rows_pad * pitch;
+    uint32_t hi = 0;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const uint32_t w = gather_byte(d, a);
+        if (a >= 2) hi |= w;
+        *reinterpret_cast<uint32_t *>(planes + a * plane + (long long)row * pitch + k0) = w;
+    }
+    if (sums) {
+        uint32_t ds[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) ds[c] = half_sums(d[c]);
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+            *reinterpret_cast<uint32_t *>(planes + (4 + a) * plane + (long long)row * pitch + k0) = gather_byte(ds, a);
+    }
+    raise_flag(flag, hi != 0);
+}
+
 // Encodings xbar[R][Ci][H*W] -> channels-last digit planes [4][R][H*W][cp]
 // (cp = Ci, a multiple of 16): per image a tile of 128 channels x 64 pixels goes
 // through LDS as packed digits; a thread then writes 16 consecutive channels of
@@ -376,11 +444,16 @@ __device__ __forceinline__ uint32_t reduce_signed(long long v)
 // j = (image, oh, ow) and k = (a, b, ci) address the channels-last digit planes
 // of the encodings directly (16 consecutive channels per piece, zeros outside
 // the image), so no patch matrix exists in memory.
+// BMODE 2: the B operand of a stride-1 convolution's weight gradient: row
+// j = (ci, a, b) is row (b, ci) of the shifted-rows planes read a * Wp bytes
+// further on; the contraction index k = (image, oh, wq) skips the kh - 1 extra
+// rows each image has there.  BMODE 1 is IMPL, 0 a stored matrix.
 // NBI: 32-row blocks of A per wave; the workgroup tile is (64 NBI) x 128 (a
 // 64-row tile keeps operands with at most 64 rows from wasting half the MFMAs).
-template <bool IMPL, int NBI>
+template <int BMODE, int NBI>
 __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 {
+    constexpr bool IMPL = BMODE == 1;
     constexpr int BI = 64 * NBI, A_PLANE = BI * PITCH, BUF_BYTES = 2 * A_PLANE + 2 * B_PLANE;
     constexpr int NA = 4 * NBI;          // 16-byte pieces of A per thread and tile
     extern __shared__ __attribute__((aligned(16))) int8_t flds[];
@@ -393,7 +466,16 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     const int bid = dk_xcd_block();
     const int split = bid / tiles;
     const int t = bid - split * tiles;
-    const int tj = t / p.tiles_i, ti = t - tj * p.tiles_i;
+    // Tiles are walked in bands of GI tile rows, down the band's columns: the
+    // 32 workgroups an XCD runs side by side then share 8 row tiles and 4 column
+    // tiles (12 operand tiles through its L2 instead of 33 for a whole column of
+    // a tall output).
+    constexpr int GI = 8;
+    const int band = t / (GI * p.tiles_j);
+    const int in_band = t - band * (GI * p.tiles_j);
+    const int rows_here = p.tiles_i - band * GI < GI ? p.tiles_i - band * GI : GI;
+    const int tj = in_band / rows_here;
+    const int ti = band * GI + (in_band - tj * rows_here);
     const bool fa = p.flags[0] != 0, fb = p.flags[1] != 0;     // workgroup-uniform
 
     const int kt0 = split * p.ktiles_per_split;
@@ -424,6 +506,19 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
             r_ih[q] = oh * p.cstride - p.cpad;
             r_iw[q] = ow * p.cstride - p.cpad;
             r_base[q] = (unsigned)img * (unsigned)(p.cH * p.cW) * (unsigned)p.cp;
+        }
+    }
+    if (BMODE == 2) {
+        const int taps = p.ckh * p.ckw;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int j = tj * BJ + srow + 32 * q;
+            r_ok[q] = j < p.J;
+            const int ci = r_ok[q] ? j / taps : 0;
+            const int ab = r_ok[q] ? j - ci * taps : 0;
+            const int fa_ = ab / p.ckw, fb_ = ab - fa_ * p.ckw;
+            r_base[q] = (unsigned)(fb_ * p.cp + ci) * (unsigned)p.sRow + (unsigned)(fa_ * p.cWo);
+            r_ih[q] = r_iw[q] = 0;
         }
     }
 
@@ -477,9 +572,22 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         const int8_t *bs_ = p.Bp + 2 * (q_ >> 2) * p.b_plane + ((long long)tj * BJ * p.Kp + (long long)(KTILE) * KT); \
         _Pragma("unroll") for (int e = 0; e < NA; ++e)                                            \
             sa[e] = *reinterpret_cast<const i32x4 *>((as_ + ((e / (2 * NBI)) * p.a_plane + (e % (2 * NBI)) * q_rows)) + s_off); \
-        if (!IMPL) {                                                                              \
+        if (BMODE == 0) {                                                                         \
             _Pragma("unroll") for (int e = 0; e < 8; ++e)                                         \
                 sb[e] = *reinterpret_cast<const i32x4 *>((bs_ + ((e >> 2) * p.b_plane + (e & 3) * q_rows)) + s_off); \
+        } else if (BMODE == 2) {                                                                  \
+            const int k0_ = (KTILE) * KT + 16 * spiece;                                           \
+            const int img_ = k0_ / p.sImgK;                                                       \
+            const unsigned koff_ = (unsigned)k0_ + (unsigned)img_ * (unsigned)p.sSkip;            \
+            const bool kok_ = k0_ < p.sK;                                                         \
+            const int8_t *bp_ = p.Bp + 2 * (q_ >> 2) * p.b_plane;                                 \
+            _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                       \
+                _Pragma("unroll") for (int pl = 0; pl < 2; ++pl) {                                \
+                    i32x4 v_ = {0, 0, 0, 0};                                                      \
+                    if (kok_ && r_ok[q]) v_ = *reinterpret_cast<const i32x4 *>(bp_ + pl * p.b_plane + (r_base[q] + koff_)); \
+                    sb[pl * 4 + q] = v_;                                                          \
+                }                                                                                 \
+            }                                                                                     \
         } else {                                                                                  \
             const int k0_ = (KTILE) * KT + 16 * spiece;                                           \
             const int tap_ = k0_ / p.cp, ci0_ = k0_ - tap_ * p.cp;                                \
@@ -615,7 +723,9 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         // End of a weight group: recombine the three accumulators with the
         // constants gw 128^s mod p in 64 bits (gw = 128^(2w), or the weight of
         // the group in the three-part form), reduce, add to the running
-        // residues and clear the accumulators.
+        // residues and clear the accumulators.  (Measured alternatives: the same
+        // in fp64, and one 64-bit product with the sum a0 + 128 a1 + 128^2 a2,
+        // take as long and three times as long.)
         uint64_t gw = 1ull << (14 * w);
         if (three) gw = w == 0 ? (uint64_t)DKF_P + 1 - (1u << 14) : w == 1 ? 1ull << 14 : (1ull << 28) - (1u << 14);
         gw = dkf_reduce(gw);
@@ -761,20 +871,32 @@ bool plan_fgemm(long long I, long long J, long long K, fgemm_plan *pl, bool sums
 
 constexpr size_t FLAG_BYTES = 256;
 
+// Shifted-rows form of the B operand of a stride-1 convolution's weight
+// gradient (f_digits_rows_kernel): sizes the GEMM needs to address it.
+struct fshift {
+    int Ci, kh, kw, Ho, Hp, Wp;
+    int row_bytes;          // R * Hp * Wp
+    int img_k, skip, K;     // Ho * Wp, (Hp - Ho) * Wp, R * Ho * Wp
+    long long plane;        // bytes per digit plane: kw * Ci * row_bytes
+};
+
 // C = A B^T over the field from digit planes.  out_q / out_f as in the kernel
 // parameters; with more than one k slice the slices go to `part` and a fold
 // kernel finishes.
 dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, uint32_t *part,
                     const int *flags, uint32_t *out_q, float *out_f, int l, float scale,
                     int accumulate, int out_hw, const char *label, hipStream_t st,
-                    const fconv_geom *impl = nullptr, long long impl_plane = 0)
+                    const fconv_geom *impl = nullptr, long long impl_plane = 0,
+                    const fshift *shift = nullptr)
 {
     static bool allowed = false;
     if (!allowed) {
-        const void *kernels[4] = {reinterpret_cast<const void *>(f_gemm_kernel<false, 1>),
-                                  reinterpret_cast<const void *>(f_gemm_kernel<false, 2>),
-                                  reinterpret_cast<const void *>(f_gemm_kernel<true, 1>),
-                                  reinterpret_cast<const void *>(f_gemm_kernel<true, 2>)};
+        const void *kernels[6] = {reinterpret_cast<const void *>(f_gemm_kernel<0, 1>),
+                                  reinterpret_cast<const void *>(f_gemm_kernel<0, 2>),
+                                  reinterpret_cast<const void *>(f_gemm_kernel<1, 1>),
+                                  reinterpret_cast<const void *>(f_gemm_kernel<1, 2>),
+                                  reinterpret_cast<const void *>(f_gemm_kernel<2, 1>),
+                                  reinterpret_cast<const void *>(f_gemm_kernel<2, 2>)};
         for (const void *kf : kernels)
             DK_REQUIRE(hipFuncSetAttribute(kf, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) == hipSuccess,
                        DK_ERR_HIP);
@@ -799,15 +921,23 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
         p.cstride = impl->stride; p.cpad = impl->pad; p.cWo = impl->Wo; p.cHoWo = impl->HoWo;
         p.b_plane = impl_plane;
     }
+    p.sRow = p.sImgK = p.sSkip = p.sK = 0;
+    if (shift) {
+        p.cp = shift->Ci; p.ckh = shift->kh; p.ckw = shift->kw; p.cWo = shift->Wp;
+        p.sRow = shift->row_bytes; p.sImgK = shift->img_k; p.sSkip = shift->skip; p.sK = shift->K;
+        p.b_plane = shift->plane;
+    }
     const long long blocks = (long long)pl.splits * pl.tiles_i * pl.tiles_j;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     {
         dk_prof_scope ps(label, st);
         const dim3 grid((unsigned)blocks), block(256);
-        if (impl && pl.nbi == 1) f_gemm_kernel<true, 1><<<grid, block, LDS_BYTES, st>>>(p);
-        else if (impl)           f_gemm_kernel<true, 2><<<grid, block, LDS_BYTES, st>>>(p);
-        else if (pl.nbi == 1)    f_gemm_kernel<false, 1><<<grid, block, LDS_BYTES, st>>>(p);
-        else                     f_gemm_kernel<false, 2><<<grid, block, LDS_BYTES, st>>>(p);
+        if (shift && pl.nbi == 1) f_gemm_kernel<2, 1><<<grid, block, LDS_BYTES, st>>>(p);
+        else if (shift)          f_gemm_kernel<2, 2><<<grid, block, LDS_BYTES, st>>>(p);
+        else if (impl && pl.nbi == 1) f_gemm_kernel<1, 1><<<grid, block, LDS_BYTES, st>>>(p);
+        else if (impl)           f_gemm_kernel<1, 2><<<grid, block, LDS_BYTES, st>>>(p);
+        else if (pl.nbi == 1)    f_gemm_kernel<0, 1><<<grid, block, LDS_BYTES, st>>>(p);
+        else                     f_gemm_kernel<0, 2><<<grid, block, LDS_BYTES, st>>>(p);
     }
     if (direct) return dk_launch_status();
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
@@ -854,6 +984,19 @@ dk_status run_digits_conv(const uint32_t *src, int8_t *planes, const fconv_geom 
     return dk_launch_status();
 }
 
+template <bool SHIFTED>
+dk_status run_digits_rows(const uint32_t *src, int8_t *planes, const fconv_geom &cg, int rows, int rows_pad,
+                          int Hk, int Wp, int len, int pitch, int sums, int *flag, hipStream_t st)
+{
+    const int chunks = (pitch / 4 + 255) / 256;
+    const long long blocks = (long long)rows_pad * chunks;
+    DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
+    dk_prof_scope ps(SHIFTED ? "f_digits_shifted" : "f_digits_dt", st);
+    f_digits_rows_kernel<SHIFTED><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(
+        src, planes, cg, rows, rows_pad, Hk, Wp, len, pitch, chunks, sums, flag);
+    return dk_launch_status();
+}
+
 fconv_geom conv_geom_of(const dk_geom &g)
 {
     fconv_geom c;
@@ -879,8 +1022,34 @@ bool plan_conv_fwd(const dk_geom &g, long long R, fgemm_plan *pl)
         pl->b_bytes = align256((size_t)4 * R * g.H * g.W * g.Ci);
     return true;
 }
+// The shifted-rows form: stride 1, more than one tap, and an output width
+// that rounding up to 16 lengthens by at most a seventh (56 -> 64).
+bool conv_wgrad_shifted(const dk_geom &g, long long R, fshift *sh)
+{
+    if (g.stride != 1 || g.kh * g.kw == 1) return false;
+    const int Wp = round_up(g.Wo, 16);
+    if (Wp * 7 > g.Wo * 8) return false;
+    const int Hp = g.Ho + g.kh - 1;
+    const long long row = R * Hp * Wp, plane = (long long)g.kw * g.Ci * row;
+    if (plane * 6 >= (1ll << 31) || R * g.Ho * Wp > (1 << 26)) return false;
+    if (sh) {
+        sh->Ci = g.Ci; sh->kh = g.kh; sh->kw = g.kw; sh->Ho = g.Ho; sh->Hp = Hp; sh->Wp = Wp;
+        sh->row_bytes = (int)row; sh->img_k = g.Ho * Wp; sh->skip = (Hp - g.Ho) * Wp;
+        sh->K = (int)(R * g.Ho * Wp);
+        sh->plane = plane;
+    }
+    return true;
+}
+
 bool plan_conv_wgrad(const dk_geom &g, long long R, fgemm_plan *pl)
 {
+    fshift sh;
+    if (conv_wgrad_shifted(g, R, &sh)) {
+        // three shifted copies instead of kh * kw: the digit-sum planes pay here too
+        if (!plan_fgemm(g.Co, g.Kg, sh.K, pl, true)) return false;
+        pl->b_bytes = align256((size_t)6 * sh.plane);
+        return true;
+    }
     // digit-sum planes only for 1x1 filters: otherwise every shifted copy of the
     // encodings would grow by half, which costs more than the shorter product saves
     return plan_fgemm(g.Co, g.Kg, R * g.Ho * g.Wo, pl, g.kh * g.kw == 1);
@@ -1047,6 +1216,19 @@ dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *xscale,
         f_flag_clear_kernel<<<dim3(1), dim3(64), 0, st>>>(flag);
     }
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+    fshift sh;
+    if (g.conv && conv_wgrad_shifted(g, R, &sh)) {
+        // the contraction index is (encoded row, output row, column of pitch Wp)
+        const fconv_geom cg = conv_geom_of(g);
+        s = run_digits_rows<false>(dtilde, Ap, cg, g.Co, pl.I_pad, sh.Ho, sh.Wp, sh.K, pl.Kp, pl.sums, flag, st);
+        if (s != DK_OK) return s;
+        const int brows = g.kw * g.Ci;
+        s = run_digits_rows<true>(xbar, Bp, cg, brows, brows, sh.Hp, sh.Wp, sh.row_bytes, sh.row_bytes, pl.sums,
+                                  flag + 1, st);
+        if (s != DK_OK) return s;
+        return run_fgemm(pl, Ap, Bp, part, flag, dwq, dW, l, scale, accumulate, 0, "f_gemm_wgrad", st,
+                         nullptr, 0, &sh);
+    }
     if (g.conv) {
         // the contraction index is (encoded row, output pixel)
         const fconv_geom cg = conv_geom_of(g);
