@@ -568,6 +568,37 @@ def test_verify_flags_tampered_stored_encodings(dk):
     assert host(v).tolist() == vref.tolist()
 
 
+def test_bias_rides_along_as_an_input_feature(dk):
+    """The layer's bias needs no entry point of its own: encoding and decoding
+    are linear, so a constant-one input feature (dense) or a constant-one
+    channel whose filter has the bias on its centre tap (convolution) decodes
+    to W x + b, and its weight gradient is the bias gradient sum_i delta_i."""
+    say("bias as an input feature")
+    K, G, M, N = 4, 3, 37, 50
+    rng = np.random.default_rng(77)
+    d = _masked_case(dk_inputs.linear(M, N + 1), K, G, seed=78)
+    b = rng.standard_normal(M).astype(np.float32)
+    d["X"][:, N] = 1.0
+    d["W"][:, N] = b
+    out = _run_masked(dk, d)
+    Y = d["X"][:, :N].astype(np.float64) @ d["W"][:, :N].astype(np.float64).T + b.astype(np.float64)
+    assert nerr(out["y"], Y) < TOL_CONTRACT
+    assert nerr(out["dW"][:, N], d["delta"].astype(np.float64).sum(0)) < TOL_CONTRACT
+    assert out["verdict"].tolist() == [0] * G
+    # convolution: 3x3, pad 1; the ones channel sees zero padding, the centre tap never does
+    Ci, Co, H, W = 5, 6, 9, 8
+    L = dk_inputs.conv(Ci + 1, Co, H, W, 3, 1, 1)
+    d = _masked_case(L, 2, 2, seed=79)
+    b = rng.standard_normal(Co).astype(np.float32)
+    d["X"][:, Ci] = 1.0
+    d["W"][:, Ci] = 0.0
+    d["W"][:, Ci, 1, 1] = b
+    out = _run_masked(dk, d)
+    Y = oracle.conv_fwd(d["W"][:, :Ci], d["X"][:, :Ci], 1, 1) + b.astype(np.float64)[None, :, None, None]
+    assert nerr(out["y"], Y) < TOL_CONTRACT
+    assert nerr(out["dW"][:, Ci, 1, 1], d["delta"].astype(np.float64).sum((0, 2, 3))) < TOL_CONTRACT
+
+
 # ----------------------------------------------------------------------
 # error behaviour through the C ABI
 # ----------------------------------------------------------------------
