@@ -889,19 +889,16 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
                     const fconv_geom *impl = nullptr, long long impl_plane = 0,
                     const fshift *shift = nullptr)
 {
-    static bool allowed = false;
-    if (!allowed) {
-        const void *kernels[6] = {reinterpret_cast<const void *>(f_gemm_kernel<0, 1>),
-                                  reinterpret_cast<const void *>(f_gemm_kernel<0, 2>),
-                                  reinterpret_cast<const void *>(f_gemm_kernel<1, 1>),
-                                  reinterpret_cast<const void *>(f_gemm_kernel<1, 2>),
-                                  reinterpret_cast<const void *>(f_gemm_kernel<2, 1>),
-                                  reinterpret_cast<const void *>(f_gemm_kernel<2, 2>)};
-        for (const void *kf : kernels)
-            DK_REQUIRE(hipFuncSetAttribute(kf, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) == hipSuccess,
-                       DK_ERR_HIP);
-        allowed = true;
-    }
+    static std::atomic<unsigned long long> allowed[6];
+    const void *kernels[6] = {reinterpret_cast<const void *>(f_gemm_kernel<0, 1>),
+                              reinterpret_cast<const void *>(f_gemm_kernel<0, 2>),
+                              reinterpret_cast<const void *>(f_gemm_kernel<1, 1>),
+                              reinterpret_cast<const void *>(f_gemm_kernel<1, 2>),
+                              reinterpret_cast<const void *>(f_gemm_kernel<2, 1>),
+                              reinterpret_cast<const void *>(f_gemm_kernel<2, 2>)};
+    const int which = (shift ? 4 : impl ? 2 : 0) + (pl.nbi == 1 ? 0 : 1);
+    const dk_status as = dk_allow_dynamic_lds(kernels[which], LDS_BYTES, allowed[which]);
+    if (as != DK_OK) return as;
     const bool direct = pl.splits == 1;
     fgemm_params p;
     p.Ap = Ap; p.Bp = Bp; p.flags = flags;

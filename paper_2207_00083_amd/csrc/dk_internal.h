@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include "darknight.h"
 
 #define DK_EXPORT extern "C" __attribute__((visibility("default")))
@@ -12,6 +13,22 @@
     } while (0)
 
 static inline bool dk_aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+// Kernels that use more than 64 KB of dynamic LDS have to be allowed to, once
+// per kernel and device (HIP keeps the attribute per device).  `done` is the
+// call site's own record, one bit per device ordinal; a race between two first
+// calls sets the attribute twice, which is harmless.
+static inline dk_status dk_allow_dynamic_lds(const void *kernel, int bytes, std::atomic<unsigned long long> &done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return DK_ERR_HIP;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return DK_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+        return DK_ERR_HIP;
+    done.fetch_or(bit, std::memory_order_release);
+    return DK_OK;
+}
 
 static inline dk_status dk_launch_status()
 {

@@ -472,14 +472,10 @@ template <class KernelT>
 dk_status launch_one(KernelT kernel, const dk_wgpatch_params &p, size_t lds_bytes, hipStream_t st,
                      const char *label)
 {
-    // more than 64 KB of dynamic LDS has to be allowed per kernel, once per process
-    static bool allowed = false;
-    if (!allowed) {
-        DK_REQUIRE(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)(LDS_LIMIT + DUMP_BYTES)) == hipSuccess, DK_ERR_HIP);
-        allowed = true;
-    }
+    static std::atomic<unsigned long long> allowed{0};       // one per kernel instantiation
+    const dk_status as = dk_allow_dynamic_lds(reinterpret_cast<const void *>(kernel), (int)(LDS_LIMIT + DUMP_BYTES),
+                                              allowed);
+    if (as != DK_OK) return as;
     const long long blocks = (long long)p.tiles_co * p.tiles_ci * p.splits;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     dk_prof_scope ps(label, st);
