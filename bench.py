@@ -7,7 +7,7 @@ is already resident in HBM:
 (dk_decode_verify = dk_verify + dk_decode in one sweep over the encoded results).
 The step is captured once into a HIP graph and replayed (--no-graph: eager).
 --noise-vectors M uses the *_m entry points (M noise vectors per group);
---workload field1 | field2 | field3.i | field4.i | field5.i runs the finite-field
+--workload field1 | field2 | field3[.i] | field4[.i] | field5[.i] runs the finite-field
 variant instead (dkf_quantize -> dkf_encode -> dkf_linear_fwd | dkf_conv_fwd ->
 dkf_decode_verify -> dkf_wgrad).
 Prints ONE JSON line: whole-path executed TFLOP/s (forward + weight gradient
@@ -380,6 +380,10 @@ def sub_workloads(name):
         return [("mbv2dw.%d" % i, c[3]) for i, c in enumerate(dk_inputs.MOBILENETV2_DW)]
     if name == "field5":
         return [("field5.%d" % i, 1) for i in range(len(dk_inputs.config5_layers()))]
+    if name == "field3":
+        return [("field3.%d" % i, 1) for i in range(len(dk_inputs.config3_layers()))]
+    if name == "field4":
+        return [("field4.%d" % i, c) for i, (_, c) in enumerate(dk_inputs.resnet50_convs())]
     return None
 
 
