@@ -267,6 +267,45 @@ def test_masked_conv_layer(dk, K, G, Ci, Co, H, W, k, stride, pad):
     assert host(verdict).tolist() == [0] * (G - 1) + [1]
 
 
+def _random_field_conv_shapes(seed, count):
+    """Seeded draw of small convolution shapes across the operand forms of the
+    field contraction: channel counts that are and are not multiples of 16
+    (implicit or materialised forward operand), output widths that do and do
+    not take the shifted-rows weight gradient, 1x1 filters, stride 2."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        k = int(rng.choice([1, 3, 3, 5]))
+        stride = int(rng.choice([1, 1, 1, 2]))
+        pad = int(rng.choice([0, k // 2]))
+        H = int(rng.choice([3, 5, 8, 9, 14]))
+        W = int(rng.choice([4, 7, 14, 16, 18, 30, 32]))
+        if H + 2 * pad < k or W + 2 * pad < k:
+            continue
+        Ci = int(rng.choice([1, 5, 16, 32, 40]))
+        Co = int(rng.choice([1, 7, 64, 70, 130]))
+        K = int(rng.choice([1, 2, 4]))
+        G = int(rng.choice([1, 2]))
+        out.append((K, G, Ci, Co, H, W, k, stride, pad))
+    return out
+
+
+@pytest.mark.parametrize("K,G,Ci,Co,H,W,k,stride,pad", _random_field_conv_shapes(20261, 24))
+def test_masked_conv_layer_random_shapes(dk, K, G, Ci, Co, H, W, k, stride, pad):
+    rng = np.random.default_rng([K, G, Ci, Co, H, W, k, stride, pad])
+    L = dk_inputs.conv(Ci, Co, H, W, k, stride, pad)
+    d = dk_inputs.field_layer_inputs(rng, L, K=K, batch=G * K, delta_std=1.0)
+    o = F.masked_layer(d["W"], d["X"], d["r"], d["delta"], d["A"], d["gamma"], stride=stride, pad=pad)
+    Ainv, nvec, B = dk.dkf_coeffs(d["A"], d["gamma"])
+    xbar = dk.dkf_encode(dev(d["X"]), dev(d["r"]), dev(d["A"]), K)
+    ybar = dk.dkf_conv_fwd(L, dk.dkf_quantize(dev(d["W"])), xbar)
+    assert np.array_equal(host(ybar), o["Ybar"])
+    y, yq, verdict = dk.dkf_decode_verify(ybar, dev(Ainv), dev(nvec), K, want_yq=True)
+    assert np.array_equal(host(yq), o["Yq"]) and not host(verdict).any()
+    dW, dwq = dk.dkf_wgrad(L, dev(d["delta"]), dev(B), dev(d["gamma"]), xbar, K, want_dwq=True)
+    assert np.array_equal(host(dwq), o["dWq"]) and np.array_equal(host(dW), o["dW"])
+
+
 def test_config2_field_sampled(dk):
     """Config 2 (conv 3x3 64->64 @32x32, batch 256, K=4) over the field at full
     size; the oracle evaluates sampled outputs of the two contractions."""

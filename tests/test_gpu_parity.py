@@ -269,6 +269,42 @@ def test_conv_masked_layer(dk, K, G, Ci, Co, H, W, k, stride, pad):
     assert out["verdict"].tolist() == [0] * G
 
 
+def _random_conv_shapes(seed, count):
+    """Seeded draw of small convolution shapes that between them reach every
+    kernel family the planner can pick: widths that are and are not multiples
+    of 4 and 8, odd and even heights, 1x1 to 5x5 filters, strides 1 and 2,
+    channel counts on both sides of the tile sizes."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        k = int(rng.choice([1, 1, 3, 3, 3, 5]))
+        stride = int(rng.choice([1, 1, 1, 2]))
+        pad = int(rng.choice([0, k // 2]))
+        H = int(rng.choice([1, 2, 4, 6, 7, 8, 12, 14, 16, 20]))
+        W = int(rng.choice([1, 2, 4, 7, 8, 12, 14, 16, 24, 32]))
+        if H + 2 * pad < k or W + 2 * pad < k:
+            continue
+        Ci = int(rng.choice([1, 3, 8, 17, 20, 32, 48, 70]))
+        Co = int(rng.choice([1, 5, 16, 33, 64, 72, 130]))
+        K = int(rng.choice([1, 2, 4]))
+        G = int(rng.choice([1, 2, 3]))
+        out.append((K, G, Ci, Co, H, W, k, stride, pad))
+    return out
+
+
+@pytest.mark.parametrize("K,G,Ci,Co,H,W,k,stride,pad", _random_conv_shapes(20260, 40))
+def test_conv_masked_layer_random_shapes(dk, K, G, Ci, Co, H, W, k, stride, pad):
+    L = dk_inputs.conv(Ci, Co, H, W, k, stride, pad)
+    say("conv masked layer, drawn shape", dict(K=K, G=G), L)
+    d = _masked_case(L, K, G, seed=[K, G, Ci, Co, H, W, k, stride, pad])
+    out = _run_masked(dk, d)
+    Y = oracle.conv_fwd(d["W"], d["X"], stride, pad)
+    dW = oracle.conv_wgrad(d["delta"], d["X"], k, k, stride, pad)
+    assert nerr(out["y"], Y) < TOL_CONTRACT
+    assert nerr(out["dW"], dW) < TOL_CONTRACT
+    assert out["verdict"].tolist() == [0] * G
+
+
 def test_wgrad_accumulate_and_scale(dk):
     say("wgrad accumulate")
     L = dk_inputs.linear(96, 200)
