@@ -61,6 +61,41 @@ def test_masked_depthwise_layer(dk, K, G, L):
     assert verdict.cpu().tolist() == [1] + [0] * (G - 1)
 
 
+def _random_dw_shapes(seed, count):
+    """Seeded draw of depthwise shapes: 3x3 filters with padding 1 and widths
+    that are multiples of 4 take the tiled kernels (strides 1 and 2, planes of
+    a few tiles up to several chunks); everything else the general ones."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        k = int(rng.choice([3, 3, 3, 5]))
+        stride = int(rng.choice([1, 2]))
+        pad = int(rng.choice([k // 2, k // 2, 0]))
+        H = int(rng.choice([4, 7, 8, 16, 30, 40, 72]))
+        W = int(rng.choice([4, 8, 12, 16, 32, 36, 72]))
+        if H + 2 * pad < k or W + 2 * pad < k:
+            continue
+        C = int(rng.choice([1, 3, 16, 24, 40]))
+        out.append((int(rng.choice([1, 2, 4])), int(rng.choice([1, 2])), C, H, W, k, stride, pad))
+    return out
+
+
+@pytest.mark.parametrize("K,G,C,H,W,k,stride,pad", _random_dw_shapes(20262, 24))
+def test_masked_depthwise_layer_random_shapes(dk, K, G, C, H, W, k, stride, pad):
+    L = dk_inputs.dwconv(C, H, W, k, stride, pad)
+    rng = np.random.default_rng([K, G, C, H, W, k, stride, pad])
+    d = dk_inputs.masked_layer_inputs(rng, L, K=K, batch=G * K, delta_std=1.0)
+    Ainv, nvec, B = dk.dk_coeffs(d["A"], d["gamma"])
+    xbar = dk.dk_encode(dev(d["X"]), dev(d["r"]), dev(d["A"]), K)
+    ybar = dk.dk_conv_fwd(L, dev(d["W"]), xbar)
+    y, verdict, _ = dk.dk_decode_verify(ybar, dev(Ainv), dev(nvec), K)
+    dW = dk.dk_wgrad(L, dev(d["delta"]), dev(B), dev(d["gamma"]), xbar, K)
+    Y = oracle.dwconv_fwd(d["W"], d["X"], stride, pad)
+    dWp = oracle.dwconv_wgrad(d["delta"], d["X"], k, k, stride, pad)
+    assert normwise_err(y.cpu().numpy(), Y) < 1e-3 and normwise_err(dW.cpu().numpy(), dWp) < 1e-3
+    assert verdict.cpu().tolist() == [0] * G
+
+
 def test_depthwise_with_two_noise_vectors_and_bad_arguments(dk):
     import ctypes as C
     L = dk_inputs.dwconv(12, 10, 10, 3)

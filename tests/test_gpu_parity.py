@@ -305,6 +305,24 @@ def test_conv_masked_layer_random_shapes(dk, K, G, Ci, Co, H, W, k, stride, pad)
     assert out["verdict"].tolist() == [0] * G
 
 
+def _random_dense_shapes(seed, count):
+    rng = np.random.default_rng(seed)
+    sizes = [1, 3, 31, 64, 65, 127, 128, 130, 200, 257, 300, 520]
+    return [(int(rng.choice([1, 2, 4, 8])), int(rng.choice([1, 2, 5])), int(rng.choice(sizes)),
+             int(rng.choice(sizes + [1030, 2049]))) for _ in range(count)]
+
+
+@pytest.mark.parametrize("K,G,M,N", _random_dense_shapes(20263, 24))
+def test_dense_masked_layer_random_shapes(dk, K, G, M, N):
+    L = dk_inputs.linear(M, N)
+    say("dense masked layer, drawn shape", dict(K=K, G=G, M=M, N=N))
+    d = _masked_case(L, K, G, seed=[K, G, M, N, 5])
+    out = _run_masked(dk, d)
+    assert nerr(out["y"], oracle.dense_fwd(d["W"], d["X"])) < TOL_CONTRACT
+    assert nerr(out["dW"], oracle.dense_wgrad(d["delta"], d["X"])) < TOL_CONTRACT
+    assert out["verdict"].tolist() == [0] * G
+
+
 def test_wgrad_accumulate_and_scale(dk):
     say("wgrad accumulate")
     L = dk_inputs.linear(96, 200)
