@@ -102,6 +102,41 @@ __device__ __forceinline__ uint32_t gather_byte(const uint32_t (&d)[4], int a)
            ((d[3] >> sh) & 255u) << 24;
 }
 
+// Sixteen packed-digit words -> one 16-byte piece of each plane at `dst`
+// (plane a at dst + a * plane); with `sums` planes 4, 5 get the digit sums of
+// the halves.  Returns the OR of the high-half words.
+__device__ __forceinline__ uint32_t store_pieces(const uint32_t (&d)[16], int8_t *dst, long long plane, int sums)
+{
+    uint32_t hi = 0;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        u32x4 w;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t dq[4] = {d[4 * q], d[4 * q + 1], d[4 * q + 2], d[4 * q + 3]};
+            w[q] = gather_byte(dq, a);
+        }
+        if (a >= 2) hi |= w.x | w.y | w.z | w.w;
+        *reinterpret_cast<u32x4 *>(dst + a * plane) = w;
+    }
+    if (sums) {
+        uint32_t ds[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) ds[c] = half_sums(d[c]);
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            u32x4 w;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t dq[4] = {ds[4 * q], ds[4 * q + 1], ds[4 * q + 2], ds[4 * q + 3]};
+                w[q] = gather_byte(dq, a);
+            }
+            *reinterpret_cast<u32x4 *>(dst + (4 + a) * plane) = w;
+        }
+    }
+    return hi;
+}
+
 // Record "some high digit is non-zero".  One lane per wave looks at the flag
 // first, so once it is set the other waves of the launch only read it.
 __device__ __forceinline__ void raise_flag(int *flag, bool mine)
@@ -112,36 +147,40 @@ __device__ __forceinline__ void raise_flag(int *flag, bool mine)
 }
 
 // Row-major operand src[rows][K] -> planes[4][rows_pad][Kp].  A workgroup
-// converts 1024 consecutive k of one row, a thread four of them; rows and k
-// beyond the operand are written as zeros.
+// converts 4096 consecutive k of one row, a thread sixteen (four 16-byte loads
+// in flight, one 16-byte store per plane); rows and k beyond the operand are
+// written as zeros.
 __global__ __launch_bounds__(256) void f_digits_kernel(const uint32_t *__restrict__ src,
                                                        int8_t *__restrict__ planes, int rows, int K,
                                                        int rows_pad, int Kp, int chunks, int vec,
                                                        int *flag)
 {
     const int row = blockIdx.x / chunks;                       // workgroup-uniform
-    const int k0 = ((blockIdx.x - row * chunks) * 256 + threadIdx.x) * 4;
+    const int k0 = ((blockIdx.x - row * chunks) * 256 + threadIdx.x) * 16;
     if (k0 >= Kp) return;
-    uint32_t d[4] = {0, 0, 0, 0};
+    uint32_t v[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) v[c] = 0;
     if (row < rows) {
         const uint32_t *s = src + (long long)row * K + k0;
-        if (vec && k0 + 3 < K) {
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(s);
-            d[0] = digits_of(v.x); d[1] = digits_of(v.y); d[2] = digits_of(v.z); d[3] = digits_of(v.w);
-        } else {
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (k0 + c < K) d[c] = digits_of(s[c]);
+        for (int q = 0; q < 4; ++q) {
+            if (vec && k0 + 4 * q + 3 < K) {
+                const u32x4 t = *reinterpret_cast<const u32x4 *>(s + 4 * q);
+                v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
+            } else {
+#pragma unroll
+                for (int c = 4 * q; c < 4 * q + 4; ++c)
+                    if (k0 + c < K) v[c] = s[c];
+            }
         }
     }
-    const long long plane = (long long)rows_pad * Kp;
-    uint32_t hi = 0;
+    // (the digits of 0 are 0, so absent elements need no flag of their own)
+    uint32_t d[16];
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        const uint32_t w = gather_byte(d, a);
-        if (a >= 2) hi |= w;
-        *reinterpret_cast<uint32_t *>(planes + a * plane + (long long)row * Kp + k0) = w;
-    }
+    for (int c = 0; c < 16; ++c) d[c] = digits_of(v[c]);
+    const long long plane = (long long)rows_pad * Kp;
+    const uint32_t hi = store_pieces(d, planes + (long long)row * Kp + k0, plane, 0);
     raise_flag(flag, hi != 0);
 }
 
@@ -177,6 +216,26 @@ __global__ __launch_bounds__(256) void f_digits_t_kernel(const uint32_t *__restr
         base = (long long)img * g.Ci * g.H * g.W;
     }
     const int khw = g.kh * g.kw;
+    // straight source with whole 16-byte vectors per row (cols % 4 == 0 and an
+    // aligned base): eight vector loads per thread, all in flight at once
+    const bool vec = !IM2COL && (cols & 3) == 0 && (((size_t)src) & 15) == 0;
+    if (vec) {
+        u32x4 t[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int item = threadIdx.x + 256 * r;
+            const int k = k0 + (item >> 4), cc = c0 + (item & 15) * 4;
+            t[r] = u32x4{0, 0, 0, 0};
+            if (k < K && cc < cols) t[r] = *reinterpret_cast<const u32x4 *>(src + (long long)k * cols + cc);
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int item = threadIdx.x + 256 * r;
+            uint32_t *dst = &tile[item >> 4][(item & 15) * 4];
+            dst[0] = digits_of(t[r].x); dst[1] = digits_of(t[r].y);
+            dst[2] = digits_of(t[r].z); dst[3] = digits_of(t[r].w);
+        }
+    } else
 #pragma unroll 8
     for (int r = 0; r < 32; ++r) {
         const int k = k0 + ty + 4 * r;                 // wave-uniform
@@ -225,8 +284,8 @@ __global__ __launch_bounds__(256) void f_digits_t_kernel(const uint32_t *__restr
 
 // Digit planes of the operands of a convolution's weight gradient, gathered
 // from NCHW field tensors; the contraction index is k = (image r, oh, ow), which
-// is contiguous in both sources.  A workgroup converts 1024 consecutive k of
-// one row, a thread four.
+// is contiguous in both sources.  A workgroup converts 4096 consecutive k of
+// one row, a thread four runs of four.
 //   MODE 1 (A): row = co, the element is dtilde[r][co][oh][ow];
 //   MODE 2 (B): row = (ci, a, b), the element is
 //               xbar[r][ci][oh*stride + a - pad][ow*stride + b - pad] or 0 outside.
@@ -238,8 +297,9 @@ __global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__re
                                                             int chunks, int sums, int *flag)
 {
     const int row = blockIdx.x / chunks;                       // workgroup-uniform
-    const int k0 = ((blockIdx.x - row * chunks) * 256 + threadIdx.x) * 4;
-    if (k0 >= Kp) return;
+    // a thread takes four groups of four k, 1024 k apart, and issues all its
+    // loads before it uses the first (bytes in flight are what the kernel lives on)
+    const int kb = (blockIdx.x - row * chunks) * 4096 + threadIdx.x * 4;
     int r_ci = 0, r_a = 0, r_b = 0;                            // what the row fixes
     if (MODE == 2) {
         const int khw = g.kh * g.kw;
@@ -247,15 +307,19 @@ __global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__re
         const int ab = row - r_ci * khw;
         r_a = ab / g.kw; r_b = ab - r_a * g.kw;
     }
-    // what k0 fixes; the three following k advance it like a mixed-radix counter
-    int k_img = k0 / g.HoWo;
-    int k_px = k0 - k_img * g.HoWo;
-    int k_oh = k_px / g.Wo, k_ow = k_px - k_oh * g.Wo;
-    uint32_t d[4] = {0, 0, 0, 0};
-    if (row < rows) {
+    uint32_t v[4][4];
+    bool ok[4][4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int k0 = kb + q * 1024;
+        // what k0 fixes; the three following k advance it like a mixed-radix counter
+        int k_img = k0 / g.HoWo;
+        int k_px = k0 - k_img * g.HoWo;
+        int k_oh = k_px / g.Wo, k_ow = k_px - k_oh * g.Wo;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (k0 + c < K) {
+            v[q][c] = 0; ok[q][c] = false;
+            if (row < rows && k0 + c < K) {
                 long long idx = -1;
                 if (MODE == 1) {
                     idx = ((long long)k_img * g.Co + row) * g.HoWo + k_px;
@@ -264,7 +328,7 @@ __global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__re
                     if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)
                         idx = (((long long)k_img * g.Ci + r_ci) * g.H + ih) * g.W + iw;
                 }
-                if (idx >= 0) d[c] = digits_of(src[idx]);
+                if (idx >= 0) { v[q][c] = src[idx]; ok[q][c] = true; }
             }
             ++k_px;
             if (++k_ow == g.Wo) { k_ow = 0; if (++k_oh == g.Ho) { k_oh = 0; k_px = 0; ++k_img; } }
@@ -273,18 +337,27 @@ __global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__re
     const long long plane = (long long)rows_pad * Kp;
     uint32_t hi = 0;
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        const uint32_t w = gather_byte(d, a);
-        if (a >= 2) hi |= w;
-        *reinterpret_cast<uint32_t *>(planes + a * plane + (long long)row * Kp + k0) = w;
-    }
-    if (sums) {
-        uint32_t ds[4];
+    for (int q = 0; q < 4; ++q) {
+        const int k0 = kb + q * 1024;
+        if (k0 >= Kp) continue;
+        uint32_t d[4], ds[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) ds[c] = half_sums(d[c]);
+        for (int c = 0; c < 4; ++c) {
+            d[c] = ok[q][c] ? digits_of(v[q][c]) : 0u;
+            ds[c] = half_sums(d[c]);
+        }
+        int8_t *dst = planes + (long long)row * Kp + k0;
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
-            *reinterpret_cast<uint32_t *>(planes + (4 + a) * plane + (long long)row * Kp + k0) = gather_byte(ds, a);
+        for (int a = 0; a < 4; ++a) {
+            const uint32_t w = gather_byte(d, a);
+            if (a >= 2) hi |= w;
+            *reinterpret_cast<uint32_t *>(dst + a * plane) = w;
+        }
+        if (sums) {
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+                *reinterpret_cast<uint32_t *>(dst + (4 + a) * plane) = gather_byte(ds, a);
+        }
     }
     raise_flag(flag, hi != 0);
 }
@@ -292,7 +365,7 @@ __global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__re
 // Digit planes of the operands of a stride-1 convolution's weight gradient with
 // the contraction index k = (image r, row h, column wq), wq < Wp = Wo rounded up
 // to 16 (so a 16-byte piece of k never leaves its row).  A workgroup converts
-// 1024 consecutive k of one plane row, a thread four (all in one image row).
+// 4096 consecutive k of one plane row, a thread sixteen (all in one image row).
 //   SHIFTED false (A): plane row = co, h < Ho: dtilde[r][co][h][wq], zero for
 //       wq >= Wo; rows beyond `rows` and k beyond R*Ho*Wp are zeros.
 //   SHIFTED true (B):  plane row = (b, ci), h < Hp = Ho + kh - 1:
@@ -304,50 +377,100 @@ __global__ __launch_bounds__(256) void f_digits_rows_kernel(const uint32_t *__re
                                                             int8_t *__restrict__ planes, fconv_geom g,
                                                             int rows, int rows_pad, int Hk, int Wp,
                                                             int len, int pitch, int chunks, int sums,
-                                                            int *flag)
+                                                            int vec, int *flag)
 {
     const int row = blockIdx.x / chunks;                       // workgroup-uniform
-    const int k0 = ((blockIdx.x - row * chunks) * 256 + threadIdx.x) * 4;
+    // all sixteen loads of a thread are issued before the first is used: the
+    // kernel lives on the number of bytes in flight
+    if (SHIFTED) {
+        // four groups of four k, 1024 k apart: neighbouring lanes stay on
+        // neighbouring 16-byte runs of the shifted source
+        const int kb = (blockIdx.x - row * chunks) * 4096 + threadIdx.x * 4;
+        const int b = row / g.Ci, ci = row - b * g.Ci;
+        uint32_t v[4][4];
+        bool ok[4][4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int k0 = kb + q * 1024;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) { v[q][c] = 0; ok[q][c] = false; }
+            if (row < rows && k0 < len) {
+                const int img = k0 / (Hk * Wp);
+                const int rem = k0 - img * (Hk * Wp);
+                const int h = rem / Wp, wq = rem - h * Wp;
+                const int ih = h - g.pad;
+                if (ih >= 0 && ih < g.H) {
+                    const uint32_t *s = src + (((long long)img * g.Ci + ci) * g.H + ih) * g.W;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const int iw = wq + c + b - g.pad;
+                        if (wq + c < g.Wo && iw >= 0 && iw < g.W) { v[q][c] = s[iw]; ok[q][c] = true; }
+                    }
+                }
+            }
+        }
+        const long long plane = (long long)rows_pad * pitch;
+        uint32_t hi = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int k0 = kb + q * 1024;
+            if (k0 >= pitch) continue;
+            uint32_t d[4], ds[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                d[c] = ok[q][c] ? digits_of(v[q][c]) : 0u;
+                ds[c] = half_sums(d[c]);
+            }
+            int8_t *dst = planes + (long long)row * pitch + k0;
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const uint32_t w = gather_byte(d, a);
+                if (a >= 2) hi |= w;
+                *reinterpret_cast<uint32_t *>(dst + a * plane) = w;
+            }
+            if (sums) {
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+                    *reinterpret_cast<uint32_t *>(dst + (4 + a) * plane) = gather_byte(ds, a);
+            }
+        }
+        raise_flag(flag, hi != 0);
+        return;
+    }
+    const int k0 = ((blockIdx.x - row * chunks) * 256 + threadIdx.x) * 16;
     if (k0 >= pitch) return;
-    uint32_t d[4] = {0, 0, 0, 0};
+    uint32_t v[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) v[c] = 0;
+    bool ok[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) ok[c] = false;
     if (row < rows && k0 < len) {
         const int img = k0 / (Hk * Wp);
         const int rem = k0 - img * (Hk * Wp);
         const int h = rem / Wp, wq = rem - h * Wp;
-        if (!SHIFTED) {
+        {
             const uint32_t *s = src + (((long long)img * g.Co + row) * g.Ho + h) * g.Wo;
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (wq + c < g.Wo) d[c] = digits_of(s[wq + c]);
-        } else {
-            const int b = row / g.Ci, ci = row - b * g.Ci;
-            const int ih = h - g.pad;
-            if (ih >= 0 && ih < g.H) {
-                const uint32_t *s = src + (((long long)img * g.Ci + ci) * g.H + ih) * g.W;
+            for (int q = 0; q < 4; ++q) {
+                if (vec && wq + 4 * q + 3 < g.Wo) {          // vec: Wo % 4 == 0 and an aligned base
+                    const u32x4 t = *reinterpret_cast<const u32x4 *>(s + wq + 4 * q);
+                    v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const int iw = wq + c + b - g.pad;
-                    if (wq + c < g.Wo && iw >= 0 && iw < g.W) d[c] = digits_of(s[iw]);
+                    for (int c = 0; c < 4; ++c) ok[4 * q + c] = true;
+                } else {
+#pragma unroll
+                    for (int c = 4 * q; c < 4 * q + 4; ++c)
+                        if (wq + c < g.Wo) { v[c] = s[wq + c]; ok[c] = true; }
                 }
             }
         }
     }
+    uint32_t d[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) d[c] = ok[c] ? digits_of(v[c]) : 0u;
     const long long plane = (long long)rows_pad * pitch;
-    uint32_t hi = 0;
-#pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        const uint32_t w = gather_byte(d, a);
-        if (a >= 2) hi |= w;
-        *reinterpret_cast<uint32_t *>(planes + a * plane + (long long)row * pitch + k0) = w;
-    }
-    if (sums) {
-        uint32_t ds[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) ds[c] = half_sums(d[c]);
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-            *reinterpret_cast<uint32_t *>(planes + (4 + a) * plane + (long long)row * pitch + k0) = gather_byte(ds, a);
-    }
+    const uint32_t hi = store_pieces(d, planes + (long long)row * pitch + k0, plane, sums);
     raise_flag(flag, hi != 0);
 }
 
@@ -357,16 +480,36 @@ __global__ __launch_bounds__(256) void f_digits_rows_kernel(const uint32_t *__re
 // one pixel to each plane.
 __global__ __launch_bounds__(256) void f_digits_nhwc_kernel(const uint32_t *__restrict__ src,
                                                             int8_t *__restrict__ planes, int Ci, int HW,
-                                                            int cp, long long plane, int *flag)
+                                                            int cp, long long plane, int vec, int *flag)
 {
     __shared__ uint32_t tile[128][65];
     const int c0 = blockIdx.x * 64, k0 = blockIdx.y * 128, img = blockIdx.z;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     const uint32_t *s = src + (long long)img * Ci * HW;
+    if (vec) {
+        // HW % 4 == 0 and an aligned base: eight 16-byte loads per thread, all in
+        // flight at once (16 lanes per channel row of the tile)
+        u32x4 t[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int item = threadIdx.x + 256 * r;
+            const int k = k0 + (item >> 4), c = c0 + (item & 15) * 4;
+            t[r] = u32x4{0, 0, 0, 0};
+            if (k < Ci && c < HW) t[r] = *reinterpret_cast<const u32x4 *>(s + (long long)k * HW + c);
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int item = threadIdx.x + 256 * r;
+            uint32_t *dst = &tile[item >> 4][(item & 15) * 4];
+            dst[0] = digits_of(t[r].x); dst[1] = digits_of(t[r].y);
+            dst[2] = digits_of(t[r].z); dst[3] = digits_of(t[r].w);
+        }
+    } else {
 #pragma unroll 8
-    for (int r = 0; r < 32; ++r) {
-        const int k = k0 + ty + 4 * r, c = c0 + tx;
-        tile[ty + 4 * r][tx] = (k < Ci && c < HW) ? digits_of(s[(long long)k * HW + c]) : 0u;
+        for (int r = 0; r < 32; ++r) {
+            const int k = k0 + ty + 4 * r, c = c0 + tx;
+            tile[ty + 4 * r][tx] = (k < Ci && c < HW) ? digits_of(s[(long long)k * HW + c]) : 0u;
+        }
     }
     __syncthreads();
     uint32_t hi = 0;
@@ -948,7 +1091,7 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
 dk_status run_digits(const uint32_t *src, int8_t *planes, int rows, int K, int rows_pad, int Kp,
                      int *flag, hipStream_t st)
 {
-    const int chunks = (Kp / 4 + 255) / 256;
+    const int chunks = (Kp + 4095) / 4096;          // Kp is a multiple of 128
     const long long blocks = (long long)rows_pad * chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     const int vec = (K % 4 == 0) && dk_aligned(src, 16);
@@ -972,7 +1115,7 @@ template <int MODE>
 dk_status run_digits_conv(const uint32_t *src, int8_t *planes, const fconv_geom &cg, int rows, int K,
                           int rows_pad, int Kp, int sums, int *flag, hipStream_t st)
 {
-    const int chunks = (Kp / 4 + 255) / 256;
+    const int chunks = (Kp + 4095) / 4096;
     const long long blocks = (long long)rows_pad * chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     dk_prof_scope ps(MODE == 1 ? "f_digits_dt" : "f_digits_im2col_t", st);
@@ -985,12 +1128,13 @@ template <bool SHIFTED>
 dk_status run_digits_rows(const uint32_t *src, int8_t *planes, const fconv_geom &cg, int rows, int rows_pad,
                           int Hk, int Wp, int len, int pitch, int sums, int *flag, hipStream_t st)
 {
-    const int chunks = (pitch / 4 + 255) / 256;
+    const int chunks = (pitch + 4095) / 4096;              // a workgroup covers 4096 k; pitch is a multiple of 16
     const long long blocks = (long long)rows_pad * chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
+    const int vec = !SHIFTED && cg.Wo % 4 == 0 && dk_aligned(src, 16);
     dk_prof_scope ps(SHIFTED ? "f_digits_shifted" : "f_digits_dt", st);
     f_digits_rows_kernel<SHIFTED><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(
-        src, planes, cg, rows, rows_pad, Hk, Wp, len, pitch, chunks, sums, flag);
+        src, planes, cg, rows, rows_pad, Hk, Wp, len, pitch, chunks, sums, vec, flag);
     return dk_launch_status();
 }
 
@@ -1104,7 +1248,7 @@ DK_EXPORT dk_status dkf_conv_fwd(const dk_layer *L, const uint32_t *Wq, const ui
         {
             dk_prof_scope ps("f_digits_nhwc", st);
             f_digits_nhwc_kernel<<<dim3((HW + 63) / 64, (g.Ci + 127) / 128, R), dim3(256), 0, st>>>(
-                xbar, Bp, g.Ci, HW, g.Ci, plane, flag + 1);
+                xbar, Bp, g.Ci, HW, g.Ci, plane, (HW % 4 == 0) && dk_aligned(xbar, 16), flag + 1);
         }
         DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
         const fconv_geom cg = conv_geom_of(g);
@@ -1122,10 +1266,6 @@ DK_EXPORT dk_status dkf_conv_fwd(const dk_layer *L, const uint32_t *Wq, const ui
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
     return run_fgemm(pl, Ap, Bp, part, flag, ybar, nullptr, 0, 1.0f, 0, g.Ho * g.Wo, "f_gemm_fwd", st);
 }
-
-namespace {
-
-} // namespace
 
 DK_EXPORT size_t dkf_fwd_workspace_bytes(int M, int N, int R)
 {
