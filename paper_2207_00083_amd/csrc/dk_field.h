@@ -15,6 +15,7 @@ dk_status dkf_delta_mix(const float *delta, const float *xscale, const uint32_t 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef i32x4 i32x4_u __attribute__((aligned(1)));     // for global loads at any byte address
 typedef int i32x16 __attribute__((ext_vector_type(16)));
 
 // v mod p for v < 2^56, by folding the bits above 2^25 twice with

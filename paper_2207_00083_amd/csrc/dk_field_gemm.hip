@@ -58,11 +58,12 @@ struct fgemm_params {
     int tiles_i, tiles_j, splits, ktiles_per_split, ktiles;
     // implicit convolution operand (B read from channels-last digit planes [R][H][W][cp])
     int cp, cH, cW, ckh, ckw, cstride, cpad, cWo, cHoWo;
-    // shifted-rows operand (B of a stride-1 convolution's weight gradient, see f_digits_rows_kernel):
+    // padded-rows operand (B of a stride-1 convolution's weight gradient, see f_digits_rows_kernel):
     // with it cp = Ci, ckh, ckw = filter size, cWo = row pitch Wp of the contraction index
-    int sRow;              // bytes per (shift, channel) row of a plane: R * Hp * Wp
+    int sRow;              // bytes per channel row of a plane: R * Hp * Wpp
     int sImgK;             // contraction indices per image: Ho * Wp
-    int sSkip;             // (Hp - Ho) * Wp: what an image adds to the offset beyond its k
+    int sImgP;             // plane bytes per image: Hp * Wpp
+    int sWpp;              // row pitch of the planes
     int sK;                // contraction length R * Ho * Wp
     int out_hw;            // 0: C[i][j] at i*J + j;  hw > 0: j = (image, pixel), C at ((image*I + i)*hw + pixel
     double s_inv;          // 2^-l for out_f
@@ -368,10 +369,11 @@ __global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__re
 // 4096 consecutive k of one plane row, a thread sixteen (all in one image row).
 //   SHIFTED false (A): plane row = co, h < Ho: dtilde[r][co][h][wq], zero for
 //       wq >= Wo; rows beyond `rows` and k beyond R*Ho*Wp are zeros.
-//   SHIFTED true (B):  plane row = (b, ci), h < Hp = Ho + kh - 1:
-//       xbar[r][ci][h - pad][wq + b - pad], zero outside the image and for
-//       wq >= Wo.  Filter tap (a, b) of channel ci is this row read from h = oh + a:
-//       three (kw) shifted copies serve all kh * kw taps.
+//   SHIFTED true (B):  plane row = ci, h < Hp = Ho + kh - 1, columns of pitch
+//       Wp (here the planes' own pitch, at least Wo rounded up to 16 plus
+//       kw - 1): xbar[r][ci][h - pad][wq - pad], zero outside the image.  Filter
+//       tap (a, b) of channel ci is this row read from h = oh + a, b bytes on:
+//       one padded copy serves all kh * kw taps.
 template <bool SHIFTED>
 __global__ __launch_bounds__(256) void f_digits_rows_kernel(const uint32_t *__restrict__ src,
                                                             int8_t *__restrict__ planes, fconv_geom g,
@@ -386,7 +388,7 @@ __global__ __launch_bounds__(256) void f_digits_rows_kernel(const uint32_t *__re
         // four groups of four k, 1024 k apart: neighbouring lanes stay on
         // neighbouring 16-byte runs of the shifted source
         const int kb = (blockIdx.x - row * chunks) * 4096 + threadIdx.x * 4;
-        const int b = row / g.Ci, ci = row - b * g.Ci;
+        const int ci = row;
         uint32_t v[4][4];
         bool ok[4][4];
 #pragma unroll
@@ -403,8 +405,8 @@ __global__ __launch_bounds__(256) void f_digits_rows_kernel(const uint32_t *__re
                     const uint32_t *s = src + (((long long)img * g.Ci + ci) * g.H + ih) * g.W;
 #pragma unroll
                     for (int c = 0; c < 4; ++c) {
-                        const int iw = wq + c + b - g.pad;
-                        if (wq + c < g.Wo && iw >= 0 && iw < g.W) { v[q][c] = s[iw]; ok[q][c] = true; }
+                        const int iw = wq + c - g.pad;
+                        if (iw >= 0 && iw < g.W) { v[q][c] = s[iw]; ok[q][c] = true; }
                     }
                 }
             }
@@ -588,9 +590,10 @@ __device__ __forceinline__ uint32_t reduce_signed(long long v)
 // of the encodings directly (16 consecutive channels per piece, zeros outside
 // the image), so no patch matrix exists in memory.
 // BMODE 2: the B operand of a stride-1 convolution's weight gradient: row
-// j = (ci, a, b) is row (b, ci) of the shifted-rows planes read a * Wp bytes
-// further on; the contraction index k = (image, oh, wq) skips the kh - 1 extra
-// rows each image has there.  BMODE 1 is IMPL, 0 a stored matrix.
+// j = (ci, a, b) is channel row ci of the padded-rows planes read a rows and b
+// bytes further on (the 16-byte loads are then not 16-byte aligned, which
+// global loads on this target allow); the contraction index k = (image, oh, wq)
+// is mapped onto the planes' own pitches.  BMODE 1 is IMPL, 0 a stored matrix.
 // NBI: 32-row blocks of A per wave; the workgroup tile is (64 NBI) x 128 (a
 // 64-row tile keeps operands with at most 64 rows from wasting half the MFMAs).
 template <int BMODE, int NBI>
@@ -660,7 +663,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
             const int ci = r_ok[q] ? j / taps : 0;
             const int ab = r_ok[q] ? j - ci * taps : 0;
             const int fa_ = ab / p.ckw, fb_ = ab - fa_ * p.ckw;
-            r_base[q] = (unsigned)(fb_ * p.cp + ci) * (unsigned)p.sRow + (unsigned)(fa_ * p.cWo);
+            r_base[q] = (unsigned)ci * (unsigned)p.sRow + (unsigned)(fa_ * p.sWpp + fb_);
             r_ih[q] = r_iw[q] = 0;
         }
     }
@@ -721,13 +724,15 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         } else if (BMODE == 2) {                                                                  \
             const int k0_ = (KTILE) * KT + 16 * spiece;                                           \
             const int img_ = k0_ / p.sImgK;                                                       \
-            const unsigned koff_ = (unsigned)k0_ + (unsigned)img_ * (unsigned)p.sSkip;            \
+            const int rem_ = k0_ - img_ * p.sImgK;                                                \
+            const int oh_ = rem_ / p.cWo;                                                         \
+            const unsigned koff_ = (unsigned)img_ * (unsigned)p.sImgP + (unsigned)(oh_ * p.sWpp + (rem_ - oh_ * p.cWo)); \
             const bool kok_ = k0_ < p.sK;                                                         \
             const int8_t *bp_ = p.Bp + 2 * (q_ >> 2) * p.b_plane;                                 \
             _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                       \
                 _Pragma("unroll") for (int pl = 0; pl < 2; ++pl) {                                \
                     i32x4 v_ = {0, 0, 0, 0};                                                      \
-                    if (kok_ && r_ok[q]) v_ = *reinterpret_cast<const i32x4 *>(bp_ + pl * p.b_plane + (r_base[q] + koff_)); \
+                    if (kok_ && r_ok[q]) v_ = *reinterpret_cast<const i32x4_u *>(bp_ + pl * p.b_plane + (r_base[q] + koff_)); \
                     sb[pl * 4 + q] = v_;                                                          \
                 }                                                                                 \
             }                                                                                     \
@@ -1017,10 +1022,10 @@ constexpr size_t FLAG_BYTES = 256;
 // Shifted-rows form of the B operand of a stride-1 convolution's weight
 // gradient (f_digits_rows_kernel): sizes the GEMM needs to address it.
 struct fshift {
-    int Ci, kh, kw, Ho, Hp, Wp;
-    int row_bytes;          // R * Hp * Wp
-    int img_k, skip, K;     // Ho * Wp, (Hp - Ho) * Wp, R * Ho * Wp
-    long long plane;        // bytes per digit plane: kw * Ci * row_bytes
+    int Ci, kh, kw, Ho, Hp, Wp, Wpp;
+    int row_bytes;          // R * Hp * Wpp
+    int img_k, img_p, K;    // Ho * Wp, Hp * Wpp, R * Ho * Wp
+    long long plane;        // bytes per digit plane: Ci * row_bytes
 };
 
 // C = A B^T over the field from digit planes.  out_q / out_f as in the kernel
@@ -1061,10 +1066,11 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
         p.cstride = impl->stride; p.cpad = impl->pad; p.cWo = impl->Wo; p.cHoWo = impl->HoWo;
         p.b_plane = impl_plane;
     }
-    p.sRow = p.sImgK = p.sSkip = p.sK = 0;
+    p.sRow = p.sImgK = p.sImgP = p.sWpp = p.sK = 0;
     if (shift) {
         p.cp = shift->Ci; p.ckh = shift->kh; p.ckw = shift->kw; p.cWo = shift->Wp;
-        p.sRow = shift->row_bytes; p.sImgK = shift->img_k; p.sSkip = shift->skip; p.sK = shift->K;
+        p.sRow = shift->row_bytes; p.sImgK = shift->img_k; p.sImgP = shift->img_p; p.sWpp = shift->Wpp;
+        p.sK = shift->K;
         p.b_plane = shift->plane;
     }
     const long long blocks = (long long)pl.splits * pl.tiles_i * pl.tiles_j;
@@ -1163,19 +1169,21 @@ bool plan_conv_fwd(const dk_geom &g, long long R, fgemm_plan *pl)
         pl->b_bytes = align256((size_t)4 * R * g.H * g.W * g.Ci);
     return true;
 }
-// The shifted-rows form: stride 1, more than one tap, and an output width
-// that rounding up to 16 lengthens by at most a seventh (56 -> 64).
+// The padded-rows form: stride 1, more than one tap, and an output width
+// that rounding up to 16 lengthens by at most a seventh (56 -> 64).  The planes'
+// rows are Wpp >= Wp + kw - 1 bytes, so a 16-byte piece read b bytes on stays
+// inside its row.
 bool conv_wgrad_shifted(const dk_geom &g, long long R, fshift *sh)
 {
     if (g.stride != 1 || g.kh * g.kw == 1) return false;
     const int Wp = round_up(g.Wo, 16);
     if (Wp * 7 > g.Wo * 8) return false;
-    const int Hp = g.Ho + g.kh - 1;
-    const long long row = R * Hp * Wp, plane = (long long)g.kw * g.Ci * row;
+    const int Hp = g.Ho + g.kh - 1, Wpp = round_up(Wp + g.kw - 1, 4);
+    const long long row = R * Hp * Wpp, plane = (long long)g.Ci * row;
     if (plane * 6 >= (1ll << 31) || R * g.Ho * Wp > (1 << 26)) return false;
     if (sh) {
-        sh->Ci = g.Ci; sh->kh = g.kh; sh->kw = g.kw; sh->Ho = g.Ho; sh->Hp = Hp; sh->Wp = Wp;
-        sh->row_bytes = (int)row; sh->img_k = g.Ho * Wp; sh->skip = (Hp - g.Ho) * Wp;
+        sh->Ci = g.Ci; sh->kh = g.kh; sh->kw = g.kw; sh->Ho = g.Ho; sh->Hp = Hp; sh->Wp = Wp; sh->Wpp = Wpp;
+        sh->row_bytes = (int)row; sh->img_k = g.Ho * Wp; sh->img_p = Hp * Wpp;
         sh->K = (int)(R * g.Ho * Wp);
         sh->plane = plane;
     }
@@ -1186,7 +1194,7 @@ bool plan_conv_wgrad(const dk_geom &g, long long R, fgemm_plan *pl)
 {
     fshift sh;
     if (conv_wgrad_shifted(g, R, &sh)) {
-        // three shifted copies instead of kh * kw: the digit-sum planes pay here too
+        // one padded copy instead of kh * kw shifted ones: the digit-sum planes pay here too
         if (!plan_fgemm(g.Co, g.Kg, sh.K, pl, true)) return false;
         pl->b_bytes = align256((size_t)6 * sh.plane);
         return true;
@@ -1359,8 +1367,7 @@ dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *xscale,
         const fconv_geom cg = conv_geom_of(g);
         s = run_digits_rows<false>(dtilde, Ap, cg, g.Co, pl.I_pad, sh.Ho, sh.Wp, sh.K, pl.Kp, pl.sums, flag, st);
         if (s != DK_OK) return s;
-        const int brows = g.kw * g.Ci;
-        s = run_digits_rows<true>(xbar, Bp, cg, brows, brows, sh.Hp, sh.Wp, sh.row_bytes, sh.row_bytes, pl.sums,
+        s = run_digits_rows<true>(xbar, Bp, cg, g.Ci, g.Ci, sh.Hp, sh.Wpp, sh.row_bytes, sh.row_bytes, pl.sums,
                                   flag + 1, st);
         if (s != DK_OK) return s;
         return run_fgemm(pl, Ap, Bp, part, flag, dwq, dW, l, scale, accumulate, 0, "f_gemm_wgrad", st,
