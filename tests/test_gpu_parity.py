@@ -622,6 +622,25 @@ def test_verify_flags_tampered_stored_encodings(dk):
     assert host(v).tolist() == vref.tolist()
 
 
+@pytest.mark.parametrize("L,K,G", [
+    (dk_inputs.conv(64, 64, 32, 32, 3), 4, 4),          # the two 16-byte-read convolution kernels
+    (dk_inputs.conv(24, 40, 14, 14, 3), 2, 3),          # patch forward, gather weight gradient
+    (dk_inputs.conv(128, 64, 14, 14, 1, 1, 0), 4, 2),   # image-aware 1x1 loaders
+    (dk_inputs.conv(32, 48, 2, 2, 3), 2, 2),            # small images on the dense engine
+    (dk_inputs.linear(300, 1100), 8, 3),                # dense, sliced contraction
+    (dk_inputs.dwconv(24, 16, 16, 3), 4, 2)])
+def test_whole_path_is_bitwise_reproducible(dk, L, K, G):
+    """No atomics on floating-point data and fixed fold orders: two runs of the
+    whole path on the same inputs agree bit for bit."""
+    say("rerun", L)
+    d = _masked_case(L, K, G, seed=4711)
+    a = _run_masked(dk, d)
+    b = _run_masked(dk, d)
+    for key in ("xbar", "ybar", "y", "dW", "resid"):
+        assert np.array_equal(a[key].view(np.uint32), b[key].view(np.uint32)), key
+    assert a["verdict"].tolist() == b["verdict"].tolist()
+
+
 def test_bias_rides_along_as_an_input_feature(dk):
     """The layer's bias needs no entry point of its own: encoding and decoding
     are linear, so a constant-one input feature (dense) or a constant-one
