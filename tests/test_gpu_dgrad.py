@@ -57,3 +57,33 @@ def test_depthwise_dgrad(dk, L):
     D = rng.normal(size=(R,) + L.out_shape).astype(np.float32)
     dx = dk.dk_dgrad(L, dev(W), dev(D))
     assert normwise_err(dx.cpu().numpy(), oracle.dwconv_dgrad(D, W, L.H, L.W, L.stride, L.pad)) < 1e-5
+
+
+def _random_dgrad_convs(seed, count):
+    """Seeded draw of convolution shapes for the data gradient: stride-1
+    shapes run as a forward convolution with flipped filters, the rest on the
+    gather loaders; widths and channel counts on both sides of the tile sizes."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        k = int(rng.choice([1, 3, 3, 5]))
+        stride = int(rng.choice([1, 1, 2]))
+        pad = int(rng.choice([0, k // 2]))
+        H = int(rng.choice([2, 4, 7, 8, 14, 16]))
+        W = int(rng.choice([2, 4, 7, 8, 14, 16, 32]))
+        if H + 2 * pad < k or W + 2 * pad < k:
+            continue
+        out.append(dk_inputs.conv(int(rng.choice([1, 3, 16, 24, 70])), int(rng.choice([1, 8, 33, 64, 130])),
+                                  H, W, k, stride, pad))
+    return out
+
+
+@pytest.mark.parametrize("L", _random_dgrad_convs(20264, 24))
+def test_conv_dgrad_random_shapes(dk, L):
+    rng = np.random.default_rng([L.Ci, L.Co, L.H, L.W, L.kh, L.stride, L.pad])
+    R = int(rng.choice([1, 3, 10]))
+    W = rng.normal(size=L.w_shape).astype(np.float32)
+    D = rng.normal(size=(R,) + L.out_shape).astype(np.float32)
+    dx = dk.dk_dgrad(L, dev(W), dev(D))
+    assert tuple(dx.shape) == (R,) + L.in_shape
+    assert normwise_err(dx.cpu().numpy(), oracle.conv_dgrad(D, W, L.H, L.W, L.stride, L.pad)) < 1e-5
