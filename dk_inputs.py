@@ -302,9 +302,12 @@ def resnet50_convs(include_stem=False):
     return list(merged.items())
 
 
-def config4(seed=4, batch=64, K=8, include_stem=False):
-    """Generator over (inputs dict, multiplicity) for the ResNet-50 shapes."""
+def config4(seed=4, batch=64, K=8, include_stem=False, index=None):
+    """Generator over (inputs dict, multiplicity) for the ResNet-50 shapes
+    (all of them, or only shape number `index`)."""
     for li, (lay, count) in enumerate(resnet50_convs(include_stem)):
+        if index is not None and li != index:
+            continue
         rng = np.random.default_rng([seed, li])   # one stream per layer
         d = masked_layer_inputs(rng, lay, K=K, batch=batch,
                                 x_dist="uniform" if lay.Ci == 3 else "relu_normal")

@@ -150,9 +150,17 @@ def _ptr(t):
     return C.c_void_p(0 if t is None else int(t.data_ptr()))
 
 
-def _workspace(nbytes, like):
+def _workspace(nbytes, like, stream=None):
+    """A temporary workspace for one call.  It is dropped when the call
+    returns while its kernels may still be queued, so it has to come from the
+    pool of the stream the kernels run on: the caching allocator then hands
+    the block only to later work on that same stream."""
     torch = _torch()
-    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=like.device)
+    nbytes = max(int(nbytes), 256)
+    if stream is None:
+        return torch.empty(nbytes, dtype=torch.uint8, device=like.device)
+    with torch.cuda.stream(stream):
+        return torch.empty(nbytes, dtype=torch.uint8, device=like.device)
 
 
 def _wshape(lay):
@@ -224,7 +232,7 @@ def dk_linear_fwd(W, xbar, ybar=None, ws=None, stream=None):
         raise ValueError("dk_linear_fwd: ybar has the wrong size")
     if ws is None:
         lay = DkLayer(0, M, N, 0, 0, 0, 0, 1, 1, 1, 0)
-        ws = _workspace(_fwd_ws_bytes(lay, R), W)
+        ws = _workspace(_fwd_ws_bytes(lay, R), W, stream)
     _check(load().dk_linear_fwd(_ptr(W), _ptr(xbar), _ptr(ybar), M, N, R, _ptr(ws), ws.numel(),
                                 _stream(stream)), "dk_linear_fwd")
     return ybar
@@ -253,7 +261,7 @@ def dk_conv_fwd(layer, W, xbar, ybar=None, ws=None, stream=None):
     if ybar.numel() != R * m:
         raise ValueError("dk_conv_fwd: ybar has the wrong size")
     if ws is None:
-        ws = _workspace(_fwd_ws_bytes(lay, R), W)
+        ws = _workspace(_fwd_ws_bytes(lay, R), W, stream)
     _check(load().dk_conv_fwd(C.byref(lay), _ptr(W), _ptr(xbar), _ptr(ybar), R, _ptr(ws),
                               ws.numel(), _stream(stream)), "dk_conv_fwd")
     return ybar
@@ -281,7 +289,7 @@ def dk_wgrad(layer, delta, B, gamma, xbar, K, dW=None, scale=1.0, accumulate=Fal
     if dW.numel() != int(np.prod(wshape)):
         raise ValueError("dk_wgrad: dW has the wrong size")
     if ws is None:
-        ws = _workspace(load().dk_workspace_bytes(C.byref(lay), DK_OP_WGRAD, G, K), delta)
+        ws = _workspace(load().dk_workspace_bytes(C.byref(lay), DK_OP_WGRAD, G, K), delta, stream)
     _check(load().dk_wgrad(C.byref(lay), _ptr(delta), _ptr(B), _ptr(gamma), _ptr(xbar), _ptr(dW),
                            G, K, float(scale), int(bool(accumulate)), _ptr(ws), ws.numel(),
                            _stream(stream)), "dk_wgrad")
@@ -319,7 +327,7 @@ def dk_verify(ybar, nvec, K, tol=1e-3, verdict=None, resid=None, ws=None, stream
     if resid is None:
         resid = torch.empty(G, dtype=torch.float32, device=ybar.device)
     if ws is None:
-        ws = _workspace(load().dk_workspace_bytes(None, DK_OP_VERIFY, G, K), ybar)
+        ws = _workspace(load().dk_workspace_bytes(None, DK_OP_VERIFY, G, K), ybar, stream)
     _check(load().dk_verify(_ptr(ybar), _ptr(nvec), float(tol), _ptr(verdict), _ptr(resid), G, K, m,
                             _ptr(ws), ws.numel(), _stream(stream)), "dk_verify")
     return verdict, resid
@@ -345,7 +353,7 @@ def dk_decode_verify(ybar, Ainv, nvec, K, tol=1e-3, y=None, verdict=None, resid=
     if resid is None:
         resid = torch.empty(G, dtype=torch.float32, device=ybar.device)
     if ws is None:
-        ws = _workspace(load().dk_workspace_bytes(None, DK_OP_VERIFY, G, K), ybar)
+        ws = _workspace(load().dk_workspace_bytes(None, DK_OP_VERIFY, G, K), ybar, stream)
     _check(load().dk_decode_verify(_ptr(ybar), _ptr(Ainv), _ptr(nvec), float(tol), _ptr(y), _ptr(verdict),
                                    _ptr(resid), G, K, m, _ptr(ws), ws.numel(), _stream(stream)),
            "dk_decode_verify")
@@ -407,7 +415,7 @@ def dk_decode_verify_m(ybar, Ainv, nvec, K, M, tol=1e-3, y=None, verdict=None, r
     if resid is None:
         resid = torch.empty(G, dtype=torch.float32, device=ybar.device)
     if ws is None:
-        ws = _workspace(load().dk_workspace_bytes_m(None, DK_OP_VERIFY, G, K, M), ybar)
+        ws = _workspace(load().dk_workspace_bytes_m(None, DK_OP_VERIFY, G, K, M), ybar, stream)
     _check(load().dk_decode_verify_m(_ptr(ybar), _ptr(Ainv), _ptr(nvec), float(tol), _ptr(y), _ptr(verdict),
                                      _ptr(resid), G, K, M, m, _ptr(ws), ws.numel(), _stream(stream)),
            "dk_decode_verify_m")
@@ -436,7 +444,7 @@ def dk_wgrad_m(layer, delta, B, gamma, xbar, K, M, dW=None, scale=1.0, accumulat
     if dW.numel() != int(np.prod(wshape)):
         raise ValueError("dk_wgrad_m: dW has the wrong size")
     if ws is None:
-        ws = _workspace(load().dk_workspace_bytes_m(C.byref(lay), DK_OP_WGRAD, G, K, M), delta)
+        ws = _workspace(load().dk_workspace_bytes_m(C.byref(lay), DK_OP_WGRAD, G, K, M), delta, stream)
     _check(load().dk_wgrad_m(C.byref(lay), _ptr(delta), _ptr(B), _ptr(gamma), _ptr(xbar), _ptr(dW),
                              G, K, M, float(scale), int(bool(accumulate)), _ptr(ws), ws.numel(),
                              _stream(stream)), "dk_wgrad_m")
@@ -461,7 +469,7 @@ def dk_dgrad(layer, W, delta, dx=None, ws=None, stream=None):
     if dx.numel() != R * n:
         raise ValueError("dk_dgrad: dx has the wrong size")
     if ws is None:
-        ws = _workspace(load().dk_dgrad_workspace_bytes(C.byref(lay), R), W)
+        ws = _workspace(load().dk_dgrad_workspace_bytes(C.byref(lay), R), W, stream)
     _check(load().dk_dgrad(C.byref(lay), _ptr(W), _ptr(delta), _ptr(dx), R, _ptr(ws), ws.numel(),
                            _stream(stream)), "dk_dgrad")
     return dx

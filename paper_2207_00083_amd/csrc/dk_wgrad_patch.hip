@@ -468,11 +468,13 @@ constexpr int DSLOT4 = 6, PSLOT4 = 10, DSLOTQ = 6, PSLOTQ = 11;
 constexpr size_t LDS_LIMIT = 150 * 1024;     // of the 160 KB a compute unit has
 constexpr size_t DUMP_BYTES = 1024;          // behind the buffers: where unused copy slots store
 
+// `allowed` is the record of one kernel (the caller keeps one per kernel: the
+// two kernels launched through here have the same function type, so a record
+// inside this template would be shared between them).
 template <class KernelT>
-dk_status launch_one(KernelT kernel, const dk_wgpatch_params &p, size_t lds_bytes, hipStream_t st,
-                     const char *label)
+dk_status launch_one(KernelT kernel, std::atomic<unsigned long long> &allowed, const dk_wgpatch_params &p,
+                     size_t lds_bytes, hipStream_t st, const char *label)
 {
-    static std::atomic<unsigned long long> allowed{0};       // one per kernel instantiation
     const dk_status as = dk_allow_dynamic_lds(reinterpret_cast<const void *>(kernel), (int)(LDS_LIMIT + DUMP_BYTES),
                                               allowed);
     if (as != DK_OK) return as;
@@ -604,8 +606,11 @@ dk_status dk_patch_wgrad_run(const dk_geom &g, dk_wgpatch_plan &pl, const float 
 {
     dk_wgpatch_params &p = pl.p;
     p.dt = dtilde; p.x = xbar; p.part = part;
-    dk_status s = pl.quad ? launch_one(conv_quad_wgrad_kernel<DSLOTQ, PSLOTQ>, p, pl.lds_bytes, st, "conv_quad_wgrad")
-                          : launch_one(conv_patch_wgrad_kernel<3, 3, DSLOT4, PSLOT4>, p, pl.lds_bytes, st, "conv_patch_wgrad");
+    static std::atomic<unsigned long long> allowed_quad{0}, allowed_patch{0};
+    dk_status s = pl.quad ? launch_one(conv_quad_wgrad_kernel<DSLOTQ, PSLOTQ>, allowed_quad, p, pl.lds_bytes, st,
+                                       "conv_quad_wgrad")
+                          : launch_one(conv_patch_wgrad_kernel<3, 3, DSLOT4, PSLOT4>, allowed_patch, p,
+                                       pl.lds_bytes, st, "conv_patch_wgrad");
     if (s != DK_OK) return s;
     dk_prof_scope ps("wgrad_fold", st);
     wgrad_fold_kernel<<<dim3((unsigned)((p.part_elems + 63) / 64)), dim3(256), 0, st>>>(

@@ -181,7 +181,7 @@ def dkf_linear_fwd(Wq, xbar, ybar=None, ws=None, stream=None):
     if ybar.numel() != R * M:
         raise ValueError("dkf_linear_fwd: ybar has the wrong size")
     if ws is None:
-        ws = _workspace(dkf_fwd_workspace_bytes(M, N, R), Wq)
+        ws = _workspace(dkf_fwd_workspace_bytes(M, N, R), Wq, stream)
     _check(load().dkf_linear_fwd(_ptr(Wq), _ptr(xbar), _ptr(ybar), M, N, R, _ptr(ws), ws.numel(),
                                  _stream(stream)), "dkf_linear_fwd")
     return ybar
@@ -206,7 +206,7 @@ def dkf_conv_fwd(layer, Wq, xbar, ybar=None, ws=None, stream=None):
     if ybar.numel() != R * lay.Co * Ho * Wo:
         raise ValueError("dkf_conv_fwd: ybar has the wrong size")
     if ws is None:
-        ws = _workspace(dkf_conv_fwd_workspace_bytes(lay, R), Wq)
+        ws = _workspace(dkf_conv_fwd_workspace_bytes(lay, R), Wq, stream)
     _check(load().dkf_conv_fwd(C.byref(lay), _ptr(Wq), _ptr(xbar), _ptr(ybar), R, _ptr(ws), ws.numel(),
                                _stream(stream)), "dkf_conv_fwd")
     return ybar
@@ -275,7 +275,7 @@ def dkf_wgrad(layer, delta, B, gamma, xbar, K, l=DKF_L, dW=None, dwq=None, want_
     if dW.numel() != wcount or (dwq is not None and dwq.numel() != wcount):
         raise ValueError("dkf_wgrad: output has the wrong size")
     if ws is None:
-        ws = _workspace(dkf_wgrad_workspace_bytes(lay, G, K), delta)
+        ws = _workspace(dkf_wgrad_workspace_bytes(lay, G, K), delta, stream)
     if xscale is not None:
         _scales(xscale, G * K, "xscale")
         _check(load().dkf_wgrad_norm(C.byref(lay), _ptr(delta), _ptr(xscale), _ptr(B), _ptr(gamma), _ptr(xbar),

@@ -157,3 +157,29 @@ def test_graph_replay(dk, cls, L, K, G):
         path.step()                                # eager again between replays
         torch.cuda.synchronize()
         assert all(torch.equal(a, b) for a, b in zip(path.outputs(), ref))
+
+
+def test_explicit_stream_with_automatic_workspaces(dk):
+    """`stream=` given, `ws=` not: the binding takes the temporary workspace
+    from that stream's pool, so work queued afterwards on the current stream
+    (which reuses freed blocks at once) cannot overwrite it while the side
+    stream's kernels still run."""
+    L, K, G = dk_inputs.linear(300, 1100), 8, 3           # sliced contraction: the workspace holds partial sums
+    path = Fp32Path(dk, L, K, G, seed=33)
+    ref = _eager_reference(path)
+    _scrub(path)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    for _ in range(3):
+        dk.dk_encode(path.X, path.r, path.A, K, xbar=path.xbar, stream=side)
+        dk.dk_linear_fwd(path.W, path.xbar, ybar=path.ybar, stream=side)
+        dk.dk_decode_verify(path.ybar, path.Ainv, path.nvec, K, tol=1e-3, y=path.y, verdict=path.verdict,
+                            resid=path.resid, stream=side)
+        dk.dk_wgrad(L, path.delta, path.B, path.gamma, path.xbar, K, dW=path.dW, stream=side)
+        # current-stream allocations of the workspaces' sizes, filled at once
+        junk = [torch.full((n,), 255, dtype=torch.uint8, device="cuda")
+                for n in (path.ws_fwd.numel(), path.ws_wg.numel(), path.ws_vf.numel())]
+        del junk
+    side.synchronize()
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(path.outputs(), ref))
