@@ -48,7 +48,9 @@ typedef enum {
     DK_ERR_ALIGN = 4,       /* a device pointer is not 4-byte aligned          */
     DK_ERR_WORKSPACE = 5,   /* workspace missing or smaller than required      */
     DK_ERR_HIP = 6,         /* the HIP runtime refused a launch                */
-    DK_ERR_SINGULAR = 7     /* dk_coeffs: A[g] is singular or gamma has a zero */
+    DK_ERR_SINGULAR = 7,    /* dk_coeffs: A[g] is singular or gamma has a zero */
+    DK_ERR_STATIC_LIMIT = 8 /* dk_decode_verify_static: more groups than its
+                               built-in scratch array serves                   */
 } dk_status;
 
 /* Layer descriptor.  kind 0: dense y = W x with W[M][N].  kind 1: NCHW
@@ -158,6 +160,28 @@ dk_status dk_decode_verify(const float *ybar, const float *Ainv,
                            int *verdict, float *resid, int G, int K,
                            long long m, void *ws, size_t ws_bytes,
                            void *stream);
+
+/* dk_decode_verify for callers that cannot allocate device memory and so
+ * have no workspace to pass: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments (minus ws), same
+ * kernels and bit-identical results; the partial maxima of the integrity
+ * check go to an array of DK_STATIC_SCRATCH_BYTES bytes built into the
+ * library's device code (each GPU the library runs on holds it until the
+ * process ends), whose address is looked up once per device on the first
+ * call there.  The call allocates and frees nothing.
+ * Limit: G <= DK_STATIC_MAX_G, else DK_ERR_STATIC_LIMIT and nothing is
+ * launched.  All calls on one GPU share the array: calls that overlap there
+ * (different streams, or graphs replayed concurrently) race on it and give
+ * undefined verdicts; calls that follow each other on one stream are safe,
+ * and nothing needs clearing between them (a call writes every slot before
+ * it reads it). */
+#define DK_STATIC_SCRATCH_BYTES (2u << 20)
+#define DK_STATIC_MAX_G 4096
+dk_status dk_decode_verify_static(const float *ybar, const float *Ainv,
+                                  const float *nvec, float tol, float *y,
+                                  int *verdict, float *resid, int G, int K,
+                                  long long m, void *stream);
+size_t dk_static_scratch_bytes(void);
 
 /* Optional per-kernel timing for benchmarks (not part of the method).  While
  * enabled (on = 1 also clears earlier records) every kernel the library

@@ -74,6 +74,8 @@ def load():
         "dk_decode": (ip, [vp, vp, vp, ip, ip, ll, vp]),
         "dk_verify": (ip, [vp, vp, fl, vp, vp, ip, ip, ll, vp, sz, vp]),
         "dk_decode_verify": (ip, [vp, vp, vp, fl, vp, vp, vp, ip, ip, ll, vp, sz, vp]),
+        "dk_decode_verify_static": (ip, [vp, vp, vp, fl, vp, vp, vp, ip, ip, ll, vp]),
+        "dk_static_scratch_bytes": (sz, []),
         "dk_coeffs_m": (ip, [vp, vp, ip, ip, ip, vp, vp, vp]),
         "dk_encode_m": (ip, [vp, vp, vp, vp, ip, ip, ip, ll, vp]),
         "dk_decode_verify_m": (ip, [vp, vp, vp, fl, vp, vp, vp, ip, ip, ip, ll, vp, sz, vp]),
@@ -358,6 +360,27 @@ def dk_decode_verify(ybar, Ainv, nvec, K, tol=1e-3, y=None, verdict=None, resid=
                                    _ptr(resid), G, K, m, _ptr(ws), ws.numel(), _stream(stream)),
            "dk_decode_verify")
     return y, verdict, resid
+
+
+def dk_decode_verify_static(ybar, Ainv, nvec, K, y, verdict, resid=None, tol=1e-3, stream=None):
+    """dk_decode_verify without a workspace and without any allocation: the
+    caller passes every output (resid may be None)."""
+    ybar, Ainv, nvec, y = _dev(ybar, "ybar"), _dev(Ainv, "Ainv"), _dev(nvec, "nvec"), _dev(y, "y")
+    G = Ainv.shape[0]
+    S = K + 2
+    if Ainv.shape != (G, S, S) or nvec.shape != (G, S) or ybar.shape[0] != G * S:
+        raise ValueError("dk_decode_verify_static: inconsistent shapes")
+    m = ybar[0].numel()
+    if y.numel() != G * K * m or verdict.numel() != G or (resid is not None and resid.numel() != G):
+        raise ValueError("dk_decode_verify_static: an output has the wrong size")
+    _check(load().dk_decode_verify_static(_ptr(ybar), _ptr(Ainv), _ptr(nvec), float(tol), _ptr(y),
+                                          _ptr(verdict), _ptr(resid), G, K, m, _stream(stream)),
+           "dk_decode_verify_static")
+    return y, verdict, resid
+
+
+def dk_static_scratch_bytes() -> int:
+    return int(load().dk_static_scratch_bytes())
 
 
 # ---- several colluding accelerators: M noise rows per group, S = K+M+1 ----

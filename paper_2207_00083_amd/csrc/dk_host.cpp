@@ -18,6 +18,7 @@ DK_EXPORT const char *dk_status_str(int s)
     case DK_ERR_WORKSPACE: return "workspace missing or too small";
     case DK_ERR_HIP: return "HIP launch failed";
     case DK_ERR_SINGULAR: return "singular encoding matrix or zero gamma";
+    case DK_ERR_STATIC_LIMIT: return "more groups than the built-in scratch array serves";
     default: return "unknown status";
     }
 }

@@ -8,6 +8,13 @@
 
 static int verify_max_chunks(int G);
 
+// Scratch memory of dk_decode_verify_static (the entry point for callers that
+// cannot allocate): the partial maxima of the integrity check live here instead
+// of in a caller's workspace.  Every GPU the library runs on holds its own copy
+// until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[DK_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int MIX_THREADS = 256;
@@ -559,5 +566,54 @@ DK_EXPORT dk_status dk_decode_verify_m(const float *ybar, const float *Ainv, con
     const bool v4 = can_vec4(m, {ybar, y});
 #define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, (float *)ws, v4, K, (hipStream_t)stream)
     DK_K_SWITCH(K + M - 1, CALL)
+#undef CALL
+}
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::atomic<float *> scratch_ptr[MAX_DEVICES];       // device address of `scratch`, per device ordinal
+
+// The current device's copy of the scratch array.  Looked up once per device
+// (with that device current); no allocation, no stream operation.
+dk_status static_scratch(float **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return DK_ERR_HIP;
+    DK_REQUIRE(dev >= 0 && dev < MAX_DEVICES, DK_ERR_UNSUPPORTED);
+    float *p = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void *q = nullptr;
+        if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return DK_ERR_HIP;
+        p = static_cast<float *>(q);
+        scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return DK_OK;
+}
+
+} // namespace
+
+DK_EXPORT size_t dk_static_scratch_bytes(void) { return DK_STATIC_SCRATCH_BYTES; }
+
+DK_EXPORT dk_status dk_decode_verify_static(const float *ybar, const float *Ainv, const float *nvec,
+                                            float tol, float *y, int *verdict, float *resid, int G,
+                                            int K, long long m, void *stream)
+{
+    DK_REQUIRE(ybar && Ainv && nvec && y && verdict, DK_ERR_NULL);
+    dk_status s = check_mix_args(G, K, m);
+    if (s != DK_OK) return s;
+    DK_REQUIRE(tol >= 0.0f, DK_ERR_SHAPE);
+    DK_REQUIRE(dk_aligned(ybar, 4) && dk_aligned(Ainv, 4) && dk_aligned(nvec, 4) && dk_aligned(y, 4) &&
+                   dk_aligned(verdict, 4) && (!resid || dk_aligned(resid, 4)), DK_ERR_ALIGN);
+    DK_REQUIRE(G <= DK_STATIC_MAX_G && dk_ws_verify_bytes(G) <= DK_STATIC_SCRATCH_BYTES, DK_ERR_STATIC_LIMIT);
+    float *part = nullptr;
+    s = static_scratch(&part);
+    if (s != DK_OK) return s;
+    // every partial pair the second pass reads is written by the first pass of
+    // the same call, so nothing of the last call's contents has to be cleared
+    const bool v4 = can_vec4(m, {ybar, y});
+#define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, part, v4, K, (hipStream_t)stream)
+    DK_K_SWITCH(K, CALL)
 #undef CALL
 }

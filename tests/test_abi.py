@@ -55,7 +55,7 @@ def test_no_torch_or_oracle_in_the_library(dk):
 
 def test_status_strings(dk):
     assert dk.dk_status_str(0) == "ok"
-    assert len({dk.dk_status_str(i) for i in range(8)}) == 8
+    assert len({dk.dk_status_str(i) for i in range(9)}) == 9
 
 
 def test_null_and_shape_errors_before_launch(dk):
@@ -88,6 +88,11 @@ def test_null_and_shape_errors_before_launch(dk):
     assert lib.dk_wgrad(C.byref(lay), one, one, one, one, null, 1, 2, 1.0, 0, one, 1 << 20, null) == 1
     assert lib.dk_wgrad(C.byref(lay), one, one, one, one, one, 1, 2, 1.0, 0, one, 8, null) == 5
     assert lib.dk_wgrad(C.byref(lay), one, one, one, one, one, 1, 99, 1.0, 0, one, 1 << 20, null) == 2
+    # the entry point without a workspace: argument errors first, then its group limit
+    assert lib.dk_decode_verify_static(one, one, one, 1e-3, null, one, null, 1, 2, 8, null) == 1
+    assert lib.dk_decode_verify_static(one, one, one, 1e-3, one, one, null, 1, 0, 8, null) == 2
+    assert lib.dk_decode_verify_static(one, one, one, 1e-3, one, one, null, 4097, 2, 8, null) == 8
+    assert lib.dk_static_scratch_bytes() == 2 << 20
 
 
 def test_workspace_queries(dk):
