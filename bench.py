@@ -40,6 +40,13 @@ def workload(name):
         return dk_inputs.config1(), "config1: dense 256->512, K=2, 1 group"
     if name == "config2":
         return dk_inputs.config2(), "config2: conv3x3 s1 p1 64->64 @32x32 NCHW, batch 256, K=4 (G=64, 384 encoded rows)"
+    if name == "config2.ragged":
+        # rows of odd length (63 channels of 31x31 pixels): no row but the first of a tensor starts on a
+        # 16-byte boundary, so the mixing kernels move unaligned vectors and finish each row element-wise
+        rng = np.random.default_rng(22)
+        return (dk_inputs.masked_layer_inputs(rng, dk_inputs.conv(63, 63, 31, 31, 3), K=4, batch=256,
+                                              noise_std=10.0, delta_std=0.1),
+                "config2 with ragged rows: conv3x3 s1 p1 63->63 @31x31, batch 256, K=4")
     if name.startswith("config3."):
         i = int(name.split(".")[1])
         return dk_inputs.config3(index=i)[0], "config3 layer %d (VGG-16 conv stack @32x32, batch 128, K=4)" % i
@@ -240,6 +247,12 @@ def field_main(args):
                 with torch.cuda.graph(graph, stream=side):
                     step()
             torch.cuda.current_stream().wait_stream(side)
+        except Exception as e:                      # noqa: BLE001 - capture refused: time eager launches
+            sys.stderr.write("bench.py: HIP graph capture failed, timing eager launches (%s)\n" % e)
+            graph = None
+        torch.cuda.synchronize()
+        if graph:
+            # replays that differ from the eager results are an error, not a reason to fall back
             for _ in range(3):
                 for t in (y, dW):
                     t.zero_()
@@ -248,9 +261,6 @@ def field_main(args):
                 torch.cuda.synchronize()
                 if not all(torch.equal(a, b) for a, b in zip((y, dW, verdict), ref)):
                     raise RuntimeError("graph replay differs from the eager step")
-        except Exception as e:                      # noqa: BLE001 - fall back to eager launches
-            sys.stderr.write("bench.py: HIP graph not used (%s)\n" % e)
-            graph = None
         for _ in range(args.warmup):
             graph.replay() if graph else step()
         torch.cuda.synchronize()
@@ -348,9 +358,10 @@ def main():
     ap.add_argument("--fork", action="store_true",
                     help="capture the weight gradient on a second graph branch (it may then overlap the "
                          "forward chain; per-kernel profiler durations of overlapped kernels are inflated)")
-    ap.add_argument("--rotate", type=int, default=1,
-                    help="buffer sets the per-kernel pass cycles through, so that no kernel finds its inputs "
-                         "in the 256 MB last-level cache from the previous step (1 = reuse one set)")
+    ap.add_argument("--rotate", type=int, default=0,
+                    help="buffer sets every pass cycles through, so that no kernel finds the inputs of the "
+                         "step before in the 256 MB last-level cache (1 = reuse one set; default: as many "
+                         "sets, at least 3, as put 600 MB between two uses of a set)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="first run three plain 1 GiB device copies (a known-size reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -394,14 +405,19 @@ def aggregate(args, subs):
     multiplicities; the roofline record is that of the layer with the largest
     share of the time."""
     import copy
-    name, layers, total_ms, total_op, batch = args.workload, [], 0.0, 0.0, None
+    name, layers, total_ms, total_op, batch, total_floor = args.workload, [], 0.0, 0.0, None, 0.0
     for sub, count in subs:
         a = copy.copy(args)
         a.workload, a.no_cpu_baseline = sub, True
         o = field_main(a) if sub.startswith("field") else layer_main(a)
         op = o["value"] * 1e12 * o["ms_per_step"] * 1e-3
         layers.append({"workload": sub, "count": count, "ms_per_step": o["ms_per_step"], "value": o["value"],
-                       "roofline_kernel": o["roofline"]["kernel"], "roofline_frac": o["roofline"]["frac"]})
+                       "roofline_kernel": o["roofline"]["kernel"], "roofline_bound": o["roofline"]["bound"],
+                       "roofline_frac": o["roofline"]["frac"]})
+        if "roofline_floor_ms" in o:
+            layers[-1].update(roofline_floor_ms=o["roofline_floor_ms"], step_frac=o["step_frac"],
+                              step_bound=o["step_bound"])
+            total_floor += count * o["roofline_floor_ms"]
         total_ms += count * o["ms_per_step"]
         total_op += count * op
         batch = o["config"]["K"] * o["config"]["G"]
@@ -422,6 +438,9 @@ def aggregate(args, subs):
         "roofline": top["roofline"],
         "layers": layers,
     }
+    if total_floor > 0.0:
+        out["roofline_floor_ms"] = total_floor
+        out["step_frac"] = total_floor / total_ms
     if not args.no_cpu_baseline:
         a = copy.copy(args)
         a.workload = subs[0][0]
@@ -472,7 +491,17 @@ def layer_main(args):
             self.ws_wg = torch.empty(lib.dk_workspace_bytes_m(C.byref(dk.DkLayer.of(L)), dk.DK_OP_WGRAD, G, K, M), **u8)
             self.ws_vf = torch.empty(lib.dk_workspace_bytes_m(None, dk.DK_OP_VERIFY, G, K, M), **u8)
 
+    # Every pass below cycles through `--rotate` sets of the per-step tensors.
+    # Between two uses of a set the other sets push more than the last-level
+    # cache's 256 MB through it, so no kernel finds the inputs of the step
+    # before still cached -- as in training, where a layer's tensors come back
+    # after the rest of the network has run.  What one kernel of a step leaves
+    # behind for the next (the forward's output, read by decode + verify) stays:
+    # the path runs that way.  The weights are shared by all sets.
     b0 = Buffers()
+    one_set = sum(t.numel() * t.element_size() for t in vars(b0).values())
+    nsets = args.rotate if args.rotate >= 1 else int(min(16, max(3, -(-600e6 // one_set) + 1)))
+    sets = [b0] + [Buffers() for _ in range(nsets - 1)]
     y, dW, verdict = b0.y, b0.dW, b0.verdict
     conv = L.kind in ("conv", "dwconv")
 
@@ -509,75 +538,90 @@ def layer_main(args):
             dk.dk_wgrad_m(L, b.delta, B_d, gamma_d, b.xbar, K, M, dW=b.dW, scale=1.0, ws=b.ws_wg)
         if ev: ev[4].record()
 
-    for _ in range(args.warmup):
-        step()
+    for i in range(max(args.warmup, nsets)):
+        step(b=sets[i % nsets])
     torch.cuda.synchronize()
+    ref = [t.clone() for t in (y, dW, verdict)]
 
-    # Capture one step into a HIP graph (the library allocates nothing and never
-    # synchronises, so its launches can be recorded) and check a few replays
-    # against the eager results before trusting it.
-    graph = None
+    # Capture one step per buffer set into a HIP graph (the library allocates
+    # nothing and never synchronises, so its launches can be recorded).  Only a
+    # failure to capture falls back to eager launches; replays that differ from
+    # the eager results are an error.
+    graphs = None
     if not args.no_graph:
-        ref = [t.clone() for t in (y, dW, verdict)]
         try:
+            graphs = []
             side = torch.cuda.Stream()
             side.wait_stream(torch.cuda.current_stream())
             with torch.cuda.stream(side):
-                graph = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(graph, stream=side):
-                    step(fork=args.fork)
+                for b in sets:
+                    g_ = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g_, stream=side):
+                        step(fork=args.fork, b=b)
+                    graphs.append(g_)
             torch.cuda.current_stream().wait_stream(side)
-            for _ in range(3):
-                for t in (y, dW):
-                    t.zero_()
-                torch.cuda.synchronize()
-                graph.replay()
-                torch.cuda.synchronize()
-                if not all(torch.equal(a, b) for a, b in zip((y, dW, verdict), ref)):
-                    raise RuntimeError("graph replay differs from the eager step")
-        except Exception as e:                      # noqa: BLE001 - fall back to eager launches
-            sys.stderr.write("bench.py: HIP graph not used (%s)\n" % e)
-            graph = None
-        for _ in range(args.warmup):
-            graph.replay() if graph else step()
+        except Exception as e:                      # noqa: BLE001 - capture refused: time eager launches
+            sys.stderr.write("bench.py: HIP graph capture failed, timing eager launches (%s)\n" % e)
+            graphs = None
         torch.cuda.synchronize()
+        if graphs:
+            for rep in range(3):
+                for b, g_ in zip(sets, graphs):
+                    for t in (b.y, b.dW):
+                        t.zero_()
+                    torch.cuda.synchronize()
+                    g_.replay()
+                    torch.cuda.synchronize()
+                    if not all(torch.equal(a, c) for a, c in zip((b.y, b.dW, b.verdict), ref)):
+                        raise RuntimeError("graph replay %d differs from the eager step" % rep)
+            for i in range(args.warmup):
+                graphs[i % nsets].replay()
+            torch.cuda.synchronize()
 
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        graph.replay() if graph else step()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    def timed(nsteps, use_sets, use_graphs):
+        t0 = time.perf_counter()
+        for i in range(nsteps):
+            if use_graphs:
+                use_graphs[i % len(use_graphs)].replay()
+            else:
+                step(b=use_sets[i % len(use_sets)])
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / nsteps * 1e3
+
+    ms_per_step = timed(args.steps, sets, graphs)
+    # for context: the same steps on one buffer set (inputs of the step before still cached)
+    warm_ms_per_step = timed(args.steps, sets[:1], graphs[:1] if graphs else None) if nsets > 1 else ms_per_step
 
     # Eager pass with an event between the entry points (stage times).
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
     for i in range(args.steps):
-        step(events[i])
+        step(events[i], b=sets[i % nsets])
     torch.cuda.synchronize()
 
-    # Third pass over the same K steps with every kernel launch bracketed by HIP
+    # Pass over the same K steps with every kernel launch bracketed by HIP
     # events on its launch stream (the brackets cost a few microseconds per
-    # launch, so this pass is not the one `value` is taken from).  It cycles
-    # through several buffer sets: between two uses of a set, the other sets
-    # push more than the last-level cache's 256 MB through it, so a bandwidth
-    # figure from this pass is not flattered by data left over from the step
-    # before.  What one kernel of a step leaves behind for the next (the forward
-    # output read by decode+verify) stays: the path runs that way.
-    sets = [b0] + [Buffers() for _ in range(max(1, args.rotate) - 1)]
-    for b in sets[1:]:
-        step(b=b)
-    torch.cuda.synchronize()
+    # launch, so this pass is not the one `value` is taken from).
     dk.dk_profile_enable(True)
     for i in range(args.steps):
-        step(b=sets[i % len(sets)])
+        step(b=sets[i % nsets])
     torch.cuda.synchronize()
     dk.dk_profile_enable(False)
     kernels = dk.dk_profile_read()
+    # and a few launches on one set only, to report what warm inputs are worth
+    warm_kernels = kernels
+    if nsets > 1:
+        dk.dk_profile_enable(True)
+        for i in range(min(5, args.steps)):
+            step(b=b0)
+        torch.cuda.synchronize()
+        dk.dk_profile_enable(False)
+        warm_kernels = dk.dk_profile_read()
 
     for b in sets:
         assert int(b.verdict.sum().item()) == 0, "clean synthetic data must verify"
         assert torch.equal(b.dW, dW) and torch.equal(b.y, y), "buffer sets disagree"
     set_bytes = sum(t.numel() * t.element_size() for t in vars(b0).values())
-    ms_per_step = wall / args.steps * 1e3
+    graph = graphs
     stage_ms = {s: float(np.mean([e[i].elapsed_time(e[i + 1]) for e in events]))
                 for i, s in enumerate(stages)}
 
@@ -592,28 +636,34 @@ def layer_main(args):
                    if k.startswith(("conv_", "contract_", "dw_")) and v[1] == args.steps}
     dom = max(contraction, key=lambda k: contraction[k][0])
     dom_ms = contraction[dom][0]
+    dom_warm_ms = warm_kernels.get(dom, (dom_ms, 0))[0]
     dom_tflops = flop_fwd / (dom_ms * 1e-3) / 1e12
-    if L.kind == "dwconv":
-        # nine multiply-adds per element moved: the depthwise kernels are bandwidth-bound;
-        # each reads one tensor of the input size and reads or writes one of the output size
-        dw_bytes = 4.0 * G * S * (n + m)
-        gbps = dw_bytes / (dom_ms * 1e-3) / 1e9
+    # What a contraction must move at least: both operands read once, the result
+    # written once (forward: encodings, weights -> results; weight gradient:
+    # mixed gradients, encodings -> dW).  Where that takes longer at 8 TB/s than
+    # the FLOP at the matrix peak (few channels, 1x1 filters on large images,
+    # depthwise), the kernel's yardstick is HBM, not MFMA.
+    w_elems = float(np.prod(L.w_shape))
+    contr_bytes = 4.0 * (G * S * (n + m) + w_elems)
+    timed_note = ("HIP events around every launch of this kernel, %d eager launches after the timed region, "
+                  "cycling through %d buffer sets of %.0f MB (avg_launch_ms); warm_launch_ms: %d launches on "
+                  "one set" % (args.steps, nsets, set_bytes / 1e6, min(5, args.steps)))
+    if contr_bytes / HBM_PEAK_GBPS / 1e9 > flop_fwd / MFMA_F32_PEAK_TFLOPS / 1e12:
+        gbps = contr_bytes / (dom_ms * 1e-3) / 1e9
         roofline = {
             "kernel": dom, "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": gbps / HBM_PEAK_GBPS, "traffic": measured_traffic(args.workload, dom),
-            "avg_launch_ms": dom_ms, "bytes_per_launch": dw_bytes,
-            "timed": "HIP events around every launch of this kernel, %d eager launches after the timed region"
-                     % args.steps,
+            "avg_launch_ms": dom_ms, "warm_launch_ms": dom_warm_ms, "bytes_per_launch": contr_bytes,
+            "timed": timed_note,
         }
     else:
-      roofline = {
-        "kernel": dom, "bound": "mfma", "achieved": dom_tflops, "peak": MFMA_F32_PEAK_TFLOPS,
-        "unit": "TFLOP/s", "frac": dom_tflops / MFMA_F32_PEAK_TFLOPS,
-        "traffic": measured_traffic(args.workload, dom),
-        "avg_launch_ms": dom_ms, "flop_per_launch": flop_fwd,
-        "timed": "HIP events around every launch of this kernel, %d eager launches after the timed region, "
-                 "cycling through %d buffer sets of %.0f MB" % (args.steps, len(sets), set_bytes / 1e6),
-      }
+        roofline = {
+            "kernel": dom, "bound": "mfma", "achieved": dom_tflops, "peak": MFMA_F32_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": dom_tflops / MFMA_F32_PEAK_TFLOPS,
+            "traffic": measured_traffic(args.workload, dom),
+            "avg_launch_ms": dom_ms, "warm_launch_ms": dom_warm_ms, "flop_per_launch": flop_fwd,
+            "timed": timed_note,
+        }
     kname = {"encode": "encode_rng" if args.rng_noise else "encode", "decode_verify": "decode_verify",
              "delta_mix": "delta_mix"}
     if args.rng_noise:
@@ -624,6 +674,15 @@ def layer_main(args):
             ms = kernels[label][0]
             hbm[k] = {"GBps": ab[k] / (ms * 1e-3) / 1e9, "frac": ab[k] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                       "bytes": ab[k], "avg_launch_ms": ms}
+
+    # Floor of the whole step: every kernel at the roofline that bounds it --
+    # each contraction the longer of FLOP / matrix peak and bytes / HBM peak,
+    # each mixing kernel its algorithmic bytes / HBM peak.
+    contr_floor_ms = max(flop_fwd / MFMA_F32_PEAK_TFLOPS / 1e12, contr_bytes / HBM_PEAK_GBPS / 1e9) * 1e3
+    mix_floor_ms = sum(ab.values()) / HBM_PEAK_GBPS / 1e9 * 1e3
+    floor_ms = 2.0 * contr_floor_ms + mix_floor_ms
+    hbm_part_ms = mix_floor_ms + (2.0 * contr_floor_ms
+                                  if contr_bytes / HBM_PEAK_GBPS / 1e9 > flop_fwd / MFMA_F32_PEAK_TFLOPS / 1e12 else 0.0)
 
     out = {
         "metric": "masked-layer TFLOP/s (fwd+wgrad, executed on all K+2 encoded rows), whole hot path",
@@ -645,6 +704,12 @@ def layer_main(args):
         "roofline": roofline,
         "hbm_kernels": hbm,
         "kernel_ms": {k: v[0] for k, v in kernels.items()},
+        "kernel_ms_sum": float(sum(v[0] * v[1] for v in kernels.values()) / args.steps),
+        "warm_ms_per_step": warm_ms_per_step,
+        "roofline_floor_ms": floor_ms,
+        "step_frac": floor_ms / ms_per_step,
+        "step_bound": "hbm" if hbm_part_ms > 0.5 * floor_ms else "mfma",
+        "buffers": "%d sets of %.0f MB used in turn in every pass (timed region included)" % (nsets, set_bytes / 1e6),
     }
     if args.with_dgrad:
         dx = torch.empty((G * K,) + L.in_shape, **f32)

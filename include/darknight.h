@@ -45,7 +45,8 @@ typedef enum {
     DK_ERR_NULL = 1,        /* a required pointer is NULL                      */
     DK_ERR_SHAPE = 2,       /* a size is non-positive, too large or K invalid  */
     DK_ERR_UNSUPPORTED = 3, /* layer geometry the kernels do not cover         */
-    DK_ERR_ALIGN = 4,       /* a device pointer is not 4-byte aligned          */
+    DK_ERR_ALIGN = 4,       /* a device pointer is not 4-byte aligned (the
+                               integrity check's workspace: 16-byte)           */
     DK_ERR_WORKSPACE = 5,   /* workspace missing or smaller than required      */
     DK_ERR_HIP = 6,         /* the HIP runtime refused a launch                */
     DK_ERR_SINGULAR = 7,    /* dk_coeffs: A[g] is singular or gamma has a zero */
@@ -147,7 +148,11 @@ dk_status dk_decode(const float *ybar, const float *Ainv, float *y, int G,
  *                                     t or s is not finite)
  *   verdict[g] = 1 if resid[g] > tol or not finite, else 0.
  * ybar[G*S][m], nvec[G][S] (device) -> verdict[G] int32, resid[G] (device;
- * resid may be NULL).  ws: at least dk_workspace_bytes(NULL, DK_OP_VERIFY, G, K). */
+ * resid may be NULL).  ws: at least dk_workspace_bytes(NULL, DK_OP_VERIFY, G, K),
+ * 16-byte aligned, contents arbitrary: the workgroups that share a group
+ * publish their maxima there under a tag drawn for the call, and the one that
+ * finds all of them present writes the verdict, so the check is one launch.
+ * Calls that overlap in time need workspaces of their own. */
 dk_status dk_verify(const float *ybar, const float *nvec, float tol,
                     int *verdict, float *resid, int G, int K, long long m,
                     void *ws, size_t ws_bytes, void *stream);
@@ -164,8 +169,8 @@ dk_status dk_decode_verify(const float *ybar, const float *Ainv,
 /* dk_decode_verify for callers that cannot allocate device memory and so
  * have no workspace to pass: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  Same arguments (minus ws), same
- * kernels and bit-identical results; the partial maxima of the integrity
- * check go to an array of DK_STATIC_SCRATCH_BYTES bytes built into the
+ * kernels and bit-identical results; the per-workgroup maxima of the
+ * integrity check go to an array of DK_STATIC_SCRATCH_BYTES bytes built into the
  * library's device code (each GPU the library runs on holds it until the
  * process ends), whose address is looked up once per device on the first
  * call there.  The call allocates and frees nothing.
@@ -173,9 +178,9 @@ dk_status dk_decode_verify(const float *ybar, const float *Ainv,
  * launched.  All calls on one GPU share the array: calls that overlap there
  * (different streams, or graphs replayed concurrently) race on it and give
  * undefined verdicts; calls that follow each other on one stream are safe,
- * and nothing needs clearing between them (a call writes every slot before
- * it reads it). */
-#define DK_STATIC_SCRATCH_BYTES (2u << 20)
+ * and nothing needs clearing between them (a slot of the array counts only
+ * if it carries the call's own tag, and a call resets the tags it set). */
+#define DK_STATIC_SCRATCH_BYTES (4u << 20)
 #define DK_STATIC_MAX_G 4096
 dk_status dk_decode_verify_static(const float *ybar, const float *Ainv,
                                   const float *nvec, float tol, float *y,

@@ -4,12 +4,17 @@
 // one workgroup owns (group g, a contiguous span of the feature axis), the
 // group's coefficients sit at a wave-uniform address (scalar loads), each lane
 // moves 16-byte vectors, and every input row is read exactly once.
+// Two variants of every kernel: ALIGNED (all rows start on 16-byte boundaries
+// and the row length is a multiple of 4) and the general one, which moves the
+// same 16-byte vectors from 4-byte-aligned addresses -- global memory accesses
+// on this target need only element alignment -- and finishes the len % 4
+// elements at the end of a row one by one.
 #include "dk_internal.h"
 
 static int verify_max_chunks(int G);
 
 // Scratch memory of dk_decode_verify_static (the entry point for callers that
-// cannot allocate): the partial maxima of the integrity check live here instead
+// cannot allocate): the per-workgroup maxima of the integrity check live here instead
 // of in a caller's workspace.  Every GPU the library runs on holds its own copy
 // until the process ends.  In host code this name is only a handle for
 // hipGetSymbolAddress, never a device address.
@@ -21,15 +26,17 @@ constexpr int MIX_THREADS = 256;
 
 enum MixMode { MIX_ENCODE = 0, MIX_DECODE = 1, MIX_DMIX = 2 };
 
-template <int VEC> struct vec_t;
-template <> struct vec_t<4> { using type = float4; };
-template <> struct vec_t<1> { using type = float; };
+typedef float f4a __attribute__((ext_vector_type(4)));                 // 16-byte aligned
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));     // element aligned
 
-template <int VEC>
+// VEC = 4: one 16-byte access (AL: from a 16-byte boundary); VEC = 1: one float.
+template <int VEC, bool AL>
 __device__ __forceinline__ void vload(float (&dst)[VEC], const float *p)
 {
     if constexpr (VEC == 4) {
-        const float4 v = *reinterpret_cast<const float4 *>(p);
+        f4a v;
+        if constexpr (AL) v = *reinterpret_cast<const f4a *>(p);
+        else v = *reinterpret_cast<const f4u *>(p);
         dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
     } else {
         dst[0] = *p;
@@ -38,37 +45,37 @@ __device__ __forceinline__ void vload(float (&dst)[VEC], const float *p)
 
 // Streaming variants for data that is not touched again soon (the decoded
 // outputs; the encoded results once they have been decoded).
-template <int VEC>
+template <int VEC, bool AL>
 __device__ __forceinline__ void vload_nt(float (&dst)[VEC], const float *p)
 {
-    if constexpr (VEC == 4) {
-        typedef float f4 __attribute__((ext_vector_type(4)));
-        const f4 v = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p));
+    if constexpr (VEC == 4 && AL) {
+        const f4a v = __builtin_nontemporal_load(reinterpret_cast<const f4a *>(p));
         dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
     } else {
-        dst[0] = __builtin_nontemporal_load(p);
+        vload<VEC, AL>(dst, p);
     }
 }
 
-template <int VEC>
-__device__ __forceinline__ void vstore_nt(float *p, const float (&src)[VEC])
-{
-    if constexpr (VEC == 4) {
-        typedef float f4 __attribute__((ext_vector_type(4)));
-        f4 v = {src[0], src[1], src[2], src[3]};
-        __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(p));
-    } else {
-        __builtin_nontemporal_store(src[0], p);
-    }
-}
-
-template <int VEC>
+template <int VEC, bool AL>
 __device__ __forceinline__ void vstore(float *p, const float (&src)[VEC])
 {
     if constexpr (VEC == 4) {
-        *reinterpret_cast<float4 *>(p) = make_float4(src[0], src[1], src[2], src[3]);
+        const f4a v = {src[0], src[1], src[2], src[3]};
+        if constexpr (AL) *reinterpret_cast<f4a *>(p) = v;
+        else *reinterpret_cast<f4u *>(p) = v;
     } else {
         *p = src[0];
+    }
+}
+
+template <int VEC, bool AL>
+__device__ __forceinline__ void vstore_nt(float *p, const float (&src)[VEC])
+{
+    if constexpr (VEC == 4 && AL) {
+        const f4a v = {src[0], src[1], src[2], src[3]};
+        __builtin_nontemporal_store(v, reinterpret_cast<f4a *>(p));
+    } else {
+        vstore<VEC, AL>(p, src);
     }
 }
 
@@ -82,7 +89,7 @@ __device__ __forceinline__ void vstore(float *p, const float (&src)[VEC])
 // sources come from in0 and the others from in1, and only nk outputs are decoded
 // and nk gradients mixed.  FULL = true is the case nk = K with every test
 // compiled away.
-template <int MODE, int K, int VEC, bool FULL>
+template <int MODE, int K, bool AL, bool FULL>
 __global__ __launch_bounds__(MIX_THREADS) void mix_kernel(
     const float *__restrict__ in0, const float *__restrict__ in1,
     const float *__restrict__ c0, const float *__restrict__ c1,
@@ -123,14 +130,12 @@ __global__ __launch_bounds__(MIX_THREADS) void mix_kernel(
     }
     float *dst = out + (long long)g * (MODE == MIX_DECODE ? nk : NOUT) * len;
 
-    const long long v0 = (long long)chunk * span;
-    long long v1 = v0 + span;
-    if (v1 > nvec) v1 = nvec;
-    for (long long v = v0 + threadIdx.x; v < v1; v += MIX_THREADS) {
-        const long long e = v * VEC;
+    // one position of the feature axis: VEC elements starting at e
+    auto body = [&](auto vec_tag, long long e) {
+        constexpr int VEC = decltype(vec_tag)::value;
         float x[NIN][VEC];
 #pragma unroll
-        for (int i = 0; i < NIN; ++i) vload<VEC>(x[i], src[i] + e);
+        for (int i = 0; i < NIN; ++i) vload<VEC, AL>(x[i], src[i] + e);
 #pragma unroll
         for (int o = 0; o < NOUT; ++o) {
             if (!FULL && MODE == MIX_DECODE && o >= nk) continue;
@@ -141,8 +146,18 @@ __global__ __launch_bounds__(MIX_THREADS) void mix_kernel(
             for (int i = 1; i < NIN; ++i)
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) acc[c] = fmaf(coef[i][o], x[i][c], acc[c]);
-            vstore<VEC>(dst + (long long)o * len + e, acc);
+            vstore<VEC, AL>(dst + (long long)o * len + e, acc);
         }
+    };
+
+    const long long v0 = (long long)chunk * span;
+    long long v1 = v0 + span;
+    if (v1 > nvec) v1 = nvec;
+    for (long long v = v0 + threadIdx.x; v < v1; v += MIX_THREADS) body(std::integral_constant<int, 4>{}, v * 4);
+    if constexpr (!AL) {
+        // the len % 4 elements behind the last whole vector
+        const long long e = nvec * 4 + threadIdx.x;
+        if (chunk == chunks - 1 && e < len) body(std::integral_constant<int, 1>{}, e);
     }
 }
 
@@ -153,12 +168,120 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
-// Integrity check, first pass: each workgroup reduces its span of one group's
-// feature axis to (max |t|, max s) and writes the pair to part[g][chunk].
-template <int K, int VEC>
-__global__ __launch_bounds__(MIX_THREADS) void verify_partial_kernel(
-    const float *__restrict__ ybar, const float *__restrict__ nvec_,
-    float *__restrict__ part, long long len, long long nvec, int chunks, long long span)
+// ---- integrity check: per-workgroup maxima and the verdict, in one launch ----
+//
+// A group's feature axis is shared by `chunks` workgroups.  Each reduces its
+// span to (max |t|, max s) and publishes the pair in its slot of the workspace;
+// the workgroup that then finds every slot of its group published folds the
+// pairs and writes the verdict.  max is order independent, so the result does
+// not depend on which workgroup that is.
+//
+// A slot is two 64-bit words, (tag low half | bits of max |t|) and (tag high
+// half | bits of max s), where the tag is a 64-bit number the host draws per
+// call, never 0.  A word counts only if it carries this call's tag half, so
+//   * nothing has to be cleared beforehand, whatever the workspace held;
+//   * each word validates its own float: no ordering between different
+//     addresses is needed, hence no release fence -- on this chip a fence at
+//     device scope writes back every dirty line of the XCD's L2, which right
+//     behind the decoded outputs cost ten times the kernel itself.
+// The finishing workgroup resets the tags to 0, so a captured graph, whose
+// replays all carry the tag of the capture, starts every replay from clean
+// slots.  Publishing is an atomic exchange whose result is waited for: it
+// has then been performed at the device's point of coherence, and the loads
+// that follow are issued after it; of two workgroups of a group, at least the
+// one whose exchange came second therefore sees the other's words, so at
+// least one workgroup sees all of them.  If several do, they write the same
+// verdict.
+struct verify_slot {
+    unsigned long long t_word, s_word;
+};
+static_assert(sizeof(verify_slot) == 16, "slot layout");
+
+__device__ __forceinline__ unsigned long long verify_word(float v, unsigned tag_half)
+{
+    return ((unsigned long long)tag_half << 32) | __float_as_uint(v);
+}
+
+__device__ __forceinline__ void verify_publish_and_finish(
+    float tmax, float smax, bool bad, verify_slot *__restrict__ slots, int g, int chunk, int chunks,
+    unsigned long long tag, float tol, int *__restrict__ verdict, float *__restrict__ resid)
+{
+    if (bad) tmax = __builtin_inff();
+    __shared__ float red[2][MIX_THREADS / 64];
+    tmax = wave_max(tmax);
+    smax = wave_max(smax);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (lane == 0) { red[0][wave] = tmax; red[1][wave] = smax; }
+    __syncthreads();
+    if (wave != 0) return;
+    verify_slot *grp = slots + (long long)g * chunks;
+    const unsigned tag_lo = (unsigned)tag, tag_hi = (unsigned)(tag >> 32);
+    if (lane == 0) {
+#pragma unroll
+        for (int w = 1; w < MIX_THREADS / 64; ++w) {
+            tmax = fmaxf(tmax, red[0][w]);
+            smax = fmaxf(smax, red[1][w]);
+        }
+        const unsigned long long o0 = __hip_atomic_exchange(&grp[chunk].t_word, verify_word(tmax, tag_lo),
+                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long o1 = __hip_atomic_exchange(&grp[chunk].s_word, verify_word(smax, tag_hi),
+                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("" ::"v"(o0), "v"(o1));          // the returning form: completion can be waited for
+    }
+    // both exchanges have returned before any of the loads below is issued
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    bool all_here = true;
+    float t = 0.0f, sm = 0.0f;
+    for (int c = lane; c < chunks; c += 64) {
+        const unsigned long long w0 = __hip_atomic_load(&grp[c].t_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long w1 = __hip_atomic_load(&grp[c].s_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        all_here &= (unsigned)(w0 >> 32) == tag_lo && (unsigned)(w1 >> 32) == tag_hi;
+        t = fmaxf(t, __uint_as_float((unsigned)w0));
+        sm = fmaxf(sm, __uint_as_float((unsigned)w1));
+    }
+    if (!__all(all_here)) return;
+    // fmaxf drops a NaN operand; the publishers turn every non-finite case into +inf beforehand
+    t = wave_max(t);
+    sm = wave_max(sm);
+    for (int c = lane; c < chunks; c += 64) {
+        __hip_atomic_store(&grp[c].t_word, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&grp[c].s_word, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (lane != 0) return;
+    const bool nonfinite = !(t <= 3.402823466e+38f);
+    const float rho = nonfinite ? __builtin_inff() : (sm > 0.0f ? t / sm : 0.0f);
+    verdict[g] = (nonfinite || rho > tol) ? 1 : 0;
+    if (resid) resid[g] = rho;
+}
+
+// One position of the feature axis in the integrity sums: updates the running
+// maxima with VEC elements of t = sum_j n_j y_j and s = sum_j |n_j y_j|.
+template <int S, int VEC>
+__device__ __forceinline__ void verify_accumulate(const float (&nv)[S], const float (&x)[S][VEC],
+                                                  float &tmax, float &smax, bool &bad)
+{
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+        float t = 0.0f, sc = 0.0f;
+#pragma unroll
+        for (int j = 0; j < S; ++j) {
+            const float pr = nv[j] * x[j][c];
+            t += pr;
+            sc += fabsf(pr);
+        }
+        // a NaN or infinity anywhere makes s non-finite (or t, via inf-inf)
+        bad |= !(sc <= 3.402823466e+38f) || !(fabsf(t) <= 3.402823466e+38f);
+        tmax = fmaxf(tmax, fabsf(t));
+        smax = fmaxf(smax, sc);
+    }
+}
+
+// The integrity check alone.
+template <int K, bool AL>
+__global__ __launch_bounds__(MIX_THREADS) void verify_kernel(
+    const float *__restrict__ ybar, const float *__restrict__ nvec_, verify_slot *__restrict__ slots,
+    long long len, long long nvec, int chunks, long long span, unsigned long long tag, float tol,
+    int *__restrict__ verdict, float *__restrict__ resid)
 {
     constexpr int S = K + 2;
     const int g = blockIdx.x / chunks;
@@ -175,57 +298,33 @@ __global__ __launch_bounds__(MIX_THREADS) void verify_partial_kernel(
     long long v1 = v0 + span;
     if (v1 > nvec) v1 = nvec;
     for (long long v = v0 + threadIdx.x; v < v1; v += MIX_THREADS) {
-        const long long e = v * VEC;
-        float t[VEC], s[VEC];
+        float x[S][4];
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) { t[c] = 0.0f; s[c] = 0.0f; }
+        for (int j = 0; j < S; ++j) vload<4, AL>(x[j], src + (long long)j * len + v * 4);
+        verify_accumulate<S, 4>(nv, x, tmax, smax, bad);
+    }
+    if constexpr (!AL) {
+        const long long e = nvec * 4 + threadIdx.x;
+        if (chunk == chunks - 1 && e < len) {
+            float x[S][1];
 #pragma unroll
-        for (int j = 0; j < S; ++j) {
-            float y[VEC];
-            vload<VEC>(y, src + (long long)j * len + e);
-#pragma unroll
-            for (int c = 0; c < VEC; ++c) {
-                const float p = nv[j] * y[c];
-                t[c] += p;
-                s[c] += fabsf(p);
-            }
-        }
-#pragma unroll
-        for (int c = 0; c < VEC; ++c) {
-            // a NaN or infinity anywhere makes s non-finite (or t, via inf-inf)
-            bad |= !(s[c] <= 3.402823466e+38f) || !(fabsf(t[c]) <= 3.402823466e+38f);
-            tmax = fmaxf(tmax, fabsf(t[c]));
-            smax = fmaxf(smax, s[c]);
+            for (int j = 0; j < S; ++j) x[j][0] = src[(long long)j * len + e];
+            verify_accumulate<S, 1>(nv, x, tmax, smax, bad);
         }
     }
-    if (bad) tmax = __builtin_inff();
-
-    __shared__ float red[2][MIX_THREADS / 64];
-    tmax = wave_max(tmax);
-    smax = wave_max(smax);
-    const int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) { red[0][wave] = tmax; red[1][wave] = smax; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-#pragma unroll
-        for (int w = 1; w < MIX_THREADS / 64; ++w) {
-            tmax = fmaxf(tmax, red[0][w]);
-            smax = fmaxf(smax, red[1][w]);
-        }
-        part[((long long)g * chunks + chunk) * 2 + 0] = tmax;
-        part[((long long)g * chunks + chunk) * 2 + 1] = smax;
-    }
+    verify_publish_and_finish(tmax, smax, bad, slots, g, chunk, chunks, tag, tol, verdict, resid);
 }
 
-// Decode and the first pass of the integrity check in one sweep over ybar:
-// both need every encoded row of the group exactly once.
+// Decode and the integrity check in one sweep over ybar: both need every
+// encoded row of the group exactly once.
 // (FULL = false: only the first nk of the template's K columns are outputs,
 // see mix_kernel.)
-template <int K, int VEC, bool FULL>
+template <int K, bool AL, bool FULL>
 __global__ __launch_bounds__(MIX_THREADS) void decode_verify_kernel(
     const float *__restrict__ ybar, const float *__restrict__ Ainv, const float *__restrict__ nvec_,
-    float *__restrict__ y, float *__restrict__ part, long long len, long long nvec, int chunks,
-    long long span, int nk_rt)
+    float *__restrict__ y, verify_slot *__restrict__ slots, long long len, long long nvec, int chunks,
+    long long span, int nk_rt, unsigned long long tag, float tol, int *__restrict__ verdict,
+    float *__restrict__ resid)
 {
     constexpr int S = K + 2;
     const int nk = FULL ? K : nk_rt;
@@ -244,14 +343,11 @@ __global__ __launch_bounds__(MIX_THREADS) void decode_verify_kernel(
 
     float tmax = 0.0f, smax = 0.0f;
     bool bad = false;
-    const long long v0 = (long long)chunk * span;
-    long long v1 = v0 + span;
-    if (v1 > nvec) v1 = nvec;
-    for (long long v = v0 + threadIdx.x; v < v1; v += MIX_THREADS) {
-        const long long e = v * VEC;
+    auto body = [&](auto vec_tag, long long e) {
+        constexpr int VEC = decltype(vec_tag)::value;
         float x[S][VEC];
 #pragma unroll
-        for (int j = 0; j < S; ++j) vload_nt<VEC>(x[j], src + (long long)j * len + e);
+        for (int j = 0; j < S; ++j) vload_nt<VEC, AL>(x[j], src + (long long)j * len + e);
 #pragma unroll
         for (int i = 0; i < K; ++i) {
             if (!FULL && i >= nk) continue;
@@ -262,81 +358,43 @@ __global__ __launch_bounds__(MIX_THREADS) void decode_verify_kernel(
             for (int j = 1; j < S; ++j)
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) acc[c] = fmaf(coef[j][i], x[j][c], acc[c]);
-            vstore_nt<VEC>(dst + (long long)i * len + e, acc);
+            vstore_nt<VEC, AL>(dst + (long long)i * len + e, acc);
         }
-#pragma unroll
-        for (int c = 0; c < VEC; ++c) {
-            float t = 0.0f, sc = 0.0f;
-#pragma unroll
-            for (int j = 0; j < S; ++j) {
-                const float pr = nv[j] * x[j][c];
-                t += pr;
-                sc += fabsf(pr);
-            }
-            bad |= !(sc <= 3.402823466e+38f) || !(fabsf(t) <= 3.402823466e+38f);
-            tmax = fmaxf(tmax, fabsf(t));
-            smax = fmaxf(smax, sc);
-        }
+        verify_accumulate<S, VEC>(nv, x, tmax, smax, bad);
+    };
+    const long long v0 = (long long)chunk * span;
+    long long v1 = v0 + span;
+    if (v1 > nvec) v1 = nvec;
+    for (long long v = v0 + threadIdx.x; v < v1; v += MIX_THREADS) body(std::integral_constant<int, 4>{}, v * 4);
+    if constexpr (!AL) {
+        const long long e = nvec * 4 + threadIdx.x;
+        if (chunk == chunks - 1 && e < len) body(std::integral_constant<int, 1>{}, e);
     }
-    if (bad) tmax = __builtin_inff();
-
-    __shared__ float red[2][MIX_THREADS / 64];
-    tmax = wave_max(tmax);
-    smax = wave_max(smax);
-    const int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) { red[0][wave] = tmax; red[1][wave] = smax; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-#pragma unroll
-        for (int w = 1; w < MIX_THREADS / 64; ++w) {
-            tmax = fmaxf(tmax, red[0][w]);
-            smax = fmaxf(smax, red[1][w]);
-        }
-        part[((long long)g * chunks + chunk) * 2 + 0] = tmax;
-        part[((long long)g * chunks + chunk) * 2 + 1] = smax;
-    }
-}
-
-// Integrity check, second pass: one wave per group folds the (at most 64)
-// partial pairs -- lane c holds chunk c -- and lane 0 takes the verdict.
-__global__ __launch_bounds__(MIX_THREADS) void verify_final_kernel(
-    const float *__restrict__ part, int chunks, float tol, int *__restrict__ verdict,
-    float *__restrict__ resid, int G)
-{
-    const int g = blockIdx.x * (MIX_THREADS / 64) + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (g >= G) return;
-    float tmax = 0.0f, smax = 0.0f;
-    for (int c = lane; c < chunks; c += 64) {
-        tmax = fmaxf(tmax, part[((long long)g * chunks + c) * 2 + 0]);
-        smax = fmaxf(smax, part[((long long)g * chunks + c) * 2 + 1]);
-    }
-    tmax = wave_max(tmax);
-    smax = wave_max(smax);
-    if (lane != 0) return;
-    const bool bad = !(tmax <= 3.402823466e+38f);
-    const float rho = bad ? __builtin_inff() : (smax > 0.0f ? tmax / smax : 0.0f);
-    verdict[g] = (bad || rho > tol) ? 1 : 0;
-    if (resid) resid[g] = rho;
+    verify_publish_and_finish(tmax, smax, bad, slots, g, chunk, chunks, tag, tol, verdict, resid);
 }
 
 struct span_plan {
-    long long nvec;   // vectors per row
+    long long nvec;   // whole 16-byte vectors per row (the len % 4 elements behind them go one by one)
     long long span;   // vectors per workgroup (multiple of MIX_THREADS)
     int chunks;       // workgroups per group
 };
 
-// Each lane moves `iters` vectors; spans shrink until the launch has a few
-// thousand workgroups (256 compute units, several resident groups each).
-span_plan plan_span(long long len, int vec, int G, int max_chunks)
+// Each lane moves `iters` vectors; spans shrink until the launch has
+// `min_blocks` workgroups: a few thousand for the plain mixing kernels (256
+// compute units, several resident groups each); a thousand for the kernels that
+// end with the integrity check's publish-and-look (two memory round trips per
+// workgroup, which a one-vector-per-lane workgroup cannot amortise: config 2
+// measured 0.0385 ms at 4096 workgroups, 0.030 ms at 1024).
+span_plan plan_span(long long len, int G, int max_chunks, long long min_blocks = 4096)
 {
     span_plan p;
-    p.nvec = len / vec;
+    p.nvec = len / 4;
     long long iters = 4;
-    while (iters > 1 && (long long)G * ((p.nvec + MIX_THREADS * iters - 1) / (MIX_THREADS * iters)) < 4096)
+    while (iters > 1 && (long long)G * ((p.nvec + MIX_THREADS * iters - 1) / (MIX_THREADS * iters)) < min_blocks)
         iters >>= 1;
     p.span = MIX_THREADS * iters;
     long long chunks = (p.nvec + p.span - 1) / p.span;
+    if (chunks < 1) chunks = 1;               // rows shorter than one vector: the tail only
     if (max_chunks > 0 && chunks > max_chunks) {
         chunks = max_chunks;
         p.span = ((p.nvec + chunks - 1) / chunks + MIX_THREADS - 1) / MIX_THREADS * MIX_THREADS;
@@ -346,7 +404,8 @@ span_plan plan_span(long long len, int vec, int G, int max_chunks)
     return p;
 }
 
-bool can_vec4(long long len, std::initializer_list<const void *> ptrs)
+// Rows of whole 16-byte vectors, all starting on 16-byte boundaries.
+bool aligned16(long long len, std::initializer_list<const void *> ptrs)
 {
     if (len % 4) return false;
     for (const void *p : ptrs)
@@ -354,21 +413,33 @@ bool can_vec4(long long len, std::initializer_list<const void *> ptrs)
     return true;
 }
 
+// The tag of one integrity-check call: distinct from every tag this process
+// drew before and never 0 (an odd multiple walked through a 64-bit mixer).
+unsigned long long next_verify_tag()
+{
+    static std::atomic<unsigned long long> counter{0x2207000830001ull};
+    unsigned long long z = counter.fetch_add(0x9e3779b97f4a7c15ull, std::memory_order_relaxed);
+    z = (z ^ (z >> 30)) * 0xbf58476d1ce4e5b9ull;
+    z = (z ^ (z >> 27)) * 0x94d049bb133111ebull;
+    z ^= z >> 31;
+    return z | 1ull;
+}
+
 template <int MODE, int K>
 dk_status launch_mix_k(const float *in0, const float *in1, const float *c0, const float *c1,
-                       float *out, int G, long long len, bool v4, int nk, hipStream_t st)
+                       float *out, int G, long long len, bool al, int nk, hipStream_t st)
 {
-    const span_plan p = plan_span(len, v4 ? 4 : 1, G, 0);
+    const span_plan p = plan_span(len, G, 0);
     const long long blocks = (long long)G * p.chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     dk_prof_scope ps(MODE == MIX_ENCODE ? "encode" : (MODE == MIX_DECODE ? "decode" : "delta_mix"), st);
-#define DK_MIX_LAUNCH(V, F)                                                                     \
-    mix_kernel<MODE, K, V, F><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(                \
+#define DK_MIX_LAUNCH(AL, F)                                                                    \
+    mix_kernel<MODE, K, AL, F><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(               \
         in0, in1, c0, c1, out, len, p.nvec, p.chunks, p.span, nk)
     if (nk == K) {
-        if (v4) DK_MIX_LAUNCH(4, true); else DK_MIX_LAUNCH(1, true);
+        if (al) DK_MIX_LAUNCH(true, true); else DK_MIX_LAUNCH(false, true);
     } else {
-        if (v4) DK_MIX_LAUNCH(4, false); else DK_MIX_LAUNCH(1, false);
+        if (al) DK_MIX_LAUNCH(true, false); else DK_MIX_LAUNCH(false, false);
     }
 #undef DK_MIX_LAUNCH
     return dk_launch_status();
@@ -389,60 +460,50 @@ dk_status launch_mix_k(const float *in0, const float *in1, const float *c0, cons
 // instantiated on KT = K + M - 1 (S = KT + 2 encodings).
 template <int MODE>
 dk_status launch_mix(const float *in0, const float *in1, const float *c0, const float *c1,
-                     float *out, int G, int K, int M, long long len, bool v4, hipStream_t st)
+                     float *out, int G, int K, int M, long long len, bool al, hipStream_t st)
 {
-#define CALL(KK) launch_mix_k<MODE, KK>(in0, in1, c0, c1, out, G, len, v4, K, st)
+#define CALL(KK) launch_mix_k<MODE, KK>(in0, in1, c0, c1, out, G, len, al, K, st)
     DK_K_SWITCH(K + M - 1, CALL)
 #undef CALL
 }
 
 template <int K>
 dk_status launch_verify_k(const float *ybar, const float *nvec, float tol, int *verdict,
-                          float *resid, int G, long long len, float *part, bool v4, hipStream_t st)
+                          float *resid, int G, long long len, verify_slot *slots, bool al, hipStream_t st)
 {
-    const span_plan p = plan_span(len, v4 ? 4 : 1, G, verify_max_chunks(G));
+    const span_plan p = plan_span(len, G, verify_max_chunks(G), 1024);
     const long long blocks = (long long)G * p.chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
-    {
-    dk_prof_scope ps("verify_partial", st);
-    if (v4)
-        verify_partial_kernel<K, 4><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
-            ybar, nvec, part, len, p.nvec, p.chunks, p.span);
+    const unsigned long long tag = next_verify_tag();
+    dk_prof_scope ps("verify", st);
+    if (al)
+        verify_kernel<K, true><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
+            ybar, nvec, slots, len, p.nvec, p.chunks, p.span, tag, tol, verdict, resid);
     else
-        verify_partial_kernel<K, 1><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
-            ybar, nvec, part, len, p.nvec, p.chunks, p.span);
-    }
-    DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
-    dk_prof_scope ps("verify_final", st);
-    verify_final_kernel<<<dim3((G + MIX_THREADS / 64 - 1) / (MIX_THREADS / 64)), dim3(MIX_THREADS), 0, st>>>(
-        part, p.chunks, tol, verdict, resid, G);
+        verify_kernel<K, false><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
+            ybar, nvec, slots, len, p.nvec, p.chunks, p.span, tag, tol, verdict, resid);
     return dk_launch_status();
 }
 
 template <int K>
 dk_status launch_decode_verify_k(const float *ybar, const float *Ainv, const float *nvec, float tol,
                                  float *y, int *verdict, float *resid, int G, long long len,
-                                 float *part, bool v4, int nk, hipStream_t st)
+                                 verify_slot *slots, bool al, int nk, hipStream_t st)
 {
-    const span_plan p = plan_span(len, v4 ? 4 : 1, G, verify_max_chunks(G));
+    const span_plan p = plan_span(len, G, verify_max_chunks(G), 1024);
     const long long blocks = (long long)G * p.chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
-    {
+    const unsigned long long tag = next_verify_tag();
     dk_prof_scope ps("decode_verify", st);
-#define DK_DV_LAUNCH(V, F)                                                                       \
-    decode_verify_kernel<K, V, F><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(            \
-        ybar, Ainv, nvec, y, part, len, p.nvec, p.chunks, p.span, nk)
+#define DK_DV_LAUNCH(AL, F)                                                                      \
+    decode_verify_kernel<K, AL, F><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(           \
+        ybar, Ainv, nvec, y, slots, len, p.nvec, p.chunks, p.span, nk, tag, tol, verdict, resid)
     if (nk == K) {
-        if (v4) DK_DV_LAUNCH(4, true); else DK_DV_LAUNCH(1, true);
+        if (al) DK_DV_LAUNCH(true, true); else DK_DV_LAUNCH(false, true);
     } else {
-        if (v4) DK_DV_LAUNCH(4, false); else DK_DV_LAUNCH(1, false);
+        if (al) DK_DV_LAUNCH(true, false); else DK_DV_LAUNCH(false, false);
     }
 #undef DK_DV_LAUNCH
-    }
-    DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
-    dk_prof_scope ps("verify_final", st);
-    verify_final_kernel<<<dim3((G + MIX_THREADS / 64 - 1) / (MIX_THREADS / 64)), dim3(MIX_THREADS), 0, st>>>(
-        part, p.chunks, tol, verdict, resid, G);
     return dk_launch_status();
 }
 
@@ -468,7 +529,7 @@ static int verify_max_chunks(int G)
 
 size_t dk_ws_verify_bytes(int G)
 {
-    return (size_t)G * verify_max_chunks(G) * 2 * sizeof(float);
+    return (size_t)G * verify_max_chunks(G) * 16;       // one verify_slot per (group, workgroup)
 }
 
 DK_EXPORT dk_status dk_encode(const float *x, const float *r, const float *A, float *xbar,
@@ -478,7 +539,7 @@ DK_EXPORT dk_status dk_encode(const float *x, const float *r, const float *A, fl
     dk_status s = check_mix_args(G, K, n);
     if (s != DK_OK) return s;
     DK_REQUIRE(dk_aligned(x, 4) && dk_aligned(r, 4) && dk_aligned(A, 4) && dk_aligned(xbar, 4), DK_ERR_ALIGN);
-    return launch_mix<MIX_ENCODE>(x, r, A, nullptr, xbar, G, K, 1, n, can_vec4(n, {x, r, xbar}),
+    return launch_mix<MIX_ENCODE>(x, r, A, nullptr, xbar, G, K, 1, n, aligned16(n, {x, r, xbar}),
                                   (hipStream_t)stream);
 }
 
@@ -490,7 +551,7 @@ DK_EXPORT dk_status dk_encode_m(const float *x, const float *r, const float *A, 
     dk_status s = check_mix_args(G, K + M - 1, n);
     if (s != DK_OK) return s;
     DK_REQUIRE(dk_aligned(x, 4) && dk_aligned(r, 4) && dk_aligned(A, 4) && dk_aligned(xbar, 4), DK_ERR_ALIGN);
-    return launch_mix<MIX_ENCODE>(x, r, A, nullptr, xbar, G, K, M, n, can_vec4(n, {x, r, xbar}),
+    return launch_mix<MIX_ENCODE>(x, r, A, nullptr, xbar, G, K, M, n, aligned16(n, {x, r, xbar}),
                                   (hipStream_t)stream);
 }
 
@@ -501,7 +562,7 @@ DK_EXPORT dk_status dk_decode(const float *ybar, const float *Ainv, float *y, in
     dk_status s = check_mix_args(G, K, m);
     if (s != DK_OK) return s;
     DK_REQUIRE(dk_aligned(ybar, 4) && dk_aligned(Ainv, 4) && dk_aligned(y, 4), DK_ERR_ALIGN);
-    return launch_mix<MIX_DECODE>(ybar, nullptr, Ainv, nullptr, y, G, K, 1, m, can_vec4(m, {ybar, y}),
+    return launch_mix<MIX_DECODE>(ybar, nullptr, Ainv, nullptr, y, G, K, 1, m, aligned16(m, {ybar, y}),
                                   (hipStream_t)stream);
 }
 
@@ -511,7 +572,7 @@ dk_status dk_delta_mix(const float *delta, const float *B, const float *gamma, f
                        int G, int K, int M, long long m, hipStream_t st)
 {
     return launch_mix<MIX_DMIX>(delta, nullptr, B, gamma, dtilde, G, K, M, m,
-                                can_vec4(m, {delta, dtilde}), st);
+                                aligned16(m, {delta, dtilde}), st);
 }
 
 DK_EXPORT dk_status dk_verify(const float *ybar, const float *nvec, float tol, int *verdict,
@@ -525,9 +586,9 @@ DK_EXPORT dk_status dk_verify(const float *ybar, const float *nvec, float tol, i
     DK_REQUIRE(dk_aligned(ybar, 4) && dk_aligned(nvec, 4) && dk_aligned(verdict, 4) &&
                    (!resid || dk_aligned(resid, 4)), DK_ERR_ALIGN);
     DK_REQUIRE(ws && ws_bytes >= dk_ws_verify_bytes(G), DK_ERR_WORKSPACE);
-    DK_REQUIRE(dk_aligned(ws, 4), DK_ERR_ALIGN);
-    const bool v4 = can_vec4(m, {ybar});
-#define CALL(KK) launch_verify_k<KK>(ybar, nvec, tol, verdict, resid, G, m, (float *)ws, v4, (hipStream_t)stream)
+    DK_REQUIRE(dk_aligned(ws, 16), DK_ERR_ALIGN);
+    const bool al = aligned16(m, {ybar});
+#define CALL(KK) launch_verify_k<KK>(ybar, nvec, tol, verdict, resid, G, m, (verify_slot *)ws, al, (hipStream_t)stream)
     DK_K_SWITCH(K, CALL)
 #undef CALL
 }
@@ -543,9 +604,9 @@ DK_EXPORT dk_status dk_decode_verify(const float *ybar, const float *Ainv, const
     DK_REQUIRE(dk_aligned(ybar, 4) && dk_aligned(Ainv, 4) && dk_aligned(nvec, 4) && dk_aligned(y, 4) &&
                    dk_aligned(verdict, 4) && (!resid || dk_aligned(resid, 4)), DK_ERR_ALIGN);
     DK_REQUIRE(ws && ws_bytes >= dk_ws_verify_bytes(G), DK_ERR_WORKSPACE);
-    DK_REQUIRE(dk_aligned(ws, 4), DK_ERR_ALIGN);
-    const bool v4 = can_vec4(m, {ybar, y});
-#define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, (float *)ws, v4, K, (hipStream_t)stream)
+    DK_REQUIRE(dk_aligned(ws, 16), DK_ERR_ALIGN);
+    const bool al = aligned16(m, {ybar, y});
+#define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, (verify_slot *)ws, al, K, (hipStream_t)stream)
     DK_K_SWITCH(K, CALL)
 #undef CALL
 }
@@ -562,9 +623,9 @@ DK_EXPORT dk_status dk_decode_verify_m(const float *ybar, const float *Ainv, con
     DK_REQUIRE(dk_aligned(ybar, 4) && dk_aligned(Ainv, 4) && dk_aligned(nvec, 4) && dk_aligned(y, 4) &&
                    dk_aligned(verdict, 4) && (!resid || dk_aligned(resid, 4)), DK_ERR_ALIGN);
     DK_REQUIRE(ws && ws_bytes >= dk_ws_verify_bytes(G), DK_ERR_WORKSPACE);
-    DK_REQUIRE(dk_aligned(ws, 4), DK_ERR_ALIGN);
-    const bool v4 = can_vec4(m, {ybar, y});
-#define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, (float *)ws, v4, K, (hipStream_t)stream)
+    DK_REQUIRE(dk_aligned(ws, 16), DK_ERR_ALIGN);
+    const bool al = aligned16(m, {ybar, y});
+#define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, (verify_slot *)ws, al, K, (hipStream_t)stream)
     DK_K_SWITCH(K + M - 1, CALL)
 #undef CALL
 }
@@ -572,20 +633,20 @@ DK_EXPORT dk_status dk_decode_verify_m(const float *ybar, const float *Ainv, con
 namespace {
 
 constexpr int MAX_DEVICES = 64;
-std::atomic<float *> scratch_ptr[MAX_DEVICES];       // device address of `scratch`, per device ordinal
+std::atomic<verify_slot *> scratch_ptr[MAX_DEVICES];       // device address of `scratch`, per device ordinal
 
 // The current device's copy of the scratch array.  Looked up once per device
 // (with that device current); no allocation, no stream operation.
-dk_status static_scratch(float **out)
+dk_status static_scratch(verify_slot **out)
 {
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return DK_ERR_HIP;
     DK_REQUIRE(dev >= 0 && dev < MAX_DEVICES, DK_ERR_UNSUPPORTED);
-    float *p = scratch_ptr[dev].load(std::memory_order_acquire);
+    verify_slot *p = scratch_ptr[dev].load(std::memory_order_acquire);
     if (!p) {
         void *q = nullptr;
         if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return DK_ERR_HIP;
-        p = static_cast<float *>(q);
+        p = static_cast<verify_slot *>(q);
         scratch_ptr[dev].store(p, std::memory_order_release);
     }
     *out = p;
@@ -607,13 +668,13 @@ DK_EXPORT dk_status dk_decode_verify_static(const float *ybar, const float *Ainv
     DK_REQUIRE(dk_aligned(ybar, 4) && dk_aligned(Ainv, 4) && dk_aligned(nvec, 4) && dk_aligned(y, 4) &&
                    dk_aligned(verdict, 4) && (!resid || dk_aligned(resid, 4)), DK_ERR_ALIGN);
     DK_REQUIRE(G <= DK_STATIC_MAX_G && dk_ws_verify_bytes(G) <= DK_STATIC_SCRATCH_BYTES, DK_ERR_STATIC_LIMIT);
-    float *part = nullptr;
+    verify_slot *part = nullptr;
     s = static_scratch(&part);
     if (s != DK_OK) return s;
-    // every partial pair the second pass reads is written by the first pass of
-    // the same call, so nothing of the last call's contents has to be cleared
-    const bool v4 = can_vec4(m, {ybar, y});
-#define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, part, v4, K, (hipStream_t)stream)
+    // a slot counts only with this call's tag and the finishing workgroup
+    // resets the tags, so nothing of the last call's contents has to be cleared
+    const bool al = aligned16(m, {ybar, y});
+#define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, part, al, K, (hipStream_t)stream)
     DK_K_SWITCH(K, CALL)
 #undef CALL
 }

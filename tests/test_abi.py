@@ -92,7 +92,7 @@ def test_null_and_shape_errors_before_launch(dk):
     assert lib.dk_decode_verify_static(one, one, one, 1e-3, null, one, null, 1, 2, 8, null) == 1
     assert lib.dk_decode_verify_static(one, one, one, 1e-3, one, one, null, 1, 0, 8, null) == 2
     assert lib.dk_decode_verify_static(one, one, one, 1e-3, one, one, null, 4097, 2, 8, null) == 8
-    assert lib.dk_static_scratch_bytes() == 2 << 20
+    assert lib.dk_static_scratch_bytes() == 4 << 20
 
 
 def test_workspace_queries(dk):

@@ -130,6 +130,41 @@ def test_verify_nonfinite_and_zero(dk):
     assert rho[0] == 0.0 and np.isinf(rho[1]) and np.isinf(rho[2]) and rho[3] == 0.0
 
 
+def test_verify_workspace_contents_do_not_matter(dk):
+    """The integrity check is one launch: workgroups publish their maxima in
+    the workspace under a tag drawn per call and the one that finds all slots
+    of its group tagged writes the verdict.  Whatever the workspace holds
+    beforehand -- garbage, or the slots of an earlier call with another
+    partition -- must not matter, and a call must leave it reusable."""
+    say("verify workspace: garbage, stale slots, reuse")
+    rng = np.random.default_rng(12)
+    cases = [(4, 3, 70000), (2, 64, 4100), (8, 2, 1003), (1, 200, 64), (4, 3, 70000)]
+    nbytes = max(dk.dk_workspace_bytes(None, dk.DK_OP_VERIFY, G, K) for K, G, _ in cases)
+    ws = torch.from_numpy(rng.integers(0, 256, nbytes, dtype=np.uint8)).cuda()
+    for rep, (K, G, n) in enumerate(cases):
+        S = K + 2
+        A, gamma = dk_inputs.sample_coeff_draws(rng, G, K)
+        Ainv, nvec, _ = dk.dk_coeffs(A, gamma)
+        X = rng.standard_normal((G * K, n)).astype(np.float32)
+        r = (10 * rng.standard_normal((G, n))).astype(np.float32)
+        ybar = oracle.encode(X, r, A).astype(np.float32)
+        expect = np.zeros(G, dtype=np.int32)
+        for g in range(rep % 2, G, 2):
+            j = int(np.argmax(np.abs(nvec[g])))
+            ybar[g * S + j, int(rng.integers(n))] += 0.5 * max(1.0, float(np.max(np.abs(ybar[g * S:(g + 1) * S]))))
+            expect[g] = 1
+        vref, rhoref = oracle.verify(ybar, nvec, 1e-3)
+        assert vref.tolist() == expect.tolist()
+        yd = dev(ybar)
+        for call in range(2):           # the same workspace twice in a row
+            v, rho = dk.dk_verify(yd, dev(nvec), K, tol=1e-3, ws=ws)
+            assert host(v).tolist() == vref.tolist(), (rep, call)
+            assert np.allclose(host(rho)[expect == 1], rhoref[expect == 1], rtol=1e-3)
+            y2, v2, rho2 = dk.dk_decode_verify(yd, dev(Ainv), dev(nvec), K, tol=1e-3, ws=ws)
+            assert host(v2).tolist() == vref.tolist(), (rep, call)
+            assert np.array_equal(host(rho2), host(rho))
+
+
 # ----------------------------------------------------------------------
 # contractions vs the plain definitions
 # ----------------------------------------------------------------------
