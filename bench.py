@@ -358,6 +358,17 @@ def main():
     ap.add_argument("--fork", action="store_true",
                     help="capture the weight gradient on a second graph branch (it may then overlap the "
                          "forward chain; per-kernel profiler durations of overlapped kernels are inflated)")
+    ap.add_argument("--fuse", choices=["never", "always", "auto"], default="auto",
+                    help="fused kernels for 1x1 convolutions (forward + decode + verify in one kernel through "
+                         "dk_conv_fwd_decode_verify; gradient mixing inside the weight gradient's loader): "
+                         "never, wherever eligible, or the library's own choice by layer shape")
+    ap.add_argument("--group-chunks", type=int, default=1, metavar="N",
+                    help="run encode -> forward -> decode+verify on N runs of virtual batches one after the "
+                         "other, so that a run's encoded results are still in the last-level cache when they "
+                         "are decoded (separate kernels only: implies --fuse never)")
+    ap.add_argument("--chunk-streams", type=int, default=1, choices=[1, 2],
+                    help="with --group-chunks: put the runs alternately on two streams (two branches of the "
+                         "captured graph), so that a run's encoding can overlap the previous run's forward")
     ap.add_argument("--rotate", type=int, default=0,
                     help="buffer sets every pass cycles through, so that no kernel finds the inputs of the "
                          "step before in the 256 MB last-level cache (1 = reuse one set; default: as many "
@@ -490,6 +501,17 @@ def layer_main(args):
             self.ws_fwd = torch.empty(lib.dk_fwd_workspace_bytes(C.byref(dk.DkLayer.of(L)), G * S), **u8)
             self.ws_wg = torch.empty(lib.dk_workspace_bytes_m(C.byref(dk.DkLayer.of(L)), dk.DK_OP_WGRAD, G, K, M), **u8)
             self.ws_vf = torch.empty(lib.dk_workspace_bytes_m(None, dk.DK_OP_VERIFY, G, K, M), **u8)
+            if args.group_chunks > 1:
+                # a run of virtual batches may need more forward workspace than the whole batch
+                # (other slicing of the contraction); one workspace pair per stream
+                nb = max(lib.dk_fwd_workspace_bytes(C.byref(dk.DkLayer.of(L)), (G * (c + 1) // args.group_chunks
+                                                                               - G * c // args.group_chunks) * S)
+                         for c in range(args.group_chunks))
+                self.ws_fwd = [torch.empty(max(nb, self.ws_fwd.numel()), **u8) for _ in range(args.chunk_streams)]
+                self.ws_vf = [torch.empty(self.ws_vf.numel(), **u8) for _ in range(args.chunk_streams)]
+            if one_call:
+                del self.ybar, self.ws_fwd, self.ws_vf
+                self.ws_fdv = torch.empty(dk.dk_conv_fwd_decode_verify_workspace_bytes(L, G, K), **u8)
 
     # Every pass below cycles through `--rotate` sets of the per-step tensors.
     # Between two uses of a set the other sets push more than the last-level
@@ -498,8 +520,16 @@ def layer_main(args):
     # after the rest of the network has run.  What one kernel of a step leaves
     # behind for the next (the forward's output, read by decode + verify) stays:
     # the path runs that way.  The weights are shared by all sets.
+    if args.group_chunks > 1:
+        args.fuse = "never"
+    fuse = {"never": dk.DK_FUSE_NEVER, "always": dk.DK_FUSE_ALWAYS, "auto": dk.DK_FUSE_AUTO}[args.fuse]
+    dk.dk_set_option(dk.DK_OPT_FUSE_FWD, fuse)
+    dk.dk_set_option(dk.DK_OPT_FUSE_WGRAD, fuse)
+    # one call for forward + decode + verify (the library fuses it where it can and may)
+    one_call = args.fuse != "never" and L.kind == "conv" and M == 1
     b0 = Buffers()
-    one_set = sum(t.numel() * t.element_size() for t in vars(b0).values())
+    one_set = sum(t.numel() * t.element_size() for v in vars(b0).values()
+                  for t in (v if isinstance(v, list) else [v]))
     nsets = args.rotate if args.rotate >= 1 else int(min(16, max(3, -(-600e6 // one_set) + 1)))
     sets = [b0] + [Buffers() for _ in range(nsets - 1)]
     y, dW, verdict = b0.y, b0.dW, b0.verdict
@@ -514,6 +544,34 @@ def layer_main(args):
         the forward chain but the encodings, so it goes on a second stream and
         the two branches of the captured graph may overlap."""
         cur = torch.cuda.current_stream()
+        if args.group_chunks > 1:
+            # virtual batches in runs: a run's encodings and results stay cached between its kernels
+            S_ = K + M + 1
+            two = args.chunk_streams == 2
+            if two:
+                side2.wait_stream(cur)
+            for c in range(args.group_chunks):
+                g0, g1 = G * c // args.group_chunks, G * (c + 1) // args.group_chunks
+                if g0 == g1:
+                    continue
+                si = c % 2 if two else 0
+                with torch.cuda.stream(side2 if si else cur):
+                    dk.dk_encode_m(b.X[g0 * K:g1 * K], b.r[g0 * M:g1 * M], A_d[g0:g1], K, M,
+                                   xbar=b.xbar[g0 * S_:g1 * S_])
+                    if conv:
+                        dk.dk_conv_fwd(L, W, b.xbar[g0 * S_:g1 * S_], ybar=b.ybar[g0 * S_:g1 * S_], ws=b.ws_fwd[si])
+                    else:
+                        dk.dk_linear_fwd(W, b.xbar[g0 * S_:g1 * S_], ybar=b.ybar[g0 * S_:g1 * S_], ws=b.ws_fwd[si])
+                    dk.dk_decode_verify_m(b.ybar[g0 * S_:g1 * S_], Ainv_d[g0:g1], nvec_d[g0:g1], K, M, tol=1e-3,
+                                          y=b.y[g0 * K:g1 * K], verdict=b.verdict[g0:g1], resid=b.resid[g0:g1],
+                                          ws=b.ws_vf[si])
+            if two:
+                cur.wait_stream(side2)
+            if ev:
+                for e_ in ev[:4]: e_.record()
+            dk.dk_wgrad_m(L, b.delta, B_d, gamma_d, b.xbar, K, M, dW=b.dW, scale=1.0, ws=b.ws_wg)
+            if ev: ev[4].record()
+            return
         if ev: ev[0].record()
         if args.rng_noise:
             dk.dk_encode_rng(b.X, A_d, K, M, 20220701, 10.0, xbar=b.xbar)
@@ -524,13 +582,18 @@ def layer_main(args):
             side2.wait_stream(cur)
             with torch.cuda.stream(side2):
                 dk.dk_wgrad_m(L, b.delta, B_d, gamma_d, b.xbar, K, M, dW=b.dW, scale=1.0, ws=b.ws_wg)
-        if conv:
-            dk.dk_conv_fwd(L, W, b.xbar, ybar=b.ybar, ws=b.ws_fwd)
+        if one_call:
+            if ev: ev[2].record()
+            dk.dk_conv_fwd_decode_verify(L, W, b.xbar, Ainv_d, nvec_d, K, tol=1e-3, y=b.y, verdict=b.verdict,
+                                         resid=b.resid, ws=b.ws_fdv)
         else:
-            dk.dk_linear_fwd(W, b.xbar, ybar=b.ybar, ws=b.ws_fwd)
-        if ev: ev[2].record()
-        dk.dk_decode_verify_m(b.ybar, Ainv_d, nvec_d, K, M, tol=1e-3, y=b.y, verdict=b.verdict, resid=b.resid,
-                              ws=b.ws_vf)
+            if conv:
+                dk.dk_conv_fwd(L, W, b.xbar, ybar=b.ybar, ws=b.ws_fwd)
+            else:
+                dk.dk_linear_fwd(W, b.xbar, ybar=b.ybar, ws=b.ws_fwd)
+            if ev: ev[2].record()
+            dk.dk_decode_verify_m(b.ybar, Ainv_d, nvec_d, K, M, tol=1e-3, y=b.y, verdict=b.verdict, resid=b.resid,
+                                  ws=b.ws_vf)
         if ev: ev[3].record()
         if fork:
             cur.wait_stream(side2)
@@ -620,7 +683,8 @@ def layer_main(args):
     for b in sets:
         assert int(b.verdict.sum().item()) == 0, "clean synthetic data must verify"
         assert torch.equal(b.dW, dW) and torch.equal(b.y, y), "buffer sets disagree"
-    set_bytes = sum(t.numel() * t.element_size() for t in vars(b0).values())
+    set_bytes = sum(t.numel() * t.element_size() for v in vars(b0).values()
+                    for t in (v if isinstance(v, list) else [v]))
     graph = graphs
     stage_ms = {s: float(np.mean([e[i].elapsed_time(e[i + 1]) for e in events]))
                 for i, s in enumerate(stages)}
@@ -633,7 +697,8 @@ def layer_main(args):
     # Dominant kernel = the contraction kernel with the longest average launch
     # (forward and weight gradient execute the same FLOP count per launch).
     contraction = {k: v for k, v in kernels.items()
-                   if k.startswith(("conv_", "contract_", "dw_")) and v[1] == args.steps}
+                   if k.startswith(("conv_", "contract_", "dw_", "fused1x1_"))
+                   and v[1] in (args.steps, args.steps * args.group_chunks)}
     dom = max(contraction, key=lambda k: contraction[k][0])
     dom_ms = contraction[dom][0]
     dom_warm_ms = warm_kernels.get(dom, (dom_ms, 0))[0]
@@ -678,11 +743,22 @@ def layer_main(args):
     # Floor of the whole step: every kernel at the roofline that bounds it --
     # each contraction the longer of FLOP / matrix peak and bytes / HBM peak,
     # each mixing kernel its algorithmic bytes / HBM peak.
-    contr_floor_ms = max(flop_fwd / MFMA_F32_PEAK_TFLOPS / 1e12, contr_bytes / HBM_PEAK_GBPS / 1e9) * 1e3
-    mix_floor_ms = sum(ab.values()) / HBM_PEAK_GBPS / 1e9 * 1e3
-    floor_ms = 2.0 * contr_floor_ms + mix_floor_ms
-    hbm_part_ms = mix_floor_ms + (2.0 * contr_floor_ms
-                                  if contr_bytes / HBM_PEAK_GBPS / 1e9 > flop_fwd / MFMA_F32_PEAK_TFLOPS / 1e12 else 0.0)
+    # Where a fused kernel ran, its floor takes the place of the two it replaces:
+    # forward + decode + verify reads the encodings and writes the K decoded rows;
+    # the weight gradient with the mixing in its loader reads the K gradients.
+    flop_ms = flop_fwd / MFMA_F32_PEAK_TFLOPS / 1e12 * 1e3
+    hbm_ms = lambda nbytes: nbytes / HBM_PEAK_GBPS / 1e9 * 1e3
+    fwd_bytes, wg_bytes, mix_bytes = contr_bytes, contr_bytes, dict(ab)
+    if "fused1x1_fwd_decode_verify" in kernels:
+        fwd_bytes = 4.0 * (G * S * n + w_elems + G * K * m)
+        mix_bytes.pop("decode_verify")
+    if "fused1x1_wgrad" in kernels:
+        wg_bytes = 4.0 * (G * K * m + G * S * n + w_elems)
+        mix_bytes.pop("delta_mix")
+    mix_floor_ms = hbm_ms(sum(mix_bytes.values()))
+    floor_ms = max(flop_ms, hbm_ms(fwd_bytes)) + max(flop_ms, hbm_ms(wg_bytes)) + mix_floor_ms
+    hbm_part_ms = (mix_floor_ms + (hbm_ms(fwd_bytes) if hbm_ms(fwd_bytes) > flop_ms else 0.0)
+                   + (hbm_ms(wg_bytes) if hbm_ms(wg_bytes) > flop_ms else 0.0))
 
     out = {
         "metric": "masked-layer TFLOP/s (fwd+wgrad, executed on all K+2 encoded rows), whole hot path",
@@ -697,6 +773,8 @@ def layer_main(args):
         "decoded_samples_per_s": G * K / (ms_per_step * 1e-3),
         "decoded_samples_per_s_fwd_only": G * K / ((stage_ms["encode"] + stage_ms["fwd"]
                                                     + stage_ms["decode_verify"]) * 1e-3),
+        "stage_note": ("fwd = 0, decode_verify = forward + decode + verify in one call"
+                       if one_call else "one entry point per stage"),
         "effective_tflops": tflops * K / S,
         "stage_ms": stage_ms,
         "fwd_stage_tflops": flop_fwd / (stage_ms["fwd"] * 1e-3) / 1e12,

@@ -166,6 +166,44 @@ dk_status dk_decode_verify(const float *ybar, const float *Ainv,
                            long long m, void *ws, size_t ws_bytes,
                            void *stream);
 
+/* ------------------------------------------------------------------------
+ * Fused forms (the paper's pipelined mode keeps the encodings of the forward
+ * pass for the backward pass and overlaps the trusted side's work with the
+ * accelerators'; on one GPU the counterpart is to stop round trips through
+ * memory between the mixing steps and the bilinear operation).
+ * ------------------------------------------------------------------------ */
+
+/* dk_conv_fwd followed by dk_decode_verify as one call:
+ *   ybar = <W, xbar> on all G*(K+2) encoded images, y = first K columns of
+ *   ybar A^{-1}, verdict/resid as in dk_verify.
+ * For 1x1 filters with stride 1 and no padding and K in {2, 4, 8} the encoded
+ * results never reach memory: a workgroup runs a virtual batch's K+2 products
+ * one after the other and folds each result tile into the decoded tiles and
+ * the integrity sums it keeps in registers.  Every other layer runs the two
+ * steps one after the other with ybar in the workspace.
+ * W, xbar[G*(K+2)] images, Ainv[G][S][S], nvec[G][S] (device) -> y[G*K] images,
+ * verdict[G], resid[G] (device; resid may be NULL).
+ * ws: dk_conv_fwd_decode_verify_workspace_bytes(L, G, K), 256-byte aligned,
+ * contents arbitrary. */
+dk_status dk_conv_fwd_decode_verify(const dk_layer *L, const float *W, const float *xbar,
+                                    const float *Ainv, const float *nvec, float tol, float *y,
+                                    int *verdict, float *resid, int G, int K, void *ws,
+                                    size_t ws_bytes, void *stream);
+size_t dk_conv_fwd_decode_verify_workspace_bytes(const dk_layer *L, int G, int K);
+
+/* Switches between the fused and the separate kernels where both exist.
+ *   DK_OPT_FUSE_FWD    dk_conv_fwd_decode_verify on eligible 1x1 layers;
+ *   DK_OPT_FUSE_WGRAD  dk_wgrad on 1x1 stride-1 layers (K in {2, 4, 8}, images
+ *                      of a multiple of 16 pixels, 16-byte aligned tensors):
+ *                      the gradient mixing runs inside the contraction's
+ *                      operand loader and dtilde is never written.
+ * value: DK_FUSE_NEVER, DK_FUSE_ALWAYS (whenever eligible) or DK_FUSE_AUTO
+ * (the library's own choice by layer shape; the default).  Process-wide. */
+enum { DK_OPT_FUSE_FWD = 0, DK_OPT_FUSE_WGRAD = 1, DK_OPT_COUNT = 2 };
+enum { DK_FUSE_NEVER = 0, DK_FUSE_ALWAYS = 1, DK_FUSE_AUTO = 2 };
+dk_status dk_set_option(int which, int value);
+int dk_get_option(int which);
+
 /* dk_decode_verify for callers that cannot allocate device memory and so
  * have no workspace to pass: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  Same arguments (minus ws), same

@@ -15,6 +15,8 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libdarknight.so")
 
 DK_OP_FWD, DK_OP_WGRAD, DK_OP_VERIFY = 0, 1, 2
+DK_OPT_FUSE_FWD, DK_OPT_FUSE_WGRAD = 0, 1
+DK_FUSE_NEVER, DK_FUSE_ALWAYS, DK_FUSE_AUTO = 0, 1, 2
 DK_MAX_K = 16
 
 _lib = None
@@ -74,6 +76,10 @@ def load():
         "dk_decode": (ip, [vp, vp, vp, ip, ip, ll, vp]),
         "dk_verify": (ip, [vp, vp, fl, vp, vp, ip, ip, ll, vp, sz, vp]),
         "dk_decode_verify": (ip, [vp, vp, vp, fl, vp, vp, vp, ip, ip, ll, vp, sz, vp]),
+        "dk_conv_fwd_decode_verify": (ip, [LP, vp, vp, vp, vp, fl, vp, vp, vp, ip, ip, vp, sz, vp]),
+        "dk_conv_fwd_decode_verify_workspace_bytes": (sz, [LP, ip, ip]),
+        "dk_set_option": (ip, [ip, ip]),
+        "dk_get_option": (ip, [ip]),
         "dk_decode_verify_static": (ip, [vp, vp, vp, fl, vp, vp, vp, ip, ip, ll, vp]),
         "dk_static_scratch_bytes": (sz, []),
         "dk_coeffs_m": (ip, [vp, vp, ip, ip, ip, vp, vp, vp]),
@@ -360,6 +366,52 @@ def dk_decode_verify(ybar, Ainv, nvec, K, tol=1e-3, y=None, verdict=None, resid=
                                    _ptr(resid), G, K, m, _ptr(ws), ws.numel(), _stream(stream)),
            "dk_decode_verify")
     return y, verdict, resid
+
+
+def dk_conv_fwd_decode_verify(layer, W, xbar, Ainv, nvec, K, tol=1e-3, y=None, verdict=None, resid=None,
+                              ws=None, stream=None):
+    """dk_conv_fwd + dk_decode_verify as one call: returns (y, verdict, resid)."""
+    torch = _torch()
+    lay = DkLayer.of(layer)
+    W, xbar, Ainv, nvec = _dev(W, "W"), _dev(xbar, "xbar"), _dev(Ainv, "Ainv"), _dev(nvec, "nvec")
+    G = Ainv.shape[0]
+    S = K + 2
+    n, m = dk_layer_in_len(lay), dk_layer_out_len(lay)
+    if n == 0:
+        raise DkError(2, "dk_conv_fwd_decode_verify")
+    if (Ainv.shape != (G, S, S) or nvec.shape != (G, S) or xbar.numel() != G * S * n
+            or W.numel() != int(np.prod(_wshape(lay)))):
+        raise ValueError("dk_conv_fwd_decode_verify: inconsistent shapes")
+    if y is None:
+        Ho = (lay.H + 2 * lay.pad - lay.kh) // lay.stride + 1
+        Wo = (lay.W + 2 * lay.pad - lay.kw) // lay.stride + 1
+        y = torch.empty((G * K, lay.Co, Ho, Wo), dtype=torch.float32, device=W.device)
+    _dev(y, "y")
+    if y.numel() != G * K * m:
+        raise ValueError("dk_conv_fwd_decode_verify: y has the wrong size")
+    if verdict is None:
+        verdict = torch.empty(G, dtype=torch.int32, device=W.device)
+    if resid is None:
+        resid = torch.empty(G, dtype=torch.float32, device=W.device)
+    if ws is None:
+        ws = _workspace(load().dk_conv_fwd_decode_verify_workspace_bytes(C.byref(lay), G, K), W, stream)
+    _check(load().dk_conv_fwd_decode_verify(C.byref(lay), _ptr(W), _ptr(xbar), _ptr(Ainv), _ptr(nvec),
+                                            float(tol), _ptr(y), _ptr(verdict), _ptr(resid), G, K, _ptr(ws),
+                                            ws.numel(), _stream(stream)), "dk_conv_fwd_decode_verify")
+    return y, verdict, resid
+
+
+def dk_conv_fwd_decode_verify_workspace_bytes(layer, G, K) -> int:
+    return int(load().dk_conv_fwd_decode_verify_workspace_bytes(C.byref(DkLayer.of(layer)), int(G), int(K)))
+
+
+def dk_set_option(which, value):
+    """DK_OPT_FUSE_FWD / DK_OPT_FUSE_WGRAD <- DK_FUSE_NEVER / DK_FUSE_ALWAYS / DK_FUSE_AUTO."""
+    _check(load().dk_set_option(int(which), int(value)), "dk_set_option")
+
+
+def dk_get_option(which) -> int:
+    return int(load().dk_get_option(int(which)))
 
 
 def dk_decode_verify_static(ybar, Ainv, nvec, K, y, verdict, resid=None, tol=1e-3, stream=None):

@@ -17,186 +17,7 @@
 
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-// Loader fast path.  Vector-ALU instructions of a wave that is fetching queue
-// behind the matrix instructions of the other waves on its SIMD, so the common
-// case -- a whole contraction step of an operand whose rows are whole 16-byte
-// vectors -- is fetched with buffer loads: the matrix is a scalar resource, the
-// step advances a scalar offset, and each lane keeps one precomputed byte
-// offset per vector (an offset past the resource's range for rows outside the
-// matrix, which then read as zero).  No address arithmetic, no predicates.
-constexpr int DK_RSRC_FLAGS = 0x00020000;         // raw buffer resource, gfx9 family
-constexpr unsigned DK_OOB = 0x80000000u;          // beyond any resource range used here
-constexpr long long DK_RSRC_MAX = 0x7fffffffll;   // largest operand (bytes) the fast path takes
-
-__device__ __forceinline__ float4 dk_buffer_load4(__amdgpu_buffer_rsrc_t rs, unsigned voff, unsigned soff)
-{
-    const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff, (int)soff, 0));
-    return make_float4(v.x, v.y, v.z, v.w);
-}
-
-template <int BM_, int BN_, int BK_, int WM_, int WN_>
-struct Cfg {
-    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
-    static constexpr int NT = 64 * WM * WN;          // threads per workgroup
-    static constexpr int TM = BM / WM / 32;          // 32x32 blocks per wave, rows
-    static constexpr int TN = BN / WN / 32;          // 32x32 blocks per wave, cols
-    static constexpr int LDA = BM + 4;               // LDS row pitch (floats)
-    static constexpr int LDB = BN + 4;
-    static constexpr int LDS_FLOATS = 2 * BK * (LDA + LDB);
-    // one contraction step of a wave: TM*TN MFMAs of 64 cycles per k pair, at about 2.1 GHz
-    static constexpr double STEP_US = TM * TN * (BK / 2) * 64 / 2100.0;
-    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 4 == 0, "tile shape");
-};
-
-// ---------------------------------------------------------------------------
-// Operand loaders.  Each fetches a BK x ROWS operand tile of contraction step
-// kt into registers (load) and later writes it k-major into LDS (store).
-// Elements outside the matrix read as zero.
-// ---------------------------------------------------------------------------
-
-struct MatParams {
-    const float *p;
-    long long ld;   // leading dimension (floats)
-    int rows;       // extent along the tile's row axis
-    int kdim;       // extent along the contraction axis
-};
-
-// Source stored [kdim][ld] with the tile's row axis contiguous.
-template <int ROWS, int BK, int NT, int LD, bool VEC>
-struct LoadKMajor {
-    using Params = MatParams;
-    static constexpr int PER_K = ROWS / 4;
-    static constexpr int N4 = BK * PER_K / NT;
-    static_assert(BK * PER_K % NT == 0, "tile/threads");
-    float4 st[N4];
-    const float *p; long long ld; int rows, kdim, row0, tid;
-    __amdgpu_buffer_rsrc_t rs; unsigned voff[N4]; bool fast;
-
-    __device__ __forceinline__ void init(const Params &a, int row0_, int tid_)
-    {
-        p = a.p; ld = a.ld; rows = a.rows; kdim = a.kdim; row0 = row0_; tid = tid_;
-        const long long bytes = (long long)a.kdim * a.ld * 4;
-        fast = VEC && bytes <= DK_RSRC_MAX;
-        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
-#pragma unroll
-        for (int e = 0; e < N4; ++e) {
-            const int idx = tid + e * NT;
-            const int kr = idx / PER_K, row = row0 + (idx % PER_K) * 4;
-            voff[e] = row + 3 < rows ? 4u * (unsigned)(kr * (int)ld + row) : DK_OOB;
-        }
-    }
-
-    __device__ __forceinline__ void load(int kt)
-    {
-        if (fast && (kt + 1) * BK <= kdim) {
-            const unsigned soff = 4u * (unsigned)(kt * BK) * (unsigned)ld;
-#pragma unroll
-            for (int e = 0; e < N4; ++e) st[e] = dk_buffer_load4(rs, voff[e], soff);
-            return;
-        }
-#pragma unroll
-        for (int e = 0; e < N4; ++e) {
-            const int idx = tid + e * NT;
-            const int kr = idx / PER_K, c4 = idx % PER_K;
-            const int k = kt * BK + kr, row = row0 + c4 * 4;
-            const float *s = p + (long long)k * ld + row;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (k < kdim) {
-                if (VEC && row + 3 < rows) {
-                    v = *reinterpret_cast<const float4 *>(s);
-                } else {
-                    if (row + 0 < rows) v.x = s[0];
-                    if (row + 1 < rows) v.y = s[1];
-                    if (row + 2 < rows) v.z = s[2];
-                    if (row + 3 < rows) v.w = s[3];
-                }
-            }
-            st[e] = v;
-        }
-    }
-
-    __device__ __forceinline__ void store(float *buf) const
-    {
-#pragma unroll
-        for (int e = 0; e < N4; ++e) {
-            const int idx = tid + e * NT;
-            const int kr = idx / PER_K, c4 = idx % PER_K;
-            *reinterpret_cast<float4 *>(buf + kr * LD + c4 * 4) = st[e];
-        }
-    }
-};
-
-// Source stored [rows][ld] with the contraction axis contiguous.
-template <int ROWS, int BK, int NT, int LD, bool VEC>
-struct LoadRowMajorK {
-    using Params = MatParams;
-    static constexpr int PER_ROW = BK / 4;
-    static constexpr int N4 = ROWS * PER_ROW / NT;
-    static_assert(ROWS * PER_ROW % NT == 0, "tile/threads");
-    float4 st[N4];
-    const float *p; long long ld; int rows, kdim, row0, tid;
-    __amdgpu_buffer_rsrc_t rs; unsigned voff[N4]; bool fast;
-
-    __device__ __forceinline__ void init(const Params &a, int row0_, int tid_)
-    {
-        p = a.p; ld = a.ld; rows = a.rows; kdim = a.kdim; row0 = row0_; tid = tid_;
-        const long long bytes = (long long)a.rows * a.ld * 4;
-        fast = VEC && bytes <= DK_RSRC_MAX;
-        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
-#pragma unroll
-        for (int e = 0; e < N4; ++e) {
-            const int idx = tid + e * NT;
-            const int r = row0 + idx / PER_ROW, kc = idx % PER_ROW;
-            voff[e] = r < rows ? 4u * (unsigned)(r * (int)ld + kc * 4) : DK_OOB;
-        }
-    }
-
-    __device__ __forceinline__ void load(int kt)
-    {
-        if (fast && (kt + 1) * BK <= kdim) {
-            const unsigned soff = 4u * (unsigned)(kt * BK);
-#pragma unroll
-            for (int e = 0; e < N4; ++e) st[e] = dk_buffer_load4(rs, voff[e], soff);
-            return;
-        }
-#pragma unroll
-        for (int e = 0; e < N4; ++e) {
-            const int idx = tid + e * NT;
-            const int row = idx / PER_ROW, kc = idx % PER_ROW;
-            const int k = kt * BK + kc * 4, r = row0 + row;
-            const float *s = p + (long long)r * ld + k;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (r < rows) {
-                if (VEC && k + 3 < kdim) {
-                    v = *reinterpret_cast<const float4 *>(s);
-                } else {
-                    if (k + 0 < kdim) v.x = s[0];
-                    if (k + 1 < kdim) v.y = s[1];
-                    if (k + 2 < kdim) v.z = s[2];
-                    if (k + 3 < kdim) v.w = s[3];
-                }
-            }
-            st[e] = v;
-        }
-    }
-
-    __device__ __forceinline__ void store(float *buf) const
-    {
-#pragma unroll
-        for (int e = 0; e < N4; ++e) {
-            const int idx = tid + e * NT;
-            const int row = idx / PER_ROW, kc = idx % PER_ROW;
-            float *d = buf + (kc * 4) * LD + row;
-            d[0 * LD] = st[e].x;
-            d[1 * LD] = st[e].y;
-            d[2 * LD] = st[e].z;
-            d[3 * LD] = st[e].w;
-        }
-    }
-};
+#include "dk_contract_tiles.h"
 
 struct ConvParams {
     const float *p;       // xbar[R][Ci][H][W] or dtilde[R][Co][Ho][Wo]
@@ -1244,6 +1065,8 @@ size_t dk_ws_wgrad_bytes(const dk_geom &g, long long R)
         dk_wgpatch_plan pl;
         for (int aligned = 0; aligned < 2; ++aligned)
             if (dk_patch_wgrad_plan(g, R, aligned != 0, &pl) && pl.part_bytes > part) part = pl.part_bytes;
+        const size_t fb = dk_fused1x1_wgrad_part_bytes(g, R);
+        if (fb > part) part = fb;
     }
     return align_up((size_t)R * g.m * sizeof(float), 256) + part;
 }
@@ -1329,6 +1152,83 @@ DK_EXPORT dk_status dk_conv_fwd(const dk_layer *L, const float *W, const float *
     return conv_fwd_impl(g, W, xbar, ybar, R, ws, ws_bytes, stream);
 }
 
+// Where the fused forms measured faster than the separate kernels (the twelve
+// 1x1 stride-1 shapes of ResNet-50 at K = 8, batch 64).
+// Weight gradient with the mixing in its loader: ahead on the 56x56 layers
+// (64->64: 0.060 ms against 0.073; 64->256: 0.148 / 0.184; 256->64: 0.119 /
+// 0.128; 256->128: 0.200 / 0.205), behind from 28x28 down (128->512: 0.133 /
+// 0.127; 512->128: 0.127 / 0.101): the mixed gradients saved are Co x pixels per
+// image, the K loads and multiply-adds per operand element are paid per step.
+static bool fused_wgrad_pays(const dk_geom &g, int K)
+{
+    (void)K;
+    return (long long)g.H * g.W >= 1600;
+}
+// Forward + decode + verify: one accumulator block per wave is all the K
+// decoded tiles leave room for, so the product itself runs at half the rate of
+// the 128x128 tiles; ahead only where the product is short (64 input channels:
+// 64->64 0.051 ms against 0.074, 64->256 0.185 / 0.195), behind from 128
+// channels on (128->512 @28x28 0.156 / 0.144, 256->64 @56x56 0.173 / 0.123).
+static bool fused_fwd_pays(const dk_geom &g, int K)
+{
+    (void)K;
+    return g.Ci <= 64;
+}
+
+// Layout of the workspace of dk_conv_fwd_decode_verify when the two steps run
+// one after the other: ybar, the forward's own workspace, the integrity slots.
+struct fwd_dv_ws {
+    size_t ybar, fwd, slots, total;
+};
+
+static fwd_dv_ws fwd_dv_layout(const dk_geom &g, int G, int K)
+{
+    const long long R = (long long)G * (K + 2);
+    fwd_dv_ws w;
+    w.ybar = align_up((size_t)R * g.m * sizeof(float), 256);
+    w.fwd = align_up(dk_ws_fwd_bytes(g, R), 256);
+    w.slots = align_up(dk_ws_verify_bytes(G), 256);
+    const size_t fused = dk_fused1x1_fwd_ok(g, K) ? align_up(dk_fused1x1_fwd_slot_bytes(g, G), 256) : 0;
+    w.total = w.ybar + w.fwd + w.slots;
+    if (fused > w.total) w.total = fused;
+    return w;
+}
+
+DK_EXPORT size_t dk_conv_fwd_decode_verify_workspace_bytes(const dk_layer *L, int G, int K)
+{
+    dk_geom g;
+    if (G < 1 || K < 1 || K > DK_MAX_K || dk_layer_geom(L, &g) != DK_OK || !g.conv) return 0;
+    return fwd_dv_layout(g, G, K).total;
+}
+
+DK_EXPORT dk_status dk_conv_fwd_decode_verify(const dk_layer *L, const float *W, const float *xbar,
+                                              const float *Ainv, const float *nvec, float tol, float *y,
+                                              int *verdict, float *resid, int G, int K, void *ws,
+                                              size_t ws_bytes, void *stream)
+{
+    DK_REQUIRE(L && W && xbar && Ainv && nvec && y && verdict, DK_ERR_NULL);
+    DK_REQUIRE(G >= 1 && K >= 1 && K <= DK_MAX_K && tol >= 0.0f, DK_ERR_SHAPE);
+    dk_geom g;
+    dk_status s = dk_layer_geom(L, &g);
+    if (s != DK_OK) return s;
+    DK_REQUIRE(g.conv, DK_ERR_UNSUPPORTED);
+    const long long R = (long long)G * (K + 2);
+    DK_REQUIRE(R * g.Ho * g.Wo < (1ll << 31) - 512, DK_ERR_SHAPE);
+    DK_REQUIRE(dk_aligned(W, 4) && dk_aligned(xbar, 4) && dk_aligned(Ainv, 4) && dk_aligned(nvec, 4) &&
+                   dk_aligned(y, 4) && dk_aligned(verdict, 4) && (!resid || dk_aligned(resid, 4)), DK_ERR_ALIGN);
+    const fwd_dv_ws w = fwd_dv_layout(g, G, K);
+    DK_REQUIRE(ws && ws_bytes >= w.total, DK_ERR_WORKSPACE);
+    DK_REQUIRE(dk_aligned(ws, 256), DK_ERR_ALIGN);
+    const int opt = dk_option(DK_OPT_FUSE_FWD);
+    if (opt != DK_FUSE_NEVER && dk_fused1x1_fwd_ok(g, K) && (opt == DK_FUSE_ALWAYS || fused_fwd_pays(g, K)))
+        return dk_fused1x1_fwd_run(g, W, xbar, Ainv, nvec, tol, y, verdict, resid, G, K, ws, (hipStream_t)stream);
+    float *ybar = (float *)ws;
+    s = conv_fwd_impl(g, W, xbar, ybar, (int)R, (char *)ws + w.ybar, w.fwd, stream);
+    if (s != DK_OK) return s;
+    return dk_decode_verify(ybar, Ainv, nvec, tol, y, verdict, resid, G, K, g.m, (char *)ws + w.ybar + w.fwd,
+                            w.slots, stream);
+}
+
 // dk_wgrad for K private inputs and M noise rows per group (S = K + M + 1).
 static dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *B, const float *gamma,
                             const float *xbar, float *dW, int G, int K, int M, float scale,
@@ -1352,6 +1252,11 @@ static dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *
     const size_t dt_bytes = align_up((size_t)R * g.m * sizeof(float), 256);
     float *part = (float *)((char *)ws + dt_bytes);
     const size_t part_bytes = ws_bytes - dt_bytes;
+
+    // 1x1 layers: the mixing can run inside the contraction's operand loader
+    if (dk_option(DK_OPT_FUSE_WGRAD) != DK_FUSE_NEVER && dk_fused1x1_wgrad_ok(g, G, K, M, delta, xbar) &&
+        (dk_option(DK_OPT_FUSE_WGRAD) == DK_FUSE_ALWAYS || fused_wgrad_pays(g, K)))
+        return dk_fused1x1_wgrad_run(g, delta, B, gamma, xbar, dW, G, K, scale, accumulate, part, part_bytes, st);
 
     s = dk_delta_mix(delta, B, gamma, dtilde, G, K, M, g.m, st);
     if (s != DK_OK) return s;

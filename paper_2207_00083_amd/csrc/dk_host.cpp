@@ -23,7 +23,26 @@ DK_EXPORT const char *dk_status_str(int s)
     }
 }
 
-DK_EXPORT int dk_version(void) { return 100; }
+DK_EXPORT int dk_version(void) { return 110; }
+
+namespace {
+std::atomic<int> g_options[DK_OPT_COUNT] = {{DK_FUSE_AUTO}, {DK_FUSE_AUTO}};
+}
+
+int dk_option(int which)
+{
+    return which >= 0 && which < DK_OPT_COUNT ? g_options[which].load(std::memory_order_relaxed) : 0;
+}
+
+DK_EXPORT dk_status dk_set_option(int which, int value)
+{
+    DK_REQUIRE(which >= 0 && which < DK_OPT_COUNT, DK_ERR_SHAPE);
+    DK_REQUIRE(value == DK_FUSE_NEVER || value == DK_FUSE_ALWAYS || value == DK_FUSE_AUTO, DK_ERR_SHAPE);
+    g_options[which].store(value, std::memory_order_relaxed);
+    return DK_OK;
+}
+
+DK_EXPORT int dk_get_option(int which) { return which >= 0 && which < DK_OPT_COUNT ? dk_option(which) : -1; }
 
 dk_status dk_layer_geom(const dk_layer *L, dk_geom *g)
 {

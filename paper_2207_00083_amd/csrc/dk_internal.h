@@ -84,6 +84,21 @@ dk_status dk_dw_dgrad_run(const dk_geom &g, const float *W, const float *delta, 
 dk_status dk_delta_mix(const float *delta, const float *B, const float *gamma, float *dtilde,
                        int G, int K, int M, long long m, hipStream_t st);
 
+// Fused kernels for 1x1 stride-1 convolutions.
+bool dk_fused1x1_wgrad_ok(const dk_geom &g, int G, int K, int M, const float *delta, const float *xbar);
+size_t dk_fused1x1_wgrad_part_bytes(const dk_geom &g, long long R);
+dk_status dk_fused1x1_wgrad_run(const dk_geom &g, const float *delta, const float *B, const float *gamma,
+                                const float *xbar, float *dW, int G, int K, float scale, int accumulate,
+                                float *part, size_t part_bytes, hipStream_t st);
+bool dk_fused1x1_fwd_ok(const dk_geom &g, int K);
+size_t dk_fused1x1_fwd_slot_bytes(const dk_geom &g, int G);
+dk_status dk_fused1x1_fwd_run(const dk_geom &g, const float *W, const float *xbar, const float *Ainv,
+                              const float *nvec, float tol, float *y, int *verdict, float *resid, int G,
+                              int K, void *slots, hipStream_t st);
+
+// Tuning switches (dk_set_option).
+int dk_option(int which);
+
 // Optional per-kernel timing (dk_profile_enable): while enabled, a scope object
 // brackets one kernel launch with two HIP events on the launch stream.
 struct dk_prof_scope {

@@ -10,6 +10,7 @@
 // on this target need only element alignment -- and finishes the len % 4
 // elements at the end of a row one by one.
 #include "dk_internal.h"
+#include "dk_verify_slots.h"
 
 static int verify_max_chunks(int G);
 
@@ -161,99 +162,6 @@ __global__ __launch_bounds__(MIX_THREADS) void mix_kernel(
     }
 }
 
-__device__ __forceinline__ float wave_max(float v)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-    return v;
-}
-
-// ---- integrity check: per-workgroup maxima and the verdict, in one launch ----
-//
-// A group's feature axis is shared by `chunks` workgroups.  Each reduces its
-// span to (max |t|, max s) and publishes the pair in its slot of the workspace;
-// the workgroup that then finds every slot of its group published folds the
-// pairs and writes the verdict.  max is order independent, so the result does
-// not depend on which workgroup that is.
-//
-// A slot is two 64-bit words, (tag low half | bits of max |t|) and (tag high
-// half | bits of max s), where the tag is a 64-bit number the host draws per
-// call, never 0.  A word counts only if it carries this call's tag half, so
-//   * nothing has to be cleared beforehand, whatever the workspace held;
-//   * each word validates its own float: no ordering between different
-//     addresses is needed, hence no release fence -- on this chip a fence at
-//     device scope writes back every dirty line of the XCD's L2, which right
-//     behind the decoded outputs cost ten times the kernel itself.
-// The finishing workgroup resets the tags to 0, so a captured graph, whose
-// replays all carry the tag of the capture, starts every replay from clean
-// slots.  Publishing is an atomic exchange whose result is waited for: it
-// has then been performed at the device's point of coherence, and the loads
-// that follow are issued after it; of two workgroups of a group, at least the
-// one whose exchange came second therefore sees the other's words, so at
-// least one workgroup sees all of them.  If several do, they write the same
-// verdict.
-struct verify_slot {
-    unsigned long long t_word, s_word;
-};
-static_assert(sizeof(verify_slot) == 16, "slot layout");
-
-__device__ __forceinline__ unsigned long long verify_word(float v, unsigned tag_half)
-{
-    return ((unsigned long long)tag_half << 32) | __float_as_uint(v);
-}
-
-__device__ __forceinline__ void verify_publish_and_finish(
-    float tmax, float smax, bool bad, verify_slot *__restrict__ slots, int g, int chunk, int chunks,
-    unsigned long long tag, float tol, int *__restrict__ verdict, float *__restrict__ resid)
-{
-    if (bad) tmax = __builtin_inff();
-    __shared__ float red[2][MIX_THREADS / 64];
-    tmax = wave_max(tmax);
-    smax = wave_max(smax);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    if (lane == 0) { red[0][wave] = tmax; red[1][wave] = smax; }
-    __syncthreads();
-    if (wave != 0) return;
-    verify_slot *grp = slots + (long long)g * chunks;
-    const unsigned tag_lo = (unsigned)tag, tag_hi = (unsigned)(tag >> 32);
-    if (lane == 0) {
-#pragma unroll
-        for (int w = 1; w < MIX_THREADS / 64; ++w) {
-            tmax = fmaxf(tmax, red[0][w]);
-            smax = fmaxf(smax, red[1][w]);
-        }
-        const unsigned long long o0 = __hip_atomic_exchange(&grp[chunk].t_word, verify_word(tmax, tag_lo),
-                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const unsigned long long o1 = __hip_atomic_exchange(&grp[chunk].s_word, verify_word(smax, tag_hi),
-                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("" ::"v"(o0), "v"(o1));          // the returning form: completion can be waited for
-    }
-    // both exchanges have returned before any of the loads below is issued
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    bool all_here = true;
-    float t = 0.0f, sm = 0.0f;
-    for (int c = lane; c < chunks; c += 64) {
-        const unsigned long long w0 = __hip_atomic_load(&grp[c].t_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const unsigned long long w1 = __hip_atomic_load(&grp[c].s_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        all_here &= (unsigned)(w0 >> 32) == tag_lo && (unsigned)(w1 >> 32) == tag_hi;
-        t = fmaxf(t, __uint_as_float((unsigned)w0));
-        sm = fmaxf(sm, __uint_as_float((unsigned)w1));
-    }
-    if (!__all(all_here)) return;
-    // fmaxf drops a NaN operand; the publishers turn every non-finite case into +inf beforehand
-    t = wave_max(t);
-    sm = wave_max(sm);
-    for (int c = lane; c < chunks; c += 64) {
-        __hip_atomic_store(&grp[c].t_word, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&grp[c].s_word, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    if (lane != 0) return;
-    const bool nonfinite = !(t <= 3.402823466e+38f);
-    const float rho = nonfinite ? __builtin_inff() : (sm > 0.0f ? t / sm : 0.0f);
-    verdict[g] = (nonfinite || rho > tol) ? 1 : 0;
-    if (resid) resid[g] = rho;
-}
-
 // One position of the feature axis in the integrity sums: updates the running
 // maxima with VEC elements of t = sum_j n_j y_j and s = sum_j |n_j y_j|.
 template <int S, int VEC>
@@ -279,7 +187,7 @@ __device__ __forceinline__ void verify_accumulate(const float (&nv)[S], const fl
 // The integrity check alone.
 template <int K, bool AL>
 __global__ __launch_bounds__(MIX_THREADS) void verify_kernel(
-    const float *__restrict__ ybar, const float *__restrict__ nvec_, verify_slot *__restrict__ slots,
+    const float *__restrict__ ybar, const float *__restrict__ nvec_, dk_verify_slot *__restrict__ slots,
     long long len, long long nvec, int chunks, long long span, unsigned long long tag, float tol,
     int *__restrict__ verdict, float *__restrict__ resid)
 {
@@ -312,7 +220,7 @@ __global__ __launch_bounds__(MIX_THREADS) void verify_kernel(
             verify_accumulate<S, 1>(nv, x, tmax, smax, bad);
         }
     }
-    verify_publish_and_finish(tmax, smax, bad, slots, g, chunk, chunks, tag, tol, verdict, resid);
+    dk_verify_publish_and_finish<MIX_THREADS>(tmax, smax, bad, slots, g, chunk, chunks, tag, tol, verdict, resid);
 }
 
 // Decode and the integrity check in one sweep over ybar: both need every
@@ -322,7 +230,7 @@ __global__ __launch_bounds__(MIX_THREADS) void verify_kernel(
 template <int K, bool AL, bool FULL>
 __global__ __launch_bounds__(MIX_THREADS) void decode_verify_kernel(
     const float *__restrict__ ybar, const float *__restrict__ Ainv, const float *__restrict__ nvec_,
-    float *__restrict__ y, verify_slot *__restrict__ slots, long long len, long long nvec, int chunks,
+    float *__restrict__ y, dk_verify_slot *__restrict__ slots, long long len, long long nvec, int chunks,
     long long span, int nk_rt, unsigned long long tag, float tol, int *__restrict__ verdict,
     float *__restrict__ resid)
 {
@@ -370,7 +278,7 @@ __global__ __launch_bounds__(MIX_THREADS) void decode_verify_kernel(
         const long long e = nvec * 4 + threadIdx.x;
         if (chunk == chunks - 1 && e < len) body(std::integral_constant<int, 1>{}, e);
     }
-    verify_publish_and_finish(tmax, smax, bad, slots, g, chunk, chunks, tag, tol, verdict, resid);
+    dk_verify_publish_and_finish<MIX_THREADS>(tmax, smax, bad, slots, g, chunk, chunks, tag, tol, verdict, resid);
 }
 
 struct span_plan {
@@ -404,6 +312,20 @@ span_plan plan_span(long long len, int G, int max_chunks, long long min_blocks =
     return p;
 }
 
+// The kernels that end with the integrity check.  With many virtual batches a
+// thousand workgroups of several vectors per lane amortise the in-kernel verdict
+// (two memory round trips per workgroup; config 2: 0.0385 ms at 4096 workgroups,
+// 0.030 ms at 1024, 0.034 ms with the verdict in a second launch).  With few
+// batches that would put hundreds of workgroups on one batch: then the spans
+// stay short (more, shorter workgroups balance better) and a second launch
+// takes the verdict.
+span_plan plan_verify_span(long long len, int G)
+{
+    span_plan p = plan_span(len, G, verify_max_chunks(G), 1024);
+    if (p.chunks > DK_VERIFY_INLINE_MAX_CHUNKS) p = plan_span(len, G, verify_max_chunks(G), 4096);
+    return p;
+}
+
 // Rows of whole 16-byte vectors, all starting on 16-byte boundaries.
 bool aligned16(long long len, std::initializer_list<const void *> ptrs)
 {
@@ -411,18 +333,6 @@ bool aligned16(long long len, std::initializer_list<const void *> ptrs)
     for (const void *p : ptrs)
         if (p && !dk_aligned(p, 16)) return false;
     return true;
-}
-
-// The tag of one integrity-check call: distinct from every tag this process
-// drew before and never 0 (an odd multiple walked through a 64-bit mixer).
-unsigned long long next_verify_tag()
-{
-    static std::atomic<unsigned long long> counter{0x2207000830001ull};
-    unsigned long long z = counter.fetch_add(0x9e3779b97f4a7c15ull, std::memory_order_relaxed);
-    z = (z ^ (z >> 30)) * 0xbf58476d1ce4e5b9ull;
-    z = (z ^ (z >> 27)) * 0x94d049bb133111ebull;
-    z ^= z >> 31;
-    return z | 1ull;
 }
 
 template <int MODE, int K>
@@ -469,31 +379,37 @@ dk_status launch_mix(const float *in0, const float *in1, const float *c0, const 
 
 template <int K>
 dk_status launch_verify_k(const float *ybar, const float *nvec, float tol, int *verdict,
-                          float *resid, int G, long long len, verify_slot *slots, bool al, hipStream_t st)
+                          float *resid, int G, long long len, dk_verify_slot *slots, bool al, hipStream_t st)
 {
-    const span_plan p = plan_span(len, G, verify_max_chunks(G), 1024);
+    const span_plan p = plan_verify_span(len, G);
     const long long blocks = (long long)G * p.chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
-    const unsigned long long tag = next_verify_tag();
-    dk_prof_scope ps("verify", st);
-    if (al)
-        verify_kernel<K, true><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
-            ybar, nvec, slots, len, p.nvec, p.chunks, p.span, tag, tol, verdict, resid);
-    else
-        verify_kernel<K, false><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
-            ybar, nvec, slots, len, p.nvec, p.chunks, p.span, tag, tol, verdict, resid);
-    return dk_launch_status();
+    const bool in_kernel = p.chunks <= DK_VERIFY_INLINE_MAX_CHUNKS;
+    const unsigned long long tag = in_kernel ? dk_next_verify_tag() : 0ull;
+    {
+        dk_prof_scope ps("verify", st);
+        if (al)
+            verify_kernel<K, true><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
+                ybar, nvec, slots, len, p.nvec, p.chunks, p.span, tag, tol, verdict, resid);
+        else
+            verify_kernel<K, false><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(
+                ybar, nvec, slots, len, p.nvec, p.chunks, p.span, tag, tol, verdict, resid);
+    }
+    DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+    return in_kernel ? DK_OK : dk_verify_finalize(slots, p.chunks, tol, verdict, resid, G, st);
 }
 
 template <int K>
 dk_status launch_decode_verify_k(const float *ybar, const float *Ainv, const float *nvec, float tol,
                                  float *y, int *verdict, float *resid, int G, long long len,
-                                 verify_slot *slots, bool al, int nk, hipStream_t st)
+                                 dk_verify_slot *slots, bool al, int nk, hipStream_t st)
 {
-    const span_plan p = plan_span(len, G, verify_max_chunks(G), 1024);
+    const span_plan p = plan_verify_span(len, G);
     const long long blocks = (long long)G * p.chunks;
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
-    const unsigned long long tag = next_verify_tag();
+    const bool in_kernel = p.chunks <= DK_VERIFY_INLINE_MAX_CHUNKS;
+    const unsigned long long tag = in_kernel ? dk_next_verify_tag() : 0ull;
+    {
     dk_prof_scope ps("decode_verify", st);
 #define DK_DV_LAUNCH(AL, F)                                                                      \
     decode_verify_kernel<K, AL, F><<<dim3((unsigned)blocks), dim3(MIX_THREADS), 0, st>>>(           \
@@ -504,7 +420,9 @@ dk_status launch_decode_verify_k(const float *ybar, const float *Ainv, const flo
         if (al) DK_DV_LAUNCH(true, false); else DK_DV_LAUNCH(false, false);
     }
 #undef DK_DV_LAUNCH
-    return dk_launch_status();
+    }
+    DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+    return in_kernel ? DK_OK : dk_verify_finalize(slots, p.chunks, tol, verdict, resid, G, st);
 }
 
 dk_status check_mix_args(int G, int K, long long len)
@@ -516,6 +434,52 @@ dk_status check_mix_args(int G, int K, long long len)
 }
 
 } // namespace
+
+// The tag of one integrity-check call: distinct from every tag this process
+// drew before and never 0 (an odd multiple walked through a 64-bit mixer).
+unsigned long long dk_next_verify_tag()
+{
+    static std::atomic<unsigned long long> counter{0x2207000830001ull};
+    unsigned long long z = counter.fetch_add(0x9e3779b97f4a7c15ull, std::memory_order_relaxed);
+    z = (z ^ (z >> 30)) * 0xbf58476d1ce4e5b9ull;
+    z = (z ^ (z >> 27)) * 0x94d049bb133111ebull;
+    z ^= z >> 31;
+    return z | 1ull;
+}
+
+namespace {
+// One wave per virtual batch folds the batch's slots -- lane c takes slots c,
+// c + 64, ... -- and lane 0 takes the verdict.
+__global__ __launch_bounds__(MIX_THREADS) void verify_final_kernel(
+    const dk_verify_slot *__restrict__ slots, int chunks, float tol, int *__restrict__ verdict,
+    float *__restrict__ resid, int G)
+{
+    const int g = blockIdx.x * (MIX_THREADS / 64) + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (g >= G) return;
+    float tmax = 0.0f, smax = 0.0f;
+    for (int c = lane; c < chunks; c += 64) {
+        tmax = fmaxf(tmax, __uint_as_float((unsigned)slots[(long long)g * chunks + c].t_word));
+        smax = fmaxf(smax, __uint_as_float((unsigned)slots[(long long)g * chunks + c].s_word));
+    }
+    tmax = dk_wave_max(tmax);
+    smax = dk_wave_max(smax);
+    if (lane != 0) return;
+    const bool bad = !(tmax <= 3.402823466e+38f);
+    const float rho = bad ? __builtin_inff() : (smax > 0.0f ? tmax / smax : 0.0f);
+    verdict[g] = (bad || rho > tol) ? 1 : 0;
+    if (resid) resid[g] = rho;
+}
+} // namespace
+
+dk_status dk_verify_finalize(const dk_verify_slot *slots, int chunks, float tol, int *verdict, float *resid,
+                             int G, hipStream_t st)
+{
+    dk_prof_scope ps("verify_final", st);
+    verify_final_kernel<<<dim3((G + MIX_THREADS / 64 - 1) / (MIX_THREADS / 64)), dim3(MIX_THREADS), 0, st>>>(
+        slots, chunks, tol, verdict, resid, G);
+    return dk_launch_status();
+}
 
 // Workgroups per group in the integrity check's first pass: 64 when there are
 // many groups, more when a few groups alone would leave most of the chip idle.
@@ -529,7 +493,7 @@ static int verify_max_chunks(int G)
 
 size_t dk_ws_verify_bytes(int G)
 {
-    return (size_t)G * verify_max_chunks(G) * 16;       // one verify_slot per (group, workgroup)
+    return (size_t)G * verify_max_chunks(G) * 16;       // one dk_verify_slot per (group, workgroup)
 }
 
 DK_EXPORT dk_status dk_encode(const float *x, const float *r, const float *A, float *xbar,
@@ -588,7 +552,7 @@ DK_EXPORT dk_status dk_verify(const float *ybar, const float *nvec, float tol, i
     DK_REQUIRE(ws && ws_bytes >= dk_ws_verify_bytes(G), DK_ERR_WORKSPACE);
     DK_REQUIRE(dk_aligned(ws, 16), DK_ERR_ALIGN);
     const bool al = aligned16(m, {ybar});
-#define CALL(KK) launch_verify_k<KK>(ybar, nvec, tol, verdict, resid, G, m, (verify_slot *)ws, al, (hipStream_t)stream)
+#define CALL(KK) launch_verify_k<KK>(ybar, nvec, tol, verdict, resid, G, m, (dk_verify_slot *)ws, al, (hipStream_t)stream)
     DK_K_SWITCH(K, CALL)
 #undef CALL
 }
@@ -606,7 +570,7 @@ DK_EXPORT dk_status dk_decode_verify(const float *ybar, const float *Ainv, const
     DK_REQUIRE(ws && ws_bytes >= dk_ws_verify_bytes(G), DK_ERR_WORKSPACE);
     DK_REQUIRE(dk_aligned(ws, 16), DK_ERR_ALIGN);
     const bool al = aligned16(m, {ybar, y});
-#define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, (verify_slot *)ws, al, K, (hipStream_t)stream)
+#define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, (dk_verify_slot *)ws, al, K, (hipStream_t)stream)
     DK_K_SWITCH(K, CALL)
 #undef CALL
 }
@@ -625,7 +589,7 @@ DK_EXPORT dk_status dk_decode_verify_m(const float *ybar, const float *Ainv, con
     DK_REQUIRE(ws && ws_bytes >= dk_ws_verify_bytes(G), DK_ERR_WORKSPACE);
     DK_REQUIRE(dk_aligned(ws, 16), DK_ERR_ALIGN);
     const bool al = aligned16(m, {ybar, y});
-#define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, (verify_slot *)ws, al, K, (hipStream_t)stream)
+#define CALL(KK) launch_decode_verify_k<KK>(ybar, Ainv, nvec, tol, y, verdict, resid, G, m, (dk_verify_slot *)ws, al, K, (hipStream_t)stream)
     DK_K_SWITCH(K + M - 1, CALL)
 #undef CALL
 }
@@ -633,20 +597,20 @@ DK_EXPORT dk_status dk_decode_verify_m(const float *ybar, const float *Ainv, con
 namespace {
 
 constexpr int MAX_DEVICES = 64;
-std::atomic<verify_slot *> scratch_ptr[MAX_DEVICES];       // device address of `scratch`, per device ordinal
+std::atomic<dk_verify_slot *> scratch_ptr[MAX_DEVICES];       // device address of `scratch`, per device ordinal
 
 // The current device's copy of the scratch array.  Looked up once per device
 // (with that device current); no allocation, no stream operation.
-dk_status static_scratch(verify_slot **out)
+dk_status static_scratch(dk_verify_slot **out)
 {
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return DK_ERR_HIP;
     DK_REQUIRE(dev >= 0 && dev < MAX_DEVICES, DK_ERR_UNSUPPORTED);
-    verify_slot *p = scratch_ptr[dev].load(std::memory_order_acquire);
+    dk_verify_slot *p = scratch_ptr[dev].load(std::memory_order_acquire);
     if (!p) {
         void *q = nullptr;
         if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return DK_ERR_HIP;
-        p = static_cast<verify_slot *>(q);
+        p = static_cast<dk_verify_slot *>(q);
         scratch_ptr[dev].store(p, std::memory_order_release);
     }
     *out = p;
@@ -668,7 +632,7 @@ DK_EXPORT dk_status dk_decode_verify_static(const float *ybar, const float *Ainv
     DK_REQUIRE(dk_aligned(ybar, 4) && dk_aligned(Ainv, 4) && dk_aligned(nvec, 4) && dk_aligned(y, 4) &&
                    dk_aligned(verdict, 4) && (!resid || dk_aligned(resid, 4)), DK_ERR_ALIGN);
     DK_REQUIRE(G <= DK_STATIC_MAX_G && dk_ws_verify_bytes(G) <= DK_STATIC_SCRATCH_BYTES, DK_ERR_STATIC_LIMIT);
-    verify_slot *part = nullptr;
+    dk_verify_slot *part = nullptr;
     s = static_scratch(&part);
     if (s != DK_OK) return s;
     // a slot counts only with this call's tag and the finishing workgroup
