@@ -199,6 +199,24 @@ def field_layer_inputs(rng, layer: Layer, K: int, batch: int, *, w_std=None,
     return dict(layer=layer, K=K, G=G, W=W, X=X, r=r, delta=delta, A=A, gamma=gamma, p=p)
 
 
+def field_collusion_layer_inputs(rng, layer: Layer, K: int, M: int, batch: int, *, w_std=None,
+                                 delta_std=0.1, p=FIELD_P):
+    """field_layer_inputs with M noise rows per group (r[G*M, ...]) and square
+    matrices of size S = K+M+1 over the field."""
+    if batch % K:
+        raise ValueError("batch must be a multiple of K")
+    G, S = batch // K, K + M + 1
+    if w_std is None:
+        w_std = float(np.sqrt(2.0 / layer.fan_in))
+    W = _normal(rng, layer.w_shape, w_std)
+    X = _normal(rng, (batch,) + layer.in_shape, 1.0)
+    r = rng.integers(0, p, size=(G * M,) + layer.in_shape, dtype=np.uint32)
+    delta = _normal(rng, (batch,) + layer.out_shape, delta_std)
+    A = rng.integers(0, p, size=(G, S, S), dtype=np.uint32)
+    gamma = rng.integers(1, p, size=(G, S), dtype=np.uint32)
+    return dict(layer=layer, K=K, M=M, G=G, W=W, X=X, r=r, delta=delta, A=A, gamma=gamma, p=p)
+
+
 def config5_field(seed=5, batch=1024, K=8, index=None):
     """The classifier shapes of config5 for the finite-field variant."""
     out = []

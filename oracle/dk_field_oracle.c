@@ -287,6 +287,81 @@ void orf_conv_wgrad_points(const fe *D, const fe *X, long R, long Ci, long H, lo
     }
 }
 
+/* ----------------------------------------------------------------------
+ * Several colluding accelerators over the field (section "Colluding GPUs",
+ * and the paragraph of "Privacy Guarantee" on it: M noise vectors uniform
+ * over F_p, A_2 of full rank): S = K + M + 1 encodings per group, sources are
+ * the K inputs, then the M noise vectors, then the phantom zero source.
+ * ---------------------------------------------------------------------- */
+
+/* xbar[gS+j] = sum_{i<K} A[g][i][j] xq[gK+i] + sum_{q<M} A[g][K+q][j] r[gM+q]. */
+void orf_encode_m(const fe *xq, const fe *r, const fe *A, fe *xbar,
+                  long G, long K, long M, long n, fe p)
+{
+    const long S = K + M + 1;
+#pragma omp parallel for schedule(static)
+    for (long g = 0; g < G; ++g)
+        for (long j = 0; j < S; ++j)
+            for (long e = 0; e < n; ++e) {
+                fe acc = 0;
+                for (long i = 0; i < K; ++i)
+                    acc = addmod(acc, mulmod(A[(g * S + i) * S + j], xq[(g * K + i) * n + e], p), p);
+                for (long q = 0; q < M; ++q)
+                    acc = addmod(acc, mulmod(A[(g * S + K + q) * S + j], r[(g * M + q) * n + e], p), p);
+                xbar[(g * S + j) * n + e] = acc;
+            }
+}
+
+/* yq[g*ncols+i] = sum_{j<S} Ainv[g][j][i] ybar[gS+j], i < ncols. */
+void orf_decode_s(const fe *ybar, const fe *Ainv, fe *yq, long G, long S, long m,
+                  long ncols, fe p)
+{
+#pragma omp parallel for schedule(static)
+    for (long g = 0; g < G; ++g)
+        for (long i = 0; i < ncols; ++i)
+            for (long e = 0; e < m; ++e) {
+                fe acc = 0;
+                for (long j = 0; j < S; ++j)
+                    acc = addmod(acc, mulmod(Ainv[(g * S + j) * S + i], ybar[(g * S + j) * m + e], p), p);
+                yq[(g * ncols + i) * m + e] = acc;
+            }
+}
+
+/* verdict[g] = 1 if sum_{j<S} nvec[g][j] ybar[gS+j] is non-zero anywhere or an
+ * entry of ybar is not a field element. */
+void orf_verify_s(const fe *ybar, const fe *nvec, int *verdict, long G, long S, long m, fe p)
+{
+#pragma omp parallel for schedule(static)
+    for (long g = 0; g < G; ++g) {
+        int bad = 0;
+        for (long e = 0; e < m; ++e) {
+            fe acc = 0;
+            for (long j = 0; j < S; ++j) {
+                const fe v = ybar[(g * S + j) * m + e];
+                if (v >= p) bad = 1;
+                acc = addmod(acc, mulmod(nvec[g * S + j], v % p, p), p);
+            }
+            if (acc != 0) bad = 1;
+        }
+        verdict[g] = bad;
+    }
+}
+
+/* dtilde[gS+j] = gamma[g][j] * sum_{i<K} B[g][j][i] dq[gK+i], j < S. */
+void orf_delta_mix_s(const fe *dq, const fe *B, const fe *gamma, fe *dtilde,
+                     long G, long K, long S, long m, fe p)
+{
+#pragma omp parallel for schedule(static)
+    for (long g = 0; g < G; ++g)
+        for (long j = 0; j < S; ++j)
+            for (long e = 0; e < m; ++e) {
+                fe acc = 0;
+                for (long i = 0; i < K; ++i)
+                    acc = addmod(acc, mulmod(B[(g * S + j) * K + i], dq[(g * K + i) * m + e], p), p);
+                dtilde[(g * S + j) * m + e] = mulmod(gamma[g * S + j], acc, p);
+            }
+}
+
 /* Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11), as in the
  * real-valued oracle. */
 static void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])

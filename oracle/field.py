@@ -310,6 +310,100 @@ def masked_dense_layer(W, X, r, delta, A, gamma, l=L_BITS, p=P):
 
 
 # ----------------------------------------------------------------------
+# Several colluding accelerators (section "Colluding GPUs" and the paragraph of
+# "Privacy Guarantee" on it): M noise vectors per group, uniform over F_p,
+# S = K + M + 1 encodings; rows of A are the K inputs (A_1), the M noise
+# vectors (A_2) and the phantom zero source.
+# ----------------------------------------------------------------------
+
+def coefficients_m(A, gamma, K, p=P):
+    """A[G,S,S], gamma[G,S], S = K+M+1 -> (Ainv[G,S,S], nvec[G,S], B[G,S,K]):
+    the first K columns of A^{-1} decode, the last must vanish, and
+    B[j][i] = Ainv[j][i] / gamma_j, so that B^T Gamma A = [I_K | 0] over the
+    K+M real sources (the section's relation)."""
+    A = np.asarray(A)
+    gamma = np.asarray(gamma)
+    G, S, _ = A.shape
+    assert S >= K + 2
+    Ainv = np.zeros((G, S, S), dtype=np.uint32)
+    nvec = np.zeros((G, S), dtype=np.uint32)
+    B = np.zeros((G, S, K), dtype=np.uint32)
+    for g in range(G):
+        inv = inv_mod_matrix(A[g].tolist(), p)
+        for j in range(S):
+            if int(gamma[g, j]) % p == 0:
+                raise ValueError("gamma must be non-zero")
+            gi = pow(int(gamma[g, j]), p - 2, p)
+            for i in range(S):
+                Ainv[g, j, i] = inv[j][i]
+            nvec[g, j] = inv[j][S - 1]
+            for i in range(K):
+                B[g, j, i] = inv[j][i] * gi % p
+    return Ainv, nvec, B
+
+
+def encode_m(xq, r, A, K, p=P):
+    xq, r, A = _u(xq), _u(r), _u(A)
+    G, S, _ = A.shape
+    M = S - K - 1
+    feat = xq.shape[1:]
+    n = int(np.prod(feat))
+    assert xq.shape[0] == G * K and r.shape[0] == G * M and M >= 1
+    out = np.empty((G * S,) + feat, dtype=np.uint32)
+    _L().orf_encode_m(_p(xq), _p(r), _p(A), _p(out), _l(G), _l(K), _l(M), _l(n), _fe(p))
+    return out
+
+
+def decode_m(ybar, Ainv, ncols, p=P):
+    ybar, Ainv = _u(ybar), _u(Ainv)
+    G, S, _ = Ainv.shape
+    feat = ybar.shape[1:]
+    m = int(np.prod(feat))
+    out = np.empty((G * ncols,) + feat, dtype=np.uint32)
+    _L().orf_decode_s(_p(ybar), _p(Ainv), _p(out), _l(G), _l(S), _l(m), _l(ncols), _fe(p))
+    return out
+
+
+def verify_m(ybar, nvec, p=P):
+    ybar, nvec = _u(ybar), _u(nvec)
+    G, S = nvec.shape
+    m = int(np.prod(ybar.shape[1:]))
+    verdict = np.zeros(G, dtype=np.int32)
+    _L().orf_verify_s(_p(ybar), _p(nvec), _p(verdict), _l(G), _l(S), _l(m), _fe(p))
+    return verdict
+
+
+def delta_mix_m(dq, B, gamma, p=P):
+    dq, B, gamma = _u(dq), _u(B), _u(gamma)
+    G, S, K = B.shape
+    feat = dq.shape[1:]
+    m = int(np.prod(feat))
+    out = np.empty((G * S,) + feat, dtype=np.uint32)
+    _L().orf_delta_mix_s(_p(dq), _p(B), _p(gamma), _p(out), _l(G), _l(K), _l(S), _l(m), _fe(p))
+    return out
+
+
+def masked_layer_m(W, X, r, delta, A, gamma, K, stride=1, pad=0, l=L_BITS, p=P):
+    """masked_layer with M = S - K - 1 noise vectors per group (r[G*M, ...]):
+    the same steps in the same order."""
+    Ainv, nvec, B = coefficients_m(A, gamma, K, p)
+    Wq, Xq = quantize(W, l, p), quantize(X, l, p)
+    Xbar = encode_m(Xq, r, A, K, p)
+    dense = np.ndim(W) == 2
+    Ybar = dense_fwd(Wq, Xbar, p) if dense else conv_fwd(Wq, Xbar, stride, pad, p)
+    verdict = verify_m(Ybar, nvec, p)
+    Yq = decode_m(Ybar, Ainv, K, p)
+    Y = dequantize(Yq, l, p)
+    Dq = quantize(delta, l, p)
+    Dtilde = delta_mix_m(Dq, B, gamma, p)
+    dWq = (dense_wgrad(Dtilde, Xbar, p) if dense
+           else conv_wgrad(Dtilde, Xbar, W.shape[2], W.shape[3], stride, pad, p))
+    dW = dequantize(dWq, l, p)
+    return dict(Wq=Wq, Xq=Xq, Xbar=Xbar, Ybar=Ybar, verdict=verdict, Yq=Yq, Y=Y, Dq=Dq,
+                Dtilde=Dtilde, dWq=dWq, dW=dW)
+
+
+# ----------------------------------------------------------------------
 # Dynamic normalisation ("Quantization", the variant for networks without
 # normalisation layers)
 # ----------------------------------------------------------------------
