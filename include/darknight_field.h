@@ -185,6 +185,40 @@ dk_status dkf_wgrad_norm(const dk_layer *L, const float *delta, const float *xsc
                          void *ws, size_t ws_bytes, void *stream);
 
 /* Workspace sizes in bytes (0 for invalid arguments). */
+/* ---- Several colluding accelerators over the field (section "Colluding
+ * GPUs"; "Privacy Guarantee", the paragraph on colluding accelerators: with M
+ * noise vectors uniform over F_p and A_2 of full rank, any M encodings are
+ * uniform whatever the inputs).  S = K + M + 1 encodings per group: A[g] is
+ * S x S over the field with rows A_1 (the K inputs), A_2 (the M noise vectors)
+ * and the phantom zero source; r[G*M][n].  Everything else as in the entry
+ * points above, which are the case M = 1; the forward entry points take
+ * R = G*S rows unchanged.  Requires K + M - 1 <= DK_MAX_K. ---- */
+
+/* dkf_coeffs for S = K+M+1: Ainv[G][S][S], nvec[G][S] (last column of Ainv),
+ * B[G][S][K] = Ainv[j][i] * gamma_j^{-1}.  Host pointers. */
+dk_status dkf_coeffs_m(const uint32_t *A, const uint32_t *gamma, int G, int K, int M,
+                       uint32_t *Ainv, uint32_t *nvec, uint32_t *B);
+
+/* xbar[gS+j] = sum_{i<K} A[g][i][j] Xq[gK+i] + sum_{q<M} A[g][K+q][j] r[gM+q]  mod p,
+ * Xq = Field(Round(x 2^l)).  x[G*K][n] float, r[G*M][n], A[G][S][S] ->
+ * xbar[G*S][n], all device. */
+dk_status dkf_encode_m(const float *x, const uint32_t *r, const uint32_t *A, uint32_t *xbar,
+                       int G, int K, int M, long long n, int l, void *stream);
+
+/* dkf_decode_verify for S = K+M+1: the first K columns of ybar A^{-1} are
+ * decoded (the M columns <W_q, r_q> are not produced), the verdict tests the
+ * combination nvec. */
+dk_status dkf_decode_verify_m(const uint32_t *ybar, const uint32_t *Ainv, const uint32_t *nvec,
+                              float *y, uint32_t *yq, int *verdict,
+                              int G, int K, int M, long long m, int l, void *stream);
+
+/* dkf_wgrad for S = K+M+1.  Workspace: dkf_wgrad_workspace_bytes_m(L, G, K, M). */
+dk_status dkf_wgrad_m(const dk_layer *L, const float *delta, const uint32_t *B,
+                      const uint32_t *gamma, const uint32_t *xbar, float *dW, uint32_t *dwq,
+                      int G, int K, int M, int l, float scale, int accumulate,
+                      void *ws, size_t ws_bytes, void *stream);
+size_t dkf_wgrad_workspace_bytes_m(const dk_layer *L, int G, int K, int M);
+
 size_t dkf_fwd_workspace_bytes(int M, int N, int R);
 size_t dkf_conv_fwd_workspace_bytes(const dk_layer *L, int R);
 size_t dkf_wgrad_workspace_bytes(const dk_layer *L, int G, int K);

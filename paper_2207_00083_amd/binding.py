@@ -108,6 +108,11 @@ def load():
         "dkf_decode_verify_norm": (ip, [vp, vp, vp, vp, vp, vp, vp, vp, ip, ip, ll, ip, vp]),
         "dkf_wgrad_norm": (ip, [LP, vp, vp, vp, vp, vp, vp, vp, ip, ip, ip, fl, ip, vp, sz, vp]),
         "dkf_conv_fwd_workspace_bytes": (sz, [LP, ip]),
+        "dkf_coeffs_m": (ip, [vp, vp, ip, ip, ip, vp, vp, vp]),
+        "dkf_encode_m": (ip, [vp, vp, vp, vp, ip, ip, ip, ll, ip, vp]),
+        "dkf_decode_verify_m": (ip, [vp, vp, vp, vp, vp, vp, ip, ip, ip, ll, ip, vp]),
+        "dkf_wgrad_m": (ip, [LP, vp, vp, vp, vp, vp, vp, ip, ip, ip, ip, fl, ip, vp, sz, vp]),
+        "dkf_wgrad_workspace_bytes_m": (sz, [LP, ip, ip, ip]),
         "dkf_fwd_workspace_bytes": (sz, [ip, ip, ip]),
         "dkf_wgrad_workspace_bytes": (sz, [LP, ip, ip]),
         "dk_profile_enable": (ip, [ip]),

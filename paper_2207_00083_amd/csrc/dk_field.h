@@ -6,9 +6,10 @@
 #include "darknight_field.h"
 
 // Gradient mixing over the field (launcher; used by dkf_wgrad).  xscale (one
-// normalisation factor per sample, device) may be null.
+// normalisation factor per sample, device) may be null.  K inputs and M noise rows
+// per group, S = K + M + 1.
 dk_status dkf_delta_mix(const float *delta, const float *xscale, const uint32_t *B,
-                        const uint32_t *gamma, uint32_t *dtilde, int G, int K, long long m, int l,
+                        const uint32_t *gamma, uint32_t *dtilde, int G, int K, int M, long long m, int l,
                         hipStream_t st);
 
 #ifdef __HIPCC__

@@ -134,23 +134,30 @@ __global__ __launch_bounds__(FT) void dequantize_kernel(const uint32_t *__restri
 
 // xbar[gS+j] = sum_i A[g][i][j] * Xq[gK+i] + A[g][K][j] * r[g]  (mod p),
 // Xq quantised on the fly from the float rows.
-template <int K, int VEC>
+// With FULL = false the group has nk <= K private inputs and K + 1 - nk noise
+// rows (several colluding accelerators): the template's K counts inputs plus
+// all noise rows but one, S = K + 2 stays the number of encodings, the first nk
+// sources are float rows of x and the others field rows of r.  FULL = true is
+// the case nk = K with every test compiled away.  The same convention holds
+// for the decoding and gradient-mixing kernels below.
+template <int K, int VEC, bool FULL>
 __global__ __launch_bounds__(FT) void f_encode_kernel(
     const float *__restrict__ x, const float *__restrict__ xscale, const uint32_t *__restrict__ r,
     const uint32_t *__restrict__ A, uint32_t *__restrict__ xbar, long long len, long long nvec,
-    int chunks, long long span, double s)
+    int chunks, long long span, double s, int nk_rt)
 {
     constexpr int S = K + 2;
+    const int nk = FULL ? K : nk_rt;            // wave-uniform
     const int g = blockIdx.x / chunks;          // wave-uniform
     const int chunk = blockIdx.x - g * chunks;
     const uint32_t *Ag = A + (long long)g * S * S;
-    const float *xs = x + (long long)g * K * len;
-    const uint32_t *rs = r + (long long)g * len;
+    const float *xs = x + (long long)g * nk * len;
+    const uint32_t *rs = r + (long long)g * (K + 1 - nk) * len;
     uint32_t *dst = xbar + (long long)g * S * len;
     // 2^l times the row's normalisation factor, if any (exact in fp64)
     double si[K];
 #pragma unroll
-    for (int i = 0; i < K; ++i) si[i] = xscale ? s * (double)xscale[(long long)g * K + i] : s;
+    for (int i = 0; i < K; ++i) si[i] = (xscale && (FULL || i < nk)) ? s * (double)xscale[(long long)g * nk + i] : s;
 
     const long long v0 = (long long)chunk * span;
     long long v1 = v0 + span;
@@ -165,13 +172,13 @@ __global__ __launch_bounds__(FT) void f_encode_kernel(
 #pragma unroll
         for (int i = 0; i <= K; ++i) {
             uint32_t q[VEC];
-            if (i < K) {
+            if (i < K && (FULL || i < nk)) {
                 float f[VEC];
                 ld_f32<VEC>(f, xs + (long long)i * len + e);
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) q[c] = dkf_quant(f[c], si[i]);
+                for (int c = 0; c < VEC; ++c) q[c] = dkf_quant(f[c], si[i < K ? i : 0]);
             } else {
-                ld_u32<VEC>(q, rs + e);
+                ld_u32<VEC>(q, rs + (long long)(i - nk) * len + e);
             }
 #pragma unroll
             for (int j = 0; j < S; ++j) {
@@ -191,14 +198,16 @@ __global__ __launch_bounds__(FT) void f_encode_kernel(
 }
 
 // Decoding and the integrity check in one pass over a group's K+2 result rows.
-template <int K, int VEC>
+template <int K, int VEC, bool FULL>
 __global__ __launch_bounds__(FT) void f_decode_verify_kernel(
     const uint32_t *__restrict__ ybar, const uint32_t *__restrict__ Ainv,
     const uint32_t *__restrict__ nvec_, const float *__restrict__ xscale,
     const float *__restrict__ wscale, float *__restrict__ y, uint32_t *__restrict__ yq,
-    int *__restrict__ verdict, long long len, long long nvec, int chunks, long long span, double s)
+    int *__restrict__ verdict, long long len, long long nvec, int chunks, long long span, double s,
+    int nk_rt)
 {
     constexpr int S = K + 2;
+    const int nk = FULL ? K : nk_rt;
     const int g = blockIdx.x / chunks;
     const int chunk = blockIdx.x - g * chunks;
     const uint32_t *Ag = Ainv + (long long)g * S * S;
@@ -209,7 +218,8 @@ __global__ __launch_bounds__(FT) void f_decode_verify_kernel(
     if (xscale) {
         const double ws = (double)wscale[0];
 #pragma unroll
-        for (int i = 0; i < K; ++i) back[i] = 1.0 / ((double)xscale[(long long)g * K + i] * ws);
+        for (int i = 0; i < K; ++i)
+            back[i] = (FULL || i < nk) ? 1.0 / ((double)xscale[(long long)g * nk + i] * ws) : 1.0;
     }
 
     bool bad = false;
@@ -246,6 +256,7 @@ __global__ __launch_bounds__(FT) void f_decode_verify_kernel(
         for (int c = 0; c < VEC; ++c) bad |= dkf_reduce(t[c]) != 0;
 #pragma unroll
         for (int i = 0; i < K; ++i) {
+            if (!FULL && i >= nk) continue;
             uint32_t o[VEC];
             float f[VEC];
 #pragma unroll
@@ -254,8 +265,8 @@ __global__ __launch_bounds__(FT) void f_decode_verify_kernel(
                 f[c] = dkf_dequant(o[c], s);
                 if (xscale) f[c] = (float)((double)f[c] * back[i]);
             }
-            st_f32<VEC>(y + ((long long)g * K + i) * len + e, f);
-            if (yq) st_u32<VEC>(yq + ((long long)g * K + i) * len + e, o);
+            st_f32<VEC>(y + ((long long)g * nk + i) * len + e, f);
+            if (yq) st_u32<VEC>(yq + ((long long)g * nk + i) * len + e, o);
         }
     }
     // verdict[g] was cleared by the launch before this one
@@ -263,24 +274,27 @@ __global__ __launch_bounds__(FT) void f_decode_verify_kernel(
 }
 
 // dtilde[gS+j] = gamma[g][j] * (sum_i B[g][j][i] * Dq[gK+i])  (mod p).
-template <int K, int VEC>
+template <int K, int VEC, bool FULL>
 __global__ __launch_bounds__(FT) void f_delta_mix_kernel(
     const float *__restrict__ delta, const float *__restrict__ xscale,
     const uint32_t *__restrict__ B, const uint32_t *__restrict__ gamma,
-    uint32_t *__restrict__ dtilde, long long len, long long nvec, int chunks, long long span, double s)
+    uint32_t *__restrict__ dtilde, long long len, long long nvec, int chunks, long long span, double s,
+    int nk_rt)
 {
     constexpr int S = K + 2;
+    const int nk = FULL ? K : nk_rt;
     const int g = blockIdx.x / chunks;
     const int chunk = blockIdx.x - g * chunks;
-    const uint32_t *Bg = B + (long long)g * S * K;
+    const uint32_t *Bg = B + (long long)g * S * nk;
     const uint32_t *gg = gamma + (long long)g * S;
-    const float *src = delta + (long long)g * K * len;
+    const float *src = delta + (long long)g * nk * len;
     uint32_t *dst = dtilde + (long long)g * S * len;
     // 2^l over the factor of the sample's stored input: the fp64 reciprocal,
     // scaled by a power of two (so the product below rounds once, in fp64)
     double si[K];
 #pragma unroll
-    for (int i = 0; i < K; ++i) si[i] = xscale ? s * (1.0 / (double)xscale[(long long)g * K + i]) : s;
+    for (int i = 0; i < K; ++i)
+        si[i] = (xscale && (FULL || i < nk)) ? s * (1.0 / (double)xscale[(long long)g * nk + i]) : s;
 
     const long long v0 = (long long)chunk * span;
     long long v1 = v0 + span;
@@ -290,6 +304,11 @@ __global__ __launch_bounds__(FT) void f_delta_mix_kernel(
         uint32_t q[K][VEC];
 #pragma unroll
         for (int i = 0; i < K; ++i) {
+            if (!FULL && i >= nk) {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) q[i][c] = 0;
+                continue;
+            }
             float f[VEC];
             ld_f32<VEC>(f, src + (long long)i * len + e);
 #pragma unroll
@@ -302,7 +321,8 @@ __global__ __launch_bounds__(FT) void f_delta_mix_kernel(
             for (int c = 0; c < VEC; ++c) acc[c] = 0;
 #pragma unroll
             for (int i = 0; i < K; ++i) {
-                const uint32_t b = Bg[j * K + i];
+                if (!FULL && i >= nk) continue;
+                const uint32_t b = Bg[j * nk + i];
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) acc[c] += (uint64_t)b * q[i][c];
             }
@@ -368,7 +388,7 @@ dk_status check_args(int G, int K, long long len, int l)
 
 template <int K>
 dk_status launch_encode(const float *x, const float *xscale, const uint32_t *r, const uint32_t *A,
-                        uint32_t *xbar, int G, long long n, int l, hipStream_t st)
+                        uint32_t *xbar, int G, long long n, int l, hipStream_t st, int nk = K)
 {
     const bool v4 = vec4_ok(n, {x, r, xbar});
     const fspan p = plan_fspan(n, v4 ? 4 : 1, G);
@@ -376,17 +396,17 @@ dk_status launch_encode(const float *x, const float *xscale, const uint32_t *r, 
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     const double s = ldexp(1.0, l);
     dk_prof_scope ps("f_encode", st);
-    if (v4)
-        f_encode_kernel<K, 4><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(x, xscale, r, A, xbar, n, p.nvec, p.chunks, p.span, s);
-    else
-        f_encode_kernel<K, 1><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(x, xscale, r, A, xbar, n, p.nvec, p.chunks, p.span, s);
+#define DKF_LAUNCH(V, F) f_encode_kernel<K, V, F><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(x, xscale, r, A, xbar, n, p.nvec, p.chunks, p.span, s, nk)
+    if (nk == K) { if (v4) DKF_LAUNCH(4, true); else DKF_LAUNCH(1, true); }
+    else         { if (v4) DKF_LAUNCH(4, false); else DKF_LAUNCH(1, false); }
+#undef DKF_LAUNCH
     return dk_launch_status();
 }
 
 template <int K>
 dk_status launch_decode_verify(const uint32_t *ybar, const uint32_t *Ainv, const uint32_t *nvec,
                                const float *xscale, const float *wscale, float *y, uint32_t *yq,
-                               int *verdict, int G, long long m, int l, hipStream_t st)
+                               int *verdict, int G, long long m, int l, hipStream_t st, int nk = K)
 {
     const bool v4 = vec4_ok(m, {ybar, y, yq});
     const fspan p = plan_fspan(m, v4 ? 4 : 1, G);
@@ -399,19 +419,18 @@ dk_status launch_decode_verify(const uint32_t *ybar, const uint32_t *Ainv, const
     }
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
     dk_prof_scope ps("f_decode_verify", st);
-    if (v4)
-        f_decode_verify_kernel<K, 4><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(
-            ybar, Ainv, nvec, xscale, wscale, y, yq, verdict, m, p.nvec, p.chunks, p.span, s);
-    else
-        f_decode_verify_kernel<K, 1><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(
-            ybar, Ainv, nvec, xscale, wscale, y, yq, verdict, m, p.nvec, p.chunks, p.span, s);
+#define DKF_LAUNCH(V, F) f_decode_verify_kernel<K, V, F><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>( \
+        ybar, Ainv, nvec, xscale, wscale, y, yq, verdict, m, p.nvec, p.chunks, p.span, s, nk)
+    if (nk == K) { if (v4) DKF_LAUNCH(4, true); else DKF_LAUNCH(1, true); }
+    else         { if (v4) DKF_LAUNCH(4, false); else DKF_LAUNCH(1, false); }
+#undef DKF_LAUNCH
     return dk_launch_status();
 }
 
 template <int K>
 dk_status launch_delta_mix(const float *delta, const float *xscale, const uint32_t *B,
                            const uint32_t *gamma, uint32_t *dtilde, int G, long long m, int l,
-                           hipStream_t st)
+                           hipStream_t st, int nk = K)
 {
     const bool v4 = vec4_ok(m, {delta, dtilde});
     const fspan p = plan_fspan(m, v4 ? 4 : 1, G);
@@ -419,21 +438,21 @@ dk_status launch_delta_mix(const float *delta, const float *xscale, const uint32
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     const double s = ldexp(1.0, l);
     dk_prof_scope ps("f_delta_mix", st);
-    if (v4)
-        f_delta_mix_kernel<K, 4><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(delta, xscale, B, gamma, dtilde, m, p.nvec, p.chunks, p.span, s);
-    else
-        f_delta_mix_kernel<K, 1><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(delta, xscale, B, gamma, dtilde, m, p.nvec, p.chunks, p.span, s);
+#define DKF_LAUNCH(V, F) f_delta_mix_kernel<K, V, F><<<dim3((unsigned)blocks), dim3(FT), 0, st>>>(delta, xscale, B, gamma, dtilde, m, p.nvec, p.chunks, p.span, s, nk)
+    if (nk == K) { if (v4) DKF_LAUNCH(4, true); else DKF_LAUNCH(1, true); }
+    else         { if (v4) DKF_LAUNCH(4, false); else DKF_LAUNCH(1, false); }
+#undef DKF_LAUNCH
     return dk_launch_status();
 }
 
 } // namespace
 
 dk_status dkf_delta_mix(const float *delta, const float *xscale, const uint32_t *B,
-                        const uint32_t *gamma, uint32_t *dtilde, int G, int K, long long m, int l,
+                        const uint32_t *gamma, uint32_t *dtilde, int G, int K, int M, long long m, int l,
                         hipStream_t st)
 {
-#define CALL(KK) launch_delta_mix<KK>(delta, xscale, B, gamma, dtilde, G, m, l, st)
-    DKF_K_SWITCH(K, CALL)
+#define CALL(KK) launch_delta_mix<KK>(delta, xscale, B, gamma, dtilde, G, m, l, st, K)
+    DKF_K_SWITCH(K + M - 1, CALL)
 #undef CALL
 }
 
@@ -588,5 +607,37 @@ DK_EXPORT dk_status dkf_decode_verify_norm(const uint32_t *ybar, const uint32_t 
     hipStream_t st = (hipStream_t)stream;
 #define CALL(KK) launch_decode_verify<KK>(ybar, Ainv, nvec, xscale, wscale, y, yq, verdict, G, m, l, st)
     DKF_K_SWITCH(K, CALL)
+#undef CALL
+}
+
+// ---- several colluding accelerators: M noise rows per group, S = K + M + 1 ----
+
+DK_EXPORT dk_status dkf_encode_m(const float *x, const uint32_t *r, const uint32_t *A, uint32_t *xbar,
+                                 int G, int K, int M, long long n, int l, void *stream)
+{
+    DK_REQUIRE(x && r && A && xbar, DK_ERR_NULL);
+    DK_REQUIRE(K >= 1 && M >= 1 && K + M - 1 <= DK_MAX_K, DK_ERR_SHAPE);
+    const dk_status s = check_args(G, K + M - 1, n, l);
+    if (s != DK_OK) return s;
+    DK_REQUIRE(dk_aligned(x, 4) && dk_aligned(r, 4) && dk_aligned(A, 4) && dk_aligned(xbar, 4), DK_ERR_ALIGN);
+    hipStream_t st = (hipStream_t)stream;
+#define CALL(KK) launch_encode<KK>(x, nullptr, r, A, xbar, G, n, l, st, K)
+    DKF_K_SWITCH(K + M - 1, CALL)
+#undef CALL
+}
+
+DK_EXPORT dk_status dkf_decode_verify_m(const uint32_t *ybar, const uint32_t *Ainv, const uint32_t *nvec,
+                                        float *y, uint32_t *yq, int *verdict, int G, int K, int M,
+                                        long long m, int l, void *stream)
+{
+    DK_REQUIRE(ybar && Ainv && nvec && y && verdict, DK_ERR_NULL);
+    DK_REQUIRE(K >= 1 && M >= 1 && K + M - 1 <= DK_MAX_K, DK_ERR_SHAPE);
+    const dk_status s = check_args(G, K + M - 1, m, l);
+    if (s != DK_OK) return s;
+    DK_REQUIRE(dk_aligned(ybar, 4) && dk_aligned(Ainv, 4) && dk_aligned(nvec, 4) && dk_aligned(y, 4) &&
+                   dk_aligned(verdict, 4) && (!yq || dk_aligned(yq, 4)), DK_ERR_ALIGN);
+    hipStream_t st = (hipStream_t)stream;
+#define CALL(KK) launch_decode_verify<KK>(ybar, Ainv, nvec, nullptr, nullptr, y, yq, verdict, G, m, l, st, K)
+    DKF_K_SWITCH(K + M - 1, CALL)
 #undef CALL
 }

@@ -1282,15 +1282,20 @@ DK_EXPORT size_t dkf_fwd_workspace_bytes(int M, int N, int R)
     return FLAG_BYTES + pl.a_bytes + pl.b_bytes + pl.part_bytes;
 }
 
-DK_EXPORT size_t dkf_wgrad_workspace_bytes(const dk_layer *L, int G, int K)
+DK_EXPORT size_t dkf_wgrad_workspace_bytes_m(const dk_layer *L, int G, int K, int M)
 {
     dk_geom g;
     if (dk_layer_geom(L, &g) != DK_OK || g.dw) return 0;
-    if (G < 1 || K < 1 || K > DK_MAX_K) return 0;
-    const long long R = (long long)G * (K + 2);
+    if (G < 1 || K < 1 || M < 1 || K + M - 1 > DK_MAX_K) return 0;
+    const long long R = (long long)G * (K + M + 1);
     fgemm_plan pl;
     if (!(g.conv ? plan_conv_wgrad(g, R, &pl) : plan_fgemm(g.M, g.N, R, &pl, true))) return 0;
     return FLAG_BYTES + align256((size_t)R * g.m * sizeof(uint32_t)) + pl.a_bytes + pl.b_bytes + pl.part_bytes;
+}
+
+DK_EXPORT size_t dkf_wgrad_workspace_bytes(const dk_layer *L, int G, int K)
+{
+    return dkf_wgrad_workspace_bytes_m(L, G, K, 1);
 }
 
 DK_EXPORT dk_status dkf_linear_fwd(const uint32_t *Wq, const uint32_t *xbar, uint32_t *ybar,
@@ -1327,7 +1332,7 @@ namespace {
 
 dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *xscale, const uint32_t *B,
                      const uint32_t *gamma, const uint32_t *xbar, float *dW, uint32_t *dwq,
-                     int G, int K, int l, float scale, int accumulate,
+                     int G, int K, int Mn, int l, float scale, int accumulate,
                      void *ws, size_t ws_bytes, void *stream)
 {
     DK_REQUIRE(L && delta && B && gamma && xbar && dW, DK_ERR_NULL);
@@ -1335,8 +1340,8 @@ dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *xscale,
     const dk_status gs = dk_layer_geom(L, &g);
     if (gs != DK_OK) return gs;
     DK_REQUIRE(!g.dw, DK_ERR_UNSUPPORTED);
-    DK_REQUIRE(G >= 1 && K >= 1 && K <= DK_MAX_K && l >= 0 && l <= DKF_MAX_L, DK_ERR_SHAPE);
-    const long long R = (long long)G * (K + 2);
+    DK_REQUIRE(G >= 1 && K >= 1 && Mn >= 1 && K + Mn - 1 <= DK_MAX_K && l >= 0 && l <= DKF_MAX_L, DK_ERR_SHAPE);
+    const long long R = (long long)G * (K + Mn + 1);
     fgemm_plan pl;
     DK_REQUIRE(g.conv ? plan_conv_wgrad(g, R, &pl) : plan_fgemm(g.M, g.N, R, &pl, true), DK_ERR_SHAPE);
     DK_REQUIRE(g.conv || pl.Kp / 128 <= 65535, DK_ERR_SHAPE);   // grid.y of the transposing digit kernel
@@ -1354,7 +1359,7 @@ dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *xscale,
     int8_t *Bp = (int8_t *)w;                      w += pl.b_bytes;
     uint32_t *part = (uint32_t *)w;
 
-    dk_status s = dkf_delta_mix(delta, xscale, B, gamma, dtilde, G, K, g.m, l, st);
+    dk_status s = dkf_delta_mix(delta, xscale, B, gamma, dtilde, G, K, Mn, g.m, l, st);
     if (s != DK_OK) return s;
     {
         dk_prof_scope ps("f_flag_clear", st);
@@ -1397,7 +1402,16 @@ DK_EXPORT dk_status dkf_wgrad(const dk_layer *L, const float *delta, const uint3
                               int G, int K, int l, float scale, int accumulate,
                               void *ws, size_t ws_bytes, void *stream)
 {
-    return wgrad_impl(L, delta, nullptr, B, gamma, xbar, dW, dwq, G, K, l, scale, accumulate, ws,
+    return wgrad_impl(L, delta, nullptr, B, gamma, xbar, dW, dwq, G, K, 1, l, scale, accumulate, ws,
+                      ws_bytes, stream);
+}
+
+DK_EXPORT dk_status dkf_wgrad_m(const dk_layer *L, const float *delta, const uint32_t *B,
+                                const uint32_t *gamma, const uint32_t *xbar, float *dW, uint32_t *dwq,
+                                int G, int K, int M, int l, float scale, int accumulate,
+                                void *ws, size_t ws_bytes, void *stream)
+{
+    return wgrad_impl(L, delta, nullptr, B, gamma, xbar, dW, dwq, G, K, M, l, scale, accumulate, ws,
                       ws_bytes, stream);
 }
 
@@ -1408,6 +1422,6 @@ DK_EXPORT dk_status dkf_wgrad_norm(const dk_layer *L, const float *delta, const 
 {
     DK_REQUIRE(xscale, DK_ERR_NULL);
     DK_REQUIRE(dk_aligned(xscale, 4), DK_ERR_ALIGN);
-    return wgrad_impl(L, delta, xscale, B, gamma, xbar, dW, dwq, G, K, l, scale, accumulate, ws,
+    return wgrad_impl(L, delta, xscale, B, gamma, xbar, dW, dwq, G, K, 1, l, scale, accumulate, ws,
                       ws_bytes, stream);
 }

@@ -56,9 +56,15 @@ bool invert(std::vector<uint32_t> &M, std::vector<uint32_t> &inv, int n)
 DK_EXPORT dk_status dkf_coeffs(const uint32_t *A, const uint32_t *gamma, int G, int K,
                                uint32_t *Ainv, uint32_t *nvec, uint32_t *B)
 {
+    return dkf_coeffs_m(A, gamma, G, K, 1, Ainv, nvec, B);
+}
+
+DK_EXPORT dk_status dkf_coeffs_m(const uint32_t *A, const uint32_t *gamma, int G, int K, int Mn,
+                                 uint32_t *Ainv, uint32_t *nvec, uint32_t *B)
+{
     DK_REQUIRE(A && gamma, DK_ERR_NULL);
-    DK_REQUIRE(G >= 1 && K >= 1 && K <= DK_MAX_K, DK_ERR_SHAPE);
-    const int S = K + 2;
+    DK_REQUIRE(G >= 1 && K >= 1 && Mn >= 1 && K + Mn - 1 <= DK_MAX_K, DK_ERR_SHAPE);
+    const int S = K + Mn + 1;
     for (long long i = 0; i < (long long)G * S * S; ++i) DK_REQUIRE(A[i] < P, DK_ERR_SHAPE);
     for (long long i = 0; i < (long long)G * S; ++i) DK_REQUIRE(gamma[i] < P, DK_ERR_SHAPE);
     // Validate everything before writing anything.

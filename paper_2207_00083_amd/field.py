@@ -286,3 +286,99 @@ def dkf_wgrad(layer, delta, B, gamma, xbar, K, l=DKF_L, dW=None, dwq=None, want_
                             _ptr(dwq), G, K, int(l), float(scale), int(bool(accumulate)), _ptr(ws),
                             ws.numel(), _stream(stream)), "dkf_wgrad")
     return dW, dwq
+
+
+# ---- several colluding accelerators: M noise rows per group, S = K+M+1 ----
+
+def dkf_coeffs_m(A, gamma, K):
+    """Host arrays A[G,S,S], gamma[G,S] (uint32), S = K+M+1 -> Ainv[G,S,S], nvec[G,S], B[G,S,K]."""
+    A = np.ascontiguousarray(A, dtype=np.uint32)
+    gamma = np.ascontiguousarray(gamma, dtype=np.uint32)
+    G, S, _ = A.shape
+    M = S - K - 1
+    Ainv = np.empty((G, S, S), dtype=np.uint32)
+    nvec = np.empty((G, S), dtype=np.uint32)
+    B = np.empty((G, S, K), dtype=np.uint32)
+    _check(load().dkf_coeffs_m(A.ctypes.data, gamma.ctypes.data, G, K, M, Ainv.ctypes.data,
+                               nvec.ctypes.data, B.ctypes.data), "dkf_coeffs_m")
+    return Ainv, nvec, B
+
+
+def dkf_encode_m(x, r, A, K, M, l=DKF_L, xbar=None, stream=None):
+    """x[G*K, ...] float, r[G*M, ...], A[G,S,S] field elements (device) -> xbar[G*S, ...]."""
+    x, r, A = _dev(x, "x"), _fe(r, "r"), _fe(A, "A")
+    G, S = A.shape[0], K + M + 1
+    n = x[0].numel()
+    if x.shape[0] != G * K or r.shape[0] != G * M or tuple(A.shape) != (G, S, S) or r[0].numel() != n:
+        raise ValueError("dkf_encode_m: inconsistent shapes")
+    if xbar is None:
+        xbar = _new_fe((G * S,) + tuple(x.shape[1:]), x)
+    _fe(xbar, "xbar")
+    if xbar.numel() != G * S * n:
+        raise ValueError("dkf_encode_m: xbar has the wrong size")
+    _check(load().dkf_encode_m(_ptr(x), _ptr(r), _ptr(A), _ptr(xbar), G, K, M, n, int(l), _stream(stream)),
+           "dkf_encode_m")
+    return xbar
+
+
+def dkf_decode_verify_m(ybar, Ainv, nvec, K, M, l=DKF_L, y=None, yq=None, verdict=None, want_yq=False,
+                        stream=None):
+    """Returns (y float [G*K, ...], yq or None, verdict int32 [G])."""
+    torch = _torch()
+    ybar, Ainv, nvec = _fe(ybar, "ybar"), _fe(Ainv, "Ainv"), _fe(nvec, "nvec")
+    G, S = Ainv.shape[0], K + M + 1
+    if tuple(Ainv.shape) != (G, S, S) or tuple(nvec.shape) != (G, S) or ybar.shape[0] != G * S:
+        raise ValueError("dkf_decode_verify_m: inconsistent shapes")
+    m = ybar[0].numel()
+    if y is None:
+        y = torch.empty((G * K,) + tuple(ybar.shape[1:]), dtype=torch.float32, device=ybar.device)
+    _dev(y, "y")
+    if yq is None and want_yq:
+        yq = _new_fe(tuple(y.shape), ybar)
+    if yq is not None:
+        _fe(yq, "yq")
+    if y.numel() != G * K * m or (yq is not None and yq.numel() != G * K * m):
+        raise ValueError("dkf_decode_verify_m: output has the wrong size")
+    if verdict is None:
+        verdict = torch.empty(G, dtype=torch.int32, device=ybar.device)
+    _check(load().dkf_decode_verify_m(_ptr(ybar), _ptr(Ainv), _ptr(nvec), _ptr(y), _ptr(yq), _ptr(verdict),
+                                      G, K, M, m, int(l), _stream(stream)), "dkf_decode_verify_m")
+    return y, yq, verdict
+
+
+def dkf_wgrad_workspace_bytes_m(layer, G, K, M) -> int:
+    return int(load().dkf_wgrad_workspace_bytes_m(C.byref(DkLayer.of(layer)), int(G), int(K), int(M)))
+
+
+def dkf_wgrad_m(layer, delta, B, gamma, xbar, K, M, l=DKF_L, dW=None, dwq=None, want_dwq=False, scale=1.0,
+                accumulate=False, ws=None, stream=None):
+    """delta[G*K, ...] float, B[G,S,K], gamma[G,S], xbar[G*S, ...] (device) -> (dW float, dwq or None)."""
+    torch = _torch()
+    lay = DkLayer.of(layer)
+    delta, B, gamma, xbar = _dev(delta, "delta"), _fe(B, "B"), _fe(gamma, "gamma"), _fe(xbar, "xbar")
+    G, S = gamma.shape
+    n, m = dk_layer_in_len(lay), dk_layer_out_len(lay)
+    if n == 0:
+        raise DkError(2, "dkf_wgrad_m")
+    if (S != K + M + 1 or tuple(B.shape) != (G, S, K) or delta.numel() != G * K * m
+            or xbar.numel() != G * S * n):
+        raise ValueError("dkf_wgrad_m: inconsistent shapes")
+    wshape = (lay.M, lay.N) if lay.kind == 0 else (lay.Co, lay.Ci, lay.kh, lay.kw)
+    wcount = int(np.prod(wshape))
+    if dW is None:
+        if accumulate:
+            raise ValueError("dkf_wgrad_m: accumulate needs an existing dW")
+        dW = torch.empty(wshape, dtype=torch.float32, device=delta.device)
+    _dev(dW, "dW")
+    if dwq is None and want_dwq:
+        dwq = _new_fe(wshape, delta)
+    if dwq is not None:
+        _fe(dwq, "dwq")
+    if dW.numel() != wcount or (dwq is not None and dwq.numel() != wcount):
+        raise ValueError("dkf_wgrad_m: output has the wrong size")
+    if ws is None:
+        ws = _workspace(dkf_wgrad_workspace_bytes_m(lay, G, K, M), delta, stream)
+    _check(load().dkf_wgrad_m(C.byref(lay), _ptr(delta), _ptr(B), _ptr(gamma), _ptr(xbar), _ptr(dW),
+                              _ptr(dwq), G, K, M, int(l), float(scale), int(bool(accumulate)), _ptr(ws),
+                              ws.numel(), _stream(stream)), "dkf_wgrad_m")
+    return dW, dwq
