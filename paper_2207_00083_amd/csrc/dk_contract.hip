@@ -129,6 +129,97 @@ struct LoadIm2colDgrad {
     }
 };
 
+// Data gradient of a strided convolution, one class of input pixels at a time.
+// With stride s, an input pixel (i, j) receives only the filter taps
+// a = (i + pad) mod s, + s, + 2s, ... (likewise b), so the pixels of one
+// residue class (i mod s, j mod s) = (pi, pj) all use the same sub-filter of
+// na x nb taps a = a0 + s a', b = b0 + s b', and for pixel i = s u + pi the
+// gradient row it meets is h = u + bh - a' with bh = (pi + pad - a0) / s: a
+// stride-1 correlation without the structural zeros of the full gather.
+struct DgradClassParams {
+    const float *p;       // delta[R][Co][Ho][Wo]
+    int Co, Ho, Wo;
+    int U, V;             // pixels of the class per image: rows, columns
+    int na, nb, bh, bw;
+    int Kc;               // Co*na*nb
+    int Q;                // R*U*V
+};
+
+// B operand: rows = class pixels q = (r, u, v), contraction k = (co, a', b').
+// When the class's tap count divides the step (1, 2 or 4 taps of a 3x3 or 1x1
+// filter), a lane's elements of a step are the same taps of consecutive channel
+// groups in every step: their offsets are computed once, a step only moves a
+// scalar offset on, and taps outside the gradient image read as zero through
+// the buffer's range check.
+template <int ROWS, int BK, int NT, int LD>
+struct LoadDgradClass {
+    using Params = DgradClassParams;
+    static constexpr int KSTEP = NT / ROWS;
+    static constexpr int NE = BK / KSTEP;
+    static_assert(NT % ROWS == 0 && BK % KSTEP == 0, "tile/threads");
+    float st[NE];
+    const float *base; int Ho, Wo, na, nb, Kc, h0, w0, pcol, ksub; bool valid;
+    __amdgpu_buffer_rsrc_t rs; unsigned voff[NE]; unsigned step_bytes; bool fast;
+
+    __device__ __forceinline__ void init(const Params &a, int q0, int tid)
+    {
+        pcol = tid % ROWS; ksub = tid / ROWS;
+        Ho = a.Ho; Wo = a.Wo; na = a.na; nb = a.nb; Kc = a.Kc;
+        const int q = q0 + pcol;
+        const int UV = a.U * a.V;
+        valid = q < a.Q;
+        const int r = valid ? q / UV : 0;
+        const int pix = valid ? q - r * UV : 0;
+        const int u = pix / a.V, v = pix - u * a.V;
+        h0 = u + a.bh; w0 = v + a.bw;
+        base = a.p + (long long)r * a.Co * a.Ho * a.Wo;
+        const int tn = na * nb;
+        const long long bytes = (long long)(a.Q / UV) * a.Co * a.Ho * a.Wo * 4;
+        fast = BK % tn == 0 && bytes <= DK_RSRC_MAX;
+        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
+        step_bytes = 4u * (unsigned)(BK / tn) * (unsigned)(a.Ho * a.Wo);
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            const int k = ksub + e * KSTEP;          // position within a step
+            const int co = k / tn, rem = k - co * tn;
+            const int fa = rem / nb, fb = rem - fa * nb;
+            const int h = h0 - fa, w = w0 - fb;
+            const bool ok = valid && (unsigned)h < (unsigned)Ho && (unsigned)w < (unsigned)Wo;
+            voff[e] = ok ? 4u * (unsigned)(((r * a.Co + co) * a.Ho + h) * a.Wo + w) : DK_OOB;
+        }
+    }
+
+    __device__ __forceinline__ void load(int kt)
+    {
+        if (fast && (kt + 1) * BK <= Kc) {
+            const unsigned soff = (unsigned)kt * step_bytes;
+#pragma unroll
+            for (int e = 0; e < NE; ++e)
+                st[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (int)voff[e], (int)soff, 0));
+            return;
+        }
+        int k = kt * BK + ksub;
+        int co = k / (na * nb);
+        int rem = k - co * (na * nb);
+        int fa = rem / nb, fb = rem - fa * nb;
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            const int h = h0 - fa, w = w0 - fb;
+            const bool ok = valid && k < Kc && (unsigned)h < (unsigned)Ho && (unsigned)w < (unsigned)Wo;
+            st[e] = ok ? base[((long long)co * Ho + h) * Wo + w] : 0.0f;
+            k += KSTEP; fb += KSTEP;
+            while (fb >= nb) { fb -= nb; ++fa; }
+            while (fa >= na) { fa -= na; ++co; }
+        }
+    }
+
+    __device__ __forceinline__ void store(float *buf) const
+    {
+#pragma unroll
+        for (int e = 0; e < NE; ++e) buf[(ksub + e * KSTEP) * LD + pcol] = st[e];
+    }
+};
+
 // Convolution weight gradient, A operand: rows = co, contraction q = (r, pix);
 // element = dtilde[r][co][pix].
 template <int ROWS, int BK, int NT, int LD>
@@ -499,6 +590,19 @@ struct EpiConvFwd {          // ybar[r][co][pix]; row = co, col = q = r*HoWo + p
     __device__ __forceinline__ long long row_off(int row) const { return (long long)row * HoWo; }
 };
 
+struct EpiDgradClass {       // dx[r][ci][s u + pi][s v + pj]; row = ci, col = q = (r, u, v)
+    int rows, cols, U, V, stride, pi, pj, Wd; long long hw, chw;   // hw = H*W, chw = Ci*H*W
+    __device__ __forceinline__ bool col_ok(int col) const { return col < cols; }
+    __device__ __forceinline__ long long col_off(int col) const
+    {
+        const int UV = U * V;
+        const int r = col / UV, pix = col - r * UV;
+        const int u = pix / V, v = pix - u * V;
+        return (long long)r * chw + (long long)(u * stride + pi) * Wd + v * stride + pj;
+    }
+    __device__ __forceinline__ long long row_off(int row) const { return (long long)row * hw; }
+};
+
 // ---------------------------------------------------------------------------
 // The engine.
 // ---------------------------------------------------------------------------
@@ -513,10 +617,10 @@ struct RunParams {
     long long out_elems;
 };
 
+// One workgroup's share: tile `bid` of the run's tiles_m x tiles_n x splits.
 template <class C, class LA, class LB, class EP>
-__global__ __launch_bounds__(C::NT) void contract_kernel(typename LA::Params pa,
-                                                          typename LB::Params pb, EP ep,
-                                                          RunParams rp)
+__device__ __forceinline__ void contract_tile(const typename LA::Params &pa, const typename LB::Params &pb,
+                                              const EP &ep, const RunParams &rp, const int bid)
 {
     __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
     constexpr int A_BUF = C::BK * C::LDA, B_BUF = C::BK * C::LDB;
@@ -529,7 +633,6 @@ __global__ __launch_bounds__(C::NT) void contract_kernel(typename LA::Params pa,
     const int wn0 = (wave / C::WM) * (C::BN / C::WN);
 
     const int tiles = rp.tiles_m * rp.tiles_n;
-    const int bid = dk_xcd_block();
     const int split = bid / tiles;
     const int t = bid - split * tiles;
     // Tiles that run at the same time should share operand panels in both
@@ -623,6 +726,37 @@ __global__ __launch_bounds__(C::NT) void contract_kernel(typename LA::Params pa,
                 *d = val;
             }
     }
+}
+
+template <class C, class LA, class LB, class EP>
+__global__ __launch_bounds__(C::NT) void contract_kernel(typename LA::Params pa,
+                                                          typename LB::Params pb, EP ep,
+                                                          RunParams rp)
+{
+    contract_tile<C, LA, LB, EP>(pa, pb, ep, rp, dk_xcd_block());
+}
+
+// Several independent contractions of the same kind in one launch (each too
+// small to fill the chip alone): workgroup b serves run c with
+// first[c] <= b < first[c + 1].
+constexpr int DK_MAX_BATCH = 9;
+template <class LA, class LB, class EP>
+struct ContractBatch {
+    typename LA::Params pa[DK_MAX_BATCH];
+    typename LB::Params pb[DK_MAX_BATCH];
+    EP ep[DK_MAX_BATCH];
+    RunParams rp[DK_MAX_BATCH];
+    int first[DK_MAX_BATCH + 1];
+    int count;
+};
+
+template <class C, class LA, class LB, class EP>
+__global__ __launch_bounds__(C::NT) void contract_batch_kernel(ContractBatch<LA, LB, EP> b)
+{
+    const int bid = dk_xcd_block();
+    int c = 0;
+    while (c + 1 < b.count && bid >= b.first[c + 1]) ++c;      // wave-uniform
+    contract_tile<C, LA, LB, EP>(b.pa[c], b.pb[c], b.ep[c], b.rp[c], bid - b.first[c]);
 }
 
 // out[i] = (accumulate ? out[i] : 0) + alpha * sum_s part[s][i].  The order of
@@ -733,14 +867,17 @@ template <class C, class LA, class LB, class EP>
 dk_status run(const typename LA::Params &pa, const typename LB::Params &pb, const EP &ep,
               int rows, int cols, long long kdim, float alpha, int accumulate, float *out,
               long long out_elems, float *part, size_t part_bytes, hipStream_t st,
-              const char *label)
+              const char *label, bool may_slice = true)
 {
     RunParams rp;
     rp.tiles_m = (rows + C::BM - 1) / C::BM;
     rp.tiles_n = (cols + C::BN - 1) / C::BN;
     rp.ktiles = (int)((kdim + C::BK - 1) / C::BK);
     const long long tiles = (long long)rp.tiles_m * rp.tiles_n;
-    const dk_split_plan sp = dk_plan_split(tiles, rp.ktiles, out_elems, C::STEP_US);
+    // (an epilogue that scatters into a larger tensor cannot go through the
+    // partial sums, which are laid out like the output: such callers do not slice)
+    const dk_split_plan sp = may_slice ? dk_plan_split(tiles, rp.ktiles, out_elems, C::STEP_US)
+                                       : dk_split_plan{1, rp.ktiles};
     rp.splits = sp.splits;
     rp.per_split = sp.ktiles_per_split;
     rp.alpha = alpha;
@@ -753,7 +890,8 @@ dk_status run(const typename LA::Params &pa, const typename LB::Params &pb, cons
         DK_REQUIRE(part && part_bytes >= (size_t)rp.splits * out_elems * sizeof(float), DK_ERR_WORKSPACE);
     {
         dk_prof_scope ps(label, st);
-        contract_kernel<C, LA, LB, EP><<<dim3((unsigned)(tiles * rp.splits)), dim3(C::NT), 0, st>>>(pa, pb, ep, rp);
+        static const int lds_pad = getenv("DK_LDS_PAD") ? atoi(getenv("DK_LDS_PAD")) : 0;
+        contract_kernel<C, LA, LB, EP><<<dim3((unsigned)(tiles * rp.splits)), dim3(C::NT), lds_pad, st>>>(pa, pb, ep, rp);
     }
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
     if (rp.splits > 1) return dk_fold_slices(part, out, out_elems, rp.splits, alpha, accumulate, st);
@@ -1383,6 +1521,117 @@ __global__ __launch_bounds__(256) void conv_dgrad_direct_kernel(const float *__r
 
 bool conv_flat_dgrad(const dk_geom &g) { return g.Ci <= 64; }
 
+// One residue class of a strided data gradient.
+struct dgrad_class {
+    int pi, pj, a0, b0, na, nb, bh, bw, U, V;
+    size_t wt_off;     // floats, start of the class's filter matrix in the workspace
+};
+
+int dgrad_classes(const dk_geom &g, dgrad_class *cl)
+{
+    const int s = g.stride;
+    size_t off = 0;
+    int n = 0;
+    for (int pi = 0; pi < s; ++pi)
+        for (int pj = 0; pj < s; ++pj) {
+            dgrad_class c;
+            c.pi = pi; c.pj = pj;
+            c.a0 = (pi + g.pad) % s; c.b0 = (pj + g.pad) % s;
+            c.na = c.a0 < g.kh ? (g.kh - c.a0 + s - 1) / s : 0;
+            c.nb = c.b0 < g.kw ? (g.kw - c.b0 + s - 1) / s : 0;
+            c.bh = (pi + g.pad - c.a0) / s; c.bw = (pj + g.pad - c.b0) / s;
+            c.U = pi < g.H ? (g.H - pi + s - 1) / s : 0;
+            c.V = pj < g.W ? (g.W - pj + s - 1) / s : 0;
+            c.wt_off = off;
+            off += ((size_t)g.Ci * g.Co * c.na * c.nb + 63) / 64 * 64;      // 256-byte steps
+            cl[n++] = c;
+        }
+    return n;
+}
+
+size_t dgrad_class_filter_bytes(const dk_geom &g)
+{
+    return ((size_t)g.Ci * g.Co * g.kh * g.kw + 64 * (size_t)g.stride * g.stride) * sizeof(float);
+}
+
+// The sub-filter matrices of all classes in one launch:
+// Wt_c[ci][(co, a', b')] = W[co][ci][a0 + s a'][b0 + s b'], class c at Wt + off[c].
+struct dgrad_filter_batch {
+    int count;
+    int a0[9], b0[9], na[9], nb[9];
+    int first[10];           // running element counts
+    long long off[9];
+};
+
+__global__ __launch_bounds__(256) void dgrad_class_filter_kernel(const float *__restrict__ W, float *__restrict__ Wt,
+                                                                 int Co, int Ci, int kh, int kw, int stride,
+                                                                 dgrad_filter_batch fb)
+{
+    const int e0 = blockIdx.x * 256 + threadIdx.x;
+    if (e0 >= fb.first[fb.count]) return;
+    int c = 0;
+    while (c + 1 < fb.count && e0 >= fb.first[c + 1]) ++c;
+    const int e = e0 - fb.first[c];
+    const int nb = fb.nb[c], tn = fb.na[c] * nb;
+    const int ci = e / (Co * tn);
+    int rem = e - ci * (Co * tn);
+    const int co = rem / tn;
+    rem -= co * tn;
+    const int ap = rem / nb, bp = rem - ap * nb;
+    Wt[fb.off[c] + e] = W[((long long)(co * Ci + ci) * kh + (fb.a0[c] + stride * ap)) * kw + (fb.b0[c] + stride * bp)];
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(float *__restrict__ p, long long count)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i < count) p[i] = 0.0f;
+}
+
+// All non-empty classes in one launch: alone, a class of a 14x14 or 7x7 image
+// has fewer tiles than the chip has compute units.
+template <class C, bool VW>
+dk_status run_dgrad_classes(const dk_geom &g, const dgrad_class *cl, int ncl, const float *Wt, const float *delta,
+                            float *dx, long long R, hipStream_t st)
+{
+    using LA = LoadRowMajorK<C::BM, C::BK, C::NT, C::LDA, VW>;
+    using LB = LoadDgradClass<C::BN, C::BK, C::NT, C::LDB>;
+    ContractBatch<LA, LB, EpiDgradClass> b;
+    b.count = 0;
+    long long blocks = 0;
+    // classes with the most taps first: their tiles take longest and must not start last
+    int order[9];
+    for (int i = 0; i < ncl; ++i) order[i] = i;
+    for (int i = 1; i < ncl; ++i)
+        for (int j = i; j > 0 && cl[order[j]].na * cl[order[j]].nb > cl[order[j - 1]].na * cl[order[j - 1]].nb; --j) {
+            const int t = order[j]; order[j] = order[j - 1]; order[j - 1] = t;
+        }
+    for (int oi = 0; oi < ncl; ++oi) {
+        const dgrad_class &c = cl[order[oi]];
+        if (c.na == 0 || c.nb == 0 || c.U == 0 || c.V == 0) continue;
+        const int Kc = g.Co * c.na * c.nb;
+        const int k = b.count++;
+        b.pb[k] = {delta, g.Co, g.Ho, g.Wo, c.U, c.V, c.na, c.nb, c.bh, c.bw, Kc, (int)(R * c.U * c.V)};
+        b.pa[k] = {Wt + c.wt_off, Kc, g.Ci, Kc};
+        b.ep[k] = {g.Ci, b.pb[k].Q, c.U, c.V, g.stride, c.pi, c.pj, g.W, (long long)g.H * g.W, g.n};
+        RunParams &rp = b.rp[k];
+        rp.tiles_m = (g.Ci + C::BM - 1) / C::BM;
+        rp.tiles_n = (b.pb[k].Q + C::BN - 1) / C::BN;
+        rp.ktiles = (Kc + C::BK - 1) / C::BK;
+        rp.per_split = rp.ktiles;
+        rp.splits = 1;          // the epilogue scatters into dx: no partial sums
+        rp.alpha = 1.0f; rp.accumulate = 0;
+        rp.out = dx; rp.part = nullptr; rp.out_elems = R * g.n;
+        b.first[k] = (int)blocks;
+        blocks += (long long)rp.tiles_m * rp.tiles_n;
+    }
+    if (b.count == 0) return DK_OK;
+    DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
+    for (int k = b.count; k <= DK_MAX_BATCH; ++k) b.first[k] = (int)blocks;
+    dk_prof_scope ps("contract_conv_dgrad_classes", st);
+    contract_batch_kernel<C, LA, LB, EpiDgradClass><<<dim3((unsigned)blocks), dim3(C::NT), 0, st>>>(b);
+    return dk_launch_status();
+}
+
 // stride 1 with pad <= k-1 and a square filter: a forward convolution of delta
 bool dgrad_as_forward(const dk_geom &g, dk_geom *t)
 {
@@ -1410,6 +1659,7 @@ DK_EXPORT size_t dk_dgrad_workspace_bytes(const dk_layer *L, int R)
     const size_t wt = align_up((size_t)g.Co * g.Ci * g.kh * g.kw * sizeof(float), 256);
     if (g.dw) return 256;
     if (dgrad_as_forward(g, &t)) return wt + dk_ws_fwd_bytes(t, R);
+    if (g.stride >= 2 && g.stride <= 3) return align_up(dgrad_class_filter_bytes(g), 256);
     // gather engine: C[Ci][R*H*W] over k = Co*kh*kw
     const long long Kd = (long long)g.Co * g.kh * g.kw;
     const size_t part = conv_flat_dgrad(g) ? split_bytes<CfgFlat>(g.Ci, (long long)R * g.H * g.W, Kd, R * g.n)
@@ -1447,6 +1697,46 @@ DK_EXPORT dk_status dk_dgrad(const dk_layer *L, const float *W, const float *del
         }
         DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
         return conv_fwd_impl(t, Wt, delta, dx, R, (char *)ws + wt_bytes, ws_bytes - wt_bytes, stream);
+    }
+    if (g.stride >= 2 && g.stride <= 3 && (long long)R * g.H * g.W < (1ll << 31) - 512) {
+        // strided: one dense sub-convolution per residue class of input pixels
+        dgrad_class cl[9];
+        const int ncl = dgrad_classes(g, cl);
+        float *Wt = (float *)ws;
+        bool any_empty = false;
+        for (int c = 0; c < ncl; ++c) any_empty |= cl[c].na == 0 || cl[c].nb == 0;
+        if (any_empty) {
+            // pixels no filter tap reaches (a 1x1 filter with stride 2 skips three of four)
+            const long long total = (long long)R * g.n;
+            DK_REQUIRE((total + 255) / 256 <= 0x7fffffffll, DK_ERR_SHAPE);
+            dk_prof_scope ps("dgrad_fill", st);
+            fill_zero_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(dx, total);
+            DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+        }
+        bool vw = true;
+        dgrad_filter_batch fb;
+        fb.count = 0;
+        fb.first[0] = 0;
+        for (int c = 0; c < ncl; ++c) {
+            const dgrad_class &k = cl[c];
+            if (k.na == 0 || k.nb == 0 || k.U == 0 || k.V == 0) continue;
+            const int q = fb.count++;
+            fb.a0[q] = k.a0; fb.b0[q] = k.b0; fb.na[q] = k.na; fb.nb[q] = k.nb;
+            fb.off[q] = (long long)k.wt_off;
+            fb.first[q + 1] = fb.first[q] + g.Co * g.Ci * k.na * k.nb;
+            vw &= (g.Co * k.na * k.nb) % 4 == 0;    // rows of whole vectors (the matrices are 256-byte aligned)
+        }
+        if (fb.count) {
+            dk_prof_scope ps("dgrad_filter", st);
+            dgrad_class_filter_kernel<<<dim3((fb.first[fb.count] + 255) / 256), dim3(256), 0, st>>>(
+                W, Wt, g.Co, g.Ci, g.kh, g.kw, g.stride, fb);
+            DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+        }
+        if (conv_flat_dgrad(g))
+            return vw ? run_dgrad_classes<CfgFlat, true>(g, cl, ncl, Wt, delta, dx, R, st)
+                      : run_dgrad_classes<CfgFlat, false>(g, cl, ncl, Wt, delta, dx, R, st);
+        return vw ? run_dgrad_classes<CfgSq, true>(g, cl, ncl, Wt, delta, dx, R, st)
+                  : run_dgrad_classes<CfgSq, false>(g, cl, ncl, Wt, delta, dx, R, st);
     }
     if ((long long)R * g.H * g.W < (1ll << 31) - 512) {
         // any other geometry: gather loader on the generic contraction engine

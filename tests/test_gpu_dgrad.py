@@ -34,7 +34,13 @@ def test_dense_dgrad(dk, R, M, N):
 
 CONVS = [dk_inputs.conv(16, 24, 12, 12, 3), dk_inputs.conv(64, 64, 16, 16, 3), dk_inputs.conv(8, 130, 10, 10, 3, 2, 1),
          dk_inputs.conv(20, 12, 7, 7, 1), dk_inputs.conv(6, 9, 11, 8, 5, 2, 2), dk_inputs.conv(24, 40, 14, 14, 1, 2, 0),
-         dk_inputs.conv(5, 7, 9, 9, 3, 1, 0), dk_inputs.conv(12, 16, 8, 8, 5, 1, 2)]
+         dk_inputs.conv(5, 7, 9, 9, 3, 1, 0), dk_inputs.conv(12, 16, 8, 8, 5, 1, 2),
+         # strided: one dense sub-convolution per residue class of input pixels
+         dk_inputs.conv(70, 130, 15, 13, 3, 2, 1), dk_inputs.conv(16, 24, 14, 14, 3, 2, 0),
+         dk_inputs.conv(12, 20, 11, 16, 2, 2, 0), dk_inputs.conv(9, 8, 13, 10, 3, 3, 1),
+         dk_inputs.conv(6, 10, 12, 12, 5, 3, 2), dk_inputs.conv(8, 8, 9, 9, 1, 3, 0),
+         dk_inputs.conv(3, 16, 30, 30, 7, 2, 3), dk_inputs.conv(130, 64, 8, 8, 1, 2, 0),
+         dk_inputs.conv(4, 6, 5, 5, 2, 3, 0)]
 
 
 @pytest.mark.parametrize("L", CONVS)
