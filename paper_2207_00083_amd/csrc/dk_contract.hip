@@ -890,8 +890,7 @@ dk_status run(const typename LA::Params &pa, const typename LB::Params &pb, cons
         DK_REQUIRE(part && part_bytes >= (size_t)rp.splits * out_elems * sizeof(float), DK_ERR_WORKSPACE);
     {
         dk_prof_scope ps(label, st);
-        static const int lds_pad = getenv("DK_LDS_PAD") ? atoi(getenv("DK_LDS_PAD")) : 0;
-        contract_kernel<C, LA, LB, EP><<<dim3((unsigned)(tiles * rp.splits)), dim3(C::NT), lds_pad, st>>>(pa, pb, ep, rp);
+        contract_kernel<C, LA, LB, EP><<<dim3((unsigned)(tiles * rp.splits)), dim3(C::NT), 0, st>>>(pa, pb, ep, rp);
     }
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
     if (rp.splits > 1) return dk_fold_slices(part, out, out_elems, rp.splits, alpha, accumulate, st);
@@ -1015,11 +1014,19 @@ dk_status run_conv_wgrad(const dk_geom &g, const float *dtilde, const float *xba
                          long long R, float alpha, int accumulate, float *part, size_t part_bytes,
                          hipStream_t st)
 {
-    using LA = LoadDeltaQ<C::BM, C::BK, C::NT, C::LDA>;
     using LB = LoadIm2colQ<C::BN, C::BK, C::NT, C::LDB>;
     const ConvParams ca = conv_params(g, dtilde, R);
     const ConvParams cb = conv_params(g, xbar, R);
     EpiDense ep = {g.Kg, g.Co, (int)g.Kg};
+    if (ca.HoWo % 4 == 0 && dk_aligned(dtilde, 16)) {
+        // the mixed gradients are plain [R][Co][Ho*Wo] images whatever the filter: whole
+        // 16-byte vectors along the pixels instead of single floats
+        using LA = LoadRowMajorKImg<C::BM, C::BK, C::NT, C::LDA, true>;
+        ImgParams pa = {dtilde, g.Co, ca.HoWo, ca.Q, ca.HoWo, g.Wo, g.Wo, 1};
+        return run<C, LA, LB, EpiDense>(pa, cb, ep, g.Co, (int)g.Kg, ca.Q, alpha, accumulate, dW,
+                                        (long long)g.Co * g.Kg, part, part_bytes, st, "contract_conv_wgrad_gather");
+    }
+    using LA = LoadDeltaQ<C::BM, C::BK, C::NT, C::LDA>;
     return run<C, LA, LB, EpiDense>(ca, cb, ep, g.Co, (int)g.Kg, ca.Q, alpha, accumulate, dW,
                                     (long long)g.Co * g.Kg, part, part_bytes, st, "contract_conv_wgrad_gather");
 }
@@ -1205,6 +1212,8 @@ size_t dk_ws_wgrad_bytes(const dk_geom &g, long long R)
             if (dk_patch_wgrad_plan(g, R, aligned != 0, &pl) && pl.part_bytes > part) part = pl.part_bytes;
         const size_t fb = dk_fused1x1_wgrad_part_bytes(g, R);
         if (fb > part) part = fb;
+        const size_t sb = dk_smallci_wgrad_part_bytes(g, R);
+        if (sb > part) part = sb;
     }
     return align_up((size_t)R * g.m * sizeof(float), 256) + part;
 }
@@ -1252,6 +1261,8 @@ static dk_status conv_fwd_impl(const dk_geom &g, const float *W, const float *xb
         if (v) return run_dense_nt<CfgSq, true, true>(xbar, Wd, ybar, R, Md, Nd, part, ws_bytes - wd_bytes, st, "contract_conv_dense_fwd");
         return run_dense_nt<CfgSq, false, false>(xbar, Wd, ybar, R, Md, Nd, part, ws_bytes - wd_bytes, st, "contract_conv_dense_fwd");
     }
+    // at most four input channels: bound by writing the results, not by the matrix cores
+    if (dk_smallci_ok(g, R, xbar, ybar)) return dk_smallci_fwd_run(g, W, xbar, ybar, R, st);
     dk_patch_plan pl;
     if (dk_patch_fwd_plan(g, R, dk_aligned(xbar, 16) && dk_aligned(ybar, 16), &pl))
         return dk_patch_fwd_run(g, pl, W, xbar, ybar, (float *)ws, st);
@@ -1426,6 +1437,8 @@ static dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *
             dWd, dW, g.Ci, g.H, g.W, g.Ho, g.Wo, g.kh, g.kw, g.stride, g.pad, scale, accumulate, total);
         return dk_launch_status();
     }
+    if (dk_smallci_ok(g, R, xbar, dtilde))
+        return dk_smallci_wgrad_run(g, dtilde, xbar, dW, R, scale, accumulate, part, part_bytes, st);
     dk_wgpatch_plan pl;
     if (dk_patch_wgrad_plan(g, R, dk_aligned(xbar, 16), &pl)) {
         DK_REQUIRE(part_bytes >= pl.part_bytes, DK_ERR_WORKSPACE);

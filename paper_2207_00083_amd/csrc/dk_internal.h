@@ -84,6 +84,15 @@ dk_status dk_dw_dgrad_run(const dk_geom &g, const float *W, const float *delta, 
 dk_status dk_delta_mix(const float *delta, const float *B, const float *gamma, float *dtilde,
                        int G, int K, int M, long long m, hipStream_t st);
 
+// Direct (vector-ALU) kernels for 3x3 stride-1 pad-1 convolutions with at most
+// four input channels.
+bool dk_smallci_ok(const dk_geom &g, long long R, const float *x, const float *other);
+size_t dk_smallci_wgrad_part_bytes(const dk_geom &g, long long R);
+dk_status dk_smallci_fwd_run(const dk_geom &g, const float *W, const float *xbar, float *ybar, long long R,
+                             hipStream_t st);
+dk_status dk_smallci_wgrad_run(const dk_geom &g, const float *dtilde, const float *xbar, float *dW, long long R,
+                               float scale, int accumulate, float *part, size_t part_bytes, hipStream_t st);
+
 // Fused kernels for 1x1 stride-1 convolutions.
 bool dk_fused1x1_wgrad_ok(const dk_geom &g, int G, int K, int M, const float *delta, const float *xbar);
 size_t dk_fused1x1_wgrad_part_bytes(const dk_geom &g, long long R);

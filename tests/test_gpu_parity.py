@@ -275,6 +275,11 @@ CONV_MASKED = [
     (1, 2, 3, 16, 30, 30, 7, 2, 3),
     (8, 1, 32, 40, 2, 2, 3, 1, 1),
     (4, 2, 70, 20, 4, 4, 3, 1, 1),
+    # at most four input channels (direct vector-ALU kernels)
+    (4, 3, 1, 5, 9, 8, 3, 1, 1),
+    (2, 2, 2, 33, 7, 4, 3, 1, 1),
+    (4, 8, 3, 64, 32, 32, 3, 1, 1),
+    (3, 2, 4, 70, 5, 12, 3, 1, 1),
     # widths that are 4 mod 8 (weight gradient splits the tile by rows)
     (4, 2, 40, 24, 12, 12, 3, 1, 1),
     (2, 3, 24, 70, 20, 20, 3, 1, 1),
