@@ -78,6 +78,7 @@ def test_null_and_shape_errors_before_launch(dk):
     assert lib.dk_linear_fwd(one, one, one, 4, 0, 4, one, 1 << 20, null) == 2
     assert lib.dk_linear_fwd(one, one, one, 4, 4, 4, null, 0, null) == 5
     lay = dk.DkLayer.of(dk_inputs.conv(4, 4, 8, 8, 3))
+    one256, f32 = C.c_void_p(256), C.c_float
     assert lib.dk_conv_fwd(None, one, one, one, 4, one, 1 << 20, null) == 1
     assert lib.dk_conv_fwd(C.byref(lay), one, one, one, 0, one, 1 << 20, null) == 2
     assert lib.dk_conv_fwd(C.byref(lay), one, one, one, 4, one, 8, null) == 5
@@ -88,6 +89,25 @@ def test_null_and_shape_errors_before_launch(dk):
     assert lib.dk_wgrad(C.byref(lay), one, one, one, one, null, 1, 2, 1.0, 0, one, 1 << 20, null) == 1
     assert lib.dk_wgrad(C.byref(lay), one, one, one, one, one, 1, 2, 1.0, 0, one, 8, null) == 5
     assert lib.dk_wgrad(C.byref(lay), one, one, one, one, one, 1, 99, 1.0, 0, one, 1 << 20, null) == 2
+    # forward + decode + verify in one call
+    assert lib.dk_conv_fwd_decode_verify(C.byref(lay), one, one, one, one, f32(1e-3), null, one, null, 1, 2,
+                                         one256, 1 << 30, null) == 1
+    assert lib.dk_conv_fwd_decode_verify(C.byref(lay), one, one, one, one, f32(1e-3), one, one, null, 0, 2,
+                                         one256, 1 << 30, null) == 2
+    assert lib.dk_conv_fwd_decode_verify(C.byref(lin), one, one, one, one, f32(1e-3), one, one, null, 1, 2,
+                                         one256, 1 << 30, null) == 3
+    assert lib.dk_conv_fwd_decode_verify(C.byref(lay), one, one, one, one, f32(1e-3), one, one, null, 1, 2,
+                                         one256, 64, null) == 5
+    assert lib.dk_conv_fwd_decode_verify(C.byref(lay), one, one, one, one, f32(1e-3), one, one, null, 1, 2,
+                                         one, 1 << 30, null) == 4
+    assert dk.dk_conv_fwd_decode_verify_workspace_bytes(dk_inputs.conv(4, 4, 8, 8, 3), 2, 2) > 0
+    assert dk.dk_conv_fwd_decode_verify_workspace_bytes(dk_inputs.linear(4, 4), 2, 2) == 0
+    # tuning switches
+    assert lib.dk_set_option(7, 1) == 2 and lib.dk_set_option(0, 5) == 2
+    assert lib.dk_set_option(dk.DK_OPT_FUSE_WGRAD, dk.DK_FUSE_NEVER) == 0
+    assert dk.dk_get_option(dk.DK_OPT_FUSE_WGRAD) == dk.DK_FUSE_NEVER
+    assert lib.dk_set_option(dk.DK_OPT_FUSE_WGRAD, dk.DK_FUSE_AUTO) == 0
+    assert dk.dk_get_option(99) == -1
     # the entry point without a workspace: argument errors first, then its group limit
     assert lib.dk_decode_verify_static(one, one, one, 1e-3, null, one, null, 1, 2, 8, null) == 1
     assert lib.dk_decode_verify_static(one, one, one, 1e-3, one, one, null, 1, 0, 8, null) == 2

@@ -105,7 +105,38 @@ class FieldPath:
         dk.dkf_wgrad(L, self.delta, self.B, self.gamma, self.xbar, K, dW=self.dW, ws=self.ws_wg)
 
 
+class FusedPath(Fp32Path):
+    """1x1 layers through the fused kernels: forward + decode + verify in one
+    kernel (its verdict taken inside the kernel or by a second launch,
+    depending on the number of tiles per virtual batch) and the weight gradient
+    with the mixing in its loader."""
+
+    def __init__(self, dk, L, K, G, seed):
+        super().__init__(dk, L, K, G, seed)
+        u8 = dict(dtype=torch.uint8, device="cuda")
+        self.ws_fdv = torch.empty(dk.dk_conv_fwd_decode_verify_workspace_bytes(L, G, K), **u8)
+
+    def outputs(self):
+        return (self.xbar, self.y, self.dW, self.verdict, self.resid)
+
+    def step(self):
+        dk, L, K = self.dk, self.L, self.K
+        dk.dk_set_option(dk.DK_OPT_FUSE_FWD, dk.DK_FUSE_ALWAYS)
+        dk.dk_set_option(dk.DK_OPT_FUSE_WGRAD, dk.DK_FUSE_ALWAYS)
+        try:
+            dk.dk_encode(self.X, self.r, self.A, K, xbar=self.xbar)
+            dk.dk_conv_fwd_decode_verify(L, self.W, self.xbar, self.Ainv, self.nvec, K, tol=1e-3, y=self.y,
+                                         verdict=self.verdict, resid=self.resid, ws=self.ws_fdv)
+            dk.dk_wgrad(L, self.delta, self.B, self.gamma, self.xbar, K, dW=self.dW, ws=self.ws_wg)
+        finally:
+            dk.dk_set_option(dk.DK_OPT_FUSE_FWD, dk.DK_FUSE_AUTO)
+            dk.dk_set_option(dk.DK_OPT_FUSE_WGRAD, dk.DK_FUSE_AUTO)
+
+
 CASES = [(Fp32Path, dk_inputs.conv(64, 64, 16, 16, 3), 4, 3), (Fp32Path, dk_inputs.linear(200, 1100), 8, 2),
+         (FusedPath, dk_inputs.conv(64, 128, 16, 16, 1, 1, 0), 8, 2),       # 8 tiles per batch: verdict in the kernel
+         (FusedPath, dk_inputs.conv(32, 64, 48, 48, 1, 1, 0), 4, 2),        # 36 tiles per batch: second launch
+         (Fp32Path, dk_inputs.conv(3, 16, 16, 16, 3), 2, 3),                # direct small-channel kernels
          (Fp32Path, dk_inputs.conv(24, 40, 14, 14, 3, 2, 1), 2, 2),
          (FieldPath, dk_inputs.conv(32, 64, 16, 16, 3), 4, 2), (FieldPath, dk_inputs.linear(130, 300), 2, 3)]
 
