@@ -424,7 +424,8 @@ def aggregate(args, subs):
         op = o["value"] * 1e12 * o["ms_per_step"] * 1e-3
         layers.append({"workload": sub, "count": count, "ms_per_step": o["ms_per_step"], "value": o["value"],
                        "roofline_kernel": o["roofline"]["kernel"], "roofline_bound": o["roofline"]["bound"],
-                       "roofline_frac": o["roofline"]["frac"]})
+                       "roofline_frac": o["roofline"]["frac"], "layer": o["config"].get("layer"),
+                       "kernel_ms": o.get("kernel_ms")})
         if "roofline_floor_ms" in o:
             layers[-1].update(roofline_floor_ms=o["roofline_floor_ms"], step_frac=o["step_frac"],
                               step_bound=o["step_bound"])
