@@ -287,6 +287,73 @@ void orf_conv_wgrad_points(const fe *D, const fe *X, long R, long Ci, long H, lo
     }
 }
 
+/* Depthwise cross-correlation over the field (one filter per channel,
+ * W[C][kh][kw]): the linear operation of the spatial half of a
+ * depthwise-separable layer on encoded rows.
+ * Y[s][c][h][w] = sum_{a,b} W[c][a][b] X[s][c][h*st+a-pad][w*st+b-pad]  (mod p). */
+void orf_dwconv_fwd(const fe *W, const fe *X, fe *Y, long R, long C, long H, long Wd,
+                    long kh, long kw, long st, long pad, fe p)
+{
+    const long Ho = (H + 2 * pad - kh) / st + 1, Wo = (Wd + 2 * pad - kw) / st + 1;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (long s = 0; s < R; ++s)
+        for (long c = 0; c < C; ++c)
+            for (long h = 0; h < Ho; ++h)
+                for (long w = 0; w < Wo; ++w) {
+                    fe acc = 0;
+                    for (long a = 0; a < kh; ++a)
+                        for (long b = 0; b < kw; ++b) {
+                            const long ih = h * st + a - pad, iw = w * st + b - pad;
+                            if (ih < 0 || ih >= H || iw < 0 || iw >= Wd) continue;
+                            acc = addmod(acc, mulmod(W[(c * kh + a) * kw + b],
+                                                     X[((s * C + c) * H + ih) * Wd + iw], p), p);
+                        }
+                    Y[((s * C + c) * Ho + h) * Wo + w] = acc;
+                }
+}
+
+/* dWq[c][a][b] = sum_{s,h,w} D[s][c][h][w] X[s][c][h*st+a-pad][w*st+b-pad]  (mod p). */
+void orf_dwconv_wgrad(const fe *D, const fe *X, fe *dWq, long R, long C, long H, long Wd,
+                      long kh, long kw, long st, long pad, fe p)
+{
+    const long Ho = (H + 2 * pad - kh) / st + 1, Wo = (Wd + 2 * pad - kw) / st + 1;
+#pragma omp parallel for schedule(static)
+    for (long c = 0; c < C; ++c)
+        for (long a = 0; a < kh; ++a)
+            for (long b = 0; b < kw; ++b) {
+                fe acc = 0;
+                for (long s = 0; s < R; ++s)
+                    for (long h = 0; h < Ho; ++h)
+                        for (long w = 0; w < Wo; ++w) {
+                            const long ih = h * st + a - pad, iw = w * st + b - pad;
+                            if (ih < 0 || ih >= H || iw < 0 || iw >= Wd) continue;
+                            acc = addmod(acc, mulmod(D[((s * C + c) * Ho + h) * Wo + w],
+                                                     X[((s * C + c) * H + ih) * Wd + iw], p), p);
+                        }
+                dWq[(c * kh + a) * kw + b] = acc;
+            }
+}
+
+/* The layer's bias in the field (quantisation algorithm: b_q = Field(Round(b 2^{2l})),
+ * two factors of 2^l because it joins products of two quantised values).  It is
+ * added to the decoded field values, entry e of every row taking bias[e / per]:
+ * yq[row][e] <- yq[row][e] + b_q[e / per]  (mod p). */
+void orf_add_bias(fe *yq, const float *bias, long rows, long m, long per, int l, fe p)
+{
+    const double s = ldexp(1.0, 2 * l);
+#pragma omp parallel for schedule(static)
+    for (long r = 0; r < rows; ++r)
+        for (long e = 0; e < m; ++e) {
+            double v = floor((double)bias[e / per] * s + 0.5);
+            if (v != v) v = 0.0;
+            if (v > 2147483647.0) v = 2147483647.0;
+            if (v < -2147483648.0) v = -2147483648.0;
+            long long z = (long long)v % (long long)p;
+            if (z < 0) z += p;
+            yq[r * m + e] = addmod(yq[r * m + e], (fe)z, p);
+        }
+}
+
 /* ----------------------------------------------------------------------
  * Several colluding accelerators over the field (section "Colluding GPUs",
  * and the paragraph of "Privacy Guarantee" on it: M noise vectors uniform

@@ -264,6 +264,58 @@ def conv_wgrad_points(D, X, kh, kw, pts, stride=1, pad=0, p=P):
     return out
 
 
+def dwconv_fwd(Wq, X, stride=1, pad=0, p=P):
+    """Depthwise cross-correlation over the field: Wq[C,kh,kw], X[R,C,H,W]."""
+    Wq, X = _u(Wq), _u(X)
+    Cc, kh, kw = Wq.shape
+    R, _, H, Wd = X.shape
+    Ho, Wo = conv_out_hw(H, Wd, kh, kw, stride, pad)
+    Y = np.empty((R, Cc, Ho, Wo), dtype=np.uint32)
+    _L().orf_dwconv_fwd(_p(Wq), _p(X), _p(Y), _l(R), _l(Cc), _l(H), _l(Wd), _l(kh), _l(kw), _l(stride),
+                        _l(pad), _fe(p))
+    return Y
+
+
+def dwconv_wgrad(D, X, kh, kw, stride=1, pad=0, p=P):
+    D, X = _u(D), _u(X)
+    R, Cc, H, Wd = X.shape
+    out = np.empty((Cc, kh, kw), dtype=np.uint32)
+    _L().orf_dwconv_wgrad(_p(D), _p(X), _p(out), _l(R), _l(Cc), _l(H), _l(Wd), _l(kh), _l(kw), _l(stride),
+                          _l(pad), _fe(p))
+    return out
+
+
+def add_bias(yq, bias, per, l=L_BITS, p=P):
+    """Decoded field values plus the quantised bias b_q = Field(Round(b 2^{2l}))
+    (quantisation algorithm); entry e of every row takes bias[e // per]
+    (per = 1 for a dense layer, Ho*Wo for a convolution)."""
+    out = _u(yq).copy()
+    bias = np.ascontiguousarray(bias, dtype=np.float32)
+    rows = out.shape[0]
+    m = int(np.prod(out.shape[1:]))
+    assert bias.size * per == m
+    _L().orf_add_bias(_p(out), _p(bias), _l(rows), _l(m), _l(per), C.c_int(l), _fe(p))
+    return out
+
+
+def masked_dw_layer(W, X, r, delta, A, gamma, stride=1, pad=0, l=L_BITS, p=P):
+    """masked_layer for a depthwise convolution W[C,kh,kw]: the same steps with
+    the depthwise correlation as the linear operation."""
+    Ainv, nvec, B = coefficients(A, gamma, p)
+    Wq, Xq = quantize(W, l, p), quantize(X, l, p)
+    Xbar = encode(Xq, r, A, p)
+    Ybar = dwconv_fwd(Wq, Xbar, stride, pad, p)
+    verdict = verify(Ybar, nvec, p)
+    Yq = decode(Ybar, Ainv, None, p)
+    Y = dequantize(Yq, l, p)
+    Dq = quantize(delta, l, p)
+    Dtilde = delta_mix(Dq, B, gamma, p)
+    dWq = dwconv_wgrad(Dtilde, Xbar, W.shape[1], W.shape[2], stride, pad, p)
+    dW = dequantize(dWq, l, p)
+    return dict(Wq=Wq, Xq=Xq, Xbar=Xbar, Ybar=Ybar, verdict=verdict, Yq=Yq, Y=Y, Dq=Dq,
+                Dtilde=Dtilde, dWq=dWq, dW=dW)
+
+
 def masked_layer(W, X, r, delta, A, gamma, stride=1, pad=0, l=L_BITS, p=P):
     """masked_dense_layer for either kind of layer: W 2-D is the dense layer,
     W 4-D the NCHW convolution (same steps, the convolution as the linear
