@@ -185,6 +185,21 @@ dk_status dkf_wgrad_norm(const dk_layer *L, const float *delta, const float *xsc
                          void *ws, size_t ws_bytes, void *stream);
 
 /* Workspace sizes in bytes (0 for invalid arguments). */
+/* The layer's bias (quantisation algorithm: b_q = Field(Round(b 2^{2l})), two
+ * factors of 2^l because it joins products of two quantised values).  Adding b
+ * to every encoded result would not decode to Y + b, so it is added on the
+ * trusted side, to the decoded field values:
+ *   yq[row][e] <- yq[row][e] + b_q[e / per]  mod p;   y = Round(lift(yq) 2^-l) 2^-l
+ * with per = 1 for a dense layer (bias[m]) and Ho*Wo for a convolution
+ * (bias[Co]).  yq[rows][m] in place, bias[m / per] float (device); y[rows][m]
+ * float (device) receives the de-quantised sums if not NULL. */
+dk_status dkf_add_bias(uint32_t *yq, float *y, const float *bias, long long rows, long long m,
+                       long long per, int l, void *stream);
+
+/* Depthwise layers (dk_layer.kind = DK_DWCONV2D, W[C][kh][kw]): dkf_conv_fwd,
+ * dkf_wgrad and their workspace queries take them too; a few multiply-adds per
+ * element moved, so they run on the vector ALUs, exact modulo p like the rest. */
+
 /* ---- Several colluding accelerators over the field (section "Colluding
  * GPUs"; "Privacy Guarantee", the paragraph on colluding accelerators: with M
  * noise vectors uniform over F_p and A_2 of full rank, any M encodings are

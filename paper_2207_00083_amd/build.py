@@ -12,7 +12,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libdarknight.so")
 SOURCES = ["dk_host.cpp", "dk_mix.hip", "dk_contract.hip", "dk_conv_patch.hip", "dk_wgrad_patch.hip",
            "dk_field_host.cpp", "dk_field.hip", "dk_field_gemm.hip", "dk_rng.hip", "dk_dwconv.hip",
-           "dk_fused1x1.hip", "dk_conv_smallci.hip"]
+           "dk_fused1x1.hip", "dk_conv_smallci.hip", "dk_field_dw.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -12,6 +12,14 @@ dk_status dkf_delta_mix(const float *delta, const float *xscale, const uint32_t 
                         const uint32_t *gamma, uint32_t *dtilde, int G, int K, int M, long long m, int l,
                         hipStream_t st);
 
+// Depthwise convolution over the field.
+size_t dkf_dw_wgrad_part_bytes(const dk_geom &g, long long R);
+dk_status dkf_dw_fwd_run(const dk_geom &g, const uint32_t *Wq, const uint32_t *xbar, uint32_t *ybar,
+                         long long R, hipStream_t st);
+dk_status dkf_dw_wgrad_run(const dk_geom &g, const uint32_t *dtilde, const uint32_t *xbar, float *dW,
+                           uint32_t *dwq, long long R, int l, float scale, int accumulate, uint32_t *part,
+                           hipStream_t st);
+
 #ifdef __HIPCC__
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));

@@ -1209,7 +1209,8 @@ bool plan_conv_wgrad(const dk_geom &g, long long R, fgemm_plan *pl)
 DK_EXPORT size_t dkf_conv_fwd_workspace_bytes(const dk_layer *L, int R)
 {
     dk_geom g;
-    if (dk_layer_geom(L, &g) != DK_OK || !g.conv || g.dw || R < 1) return 0;
+    if (dk_layer_geom(L, &g) != DK_OK || !g.conv || R < 1) return 0;
+    if (g.dw) return 256;               // the depthwise kernel needs none
     fgemm_plan pl;
     if (!plan_conv_fwd(g, R, &pl)) return 0;
     return FLAG_BYTES + pl.a_bytes + pl.b_bytes + pl.part_bytes;
@@ -1222,8 +1223,12 @@ DK_EXPORT dk_status dkf_conv_fwd(const dk_layer *L, const uint32_t *Wq, const ui
     dk_geom g;
     const dk_status gs = dk_layer_geom(L, &g);
     if (gs != DK_OK) return gs;
-    DK_REQUIRE(g.conv && !g.dw, DK_ERR_UNSUPPORTED);
+    DK_REQUIRE(g.conv, DK_ERR_UNSUPPORTED);
     DK_REQUIRE(R >= 1, DK_ERR_SHAPE);
+    if (g.dw) {
+        DK_REQUIRE(dk_aligned(Wq, 4) && dk_aligned(xbar, 4) && dk_aligned(ybar, 4), DK_ERR_ALIGN);
+        return dkf_dw_fwd_run(g, Wq, xbar, ybar, R, (hipStream_t)stream);
+    }
     fgemm_plan pl;
     DK_REQUIRE(plan_conv_fwd(g, R, &pl), DK_ERR_SHAPE);
     DK_REQUIRE(dk_aligned(Wq, 4) && dk_aligned(xbar, 4) && dk_aligned(ybar, 4), DK_ERR_ALIGN);
@@ -1285,9 +1290,10 @@ DK_EXPORT size_t dkf_fwd_workspace_bytes(int M, int N, int R)
 DK_EXPORT size_t dkf_wgrad_workspace_bytes_m(const dk_layer *L, int G, int K, int M)
 {
     dk_geom g;
-    if (dk_layer_geom(L, &g) != DK_OK || g.dw) return 0;
+    if (dk_layer_geom(L, &g) != DK_OK) return 0;
     if (G < 1 || K < 1 || M < 1 || K + M - 1 > DK_MAX_K) return 0;
     const long long R = (long long)G * (K + M + 1);
+    if (g.dw) return FLAG_BYTES + align256((size_t)R * g.m * sizeof(uint32_t)) + dkf_dw_wgrad_part_bytes(g, R);
     fgemm_plan pl;
     if (!(g.conv ? plan_conv_wgrad(g, R, &pl) : plan_fgemm(g.M, g.N, R, &pl, true))) return 0;
     return FLAG_BYTES + align256((size_t)R * g.m * sizeof(uint32_t)) + pl.a_bytes + pl.b_bytes + pl.part_bytes;
@@ -1339,9 +1345,21 @@ dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *xscale,
     dk_geom g;
     const dk_status gs = dk_layer_geom(L, &g);
     if (gs != DK_OK) return gs;
-    DK_REQUIRE(!g.dw, DK_ERR_UNSUPPORTED);
     DK_REQUIRE(G >= 1 && K >= 1 && Mn >= 1 && K + Mn - 1 <= DK_MAX_K && l >= 0 && l <= DKF_MAX_L, DK_ERR_SHAPE);
     const long long R = (long long)G * (K + Mn + 1);
+    if (g.dw) {
+        DK_REQUIRE(R < (1ll << 31), DK_ERR_SHAPE);
+        DK_REQUIRE(dk_aligned(delta, 4) && dk_aligned(B, 4) && dk_aligned(gamma, 4) && dk_aligned(xbar, 4) &&
+                       dk_aligned(dW, 4) && (!dwq || dk_aligned(dwq, 4)), DK_ERR_ALIGN);
+        const size_t dtb = align256((size_t)R * g.m * sizeof(uint32_t));
+        DK_REQUIRE(ws && ws_bytes >= FLAG_BYTES + dtb + dkf_dw_wgrad_part_bytes(g, R), DK_ERR_WORKSPACE);
+        DK_REQUIRE(dk_aligned(ws, 256), DK_ERR_ALIGN);
+        uint32_t *dt = (uint32_t *)((char *)ws + FLAG_BYTES);
+        uint32_t *pt = (uint32_t *)((char *)ws + FLAG_BYTES + dtb);
+        const dk_status ms = dkf_delta_mix(delta, xscale, B, gamma, dt, G, K, Mn, g.m, l, (hipStream_t)stream);
+        if (ms != DK_OK) return ms;
+        return dkf_dw_wgrad_run(g, dt, xbar, dW, dwq, R, l, scale, accumulate, pt, (hipStream_t)stream);
+    }
     fgemm_plan pl;
     DK_REQUIRE(g.conv ? plan_conv_wgrad(g, R, &pl) : plan_fgemm(g.M, g.N, R, &pl, true), DK_ERR_SHAPE);
     DK_REQUIRE(g.conv || pl.Kp / 128 <= 65535, DK_ERR_SHAPE);   // grid.y of the transposing digit kernel

@@ -198,7 +198,8 @@ def dkf_conv_fwd(layer, Wq, xbar, ybar=None, ws=None, stream=None):
     R = xbar.shape[0]
     Ho = (lay.H + 2 * lay.pad - lay.kh) // lay.stride + 1
     Wo = (lay.W + 2 * lay.pad - lay.kw) // lay.stride + 1
-    if xbar[0].numel() != lay.Ci * lay.H * lay.W or Wq.numel() != lay.Co * lay.Ci * lay.kh * lay.kw:
+    wcount = lay.Ci * lay.kh * lay.kw if lay.kind == 2 else lay.Co * lay.Ci * lay.kh * lay.kw
+    if xbar[0].numel() != lay.Ci * lay.H * lay.W or Wq.numel() != wcount:
         raise ValueError("dkf_conv_fwd: inconsistent shapes")
     if ybar is None:
         ybar = _new_fe((R, lay.Co, Ho, Wo), Wq)
@@ -261,7 +262,8 @@ def dkf_wgrad(layer, delta, B, gamma, xbar, K, l=DKF_L, dW=None, dwq=None, want_
     if (S != K + 2 or tuple(B.shape) != (G, S, K) or delta.numel() != G * K * m
             or xbar.numel() != G * S * n):
         raise ValueError("dkf_wgrad: inconsistent shapes")
-    wshape = (lay.M, lay.N) if lay.kind == 0 else (lay.Co, lay.Ci, lay.kh, lay.kw)
+    wshape = ((lay.M, lay.N) if lay.kind == 0 else (lay.Ci, lay.kh, lay.kw) if lay.kind == 2
+              else (lay.Co, lay.Ci, lay.kh, lay.kw))
     wcount = int(np.prod(wshape))
     if dW is None:
         if accumulate:
@@ -286,6 +288,26 @@ def dkf_wgrad(layer, delta, B, gamma, xbar, K, l=DKF_L, dW=None, dwq=None, want_
                             _ptr(dwq), G, K, int(l), float(scale), int(bool(accumulate)), _ptr(ws),
                             ws.numel(), _stream(stream)), "dkf_wgrad")
     return dW, dwq
+
+
+def dkf_add_bias(yq, bias, per, l=DKF_L, y=None, want_y=True, stream=None):
+    """yq[rows, ...] field elements (device, updated in place) += Field(Round(bias 2^{2l}))[e // per];
+    returns (yq, y) with y the de-quantised sums (None if want_y is False)."""
+    torch = _torch()
+    yq, bias = _fe(yq, "yq"), _dev(bias, "bias")
+    rows = yq.shape[0]
+    m = yq[0].numel()
+    if bias.numel() * per != m:
+        raise ValueError("dkf_add_bias: bias does not fit the rows")
+    if y is None and want_y:
+        y = torch.empty(tuple(yq.shape), dtype=torch.float32, device=yq.device)
+    if y is not None:
+        _dev(y, "y")
+        if y.numel() != yq.numel():
+            raise ValueError("dkf_add_bias: y has the wrong size")
+    _check(load().dkf_add_bias(_ptr(yq), _ptr(y), _ptr(bias), rows, m, int(per), int(l), _stream(stream)),
+           "dkf_add_bias")
+    return yq, y
 
 
 # ---- several colluding accelerators: M noise rows per group, S = K+M+1 ----
