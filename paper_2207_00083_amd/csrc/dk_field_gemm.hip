@@ -67,6 +67,7 @@ struct fgemm_params {
     int sK;                // contraction length R * Ho * Wp
     int out_hw;            // 0: C[i][j] at i*J + j;  hw > 0: j = (image, pixel), C at ((image*I + i)*hw + pixel
     double s_inv;          // 2^-l for out_f
+    int lq;                // l
     float scale;
     int accumulate;
     int sums;              // planes 4, 5 of both operands hold the digit sums of the halves
@@ -569,14 +570,26 @@ __global__ __launch_bounds__(256) void f_digits_wconv_kernel(const uint32_t *__r
 
 __global__ void f_flag_clear_kernel(int *flags) { if (threadIdx.x < 2) flags[threadIdx.x] = 0; }
 
-// |v| < 2^62 -> v mod p in [0, p)
-__device__ __forceinline__ uint32_t reduce_signed(long long v)
+// a0 + 2^7 a1 + 2^14 a2 (three int32 digit-class sums) as a lazily reduced
+// residue below 2^25 + 2^9, in 32-bit operations only (64-bit shifts and
+// multiply-adds run at a fraction of their rate): each term is split where
+// its shift crosses 2^25 and the upper part comes back multiplied by 39 = 2^25 mod p
+// (24-bit multiply-adds; arithmetic shifts keep the split exact for negative sums);
+// 2p makes the total positive before the last fold.
+__device__ __forceinline__ uint32_t fold_sum3(int a0, int a1, int a2)
 {
-    const bool neg = v < 0;
-    const uint64_t m = neg ? (uint64_t)(-v) : (uint64_t)v;
-    const uint64_t t = (m >> 25) * 39u + (m & 0x1ffffffu);     // < 2^43
-    const uint32_t r = dkf_reduce(t);
-    return (neg && r) ? DKF_P - r : r;
+    const int x0 = __mul24(a0 >> 25, 39) + (a0 & 0x1ffffff);                 // a0:       |.| < 2^25 + 2^12
+    const int x1 = __mul24(a1 >> 18, 39) + (int)(((uint32_t)a1 << 7) & 0x1ffffffu);          // 2^7 a1:   (-2^19, 2^25 + 2^19)
+    const int x2 = __mul24(a2 >> 11, 39) + (int)(((uint32_t)a2 << 14) & 0x1ffffffu);         // 2^14 a2:  (-2^26, 2^25 + 2^26)
+    const uint32_t sum = (uint32_t)(x0 + x1 + x2 + 2 * (int)DKF_P);          // in (0, 2^28)
+    return __umul24(sum >> 25, 39u) + (sum & 0x1ffffffu);
+}
+
+// t 2^14 mod p for t < 2^26, lazily reduced (below 2^25 + 2^21): the bits that the
+// shift moves above 2^25 come back multiplied by 39.
+__device__ __forceinline__ uint32_t shift14(uint32_t t)
+{
+    return __umul24(t >> 11, 39u) + ((t << 14) & 0x1ffffffu);
 }
 
 // One workgroup: a 128 x 128 tile of C over one k slice, all four digit-half
@@ -711,56 +724,64 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     const int nsteps = nparts * (kt1 - kt0);
 
     i32x4 sa[NA], sb[8];
-#define DKF_FETCH(PI, KTILE)                                                                      \
+    // What a fetch of tile (part PI, k tile KTILE) needs besides the piece number.
+#define DKF_FETCH_PREP(PI, KTILE)                                                                 \
+    const int q_ = DKF_PART(PI);                                                                  \
+    const int8_t *as_ = p.Ap + 2 * (q_ & 3) * p.a_plane + ((long long)ti * BI * p.Kp + (long long)(KTILE) * KT); \
+    const int8_t *bs_ = p.Bp + 2 * (q_ >> 2) * p.b_plane + ((long long)tj * BJ * p.Kp + (long long)(KTILE) * KT); \
+    const int k0_ = (KTILE) * KT + 16 * spiece;                                                   \
+    unsigned koff_ = 0;                                                                           \
+    bool kok_ = true;                                                                             \
+    int fa_ = 0, fb_ = 0;                                                                         \
+    const int8_t *bp_ = p.Bp + 2 * (q_ >> 2) * p.b_plane;                                         \
+    if (BMODE == 2) {                                                                             \
+        const int img_ = k0_ / p.sImgK;                                                           \
+        const int rem_ = k0_ - img_ * p.sImgK;                                                    \
+        const int oh_ = rem_ / p.cWo;                                                             \
+        koff_ = (unsigned)img_ * (unsigned)p.sImgP + (unsigned)(oh_ * p.sWpp + (rem_ - oh_ * p.cWo)); \
+        kok_ = k0_ < p.sK;                                                                        \
+    } else if (BMODE == 1) {                                                                      \
+        const int tap_ = k0_ / p.cp;                                                              \
+        fa_ = tap_ / p.ckw;                                                                       \
+        fb_ = tap_ - fa_ * p.ckw;                                                                 \
+        kok_ = tap_ < p.ckh * p.ckw;                                                              \
+        bp_ += k0_ - tap_ * p.cp;                                                                 \
+    }
+    // Pieces E0 <= e < E1 of A (of NA) and F0 <= e < F1 of B (of 8) into the staging registers.
+#define DKF_FETCH_PIECES(E0, E1, F0, F1)                                                          \
     {                                                                                             \
-        const int q_ = DKF_PART(PI);                                                              \
-        const int8_t *as_ = p.Ap + 2 * (q_ & 3) * p.a_plane + ((long long)ti * BI * p.Kp + (long long)(KTILE) * KT); \
-        const int8_t *bs_ = p.Bp + 2 * (q_ >> 2) * p.b_plane + ((long long)tj * BJ * p.Kp + (long long)(KTILE) * KT); \
-        _Pragma("unroll") for (int e = 0; e < NA; ++e)                                            \
+        _Pragma("unroll") for (int e = (E0); e < (E1); ++e)                                       \
             sa[e] = *reinterpret_cast<const i32x4 *>((as_ + ((e / (2 * NBI)) * p.a_plane + (e % (2 * NBI)) * q_rows)) + s_off); \
-        if (BMODE == 0) {                                                                         \
-            _Pragma("unroll") for (int e = 0; e < 8; ++e)                                         \
-                sb[e] = *reinterpret_cast<const i32x4 *>((bs_ + ((e >> 2) * p.b_plane + (e & 3) * q_rows)) + s_off); \
-        } else if (BMODE == 2) {                                                                  \
-            const int k0_ = (KTILE) * KT + 16 * spiece;                                           \
-            const int img_ = k0_ / p.sImgK;                                                       \
-            const int rem_ = k0_ - img_ * p.sImgK;                                                \
-            const int oh_ = rem_ / p.cWo;                                                         \
-            const unsigned koff_ = (unsigned)img_ * (unsigned)p.sImgP + (unsigned)(oh_ * p.sWpp + (rem_ - oh_ * p.cWo)); \
-            const bool kok_ = k0_ < p.sK;                                                         \
-            const int8_t *bp_ = p.Bp + 2 * (q_ >> 2) * p.b_plane;                                 \
-            _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                       \
-                _Pragma("unroll") for (int pl = 0; pl < 2; ++pl) {                                \
-                    i32x4 v_ = {0, 0, 0, 0};                                                      \
-                    if (kok_ && r_ok[q]) v_ = *reinterpret_cast<const i32x4_u *>(bp_ + pl * p.b_plane + (r_base[q] + koff_)); \
-                    sb[pl * 4 + q] = v_;                                                          \
-                }                                                                                 \
-            }                                                                                     \
-        } else {                                                                                  \
-            const int k0_ = (KTILE) * KT + 16 * spiece;                                           \
-            const int tap_ = k0_ / p.cp, ci0_ = k0_ - tap_ * p.cp;                                \
-            const int fa_ = tap_ / p.ckw, fb_ = tap_ - fa_ * p.ckw;                               \
-            const bool tap_ok_ = tap_ < p.ckh * p.ckw;                                            \
-            const int8_t *bp_ = p.Bp + 2 * (q_ >> 2) * p.b_plane + ci0_;                          \
-            _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                       \
+        _Pragma("unroll") for (int e = (F0); e < (F1); ++e) {                                     \
+            const int pl = e >> 2, q = e & 3;                                                     \
+            if (BMODE == 0) {                                                                     \
+                sb[e] = *reinterpret_cast<const i32x4 *>((bs_ + (pl * p.b_plane + q * q_rows)) + s_off); \
+            } else if (BMODE == 2) {                                                              \
+                i32x4 v_ = {0, 0, 0, 0};                                                          \
+                if (kok_ && r_ok[q]) v_ = *reinterpret_cast<const i32x4_u *>(bp_ + pl * p.b_plane + (r_base[q] + koff_)); \
+                sb[e] = v_;                                                                       \
+            } else {                                                                              \
                 const int ih_ = r_ih[q] + fa_, iw_ = r_iw[q] + fb_;                               \
-                const bool ok_ = tap_ok_ && r_ok[q] && ih_ >= 0 && ih_ < p.cH && iw_ >= 0 && iw_ < p.cW; \
+                const bool ok_ = kok_ && r_ok[q] && ih_ >= 0 && ih_ < p.cH && iw_ >= 0 && iw_ < p.cW; \
                 const unsigned off_ = r_base[q] + (unsigned)(ih_ * p.cW + iw_) * (unsigned)p.cp;  \
-                _Pragma("unroll") for (int pl = 0; pl < 2; ++pl) {                                \
-                    i32x4 v_ = {0, 0, 0, 0};                                                      \
-                    if (ok_) v_ = *reinterpret_cast<const i32x4 *>(bp_ + pl * p.b_plane + off_);  \
-                    sb[pl * 4 + q] = v_;                                                          \
-                }                                                                                 \
+                i32x4 v_ = {0, 0, 0, 0};                                                          \
+                if (ok_) v_ = *reinterpret_cast<const i32x4 *>(bp_ + pl * p.b_plane + off_);      \
+                sb[e] = v_;                                                                       \
             }                                                                                     \
         }                                                                                         \
     }
-#define DKF_STASH(BUF)                                                                            \
+#define DKF_STASH_PIECES(BUF, E0, E1, F0, F1)                                                     \
     {                                                                                             \
-        _Pragma("unroll") for (int e = 0; e < NA; ++e)                                            \
+        _Pragma("unroll") for (int e = (E0); e < (E1); ++e)                                       \
             *reinterpret_cast<i32x4 *>((BUF) + (e / (2 * NBI)) * A_PLANE + (e % (2 * NBI)) * 32 * PITCH + s_dst) = sa[e]; \
-        _Pragma("unroll") for (int e = 0; e < 8; ++e)                                             \
+        _Pragma("unroll") for (int e = (F0); e < (F1); ++e)                                       \
             *reinterpret_cast<i32x4 *>((BUF) + 2 * A_PLANE + (e >> 2) * B_PLANE + (e & 3) * 32 * PITCH + s_dst) = sb[e]; \
     }
+    // Quarter U of a tile's pieces: written to LDS from the staging registers, which then
+    // take the same pieces of the tile two steps ahead.
+#define DKF_TURN(BUF, U)                                                                          \
+    DKF_STASH_PIECES(BUF, (U) * NBI, ((U) + 1) * NBI, 2 * (U), 2 * (U) + 2)                       \
+    DKF_FETCH_PIECES((U) * NBI, ((U) + 1) * NBI, 2 * (U), 2 * (U) + 2)
     // in the order the MFMAs of a step consume them: A and B planes 0 first
 #define DKF_READ(A, B, KS)                                                                        \
     {                                                                                             \
@@ -784,15 +805,27 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
                         acc[bi][bj][pa + pb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(             \
                             A[bi][pa], B[bj][pb], acc[bi][bj][pa + pb], 0, 0, 0);                 \
     }
-    // one MFMA and one LDS read per operand piece of the next sub-step (2 NBI + 4
-    // of them), then the remaining MFMAs: the reads have time to come back
-#define DKF_PACE_READS()                                                                          \
+    // Issue order of a 32-k sub-step: its 8 NBI MFMAs with, one each, the NR LDS reads of the
+    // next sub-step's operands, then the NBI + 2 (LDS write, global load) pairs of this
+    // quarter of the staging registers.  Spread like this the global loads of the four waves
+    // reach the vector-memory path at the rate it takes them; issued in one burst at the end
+    // of a step they held the waves (and so the matrix pipes) until it had taken them all.
+#define DKF_PACE(NR)                                                                              \
     {                                                                                             \
-        _Pragma("unroll") for (int e = 0; e < 2 * NBI + 4; ++e) {                                 \
+        constexpr int nw_ = NBI + 2, nm_ = 8 * NBI;                                               \
+        constexpr int both_ = (NR) + nw_ > nm_ ? (NR) + nw_ - nm_ : 0;                            \
+        _Pragma("unroll") for (int e = 0; e < (NR) - both_; ++e) {                                \
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    \
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                    \
         }                                                                                         \
-        __builtin_amdgcn_sched_group_barrier(0x008, 8 * NBI - (2 * NBI + 4), 0);                  \
+        _Pragma("unroll") for (int e = 0; e < nw_; ++e) {                                         \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    \
+            if (e < both_) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                     \
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                                    \
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                    \
+        }                                                                                         \
+        if (nm_ - ((NR) - both_) - nw_ > 0)                                                       \
+            __builtin_amdgcn_sched_group_barrier(0x008, nm_ - ((NR) - both_) - nw_, 0);           \
         __builtin_amdgcn_sched_barrier(0);                                                        \
     }
     // keep consumed operand registers live up to here, so that a read issued
@@ -813,10 +846,17 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     int pi = 0, kt = kt0;                 // part index and k tile of the current step
     int pi2 = 0, kt2 = kt0;               // ... of the step the next fetch is for
     if (nsteps > 0) {
-        DKF_FETCH(0, kt0)
-        DKF_STASH(flds)
+        {
+            DKF_FETCH_PREP(0, kt0)
+            DKF_FETCH_PIECES(0, NA, 0, 8)
+        }
+        DKF_STASH_PIECES(flds, 0, NA, 0, 8)
         DKF_ADVANCE(pi2, kt2)
-        if (nsteps > 1) DKF_FETCH(pi2, kt2)
+        {
+            // (a tile beyond the last step is part 0 of a valid k tile: in bounds, never used)
+            DKF_FETCH_PREP(pi2, kt2)
+            DKF_FETCH_PIECES(0, NA, 0, 8)
+        }
         DKF_ADVANCE(pi2, kt2)
     }
     __syncthreads();
@@ -835,51 +875,50 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         for (; step < g_end; ++step) {
             const int8_t *cur = flds + (step & 1) * BUF_BYTES;
             int8_t *nxt = flds + ((step + 1) & 1) * BUF_BYTES;
-            // Four 32-k sub-steps.  The operands of step s+1 are read from LDS while
-            // the 16 MFMAs of step s issue (one read per two MFMAs); the LDS
-            // writes of the next tile go between the MFMAs of the last step.
+            // Four 32-k sub-steps.  The operands of sub-step u+1 are read from LDS while
+            // the MFMAs of sub-step u issue; each sub-step also moves a quarter of the
+            // staging registers (tile s+1) to the other LDS buffer and refills them from
+            // tile s+2 (past the last step: part 0 of a valid k tile, never used).
+            DKF_FETCH_PREP(pi2, kt2)
             i32x4 a0[NBI][2], b0[2][2], a1[NBI][2], b1[2][2];
             DKF_READ(a0, b0, 0)
             __builtin_amdgcn_sched_barrier(0);
             DKF_READ(a1, b1, 1)
             DKF_MMA(a0, b0)
-            DKF_PACE_READS()
+            DKF_TURN(nxt, 0)
+            DKF_PACE(2 * NBI + 4)
             DKF_KEEP(a0, b0)
             DKF_READ(a0, b0, 2)
             DKF_MMA(a1, b1)
-            DKF_PACE_READS()
+            DKF_TURN(nxt, 1)
+            DKF_PACE(2 * NBI + 4)
             DKF_KEEP(a1, b1)
             DKF_READ(a1, b1, 3)
             DKF_MMA(a0, b0)
-            DKF_PACE_READS()
+            DKF_TURN(nxt, 2)
+            DKF_PACE(2 * NBI + 4)
             DKF_KEEP(a0, b0)
             DKF_MMA(a1, b1)
-            // (after the last step this stores stale registers to the idle buffer)
-            DKF_STASH(nxt)
-#pragma unroll
-            for (int e = 0; e < 8 * NBI; ++e) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // one LDS write
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if (step + 2 < nsteps) DKF_FETCH(pi2, kt2)
+            DKF_TURN(nxt, 3)
+            DKF_PACE(0)
             __syncthreads();
             DKF_ADVANCE(pi, kt)
             DKF_ADVANCE(pi2, kt2)
         }
 
-        // End of a weight group: recombine the three accumulators with the
-        // constants gw 128^s mod p in 64 bits (gw = 128^(2w), or the weight of
-        // the group in the three-part form), reduce, add to the running
-        // residues and clear the accumulators.  (Measured alternatives: the same
-        // in fp64, and one 64-bit product with the sum a0 + 128 a1 + 128^2 a2,
-        // take as long and three times as long.)
-        uint64_t gw = 1ull << (14 * w);
-        if (three) gw = w == 0 ? (uint64_t)DKF_P + 1 - (1u << 14) : w == 1 ? 1ull << 14 : (1ull << 28) - (1u << 14);
-        gw = dkf_reduce(gw);
-        const int c0 = (int)gw;
-        const int c1 = (int)dkf_reduce(gw << 7);
-        const int c2 = (int)dkf_reduce(gw << 14);
+        // End of a weight group: S = a0 + 2^7 a1 + 2^14 a2 of the three accumulators
+        // joins the running sums with the group's weight, which is a signed sum of
+        // powers of 2^14 in every case -- 1, 2^14, 2^28 for the four-part form and
+        // 1 - 2^14, 2^14, 2^28 - 2^14 for the three-part form -- so shifts, 24-bit
+        // multiplies by 39 and additions do it (64-bit products with the weights took
+        // three times as long).  Nothing is reduced below p here: a group adds less
+        // than 2^27 to a running sum, which the epilogue reduces once.
+        // The weight as masks over t, +-2^14 t and 2^28 t (uniform, so no branches and
+        // one short dependency chain per value; 2p - u > 0 stands for -u).
+        const uint32_t m_one = (w == 0) ? ~0u : 0u;
+        const uint32_t m_add = (w == 1) ? ~0u : 0u;
+        const uint32_t m_sub = (three && w != 1) ? ~0u : 0u;
+        const uint32_t m_two = (w == 2) ? ~0u : 0u;
 #pragma unroll
         for (int bi = 0; bi < NBI; ++bi)
 #pragma unroll
@@ -887,30 +926,61 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
                 __builtin_amdgcn_sched_barrier(0);     // one block at a time: short live ranges
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const long long val = (long long)acc[bi][bj][0][v] * c0 +
-                                          (long long)acc[bi][bj][1][v] * c1 +
-                                          (long long)acc[bi][bj][2][v] * c2;      // |val| < 2^58
-                    const uint32_t u = res[bi][bj][v] + reduce_signed(val);
-                    res[bi][bj][v] = u >= DKF_P ? u - DKF_P : u;
+                    const uint32_t t = fold_sum3(acc[bi][bj][0][v], acc[bi][bj][1][v], acc[bi][bj][2][v]);
+                    const uint32_t u = shift14(t);
+                    const uint32_t uu = shift14(u);
+                    res[bi][bj][v] += (t & m_one) + (u & m_add) + ((2u * DKF_P - u) & m_sub) + (uu & m_two);
                 }
 #pragma unroll
-                for (int s = 0; s < 3; ++s)
+                for (int c = 0; c < 3; ++c)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[bi][bj][s][v] = 0;
+                    for (int v = 0; v < 16; ++v) acc[bi][bj][c][v] = 0;
             }
         __builtin_amdgcn_sched_barrier(0);
     }
 #undef DKF_PART
 #undef DKF_GROUP
 #undef DKF_ADVANCE
-#undef DKF_PACE_READS
+#undef DKF_PACE
 #undef DKF_KEEP
-#undef DKF_FETCH
-#undef DKF_STASH
+#undef DKF_FETCH_PREP
+#undef DKF_FETCH_PIECES
+#undef DKF_STASH_PIECES
+#undef DKF_TURN
 #undef DKF_READ
 #undef DKF_MMA
 
     uint32_t *dst_q = p.out_q ? p.out_q + (long long)split * p.I * p.J : nullptr;   // (one slice if remapped)
+    if (!p.out_hw && ti * BI + BI <= p.I && tj * BJ + BJ <= p.J) {
+        // Tile inside a row-major result: no bounds tests, uniform offsets from one lane
+        // address, and Round(lift(q) 2^-l) 2^-l in integers -- n = (lift(q) + 2^(l-1)) >> l is
+        // the floor of lift(q) 2^-l + 1/2, n 2^-l is exact in fp32, and scale 2^-l is an exact
+        // product, so n (scale 2^-l) rounds once, to the value scale (n 2^-l) rounds to.
+        const long long o0 = (long long)(ti * BI + wi0 + 4 * lh) * p.J + (tj * BJ + wj0 + li);
+        uint32_t *q0 = dst_q ? dst_q + o0 : nullptr;
+        float *f0 = p.out_f ? p.out_f + o0 : nullptr;
+        const float c = p.scale * (float)p.s_inv;
+        const int half = p.lq > 0 ? 1 << (p.lq - 1) : 0;
+#pragma unroll
+        for (int bi = 0; bi < NBI; ++bi)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const long long orow = (long long)(bi * 32 + 8 * (v / 4) + (v % 4)) * p.J;
+#pragma unroll
+                for (int bj = 0; bj < 2; ++bj) {
+                    const uint32_t r = res[bi][bj][v];                                 // < 2^28
+                    const uint32_t u = __umul24(r >> 25, 39u) + (r & 0x1ffffffu);
+                    const uint32_t q = u >= DKF_P ? u - DKF_P : u;
+                    if (q0) q0[orow + bj * 32] = q;
+                    if (f0) {
+                        const int lift = q > DKF_P / 2 ? (int)q - (int)DKF_P : (int)q;
+                        const float f = (float)((lift + half) >> p.lq) * c;
+                        f0[orow + bj * 32] = p.accumulate ? f0[orow + bj * 32] + f : f;
+                    }
+                }
+            }
+        return;
+    }
 #pragma unroll
     for (int bi = 0; bi < NBI; ++bi)
 #pragma unroll
@@ -923,7 +993,9 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
                 if (i < p.I && j < p.J) {
                     const long long o = p.out_hw ? ((long long)jimg * p.I + i) * p.out_hw + jpix
                                                  : (long long)i * p.J + j;
-                    const uint32_t q = res[bi][bj][v];
+                    const uint32_t r = res[bi][bj][v];                                 // < 2^28
+                    const uint32_t u = __umul24(r >> 25, 39u) + (r & 0x1ffffffu);
+                    const uint32_t q = u >= DKF_P ? u - DKF_P : u;
                     if (dst_q) dst_q[o] = q;
                     if (p.out_f) {
                         const float f = p.scale * dkf_dequant(q, p.s_inv);
@@ -1057,7 +1129,7 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
     p.I = pl.I; p.J = pl.J; p.Kp = pl.Kp;
     p.tiles_i = pl.tiles_i; p.tiles_j = pl.tiles_j; p.splits = pl.splits;
     p.ktiles_per_split = pl.ktiles_per_split; p.ktiles = pl.ktiles;
-    p.s_inv = ldexp(1.0, -l); p.scale = scale; p.accumulate = accumulate;
+    p.s_inv = ldexp(1.0, -l); p.lq = l; p.scale = scale; p.accumulate = accumulate;
     p.sums = pl.sums;
     p.out_hw = direct ? out_hw : 0;
     p.cp = p.cH = p.cW = p.ckh = p.ckw = p.cstride = p.cpad = p.cWo = p.cHoWo = 0;
