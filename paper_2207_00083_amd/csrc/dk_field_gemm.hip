@@ -926,10 +926,17 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
                 __builtin_amdgcn_sched_barrier(0);     // one block at a time: short live ranges
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const uint32_t t = fold_sum3(acc[bi][bj][0][v], acc[bi][bj][1][v], acc[bi][bj][2][v]);
+                    // (read where they are used: left to the compiler, all 192 accumulators
+                    // are copied out first and a part of the running sums is spilled)
+                    int a0, a1, a2;
+                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a0) : "a"(acc[bi][bj][0][v]));
+                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a1) : "a"(acc[bi][bj][1][v]));
+                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a2) : "a"(acc[bi][bj][2][v]));
+                    const uint32_t t = fold_sum3(a0, a1, a2);
                     const uint32_t u = shift14(t);
                     const uint32_t uu = shift14(u);
                     res[bi][bj][v] += (t & m_one) + (u & m_add) + ((2u * DKF_P - u) & m_sub) + (uu & m_two);
+                    if (v % 4 == 3) __builtin_amdgcn_sched_barrier(0);     // few values in flight: no spills
                 }
 #pragma unroll
                 for (int c = 0; c < 3; ++c)
