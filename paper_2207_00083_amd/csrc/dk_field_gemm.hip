@@ -34,6 +34,7 @@
 // are written k-major by the digit kernels (straight for row-major operands,
 // through an LDS transpose for the weight gradient, whose contraction index is
 // the encoded-row index).
+#include <type_traits>
 #include "dk_field.h"
 
 namespace {
@@ -45,6 +46,7 @@ constexpr int B_PLANE = BJ * PITCH;
 constexpr int LDS_BYTES = 2 * (2 * BI * PITCH + 2 * B_PLANE);   // 147456: two buffers of the 128-row tile
 constexpr int MAX_KSPLIT = 1 << 17;    // k values per slice (int32 accumulators)
 constexpr int MAX_KSPLIT_SUMS = 1 << 16;   // ... when the digit-sum planes are multiplied
+constexpr int RSRC_FLAGS = 0x00020000;  // raw buffer resource, gfx9 family
 constexpr int MAX_SPLITS = 256;        // k slices per output tile (the fold adds their residues in 64 bits)
 
 struct fgemm_params {
@@ -724,16 +726,37 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     const int nsteps = nparts * (kt1 - kt0);
 
     i32x4 sa[NA], sb[8];
-    // What a fetch of tile (part PI, k tile KTILE) needs besides the piece number.
-#define DKF_FETCH_PREP(PI, KTILE)                                                                 \
-    const int q_ = DKF_PART(PI);                                                                  \
-    const int8_t *as_ = p.Ap + 2 * (q_ & 3) * p.a_plane + ((long long)ti * BI * p.Kp + (long long)(KTILE) * KT); \
-    const int8_t *bs_ = p.Bp + 2 * (q_ >> 2) * p.b_plane + ((long long)tj * BJ * p.Kp + (long long)(KTILE) * KT); \
+    // Stored operands are fetched with buffer loads: a resource per digit plane of the part
+    // being fetched, spanning this tile's rows (rebuilt when the part changes), the lane's
+    // row and piece in four precomputed offsets and the k tile in the scalar offset -- no
+    // address arithmetic per load (64-bit lane addresses cost a vector instruction per load
+    // and a dozen scalar ones per step, all issued by the one wave that feeds the matrix pipe).
+    __amdgpu_buffer_rsrc_t rsA0, rsA1, rsB0, rsB1;
+    const int8_t *bpart = p.Bp;
+    unsigned voff[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) voff[q] = (unsigned)(32 * q) * (unsigned)p.Kp + s_off;
+#define DKF_FETCH_PART(PI)                                                                        \
+    {                                                                                             \
+        const int q_ = DKF_PART(PI);                                                              \
+        const int8_t *a_ = p.Ap + 2 * (q_ & 3) * p.a_plane + (long long)ti * BI * p.Kp;           \
+        rsA0 = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(a_), 0, BI * p.Kp, RSRC_FLAGS); \
+        rsA1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(a_ + p.a_plane), 0, BI * p.Kp, RSRC_FLAGS); \
+        bpart = p.Bp + 2 * (q_ >> 2) * p.b_plane;                                                 \
+        if (BMODE == 0) {                                                                         \
+            const int8_t *b_ = bpart + (long long)tj * BJ * p.Kp;                                 \
+            rsB0 = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(b_), 0, BJ * p.Kp, RSRC_FLAGS); \
+            rsB1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(b_ + p.b_plane), 0, BJ * p.Kp, RSRC_FLAGS); \
+        }                                                                                         \
+    }
+    // What a fetch of k tile KTILE needs besides the piece number.
+#define DKF_FETCH_PREP(KTILE)                                                                     \
+    const int soff_ = (KTILE) * KT;                                                               \
     const int k0_ = (KTILE) * KT + 16 * spiece;                                                   \
     unsigned koff_ = 0;                                                                           \
     bool kok_ = true;                                                                             \
     int fa_ = 0, fb_ = 0;                                                                         \
-    const int8_t *bp_ = p.Bp + 2 * (q_ >> 2) * p.b_plane;                                         \
+    const int8_t *bp_ = bpart;                                                                    \
     if (BMODE == 2) {                                                                             \
         const int img_ = k0_ / p.sImgK;                                                           \
         const int rem_ = k0_ - img_ * p.sImgK;                                                    \
@@ -751,11 +774,13 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 #define DKF_FETCH_PIECES(E0, E1, F0, F1)                                                          \
     {                                                                                             \
         _Pragma("unroll") for (int e = (E0); e < (E1); ++e)                                       \
-            sa[e] = *reinterpret_cast<const i32x4 *>((as_ + ((e / (2 * NBI)) * p.a_plane + (e % (2 * NBI)) * q_rows)) + s_off); \
+            sa[e] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(              \
+                (e / (2 * NBI)) ? rsA1 : rsA0, (int)voff[e % (2 * NBI)], soff_, 0));              \
         _Pragma("unroll") for (int e = (F0); e < (F1); ++e) {                                     \
             const int pl = e >> 2, q = e & 3;                                                     \
             if (BMODE == 0) {                                                                     \
-                sb[e] = *reinterpret_cast<const i32x4 *>((bs_ + (pl * p.b_plane + q * q_rows)) + s_off); \
+                sb[e] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(          \
+                    pl ? rsB1 : rsB0, (int)voff[q], soff_, 0));                                   \
             } else if (BMODE == 2) {                                                              \
                 i32x4 v_ = {0, 0, 0, 0};                                                          \
                 if (kok_ && r_ok[q]) v_ = *reinterpret_cast<const i32x4_u *>(bp_ + pl * p.b_plane + (r_base[q] + koff_)); \
@@ -846,18 +871,21 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     int pi = 0, kt = kt0;                 // part index and k tile of the current step
     int pi2 = 0, kt2 = kt0;               // ... of the step the next fetch is for
     if (nsteps > 0) {
+        DKF_FETCH_PART(0)
         {
-            DKF_FETCH_PREP(0, kt0)
+            DKF_FETCH_PREP(kt0)
             DKF_FETCH_PIECES(0, NA, 0, 8)
         }
         DKF_STASH_PIECES(flds, 0, NA, 0, 8)
         DKF_ADVANCE(pi2, kt2)
+        if (kt2 == kt0) DKF_FETCH_PART(pi2)
         {
             // (a tile beyond the last step is part 0 of a valid k tile: in bounds, never used)
-            DKF_FETCH_PREP(pi2, kt2)
+            DKF_FETCH_PREP(kt2)
             DKF_FETCH_PIECES(0, NA, 0, 8)
         }
         DKF_ADVANCE(pi2, kt2)
+        if (kt2 == kt0) DKF_FETCH_PART(pi2)
     }
     __syncthreads();
 
@@ -879,7 +907,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
             // the MFMAs of sub-step u issue; each sub-step also moves a quarter of the
             // staging registers (tile s+1) to the other LDS buffer and refills them from
             // tile s+2 (past the last step: part 0 of a valid k tile, never used).
-            DKF_FETCH_PREP(pi2, kt2)
+            DKF_FETCH_PREP(kt2)
             i32x4 a0[NBI][2], b0[2][2], a1[NBI][2], b1[2][2];
             DKF_READ(a0, b0, 0)
             __builtin_amdgcn_sched_barrier(0);
@@ -904,6 +932,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
             __syncthreads();
             DKF_ADVANCE(pi, kt)
             DKF_ADVANCE(pi2, kt2)
+            if (kt2 == kt0) DKF_FETCH_PART(pi2)
         }
 
         // End of a weight group: S = a0 + 2^7 a1 + 2^14 a2 of the three accumulators
@@ -913,43 +942,56 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         // multiplies by 39 and additions do it (64-bit products with the weights took
         // three times as long).  Nothing is reduced below p here: a group adds less
         // than 2^27 to a running sum, which the epilogue reduces once.
-        // The weight as masks over t, +-2^14 t and 2^28 t (uniform, so no branches and
-        // one short dependency chain per value; 2p - u > 0 stands for -u).
-        const uint32_t m_one = (w == 0) ? ~0u : 0u;
-        const uint32_t m_add = (w == 1) ? ~0u : 0u;
-        const uint32_t m_sub = (three && w != 1) ? ~0u : 0u;
-        const uint32_t m_two = (w == 2) ? ~0u : 0u;
+        // One straight-line copy per weight (uniform switch), a 32 x 32 block at a time.
+        auto join = [&](auto weight) {
+            constexpr int WEIGHT = decltype(weight)::value;
 #pragma unroll
-        for (int bi = 0; bi < NBI; ++bi)
+            for (int bi = 0; bi < NBI; ++bi)
 #pragma unroll
-            for (int bj = 0; bj < 2; ++bj) {
-                __builtin_amdgcn_sched_barrier(0);     // one block at a time: short live ranges
+                for (int bj = 0; bj < 2; ++bj) {
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    // (read where they are used: left to the compiler, all 192 accumulators
-                    // are copied out first and a part of the running sums is spilled)
-                    int a0, a1, a2;
-                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a0) : "a"(acc[bi][bj][0][v]));
-                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a1) : "a"(acc[bi][bj][1][v]));
-                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a2) : "a"(acc[bi][bj][2][v]));
-                    const uint32_t t = fold_sum3(a0, a1, a2);
-                    const uint32_t u = shift14(t);
-                    const uint32_t uu = shift14(u);
-                    res[bi][bj][v] += (t & m_one) + (u & m_add) + ((2u * DKF_P - u) & m_sub) + (uu & m_two);
-                    if (v % 4 == 3) __builtin_amdgcn_sched_barrier(0);     // few values in flight: no spills
+                    for (int v = 0; v < 16; ++v) {
+                        int a0, a1, a2;
+                        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a0) : "a"(acc[bi][bj][0][v]));
+                        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a1) : "a"(acc[bi][bj][1][v]));
+                        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a2) : "a"(acc[bi][bj][2][v]));
+                        const uint32_t t = fold_sum3(a0, a1, a2);
+                        if (WEIGHT == 0) {                 // 1
+                            res[bi][bj][v] += t;
+                        } else if (WEIGHT == 1) {          // 1 - 2^14 (2p - u > 0 stands for -u)
+                            res[bi][bj][v] += t + (2u * DKF_P - shift14(t));
+                        } else if (WEIGHT == 2) {          // 2^14
+                            res[bi][bj][v] += shift14(t);
+                        } else if (WEIGHT == 3) {          // 2^28 - 2^14
+                            const uint32_t u = shift14(t);
+                            res[bi][bj][v] += shift14(u) + (2u * DKF_P - u);
+                        } else {                           // 2^28
+                            res[bi][bj][v] += shift14(shift14(t));
+                        }
+                        if (v % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+                    }
+#pragma unroll
+                    for (int c = 0; c < 3; ++c)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[bi][bj][c][v] = 0;
                 }
-#pragma unroll
-                for (int c = 0; c < 3; ++c)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[bi][bj][c][v] = 0;
-            }
-        __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        switch (three ? (w == 0 ? 1 : w == 1 ? 2 : 3) : 2 * w) {
+        case 0: join(std::integral_constant<int, 0>{}); break;
+        case 1: join(std::integral_constant<int, 1>{}); break;
+        case 2: join(std::integral_constant<int, 2>{}); break;
+        case 3: join(std::integral_constant<int, 3>{}); break;
+        default: join(std::integral_constant<int, 4>{}); break;
+        }
     }
 #undef DKF_PART
 #undef DKF_GROUP
 #undef DKF_ADVANCE
 #undef DKF_PACE
 #undef DKF_KEEP
+#undef DKF_FETCH_PART
 #undef DKF_FETCH_PREP
 #undef DKF_FETCH_PIECES
 #undef DKF_STASH_PIECES
