@@ -747,6 +747,9 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
             const int8_t *b_ = bpart + (long long)tj * BJ * p.Kp;                                 \
             rsB0 = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(b_), 0, BJ * p.Kp, RSRC_FLAGS); \
             rsB1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(b_ + p.b_plane), 0, BJ * p.Kp, RSRC_FLAGS); \
+        } else if (BMODE == 1) {       /* whole planes (below 2^31 bytes): a piece outside the image reads as zero */ \
+            rsB0 = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(bpart), 0, (int)p.b_plane, RSRC_FLAGS); \
+            rsB1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(bpart + p.b_plane), 0, (int)p.b_plane, RSRC_FLAGS); \
         }                                                                                         \
     }
     // What a fetch of k tile KTILE needs besides the piece number.
@@ -768,7 +771,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         fa_ = tap_ / p.ckw;                                                                       \
         fb_ = tap_ - fa_ * p.ckw;                                                                 \
         kok_ = tap_ < p.ckh * p.ckw;                                                              \
-        bp_ += k0_ - tap_ * p.cp;                                                                 \
+        koff_ = (unsigned)(k0_ - tap_ * p.cp);                                                    \
     }
     // Pieces E0 <= e < E1 of A (of NA) and F0 <= e < F1 of B (of 8) into the staging registers.
 #define DKF_FETCH_PIECES(E0, E1, F0, F1)                                                          \
@@ -782,16 +785,18 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
                 sb[e] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(          \
                     pl ? rsB1 : rsB0, (int)voff[q], soff_, 0));                                   \
             } else if (BMODE == 2) {                                                              \
-                i32x4 v_ = {0, 0, 0, 0};                                                          \
-                if (kok_ && r_ok[q]) v_ = *reinterpret_cast<const i32x4_u *>(bp_ + pl * p.b_plane + (r_base[q] + koff_)); \
-                sb[e] = v_;                                                                       \
+                /* no branch between the MFMAs: a piece of a row beyond J or of a k beyond the */ \
+                /* contraction only has to stay in bounds (those rows are never stored, those */  \
+                /* k meet zero columns of A), so it reads the start of the plane */               \
+                const unsigned off_ = (kok_ && r_ok[q]) ? r_base[q] + koff_ : 0u;                 \
+                sb[e] = *reinterpret_cast<const i32x4_u *>(bp_ + pl * p.b_plane + off_);          \
             } else {                                                                              \
                 const int ih_ = r_ih[q] + fa_, iw_ = r_iw[q] + fb_;                               \
                 const bool ok_ = kok_ && r_ok[q] && ih_ >= 0 && ih_ < p.cH && iw_ >= 0 && iw_ < p.cW; \
-                const unsigned off_ = r_base[q] + (unsigned)(ih_ * p.cW + iw_) * (unsigned)p.cp;  \
-                i32x4 v_ = {0, 0, 0, 0};                                                          \
-                if (ok_) v_ = *reinterpret_cast<const i32x4 *>(bp_ + pl * p.b_plane + off_);      \
-                sb[e] = v_;                                                                       \
+                const unsigned off_ = ok_ ? r_base[q] + (unsigned)(ih_ * p.cW + iw_) * (unsigned)p.cp + koff_ \
+                                          : 0x80000000u;                                          \
+                sb[e] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(          \
+                    pl ? rsB1 : rsB0, (int)off_, 0, 0));                                          \
             }                                                                                     \
         }                                                                                         \
     }
