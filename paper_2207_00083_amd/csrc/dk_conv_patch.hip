@@ -82,9 +82,16 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_patch_fwd_kernel(dk_patch_p
         r0 = tile_n / p.tiles_per_img;
         p0 = (tile_n - r0 * p.tiles_per_img) * BN;
         ho_a = p0 / p.Wo;
-    } else {
+    } else if (p.multi == 1) {
         r0 = tile_n * p.IPT;
         p0 = 0;
+        ho_a = 0;
+    } else {
+        // BN consecutive pixels of the whole batch, starting anywhere in image r0: no column of
+        // a tile is wasted whatever the image size; the patch holds every image they touch
+        const long long g0 = (long long)tile_n * BN;
+        r0 = (int)(g0 / p.HoWo);
+        p0 = (int)(g0 - (long long)r0 * p.HoWo);
         ho_a = 0;
     }
     const int ih_a = ho_a * p.stride - p.pad;
@@ -99,11 +106,14 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_patch_fwd_kernel(dk_patch_p
         bool ok;
         if (!p.multi) {
             img_l = 0; pix = p0 + jn; ok = pix < p.HoWo;
-        } else {
+        } else if (p.multi == 1) {
             img_l = jn / p.HoWo; pix = jn - img_l * p.HoWo;
             ok = jn < p.BN_eff && r0 + img_l < p.R;
+        } else {
+            img_l = (p0 + jn) / p.HoWo; pix = p0 + jn - img_l * p.HoWo;
+            ok = r0 + img_l < p.R;
         }
-        if (!ok) { img_l = 0; pix = p0; }
+        if (!ok) { img_l = 0; pix = p.multi == 2 ? 0 : p0; }
         const int ho = pix / p.Wo, wo = pix - ho * p.Wo;
         fbase[ni] = img_l * CB * p.PLANE + (ho - ho_a) * p.stride * p.PW + p.LPAD - p.pad +
                     wo * p.stride + lh * (CB / 2) * p.PLANE;
@@ -311,9 +321,16 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_quad_fwd_kernel(dk_patch_pa
         r0 = tile_n / p.tiles_per_img;
         p0 = (tile_n - r0 * p.tiles_per_img) * BN;
         ho_a = p0 / p.Wo;
-    } else {
+    } else if (p.multi == 1) {
         r0 = tile_n * p.IPT;
         p0 = 0;
+        ho_a = 0;
+    } else {
+        // BN consecutive pixels of the whole batch, starting anywhere in image r0: no column of
+        // a tile is wasted whatever the image size; the patch holds every image they touch
+        const long long g0 = (long long)tile_n * BN;
+        r0 = (int)(g0 / p.HoWo);
+        p0 = (int)(g0 - (long long)r0 * p.HoWo);
         ho_a = 0;
     }
     const int ih_a = ho_a - p.pad;
@@ -532,7 +549,7 @@ inline int round_up(int v, int a) { return (v + a - 1) / a * a; }
 // Tile geometry for one configuration; returns false if the layer does not
 // fit this kernel family (the caller then uses the generic implicit GEMM).
 template <class C>
-bool plan_cfg(const dk_geom &g, long long R, bool x_aligned16, dk_patch_plan *pl)
+bool plan_cfg(const dk_geom &g, long long R, bool x_aligned16, dk_patch_plan *pl, bool sliding = false)
 {
     dk_patch_params &p = pl->p;
     p = dk_patch_params();
@@ -542,7 +559,17 @@ bool plan_cfg(const dk_geom &g, long long R, bool x_aligned16, dk_patch_plan *pl
     p.Ho = g.Ho; p.Wo = g.Wo; p.HoWo = HoWo; p.R = (int)R;
     p.img_g = (int)g.n;
     int n_img, rows_spanned;
-    if (HoWo >= C::bn) {
+    if (sliding) {
+        // tiles of bn consecutive pixels of the batch; whole images in the patch
+        p.multi = 2; p.BN_eff = C::bn;
+        n_img = (C::bn - 1 + HoWo - 1) / HoWo + 1;      // images a tile can touch
+        p.IPT = n_img;
+        p.tiles_per_img = 0;
+        const long long tn = (R * HoWo + C::bn - 1) / C::bn;
+        if (tn >= (1ll << 30) || (long long)n_img * g.n >= (1ll << 30)) return false;
+        p.tiles_n = (int)tn;
+        rows_spanned = g.Ho;
+    } else if (HoWo >= C::bn) {
         p.multi = 0; p.IPT = 1; p.BN_eff = C::bn;
         p.tiles_per_img = (HoWo + C::bn - 1) / C::bn;
         p.tiles_n = (int)(R * p.tiles_per_img);
@@ -651,6 +678,13 @@ bool dk_patch_fwd_plan(const dk_geom &g, long long R, bool aligned16, dk_patch_p
         pl->flat = g.Co <= 64;
         if (aligned16 && (pl->flat ? plan_quad<Q3Flat>(g, R, pl) : plan_quad<Q3Sq>(g, R, pl))) return true;
         pl->quad = false;
+        // columns of the per-image tilings that carry pixels; below nine tenths, tiles that
+        // slide over the batch are tried first (they need whole images in LDS)
+        const int bn = pl->flat ? P3Flat::bn : P3Sq::bn;
+        const int HoWo = g.Ho * g.Wo;
+        const double used = HoWo >= bn ? (double)HoWo / ((HoWo + bn - 1) / bn * bn) : (double)(bn / HoWo * HoWo) / bn;
+        if (used < 0.9 && (pl->flat ? plan_cfg<P3Flat>(g, R, aligned16, pl, true) : plan_cfg<P3Sq>(g, R, aligned16, pl, true)))
+            return true;
         return pl->flat ? plan_cfg<P3Flat>(g, R, aligned16, pl) : plan_cfg<P3Sq>(g, R, aligned16, pl);
     }
     return false;

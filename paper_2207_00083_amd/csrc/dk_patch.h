@@ -10,7 +10,7 @@ struct dk_patch_params {
     float *part;        // split-K partial sums [splits][out_elems]
     int Ci, Co, H, W, stride, pad, Ho, Wo, HoWo, R;
     int img_g;          // Ci*H*W
-    int multi;          // 0: a tile is BN pixels of one image; 1: IPT whole images
+    int multi;          // 0: a tile is BN pixels of one image; 1: IPT whole images; 2: BN pixels of the batch
     int IPT, BN_eff, tiles_per_img;
     int PH, PW, PLANE, LPAD;      // patch rows, row pitch, plane size, left pad (floats)
     int patch_floats;             // LDS floats of the patch region
