@@ -176,7 +176,7 @@ struct LoadDgradClass {
         const int tn = na * nb;
         const long long bytes = (long long)(a.Q / UV) * a.Co * a.Ho * a.Wo * 4;
         fast = BK % tn == 0 && bytes <= DK_RSRC_MAX;
-        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
+        rs = dk_uniform_rsrc(a.p, (int)bytes);
         step_bytes = 4u * (unsigned)(BK / tn) * (unsigned)(a.Ho * a.Wo);
 #pragma unroll
         for (int e = 0; e < NE; ++e) {
@@ -241,7 +241,7 @@ struct LoadDeltaQ {
         p = a.p; Co = a.Co; HoWo = a.HoWo; Q = a.Q; row0 = row0_; kq = tid % BK; rsub = tid / BK;
         const long long bytes = (long long)(a.Q / a.HoWo) * a.Co * a.HoWo * 4;
         fast = bytes <= DK_RSRC_MAX && HoWo >= BK;
-        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
+        rs = dk_uniform_rsrc(a.p, (int)bytes);
 #pragma unroll
         for (int e = 0; e < NE; ++e) {
             const int co = row0 + rsub + e * RSTEP;
@@ -313,7 +313,7 @@ struct LoadIm2colQ {
         kq = tid % BK; rsub = tid / BK;
         const long long bytes = (long long)(a.Q / a.HoWo) * a.img * 4;
         fast = bytes <= DK_RSRC_MAX && HoWo >= BK && HoWo < 65536 && Wo > 1;
-        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
+        rs = dk_uniform_rsrc(a.p, (int)bytes);
         wo_magic = (unsigned)((0x100000000ull + (unsigned)Wo - 1) / (unsigned)Wo);
         cur_kt = -2; cur_pix = 0; cur_img = 0;
 #pragma unroll
@@ -420,7 +420,7 @@ struct LoadKMajorImg {
         // whole tensor as one resource: [R][C][chs]
         const long long bytes = (long long)(a.Q / a.HW) * a.C * a.chs * 4;
         fast = VEC && bytes <= DK_RSRC_MAX;
-        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
+        rs = dk_uniform_rsrc(a.p, (int)bytes);
 #pragma unroll
         for (int e = 0; e < N4; ++e) {
             const int kr = (tid + e * NT) / PER_K;
@@ -486,7 +486,7 @@ struct LoadRowMajorKImg {
         p = a.p; C = a.C; HW = a.HW; Q = a.Q; row0 = row0_; tid = tid_;
         const long long bytes = (long long)(a.Q / a.HW) * a.C * a.HW * 4;
         fast = bytes <= DK_RSRC_MAX && HW >= BK;
-        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
+        rs = dk_uniform_rsrc(a.p, (int)bytes);
 #pragma unroll
         for (int e = 0; e < N4; ++e) {
             const int row = row0 + (tid + e * NT) / PER_ROW;
@@ -737,8 +737,14 @@ __global__ __launch_bounds__(C::NT) void contract_kernel(typename LA::Params pa,
 }
 
 // Several independent contractions of the same kind in one launch (each too
-// small to fill the chip alone): workgroup b serves run c with
-// first[c] <= b < first[c + 1].
+// small to fill the chip alone).  The hardware deals workgroups to the eight
+// XCDs in turn, so workgroup b is slot b / 8 of XCD b % 8; every XCD walks the
+// runs in the order given (longest tiles first) and takes a contiguous eighth
+// of each run's tiles (neighbours share operand panels in its L2): run c owns
+// slots first[c] .. first[c + 1] - 1 of every XCD, slot s of XCD x being tile
+// x (first[c + 1] - first[c]) + s - first[c]; slots past the run's last tile
+// do nothing.  (One contiguous range of workgroups per run put all the long
+// tiles on the first XCDs: twice the time for the strided data gradient.)
 constexpr int DK_MAX_BATCH = 9;
 template <class LA, class LB, class EP>
 struct ContractBatch {
@@ -753,10 +759,16 @@ struct ContractBatch {
 template <class C, class LA, class LB, class EP>
 __global__ __launch_bounds__(C::NT) void contract_batch_kernel(ContractBatch<LA, LB, EP> b)
 {
-    const int bid = dk_xcd_block();
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     int c = 0;
-    while (c + 1 < b.count && bid >= b.first[c + 1]) ++c;      // wave-uniform
-    contract_tile<C, LA, LB, EP>(b.pa[c], b.pb[c], b.ep[c], b.rp[c], bid - b.first[c]);
+    while (c + 1 < b.count && slot >= b.first[c + 1]) ++c;
+    // wave-uniform, and the compiler has to know: taken for divergent, the run's parameters
+    // land in vector registers and every buffer load is wrapped in a loop over the distinct
+    // resource descriptors of the wave
+    c = __builtin_amdgcn_readfirstlane(c);
+    const int tile = xcd * (b.first[c + 1] - b.first[c]) + slot - b.first[c];
+    if (tile >= b.rp[c].tiles_m * b.rp[c].tiles_n * b.rp[c].splits) return;
+    contract_tile<C, LA, LB, EP>(b.pa[c], b.pb[c], b.ep[c], b.rp[c], tile);
 }
 
 // out[i] = (accumulate ? out[i] : 0) + alpha * sum_s part[s][i].  The order of
@@ -1610,7 +1622,7 @@ dk_status run_dgrad_classes(const dk_geom &g, const dgrad_class *cl, int ncl, co
     using LB = LoadDgradClass<C::BN, C::BK, C::NT, C::LDB>;
     ContractBatch<LA, LB, EpiDgradClass> b;
     b.count = 0;
-    long long blocks = 0;
+    long long slots = 0;
     // classes with the most taps first: their tiles take longest and must not start last
     int order[9];
     for (int i = 0; i < ncl; ++i) order[i] = i;
@@ -1634,14 +1646,14 @@ dk_status run_dgrad_classes(const dk_geom &g, const dgrad_class *cl, int ncl, co
         rp.splits = 1;          // the epilogue scatters into dx: no partial sums
         rp.alpha = 1.0f; rp.accumulate = 0;
         rp.out = dx; rp.part = nullptr; rp.out_elems = R * g.n;
-        b.first[k] = (int)blocks;
-        blocks += (long long)rp.tiles_m * rp.tiles_n;
+        b.first[k] = (int)slots;
+        slots += ((long long)rp.tiles_m * rp.tiles_n + 7) / 8;       // per XCD
     }
     if (b.count == 0) return DK_OK;
-    DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
-    for (int k = b.count; k <= DK_MAX_BATCH; ++k) b.first[k] = (int)blocks;
+    DK_REQUIRE(slots * 8 <= 0x7fffffffll, DK_ERR_SHAPE);
+    for (int k = b.count; k <= DK_MAX_BATCH; ++k) b.first[k] = (int)slots;
     dk_prof_scope ps("contract_conv_dgrad_classes", st);
-    contract_batch_kernel<C, LA, LB, EpiDgradClass><<<dim3((unsigned)blocks), dim3(C::NT), 0, st>>>(b);
+    contract_batch_kernel<C, LA, LB, EpiDgradClass><<<dim3((unsigned)(slots * 8)), dim3(C::NT), 0, st>>>(b);
     return dk_launch_status();
 }
 

@@ -17,6 +17,19 @@ constexpr int DK_RSRC_FLAGS = 0x00020000;         // raw buffer resource, gfx9 f
 constexpr unsigned DK_OOB = 0x80000000u;          // beyond any resource range used here
 constexpr long long DK_RSRC_MAX = 0x7fffffffll;   // largest operand (bytes) the fast path takes
 
+// A resource over `bytes` bytes at p.  Both are wave-uniform by construction, but a size
+// that went through an integer division was computed on the vector ALU, and a resource in
+// vector registers makes the compiler wrap every load in a loop over the wave's distinct
+// descriptors: pin the words to scalar registers.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t dk_uniform_rsrc(const float *p, int bytes)
+{
+    const unsigned long long a = reinterpret_cast<unsigned long long>(p);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<float *>(((unsigned long long)hi << 32) | lo), 0,
+                                             __builtin_amdgcn_readfirstlane(bytes), DK_RSRC_FLAGS);
+}
+
 __device__ __forceinline__ float4 dk_buffer_load4(__amdgpu_buffer_rsrc_t rs, unsigned voff, unsigned soff)
 {
     const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)voff, (int)soff, 0));
@@ -66,7 +79,7 @@ struct LoadKMajor {
         p = a.p; ld = a.ld; rows = a.rows; kdim = a.kdim; row0 = row0_; tid = tid_;
         const long long bytes = (long long)a.kdim * a.ld * 4;
         fast = VEC && bytes <= DK_RSRC_MAX;
-        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
+        rs = dk_uniform_rsrc(a.p, (int)bytes);
 #pragma unroll
         for (int e = 0; e < N4; ++e) {
             const int idx = tid + e * NT;
@@ -79,7 +92,7 @@ struct LoadKMajor {
     __device__ __forceinline__ void rebase(const float *np)
     {
         p = np;
-        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(np), 0, (int)((long long)kdim * ld * 4), DK_RSRC_FLAGS);
+        rs = dk_uniform_rsrc(np, (int)((long long)kdim * ld * 4));
     }
 
     __device__ __forceinline__ void load(int kt)
@@ -138,7 +151,7 @@ struct LoadRowMajorK {
         p = a.p; ld = a.ld; rows = a.rows; kdim = a.kdim; row0 = row0_; tid = tid_;
         const long long bytes = (long long)a.rows * a.ld * 4;
         fast = VEC && bytes <= DK_RSRC_MAX;
-        rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.p), 0, (int)bytes, DK_RSRC_FLAGS);
+        rs = dk_uniform_rsrc(a.p, (int)bytes);
 #pragma unroll
         for (int e = 0; e < N4; ++e) {
             const int idx = tid + e * NT;
