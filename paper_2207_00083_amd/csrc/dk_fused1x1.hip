@@ -154,6 +154,109 @@ __global__ __launch_bounds__(FwdCfg::NT) void fused1x1_fwd_kernel(fused_fwd_para
                                         p.resid);
 }
 
+// The same for at most 64 input channels: the whole contraction is one step.  The filter
+// tile goes to LDS once and serves all K + 2 encodings; an encoding is one 64 x 64 image tile,
+// one barrier and 32 MFMAs per wave (the general kernel reloads the filter tile with every
+// encoding and synchronises every 8 MFMAs, and its loader arithmetic weighs as much as its
+// matrix work).  Same order of operations per output, so the same bits.
+template <int K>
+__global__ __launch_bounds__(FwdCfg::NT) void fused1x1_fwd64_kernel(fused_fwd_params p)
+{
+    constexpr int S = K + 2;
+    constexpr int BM = 64, BN = 64, BKW = 64, NT = FwdCfg::NT, LDA = BM + 4, LDB = BN + 4;
+    __shared__ __attribute__((aligned(16))) float lds[BKW * LDA + 2 * BKW * LDB];
+    float *const As = lds;
+    float *const Bs = lds + BKW * LDA;          // two buffers of BKW * LDB floats
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave % 2) * 32, wn0 = (wave / 2) * 32;
+    const int li = lane & 31, lh = lane >> 5;
+
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int bid = dk_xcd_block();
+    const int g = bid / tiles;
+    const int t = bid - g * tiles;
+    const int tile_n = t / p.tiles_m, tile_m = t - tile_n * p.tiles_m;
+    const int row0 = tile_m * BM, col0 = tile_n * BN;
+
+    using LA = LoadRowMajorK<BM, BKW, NT, LDA, true>;       // W[Co][Ci]: rows = co, k = ci
+    using LB = LoadKMajor<BN, BKW, NT, LDB, true>;          // image [Ci][HW]: k = ci, rows = pixel
+    const long long img = (long long)p.Ci * p.HW;
+    const float *img0 = p.xbar + (long long)g * S * img;
+    LA la; LB lb;
+    la.init(MatParams{p.W, p.Ci, p.Co, p.Ci}, row0, tid);
+    lb.init(MatParams{img0, p.HW, p.HW, p.Ci}, col0, tid);
+
+    f32x16 Tt, Sa, Y[K];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { Tt[v] = 0.0f; Sa[v] = 0.0f; }
+#pragma unroll
+    for (int i = 0; i < K; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) Y[i][v] = 0.0f;
+
+    la.load(0); lb.load(0);
+    la.store(As); lb.store(Bs);
+    __syncthreads();
+    const float *a_s = As + lh * LDA + wm0 + li;
+    for (int j = 0; j < S; ++j) {
+        const int cur = j & 1;
+        if (j + 1 < S) {
+            lb.rebase(img0 + (long long)(j + 1) * img);            // next encoding of the batch
+            lb.load(0);
+        }
+        // coefficients of this encoding (scalar loads, back before the MFMAs are through)
+        const float nj = p.nvec[(long long)g * S + j];
+        float cj[K];
+#pragma unroll
+        for (int i = 0; i < K; ++i) cj[i] = p.Ainv[((long long)g * S + j) * S + i];
+        const float *b_s = Bs + cur * (BKW * LDB) + lh * LDB + wn0 + li;
+        f32x16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+        for (int kk = 0; kk < BKW; kk += 2)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_s[kk * LDA], b_s[kk * LDB], acc, 0, 0, 0);
+        if (j + 1 < S) lb.store(Bs + (cur ^ 1) * (BKW * LDB));
+        // fold the encoding's tile into the decoded tiles (a product for j = 0, fused
+        // multiply-adds after it: the decoding kernel's operations) and the integrity sums
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float a = acc[v];
+#pragma unroll
+            for (int i = 0; i < K; ++i) Y[i][v] = fmaf(cj[i], a, Y[i][v]);
+            const float pr = nj * a;
+            Tt[v] += pr;
+            Sa[v] += fabsf(pr);
+        }
+        __syncthreads();
+    }
+
+    const int col = col0 + wn0 + li;
+    float tmax = 0.0f, smax = 0.0f;
+    bool bad = false;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        bad |= !(Sa[v] <= 3.402823466e+38f) || !(fabsf(Tt[v]) <= 3.402823466e+38f);
+        tmax = fmaxf(tmax, fabsf(Tt[v]));
+        smax = fmaxf(smax, Sa[v]);
+    }
+    if (col < p.HW) {
+#pragma unroll
+        for (int i = 0; i < K; ++i) {
+            float *dst = p.y + ((long long)g * K + i) * p.Co * p.HW + col;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + wm0 + 8 * (v / 4) + 4 * lh + (v % 4);
+                if (row < p.Co) dst[(long long)row * p.HW] = Y[i][v];
+            }
+        }
+    }
+    dk_verify_publish_and_finish<NT>(tmax, smax, bad, p.slots, g, t, tiles, p.tag, p.tol, p.verdict,
+                                     p.resid);
+}
+
 // ---------------------------------------------------------------------------
 // weight gradient with the gradient mixing in the operand loader
 // ---------------------------------------------------------------------------
@@ -487,7 +590,8 @@ dk_status dk_fused1x1_fwd_run(const dk_geom &g, const float *W, const float *xba
     dk_prof_scope ps("fused1x1_fwd_decode_verify", st);
 #define DK_FF(KK)                                                                  \
     do {                                                                           \
-        if (vec) fused1x1_fwd_kernel<KK, true><<<grid, block, 0, st>>>(p);         \
+        if (vec && g.Ci <= 64) fused1x1_fwd64_kernel<KK><<<grid, block, 0, st>>>(p); \
+        else if (vec) fused1x1_fwd_kernel<KK, true><<<grid, block, 0, st>>>(p);    \
         else fused1x1_fwd_kernel<KK, false><<<grid, block, 0, st>>>(p);            \
     } while (0)
     if (K == 2) DK_FF(2); else if (K == 4) DK_FF(4); else DK_FF(8);
