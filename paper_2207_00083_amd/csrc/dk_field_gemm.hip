@@ -1105,7 +1105,8 @@ bool plan_fgemm(long long I, long long J, long long K, fgemm_plan *pl, bool sums
 {
     const int max_kslice = sums ? MAX_KSPLIT_SUMS : MAX_KSPLIT;
     pl->sums = sums ? 1 : 0;
-    if (I < 1 || J < 1 || K < 1 || I > (1 << 24) || J > (1 << 24) || K > (1 << 26)) return false;
+    // (128 rows of Kp bytes are one buffer resource and a lane's offsets in it are 32-bit: Kp < 2^24)
+    if (I < 1 || J < 1 || K < 1 || I > (1 << 24) || J > (1 << 24) || K > (1 << 24) - KT) return false;
     pl->I = (int)I; pl->J = (int)J; pl->K = (int)K;
     pl->nbi = (I % 128 != 0 && I % 128 <= 64) ? 1 : 2;      // a last half-empty 128-row tile: use 64-row tiles
     pl->I_pad = round_up((int)I, 64 * pl->nbi);
