@@ -200,6 +200,12 @@ CONV_CASES = [
     (5, 7, 6, 6, 3, 1, 0, 2),
     (130, 20, 4, 4, 3, 1, 1, 3),
     (32, 40, 2, 2, 3, 1, 1, 12),
+    # pixel tiles that slide over the batch (images of 100, 196, 49 and 99 pixels; ragged last tile)
+    (16, 64, 10, 10, 3, 1, 1, 7),
+    (24, 136, 14, 14, 3, 1, 1, 5),
+    (8, 130, 7, 7, 3, 1, 1, 9),
+    (12, 72, 11, 9, 3, 1, 1, 6),
+    (10, 48, 13, 13, 3, 1, 0, 4),
 ]
 
 
