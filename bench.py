@@ -180,7 +180,7 @@ def field_cpu_baseline(d, budget_s=15.0):
 
 def field_main(args):
     """The finite-field variant of a layer:
-    dkf_quantize(W) -> dkf_encode -> dkf_linear_fwd | dkf_conv_fwd -> dkf_decode_verify -> dkf_wgrad."""
+    dkf_encode -> dkf_linear_fwd_w | dkf_quantize(W), dkf_conv_fwd -> dkf_decode_verify -> dkf_wgrad."""
     import torch
     import paper_2207_00083_amd as dk
     dk.load()
@@ -216,7 +216,8 @@ def field_main(args):
 
     def step(ev=None):
         if ev: ev[0].record()
-        dk.dkf_quantize(W, xq=Wq)
+        if conv:
+            dk.dkf_quantize(W, xq=Wq)
         if ev: ev[1].record()
         if args.rng_noise:
             dk.dkf_encode_rng(X, A_d, K, 20220701, xbar=xbar)
@@ -226,7 +227,8 @@ def field_main(args):
         if conv:
             dk.dkf_conv_fwd(L, Wq, xbar, ybar=ybar, ws=ws_f)
         else:
-            dk.dkf_linear_fwd(Wq, xbar, ybar=ybar, ws=ws_f)
+            # dense layers: the weights are quantised where they are split into digits (no W_q round trip)
+            dk.dkf_linear_fwd_w(W, xbar, ybar=ybar, ws=ws_f)
         if ev: ev[3].record()
         dk.dkf_decode_verify(ybar, Ainv_d, nvec_d, K, y=y, verdict=verdict)
         if ev: ev[4].record()

@@ -89,6 +89,15 @@ dk_status dkf_encode_rng(const float *x, const uint32_t *A, uint32_t *xbar, int 
 dk_status dkf_linear_fwd(const uint32_t *Wq, const uint32_t *xbar, uint32_t *ybar,
                          int M, int N, int R, void *ws, size_t ws_bytes, void *stream);
 
+/* The same with the weights given as real values W[M][N] (float, device):
+ * W_q = Field(Round(W 2^l)) of the quantisation algorithm is formed where the
+ * weights are split into digits, so the quantised matrix is never written
+ * (for a weight matrix that changes with every step this saves its round trip
+ * through memory).  Same result as dkf_quantize followed by dkf_linear_fwd,
+ * same workspace. */
+dk_status dkf_linear_fwd_w(const float *W, int l, const uint32_t *xbar, uint32_t *ybar,
+                           int M, int N, int R, void *ws, size_t ws_bytes, void *stream);
+
 /* The same step for a convolution layer (kind DK_CONV2D): NCHW
  * cross-correlation without bias over the field,
  *   ybar[rho][co][h][w] = sum_{ci,a,b} Wq[co][ci][a][b]

@@ -15,14 +15,14 @@ from .binding import (DkError, DkLayer, lib_path, load, dk_version, dk_status_st
                       dk_coeffs_m, dk_encode_m, dk_decode_verify_m, dk_wgrad_m, dk_noise_rng, dk_encode_rng, dk_dgrad,
                       DK_OP_FWD, DK_OP_WGRAD, DK_OP_VERIFY, DK_MAX_K)
 
-from .field import (DKF_P, DKF_L, dkf_coeffs, dkf_quantize, dkf_dequantize, dkf_encode, dkf_linear_fwd,
+from .field import (DKF_P, DKF_L, dkf_coeffs, dkf_quantize, dkf_dequantize, dkf_encode, dkf_linear_fwd, dkf_linear_fwd_w,
                     dkf_decode_verify, dkf_wgrad, dkf_fwd_workspace_bytes, dkf_wgrad_workspace_bytes,
                     dkf_conv_fwd, dkf_conv_fwd_workspace_bytes, dkf_noise_rng, dkf_encode_rng, dkf_norm_scales,
                     dkf_coeffs_m, dkf_encode_m, dkf_decode_verify_m, dkf_wgrad_m, dkf_wgrad_workspace_bytes_m,
                     dkf_add_bias)
 
 __all__ = ["DKF_P", "DKF_L", "dkf_coeffs", "dkf_quantize", "dkf_dequantize", "dkf_encode",
-           "dkf_linear_fwd", "dkf_decode_verify", "dkf_wgrad", "dkf_fwd_workspace_bytes",
+           "dkf_linear_fwd", "dkf_linear_fwd_w", "dkf_decode_verify", "dkf_wgrad", "dkf_fwd_workspace_bytes",
            "dkf_wgrad_workspace_bytes", "dkf_conv_fwd", "dkf_conv_fwd_workspace_bytes",
            "DkError", "DkLayer", "lib_path", "load", "dk_version", "dk_status_str",
            "dk_workspace_bytes", "dk_layer_in_len", "dk_layer_out_len", "dk_coeffs",

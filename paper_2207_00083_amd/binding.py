@@ -98,6 +98,7 @@ def load():
         "dkf_dequantize": (ip, [vp, vp, ll, ip, vp]),
         "dkf_encode": (ip, [vp, vp, vp, vp, ip, ip, ll, ip, vp]),
         "dkf_linear_fwd": (ip, [vp, vp, vp, ip, ip, ip, vp, sz, vp]),
+        "dkf_linear_fwd_w": (ip, [vp, ip, vp, vp, ip, ip, ip, vp, sz, vp]),
         "dkf_decode_verify": (ip, [vp, vp, vp, vp, vp, vp, ip, ip, ll, ip, vp]),
         "dkf_wgrad": (ip, [LP, vp, vp, vp, vp, vp, vp, ip, ip, ip, fl, ip, vp, sz, vp]),
         "dkf_conv_fwd": (ip, [LP, vp, vp, vp, ip, vp, sz, vp]),

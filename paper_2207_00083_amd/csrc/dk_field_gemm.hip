@@ -153,11 +153,14 @@ __device__ __forceinline__ void raise_flag(int *flag, bool mine)
 // Row-major operand src[rows][K] -> planes[4][rows_pad][Kp].  A workgroup
 // converts 4096 consecutive k of one row, a thread sixteen (four 16-byte loads
 // in flight, one 16-byte store per plane); rows and k beyond the operand are
-// written as zeros.
-__global__ __launch_bounds__(256) void f_digits_kernel(const uint32_t *__restrict__ src,
+// written as zeros.  F32: the source holds real values and the field elements
+// Field(Round(x scale)) are formed here, so the quantised operand never exists
+// in memory.
+template <bool F32>
+__global__ __launch_bounds__(256) void f_digits_kernel(const void *__restrict__ src_,
                                                        int8_t *__restrict__ planes, int rows, int K,
                                                        int rows_pad, int Kp, int chunks, int vec,
-                                                       int *flag)
+                                                       double scale, int *flag)
 {
     const int row = blockIdx.x / chunks;                       // workgroup-uniform
     const int k0 = ((blockIdx.x - row * chunks) * 256 + threadIdx.x) * 16;
@@ -166,7 +169,7 @@ __global__ __launch_bounds__(256) void f_digits_kernel(const uint32_t *__restric
 #pragma unroll
     for (int c = 0; c < 16; ++c) v[c] = 0;
     if (row < rows) {
-        const uint32_t *s = src + (long long)row * K + k0;
+        const uint32_t *s = static_cast<const uint32_t *>(src_) + (long long)row * K + k0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             if (vec && k0 + 4 * q + 3 < K) {
@@ -177,6 +180,11 @@ __global__ __launch_bounds__(256) void f_digits_kernel(const uint32_t *__restric
                 for (int c = 4 * q; c < 4 * q + 4; ++c)
                     if (k0 + c < K) v[c] = s[c];
             }
+        }
+        if (F32) {
+#pragma unroll
+            for (int c = 0; c < 16; ++c)
+                if (k0 + c < K) v[c] = dkf_quant(__uint_as_float(v[c]), scale);
         }
     }
     // (the digits of 0 are 0, so absent elements need no flag of their own)
@@ -1229,8 +1237,22 @@ dk_status run_digits(const uint32_t *src, int8_t *planes, int rows, int K, int r
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     const int vec = (K % 4 == 0) && dk_aligned(src, 16);
     dk_prof_scope ps("f_digits", st);
-    f_digits_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(src, planes, rows, K, rows_pad, Kp,
-                                                                  chunks, vec, flag);
+    f_digits_kernel<false><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(src, planes, rows, K, rows_pad, Kp,
+                                                                         chunks, vec, 1.0, flag);
+    return dk_launch_status();
+}
+
+// ... of real values, quantised with l fractional bits on the way
+dk_status run_digits_f32(const float *src, int l, int8_t *planes, int rows, int K, int rows_pad, int Kp,
+                         int *flag, hipStream_t st)
+{
+    const int chunks = (Kp + 4095) / 4096;
+    const long long blocks = (long long)rows_pad * chunks;
+    DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
+    const int vec = (K % 4 == 0) && dk_aligned(src, 16);
+    dk_prof_scope ps("f_digits_quantize", st);
+    f_digits_kernel<true><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(src, planes, rows, K, rows_pad, Kp,
+                                                                        chunks, vec, ldexp(1.0, l), flag);
     return dk_launch_status();
 }
 
@@ -1431,14 +1453,17 @@ DK_EXPORT size_t dkf_wgrad_workspace_bytes(const dk_layer *L, int G, int K)
     return dkf_wgrad_workspace_bytes_m(L, G, K, 1);
 }
 
-DK_EXPORT dk_status dkf_linear_fwd(const uint32_t *Wq, const uint32_t *xbar, uint32_t *ybar,
-                                   int M, int N, int R, void *ws, size_t ws_bytes, void *stream)
+namespace {
+
+// Wq or W (real values, quantised with l fractional bits inside the digit kernel)
+dk_status linear_fwd_impl(const uint32_t *Wq, const float *W, int l, const uint32_t *xbar, uint32_t *ybar,
+                          int M, int N, int R, void *ws, size_t ws_bytes, void *stream)
 {
-    DK_REQUIRE(Wq && xbar && ybar, DK_ERR_NULL);
-    DK_REQUIRE(M >= 1 && N >= 1 && R >= 1, DK_ERR_SHAPE);
+    DK_REQUIRE((Wq || W) && xbar && ybar, DK_ERR_NULL);
+    DK_REQUIRE(M >= 1 && N >= 1 && R >= 1 && l >= 0 && l <= DKF_MAX_L, DK_ERR_SHAPE);
     fgemm_plan pl;
     DK_REQUIRE(plan_fgemm(R, M, N, &pl), DK_ERR_SHAPE);
-    DK_REQUIRE(dk_aligned(Wq, 4) && dk_aligned(xbar, 4) && dk_aligned(ybar, 4), DK_ERR_ALIGN);
+    DK_REQUIRE(dk_aligned(Wq, 4) && dk_aligned(W, 4) && dk_aligned(xbar, 4) && dk_aligned(ybar, 4), DK_ERR_ALIGN);
     DK_REQUIRE(ws && ws_bytes >= FLAG_BYTES + pl.a_bytes + pl.b_bytes + pl.part_bytes, DK_ERR_WORKSPACE);
     DK_REQUIRE(dk_aligned(ws, 256), DK_ERR_ALIGN);
     hipStream_t st = (hipStream_t)stream;
@@ -1456,9 +1481,26 @@ DK_EXPORT dk_status dkf_linear_fwd(const uint32_t *Wq, const uint32_t *xbar, uin
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
     dk_status s = run_digits(xbar, Ap, R, N, pl.I_pad, pl.Kp, flag, st);
     if (s != DK_OK) return s;
-    s = run_digits(Wq, Bp, M, N, pl.J_pad, pl.Kp, flag + 1, st);
+    s = Wq ? run_digits(Wq, Bp, M, N, pl.J_pad, pl.Kp, flag + 1, st)
+           : run_digits_f32(W, l, Bp, M, N, pl.J_pad, pl.Kp, flag + 1, st);
     if (s != DK_OK) return s;
     return run_fgemm(pl, Ap, Bp, part, flag, ybar, nullptr, 0, 1.0f, 0, 0, "f_gemm_fwd", st);
+}
+
+} // namespace
+
+DK_EXPORT dk_status dkf_linear_fwd(const uint32_t *Wq, const uint32_t *xbar, uint32_t *ybar,
+                                   int M, int N, int R, void *ws, size_t ws_bytes, void *stream)
+{
+    DK_REQUIRE(Wq, DK_ERR_NULL);
+    return linear_fwd_impl(Wq, nullptr, 0, xbar, ybar, M, N, R, ws, ws_bytes, stream);
+}
+
+DK_EXPORT dk_status dkf_linear_fwd_w(const float *W, int l, const uint32_t *xbar, uint32_t *ybar,
+                                     int M, int N, int R, void *ws, size_t ws_bytes, void *stream)
+{
+    DK_REQUIRE(W, DK_ERR_NULL);
+    return linear_fwd_impl(nullptr, W, l, xbar, ybar, M, N, R, ws, ws_bytes, stream);
 }
 
 namespace {

@@ -187,6 +187,25 @@ def dkf_linear_fwd(Wq, xbar, ybar=None, ws=None, stream=None):
     return ybar
 
 
+def dkf_linear_fwd_w(W, xbar, l=DKF_L, ybar=None, ws=None, stream=None):
+    """W[M,N] float, xbar[R,N] field elements (device) -> ybar[R,M]; the weights are quantised on the way."""
+    W, xbar = _dev(W, "W"), _fe(xbar, "xbar")
+    M, N = W.shape
+    R = xbar.shape[0]
+    if xbar[0].numel() != N:
+        raise ValueError("dkf_linear_fwd_w: inconsistent shapes")
+    if ybar is None:
+        ybar = _new_fe((R, M), xbar)
+    _fe(ybar, "ybar")
+    if ybar.numel() != R * M:
+        raise ValueError("dkf_linear_fwd_w: ybar has the wrong size")
+    if ws is None:
+        ws = _workspace(dkf_fwd_workspace_bytes(M, N, R), xbar, stream)
+    _check(load().dkf_linear_fwd_w(_ptr(W), int(l), _ptr(xbar), _ptr(ybar), M, N, R, _ptr(ws), ws.numel(),
+                                   _stream(stream)), "dkf_linear_fwd_w")
+    return ybar
+
+
 def dkf_conv_fwd_workspace_bytes(layer, R) -> int:
     return int(load().dkf_conv_fwd_workspace_bytes(C.byref(DkLayer.of(layer)), int(R)))
 

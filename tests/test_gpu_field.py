@@ -351,3 +351,17 @@ def test_field_arguments_refused(dk):
     conv = dk_inputs.conv(4, 4, 8, 8, 3)
     assert dk.dkf_wgrad_workspace_bytes(conv, 1, 2) > 0 and dk.dkf_conv_fwd_workspace_bytes(conv, 4) > 0
     assert dk.dkf_conv_fwd_workspace_bytes(dk_inputs.linear(4, 4), 4) == 0
+
+
+@pytest.mark.parametrize("M,N,R,l", [(40, 200, 12, 8), (130, 515, 7, 8), (64, 4096, 20, 3), (16, 33, 5, 12)])
+def test_linear_forward_from_real_weights(dk, M, N, R, l):
+    """dkf_linear_fwd_w = dkf_quantize + dkf_linear_fwd, bit for bit, and the oracle's product."""
+    rng = np.random.default_rng([M, N, R, l])
+    W = rng.normal(0, 0.7, size=(M, N)).astype(np.float32)
+    W[0, 0] = 2.0 ** -(l + 1)                      # a tie of Round
+    W[M - 1, N - 1] = -3.5 * 2.0 ** -l
+    xbar = rng.integers(0, F.P, size=(R, N), dtype=np.uint32)
+    got = host(dk.dkf_linear_fwd_w(dev(W), dev(xbar), l=l))
+    two = host(dk.dkf_linear_fwd(dk.dkf_quantize(dev(W), l=l), dev(xbar)))
+    assert np.array_equal(got, two)
+    assert np.array_equal(got, F.dense_fwd(F.quantize(W, l=l), xbar))
