@@ -2,8 +2,9 @@
 // the spatial half of a depthwise-separable layer) and of the layer bias.
 // A few multiply-adds per element moved, so these are plain bandwidth-bound
 // kernels on the vector ALUs: products of two field elements are below 2^50,
-// up to 64 of them are summed in 64 bits and reduced once by folding with
-// 2^25 = 39 (mod p).
+// at most 49 (forward: the taps) or 32 (weight gradient: pixels between two
+// reductions) of them are summed in 64 bits and reduced once by folding with
+// 2^25 = 39 (mod p), which takes values below 2^56.
 #include "dk_field.h"
 
 namespace {

@@ -905,9 +905,9 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     // Outer loop: weight groups; inner loop: the steps of one group, a plain
     // pipelined MFMA loop that runs on across part and group boundaries, so only
     // the first tile of the workgroup waits for memory.  During step s the
-    // staging registers hold tile s+1 (its loads were issued before the barrier
-    // that opened step s); they go to the other LDS buffer during the last 32-k
-    // sub-step, and the loads of tile s+2 are issued right behind them.
+    // staging registers hold tile s+1; quarter by quarter, one per 32-k sub-step,
+    // they go to the other LDS buffer and are refilled from tile s+2, so every
+    // load has a whole step to arrive.
     int step = 0;
     while (step < nsteps) {
         const int w = DKF_GROUP(DKF_PART(pi));
