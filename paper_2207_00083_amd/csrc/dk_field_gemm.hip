@@ -719,19 +719,8 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     // share accumulators (one weight group).  With the sum planes and both high
     // halves present: (lo,lo), (sum,sum), (hi,hi), a group each.
     // Steps (part, k tile) form one software-pipelined sequence.
-    const bool three = p.sums && fa && fb;
-    int plist = 0, nparts = 0;           // four bits per active part
-    if (three) {
-        plist = 0x0 | 0xA << 4 | 0x5 << 8;
-        nparts = 3;
-    } else {
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            if (!((q & 1) && !fa) && !((q >> 1) && !fb)) plist |= ((q & 1) | (q >> 1) << 2) << (4 * nparts++);
-    }
 #define DKF_PART(I) ((plist >> (4 * (I))) & 15)
 #define DKF_GROUP(Q) ((Q) == 0xA ? 1 : ((Q) & 1) + ((Q) >> 2))
-    const int nsteps = nparts * (kt1 - kt0);
 
     i32x4 sa[NA], sb[8];
     // Stored operands are fetched with buffer loads: a resource per digit plane of the part
@@ -744,9 +733,10 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     unsigned voff[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) voff[q] = (unsigned)(32 * q) * (unsigned)p.Kp + s_off;
-#define DKF_FETCH_PART(PI)                                                                        \
+#define DKF_FETCH_PART(PI) DKF_FETCH_PART_Q(DKF_PART(PI))
+#define DKF_FETCH_PART_Q(Q)                                                                       \
     {                                                                                             \
-        const int q_ = DKF_PART(PI);                                                              \
+        const int q_ = (Q);                                                                       \
         const int8_t *a_ = p.Ap + 2 * (q_ & 3) * p.a_plane + (long long)ti * BI * p.Kp;           \
         rsA0 = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(a_), 0, BI * p.Kp, RSRC_FLAGS); \
         rsA1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(a_ + p.a_plane), 0, BI * p.Kp, RSRC_FLAGS); \
@@ -883,12 +873,25 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     }
     int pi = 0, kt = kt0;                 // part index and k tile of the current step
     int pi2 = 0, kt2 = kt0;               // ... of the step the next fetch is for
+    // The first part is (lo,lo) whatever the flags say: its first tile is on its way before
+    // the flags (a dependent scalar load) are looked at.
+    if (kt1 > kt0) {
+        DKF_FETCH_PART_Q(0)
+        DKF_FETCH_PREP(kt0)
+        DKF_FETCH_PIECES(0, NA, 0, 8)
+    }
+    const bool three = p.sums && fa && fb;
+    int plist = 0, nparts = 0;           // four bits per active part
+    if (three) {
+        plist = 0x0 | 0xA << 4 | 0x5 << 8;
+        nparts = 3;
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (!((q & 1) && !fa) && !((q >> 1) && !fb)) plist |= ((q & 1) | (q >> 1) << 2) << (4 * nparts++);
+    }
+    const int nsteps = nparts * (kt1 - kt0);
     if (nsteps > 0) {
-        DKF_FETCH_PART(0)
-        {
-            DKF_FETCH_PREP(kt0)
-            DKF_FETCH_PIECES(0, NA, 0, 8)
-        }
         DKF_STASH_PIECES(flds, 0, NA, 0, 8)
         DKF_ADVANCE(pi2, kt2)
         if (kt2 == kt0) DKF_FETCH_PART(pi2)
@@ -1005,6 +1008,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 #undef DKF_PACE
 #undef DKF_KEEP
 #undef DKF_FETCH_PART
+#undef DKF_FETCH_PART_Q
 #undef DKF_FETCH_PREP
 #undef DKF_FETCH_PIECES
 #undef DKF_STASH_PIECES
