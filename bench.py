@@ -378,7 +378,13 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="first run three plain 1 GiB device copies (a known-size reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--mfma-rate", action="store_true",
+                    help="only measure what the int8 matrix pipe sustains with constant and with random operands "
+                         "(dkf_probe_mfma_rate) and print both rates")
     args = ap.parse_args()
+    if args.mfma_rate:
+        print(json.dumps(mfma_rate()))
+        return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.stderr.write("bench.py: this build covers the one-GPU hot path only; run with --gpus 1\n")
         raise SystemExit(2)
@@ -389,6 +395,28 @@ def main():
         return
     out = field_main(args) if args.workload.startswith("field") else layer_main(args)
     print(json.dumps(out))
+
+
+def mfma_rate():
+    """int8 operations per second of a kernel that issues nothing but int8 matrix instructions."""
+    import torch
+    import paper_2207_00083_amd as dk
+    dk.load()
+    out = {"metric": "int8 matrix-instruction rate, operands in registers, one wave per SIMD", "unit": "TOP/s",
+           "peak": 5000.0}
+    for name, rnd in (("constant_operands", 0), ("random_operands", 1)):
+        dk.dkf_probe_mfma_rate(rnd, 2000)
+        torch.cuda.synchronize()
+        rates = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            ops = dk.dkf_probe_mfma_rate(rnd, 40000)
+            e1.record()
+            torch.cuda.synchronize()
+            rates.append(ops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        out[name] = {"TOPs": sum(rates) / len(rates), "min": min(rates), "max": max(rates)}
+    return out
 
 
 def sub_workloads(name):

@@ -19,7 +19,7 @@ from .field import (DKF_P, DKF_L, dkf_coeffs, dkf_quantize, dkf_dequantize, dkf_
                     dkf_decode_verify, dkf_wgrad, dkf_fwd_workspace_bytes, dkf_wgrad_workspace_bytes,
                     dkf_conv_fwd, dkf_conv_fwd_workspace_bytes, dkf_noise_rng, dkf_encode_rng, dkf_norm_scales,
                     dkf_coeffs_m, dkf_encode_m, dkf_decode_verify_m, dkf_wgrad_m, dkf_wgrad_workspace_bytes_m,
-                    dkf_add_bias)
+                    dkf_add_bias, dkf_probe_mfma_rate)
 
 __all__ = ["DKF_P", "DKF_L", "dkf_coeffs", "dkf_quantize", "dkf_dequantize", "dkf_encode",
            "dkf_linear_fwd", "dkf_linear_fwd_w", "dkf_decode_verify", "dkf_wgrad", "dkf_fwd_workspace_bytes",
@@ -32,5 +32,5 @@ __all__ = ["DKF_P", "DKF_L", "dkf_coeffs", "dkf_quantize", "dkf_dequantize", "dk
            "DK_OPT_FUSE_FWD", "DK_OPT_FUSE_WGRAD", "DK_FUSE_NEVER", "DK_FUSE_ALWAYS", "DK_FUSE_AUTO",
            "dk_coeffs_m", "dk_encode_m", "dk_decode_verify_m", "dk_wgrad_m", "dk_noise_rng", "dk_encode_rng", "dk_dgrad",
            "dkf_noise_rng", "dkf_encode_rng", "dkf_norm_scales",
-           "dkf_add_bias", "dkf_coeffs_m", "dkf_encode_m", "dkf_decode_verify_m", "dkf_wgrad_m", "dkf_wgrad_workspace_bytes_m",
+           "dkf_add_bias", "dkf_probe_mfma_rate", "dkf_coeffs_m", "dkf_encode_m", "dkf_decode_verify_m", "dkf_wgrad_m", "dkf_wgrad_workspace_bytes_m",
            "DK_OP_FWD", "DK_OP_WGRAD", "DK_OP_VERIFY", "DK_MAX_K"]

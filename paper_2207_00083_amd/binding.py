@@ -109,6 +109,7 @@ def load():
         "dkf_decode_verify_norm": (ip, [vp, vp, vp, vp, vp, vp, vp, vp, ip, ip, ll, ip, vp]),
         "dkf_wgrad_norm": (ip, [LP, vp, vp, vp, vp, vp, vp, vp, ip, ip, ip, fl, ip, vp, sz, vp]),
         "dkf_conv_fwd_workspace_bytes": (sz, [LP, ip]),
+        "dkf_probe_mfma_rate": (ip, [ip, ip, vp, vp]),
         "dkf_add_bias": (ip, [vp, vp, vp, ll, ll, ll, ip, vp]),
         "dkf_coeffs_m": (ip, [vp, vp, ip, ip, ip, vp, vp, vp]),
         "dkf_encode_m": (ip, [vp, vp, vp, vp, ip, ip, ip, ll, ip, vp]),

@@ -1616,3 +1616,54 @@ DK_EXPORT dk_status dkf_wgrad_norm(const dk_layer *L, const float *delta, const 
     return wgrad_impl(L, delta, xscale, B, gamma, xbar, dW, dwq, G, K, 1, l, scale, accumulate, ws,
                       ws_bytes, stream);
 }
+
+// ---------------------------------------------------------------------------
+// Diagnostic: what the int8 matrix pipe sustains when nothing else limits it.
+// ---------------------------------------------------------------------------
+namespace {
+
+// One wave per SIMD (four per workgroup, one workgroup per compute unit), eight independent
+// accumulator blocks, operands in registers: 16 MFMAs per iteration and nothing else.
+__global__ __launch_bounds__(256) void f_mfma_rate_kernel(int random_operands, int iterations, int *out)
+{
+    const unsigned seed = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+    i32x4 a[2], b[2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const unsigned h = (seed ^ (0x9e3779b9u * (unsigned)(4 * x + c + 1))) * 2246822519u;
+            a[x][c] = random_operands ? (int)(h ^ (h >> 15)) : 0x01010101;
+            b[x][c] = random_operands ? (int)((h * 3266489917u) ^ (h >> 13)) : 0x01010101;
+        }
+    i32x16 acc[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[q][v] = 0;
+    for (int it = 0; it < iterations; ++it) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                acc[q] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[q & 1], b[(q >> 1) & 1], acc[q], 0, 0, 0);
+    }
+    int sum = 0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sum ^= acc[q][v];
+    if (out && sum == 0x7ffffff1) out[threadIdx.x] = sum;      // keeps the loop; practically never true
+}
+
+} // namespace
+
+DK_EXPORT dk_status dkf_probe_mfma_rate(int random_operands, int iterations, double *int8_ops, void *stream)
+{
+    DK_REQUIRE(iterations >= 1 && iterations <= (1 << 24), DK_ERR_SHAPE);
+    const int blocks = 256;
+    dk_prof_scope ps(random_operands ? "f_mfma_rate_random" : "f_mfma_rate_constant", (hipStream_t)stream);
+    f_mfma_rate_kernel<<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(random_operands, iterations, nullptr);
+    if (int8_ops) *int8_ops = (double)blocks * 4.0 * (double)iterations * 16.0 * 65536.0;
+    return dk_launch_status();
+}
