@@ -379,8 +379,8 @@ def main():
                     help="first run three plain 1 GiB device copies (a known-size reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--mfma-rate", action="store_true",
-                    help="only measure what the int8 matrix pipe sustains with constant and with random operands "
-                         "(dkf_probe_mfma_rate) and print both rates")
+                    help="only measure what the int8 matrix pipe sustains with constant operands, random bytes and "
+                         "random balanced base-128 digits (dkf_probe_mfma_rate) and print the rates")
     args = ap.parse_args()
     if args.mfma_rate:
         print(json.dumps(mfma_rate()))
@@ -404,7 +404,7 @@ def mfma_rate():
     dk.load()
     out = {"metric": "int8 matrix-instruction rate, operands in registers, one wave per SIMD", "unit": "TOP/s",
            "peak": 5000.0}
-    for name, rnd in (("constant_operands", 0), ("random_operands", 1)):
+    for name, rnd in (("constant_operands", 0), ("random_bytes", 1), ("random_balanced_digits", 2)):
         dk.dkf_probe_mfma_rate(rnd, 2000)
         torch.cuda.synchronize()
         rates = []

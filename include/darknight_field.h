@@ -250,7 +250,9 @@ size_t dkf_wgrad_workspace_bytes(const dk_layer *L, int G, int K);
 /* Diagnostic (for the roofline discussion, not part of the path): launches a
  * kernel that does nothing but int8 matrix instructions, `iterations` x 16 per
  * wave on one wave per SIMD of 256 compute units, with constant operands
- * (random_operands = 0) or pseudo-random ones (1) in registers, and stores the
+ * (random_operands = 0), pseudo-random bytes (1) or pseudo-random balanced
+ * base-128 digits, i.e. bytes in [-64, 63] as the digit planes hold them (2),
+ * in registers, and stores the
  * number of int8 operations of the launch in *int8_ops (host, may be NULL).
  * Time it with events on `stream`: operations / time is what the matrix pipe
  * sustains for such operands when nothing else limits it. */

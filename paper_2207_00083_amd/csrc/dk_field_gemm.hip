@@ -1633,8 +1633,13 @@ __global__ __launch_bounds__(256) void f_mfma_rate_kernel(int random_operands, i
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const unsigned h = (seed ^ (0x9e3779b9u * (unsigned)(4 * x + c + 1))) * 2246822519u;
-            a[x][c] = random_operands ? (int)(h ^ (h >> 15)) : 0x01010101;
-            b[x][c] = random_operands ? (int)((h * 3266489917u) ^ (h >> 13)) : 0x01010101;
+            unsigned ra = h ^ (h >> 15), rb = (h * 3266489917u) ^ (h >> 13);
+            if (random_operands == 2) {            // balanced base-128 digits: bytes in [-64, 63]
+                ra = (ra & 0x7f7f7f7fu) | ((ra & 0x40404040u) << 1);
+                rb = (rb & 0x7f7f7f7fu) | ((rb & 0x40404040u) << 1);
+            }
+            a[x][c] = random_operands ? (int)ra : 0x01010101;
+            b[x][c] = random_operands ? (int)rb : 0x01010101;
         }
     i32x16 acc[8];
 #pragma unroll
@@ -1662,6 +1667,7 @@ DK_EXPORT dk_status dkf_probe_mfma_rate(int random_operands, int iterations, dou
 {
     DK_REQUIRE(iterations >= 1 && iterations <= (1 << 24), DK_ERR_SHAPE);
     const int blocks = 256;
+    DK_REQUIRE(random_operands >= 0 && random_operands <= 2, DK_ERR_SHAPE);
     dk_prof_scope ps(random_operands ? "f_mfma_rate_random" : "f_mfma_rate_constant", (hipStream_t)stream);
     f_mfma_rate_kernel<<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(random_operands, iterations, nullptr);
     if (int8_ops) *int8_ops = (double)blocks * 4.0 * (double)iterations * 16.0 * 65536.0;

@@ -332,7 +332,7 @@ def dkf_add_bias(yq, bias, per, l=DKF_L, y=None, want_y=True, stream=None):
 def dkf_probe_mfma_rate(random_operands, iterations=20000, stream=None):
     """Launches the int8 matrix-instruction rate probe; returns the int8 operations of the launch."""
     ops = C.c_double(0.0)
-    _check(load().dkf_probe_mfma_rate(int(bool(random_operands)), int(iterations), C.byref(ops), _stream(stream)),
+    _check(load().dkf_probe_mfma_rate(int(random_operands), int(iterations), C.byref(ops), _stream(stream)),
            "dkf_probe_mfma_rate")
     return ops.value
 
