@@ -198,6 +198,20 @@ def test_field_errors_before_launch(dk):
                               null) == 1
     assert dk.dkf_fwd_workspace_bytes(4, 4, 4) > 0 and dk.dkf_fwd_workspace_bytes(0, 4, 4) == 0
     assert dk.dkf_wgrad_workspace_bytes(dk_inputs.linear(4, 4), 1, 2) > 0
+    # entry points added later: real weights into the dense forward, the bias, depthwise layers, the rate probe
+    assert lib.dkf_linear_fwd_w(null, 8, one, one, 4, 4, 4, one, 1 << 30, null) == 1
+    assert lib.dkf_linear_fwd_w(one, 13, one, one, 4, 4, 4, one, 1 << 30, null) == 2
+    assert lib.dkf_linear_fwd_w(one, 8, one, one, 4, 4, 4, one, 16, null) == 5
+    assert lib.dkf_add_bias(null, null, one, 4, 8, 1, 8, null) == 1
+    assert lib.dkf_add_bias(one, null, one, 4, 8, 3, 8, null) == 2          # per does not divide m
+    assert lib.dkf_add_bias(one, null, one, 4, 8, 1, 13, null) == 2
+    assert lib.dkf_add_bias(C.c_void_p(258), null, one, 4, 8, 1, 8, null) == 4
+    dw = dk_inputs.dwconv(4, 8, 8, 3)
+    assert dk.dkf_conv_fwd_workspace_bytes(dw, 4) > 0 and dk.dkf_wgrad_workspace_bytes(dw, 1, 2) > 0
+    assert lib.dkf_wgrad(C.byref(dk.DkLayer.of(dw)), one, one, one, one, one, null, 1, 2, 8, 1.0, 0, one, 64,
+                         null) == 5
+    assert lib.dkf_probe_mfma_rate(0, 0, null, null) == 2
+    assert lib.dkf_probe_mfma_rate(3, 10, null, null) == 2
 
 
 def test_field_coeffs_match_the_oracle_and_report_singular(dk):

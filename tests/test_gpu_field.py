@@ -365,3 +365,11 @@ def test_linear_forward_from_real_weights(dk, M, N, R, l):
     two = host(dk.dkf_linear_fwd(dk.dkf_quantize(dev(W), l=l), dev(xbar)))
     assert np.array_equal(got, two)
     assert np.array_equal(got, F.dense_fwd(F.quantize(W, l=l), xbar))
+
+
+def test_matrix_rate_probe_runs(dk):
+    import torch
+    for kind in (0, 1, 2):
+        ops = dk.dkf_probe_mfma_rate(kind, 50)
+        assert ops == 256 * 4 * 50 * 16 * 65536.0
+    torch.cuda.synchronize()
