@@ -379,8 +379,8 @@ def main():
                     help="first run three plain 1 GiB device copies (a known-size reference for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--mfma-rate", action="store_true",
-                    help="only measure what the int8 matrix pipe sustains with constant operands, random bytes and "
-                         "random balanced base-128 digits (dkf_probe_mfma_rate) and print the rates")
+                    help="only measure what the matrix pipes sustain with constant and with random operands "
+                         "(dkf_probe_mfma_rate: int8; dk_probe_mfma_rate: fp32) and print the rates")
     args = ap.parse_args()
     if args.mfma_rate:
         print(json.dumps(mfma_rate()))
@@ -398,24 +398,30 @@ def main():
 
 
 def mfma_rate():
-    """int8 operations per second of a kernel that issues nothing but int8 matrix instructions."""
+    """Operations per second of kernels that issue nothing but matrix instructions (int8 and fp32)."""
     import torch
     import paper_2207_00083_amd as dk
     dk.load()
-    out = {"metric": "int8 matrix-instruction rate, operands in registers, one wave per SIMD", "unit": "TOP/s",
-           "peak": 5000.0}
-    for name, rnd in (("constant_operands", 0), ("random_bytes", 1), ("random_balanced_digits", 2)):
-        dk.dkf_probe_mfma_rate(rnd, 2000)
+
+    def rate(probe, kind):
+        probe(kind, 2000)
         torch.cuda.synchronize()
         rates = []
         for _ in range(5):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            ops = dk.dkf_probe_mfma_rate(rnd, 40000)
+            ops = probe(kind, 40000)
             e1.record()
             torch.cuda.synchronize()
             rates.append(ops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
-        out[name] = {"TOPs": sum(rates) / len(rates), "min": min(rates), "max": max(rates)}
+        return {"T_per_s": sum(rates) / len(rates), "min": min(rates), "max": max(rates)}
+
+    out = {"metric": "matrix-instruction rate, operands in registers, one wave per SIMD",
+           "int8": {"unit": "TOP/s", "peak": 5000.0}, "fp32": {"unit": "TFLOP/s", "peak": 157.3}}
+    for name, kind in (("constant_operands", 0), ("random_bytes", 1), ("random_balanced_digits", 2)):
+        out["int8"][name] = rate(dk.dkf_probe_mfma_rate, kind)
+    for name, kind in (("constant_operands", 0), ("random_operands", 1)):
+        out["fp32"][name] = rate(dk.dk_probe_mfma_rate, kind)
     return out
 
 

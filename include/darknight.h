@@ -233,6 +233,15 @@ size_t dk_static_scratch_bytes(void);
  * are not timed).  Not thread-safe. */
 dk_status dk_profile_enable(int on);
 
+/* Diagnostic (for the roofline discussion, not part of the path): launches a
+ * kernel that does nothing but fp32 matrix instructions, `iterations` x 16 per
+ * wave on one wave per SIMD of 256 compute units, with constant operands
+ * (random_operands = 0) or pseudo-random ones (1) in registers, and stores the
+ * FLOP of the launch in *flop (host, may be NULL).  Timed with events on
+ * `stream`, FLOP / time is what the matrix pipe sustains for such operands
+ * when nothing else limits it. */
+dk_status dk_probe_mfma_rate(int random_operands, int iterations, double *flop, void *stream);
+
 /* Waits for the recorded events and returns the number of distinct kernel
  * labels; for 0 <= index < that number also writes the label (host buffer of
  * name_cap bytes), its average launch duration in milliseconds and its launch

@@ -10,6 +10,7 @@ from .binding import (DkError, DkLayer, lib_path, load, dk_version, dk_status_st
                       dk_workspace_bytes, dk_layer_in_len, dk_layer_out_len, dk_coeffs,
                       dk_encode, dk_linear_fwd, dk_conv_fwd, dk_wgrad, dk_decode, dk_verify,
                       dk_decode_verify, dk_decode_verify_static, dk_static_scratch_bytes, dk_profile_enable, dk_profile_read,
+                      dk_probe_mfma_rate,
                       dk_conv_fwd_decode_verify, dk_conv_fwd_decode_verify_workspace_bytes, dk_set_option, dk_get_option,
                       DK_OPT_FUSE_FWD, DK_OPT_FUSE_WGRAD, DK_FUSE_NEVER, DK_FUSE_ALWAYS, DK_FUSE_AUTO,
                       dk_coeffs_m, dk_encode_m, dk_decode_verify_m, dk_wgrad_m, dk_noise_rng, dk_encode_rng, dk_dgrad,
@@ -28,6 +29,7 @@ __all__ = ["DKF_P", "DKF_L", "dkf_coeffs", "dkf_quantize", "dkf_dequantize", "dk
            "dk_workspace_bytes", "dk_layer_in_len", "dk_layer_out_len", "dk_coeffs",
            "dk_encode", "dk_linear_fwd", "dk_conv_fwd", "dk_wgrad", "dk_decode", "dk_verify",
            "dk_decode_verify", "dk_decode_verify_static", "dk_static_scratch_bytes", "dk_profile_enable", "dk_profile_read",
+           "dk_probe_mfma_rate",
            "dk_conv_fwd_decode_verify", "dk_conv_fwd_decode_verify_workspace_bytes", "dk_set_option", "dk_get_option",
            "DK_OPT_FUSE_FWD", "DK_OPT_FUSE_WGRAD", "DK_FUSE_NEVER", "DK_FUSE_ALWAYS", "DK_FUSE_AUTO",
            "dk_coeffs_m", "dk_encode_m", "dk_decode_verify_m", "dk_wgrad_m", "dk_noise_rng", "dk_encode_rng", "dk_dgrad",

@@ -110,6 +110,7 @@ def load():
         "dkf_wgrad_norm": (ip, [LP, vp, vp, vp, vp, vp, vp, vp, ip, ip, ip, fl, ip, vp, sz, vp]),
         "dkf_conv_fwd_workspace_bytes": (sz, [LP, ip]),
         "dkf_probe_mfma_rate": (ip, [ip, ip, vp, vp]),
+        "dk_probe_mfma_rate": (ip, [ip, ip, vp, vp]),
         "dkf_add_bias": (ip, [vp, vp, vp, ll, ll, ll, ip, vp]),
         "dkf_coeffs_m": (ip, [vp, vp, ip, ip, ip, vp, vp, vp]),
         "dkf_encode_m": (ip, [vp, vp, vp, vp, ip, ip, ip, ll, ip, vp]),
@@ -592,6 +593,14 @@ def dk_encode_rng(x, A, K, M, seed, noise_std, xbar=None, stream=None):
 def dk_profile_enable(on=True):
     """Start (clearing old records) or stop per-kernel event timing."""
     _check(load().dk_profile_enable(1 if on else 0), "dk_profile_enable")
+
+
+def dk_probe_mfma_rate(random_operands, iterations=20000, stream=None):
+    """Launches the fp32 matrix-instruction rate probe; returns the FLOP of the launch."""
+    flop = C.c_double(0.0)
+    _check(load().dk_probe_mfma_rate(int(random_operands), int(iterations), C.byref(flop), _stream(stream)),
+           "dk_probe_mfma_rate")
+    return flop.value
 
 
 def dk_profile_read():

@@ -1789,3 +1789,54 @@ DK_EXPORT dk_status dk_dgrad(const dk_layer *L, const float *W, const float *del
         W, delta, dx, total, g.Ci, g.Co, g.H, g.W, g.kh, g.kw, g.stride, g.pad, g.Ho, g.Wo);
     return dk_launch_status();
 }
+
+// ---------------------------------------------------------------------------
+// Diagnostic: what the fp32 matrix pipe sustains when nothing else limits it.
+// ---------------------------------------------------------------------------
+namespace {
+
+// One wave per SIMD, eight independent accumulator blocks, operands in registers:
+// 16 MFMAs per iteration and nothing else.
+__global__ __launch_bounds__(256) void mfma_rate_kernel(int random_operands, int iterations, float *out)
+{
+    const unsigned seed = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+    float a[2], b[2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+        const unsigned h = (seed ^ (0x9e3779b9u * (unsigned)(x + 1))) * 2246822519u;
+        // random: uniform in [1, 2) with a random sign (all mantissa bits toggle, no overflow)
+        a[x] = random_operands ? __uint_as_float(0x3f800000u | ((h ^ (h >> 15)) & 0x807fffffu)) : 1.0f;
+        b[x] = random_operands ? __uint_as_float(0x3f800000u | (((h * 3266489917u) ^ (h >> 13)) & 0x807fffffu)) : 1.0f;
+    }
+    f32x16 acc[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[q][v] = 0.0f;
+    for (int it = 0; it < iterations; ++it) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                acc[q] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q & 1], b[(q >> 1) & 1], acc[q], 0, 0, 0);
+    }
+    float sum = 0.0f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sum += acc[q][v];
+    if (out && sum == 1.2345e-30f) out[threadIdx.x] = sum;     // keeps the loop; practically never true
+}
+
+} // namespace
+
+DK_EXPORT dk_status dk_probe_mfma_rate(int random_operands, int iterations, double *flop, void *stream)
+{
+    DK_REQUIRE(iterations >= 1 && iterations <= (1 << 24) && random_operands >= 0 && random_operands <= 1,
+               DK_ERR_SHAPE);
+    const int blocks = 256;
+    dk_prof_scope ps(random_operands ? "mfma_rate_random" : "mfma_rate_constant", (hipStream_t)stream);
+    mfma_rate_kernel<<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(random_operands, iterations, nullptr);
+    if (flop) *flop = (double)blocks * 4.0 * (double)iterations * 16.0 * 4096.0;
+    return dk_launch_status();
+}

@@ -214,3 +214,10 @@ def test_explicit_stream_with_automatic_workspaces(dk):
     side.synchronize()
     torch.cuda.synchronize()
     assert all(torch.equal(a, b) for a, b in zip(path.outputs(), ref))
+
+
+def test_fp32_matrix_rate_probe_runs(dk):
+    import torch
+    for kind in (0, 1):
+        assert dk.dk_probe_mfma_rate(kind, 50) == 256 * 4 * 50 * 16 * 4096.0
+    torch.cuda.synchronize()
