@@ -44,7 +44,11 @@ def host(t):
 
 DW = [(2, 3, dk_inputs.dwconv(12, 16, 16, 3)), (4, 2, dk_inputs.dwconv(24, 15, 13, 3, 2)),
       (1, 2, dk_inputs.dwconv(8, 7, 7, 5, 1, 2)), (8, 1, dk_inputs.dwconv(6, 9, 9, 7, 2, 3)),
-      (2, 40, dk_inputs.dwconv(3, 20, 20, 3)), (2, 2, dk_inputs.dwconv(300, 4, 4, 3))]
+      (2, 40, dk_inputs.dwconv(3, 20, 20, 3)), (2, 2, dk_inputs.dwconv(300, 4, 4, 3)),
+      # rows of 4 n outputs (four per thread): stride 2, 5x5, 7x7, one strip per row, a single row
+      (2, 3, dk_inputs.dwconv(10, 16, 16, 3, 2, 1)), (4, 1, dk_inputs.dwconv(5, 12, 12, 5, 1, 2)),
+      (2, 2, dk_inputs.dwconv(4, 16, 16, 7, 2, 3)), (2, 2, dk_inputs.dwconv(7, 8, 8, 5, 2, 2)),
+      (2, 2, dk_inputs.dwconv(3, 1, 4, 3, 1, 1)), (1, 2, dk_inputs.dwconv(2, 40, 36, 3, 1, 1))]
 
 
 @pytest.mark.parametrize("K,G,L", DW)
