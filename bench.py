@@ -7,7 +7,7 @@ is already resident in HBM:
 (dk_decode_verify = dk_verify + dk_decode in one sweep over the encoded results).
 The step is captured once into a HIP graph and replayed (--no-graph: eager).
 --noise-vectors M uses the *_m entry points (M noise vectors per group);
---workload field1 | field2 | field3[.i] | field4[.i] | field5[.i] runs the finite-field
+--workload field1 | field2 | field3[.i] | field4[.i] | field5[.i] | fieldmbv2dw[.i] runs the finite-field
 variant instead (dkf_quantize -> dkf_encode -> dkf_linear_fwd | dkf_conv_fwd ->
 dkf_decode_verify -> dkf_wgrad).
 Prints ONE JSON line: whole-path executed TFLOP/s (forward + weight gradient
@@ -147,6 +147,10 @@ def field_workload(name):
         i = int(name.split(".")[1])
         return (dk_inputs.config5_field(index=i)[0],
                 "config5 layer %d over F_p, p=2^25-39, l=8 (VGG classifier, batch 1024, K=8)" % i)
+    if name.startswith("fieldmbv2dw."):
+        i = int(name.split(".")[1])
+        d, count = dk_inputs.mobilenetv2_dw_field(index=i)
+        return d, "MobileNetV2 depthwise 3x3 layer %d x%d over F_p (224x224 input, batch 64, K=8)" % (i, count)
     raise SystemExit("unknown workload " + name)
 
 
@@ -160,8 +164,9 @@ def field_cpu_baseline(d, budget_s=15.0):
     def run(ng):
         sl = slice(0, ng * K)
         t0 = time.perf_counter()
-        F.masked_layer(d["W"], d["X"][sl], d["r"][:ng], d["delta"][sl], d["A"][:ng], d["gamma"][:ng],
-                       stride=L.stride, pad=L.pad)
+        layer = F.masked_dw_layer if L.kind == "dwconv" else F.masked_layer
+        layer(d["W"], d["X"][sl], d["r"][:ng], d["delta"][sl], d["A"][:ng], d["gamma"][:ng],
+              stride=L.stride, pad=L.pad)
         return time.perf_counter() - t0
 
     import oracle
@@ -300,12 +305,27 @@ def field_main(args):
     # stride-1 filters whose output width grows by at most 1/7 when rounded up to 16)
     three_part = (L.kind == "linear" or L.kh * L.kw == 1 or
                   (L.stride == 1 and (L.Wo + 15) // 16 * 16 * 7 <= L.Wo * 8))
+    n, m = dk.dk_layer_in_len(L), dk.dk_layer_out_len(L)
+    if L.kind == "dwconv":
+        # a few multiply-adds per element moved: both kernels read the encodings (or the mixed
+        # gradients and the encodings) once and write (or reduce) once -- 4 R (n + m) bytes each
+        dwk = {"f_dw_fwd": 4.0 * R * (n + m), "f_dw_wgrad": 4.0 * R * (n + m)}
+        dom = max(dwk, key=lambda k: kernels[k][0])
+        ach = dwk[dom] / (kernels[dom][0] * 1e-3) / 1e9
+        roofline = {
+            "kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": ach / HBM_PEAK_GBPS, "traffic": None, "avg_launch_ms": kernels[dom][0],
+            "bytes_per_launch": dwk[dom],
+            "other": {k: {"avg_launch_ms": kernels[k][0], "GBps": b / (kernels[k][0] * 1e-3) / 1e9}
+                      for k, b in dwk.items() if k != dom},
+            "timed": "HIP events around every launch of this kernel, %d eager steps after the timed region" % args.steps,
+        }
     gemm = {"f_gemm_fwd": 8, "f_gemm_wgrad": 12 if three_part else 16}
-    dom = max(gemm, key=lambda k: kernels[k][0])
-    gemm_ms = kernels[dom][0]
-    int8_ops = 2.0 * mac * gemm[dom]
-    ach = int8_ops / (gemm_ms * 1e-3) / 1e12
-    roofline = {
+    dom = max(gemm, key=lambda k: kernels[k][0]) if L.kind != "dwconv" else None
+    gemm_ms = kernels[dom][0] if dom else 0.0
+    int8_ops = 2.0 * mac * gemm[dom] if dom else 0.0
+    ach = int8_ops / (gemm_ms * 1e-3) / 1e12 if dom else 0.0
+    roofline = roofline if L.kind == "dwconv" else {
         "kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s",
         "frac": ach / MFMA_I8_PEAK_TOPS, "traffic": measured_traffic(args.workload, dom),
         "avg_launch_ms": gemm_ms, "int8_op_per_launch": int8_ops,
@@ -315,7 +335,6 @@ def field_main(args):
                               for k, c in gemm.items() if k != dom},
         "timed": "HIP events around every launch of this kernel, %d eager steps after the timed region" % args.steps,
     }
-    n, m = dk.dk_layer_in_len(L), dk.dk_layer_out_len(L)
     ab = {"f_encode": 4 * G * n * (K + 1 + S), "f_decode_verify": 4 * G * m * (S + K),
           "f_delta_mix": 4 * G * m * (K + S)}
     hbm = {k: {"GBps": b / (kernels[k][0] * 1e-3) / 1e9, "frac": b / (kernels[k][0] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
@@ -442,6 +461,8 @@ def sub_workloads(name):
         return [("field3.%d" % i, 1) for i in range(len(dk_inputs.config3_layers()))]
     if name == "field4":
         return [("field4.%d" % i, c) for i, (_, c) in enumerate(dk_inputs.resnet50_convs())]
+    if name == "fieldmbv2dw":
+        return [("fieldmbv2dw.%d" % i, c[3]) for i, c in enumerate(dk_inputs.MOBILENETV2_DW)]
     return None
 
 

@@ -349,6 +349,13 @@ def mobilenetv2_dw(seed=6, batch=64, K=8, index=None):
     return out
 
 
+def mobilenetv2_dw_field(seed=6, batch=64, K=8, index=0):
+    """One depthwise 3x3 layer of MobileNetV2, finite-field variant: (inputs, multiplicity)."""
+    c, hw, st, count = MOBILENETV2_DW[index]
+    rng = np.random.default_rng([seed, index, 1])
+    return field_layer_inputs(rng, dwconv(c, hw, hw, 3, st), K=K, batch=batch), count
+
+
 def config5_layers():
     return [linear(4096, 25088), linear(4096, 4096), linear(1000, 4096)]
 
