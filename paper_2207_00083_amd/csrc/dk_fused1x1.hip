@@ -321,8 +321,9 @@ __global__ __launch_bounds__(C::NT) void fused1x1_wgrad_kernel(fused_wg_params p
     float4 breg[N4B];        // the encoding's tile of the current step
 
     // contraction step u = (chunk c, encoding j); chunk c = (virtual batch g, pixel chunk)
-    auto fetch_delta = [&](int c) {
-        const int g = c / p.cpi, pix0 = (c - g * p.cpi) * 16;
+    // (the virtual batch g and the first pixel pix0 of a chunk are carried along by the loop:
+    // a division per step, done on the vector ALU, costs as much as the mixing itself)
+    auto fetch_delta = [&](int g, int pix0) {
 #pragma unroll
         for (int i = 0; i < K; ++i) {
             const unsigned soff = 4u * ((unsigned)(g * K + i) * (unsigned)p.Co * (unsigned)p.HW + (unsigned)pix0);
@@ -330,16 +331,14 @@ __global__ __launch_bounds__(C::NT) void fused1x1_wgrad_kernel(fused_wg_params p
             for (int e = 0; e < N4A; ++e) dreg[i][e] = dk_buffer_load4(rsD, voffA[e], soff);
         }
     };
-    auto fetch_x = [&](int c, int j) {
-        const int g = c / p.cpi, pix0 = (c - g * p.cpi) * 16;
+    auto fetch_x = [&](int g, int pix0, int j) {
         const unsigned soff = 4u * ((unsigned)(g * S + j) * (unsigned)p.Ci * (unsigned)p.HW + (unsigned)pix0);
 #pragma unroll
         for (int e = 0; e < N4B; ++e) breg[e] = dk_buffer_load4(rsX, voffB[e], soff);
     };
     // mixed gradient of encoding j from the chunk's K tiles (the mixing kernel's
     // own operations, in its order), written k-major like the other operand
-    auto put = [&](int c, int j, float *as, float *bs) {
-        const int g = c / p.cpi;
+    auto put = [&](int g, int j, float *as, float *bs) {
         const float gj = p.gamma[(long long)g * S + j];
         float cf[K];
 #pragma unroll
@@ -380,22 +379,26 @@ __global__ __launch_bounds__(C::NT) void fused1x1_wgrad_kernel(fused_wg_params p
     int c1 = c0 + p.per_split;
     if (c1 > p.nch) c1 = p.nch;
     if (c0 < c1) {
-        fetch_delta(c0);
-        fetch_x(c0, 0);
-        put(c0, 0, As, Bs);
+        int g = c0 / p.cpi, pix0 = (c0 - g * p.cpi) * 16;         // of chunk c
+        fetch_delta(g, pix0);
+        fetch_x(g, pix0, 0);
+        put(g, 0, As, Bs);
         __syncthreads();
         int c = c0, j = 0;
         for (int step = 0;; ++step) {
             const int cur = step & 1;
-            int j1 = j + 1, cn = c;
-            if (j1 == S) { j1 = 0; cn = c + 1; }
+            int j1 = j + 1, cn = c, gn = g, pn = pix0;                 // ... of the next step's chunk
+            if (j1 == S) {
+                j1 = 0; cn = c + 1; pn = pix0 + 16;
+                if (pn == p.cpi * 16) { pn = 0; gn = g + 1; }
+            }
             const bool more = cn < c1;
             if (more) {
                 // the chunk's last mixed tile was formed one step ago: its K tiles
                 // can be overwritten by the next chunk's now
                 __builtin_amdgcn_s_setprio(3);
-                if (j1 == 0) fetch_delta(cn);
-                fetch_x(cn, j1);
+                if (j1 == 0) fetch_delta(gn, pn);
+                fetch_x(gn, pn, j1);
                 __builtin_amdgcn_s_setprio(0);
             }
             const float *a_s = As + cur * A_BUF + lh * C::LDA + wm0 + li;
@@ -413,10 +416,10 @@ __global__ __launch_bounds__(C::NT) void fused1x1_wgrad_kernel(fused_wg_params p
                     for (int ni = 0; ni < C::TN; ++ni)
                         acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi], b[ni], acc[mi][ni], 0, 0, 0);
             }
-            if (more) put(cn, j1, As + (cur ^ 1) * A_BUF, Bs + (cur ^ 1) * B_BUF);
+            if (more) put(gn, j1, As + (cur ^ 1) * A_BUF, Bs + (cur ^ 1) * B_BUF);
             __syncthreads();
             if (!more) break;
-            c = cn; j = j1;
+            c = cn; j = j1; g = gn; pix0 = pn;
         }
     }
 
