@@ -407,6 +407,7 @@ struct LoadKMajorImg {
     const float *src[VEC ? 1 : 4];   // element (k = 0) of this lane's pixel(s); null = outside
     int C, chs, tid;
     __amdgpu_buffer_rsrc_t rs; unsigned voff[N4]; bool fast;
+    unsigned poff[VEC ? 1 : 4];      // single pixels (rows that are not whole 16-byte vectors): byte offsets
 
     __device__ __forceinline__ void init(const Params &a, int q0, int tid_)
     {
@@ -419,21 +420,38 @@ struct LoadKMajorImg {
         }
         // whole tensor as one resource: [R][C][chs]
         const long long bytes = (long long)(a.Q / a.HW) * a.C * a.chs * 4;
-        fast = VEC && bytes <= DK_RSRC_MAX;
+        fast = bytes <= DK_RSRC_MAX;
         rs = dk_uniform_rsrc(a.p, (int)bytes);
 #pragma unroll
         for (int e = 0; e < N4; ++e) {
             const int kr = (tid + e * NT) / PER_K;
-            voff[e] = src[0] ? 4u * (unsigned)((src[0] - a.p) + (long long)kr * chs) : DK_OOB;
+            voff[e] = VEC ? (src[0] ? 4u * (unsigned)((src[0] - a.p) + (long long)kr * chs) : DK_OOB)
+                          : 4u * (unsigned)kr * (unsigned)chs;
         }
+#pragma unroll
+        for (int u = 0; u < (VEC ? 1 : 4); ++u)
+            poff[u] = src[u] ? 4u * (unsigned)(src[u] - a.p) : DK_OOB;     // (DK_OOB + a row offset stays out of range)
     }
 
     __device__ __forceinline__ void load(int kt)
     {
         if (fast && (kt + 1) * BK <= C) {
             const unsigned soff = 4u * (unsigned)(kt * BK) * (unsigned)chs;
+            if constexpr (VEC) {
 #pragma unroll
-            for (int e = 0; e < N4; ++e) st[e] = dk_buffer_load4(rs, voff[e], soff);
+                for (int e = 0; e < N4; ++e) st[e] = dk_buffer_load4(rs, voff[e], soff);
+            } else {
+                // four single pixels of a channel, possibly of two images
+#pragma unroll
+                for (int e = 0; e < N4; ++e) {
+                    float v[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        v[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                                             rs, (int)(poff[u] + voff[e]), (int)soff, 0));
+                    st[e] = make_float4(v[0], v[1], v[2], v[3]);
+                }
+            }
             return;
         }
 #pragma unroll
