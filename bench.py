@@ -297,7 +297,8 @@ def field_main(args):
     tops = op_step / (ms_per_step * 1e-3) / 1e12
     # The contraction kernel runs twice a step.  The forward multiplies 4 digit
     # planes of the encodings with the 2 non-zero planes of ordinary weights
-    # (8 int8 products per field product), the weight gradient 4 x 4 planes (16),
+    # (8 int8 products per field product; 4 when one plane holds them, see below),
+    # the weight gradient 4 x 4 planes (16),
     # or three products of half against half (12) where the operands come with
     # digit-sum planes: dense layers, 1x1 and most stride-1 convolutions.  Executed products
     # are counted.  The roofline record is the longer of the two launches.
@@ -320,7 +321,12 @@ def field_main(args):
                       for k, b in dwk.items() if k != dom},
             "timed": "HIP events around every launch of this kernel, %d eager steps after the timed region" % args.steps,
         }
-    gemm = {"f_gemm_fwd": 8, "f_gemm_wgrad": 12 if three_part else 16}
+    # Weights whose quantised values all lie in [-64, 63] fill one digit plane; the forward then
+    # multiplies 4 x 1 planes (the library takes those steps for dense layers and for
+    # convolutions with more than 64 output channels).
+    wq = np.rint(np.asarray(d["W"], dtype=np.float64) * 2.0 ** 8)
+    one_digit = bool(wq.min() >= -64 and wq.max() <= 63) and (L.kind == "linear" or L.Co > 64)
+    gemm = {"f_gemm_fwd": 4 if one_digit else 8, "f_gemm_wgrad": 12 if three_part else 16}
     dom = max(gemm, key=lambda k: kernels[k][0]) if L.kind != "dwconv" else None
     gemm_ms = kernels[dom][0] if dom else 0.0
     int8_ops = 2.0 * mac * gemm[dom] if dom else 0.0
@@ -329,6 +335,7 @@ def field_main(args):
         "kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s",
         "frac": ach / MFMA_I8_PEAK_TOPS, "traffic": measured_traffic(args.workload, dom),
         "avg_launch_ms": gemm_ms, "int8_op_per_launch": int8_ops,
+        "digit_products_per_field_product": gemm,
         "field_top_per_s": 2.0 * mac / (gemm_ms * 1e-3) / 1e12,
         "other_contraction": {k: {"avg_launch_ms": kernels[k][0],
                                   "int8_TOPs": 2.0 * mac * c / (kernels[k][0] * 1e-3) / 1e12}

@@ -54,7 +54,7 @@ struct fgemm_params {
     const int8_t *Bp;      // [4 or 6][J_pad][Kp]
     uint32_t *out_q;       // residues [splits][I][J] (a slice per k split), or NULL
     float *out_f;          // de-quantised result [I][J] (only with one split), or NULL
-    const int *flags;      // [0]: A has non-zero high digits, [1]: B has (device)
+    const int *flags;      // [0]: A, [1]: B; bit 0: non-zero high digits (planes 2, 3), bit 1: non-zero plane 1 (device)
     long long a_plane, b_plane;   // bytes per plane
     int I, J, Kp;
     int tiles_i, tiles_j, splits, ktiles_per_split, ktiles;
@@ -73,6 +73,7 @@ struct fgemm_params {
     float scale;
     int accumulate;
     int sums;              // planes 4, 5 of both operands hold the digit sums of the halves
+    int single_mask;       // bit 0: a SINGLE = 1 launch accompanies this one, bit 1: a SINGLE = 2 launch
 };
 
 // Four balanced base-128 digits of the centred lift of q, packed one per byte.
@@ -108,10 +109,13 @@ __device__ __forceinline__ uint32_t gather_byte(const uint32_t (&d)[4], int a)
 
 // Sixteen packed-digit words -> one 16-byte piece of each plane at `dst`
 // (plane a at dst + a * plane); with `sums` planes 4, 5 get the digit sums of
-// the halves.  Returns the OR of the high-half words.
-__device__ __forceinline__ uint32_t store_pieces(const uint32_t (&d)[16], int8_t *dst, long long plane, int sums)
+// the halves.  Returns the OR of the high-half words; `mid` gets the OR of
+// the words of plane 1.
+__device__ __forceinline__ uint32_t store_pieces(const uint32_t (&d)[16], int8_t *dst, long long plane, int sums,
+                                                 uint32_t &mid)
 {
     uint32_t hi = 0;
+    mid = 0;
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
         u32x4 w;
@@ -121,6 +125,7 @@ __device__ __forceinline__ uint32_t store_pieces(const uint32_t (&d)[16], int8_t
             w[q] = gather_byte(dq, a);
         }
         if (a >= 2) hi |= w.x | w.y | w.z | w.w;
+        if (a == 1) mid |= w.x | w.y | w.z | w.w;
         *reinterpret_cast<u32x4 *>(dst + a * plane) = w;
     }
     if (sums) {
@@ -141,12 +146,14 @@ __device__ __forceinline__ uint32_t store_pieces(const uint32_t (&d)[16], int8_t
     return hi;
 }
 
-// Record "some high digit is non-zero".  One lane per wave looks at the flag
+// Record "some high digit (planes 2, 3) is non-zero" in bit 0 and "some digit
+// of plane 1 is non-zero" in bit 1.  One lane per wave looks at the flag
 // first, so once it is set the other waves of the launch only read it.
-__device__ __forceinline__ void raise_flag(int *flag, bool mine)
+__device__ __forceinline__ void raise_flag(int *flag, uint32_t hi, uint32_t mid)
 {
-    if (flag && __any(mine) && (threadIdx.x & 63) == 0) {
-        if (__atomic_load_n(flag, __ATOMIC_RELAXED) == 0) atomicOr(flag, 1);
+    const int want = (__any(hi != 0) ? 1 : 0) | (__any(mid != 0) ? 2 : 0);
+    if (flag && want && (threadIdx.x & 63) == 0) {
+        if ((__atomic_load_n(flag, __ATOMIC_RELAXED) & want) != want) atomicOr(flag, want);
     }
 }
 
@@ -192,8 +199,9 @@ __global__ __launch_bounds__(256) void f_digits_kernel(const void *__restrict__ 
 #pragma unroll
     for (int c = 0; c < 16; ++c) d[c] = digits_of(v[c]);
     const long long plane = (long long)rows_pad * Kp;
-    const uint32_t hi = store_pieces(d, planes + (long long)row * Kp + k0, plane, 0);
-    raise_flag(flag, hi != 0);
+    uint32_t mid;
+    const uint32_t hi = store_pieces(d, planes + (long long)row * Kp + k0, plane, 0, mid);
+    raise_flag(flag, hi, mid);
 }
 
 struct fconv_geom {
@@ -266,7 +274,7 @@ __global__ __launch_bounds__(256) void f_digits_t_kernel(const uint32_t *__restr
     }
     __syncthreads();
     const long long plane = (long long)cols_pad * Kp;
-    uint32_t hi = 0;
+    uint32_t hi = 0, mid = 0;
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
         const int item = threadIdx.x + 256 * r;       // (row, 16 k): eight lanes write 128 contiguous bytes
@@ -286,12 +294,13 @@ __global__ __launch_bounds__(256) void f_digits_t_kernel(const uint32_t *__restr
             w[5][g] = gather_byte(ds, 1);
         }
         hi |= w[2].x | w[2].y | w[2].z | w[2].w | w[3].x | w[3].y | w[3].z | w[3].w;
+        mid |= w[1].x | w[1].y | w[1].z | w[1].w;
 #pragma unroll
         for (int a = 0; a < 6; ++a)
             if (a < 4 || sums)
                 *reinterpret_cast<u32x4 *>(planes + a * plane + (long long)(c0 + col) * Kp + k0 + 16 * kq) = w[a];
     }
-    raise_flag(flag, hi != 0);
+    raise_flag(flag, hi, mid);
 }
 
 // Digit planes of the operands of a convolution's weight gradient, gathered
@@ -347,7 +356,7 @@ __global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__re
         }
     }
     const long long plane = (long long)rows_pad * Kp;
-    uint32_t hi = 0;
+    uint32_t hi = 0, mid = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int k0 = kb + q * 1024;
@@ -363,6 +372,7 @@ __global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__re
         for (int a = 0; a < 4; ++a) {
             const uint32_t w = gather_byte(d, a);
             if (a >= 2) hi |= w;
+            if (a == 1) mid |= w;
             *reinterpret_cast<uint32_t *>(dst + a * plane) = w;
         }
         if (sums) {
@@ -371,7 +381,7 @@ __global__ __launch_bounds__(256) void f_digits_conv_kernel(const uint32_t *__re
                 *reinterpret_cast<uint32_t *>(dst + (4 + a) * plane) = gather_byte(ds, a);
         }
     }
-    raise_flag(flag, hi != 0);
+    raise_flag(flag, hi, mid);
 }
 
 // Digit planes of the operands of a stride-1 convolution's weight gradient with
@@ -423,7 +433,7 @@ __global__ __launch_bounds__(256) void f_digits_rows_kernel(const uint32_t *__re
             }
         }
         const long long plane = (long long)rows_pad * pitch;
-        uint32_t hi = 0;
+        uint32_t hi = 0, mid = 0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int k0 = kb + q * 1024;
@@ -439,6 +449,7 @@ __global__ __launch_bounds__(256) void f_digits_rows_kernel(const uint32_t *__re
             for (int a = 0; a < 4; ++a) {
                 const uint32_t w = gather_byte(d, a);
                 if (a >= 2) hi |= w;
+                if (a == 1) mid |= w;
                 *reinterpret_cast<uint32_t *>(dst + a * plane) = w;
             }
             if (sums) {
@@ -447,7 +458,7 @@ __global__ __launch_bounds__(256) void f_digits_rows_kernel(const uint32_t *__re
                     *reinterpret_cast<uint32_t *>(dst + (4 + a) * plane) = gather_byte(ds, a);
             }
         }
-        raise_flag(flag, hi != 0);
+        raise_flag(flag, hi, mid);
         return;
     }
     const int k0 = ((blockIdx.x - row * chunks) * 256 + threadIdx.x) * 16;
@@ -483,8 +494,9 @@ __global__ __launch_bounds__(256) void f_digits_rows_kernel(const uint32_t *__re
 #pragma unroll
     for (int c = 0; c < 16; ++c) d[c] = ok[c] ? digits_of(v[c]) : 0u;
     const long long plane = (long long)rows_pad * pitch;
-    const uint32_t hi = store_pieces(d, planes + (long long)row * pitch + k0, plane, sums);
-    raise_flag(flag, hi != 0);
+    uint32_t mid;
+    const uint32_t hi = store_pieces(d, planes + (long long)row * pitch + k0, plane, sums, mid);
+    raise_flag(flag, hi, mid);
 }
 
 // Encodings xbar[R][Ci][H*W] -> channels-last digit planes [4][R][H*W][cp]
@@ -525,7 +537,7 @@ __global__ __launch_bounds__(256) void f_digits_nhwc_kernel(const uint32_t *__re
         }
     }
     __syncthreads();
-    uint32_t hi = 0;
+    uint32_t hi = 0, mid = 0;
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
         const int item = threadIdx.x + 256 * r;       // (pixel, 16 channels)
@@ -541,11 +553,12 @@ __global__ __launch_bounds__(256) void f_digits_nhwc_kernel(const uint32_t *__re
             for (int a = 0; a < 4; ++a) w[a][g] = gather_byte(d, a);
         }
         hi |= w[2].x | w[2].y | w[2].z | w[2].w | w[3].x | w[3].y | w[3].z | w[3].w;
+        mid |= w[1].x | w[1].y | w[1].z | w[1].w;
 #pragma unroll
         for (int a = 0; a < 4; ++a)
             *reinterpret_cast<u32x4 *>(planes + a * plane + ((long long)img * HW + c0 + col) * cp + k0 + 16 * kq) = w[a];
     }
-    raise_flag(flag, hi != 0);
+    raise_flag(flag, hi, mid);
 }
 
 // Filters W[Co][Ci][kh*kw] -> digit planes [4][rows_pad][Kp] with the
@@ -568,14 +581,15 @@ __global__ __launch_bounds__(256) void f_digits_wconv_kernel(const uint32_t *__r
         }
     }
     const long long plane = (long long)rows_pad * Kp;
-    uint32_t hi = 0;
+    uint32_t hi = 0, mid = 0;
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
         const uint32_t w = gather_byte(d, a);
         if (a >= 2) hi |= w;
+        if (a == 1) mid |= w;
         *reinterpret_cast<uint32_t *>(planes + a * plane + (long long)row * Kp + k0) = w;
     }
-    raise_flag(flag, hi != 0);
+    raise_flag(flag, hi, mid);
 }
 
 __global__ void f_flag_clear_kernel(int *flags) { if (threadIdx.x < 2) flags[threadIdx.x] = 0; }
@@ -619,7 +633,14 @@ __device__ __forceinline__ uint32_t shift14(uint32_t t)
 // is mapped onto the planes' own pitches.  BMODE 1 is IMPL, 0 a stored matrix.
 // NBI: 32-row blocks of A per wave; the workgroup tile is (64 NBI) x 128 (a
 // 64-row tile keeps operands with at most 64 rows from wasting half the MFMAs).
-template <int BMODE, int NBI>
+// SINGLE: an operand whose elements all fit one digit (ordinary quantised
+// weights: |Round(w 2^l)| < 64) has an all-zero plane 1 as well; the SINGLE = 1
+// (A is such) and SINGLE = 2 (B is) variants move and multiply one plane of it
+// instead of two, half the MFMAs of a step.  The digit kernels' flags decide on
+// the device which variant does the work: the host launches the general kernel
+// and the variants named in p.single_mask one after the other, and the
+// workgroups of all but one of them return at once.
+template <int BMODE, int NBI, int SINGLE = 0>
 __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 {
     constexpr bool IMPL = BMODE == 1;
@@ -645,7 +666,8 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     const int rows_here = p.tiles_i - band * GI < GI ? p.tiles_i - band * GI : GI;
     const int tj = in_band / rows_here;
     const int ti = band * GI + (in_band - tj * rows_here);
-    const bool fa = p.flags[0] != 0, fb = p.flags[1] != 0;     // workgroup-uniform
+    const int flag_a = p.flags[0], flag_b = p.flags[1];        // workgroup-uniform
+    const bool fa = (flag_a & 1) != 0, fb = (flag_b & 1) != 0;
 
     const int kt0 = split * p.ktiles_per_split;
     int kt1 = kt0 + p.ktiles_per_split;
@@ -775,10 +797,12 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 #define DKF_FETCH_PIECES(E0, E1, F0, F1)                                                          \
     {                                                                                             \
         _Pragma("unroll") for (int e = (E0); e < (E1); ++e)                                       \
-            sa[e] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(              \
-                (e / (2 * NBI)) ? rsA1 : rsA0, (int)voff[e % (2 * NBI)], soff_, 0));              \
+            if (e / (2 * NBI) < npa_)                                                             \
+                sa[e] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(          \
+                    (e / (2 * NBI)) ? rsA1 : rsA0, (int)voff[e % (2 * NBI)], soff_, 0));          \
         _Pragma("unroll") for (int e = (F0); e < (F1); ++e) {                                     \
             const int pl = e >> 2, q = e & 3;                                                     \
+            if (pl >= npb_) continue;                                                             \
             if (BMODE == 0) {                                                                     \
                 sb[e] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(          \
                     pl ? rsB1 : rsB0, (int)voff[q], soff_, 0));                                   \
@@ -801,9 +825,11 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 #define DKF_STASH_PIECES(BUF, E0, E1, F0, F1)                                                     \
     {                                                                                             \
         _Pragma("unroll") for (int e = (E0); e < (E1); ++e)                                       \
-            *reinterpret_cast<i32x4 *>((BUF) + (e / (2 * NBI)) * A_PLANE + (e % (2 * NBI)) * 32 * PITCH + s_dst) = sa[e]; \
+            if (e / (2 * NBI) < npa_)                                                             \
+                *reinterpret_cast<i32x4 *>((BUF) + (e / (2 * NBI)) * A_PLANE + (e % (2 * NBI)) * 32 * PITCH + s_dst) = sa[e]; \
         _Pragma("unroll") for (int e = (F0); e < (F1); ++e)                                       \
-            *reinterpret_cast<i32x4 *>((BUF) + 2 * A_PLANE + (e >> 2) * B_PLANE + (e & 3) * 32 * PITCH + s_dst) = sb[e]; \
+            if ((e >> 2) < npb_)                                                                  \
+                *reinterpret_cast<i32x4 *>((BUF) + 2 * A_PLANE + (e >> 2) * B_PLANE + (e & 3) * 32 * PITCH + s_dst) = sb[e]; \
     }
     // Quarter U of a tile's pieces: written to LDS from the staging registers, which then
     // take the same pieces of the tile two steps ahead.
@@ -817,17 +843,21 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
             A[bi][0] = *reinterpret_cast<const i32x4 *>(cur + a_rd + bi * 32 * PITCH + (KS) * 32); \
         _Pragma("unroll") for (int bj = 0; bj < 2; ++bj)                                          \
             B[bj][0] = *reinterpret_cast<const i32x4 *>(cur + b_rd + bj * 32 * PITCH + (KS) * 32); \
-        _Pragma("unroll") for (int bj = 0; bj < 2; ++bj)                                          \
-            B[bj][1] = *reinterpret_cast<const i32x4 *>(cur + B_PLANE + b_rd + bj * 32 * PITCH + (KS) * 32); \
-        _Pragma("unroll") for (int bi = 0; bi < NBI; ++bi)                                          \
-            A[bi][1] = *reinterpret_cast<const i32x4 *>(cur + A_PLANE + a_rd + bi * 32 * PITCH + (KS) * 32); \
+        if (npb_ > 1) {                                                                           \
+            _Pragma("unroll") for (int bj = 0; bj < 2; ++bj)                                      \
+                B[bj][1] = *reinterpret_cast<const i32x4 *>(cur + B_PLANE + b_rd + bj * 32 * PITCH + (KS) * 32); \
+        }                                                                                         \
+        if (npa_ > 1) {                                                                           \
+            _Pragma("unroll") for (int bi = 0; bi < NBI; ++bi)                                    \
+                A[bi][1] = *reinterpret_cast<const i32x4 *>(cur + A_PLANE + a_rd + bi * 32 * PITCH + (KS) * 32); \
+        }                                                                                         \
     }
     // digit pairs outermost: four independent accumulators lie between two
     // MFMAs into the same one
 #define DKF_MMA(A, B)                                                                             \
     {                                                                                             \
-        _Pragma("unroll") for (int pa = 0; pa < 2; ++pa)                                          \
-            _Pragma("unroll") for (int pb = 0; pb < 2; ++pb)                                      \
+        _Pragma("unroll") for (int pa = 0; pa < npa_; ++pa)                                       \
+            _Pragma("unroll") for (int pb = 0; pb < npb_; ++pb)                                   \
                 _Pragma("unroll") for (int bi = 0; bi < NBI; ++bi)                                  \
                     _Pragma("unroll") for (int bj = 0; bj < 2; ++bj)                              \
                         acc[bi][bj][pa + pb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(             \
@@ -838,9 +868,10 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     // quarter of the staging registers.  Spread like this the global loads of the four waves
     // reach the vector-memory path at the rate it takes them; issued in one burst at the end
     // of a step they held the waves (and so the matrix pipes) until it had taken them all.
-#define DKF_PACE(NR)                                                                              \
+#define DKF_PACE(NR, U)                                                                           \
     {                                                                                             \
-        constexpr int nw_ = NBI + 2, nm_ = 8 * NBI;                                               \
+        constexpr int nw_ = ((U) / 2 < npa_ ? NBI : 0) + ((U) / 2 < npb_ ? 2 : 0);                \
+        constexpr int nm_ = 2 * npa_ * npb_ * NBI;                                                \
         constexpr int both_ = (NR) + nw_ > nm_ ? (NR) + nw_ - nm_ : 0;                            \
         _Pragma("unroll") for (int e = 0; e < (NR) - both_; ++e) {                                \
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    \
@@ -862,17 +893,56 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
     {                                                                                             \
         _Pragma("unroll") for (int x = 0; x < 2; ++x)                                             \
             _Pragma("unroll") for (int y = 0; y < 2; ++y) {                                       \
-                if (x < NBI) asm volatile("" ::"v"(A[x][y]));                                     \
-                asm volatile("" ::"v"(B[x][y]));                                                  \
+                if (x < NBI && y < npa_) asm volatile("" ::"v"(A[x][y]));                         \
+                if (y < npb_) asm volatile("" ::"v"(B[x][y]));                                    \
             }                                                                                     \
+    }
+    // Four 32-k sub-steps with NPA planes of A and NPB of B.  The operands of sub-step
+    // u+1 are read from LDS while the MFMAs of sub-step u issue; each sub-step also moves a
+    // quarter of the staging registers (tile s+1) to the other LDS buffer and refills them
+    // from tile s+2 (past the last step: part 0 of a valid k tile, never used).  Quarters
+    // 0, 1 are the pieces of plane 0 and quarters 2, 3 those of plane 1 of both operands.
+#define DKF_STEP(NPA, NPB)                                                                        \
+    {                                                                                             \
+        constexpr int npa_ = (NPA), npb_ = (NPB), nr_ = npa_ * NBI + npb_ * 2;                    \
+        i32x4 a0[NBI][2], b0[2][2], a1[NBI][2], b1[2][2];                                         \
+        DKF_READ(a0, b0, 0)                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                        \
+        DKF_READ(a1, b1, 1)                                                                       \
+        DKF_MMA(a0, b0)                                                                           \
+        DKF_TURN(nxt, 0)                                                                          \
+        DKF_PACE(nr_, 0)                                                                          \
+        DKF_KEEP(a0, b0)                                                                          \
+        DKF_READ(a0, b0, 2)                                                                       \
+        DKF_MMA(a1, b1)                                                                           \
+        DKF_TURN(nxt, 1)                                                                          \
+        DKF_PACE(nr_, 1)                                                                          \
+        DKF_KEEP(a1, b1)                                                                          \
+        DKF_READ(a1, b1, 3)                                                                       \
+        DKF_MMA(a0, b0)                                                                           \
+        DKF_TURN(nxt, 2)                                                                          \
+        DKF_PACE(nr_, 2)                                                                          \
+        DKF_KEEP(a0, b0)                                                                          \
+        DKF_MMA(a1, b1)                                                                           \
+        DKF_TURN(nxt, 3)                                                                          \
+        DKF_PACE(0, 3)                                                                            \
     }
     // (part index, k tile) of a step advance like a two-digit counter
 #define DKF_ADVANCE(PI, KT)                                                                       \
     {                                                                                             \
         if (KT + 1 == kt1) { KT = kt0; ++PI; } else ++KT;                                         \
     }
+    constexpr int npa_ = 2, npb_ = 2;     // planes per operand outside the single-digit steps
     int pi = 0, kt = kt0;                 // part index and k tile of the current step
     int pi2 = 0, kt2 = kt0;               // ... of the step the next fetch is for
+    // With one-plane launches alongside, the flags name the launch that does this product
+    // (uniform; the workgroups of the others leave before they touch memory).
+    if (p.single_mask) {
+        const int single = ((p.single_mask & 1) && flag_a == 0) ? 1 : ((p.single_mask & 2) && flag_b == 0) ? 2 : 0;
+        if (single != SINGLE) return;
+    } else if (SINGLE) {
+        return;
+    }
     // The first part is (lo,lo) whatever the flags say: its first tile is on its way before
     // the flags (a dependent scalar load) are looked at.
     if (kt1 > kt0) {
@@ -919,32 +989,8 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
         for (; step < g_end; ++step) {
             const int8_t *cur = flds + (step & 1) * BUF_BYTES;
             int8_t *nxt = flds + ((step + 1) & 1) * BUF_BYTES;
-            // Four 32-k sub-steps.  The operands of sub-step u+1 are read from LDS while
-            // the MFMAs of sub-step u issue; each sub-step also moves a quarter of the
-            // staging registers (tile s+1) to the other LDS buffer and refills them from
-            // tile s+2 (past the last step: part 0 of a valid k tile, never used).
             DKF_FETCH_PREP(kt2)
-            i32x4 a0[NBI][2], b0[2][2], a1[NBI][2], b1[2][2];
-            DKF_READ(a0, b0, 0)
-            __builtin_amdgcn_sched_barrier(0);
-            DKF_READ(a1, b1, 1)
-            DKF_MMA(a0, b0)
-            DKF_TURN(nxt, 0)
-            DKF_PACE(2 * NBI + 4)
-            DKF_KEEP(a0, b0)
-            DKF_READ(a0, b0, 2)
-            DKF_MMA(a1, b1)
-            DKF_TURN(nxt, 1)
-            DKF_PACE(2 * NBI + 4)
-            DKF_KEEP(a1, b1)
-            DKF_READ(a1, b1, 3)
-            DKF_MMA(a0, b0)
-            DKF_TURN(nxt, 2)
-            DKF_PACE(2 * NBI + 4)
-            DKF_KEEP(a0, b0)
-            DKF_MMA(a1, b1)
-            DKF_TURN(nxt, 3)
-            DKF_PACE(0)
+            DKF_STEP(SINGLE == 1 ? 1 : 2, SINGLE == 2 ? 1 : 2)
             __syncthreads();
             DKF_ADVANCE(pi, kt)
             DKF_ADVANCE(pi2, kt2)
@@ -1015,6 +1061,7 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
 #undef DKF_TURN
 #undef DKF_READ
 #undef DKF_MMA
+#undef DKF_STEP
 
     uint32_t *dst_q = p.out_q ? p.out_q + (long long)split * p.I * p.J : nullptr;   // (one slice if remapped)
     if (!p.out_hw && ti * BI + BI <= p.I && tj * BJ + BJ <= p.J) {
@@ -1174,18 +1221,25 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
                     const int *flags, uint32_t *out_q, float *out_f, int l, float scale,
                     int accumulate, int out_hw, const char *label, hipStream_t st,
                     const fconv_geom *impl = nullptr, long long impl_plane = 0,
-                    const fshift *shift = nullptr)
+                    const fshift *shift = nullptr, int single_mask = 0)
 {
-    static std::atomic<unsigned long long> allowed[6];
-    const void *kernels[6] = {reinterpret_cast<const void *>(f_gemm_kernel<0, 1>),
-                              reinterpret_cast<const void *>(f_gemm_kernel<0, 2>),
-                              reinterpret_cast<const void *>(f_gemm_kernel<1, 1>),
-                              reinterpret_cast<const void *>(f_gemm_kernel<1, 2>),
-                              reinterpret_cast<const void *>(f_gemm_kernel<2, 1>),
-                              reinterpret_cast<const void *>(f_gemm_kernel<2, 2>)};
-    const int which = (shift ? 4 : impl ? 2 : 0) + (pl.nbi == 1 ? 0 : 1);
-    const dk_status as = dk_allow_dynamic_lds(kernels[which], LDS_BYTES, allowed[which]);
-    if (as != DK_OK) return as;
+    using kernel_t = void (*)(fgemm_params);
+    // [operand form][NBI - 1][SINGLE]; a null entry is a variant no caller asks for
+    static const kernel_t kernels[3][2][3] = {
+        {{f_gemm_kernel<0, 1, 0>, f_gemm_kernel<0, 1, 1>, f_gemm_kernel<0, 1, 2>},
+         {f_gemm_kernel<0, 2, 0>, f_gemm_kernel<0, 2, 1>, f_gemm_kernel<0, 2, 2>}},
+        {{f_gemm_kernel<1, 1, 0>, f_gemm_kernel<1, 1, 1>, nullptr},
+         {f_gemm_kernel<1, 2, 0>, f_gemm_kernel<1, 2, 1>, nullptr}},
+        {{f_gemm_kernel<2, 1, 0>, nullptr, nullptr}, {f_gemm_kernel<2, 2, 0>, nullptr, nullptr}}};
+    static std::atomic<unsigned long long> allowed[3][2][3];
+    const int form = shift ? 2 : impl ? 1 : 0, nb = pl.nbi == 1 ? 0 : 1;
+    for (int sg = 0; sg < 3; ++sg) {
+        if (sg && !(single_mask >> (sg - 1) & 1)) continue;
+        DK_REQUIRE(kernels[form][nb][sg] != nullptr, DK_ERR_UNSUPPORTED);
+        const dk_status as = dk_allow_dynamic_lds(reinterpret_cast<const void *>(kernels[form][nb][sg]),
+                                                  LDS_BYTES, allowed[form][nb][sg]);
+        if (as != DK_OK) return as;
+    }
     const bool direct = pl.splits == 1;
     fgemm_params p;
     p.Ap = Ap; p.Bp = Bp; p.flags = flags;
@@ -1198,6 +1252,7 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
     p.ktiles_per_split = pl.ktiles_per_split; p.ktiles = pl.ktiles;
     p.s_inv = ldexp(1.0, -l); p.lq = l; p.scale = scale; p.accumulate = accumulate;
     p.sums = pl.sums;
+    p.single_mask = single_mask;
     p.out_hw = direct ? out_hw : 0;
     p.cp = p.cH = p.cW = p.ckh = p.ckw = p.cstride = p.cpad = p.cWo = p.cHoWo = 0;
     if (impl) {
@@ -1217,12 +1272,8 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
     {
         dk_prof_scope ps(label, st);
         const dim3 grid((unsigned)blocks), block(256);
-        if (shift && pl.nbi == 1) f_gemm_kernel<2, 1><<<grid, block, LDS_BYTES, st>>>(p);
-        else if (shift)          f_gemm_kernel<2, 2><<<grid, block, LDS_BYTES, st>>>(p);
-        else if (impl && pl.nbi == 1) f_gemm_kernel<1, 1><<<grid, block, LDS_BYTES, st>>>(p);
-        else if (impl)           f_gemm_kernel<1, 2><<<grid, block, LDS_BYTES, st>>>(p);
-        else if (pl.nbi == 1)    f_gemm_kernel<0, 1><<<grid, block, LDS_BYTES, st>>>(p);
-        else                     f_gemm_kernel<0, 2><<<grid, block, LDS_BYTES, st>>>(p);
+        for (int sg = 0; sg < 3; ++sg)
+            if (!sg || (single_mask >> (sg - 1) & 1)) kernels[form][nb][sg]<<<grid, block, LDS_BYTES, st>>>(p);
     }
     if (direct) return dk_launch_status();
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
@@ -1394,6 +1445,10 @@ DK_EXPORT dk_status dkf_conv_fwd(const dk_layer *L, const uint32_t *Wq, const ui
     int8_t *Ap = (int8_t *)w;                      w += pl.a_bytes;
     int8_t *Bp = (int8_t *)w;                      w += pl.b_bytes;
     uint32_t *part = (uint32_t *)w;
+    // The one-plane steps for filters that fit one digit (A holds the filters) pay where
+    // the matrix pipe bounds the product; with at most 64 output channels the gathered
+    // operand does, and the second launch would only cost its start-up.
+    const int filters_single = pl.nbi == 2 ? 1 : 0;
 
     {
         dk_prof_scope ps("f_flag_clear", st);
@@ -1419,7 +1474,7 @@ DK_EXPORT dk_status dkf_conv_fwd(const dk_layer *L, const uint32_t *Wq, const ui
         DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
         const fconv_geom cg = conv_geom_of(g);
         return run_fgemm(pl, Ap, Bp, part, flag, ybar, nullptr, 0, 1.0f, 0, g.Ho * g.Wo, "f_gemm_fwd", st,
-                         &cg, plane);
+                         &cg, plane, nullptr, filters_single);
     }
     dk_status s = run_digits(Wq, Ap, g.Co, (int)g.Kg, pl.I_pad, pl.Kp, flag, st);
     if (s != DK_OK) return s;
@@ -1430,7 +1485,8 @@ DK_EXPORT dk_status dkf_conv_fwd(const dk_layer *L, const uint32_t *Wq, const ui
             xbar, Bp, conv_geom_of(g), (int)g.Kg, pl.J, pl.J_pad, pl.Kp, 0, flag + 1);
     }
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
-    return run_fgemm(pl, Ap, Bp, part, flag, ybar, nullptr, 0, 1.0f, 0, g.Ho * g.Wo, "f_gemm_fwd", st);
+    return run_fgemm(pl, Ap, Bp, part, flag, ybar, nullptr, 0, 1.0f, 0, g.Ho * g.Wo, "f_gemm_fwd", st,
+                     nullptr, 0, nullptr, filters_single);
 }
 
 DK_EXPORT size_t dkf_fwd_workspace_bytes(int M, int N, int R)
@@ -1488,7 +1544,8 @@ dk_status linear_fwd_impl(const uint32_t *Wq, const float *W, int l, const uint3
     s = Wq ? run_digits(Wq, Bp, M, N, pl.J_pad, pl.Kp, flag + 1, st)
            : run_digits_f32(W, l, Bp, M, N, pl.J_pad, pl.Kp, flag + 1, st);
     if (s != DK_OK) return s;
-    return run_fgemm(pl, Ap, Bp, part, flag, ybar, nullptr, 0, 1.0f, 0, 0, "f_gemm_fwd", st);
+    return run_fgemm(pl, Ap, Bp, part, flag, ybar, nullptr, 0, 1.0f, 0, 0, "f_gemm_fwd", st,
+                     nullptr, 0, nullptr, /*single_mask (B holds the weights)*/ 2);
 }
 
 } // namespace

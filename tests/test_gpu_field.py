@@ -86,6 +86,32 @@ def test_linear_fwd_digit_halves_skipped(dk, x_small, w_small):
     assert not host(dk.dkf_linear_fwd(dev(W), dev(Z))).any()
 
 
+@pytest.mark.parametrize("top", [63, 64, 127, 8191])
+def test_forward_one_digit_weights(dk, top):
+    """Weights whose field images all lie in [-64, 63] occupy one digit plane and take the
+    one-plane steps; a single element just outside (64, or -65) must switch them off.  Dense
+    product, convolution read in place (16 channels) and through the stored patch matrix."""
+    rng = np.random.default_rng([top, 41])
+    def weights(shape):
+        w = rng.integers(-64, 64, size=shape)
+        w.reshape(-1)[:2] = (-64, 63)
+        if top > 63:
+            w.reshape(-1)[w.size // 2] = top
+            w.reshape(-1)[w.size // 3] = -top - 1
+        return (w % P).astype(np.uint32)
+    for R, M, N in ((150, 140, 260), (70, 64, 1000)):
+        X = rng.integers(0, P, size=(R, N), dtype=np.uint32)
+        W = weights((M, N))
+        assert np.array_equal(host(dk.dkf_linear_fwd(dev(W), dev(X))), F.dense_fwd(W, X))
+    for Ci, Co, H, k, stride, pad in ((16, 96, 12, 3, 1, 1), (32, 130, 9, 3, 2, 1), (3, 70, 10, 5, 1, 2),
+                                     (16, 40, 12, 3, 1, 1)):
+        L = dk_inputs.conv(Ci, Co, H, H, k, stride, pad)
+        X = rng.integers(0, P, size=(5, Ci, H, H), dtype=np.uint32)
+        W = weights((Co, Ci, k, k))
+        got = host(dk.dkf_conv_fwd(L, dev(W), dev(X)))
+        assert np.array_equal(got, F.conv_fwd(W, X, stride=stride, pad=pad))
+
+
 def test_linear_fwd_extreme_digits(dk):
     """Operands at the ends of the centred range and at digit boundaries."""
     vals = np.array([0, 1, P - 1, P // 2, P // 2 + 1, 63, 64, 65, P - 64, P - 65, 8191, 8192, 8256, 8257,
