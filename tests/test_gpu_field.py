@@ -363,6 +363,48 @@ def test_config2_field_sampled(dk):
     assert np.array_equal(host(dW), F.dequantize(got))
 
 
+@pytest.mark.parametrize("cfg,index", [(3, 3), (3, 8), (4, 11), (4, 13), (4, 16)])
+def test_config34_field_layers_sampled(dk, cfg, index):
+    """Layers of configs 3 and 4 with more than 64 output channels over the field at full size
+    (3x3 at 16x16 and 4x4, 3x3 stride 2, 1x1 256->1024 and 1024->512): the He-initialised
+    filters fit one digit plane, so their forward takes the one-plane steps of the contraction,
+    except those of the 1x1 256->1024 layer (smallest fan-in: a few weights lie beyond 63/256),
+    which takes two planes.
+    The oracle evaluates sampled outputs of the two contractions."""
+    d = dk_inputs.config3_field(index=index) if cfg == 3 else dk_inputs.config4_field(index=index)[0]
+    L, K, G = d["layer"], d["K"], d["G"]
+    S = K + 2
+    rng = np.random.default_rng([cfg, index, 5])
+    Ainv, nvec, B = dk.dkf_coeffs(d["A"], d["gamma"])
+    Wq_o = F.quantize(d["W"])
+    lifted = np.where(Wq_o > P // 2, Wq_o.astype(np.int64) - P, Wq_o.astype(np.int64))
+    assert L.Co > 64 and (lifted.min() >= -64 and lifted.max() <= 63) == (index != 13)
+    xbar_o = F.encode(F.quantize(d["X"]), d["r"], d["A"])
+    xbar = dk.dkf_encode(dev(d["X"]), dev(d["r"]), dev(d["A"]), K)
+    assert np.array_equal(host(xbar), xbar_o)
+    ybar = dk.dkf_conv_fwd(L, dk.dkf_quantize(dev(d["W"])), xbar)
+    yb = host(ybar)
+    n = 3000
+    pts = np.stack([rng.integers(0, G * S, n), rng.integers(0, L.Co, n), rng.integers(0, L.Ho, n),
+                    rng.integers(0, L.Wo, n)], 1)
+    pts[:4, 2:] = [[0, 0], [0, L.Wo - 1], [L.Ho - 1, 0], [L.Ho - 1, L.Wo - 1]]
+    pts[:4, :2] = [[0, 0], [G * S - 1, L.Co - 1], [0, L.Co - 1], [G * S - 1, 0]]
+    assert np.array_equal(yb[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]],
+                          F.conv_fwd_points(Wq_o, xbar_o, pts, L.stride, L.pad))
+    y, yq, verdict = dk.dkf_decode_verify(ybar, dev(Ainv), dev(nvec), K, want_yq=True)
+    assert not host(verdict).any() and not F.verify(yb, nvec).any()
+    assert np.array_equal(host(yq), F.decode(yb, Ainv))
+    dW, dwq = dk.dkf_wgrad(L, dev(d["delta"]), dev(B), dev(d["gamma"]), xbar, K, want_dwq=True)
+    dt_o = F.delta_mix(F.quantize(d["delta"]), B, d["gamma"])
+    m = 200
+    wpts = np.stack([rng.integers(0, L.Co, m), rng.integers(0, L.Ci, m), rng.integers(0, L.kh, m),
+                     rng.integers(0, L.kw, m)], 1)
+    got = host(dwq)
+    assert np.array_equal(got[wpts[:, 0], wpts[:, 1], wpts[:, 2], wpts[:, 3]],
+                          F.conv_wgrad_points(dt_o, xbar_o, L.kh, L.kw, wpts, L.stride, L.pad))
+    assert np.array_equal(host(dW), F.dequantize(got))
+
+
 def test_field_arguments_refused(dk):
     import torch
     from paper_2207_00083_amd import DkError
