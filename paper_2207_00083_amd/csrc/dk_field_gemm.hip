@@ -4,14 +4,14 @@
 // A field element is first lifted to its centred representative in
 // (-p/2, p/2) and written as four balanced base-128 digits,
 //     v = e0 + 128 e1 + 128^2 e2 + 128^3 e3,   e0..e2 in [-64, 63], |e3| <= 8,
-// one int8 plane per digit.  A product of two elements is then the sum of 16
+// one int8 plane per digit (a lift within [-127, 127] stays one digit e0 = v).  A product of two elements is then the sum of 16
 // digit products weighted by 128^(a+b).  The digits of each operand are taken
 // in two halves ("low" = digits 0,1; "high" = digits 2,3); one part of a launch
 // multiplies one half of A with one half of B and keeps one int32 accumulator
 // per weight 128^s, s = 0..2 (more accumulators than that do not fit the 256
 // accumulation registers of a wave with a 64 x 64 tile).  An accumulator holds
-// at most two digit products per k, each at most 2^12 in magnitude, so 2^17
-// values of k fit with room to spare.  The epilogue recombines the three
+// at most two digit products per k, each at most 2^12 in magnitude, or one of
+// two single-digit elements, at most 127^2: 2^17 values of k fit.  The epilogue recombines the three
 // accumulators in 64 bits, reduces modulo p and applies the part's weight
 // 128^(2 (ha + hb)).  A workgroup runs the four parts of its tile one after the
 // other and adds their residues in registers; a part that involves a high half
@@ -76,11 +76,19 @@ struct fgemm_params {
     int single_mask;       // bit 0: a SINGLE = 1 launch accompanies this one, bit 1: a SINGLE = 2 launch
 };
 
-// Four balanced base-128 digits of the centred lift of q, packed one per byte.
+// Four base-128 digits of the centred lift of q, packed one per byte: balanced
+// digits in [-64, 63], except that a lift within [-127, 127] is its own single
+// digit (a byte holds it, and ordinary quantised weights then occupy one plane
+// up to twice the magnitude).  Either way the lift is sum_i e_i 128^i with
+// |e_0| <= 127, |e_i| <= 64 above it, and e_0 beyond [-64, 63] only next to
+// zero higher digits: a digit product is at most 127^2 where both factors are
+// such single digits (127^2 2^17 < 2^31) and at most 127 * 64 < 2^13 otherwise,
+// and a digit sum of the halves is the digit itself.
 __device__ __forceinline__ uint32_t digits_of(uint32_t q)
 {
     int w = (int)q;
     if (q > DKF_P / 2) w -= (int)DKF_P;
+    if (w >= -127 && w <= 127) return (uint32_t)(w & 255);
     const int e0 = ((w + 64) & 127) - 64;
     w = (w - e0) >> 7;
     const int e1 = ((w + 64) & 127) - 64;
@@ -634,7 +642,7 @@ __device__ __forceinline__ uint32_t shift14(uint32_t t)
 // NBI: 32-row blocks of A per wave; the workgroup tile is (64 NBI) x 128 (a
 // 64-row tile keeps operands with at most 64 rows from wasting half the MFMAs).
 // SINGLE: an operand whose elements all fit one digit (ordinary quantised
-// weights: |Round(w 2^l)| < 64) has an all-zero plane 1 as well; the SINGLE = 1
+// weights: |Round(w 2^l)| <= 127) has an all-zero plane 1 as well; the SINGLE = 1
 // (A is such) and SINGLE = 2 (B is) variants move and multiply one plane of it
 // instead of two, half the MFMAs of a step.  The digit kernels' flags decide on
 // the device which variant does the work: the host launches the general kernel

@@ -86,16 +86,16 @@ def test_linear_fwd_digit_halves_skipped(dk, x_small, w_small):
     assert not host(dk.dkf_linear_fwd(dev(W), dev(Z))).any()
 
 
-@pytest.mark.parametrize("top", [63, 64, 127, 8191])
+@pytest.mark.parametrize("top", [127, 128, 200, 8191])
 def test_forward_one_digit_weights(dk, top):
-    """Weights whose field images all lie in [-64, 63] occupy one digit plane and take the
-    one-plane steps; a single element just outside (64, or -65) must switch them off.  Dense
+    """Weights whose field images all lie in [-127, 127] occupy one digit plane and take the
+    one-plane steps; a single element just outside (128, or -129) must switch them off.  Dense
     product, convolution read in place (16 channels) and through the stored patch matrix."""
     rng = np.random.default_rng([top, 41])
     def weights(shape):
-        w = rng.integers(-64, 64, size=shape)
-        w.reshape(-1)[:2] = (-64, 63)
-        if top > 63:
+        w = rng.integers(-127, 128, size=shape)
+        w.reshape(-1)[:4] = (-127, 127, 64, -65)
+        if top > 127:
             w.reshape(-1)[w.size // 2] = top
             w.reshape(-1)[w.size // 3] = -top - 1
         return (w % P).astype(np.uint32)
@@ -114,8 +114,9 @@ def test_forward_one_digit_weights(dk, top):
 
 def test_linear_fwd_extreme_digits(dk):
     """Operands at the ends of the centred range and at digit boundaries."""
-    vals = np.array([0, 1, P - 1, P // 2, P // 2 + 1, 63, 64, 65, P - 64, P - 65, 8191, 8192, 8256, 8257,
-                     P - 8256, P - 8257, 1 << 21, (1 << 24) - 1], dtype=np.uint32)
+    vals = np.array([0, 1, P - 1, P // 2, P // 2 + 1, 63, 64, 65, P - 64, P - 65, 127, 128, 129, P - 127,
+                     P - 128, P - 129, 8191, 8192, 8256, 8257, P - 8256, P - 8257, 1 << 21, (1 << 24) - 1],
+                    dtype=np.uint32)
     X = np.tile(vals, (len(vals), 1))
     W = np.tile(vals[:, None], (1, len(vals)))
     got = host(dk.dkf_linear_fwd(dev(np.ascontiguousarray(W)), dev(X)))
@@ -127,6 +128,11 @@ def test_linear_fwd_extreme_digits(dk):
     X = np.full((2, N), v, dtype=np.uint32)
     W = np.full((3, N), v, dtype=np.uint32)
     assert np.array_equal(host(dk.dkf_linear_fwd(dev(W), dev(X))), F.dense_fwd(W, X))
+    # the largest single-digit elements (a lift of +-127 is one digit): products of 127^2
+    for vx, vw in ((127, 127), (P - 127, 127), (P - 127, P - 127)):
+        X = np.full((2, N), vx, dtype=np.uint32)
+        W = np.full((3, N), vw, dtype=np.uint32)
+        assert np.array_equal(host(dk.dkf_linear_fwd(dev(W), dev(X))), F.dense_fwd(W, X))
 
 
 @pytest.mark.parametrize("K,G,m", [(1, 2, 33), (2, 3, 512), (4, 4, 1028), (8, 2, 1000), (16, 1, 77)])
@@ -193,11 +199,13 @@ def test_masked_dense_layer(dk, K, G, M, N):
     assert np.array_equal(lift, Xi @ Wi.T)
 
 
-@pytest.mark.parametrize("va,vb", [(-15736896, -15736896), (-15736896, 15720383), (15720383, 15720383)])
+@pytest.mark.parametrize("va,vb", [(-15736896, -15736896), (-15736896, 15720383), (15720383, 15720383),
+                                   (127, 127), (-127, 127), (-127, 15720383)])
 def test_wgrad_extreme_digit_sums(dk, va, vb):
     """Operands whose base-128 digits are all at one end (-64, -64, -64, -7 or
     63, 63, 63, 7), on every row: the digit sums of the halves reach -128 and
-    126, the largest accumulator growth per term of the weight gradient."""
+    126, the largest accumulator growth per term of the weight gradient; and
+    the largest single-digit elements (+-127, one digit each)."""
     G, K, M, N = 700, 1, 70, 130
     S = K + 2
     L = dk_inputs.linear(M, N)
