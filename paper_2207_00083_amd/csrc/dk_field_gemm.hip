@@ -1102,6 +1102,25 @@ __global__ __launch_bounds__(256) void f_gemm_kernel(fgemm_params p)
             }
         return;
     }
+    if (p.out_hw && !p.out_f && dst_q && ti * BI + BI <= p.I && tj * BJ + BJ <= p.J) {
+        // Tile inside an image-major result (a convolution's forward): a lane's two columns
+        // are two (image, pixel) pairs, one address each; rows are uniform multiples of hw.
+#pragma unroll
+        for (int bj = 0; bj < 2; ++bj) {
+            const int j = tj * BJ + wj0 + bj * 32 + li;
+            const int jimg = j / p.out_hw, jpix = j - jimg * p.out_hw;
+            uint32_t *q0 = dst_q + ((long long)jimg * p.I + (ti * BI + wi0 + 4 * lh)) * p.out_hw + jpix;
+#pragma unroll
+            for (int bi = 0; bi < NBI; ++bi)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const uint32_t r = res[bi][bj][v];                                 // < 2^28
+                    const uint32_t u = __umul24(r >> 25, 39u) + (r & 0x1ffffffu);
+                    q0[(long long)(bi * 32 + 8 * (v / 4) + (v % 4)) * p.out_hw] = u >= DKF_P ? u - DKF_P : u;
+                }
+        }
+        return;
+    }
 #pragma unroll
     for (int bi = 0; bi < NBI; ++bi)
 #pragma unroll
