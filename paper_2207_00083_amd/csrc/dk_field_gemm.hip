@@ -88,15 +88,17 @@ __device__ __forceinline__ uint32_t digits_of(uint32_t q)
 {
     int w = (int)q;
     if (q > DKF_P / 2) w -= (int)DKF_P;
-    if (w >= -127 && w <= 127) return (uint32_t)(w & 255);
-    const int e0 = ((w + 64) & 127) - 64;
-    w = (w - e0) >> 7;
-    const int e1 = ((w + 64) & 127) - 64;
-    w = (w - e1) >> 7;
-    const int e2 = ((w + 64) & 127) - 64;
-    const int e3 = (w - e2) >> 7;
-    return (uint32_t)(e0 & 255) | (uint32_t)(e1 & 255) << 8 | (uint32_t)(e2 & 255) << 16 |
-           (uint32_t)(e3 & 255) << 24;
+    // With 64 added to each of the three low digits they are the plain 7-bit fields of
+    // u = w + 64 (1 + 128 + 128^2), and what lies above them is e3 (arithmetic shifts keep
+    // this true for negative u).  The fields are spread to one per byte, 64 is taken off
+    // again by flipping bit 6, and bit 7 becomes a copy of bit 6 (the sign of a value in
+    // [-64, 63]).
+    const int u = w + 64 * (1 + 128 + 128 * 128);
+    uint32_t x = ((uint32_t)u & 0x7fu) | (((uint32_t)u << 1) & 0x7f00u) | (((uint32_t)u << 2) & 0x7f0000u);
+    x ^= 0x404040u;
+    x |= (x & 0x404040u) << 1;
+    x |= (uint32_t)(u >> 21) << 24;
+    return (uint32_t)(w + 127) <= 254u ? (uint32_t)(w & 255) : x;
 }
 
 // (e0 + e2, e1 + e3) of a packed-digit word in its two low bytes: a byte-wise
@@ -110,9 +112,11 @@ __device__ __forceinline__ uint32_t half_sums(uint32_t d)
 // byte `a` of four packed-digit words -> one word of plane a
 __device__ __forceinline__ uint32_t gather_byte(const uint32_t (&d)[4], int a)
 {
-    const int sh = 8 * a;
-    return ((d[0] >> sh) & 255u) | ((d[1] >> sh) & 255u) << 8 | ((d[2] >> sh) & 255u) << 16 |
-           ((d[3] >> sh) & 255u) << 24;
+    // byte permutes: (byte a of d0, byte a of d1), the same of d2, d3, then the two pairs
+    const uint32_t sel = 0x0c0c0000u | (uint32_t)a | (uint32_t)(4 + a) << 8;
+    const uint32_t p01 = __builtin_amdgcn_perm(d[1], d[0], sel);
+    const uint32_t p23 = __builtin_amdgcn_perm(d[3], d[2], sel);
+    return __builtin_amdgcn_perm(p23, p01, 0x05040100u);
 }
 
 // Sixteen packed-digit words -> one 16-byte piece of each plane at `dst`
@@ -508,40 +512,48 @@ __global__ __launch_bounds__(256) void f_digits_rows_kernel(const uint32_t *__re
 }
 
 // Encodings xbar[R][Ci][H*W] -> channels-last digit planes [4][R][H*W][cp]
-// (cp = Ci, a multiple of 16): per image a tile of 128 channels x 64 pixels goes
+// (cp = Ci, a multiple of 16): per image a tile of KC channels x 8192 / KC
+// pixels (128 x 64, or 64 x 128 when there are at most 64 channels) goes
 // through LDS as packed digits; a thread then writes 16 consecutive channels of
-// one pixel to each plane.
+// one pixel to each plane.  Row k of the LDS tile is rotated by (k / 16) * 512 / KC
+// words, so that the lanes of a wave, which read one word each from rows 16
+// apart, meet distinct banks.
+template <int KC>
 __global__ __launch_bounds__(256) void f_digits_nhwc_kernel(const uint32_t *__restrict__ src,
                                                             int8_t *__restrict__ planes, int Ci, int HW,
                                                             int cp, long long plane, int vec, int *flag)
 {
-    __shared__ uint32_t tile[128][65];
-    const int c0 = blockIdx.x * 64, k0 = blockIdx.y * 128, img = blockIdx.z;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    constexpr int PX = 8192 / KC, ROT = 512 / KC, KQ = KC / 16;
+    __shared__ __attribute__((aligned(16))) uint32_t tile[KC * PX];
+    const int c0 = blockIdx.x * PX, k0 = blockIdx.y * KC, img = blockIdx.z;
     const uint32_t *s = src + (long long)img * Ci * HW;
     if (vec) {
         // HW % 4 == 0 and an aligned base: eight 16-byte loads per thread, all in
-        // flight at once (16 lanes per channel row of the tile)
+        // flight at once (PX / 4 lanes per channel row of the tile)
         u32x4 t[8];
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const int item = threadIdx.x + 256 * r;
-            const int k = k0 + (item >> 4), c = c0 + (item & 15) * 4;
+            const int k = k0 + item / (PX / 4), c = c0 + (item % (PX / 4)) * 4;
             t[r] = u32x4{0, 0, 0, 0};
             if (k < Ci && c < HW) t[r] = *reinterpret_cast<const u32x4 *>(s + (long long)k * HW + c);
         }
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const int item = threadIdx.x + 256 * r;
-            uint32_t *dst = &tile[item >> 4][(item & 15) * 4];
-            dst[0] = digits_of(t[r].x); dst[1] = digits_of(t[r].y);
-            dst[2] = digits_of(t[r].z); dst[3] = digits_of(t[r].w);
+            const int kl = item / (PX / 4), c = (item % (PX / 4)) * 4;
+            u32x4 d;
+            d.x = digits_of(t[r].x); d.y = digits_of(t[r].y); d.z = digits_of(t[r].z); d.w = digits_of(t[r].w);
+            *reinterpret_cast<u32x4 *>(&tile[kl * PX + ((c + (kl >> 4) * ROT) & (PX - 1))]) = d;
         }
     } else {
 #pragma unroll 8
         for (int r = 0; r < 32; ++r) {
-            const int k = k0 + ty + 4 * r, c = c0 + tx;
-            tile[ty + 4 * r][tx] = (k < Ci && c < HW) ? digits_of(s[(long long)k * HW + c]) : 0u;
+            const int e = threadIdx.x + 256 * r;
+            const int kl = e / PX, cl = e % PX;
+            const int k = k0 + kl, c = c0 + cl;
+            tile[kl * PX + ((cl + (kl >> 4) * ROT) & (PX - 1))] =
+                (k < Ci && c < HW) ? digits_of(s[(long long)k * HW + c]) : 0u;
         }
     }
     __syncthreads();
@@ -549,14 +561,15 @@ __global__ __launch_bounds__(256) void f_digits_nhwc_kernel(const uint32_t *__re
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
         const int item = threadIdx.x + 256 * r;       // (pixel, 16 channels)
-        const int kq = item & 7, col = item >> 3;
+        const int kq = item % KQ, col = item / KQ;
         if (c0 + col >= HW || k0 + 16 * kq >= cp) continue;
+        const int at = (col + kq * ROT) & (PX - 1);
         u32x4 w[4];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             uint32_t d[4];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) d[c] = tile[16 * kq + 4 * g + c][col];
+            for (int c = 0; c < 4; ++c) d[c] = tile[(16 * kq + 4 * g + c) * PX + at];
 #pragma unroll
             for (int a = 0; a < 4; ++a) w[a][g] = gather_byte(d, a);
         }
@@ -1495,8 +1508,13 @@ DK_EXPORT dk_status dkf_conv_fwd(const dk_layer *L, const uint32_t *Wq, const ui
         DK_REQUIRE(R <= 65535 && (g.Ci + 127) / 128 <= 65535, DK_ERR_SHAPE);
         {
             dk_prof_scope ps("f_digits_nhwc", st);
-            f_digits_nhwc_kernel<<<dim3((HW + 63) / 64, (g.Ci + 127) / 128, R), dim3(256), 0, st>>>(
-                xbar, Bp, g.Ci, HW, g.Ci, plane, (HW % 4 == 0) && dk_aligned(xbar, 16), flag + 1);
+            const int vec = (HW % 4 == 0) && dk_aligned(xbar, 16);
+            if (g.Ci <= 64)
+                f_digits_nhwc_kernel<64><<<dim3((HW + 127) / 128, 1, R), dim3(256), 0, st>>>(
+                    xbar, Bp, g.Ci, HW, g.Ci, plane, vec, flag + 1);
+            else
+                f_digits_nhwc_kernel<128><<<dim3((HW + 63) / 64, (g.Ci + 127) / 128, R), dim3(256), 0, st>>>(
+                    xbar, Bp, g.Ci, HW, g.Ci, plane, vec, flag + 1);
         }
         DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
         const fconv_geom cg = conv_geom_of(g);
