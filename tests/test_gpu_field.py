@@ -112,6 +112,17 @@ def test_forward_one_digit_weights(dk, top):
         assert np.array_equal(got, F.conv_fwd(W, X, stride=stride, pad=pad))
 
 
+def test_every_field_element_through_the_digit_planes(dk):
+    """All p field elements as entries of the encoded operand, against rows of ones and of
+    random field elements: a wrong digit of any element changes a sum that the oracle fixes."""
+    N, R = 8192, 4096
+    X = (np.arange(R * N, dtype=np.int64) % P).astype(np.uint32).reshape(R, N)
+    rng = np.random.default_rng(2207)
+    W = np.stack([np.ones(N, dtype=np.uint32), rng.integers(0, P, N, dtype=np.uint32),
+                  rng.integers(0, 128, N).astype(np.uint32)])
+    assert np.array_equal(host(dk.dkf_linear_fwd(dev(W), dev(X))), F.dense_fwd(W, X))
+
+
 def test_linear_fwd_extreme_digits(dk):
     """Operands at the ends of the centred range and at digit boundaries."""
     vals = np.array([0, 1, P - 1, P // 2, P // 2 + 1, 63, 64, 65, P - 64, P - 65, 127, 128, 129, P - 127,
