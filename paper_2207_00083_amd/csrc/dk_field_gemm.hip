@@ -1187,6 +1187,45 @@ __global__ __launch_bounds__(256) void f_fold_kernel(const uint32_t *__restrict_
     }
 }
 
+// The same for many slices of a small result (a weight gradient of a few thousand
+// elements cut into up to 256 slices): with one thread per element the launch is a few
+// workgroups that each walk all slices one load after the other.  Here a workgroup takes
+// 64 elements and its SG waves every SG-th slice; the SG partial sums (below 2^33 each) meet
+// in LDS.  Sums of residues: any order gives the same result.
+template <int SG>
+__global__ __launch_bounds__(64 * SG) void f_fold_deep_kernel(const uint32_t *__restrict__ part,
+                                                              uint32_t *__restrict__ out_q,
+                                                              float *__restrict__ dW, long long elems,
+                                                              int splits, double s_inv, float scale,
+                                                              int accumulate, int I, int J, int out_hw)
+{
+    __shared__ uint64_t red[SG][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long long e = (long long)blockIdx.x * 64 + lane;
+    uint64_t s = 0;
+    if (e < elems)
+        for (int k = wave; k < splits; k += SG) s += part[(long long)k * elems + e];
+    red[wave][lane] = s;
+    __syncthreads();
+    if (wave != 0 || e >= elems) return;
+#pragma unroll
+    for (int w = 1; w < SG; ++w) s += red[w][lane];
+    const uint32_t q = dkf_reduce(s);
+    if (out_q) {
+        long long o = e;
+        if (out_hw) {
+            const int i = (int)(e / J), j = (int)(e - (long long)i * J);
+            const int img = j / out_hw;
+            o = ((long long)img * I + i) * out_hw + (j - img * out_hw);
+        }
+        out_q[o] = q;
+    }
+    if (dW) {
+        const float v = scale * dkf_dequant(q, s_inv);
+        dW[e] = accumulate ? dW[e] + v : v;
+    }
+}
+
 inline int round_up(int v, int a) { return (v + a - 1) / a * a; }
 inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
@@ -1319,8 +1358,12 @@ dk_status run_fgemm(const fgemm_plan &pl, const int8_t *Ap, const int8_t *Bp, ui
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
     const long long elems = (long long)pl.I * pl.J;
     dk_prof_scope ps("f_fold", st);
-    f_fold_kernel<<<dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st>>>(
-        part, out_q, out_f, elems, pl.splits, p.s_inv, scale, accumulate, pl.I, pl.J, out_hw);
+    if (pl.splits >= 16 && elems <= 256 * 1024)
+        f_fold_deep_kernel<16><<<dim3((unsigned)((elems + 63) / 64)), dim3(1024), 0, st>>>(
+            part, out_q, out_f, elems, pl.splits, p.s_inv, scale, accumulate, pl.I, pl.J, out_hw);
+    else
+        f_fold_kernel<<<dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st>>>(
+            part, out_q, out_f, elems, pl.splits, p.s_inv, scale, accumulate, pl.I, pl.J, out_hw);
     return dk_launch_status();
 }
 
