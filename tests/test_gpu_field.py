@@ -99,10 +99,14 @@ def test_forward_one_digit_weights(dk, top):
             w.reshape(-1)[w.size // 2] = top
             w.reshape(-1)[w.size // 3] = -top - 1
         return (w % P).astype(np.uint32)
-    for R, M, N in ((150, 140, 260), (70, 64, 1000)):
+    for R, M, N in ((150, 140, 260), (70, 64, 1000), (3, 5, 7), (300, 1, 129)):
         X = rng.integers(0, P, size=(R, N), dtype=np.uint32)
         W = weights((M, N))
         assert np.array_equal(host(dk.dkf_linear_fwd(dev(W), dev(X))), F.dense_fwd(W, X))
+    # all-zero weights (no plane holds anything) and all-zero encodings next to one-digit weights
+    X = rng.integers(0, P, size=(130, 200), dtype=np.uint32)
+    assert not host(dk.dkf_linear_fwd(dev(np.zeros((70, 200), dtype=np.uint32)), dev(X))).any()
+    assert not host(dk.dkf_linear_fwd(dev(weights((70, 200))), dev(np.zeros_like(X)))).any()
     for Ci, Co, H, k, stride, pad in ((16, 96, 12, 3, 1, 1), (32, 130, 9, 3, 2, 1), (3, 70, 10, 5, 1, 2),
                                      (16, 40, 12, 3, 1, 1)):
         L = dk_inputs.conv(Ci, Co, H, H, k, stride, pad)
