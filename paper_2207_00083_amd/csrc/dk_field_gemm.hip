@@ -1404,6 +1404,103 @@ dk_status run_digits_t(const uint32_t *src, int8_t *planes, int K, int cols, int
     return dk_launch_status();
 }
 
+// The gradient mixing of the backward pass written straight into the digit planes of a
+// convolution's weight-gradient operand A (rows = output channels, k = (encoded row,
+// output pixel)):
+//     dtilde[gS+j] = gamma[g][j] * (sum_i B[g][j][i] * Dq[gK+i])  (mod p),  Dq = Field(Round(delta 2^l)),
+// so the mixed gradients never exist as a tensor (a write and a read of 4 bytes per element
+// less).  One thread: four consecutive pixels of one channel of one virtual batch, its K
+// gradient values quantised once and mixed into all S = K + 2 encoded rows; per row one
+// 4-byte word to each plane.  Needs Ho*Wo % 4 == 0 and a 16-byte aligned delta.  Rows
+// beyond Co and k beyond the contraction are zeroed by f_pad_planes_kernel.
+template <int K>
+__global__ __launch_bounds__(256) void f_delta_mix_digits_kernel(
+    const float *__restrict__ delta, const float *__restrict__ xscale, const uint32_t *__restrict__ B,
+    const uint32_t *__restrict__ gamma, int8_t *__restrict__ planes, int HoWo, long long len,
+    long long nvec, int chunks, long long span, double s, int Kp, long long plane, int sums, int *flag)
+{
+    constexpr int S = K + 2;
+    const int g = blockIdx.x / chunks;
+    const int chunk = blockIdx.x - g * chunks;
+    const uint32_t *Bg = B + (long long)g * S * K;
+    const uint32_t *gg = gamma + (long long)g * S;
+    const float *src = delta + (long long)g * K * len;
+    double si[K];
+#pragma unroll
+    for (int i = 0; i < K; ++i) si[i] = xscale ? s * (1.0 / (double)xscale[(long long)g * K + i]) : s;
+    uint32_t hi = 0, mid = 0;
+    const long long v0 = (long long)chunk * span;
+    long long v1 = v0 + span;
+    if (v1 > nvec) v1 = nvec;
+    for (long long v = v0 + threadIdx.x; v < v1; v += 256) {
+        const unsigned e = (unsigned)(v * 4);                    // len < 2^31
+        const unsigned co = e / (unsigned)HoWo, px = e - co * (unsigned)HoWo;
+        uint32_t q[K][4];
+#pragma unroll
+        for (int i = 0; i < K; ++i) {
+            const float4 f = *reinterpret_cast<const float4 *>(src + (long long)i * len + e);
+            q[i][0] = dkf_quant(f.x, si[i]); q[i][1] = dkf_quant(f.y, si[i]);
+            q[i][2] = dkf_quant(f.z, si[i]); q[i][3] = dkf_quant(f.w, si[i]);
+        }
+        int8_t *row = planes + (long long)co * Kp + (long long)g * S * HoWo + px;
+#pragma unroll
+        for (int j = 0; j < S; ++j) {
+            uint64_t acc[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int i = 0; i < K; ++i) {
+                const uint32_t b = Bg[j * K + i];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[c] += (uint64_t)b * q[i][c];
+            }
+            const uint32_t gj = gg[j];
+            uint32_t d[4], ds[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                d[c] = digits_of(dkf_reduce((uint64_t)gj * dkf_reduce(acc[c])));
+                ds[c] = half_sums(d[c]);
+            }
+            int8_t *dst = row + (long long)j * HoWo;
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const uint32_t w = gather_byte(d, a);
+                if (a >= 2) hi |= w;
+                if (a == 1) mid |= w;
+                *reinterpret_cast<uint32_t *>(dst + a * plane) = w;
+            }
+            if (sums) {
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+                    *reinterpret_cast<uint32_t *>(dst + (4 + a) * plane) = gather_byte(ds, a);
+            }
+        }
+    }
+    raise_flag(flag, hi, mid);
+}
+
+// Zero words of digit planes [nplanes][rows_pad][Kp] outside an operand of `rows` rows and
+// K (a multiple of 4) contraction indices: k in [K, Kp) of the rows, everything of the rows
+// beyond them.  One thread per word.
+__global__ __launch_bounds__(256) void f_pad_planes_kernel(int8_t *__restrict__ planes, long long plane,
+                                                           int rows, int rows_pad, int K, int Kp,
+                                                           long long per_plane, long long total)
+{
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const long long pln = idx / per_plane;
+    long long rem = idx - pln * per_plane;
+    const long long tw = (Kp - K) / 4, tail = (long long)rows * tw;
+    long long at;
+    if (rem < tail) {
+        const long long r = rem / tw;
+        at = r * Kp + K + 4 * (rem - r * tw);
+    } else {
+        rem -= tail;
+        const long long r = rem / (Kp / 4);
+        at = (rows + r) * Kp + 4 * (rem - r * (Kp / 4));
+    }
+    *reinterpret_cast<uint32_t *>(planes + pln * plane + at) = 0u;
+}
+
 template <int MODE>
 dk_status run_digits_conv(const uint32_t *src, int8_t *planes, const fconv_geom &cg, int rows, int K,
                           int rows_pad, int Kp, int sums, int *flag, hipStream_t st)
@@ -1415,6 +1512,53 @@ dk_status run_digits_conv(const uint32_t *src, int8_t *planes, const fconv_geom 
     f_digits_conv_kernel<MODE><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(src, planes, cg, rows, K,
                                                                              rows_pad, Kp, chunks, sums, flag);
     return dk_launch_status();
+}
+
+template <int K>
+dk_status launch_mix_digits(const float *delta, const float *xscale, const uint32_t *B, const uint32_t *gamma,
+                            int8_t *planes, int G, int HoWo, long long len, int l, int Kp, long long plane,
+                            int sums, int *flag, hipStream_t st)
+{
+    // each lane moves `iters` vectors of four; spans shrink until the launch has a few thousand workgroups
+    const long long nvec = len / 4;
+    long long iters = 4;
+    while (iters > 1 && (long long)G * ((nvec + 256 * iters - 1) / (256 * iters)) < 4096) iters >>= 1;
+    const long long span = 256 * iters;
+    const int chunks = (int)((nvec + span - 1) / span);
+    const long long blocks = (long long)G * chunks;
+    DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
+    dk_prof_scope ps("f_delta_mix_digits", st);
+    f_delta_mix_digits_kernel<K><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(
+        delta, xscale, B, gamma, planes, HoWo, len, nvec, chunks, span, ldexp(1.0, l), Kp, plane, sums, flag);
+    return dk_launch_status();
+}
+
+// The A planes of a convolution's weight gradient from the un-mixed gradients (see the kernel).
+dk_status run_mix_digits(const float *delta, const float *xscale, const uint32_t *B, const uint32_t *gamma,
+                         int8_t *planes, int G, int K, int Co, int HoWo, int l, int rows_pad, int Kc, int Kp,
+                         int sums, int *flag, hipStream_t st)
+{
+    const long long plane = (long long)rows_pad * Kp;
+    const int nplanes = sums ? 6 : 4;
+    const long long per_plane = (long long)Co * ((Kp - Kc) / 4) + (long long)(rows_pad - Co) * (Kp / 4);
+    if (per_plane > 0) {
+        const long long total = per_plane * nplanes;
+        DK_REQUIRE((total + 255) / 256 <= 0x7fffffffll, DK_ERR_SHAPE);
+        dk_prof_scope ps("f_pad_planes", st);
+        f_pad_planes_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(
+            planes, plane, Co, rows_pad, Kc, Kp, per_plane, total);
+        DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
+    }
+    const long long len = (long long)Co * HoWo;
+#define DKF_MD(KK) launch_mix_digits<KK>(delta, xscale, B, gamma, planes, G, HoWo, len, l, Kp, plane, sums, flag, st)
+    switch (K) {
+    case 1: return DKF_MD(1);   case 2: return DKF_MD(2);   case 3: return DKF_MD(3);   case 4: return DKF_MD(4);
+    case 5: return DKF_MD(5);   case 6: return DKF_MD(6);   case 7: return DKF_MD(7);   case 8: return DKF_MD(8);
+    case 9: return DKF_MD(9);   case 10: return DKF_MD(10); case 11: return DKF_MD(11); case 12: return DKF_MD(12);
+    case 13: return DKF_MD(13); case 14: return DKF_MD(14); case 15: return DKF_MD(15); case 16: return DKF_MD(16);
+    default: return DK_ERR_SHAPE;
+    }
+#undef DKF_MD
 }
 
 template <bool SHIFTED>
@@ -1695,15 +1839,23 @@ dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *xscale,
     int8_t *Bp = (int8_t *)w;                      w += pl.b_bytes;
     uint32_t *part = (uint32_t *)w;
 
-    dk_status s = dkf_delta_mix(delta, xscale, B, gamma, dtilde, G, K, Mn, g.m, l, st);
-    if (s != DK_OK) return s;
+    fshift sh;
+    const bool shifted = g.conv && conv_wgrad_shifted(g, R, &sh);
+    // the contraction index (encoded row, output pixel) with whole groups of four pixels:
+    // the mixing kernel writes the A planes itself
+    const bool mix_to_planes = g.conv && !shifted && Mn == 1 && (g.Ho * g.Wo) % 4 == 0 &&
+                               dk_aligned(delta, 16) && g.m < (1ll << 31) - 4;
+    dk_status s = DK_OK;
+    if (!mix_to_planes) {
+        s = dkf_delta_mix(delta, xscale, B, gamma, dtilde, G, K, Mn, g.m, l, st);
+        if (s != DK_OK) return s;
+    }
     {
         dk_prof_scope ps("f_flag_clear", st);
         f_flag_clear_kernel<<<dim3(1), dim3(64), 0, st>>>(flag);
     }
     DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
-    fshift sh;
-    if (g.conv && conv_wgrad_shifted(g, R, &sh)) {
+    if (shifted) {
         // the contraction index is (encoded row, output row, column of pitch Wp)
         const fconv_geom cg = conv_geom_of(g);
         s = run_digits_rows<false>(dtilde, Ap, cg, g.Co, pl.I_pad, sh.Ho, sh.Wp, sh.K, pl.Kp, pl.sums, flag, st);
@@ -1717,7 +1869,9 @@ dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *xscale,
     if (g.conv) {
         // the contraction index is (encoded row, output pixel)
         const fconv_geom cg = conv_geom_of(g);
-        s = run_digits_conv<1>(dtilde, Ap, cg, g.Co, pl.K, pl.I_pad, pl.Kp, pl.sums, flag, st);
+        s = mix_to_planes ? run_mix_digits(delta, xscale, B, gamma, Ap, G, K, g.Co, g.Ho * g.Wo, l, pl.I_pad,
+                                           pl.K, pl.Kp, pl.sums, flag, st)
+                          : run_digits_conv<1>(dtilde, Ap, cg, g.Co, pl.K, pl.I_pad, pl.Kp, pl.sums, flag, st);
         if (s != DK_OK) return s;
         s = run_digits_conv<2>(xbar, Bp, cg, (int)g.Kg, pl.K, pl.J_pad, pl.Kp, pl.sums, flag + 1, st);
         if (s != DK_OK) return s;
