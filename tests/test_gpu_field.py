@@ -292,7 +292,11 @@ def test_config5_field_sampled(dk, index):
     (8, 1, 20, 12, 7, 7, 1, 1, 0), (1, 2, 6, 9, 11, 8, 5, 2, 2), (4, 1, 64, 64, 16, 16, 3, 1, 1),
     # stride 1 with an output width that is, or nearly is, a multiple of 16
     (2, 2, 5, 7, 16, 16, 3, 1, 1), (3, 1, 6, 9, 9, 30, 3, 1, 0), (2, 1, 4, 6, 12, 16, 5, 1, 2),
-    (1, 3, 3, 4, 8, 16, 3, 1, 0), (2, 1, 3, 130, 5, 32, 3, 1, 1), (2, 2, 70, 3, 6, 14, 3, 1, 1)])
+    (1, 3, 3, 4, 8, 16, 3, 1, 0), (2, 1, 3, 130, 5, 32, 3, 1, 1), (2, 2, 70, 3, 6, 14, 3, 1, 1),
+    # the contraction index (encoded row, output pixel) with Ho*Wo a multiple of 4: the gradient mixing
+    # writes the digit planes itself (rows and k beyond the operand zeroed separately)
+    (4, 2, 20, 12, 6, 6, 1, 1, 0), (2, 3, 16, 70, 8, 8, 3, 2, 1), (8, 1, 8, 130, 4, 12, 1, 1, 0),
+    (16, 1, 4, 6, 4, 4, 1, 1, 0), (3, 2, 64, 128, 4, 8, 1, 1, 0)])
 def test_masked_conv_layer(dk, K, G, Ci, Co, H, W, k, stride, pad):
     rng = np.random.default_rng([K, G, Ci, Co, H, k, 17])
     L = dk_inputs.conv(Ci, Co, H, W, k, stride, pad)
