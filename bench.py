@@ -323,9 +323,10 @@ def field_main(args):
         }
     # Weights whose quantised values all lie in [-127, 127] fill one digit plane; the forward then
     # multiplies 4 x 1 planes (the library takes those steps for dense layers and for
-    # convolutions with more than 64 output channels).
+    # convolutions with more than 64 output channels and a contraction of at least 512).
     wq = np.rint(np.asarray(d["W"], dtype=np.float64) * 2.0 ** 8)
-    one_digit = bool(wq.min() >= -127 and wq.max() <= 127) and (L.kind == "linear" or L.Co > 64)
+    one_digit = bool(wq.min() >= -127 and wq.max() <= 127) and (
+        L.kind == "linear" or (L.Co > 64 and L.Ci * L.kh * L.kw >= 512))
     gemm = {"f_gemm_fwd": 4 if one_digit else 8, "f_gemm_wgrad": 12 if three_part else 16}
     dom = max(gemm, key=lambda k: kernels[k][0]) if L.kind != "dwconv" else None
     gemm_ms = kernels[dom][0] if dom else 0.0

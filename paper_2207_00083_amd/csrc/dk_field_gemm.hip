@@ -1674,8 +1674,9 @@ DK_EXPORT dk_status dkf_conv_fwd(const dk_layer *L, const uint32_t *Wq, const ui
     uint32_t *part = (uint32_t *)w;
     // The one-plane steps for filters that fit one digit (A holds the filters) pay where
     // the matrix pipe bounds the product; with at most 64 output channels the gathered
-    // operand does, and the second launch would only cost its start-up.
-    const int filters_single = pl.nbi == 2 ? 1 : 0;
+    // operand does, with a short contraction the workgroups' fixed costs do, and the second
+    // launch would only cost its start-up (13 us for 3 900 workgroups).
+    const int filters_single = (pl.nbi == 2 && g.Kg >= 512) ? 1 : 0;
 
     {
         dk_prof_scope ps("f_flag_clear", st);

@@ -107,8 +107,9 @@ def test_forward_one_digit_weights(dk, top):
     X = rng.integers(0, P, size=(130, 200), dtype=np.uint32)
     assert not host(dk.dkf_linear_fwd(dev(np.zeros((70, 200), dtype=np.uint32)), dev(X))).any()
     assert not host(dk.dkf_linear_fwd(dev(weights((70, 200))), dev(np.zeros_like(X)))).any()
-    for Ci, Co, H, k, stride, pad in ((16, 96, 12, 3, 1, 1), (32, 130, 9, 3, 2, 1), (3, 70, 10, 5, 1, 2),
-                                     (16, 40, 12, 3, 1, 1)):
+    # (the one-plane steps need more than 64 output channels and a contraction of at least 512)
+    for Ci, Co, H, k, stride, pad in ((64, 96, 8, 3, 1, 1), (128, 130, 9, 3, 2, 1), (60, 70, 6, 3, 1, 1),
+                                     (512, 65, 5, 1, 1, 0), (16, 96, 12, 3, 1, 1), (16, 40, 12, 3, 1, 1)):
         L = dk_inputs.conv(Ci, Co, H, H, k, stride, pad)
         X = rng.integers(0, P, size=(5, Ci, H, H), dtype=np.uint32)
         W = weights((Co, Ci, k, k))
