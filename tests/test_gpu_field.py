@@ -297,7 +297,10 @@ def test_config5_field_sampled(dk, index):
     # the contraction index (encoded row, output pixel) with Ho*Wo a multiple of 4: the gradient mixing
     # writes the digit planes itself (rows and k beyond the operand zeroed separately)
     (4, 2, 20, 12, 6, 6, 1, 1, 0), (2, 3, 16, 70, 8, 8, 3, 2, 1), (8, 1, 8, 130, 4, 12, 1, 1, 0),
-    (16, 1, 4, 6, 4, 4, 1, 1, 0), (3, 2, 64, 128, 4, 8, 1, 1, 0)])
+    (16, 1, 4, 6, 4, 4, 1, 1, 0), (3, 2, 64, 128, 4, 8, 1, 1, 0),
+    # a long contraction over a small result: the forward is cut into 16 or more k slices, folded by the
+    # kernel that spreads the slices over the waves of a workgroup, into the image-major layout
+    (2, 1, 256, 40, 4, 4, 3, 1, 1), (1, 1, 300, 7, 3, 5, 3, 1, 1)])
 def test_masked_conv_layer(dk, K, G, Ci, Co, H, W, k, stride, pad):
     rng = np.random.default_rng([K, G, Ci, Co, H, k, 17])
     L = dk_inputs.conv(Ci, Co, H, W, k, stride, pad)
