@@ -613,6 +613,41 @@ __global__ __launch_bounds__(256) void f_digits_wconv_kernel(const uint32_t *__r
     raise_flag(flag, hi, mid);
 }
 
+// The same with a whole filter row staged in LDS: W[row][Ci][taps] is read as it lies in
+// memory (the kernel above reads it with a stride of `taps` words per lane), and the planes
+// are written in their own order.  One workgroup per plane row; Ci * taps words of LDS.
+__global__ __launch_bounds__(256) void f_digits_wconv_lds_kernel(const uint32_t *__restrict__ W,
+                                                                 int8_t *__restrict__ planes, int Co, int Ci,
+                                                                 int taps, int cp, int rows_pad, int Kp,
+                                                                 int *flag)
+{
+    extern __shared__ uint32_t wrow[];
+    const int row = blockIdx.x, n = Ci * taps;
+    if (row < Co) {
+        const uint32_t *src = W + (long long)row * n;
+        for (int i = threadIdx.x; i < n; i += 256) wrow[i] = digits_of(src[i]);
+    }
+    __syncthreads();
+    const long long plane = (long long)rows_pad * Kp;
+    uint32_t hi = 0, mid = 0;
+    for (int k0 = threadIdx.x * 4; k0 < Kp; k0 += 1024) {
+        // cp is a multiple of 16: the four k share their tap
+        const int tap = k0 / cp, ci0 = k0 - tap * cp;
+        uint32_t d[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            d[c] = (row < Co && tap < taps && ci0 + c < Ci) ? wrow[(ci0 + c) * taps + tap] : 0u;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const uint32_t w = gather_byte(d, a);
+            if (a >= 2) hi |= w;
+            if (a == 1) mid |= w;
+            *reinterpret_cast<uint32_t *>(planes + a * plane + (long long)row * Kp + k0) = w;
+        }
+    }
+    raise_flag(flag, hi, mid);
+}
+
 __global__ void f_flag_clear_kernel(int *flags) { if (threadIdx.x < 2) flags[threadIdx.x] = 0; }
 
 // a0 + 2^7 a1 + 2^14 a2 (three int32 digit-class sums) as a lazily reduced
@@ -1688,8 +1723,13 @@ DK_EXPORT dk_status dkf_conv_fwd(const dk_layer *L, const uint32_t *Wq, const ui
         const int chunks = (pl.Kp / 4 + 255) / 256;
         {
             dk_prof_scope ps("f_digits_w", st);
-            f_digits_wconv_kernel<<<dim3((unsigned)(pl.I_pad * chunks)), dim3(256), 0, st>>>(
-                Wq, Ap, g.Co, g.Ci, taps, g.Ci, pl.I_pad, pl.Kp, chunks, flag);
+            if (taps > 1 && (long long)g.Ci * taps <= 12288)
+                f_digits_wconv_lds_kernel<<<dim3((unsigned)pl.I_pad), dim3(256),
+                                            (size_t)g.Ci * taps * sizeof(uint32_t), st>>>(
+                    Wq, Ap, g.Co, g.Ci, taps, g.Ci, pl.I_pad, pl.Kp, flag);
+            else
+                f_digits_wconv_kernel<<<dim3((unsigned)(pl.I_pad * chunks)), dim3(256), 0, st>>>(
+                    Wq, Ap, g.Co, g.Ci, taps, g.Ci, pl.I_pad, pl.Kp, chunks, flag);
         }
         DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
         const long long plane = (long long)R * HW * g.Ci;
