@@ -1441,19 +1441,22 @@ dk_status run_digits_t(const uint32_t *src, int8_t *planes, int K, int cols, int
 
 // The gradient mixing of the backward pass written straight into the digit planes of a
 // convolution's weight-gradient operand A (rows = output channels, k = (encoded row,
-// output pixel)):
+// output row, column of pitch Wp); Wp = Wo, or Wo rounded up to 16 for the padded-rows
+// form, whose columns beyond Wo are written as zeros here):
 //     dtilde[gS+j] = gamma[g][j] * (sum_i B[g][j][i] * Dq[gK+i])  (mod p),  Dq = Field(Round(delta 2^l)),
 // so the mixed gradients never exist as a tensor (a write and a read of 4 bytes per element
 // less).  One thread: four consecutive pixels of one channel of one virtual batch, its K
 // gradient values quantised once and mixed into all S = K + 2 encoded rows; per row one
-// 4-byte word to each plane.  Needs Ho*Wo % 4 == 0 and a 16-byte aligned delta.  Rows
-// beyond Co and k beyond the contraction are zeroed by f_pad_planes_kernel.
+// 4-byte word to each plane.  Needs Ho*Wo % 4 == 0 (Wo % 4 == 0 when Wp > Wo: a group of
+// four then stays in its row) and a 16-byte aligned delta.  Rows beyond Co and k beyond
+// the contraction are zeroed by f_pad_planes_kernel.
 template <int K>
 __global__ __launch_bounds__(256) void f_delta_mix_digits_kernel(
     const float *__restrict__ delta, const float *__restrict__ xscale, const uint32_t *__restrict__ B,
-    const uint32_t *__restrict__ gamma, int8_t *__restrict__ planes, int HoWo, long long len,
+    const uint32_t *__restrict__ gamma, int8_t *__restrict__ planes, int Ho, int Wo, int Wp, long long len,
     long long nvec, int chunks, long long span, double s, int Kp, long long plane, int sums, int *flag)
 {
+    const int HoWo = Ho * Wo, img_k = Ho * Wp;
     constexpr int S = K + 2;
     const int g = blockIdx.x / chunks;
     const int chunk = blockIdx.x - g * chunks;
@@ -1477,7 +1480,9 @@ __global__ __launch_bounds__(256) void f_delta_mix_digits_kernel(
             q[i][0] = dkf_quant(f.x, si[i]); q[i][1] = dkf_quant(f.y, si[i]);
             q[i][2] = dkf_quant(f.z, si[i]); q[i][3] = dkf_quant(f.w, si[i]);
         }
-        int8_t *row = planes + (long long)co * Kp + (long long)g * S * HoWo + px;
+        const unsigned h = px / (unsigned)Wo, w = px - h * (unsigned)Wo;
+        int8_t *row = planes + (long long)co * Kp + (long long)g * S * img_k + h * Wp + w;
+        const int gutter = (Wp > Wo && (int)w + 4 == Wo) ? (Wp - Wo) / 4 : 0;     // zero words after this group
 #pragma unroll
         for (int j = 0; j < S; ++j) {
             uint64_t acc[4] = {0, 0, 0, 0};
@@ -1494,19 +1499,22 @@ __global__ __launch_bounds__(256) void f_delta_mix_digits_kernel(
                 d[c] = digits_of(dkf_reduce((uint64_t)gj * dkf_reduce(acc[c])));
                 ds[c] = half_sums(d[c]);
             }
-            int8_t *dst = row + (long long)j * HoWo;
+            int8_t *dst = row + (long long)j * img_k;
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
-                const uint32_t w = gather_byte(d, a);
-                if (a >= 2) hi |= w;
-                if (a == 1) mid |= w;
-                *reinterpret_cast<uint32_t *>(dst + a * plane) = w;
+                const uint32_t word = gather_byte(d, a);
+                if (a >= 2) hi |= word;
+                if (a == 1) mid |= word;
+                *reinterpret_cast<uint32_t *>(dst + a * plane) = word;
             }
             if (sums) {
 #pragma unroll
                 for (int a = 0; a < 2; ++a)
                     *reinterpret_cast<uint32_t *>(dst + (4 + a) * plane) = gather_byte(ds, a);
             }
+            for (int z = 1; z <= gutter; ++z)
+                for (int a = 0; a < (sums ? 6 : 4); ++a)
+                    *reinterpret_cast<uint32_t *>(dst + a * plane + 4 * z) = 0u;
         }
     }
     raise_flag(flag, hi, mid);
@@ -1551,8 +1559,8 @@ dk_status run_digits_conv(const uint32_t *src, int8_t *planes, const fconv_geom 
 
 template <int K>
 dk_status launch_mix_digits(const float *delta, const float *xscale, const uint32_t *B, const uint32_t *gamma,
-                            int8_t *planes, int G, int HoWo, long long len, int l, int Kp, long long plane,
-                            int sums, int *flag, hipStream_t st)
+                            int8_t *planes, int G, int Ho, int Wo, int Wp, long long len, int l, int Kp,
+                            long long plane, int sums, int *flag, hipStream_t st)
 {
     // each lane moves `iters` vectors of four; spans shrink until the launch has a few thousand workgroups
     const long long nvec = len / 4;
@@ -1564,14 +1572,14 @@ dk_status launch_mix_digits(const float *delta, const float *xscale, const uint3
     DK_REQUIRE(blocks <= 0x7fffffffll, DK_ERR_SHAPE);
     dk_prof_scope ps("f_delta_mix_digits", st);
     f_delta_mix_digits_kernel<K><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(
-        delta, xscale, B, gamma, planes, HoWo, len, nvec, chunks, span, ldexp(1.0, l), Kp, plane, sums, flag);
+        delta, xscale, B, gamma, planes, Ho, Wo, Wp, len, nvec, chunks, span, ldexp(1.0, l), Kp, plane, sums, flag);
     return dk_launch_status();
 }
 
 // The A planes of a convolution's weight gradient from the un-mixed gradients (see the kernel).
 dk_status run_mix_digits(const float *delta, const float *xscale, const uint32_t *B, const uint32_t *gamma,
-                         int8_t *planes, int G, int K, int Co, int HoWo, int l, int rows_pad, int Kc, int Kp,
-                         int sums, int *flag, hipStream_t st)
+                         int8_t *planes, int G, int K, int Co, int Ho, int Wo, int Wp, int l, int rows_pad,
+                         int Kc, int Kp, int sums, int *flag, hipStream_t st)
 {
     const long long plane = (long long)rows_pad * Kp;
     const int nplanes = sums ? 6 : 4;
@@ -1584,8 +1592,8 @@ dk_status run_mix_digits(const float *delta, const float *xscale, const uint32_t
             planes, plane, Co, rows_pad, Kc, Kp, per_plane, total);
         DK_REQUIRE(hipGetLastError() == hipSuccess, DK_ERR_HIP);
     }
-    const long long len = (long long)Co * HoWo;
-#define DKF_MD(KK) launch_mix_digits<KK>(delta, xscale, B, gamma, planes, G, HoWo, len, l, Kp, plane, sums, flag, st)
+    const long long len = (long long)Co * Ho * Wo;
+#define DKF_MD(KK) launch_mix_digits<KK>(delta, xscale, B, gamma, planes, G, Ho, Wo, Wp, len, l, Kp, plane, sums, flag, st)
     switch (K) {
     case 1: return DKF_MD(1);   case 2: return DKF_MD(2);   case 3: return DKF_MD(3);   case 4: return DKF_MD(4);
     case 5: return DKF_MD(5);   case 6: return DKF_MD(6);   case 7: return DKF_MD(7);   case 8: return DKF_MD(8);
@@ -1882,9 +1890,9 @@ dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *xscale,
 
     fshift sh;
     const bool shifted = g.conv && conv_wgrad_shifted(g, R, &sh);
-    // the contraction index (encoded row, output pixel) with whole groups of four pixels:
-    // the mixing kernel writes the A planes itself
-    const bool mix_to_planes = g.conv && !shifted && Mn == 1 && (g.Ho * g.Wo) % 4 == 0 &&
+    // whole groups of four pixels (inside a row where the rows are padded): the mixing kernel
+    // writes the A planes itself
+    const bool mix_to_planes = g.conv && Mn == 1 && (shifted ? g.Wo % 4 == 0 : (g.Ho * g.Wo) % 4 == 0) &&
                                dk_aligned(delta, 16) && g.m < (1ll << 31) - 4;
     dk_status s = DK_OK;
     if (!mix_to_planes) {
@@ -1899,7 +1907,10 @@ dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *xscale,
     if (shifted) {
         // the contraction index is (encoded row, output row, column of pitch Wp)
         const fconv_geom cg = conv_geom_of(g);
-        s = run_digits_rows<false>(dtilde, Ap, cg, g.Co, pl.I_pad, sh.Ho, sh.Wp, sh.K, pl.Kp, pl.sums, flag, st);
+        s = mix_to_planes ? run_mix_digits(delta, xscale, B, gamma, Ap, G, K, g.Co, g.Ho, g.Wo, sh.Wp, l, pl.I_pad,
+                                           sh.K, pl.Kp, pl.sums, flag, st)
+                          : run_digits_rows<false>(dtilde, Ap, cg, g.Co, pl.I_pad, sh.Ho, sh.Wp, sh.K, pl.Kp, pl.sums,
+                                                   flag, st);
         if (s != DK_OK) return s;
         s = run_digits_rows<true>(xbar, Bp, cg, g.Ci, g.Ci, sh.Hp, sh.Wpp, sh.row_bytes, sh.row_bytes, pl.sums,
                                   flag + 1, st);
@@ -1910,7 +1921,7 @@ dk_status wgrad_impl(const dk_layer *L, const float *delta, const float *xscale,
     if (g.conv) {
         // the contraction index is (encoded row, output pixel)
         const fconv_geom cg = conv_geom_of(g);
-        s = mix_to_planes ? run_mix_digits(delta, xscale, B, gamma, Ap, G, K, g.Co, g.Ho * g.Wo, l, pl.I_pad,
+        s = mix_to_planes ? run_mix_digits(delta, xscale, B, gamma, Ap, G, K, g.Co, g.Ho, g.Wo, g.Wo, l, pl.I_pad,
                                            pl.K, pl.Kp, pl.sums, flag, st)
                           : run_digits_conv<1>(dtilde, Ap, cg, g.Co, pl.K, pl.I_pad, pl.Kp, pl.sums, flag, st);
         if (s != DK_OK) return s;
