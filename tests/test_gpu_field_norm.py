@@ -141,7 +141,8 @@ def test_masked_dense_layer_normalised(dk, K, G, M, N):
 
 @pytest.mark.parametrize("K,G,Ci,Co,H,W,k,stride,pad", [
     (2, 1, 3, 5, 9, 7, 3, 1, 1), (4, 2, 16, 24, 12, 12, 3, 1, 1), (8, 1, 20, 12, 7, 7, 1, 1, 0),
-    (1, 2, 6, 9, 11, 8, 5, 2, 2), (4, 2, 20, 12, 6, 6, 1, 1, 0)])
+    (1, 2, 6, 9, 11, 8, 5, 2, 2), (4, 2, 20, 12, 6, 6, 1, 1, 0), (2, 1, 8, 10, 6, 16, 3, 1, 1),
+    (2, 2, 5, 7, 5, 30, 3, 1, 0)])
 def test_masked_conv_layer_normalised(dk, K, G, Ci, Co, H, W, k, stride, pad):
     rng = np.random.default_rng([K, G, Ci, Co, H, k, 23])
     L = dk_inputs.conv(Ci, Co, H, W, k, stride, pad)
