@@ -325,8 +325,10 @@ def field_main(args):
     # multiplies 4 x 1 planes (the library takes those steps for dense layers and for
     # convolutions with more than 64 output channels and a contraction of at least 512).
     wq = np.rint(np.asarray(d["W"], dtype=np.float64) * 2.0 ** 8)
+    # (128-row tiles: the library takes 64-row tiles when the last 128 output channels are at most 64)
+    wide_tiles = L.kind != "linear" and not (L.Co % 128 != 0 and L.Co % 128 <= 64)
     one_digit = bool(wq.min() >= -127 and wq.max() <= 127) and (
-        L.kind == "linear" or (L.Co > 64 and L.Ci * L.kh * L.kw >= 512))
+        L.kind == "linear" or (wide_tiles and L.Ci * L.kh * L.kw >= 512))
     gemm = {"f_gemm_fwd": 4 if one_digit else 8, "f_gemm_wgrad": 12 if three_part else 16}
     dom = max(gemm, key=lambda k: kernels[k][0]) if L.kind != "dwconv" else None
     gemm_ms = kernels[dom][0] if dom else 0.0

@@ -90,8 +90,8 @@ dk_status dkf_encode_rng(const float *x, const uint32_t *A, uint32_t *xbar, int 
  * multiplied as four base-128 digits each, all-zero digit planes are found on
  * the device and skipped, so weights with |Round(w 2^l)| < 2^13 cost half of
  * arbitrary field elements and weights with |Round(w 2^l)| <= 127 a quarter (the same
- * holds for dkf_conv_fwd with more than 64 output channels and a contraction
- * Ci kh kw of at least 512). */
+ * holds for dkf_conv_fwd with a contraction Ci kh kw of at least 512, unless
+ * the last 128 output channels are at most 64). */
 dk_status dkf_linear_fwd(const uint32_t *Wq, const uint32_t *xbar, uint32_t *ybar,
                          int M, int N, int R, void *ws, size_t ws_bytes, void *stream);
 
